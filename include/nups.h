@@ -1,0 +1,214 @@
+/*
+ * nups.h - C ABI of the MI355X-native minibatch step of sparse-parameter SGD for the
+ * workloads of "NuPS: A Parameter Server for Machine Learning with Non-Uniform
+ * Parameter Access" (SIGMOD '22): draw negative keys, pull rows, compute the
+ * per-example gradients, aggregate per key and push the updates back.
+ *
+ * Conventions (all entry points):
+ *  - Every call returns a nups_status; nothing throws across the boundary.
+ *    nups_last_error() gives a thread-local description of the last failure.
+ *  - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
+ *  - The library never owns table, state, batch or output memory: the caller
+ *    allocates it and keeps it alive while the context uses it.  The library owns
+ *    only its workspace and the opaque objects it hands out.
+ *  - All device work is enqueued on the HIP stream given to nups_init; calls return
+ *    without waiting unless they hand a value back to the host (stated per call).
+ *  - A table is a dense [num_keys, row_stride] fp32 array; the first `dim` floats of
+ *    a row are the parameter, the rest is padding that stays zero.  row_stride must be
+ *    a multiple of 64 floats (at most 1024); keys are uint32 row numbers.
+ *  - Keys outside [0, num_keys) never cause an out-of-range access: the kernels skip
+ *    or clamp them, raise a device-side flag, and the next call that synchronises
+ *    (nups_step with a loss pointer, nups_debug_structure, nups_check) returns
+ *    NUPS_ERR_KEY_RANGE.
+ */
+#ifndef NUPS_H
+#define NUPS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct nups_ctx nups_ctx;        /* tables + workspace + stream      */
+typedef struct nups_dist nups_dist;      /* a registered target distribution */
+typedef struct nups_sample nups_sample;  /* handle returned by PrepareSample */
+
+typedef enum {
+    NUPS_OK = 0,
+    NUPS_ERR_ARG = -1,           /* null pointer, negative size, inconsistent shapes        */
+    NUPS_ERR_KEY_RANGE = -2,     /* a key was >= num_keys                                   */
+    NUPS_ERR_OVERPULL = -3,      /* PullSample asked for more than the handle still holds   */
+    NUPS_ERR_STATE = -4,         /* call not valid in the object's current state            */
+    NUPS_ERR_DEVICE = -5,        /* a HIP call failed                                       */
+    NUPS_ERR_UNIMPLEMENTED = -6
+} nups_status;
+
+/* Sampling schemes of Section 4.4, named by the conformity level they provide (Section 4.1). */
+typedef enum {
+    NUPS_CONFORM = 1,      /* independent sampling: i.i.d. draws, each used once           */
+    NUPS_BOUNDED = 2,      /* sample reuse: pools of G draws, each traversed U times       */
+    NUPS_LONGTERM = 3,     /* sample reuse over a long-lived pool of P draws, R passes     */
+    NUPS_NONCONFORM = 4    /* local sampling / direct-access repurposing within the batch  */
+} nups_scheme;
+
+/* The three tasks of Section 5.1. */
+typedef enum { NUPS_TASK_SGNS = 1, NUPS_TASK_MF = 2, NUPS_TASK_KGE = 3 } nups_task;
+
+/* ---- context ----------------------------------------------------------------------- */
+
+/*
+ * Creates a context over n_tables (1..4) caller-owned tables (the key -> value-vector
+ * store of Section 3.1).  tables_dev[t] is the device address of table t,
+ * num_keys[t] x row_stride[t] floats.  hip_stream is a hipStream_t (NULL = the
+ * default stream).  Errors: NUPS_ERR_ARG on null pointers, dim <= 0, dim > row_stride,
+ * row_stride not a multiple of 64 or > 1024, num_keys outside 1..2^32-1;
+ * NUPS_ERR_DEVICE if no device is usable.
+ */
+nups_status nups_init(nups_ctx **out, int n_tables, float *const *tables_dev, const int64_t *num_keys,
+                      const int32_t *dim, const int32_t *row_stride, void *hip_stream);
+
+/* Releases the workspace and every distribution and handle created from ctx. */
+nups_status nups_destroy(nups_ctx *ctx);
+
+/*
+ * Attaches per-row optimiser state (AdaGrad accumulators, same shape as the table,
+ * caller-owned, device).  Table 1 of the paper stores it with the value (1000 values
+ * per key for dimension 500); here it is a second array with the same row numbering.
+ */
+nups_status nups_set_state(nups_ctx *ctx, int table, float *state_dev);
+
+/*
+ * Declares the hot keys of a table (Section 3.2: frequently accessed keys get the
+ * technique for hot spots, the long tail the other one).  keys_host holds k distinct
+ * keys, hottest first; k = 0 switches the hot path off at no cost.  The set changes
+ * how updates are aggregated, never the result beyond fp32 summation order.
+ */
+nups_status nups_set_hot_keys(nups_ctx *ctx, int table, const uint32_t *keys_host, int64_t k);
+
+/* ---- direct access (Section 3.1) ------------------------------------------------- */
+
+/* pull: values_dev[i, :] = table[keys_dev[i], :] for i < n (whole stored rows, row_stride floats each).
+ * A key that occurs twice is returned twice.  Out-of-range keys yield a zero row. */
+nups_status nups_pull(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_t n, float *values_dev);
+
+/* push: table[k, :] += sum of updates_dev[i, :] over all i with keys_dev[i] == k (additive; duplicates
+ * within one call add up, each key is written once).  updates_dev is [n, row_stride]. */
+nups_status nups_push(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_t n, const float *updates_dev);
+
+/* ---- sampling access (Sections 4.3, 4.4) ---------------------------------------- */
+
+/*
+ * Host-only helper: builds the alias table of pi_k = weights[k] / sum(weights) (fp64
+ * weights, length num_keys).  Bucket b keeps itself when a uniform 32-bit word is
+ * below thresh[b] and yields alias[b] otherwise.  Needs no GPU.
+ * Errors: NUPS_ERR_ARG for null pointers, negative / NaN / infinite weights or a zero sum.
+ */
+nups_status nups_build_alias_table(const double *weights_host, int64_t num_keys,
+                                   uint32_t *thresh_host, uint32_t *alias_host);
+
+/*
+ * register_distribution(pi, L) of Section 4.3: registers the target distribution over
+ * the keys of `table` together with the scheme that serves it.  weights_host = NULL
+ * means uniform.  Scheme parameters: U (use frequency) and G (pool size) for
+ * NUPS_BOUNDED (1 <= G <= 1024); P (pool size) and R (passes per pool) for
+ * NUPS_LONGTERM; ignored otherwise.  seed keys the counter-based generator: sample
+ * i of the handle prepared for step t is a pure function of (seed, dist, t, i).
+ */
+nups_status nups_register_distribution(nups_ctx *ctx, int table, const double *weights_host,
+                                       nups_scheme scheme, int32_t U, int32_t G, int64_t P, int32_t R,
+                                       uint64_t seed, nups_dist **out);
+
+/*
+ * NUPS_NONCONFORM only: the keys the minibatch accesses anyway, from which samples are
+ * taken.  Sample p belongs to example p / per_example; its first `split` samples come
+ * from keys_a_dev, the others from keys_b_dev (both [n_examples], may be the same
+ * array); candidates are the examples of the same tile of `tile` consecutive examples.
+ * The arrays must stay valid until the handles prepared from them are released.
+ */
+nups_status nups_set_local_keys(nups_dist *dist, const uint32_t *keys_a_dev, const uint32_t *keys_b_dev,
+                                int64_t n_examples, int32_t per_example, int32_t split, int32_t tile);
+
+/*
+ * PrepareSample(dist, N): enqueues the drawing of N sample keys for step `step` and
+ * returns at once.  For NUPS_LONGTERM the distribution's cursor advances by N (step
+ * is ignored).  The handle must be released with nups_release_sample.
+ */
+nups_status nups_prepare_sample(nups_dist *dist, int64_t n, uint64_t step, nups_sample **out);
+
+/*
+ * PullSample(handle, n_j): hands out the next n_j samples of the handle: their keys
+ * into keys_dev[n_j] and, if values_dev != NULL, their rows into values_dev[n_j,
+ * row_stride].  Partial pulls may be repeated until the N samples are used up;
+ * asking for more returns NUPS_ERR_OVERPULL and hands out nothing.  The copies are
+ * enqueued on the stream (stream-ordered, not host-blocking).
+ */
+nups_status nups_pull_sample(nups_sample *handle, int64_t n_j, uint32_t *keys_dev, float *values_dev);
+
+/* Device address of all N keys of the handle (valid until release; filled in stream order). */
+nups_status nups_sample_keys(nups_sample *handle, const uint32_t **keys_dev, int64_t *n);
+
+/* Gives the handle back; releasing twice is NUPS_ERR_STATE. */
+nups_status nups_release_sample(nups_sample *handle);
+
+/* ---- one minibatch step (Section 5.1 tasks) ------------------------------------- */
+
+typedef struct {
+    int32_t task;          /* nups_task                                                          */
+    int64_t B;             /* examples in the batch                                              */
+    const uint32_t *k0;    /* dev [B]: SGNS center word | MF row    | KGE subject                 */
+    const uint32_t *k1;    /* dev [B]: SGNS context word| MF column | KGE relation                */
+    const uint32_t *k2;    /* dev [B]: KGE object (else NULL)                                     */
+    const float *val;      /* dev [B]: MF cell value (else NULL)                                  */
+    int32_t n_neg;         /* SGNS: negatives per pair; KGE: subject-replacing negatives per triple */
+    int32_t n_neg2;        /* KGE: object-replacing negatives per triple (else 0)                 */
+    float lr;              /* learning rate                                                       */
+    float l2;              /* MF: L2 regularisation weight                                        */
+    float eps;             /* KGE: AdaGrad epsilon                                                */
+    const uint32_t *negs;  /* dev [B * (n_neg + n_neg2)] sampled keys, example-major (NULL if none) */
+} nups_batch;
+
+/*
+ * One synchronous minibatch step on tables 0 and 1 of the context
+ * (SGNS: input / output vectors; MF: row / column factors; KGE: entities / relations,
+ * both with state attached).  All gradients are taken against the values at the start
+ * of the step, contributions to one key are summed, and each touched row is updated
+ * once (SGD, or AdaGrad for KGE).  If loss_sum_host != NULL the call waits for the
+ * step and stores the batch loss (and reports pending key-range errors); with NULL it
+ * only enqueues.
+ */
+nups_status nups_step(nups_ctx *ctx, const nups_batch *batch, double *loss_sum_host);
+
+/*
+ * Aggregation structure of the last nups_step / nups_push on `table`: the distinct
+ * keys in ascending order and how many accesses each received.  Buffers are device
+ * arrays with room for as many entries as the call had accesses to that table.
+ * Waits for the stream.
+ */
+nups_status nups_debug_structure(nups_ctx *ctx, int table, uint32_t *uniq_keys_dev, uint32_t *counts_dev,
+                                 int64_t *n_uniq_host);
+
+/* Waits for the stream and returns NUPS_ERR_KEY_RANGE if any kernel since the last check saw a bad key. */
+nups_status nups_check(nups_ctx *ctx);
+
+/* ---- measurement ------------------------------------------------------------------ */
+
+/* Phases whose device time can be recorded with HIP events around their launches. */
+enum { NUPS_PHASE_SAMPLE = 0, NUPS_PHASE_PLAN = 1, NUPS_PHASE_GRAD = 2, NUPS_PHASE_APPLY0 = 3,
+       NUPS_PHASE_APPLY1 = 4, NUPS_PHASE_PULL = 5, NUPS_PHASE_PUSH = 6, NUPS_PHASE_COUNT = 7 };
+
+/* Switches per-phase event timing on or off (off by default; it adds event records to the stream). */
+nups_status nups_profile(nups_ctx *ctx, int enable);
+
+/* Waits for the stream; returns accumulated milliseconds and launch count of a phase and resets them. */
+nups_status nups_profile_read(nups_ctx *ctx, int phase, double *ms_total, int64_t *launches);
+
+const char *nups_phase_name(int phase);
+
+/* Description of the calling thread's last error ("" if none). */
+const char *nups_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NUPS_H */

@@ -419,16 +419,18 @@ static void apply_sgd(float *table, int32_t stride, int32_t dim, const uint32_t 
  * G <- fl32(G + delta^2); theta <- fl32(theta - lr * delta / (sqrt(G) + eps)) with the new G.
  * Rows that the step does not touch keep value and state (sparse AdaGrad).
  */
+/* `split` > 0: accumulator entries split.. are stored from float `split_at` on (complex rows); 0: contiguous. */
 static void apply_adagrad(float *table, float *state, int32_t stride, int32_t dim, const uint32_t *uniq,
-                          int64_t nu, const double *acc, float lr, float eps)
+                          int64_t nu, const double *acc, float lr, float eps, int32_t split, int32_t split_at)
 {
     for (int64_t u = 0; u < nu; ++u) {
         float *row = table + (int64_t)uniq[u] * stride;
         float *g2 = state + (int64_t)uniq[u] * stride;
         for (int32_t m = 0; m < dim; ++m) {
+            int32_t at = (split > 0 && m >= split) ? split_at + (m - split) : m;
             double d = acc[u * dim + m];
-            g2[m] = (float)((double)g2[m] + d * d);
-            row[m] = (float)((double)row[m] - (double)lr * d / (sqrt((double)g2[m]) + (double)eps));
+            g2[at] = (float)((double)g2[at] + d * d);
+            row[at] = (float)((double)row[at] - (double)lr * d / (sqrt((double)g2[at]) + (double)eps));
         }
     }
 }
@@ -436,7 +438,7 @@ static void apply_adagrad(float *table, float *state, int32_t stride, int32_t di
 void nor_apply_adagrad_rows(float *table, float *state, int32_t stride, int32_t dim, const uint32_t *uniq,
                             int64_t nu, const double *acc, float lr, float eps)
 {
-    apply_adagrad(table, state, stride, dim, uniq, nu, acc, lr, eps);
+    apply_adagrad(table, state, stride, dim, uniq, nu, acc, lr, eps, 0, 0);
 }
 
 /* ------------------------------------------------------------------------- */
@@ -626,31 +628,33 @@ double nor_loss_mf(const float *W, const float *H, int32_t stride, int32_t dim,
 /* ------------------------------------------------------------------------- */
 /* Knowledge-graph embeddings: ComplEx (Trouillon et al. 2016) with logistic   */
 /* loss, negative sampling by corrupting subject and object, AdaGrad           */
-/* (Section 5.1).  A row holds dim/2 real parts followed by dim/2 imaginary    */
-/* parts.                                                                      */
+/* (Section 5.1).  Storage layout of a complex row of `dim` values in a row of */
+/* `stride` floats: the dim/2 real parts start at float 0, the dim/2 imaginary */
+/* parts start at float stride/2 (so a stored row is two equal halves); the    */
+/* paper does not prescribe a layout.                                          */
 /* ------------------------------------------------------------------------- */
-/* score(s, r, o) = Re( sum_m s_m r_m conj(o_m) ). */
-static double complex_score(const float *s, const float *r, const float *o, int32_t half)
+/* score(s, r, o) = Re( sum_m s_m r_m conj(o_m) ); `im` = offset of the imaginary half. */
+static double complex_score(const float *s, const float *r, const float *o, int32_t half, int32_t im)
 {
     double phi = 0.0;
     for (int32_t m = 0; m < half; ++m) {
-        double sr = s[m], si = s[half + m], rr = r[m], ri = r[half + m], orr = o[m], oi = o[half + m];
+        double sr = s[m], si = s[im + m], rr = r[m], ri = r[im + m], orr = o[m], oi = o[im + m];
         phi += sr * rr * orr + si * rr * oi + sr * ri * oi - si * ri * orr;
     }
     return phi;
 }
 
-double nor_complex_score(const float *s, const float *r, const float *o, int32_t dim)
+double nor_complex_score(const float *s, const float *r, const float *o, int32_t stride, int32_t dim)
 {
-    return complex_score(s, r, o, dim / 2);
+    return complex_score(s, r, o, dim / 2, stride / 2);
 }
 
-/* acc_* += g * dscore/d(row) for the three rows of one scored triple. */
-static void complex_grad(const float *s, const float *r, const float *o, int32_t half, double g,
+/* acc_* += g * dscore/d(row) for the three rows of one scored triple (accumulators are [dim]: re then im). */
+static void complex_grad(const float *s, const float *r, const float *o, int32_t half, int32_t im, double g,
                          double *as, double *ar, double *ao)
 {
     for (int32_t m = 0; m < half; ++m) {
-        double sr = s[m], si = s[half + m], rr = r[m], ri = r[half + m], orr = o[m], oi = o[half + m];
+        double sr = s[m], si = s[im + m], rr = r[m], ri = r[im + m], orr = o[m], oi = o[im + m];
         as[m]        += g * (rr * orr + ri * oi);
         as[half + m] += g * (rr * oi - ri * orr);
         ar[m]        += g * (sr * orr + si * oi);
@@ -680,7 +684,8 @@ int nor_step_kge(float *E, float *GE, float *R, float *GR, int64_t n_ent, int64_
     if (!E || !GE || !R || !GR || n_ent <= 0 || n_rel <= 0 || stride <= 0 || dim <= 0 || dim > stride
         || (dim & 1) || B < 0 || nh < 0 || nt < 0 || (B > 0 && (!subj || !rel || !obj))
         || (B > 0 && nh + nt > 0 && !negs)) return NOR_ERR_ARG;
-    int32_t nn = nh + nt, half = dim / 2;
+    int32_t nn = nh + nt, half = dim / 2, im = stride / 2;
+    if ((stride & 1) || half > im) return NOR_ERR_ARG;
     if (!keys_in_range(subj, B, n_ent) || !keys_in_range(obj, B, n_ent) || !keys_in_range(rel, B, n_rel)
         || !keys_in_range(negs, B * (int64_t)nn, n_ent)) return NOR_ERR_KEY;
     int64_t n_acc = B * (int64_t)(2 + nn);
@@ -716,15 +721,15 @@ int nor_step_kge(float *E, float *GE, float *R, float *GR, int64_t n_ent, int64_
             }
             const float *s = E + (int64_t)ks * stride;
             const float *o = E + (int64_t)ko * stride;
-            double phi = complex_score(s, r, o, half);
+            double phi = complex_score(s, r, o, half, im);
             loss += softplus(-label * phi);
             double g = -label * sigmoid(-label * phi);
-            complex_grad(s, r, o, half, g, acc_e + slot_of(ue, nue, ks) * dim, ar,
+            complex_grad(s, r, o, half, im, g, acc_e + slot_of(ue, nue, ks) * dim, ar,
                          acc_e + slot_of(ue, nue, ko) * dim);
         }
     }
-    apply_adagrad(E, GE, stride, dim, ue, nue, acc_e, lr, eps);
-    apply_adagrad(R, GR, stride, dim, ur, nur, acc_r, lr, eps);
+    apply_adagrad(E, GE, stride, dim, ue, nue, acc_e, lr, eps, half, im);
+    apply_adagrad(R, GR, stride, dim, ur, nur, acc_r, lr, eps, half, im);
     if (loss_out) *loss_out = loss;
     if (n_uniq_e) *n_uniq_e = nue;
     if (n_uniq_r) *n_uniq_r = nur;
@@ -742,7 +747,7 @@ double nor_loss_kge(const float *E, const float *R, int32_t stride, int32_t dim,
                     const uint32_t *subj, const uint32_t *rel, const uint32_t *obj, const uint32_t *negs,
                     int64_t B, int32_t nh, int32_t nt)
 {
-    int32_t nn = nh + nt, half = dim / 2;
+    int32_t nn = nh + nt, half = dim / 2, im = stride / 2;
     double loss = 0.0;
     for (int64_t e = 0; e < B; ++e) {
         const float *r = R + (int64_t)rel[e] * stride;
@@ -753,7 +758,7 @@ double nor_loss_kge(const float *E, const float *R, int32_t stride, int32_t dim,
                 label = -1.0;
                 if (t - 1 < nh) ks = negs[e * nn + (t - 1)]; else ko = negs[e * nn + (t - 1)];
             }
-            loss += softplus(-label * complex_score(E + (int64_t)ks * stride, r, E + (int64_t)ko * stride, half));
+            loss += softplus(-label * complex_score(E + (int64_t)ks * stride, r, E + (int64_t)ko * stride, half, im));
         }
     }
     return loss;

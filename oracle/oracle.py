@@ -248,7 +248,10 @@ def loss_kge(E, R, dim, subj, rel, obj, negs, nh, nt):
 
 
 def complex_score(s_row, r_row, o_row, dim):
+    """Score of one triple; rows are stored rows (real parts at 0, imaginary parts at len/2)."""
     s = np.ascontiguousarray(s_row, dtype=np.float32)
     r = np.ascontiguousarray(r_row, dtype=np.float32)
     o = np.ascontiguousarray(o_row, dtype=np.float32)
-    return lib().nor_complex_score(_p(s, C.c_float), _p(r, C.c_float), _p(o, C.c_float), C.c_int32(dim))
+    assert len(s) == len(r) == len(o)
+    return lib().nor_complex_score(_p(s, C.c_float), _p(r, C.c_float), _p(o, C.c_float), C.c_int32(len(s)),
+                                   C.c_int32(dim))

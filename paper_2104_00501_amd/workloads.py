@@ -81,6 +81,20 @@ def uniform_table(num_keys: int, dim: int, lo: float, hi: float, seed: int) -> n
     return t
 
 
+def complex_table(num_keys: int, dim: int, lo: float, hi: float, seed: int) -> np.ndarray:
+    """Table of complex rows: dim/2 real parts from float 0, dim/2 imaginary parts from float stride/2."""
+    rng = np.random.default_rng(seed)
+    stride = padded_stride(dim)
+    if stride % 128:
+        stride += ROW_LANES          # both halves have to be multiples of 64 floats
+    half = dim // 2
+    t = np.zeros((num_keys, stride), dtype=np.float32)
+    t[:, :half] = rng.random((num_keys, half), dtype=np.float32) * np.float32(hi - lo) + np.float32(lo)
+    t[:, stride // 2:stride // 2 + half] = (rng.random((num_keys, half), dtype=np.float32)
+                                            * np.float32(hi - lo) + np.float32(lo))
+    return t
+
+
 def zero_table(num_keys: int, dim: int) -> np.ndarray:
     return np.zeros((num_keys, padded_stride(dim)), dtype=np.float32)
 
