@@ -1,0 +1,464 @@
+// Host side of the C ABI declared in include/nups.h: argument checks, workspace, object lifetimes.
+#include <algorithm>
+#include <cstring>
+
+#include "nups_internal.h"
+
+namespace nups {
+
+static thread_local std::string g_error;
+
+void set_error(const std::string &msg) { g_error = msg; }
+
+nups_status fail(nups_status st, const std::string &msg)
+{
+    g_error = msg;
+    return st;
+}
+
+bool hip_ok(hipError_t e, const char *what)
+{
+    if (e == hipSuccess) return true;
+    g_error = std::string(what) + ": " + hipGetErrorString(e);
+    return false;
+}
+
+nups_status ensure_f32(float **buf, size_t *cap, size_t need, hipStream_t stream)
+{
+    if (*cap >= need && *buf) return NUPS_OK;
+    NUPS_HIP(hipStreamSynchronize(stream));
+    if (*buf) NUPS_HIP(hipFree(*buf));
+    *buf = nullptr;
+    const size_t n = need + need / 4 + 1024;
+    NUPS_HIP(hipMalloc((void **)buf, sizeof(float) * n));
+    *cap = n;
+    return NUPS_OK;
+}
+
+static nups_status ensure_u32(uint32_t **buf, size_t *cap, size_t need, hipStream_t stream)
+{
+    if (*cap >= need && *buf) return NUPS_OK;
+    NUPS_HIP(hipStreamSynchronize(stream));
+    if (*buf) NUPS_HIP(hipFree(*buf));
+    *buf = nullptr;
+    const size_t n = need + need / 4 + 1024;
+    NUPS_HIP(hipMalloc((void **)buf, sizeof(uint32_t) * n));
+    *cap = n;
+    return NUPS_OK;
+}
+
+PhaseScope::PhaseScope(nups_ctx *c, int p) : ctx(c), phase(p)
+{
+    if (!ctx->profiling) return;
+    Phase &ph = ctx->phase[phase];
+    auto get = [&]() {
+        hipEvent_t e = nullptr;
+        if (!ph.free_events.empty()) { e = ph.free_events.back(); ph.free_events.pop_back(); }
+        else if (hipEventCreate(&e) != hipSuccess) e = nullptr;
+        return e;
+    };
+    start = get();
+    if (start) (void)hipEventRecord(start, ctx->stream);
+}
+
+PhaseScope::~PhaseScope()
+{
+    if (!start) return;
+    Phase &ph = ctx->phase[phase];
+    hipEvent_t stop = nullptr;
+    if (!ph.free_events.empty()) { stop = ph.free_events.back(); ph.free_events.pop_back(); }
+    else if (hipEventCreate(&stop) != hipSuccess) stop = nullptr;
+    if (!stop) { ph.free_events.push_back(start); return; }
+    (void)hipEventRecord(stop, ctx->stream);
+    ph.pending.emplace_back(start, stop);
+}
+
+static void free_plan(Plan &pl)
+{
+    PlanArgs &a = pl.a;
+    for (uint32_t *p : {a.bitmap, a.word_rank, a.tile_sum, a.uniq, a.count, a.seg, a.slot, a.rank, a.perm,
+                        a.long_list, a.meta})
+        if (p) (void)hipFree(p);
+    pl = Plan{};
+}
+
+static void free_sample(nups_sample *h)
+{
+    if (h->keys_dev) (void)hipFree(h->keys_dev);
+    if (h->fresh_dev) (void)hipFree(h->fresh_dev);
+    delete h;
+}
+
+static void free_dist(nups_dist *d)
+{
+    for (nups_sample *h : d->live) free_sample(h);
+    for (nups_sample *h : d->recycled) free_sample(h);
+    if (d->thresh_dev) (void)hipFree(d->thresh_dev);
+    if (d->alias_dev) (void)hipFree(d->alias_dev);
+    delete d;
+}
+
+// Waits for the stream and turns a raised device flag into an error.
+static nups_status sync_and_check(nups_ctx *ctx)
+{
+    NUPS_HIP(hipMemcpyAsync(ctx->flag_pinned, ctx->error_flag, sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
+    NUPS_HIP(hipStreamSynchronize(ctx->stream));
+    if (*ctx->flag_pinned != 0) {
+        NUPS_HIP(hipMemsetAsync(ctx->error_flag, 0, sizeof(uint32_t), ctx->stream));
+        NUPS_HIP(hipStreamSynchronize(ctx->stream));
+        return fail(NUPS_ERR_KEY_RANGE, "a key was outside its table (it was skipped)");
+    }
+    return NUPS_OK;
+}
+
+static bool valid_table(const nups_ctx *ctx, int t) { return ctx && t >= 0 && t < ctx->n_tables; }
+
+}  // namespace nups
+
+using namespace nups;
+
+extern "C" {
+
+const char *nups_last_error(void) { return g_error.c_str(); }
+
+const char *nups_phase_name(int phase)
+{
+    static const char *names[NUPS_PHASE_COUNT] = {"sample", "plan", "grad", "apply0", "apply1", "pull", "push"};
+    return (phase >= 0 && phase < NUPS_PHASE_COUNT) ? names[phase] : "";
+}
+
+nups_status nups_init(nups_ctx **out, int n_tables, float *const *tables_dev, const int64_t *num_keys,
+                      const int32_t *dim, const int32_t *row_stride, void *hip_stream)
+{
+    if (!out) return fail(NUPS_ERR_ARG, "nups_init: out is null");
+    *out = nullptr;
+    if (!tables_dev || !num_keys || !dim || !row_stride) return fail(NUPS_ERR_ARG, "nups_init: null array");
+    if (n_tables < 1 || n_tables > kMaxTables) return fail(NUPS_ERR_ARG, "nups_init: n_tables must be 1..4");
+    for (int t = 0; t < n_tables; ++t) {
+        if (!tables_dev[t]) return fail(NUPS_ERR_ARG, "nups_init: null table");
+        if (num_keys[t] < 1 || num_keys[t] > 0xFFFFFFFFll) return fail(NUPS_ERR_ARG, "nups_init: num_keys out of range");
+        if (dim[t] < 1 || dim[t] > row_stride[t]) return fail(NUPS_ERR_ARG, "nups_init: need 1 <= dim <= row_stride");
+        if (row_stride[t] % 64 != 0 || row_stride[t] > kMaxStride)
+            return fail(NUPS_ERR_ARG, "nups_init: row_stride must be a multiple of 64 floats, at most 1024");
+    }
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(NUPS_ERR_DEVICE, "nups_init: no HIP device");
+    nups_ctx *ctx = new nups_ctx();
+    NUPS_HIP(hipGetDevice(&ctx->device));
+    ctx->n_tables = n_tables;
+    ctx->stream = (hipStream_t)hip_stream;
+    for (int t = 0; t < n_tables; ++t) {
+        ctx->tab[t].data = tables_dev[t];
+        ctx->tab[t].num_keys = num_keys[t];
+        ctx->tab[t].dim = dim[t];
+        ctx->tab[t].stride = row_stride[t];
+    }
+    hipError_t e = hipMalloc((void **)&ctx->loss_dev, sizeof(double));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->error_flag, sizeof(uint32_t));
+    if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->loss_pinned, sizeof(double), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->flag_pinned, sizeof(uint32_t), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipMemsetAsync(ctx->error_flag, 0, sizeof(uint32_t), ctx->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(ctx->loss_dev, 0, sizeof(double), ctx->stream);
+    if (e != hipSuccess) {
+        hip_ok(e, "nups_init: workspace allocation");
+        nups_destroy(ctx);
+        return NUPS_ERR_DEVICE;
+    }
+    *out = ctx;
+    return NUPS_OK;
+}
+
+nups_status nups_destroy(nups_ctx *ctx)
+{
+    if (!ctx) return fail(NUPS_ERR_ARG, "nups_destroy: null context");
+    (void)hipStreamSynchronize(ctx->stream);
+    for (nups_dist *d : ctx->dists) free_dist(d);
+    for (int t = 0; t < kMaxTables; ++t) {
+        free_plan(ctx->tab[t].plan);
+        if (ctx->tab[t].hot_slot_dev) (void)hipFree(ctx->tab[t].hot_slot_dev);
+    }
+    if (ctx->coef) (void)hipFree(ctx->coef);
+    if (ctx->stage) (void)hipFree(ctx->stage);
+    if (ctx->loss_dev) (void)hipFree(ctx->loss_dev);
+    if (ctx->error_flag) (void)hipFree(ctx->error_flag);
+    if (ctx->loss_pinned) (void)hipHostFree(ctx->loss_pinned);
+    if (ctx->flag_pinned) (void)hipHostFree(ctx->flag_pinned);
+    for (Phase &ph : ctx->phase) {
+        for (auto &pr : ph.pending) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
+        for (hipEvent_t ev : ph.free_events) (void)hipEventDestroy(ev);
+    }
+    delete ctx;
+    return NUPS_OK;
+}
+
+nups_status nups_set_state(nups_ctx *ctx, int table, float *state_dev)
+{
+    if (!valid_table(ctx, table)) return fail(NUPS_ERR_ARG, "nups_set_state: bad context or table");
+    if (!state_dev) return fail(NUPS_ERR_ARG, "nups_set_state: null state");
+    ctx->tab[table].state = state_dev;
+    return NUPS_OK;
+}
+
+nups_status nups_set_hot_keys(nups_ctx *ctx, int table, const uint32_t *keys_host, int64_t k)
+{
+    if (!valid_table(ctx, table)) return fail(NUPS_ERR_ARG, "nups_set_hot_keys: bad context or table");
+    if (k < 0 || (k > 0 && !keys_host)) return fail(NUPS_ERR_ARG, "nups_set_hot_keys: bad key list");
+    Table &t = ctx->tab[table];
+    std::vector<uint32_t> keys(keys_host, keys_host + k);
+    std::vector<uint32_t> sorted(keys);
+    std::sort(sorted.begin(), sorted.end());
+    if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end())
+        return fail(NUPS_ERR_ARG, "nups_set_hot_keys: keys must be distinct");
+    if (k > 0 && (int64_t)sorted.back() >= t.num_keys) return fail(NUPS_ERR_KEY_RANGE, "nups_set_hot_keys: key out of range");
+    t.hot_keys.swap(keys);
+    return NUPS_OK;
+}
+
+nups_status nups_pull(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_t n, float *values_dev)
+{
+    if (!valid_table(ctx, table)) return fail(NUPS_ERR_ARG, "nups_pull: bad context or table");
+    if (n < 0 || (n > 0 && (!keys_dev || !values_dev))) return fail(NUPS_ERR_ARG, "nups_pull: bad arguments");
+    return launch_pull(ctx, ctx->tab[table], keys_dev, n, values_dev);
+}
+
+nups_status nups_push(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_t n, const float *updates_dev)
+{
+    if (!valid_table(ctx, table)) return fail(NUPS_ERR_ARG, "nups_push: bad context or table");
+    if (n < 0 || n > 0x7FFFFFFFll || (n > 0 && (!keys_dev || !updates_dev)))
+        return fail(NUPS_ERR_ARG, "nups_push: bad arguments");
+    Table &t = ctx->tab[table];
+    nups_status st;
+    if ((st = ensure_plan_capacity(ctx, t, (size_t)n)) != NUPS_OK) return st;
+    t.plan.a.src = KeySource{{keys_dev, nullptr, nullptr}, {(uint32_t)n, 0, 0}};
+    t.plan.a.n = (uint32_t)n;
+    Plan *plans[1] = {&t.plan};
+    if ((st = build_plans(ctx, plans, 1)) != NUPS_OK) return st;
+    if (n == 0) return NUPS_OK;
+    return launch_push_apply(ctx, t, updates_dev);
+}
+
+nups_status nups_register_distribution(nups_ctx *ctx, int table, const double *weights_host, nups_scheme scheme,
+                                       int32_t U, int32_t G, int64_t P, int32_t R, uint64_t seed, nups_dist **out)
+{
+    if (!out) return fail(NUPS_ERR_ARG, "nups_register_distribution: out is null");
+    *out = nullptr;
+    if (!valid_table(ctx, table)) return fail(NUPS_ERR_ARG, "nups_register_distribution: bad context or table");
+    if (scheme < NUPS_CONFORM || scheme > NUPS_NONCONFORM)
+        return fail(NUPS_ERR_ARG, "nups_register_distribution: unknown scheme");
+    if (scheme == NUPS_BOUNDED && (U < 1 || G < 1 || G > 1024))
+        return fail(NUPS_ERR_ARG, "nups_register_distribution: BOUNDED needs U >= 1 and 1 <= G <= 1024");
+    if (scheme == NUPS_LONGTERM && (P < 1 || R < 1 || P > (1ll << 40)))
+        return fail(NUPS_ERR_ARG, "nups_register_distribution: LONG-TERM needs P >= 1 and R >= 1");
+    if (ctx->dists.size() >= 255) return fail(NUPS_ERR_STATE, "nups_register_distribution: too many distributions");
+    const int64_t V = ctx->tab[table].num_keys;
+    std::vector<uint32_t> thresh, alias;
+    if (weights_host) {
+        thresh.resize((size_t)V);
+        alias.resize((size_t)V);
+        nups_status st = nups_build_alias_table(weights_host, V, thresh.data(), alias.data());
+        if (st != NUPS_OK) return st;
+    }
+    nups_dist *d = new nups_dist();
+    d->ctx = ctx;
+    d->table = table;
+    d->id = (uint32_t)ctx->dists.size();
+    d->scheme = scheme;
+    d->uniform = (weights_host == nullptr);
+    d->U = U; d->G = G; d->P = P; d->R = R;
+    d->seed = seed;
+    if (weights_host) {
+        hipError_t e = hipMalloc((void **)&d->thresh_dev, sizeof(uint32_t) * (size_t)V);
+        if (e == hipSuccess) e = hipMalloc((void **)&d->alias_dev, sizeof(uint32_t) * (size_t)V);
+        if (e == hipSuccess) e = hipMemcpy(d->thresh_dev, thresh.data(), sizeof(uint32_t) * (size_t)V, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(d->alias_dev, alias.data(), sizeof(uint32_t) * (size_t)V, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            hip_ok(e, "nups_register_distribution: alias table upload");
+            free_dist(d);
+            return NUPS_ERR_DEVICE;
+        }
+    }
+    ctx->dists.push_back(d);
+    *out = d;
+    return NUPS_OK;
+}
+
+nups_status nups_set_local_keys(nups_dist *dist, const uint32_t *keys_a_dev, const uint32_t *keys_b_dev,
+                                int64_t n_examples, int32_t per_example, int32_t split, int32_t tile)
+{
+    if (!dist) return fail(NUPS_ERR_ARG, "nups_set_local_keys: null distribution");
+    if (dist->scheme != NUPS_NONCONFORM) return fail(NUPS_ERR_STATE, "nups_set_local_keys: scheme is not NON-CONFORM");
+    if (!keys_a_dev || !keys_b_dev || n_examples < 1 || n_examples > 0x7FFFFFFFll || per_example < 1 || split < 0
+        || split > per_example || tile < 1)
+        return fail(NUPS_ERR_ARG, "nups_set_local_keys: bad arguments");
+    dist->local_a = keys_a_dev;
+    dist->local_b = keys_b_dev;
+    dist->local_n = n_examples;
+    dist->per_example = per_example;
+    dist->split = split;
+    dist->tile = tile;
+    return NUPS_OK;
+}
+
+nups_status nups_prepare_sample(nups_dist *dist, int64_t n, uint64_t step, nups_sample **out)
+{
+    if (!out) return fail(NUPS_ERR_ARG, "nups_prepare_sample: out is null");
+    *out = nullptr;
+    if (!dist) return fail(NUPS_ERR_ARG, "nups_prepare_sample: null distribution");
+    if (n < 0 || n > 0x7FFFFFFFll) return fail(NUPS_ERR_ARG, "nups_prepare_sample: n out of range");
+    if (step >> 48) return fail(NUPS_ERR_ARG, "nups_prepare_sample: step must be below 2^48");
+    if (dist->scheme == NUPS_NONCONFORM) {
+        if (!dist->local_a) return fail(NUPS_ERR_STATE, "nups_prepare_sample: call nups_set_local_keys first");
+        if (n > dist->local_n * (int64_t)dist->per_example)
+            return fail(NUPS_ERR_ARG, "nups_prepare_sample: more samples than examples * per_example");
+    }
+    nups_ctx *ctx = dist->ctx;
+    nups_sample *h = nullptr;
+    if (!dist->recycled.empty()) { h = dist->recycled.back(); dist->recycled.pop_back(); }
+    else { h = new nups_sample(); h->dist = dist; }
+    nups_status st = ensure_u32(&h->keys_dev, &h->cap, (size_t)n, ctx->stream);
+    if (st == NUPS_OK && dist->scheme == NUPS_BOUNDED)
+        st = ensure_u32(&h->fresh_dev, &h->fresh_cap, (size_t)((n + dist->U - 1) / dist->U), ctx->stream);
+    if (st != NUPS_OK) { dist->recycled.push_back(h); return st; }
+    h->n = n;
+    h->pulled = 0;
+    h->live = true;
+    st = launch_sample(dist, h, step);
+    if (st != NUPS_OK) { h->live = false; dist->recycled.push_back(h); return st; }
+    dist->live.push_back(h);
+    *out = h;
+    return NUPS_OK;
+}
+
+nups_status nups_pull_sample(nups_sample *h, int64_t n_j, uint32_t *keys_dev, float *values_dev)
+{
+    if (!h) return fail(NUPS_ERR_ARG, "nups_pull_sample: null handle");
+    if (!h->live) return fail(NUPS_ERR_STATE, "nups_pull_sample: handle was released");
+    if (n_j < 0) return fail(NUPS_ERR_ARG, "nups_pull_sample: negative count");
+    if (h->pulled + n_j > h->n) return fail(NUPS_ERR_OVERPULL, "nups_pull_sample: more samples requested than prepared");
+    if (n_j == 0) return NUPS_OK;
+    nups_ctx *ctx = h->dist->ctx;
+    const uint32_t *src = h->keys_dev + h->pulled;
+    if (keys_dev)
+        NUPS_HIP(hipMemcpyAsync(keys_dev, src, sizeof(uint32_t) * (size_t)n_j, hipMemcpyDeviceToDevice, ctx->stream));
+    if (values_dev) {
+        nups_status st = launch_pull(ctx, ctx->tab[h->dist->table], src, n_j, values_dev);
+        if (st != NUPS_OK) return st;
+    }
+    h->pulled += n_j;
+    return NUPS_OK;
+}
+
+nups_status nups_sample_keys(nups_sample *h, const uint32_t **keys_dev, int64_t *n)
+{
+    if (!h || !keys_dev) return fail(NUPS_ERR_ARG, "nups_sample_keys: null argument");
+    if (!h->live) return fail(NUPS_ERR_STATE, "nups_sample_keys: handle was released");
+    *keys_dev = h->keys_dev;
+    if (n) *n = h->n;
+    return NUPS_OK;
+}
+
+nups_status nups_release_sample(nups_sample *h)
+{
+    if (!h) return fail(NUPS_ERR_ARG, "nups_release_sample: null handle");
+    if (!h->live) return fail(NUPS_ERR_STATE, "nups_release_sample: handle already released");
+    nups_dist *d = h->dist;
+    h->live = false;
+    d->live.erase(std::remove(d->live.begin(), d->live.end(), h), d->live.end());
+    d->recycled.push_back(h);
+    return NUPS_OK;
+}
+
+nups_status nups_step(nups_ctx *ctx, const nups_batch *b, double *loss_sum_host)
+{
+    if (!ctx || !b) return fail(NUPS_ERR_ARG, "nups_step: null argument");
+    if (ctx->n_tables < 2) return fail(NUPS_ERR_STATE, "nups_step: the context needs two tables");
+    if (b->B < 0 || b->B > (1ll << 24)) return fail(NUPS_ERR_ARG, "nups_step: batch size out of range");
+    if (b->n_neg < 0 || b->n_neg2 < 0 || b->n_neg > 4096 || b->n_neg2 > 4096)
+        return fail(NUPS_ERR_ARG, "nups_step: negative counts out of range");
+    if (b->B > 0 && (!b->k0 || !b->k1)) return fail(NUPS_ERR_ARG, "nups_step: null key array");
+    const int64_t nn = (int64_t)b->n_neg + b->n_neg2;
+    if (b->B * (nn + 2) > 0x7FFFFFFFll) return fail(NUPS_ERR_ARG, "nups_step: too many accesses for one step");
+    if (ctx->tab[0].stride != ctx->tab[1].stride) return fail(NUPS_ERR_ARG, "nups_step: tables 0 and 1 need equal row_stride");
+    nups_status st;
+    switch (b->task) {
+    case NUPS_TASK_SGNS:
+        if (b->n_neg2 != 0) return fail(NUPS_ERR_ARG, "nups_step: SGNS uses n_neg only");
+        if (b->B > 0 && b->n_neg > 0 && !b->negs) return fail(NUPS_ERR_ARG, "nups_step: null negatives");
+        st = launch_step_sgns(ctx, *b);
+        break;
+    case NUPS_TASK_MF:
+        if (b->B > 0 && !b->val) return fail(NUPS_ERR_ARG, "nups_step: null cell values");
+        if (nn != 0) return fail(NUPS_ERR_ARG, "nups_step: MF has no sampling access");
+        st = launch_step_mf(ctx, *b);
+        break;
+    case NUPS_TASK_KGE:
+        if (b->B > 0 && !b->k2) return fail(NUPS_ERR_ARG, "nups_step: null object keys");
+        if (b->B > 0 && nn > 0 && !b->negs) return fail(NUPS_ERR_ARG, "nups_step: null negatives");
+        if (!ctx->tab[0].state || !ctx->tab[1].state)
+            return fail(NUPS_ERR_STATE, "nups_step: KGE needs AdaGrad state on tables 0 and 1 (nups_set_state)");
+        st = launch_step_kge(ctx, *b);
+        break;
+    default:
+        return fail(NUPS_ERR_ARG, "nups_step: unknown task");
+    }
+    if (st != NUPS_OK) return st;
+    if (loss_sum_host) {
+        NUPS_HIP(hipMemcpyAsync(ctx->loss_pinned, ctx->loss_dev, sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
+        st = sync_and_check(ctx);
+        *loss_sum_host = *ctx->loss_pinned;
+        return st;
+    }
+    return NUPS_OK;
+}
+
+nups_status nups_debug_structure(nups_ctx *ctx, int table, uint32_t *uniq_keys_dev, uint32_t *counts_dev,
+                                 int64_t *n_uniq_host)
+{
+    if (!valid_table(ctx, table) || !n_uniq_host) return fail(NUPS_ERR_ARG, "nups_debug_structure: bad arguments");
+    Plan &pl = ctx->tab[table].plan;
+    if (!pl.valid) return fail(NUPS_ERR_STATE, "nups_debug_structure: no step or push has run on this table");
+    uint32_t meta[kMetaWords];
+    NUPS_HIP(hipMemcpyAsync(meta, pl.a.meta, sizeof(meta), hipMemcpyDeviceToHost, ctx->stream));
+    NUPS_HIP(hipStreamSynchronize(ctx->stream));
+    const size_t nu = meta[kMetaNumUniq];
+    if (uniq_keys_dev)
+        NUPS_HIP(hipMemcpyAsync(uniq_keys_dev, pl.a.uniq, sizeof(uint32_t) * nu, hipMemcpyDeviceToDevice, ctx->stream));
+    if (counts_dev)
+        NUPS_HIP(hipMemcpyAsync(counts_dev, pl.a.count, sizeof(uint32_t) * nu, hipMemcpyDeviceToDevice, ctx->stream));
+    *n_uniq_host = (int64_t)nu;
+    return sync_and_check(ctx);
+}
+
+nups_status nups_check(nups_ctx *ctx)
+{
+    if (!ctx) return fail(NUPS_ERR_ARG, "nups_check: null context");
+    return sync_and_check(ctx);
+}
+
+nups_status nups_profile(nups_ctx *ctx, int enable)
+{
+    if (!ctx) return fail(NUPS_ERR_ARG, "nups_profile: null context");
+    ctx->profiling = enable != 0;
+    return NUPS_OK;
+}
+
+nups_status nups_profile_read(nups_ctx *ctx, int phase, double *ms_total, int64_t *launches)
+{
+    if (!ctx || phase < 0 || phase >= NUPS_PHASE_COUNT) return fail(NUPS_ERR_ARG, "nups_profile_read: bad arguments");
+    NUPS_HIP(hipStreamSynchronize(ctx->stream));
+    Phase &ph = ctx->phase[phase];
+    for (auto &pr : ph.pending) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) { ph.ms += ms; ph.launches += 1; }
+        ph.free_events.push_back(pr.first);
+        ph.free_events.push_back(pr.second);
+    }
+    ph.pending.clear();
+    if (ms_total) *ms_total = ph.ms;
+    if (launches) *launches = ph.launches;
+    ph.ms = 0.0;
+    ph.launches = 0;
+    return NUPS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,183 @@
+// Device-side helpers: counter-based random words, 16-lane row groups, workgroup scans.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "nups_internal.h"
+
+namespace nups {
+
+struct Words {
+    uint32_t x0, x1, x2, x3;
+};
+
+// Philox-4x32, 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11).
+__device__ __forceinline__ Words philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1)
+{
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+        const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0;
+        const uint32_t n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += W0; k1 += W1;
+    }
+    return Words{c0, c1, c2, c3};
+}
+
+// The four words of draw `draw` of step `step`: key = seed halves,
+// counter = (draw lo, draw hi, step lo, stream | dist << 8 | step bits 32..47 << 16).
+__device__ __forceinline__ Words draw_words(uint64_t seed, uint32_t stream, uint32_t dist, uint64_t step,
+                                            uint64_t draw)
+{
+    const uint32_t c3 = (stream & 0xFFu) | ((dist & 0xFFu) << 8) | ((uint32_t)((step >> 32) & 0xFFFFu) << 16);
+    return philox4x32_10((uint32_t)draw, (uint32_t)(draw >> 32), (uint32_t)step, c3, (uint32_t)seed,
+                         (uint32_t)(seed >> 32));
+}
+
+// Sum over the 16 lanes of a row group; every lane of the group receives the total.
+__device__ __forceinline__ float group_sum(float x)
+{
+    x += __shfl_xor(x, 1, kGroup);
+    x += __shfl_xor(x, 2, kGroup);
+    x += __shfl_xor(x, 4, kGroup);
+    x += __shfl_xor(x, 8, kGroup);
+    return x;
+}
+
+__device__ __forceinline__ float wave_sum(float x)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+__device__ __forceinline__ float dot4(const float4 a, const float4 b)
+{
+    return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+}
+
+__device__ __forceinline__ void axpy4(float4 &acc, float a, const float4 x)
+{
+    acc.x += a * x.x; acc.y += a * x.y; acc.z += a * x.z; acc.w += a * x.w;
+}
+
+// A row of NV4 * 64 floats held by a 16-lane group: lane l owns float4 number l + 16 q, q < NV4.
+template <int NV4>
+struct Row {
+    float4 v[NV4];
+};
+
+template <int NV4>
+__device__ __forceinline__ void load_row(Row<NV4> &r, const float *base, int lane)
+{
+    const float4 *p = reinterpret_cast<const float4 *>(base) + lane;
+#pragma unroll
+    for (int q = 0; q < NV4; ++q) r.v[q] = p[q * kGroup];
+}
+
+template <int NV4>
+__device__ __forceinline__ void store_row(float *base, const Row<NV4> &r, int lane)
+{
+    float4 *p = reinterpret_cast<float4 *>(base) + lane;
+#pragma unroll
+    for (int q = 0; q < NV4; ++q) p[q * kGroup] = r.v[q];
+}
+
+template <int NV4>
+__device__ __forceinline__ void zero_row(Row<NV4> &r)
+{
+#pragma unroll
+    for (int q = 0; q < NV4; ++q) r.v[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+template <int NV4>
+__device__ __forceinline__ float partial_dot(const Row<NV4> &a, const Row<NV4> &b)
+{
+    float s = 0.f;
+#pragma unroll
+    for (int q = 0; q < NV4; ++q) s += dot4(a.v[q], b.v[q]);
+    return s;
+}
+
+template <int NV4>
+__device__ __forceinline__ void axpy_row(Row<NV4> &acc, float a, const Row<NV4> &x)
+{
+#pragma unroll
+    for (int q = 0; q < NV4; ++q) axpy4(acc.v[q], a, x.v[q]);
+}
+
+__device__ __forceinline__ float sigmoidf(float z) { return 1.0f / (1.0f + __expf(-z)); }
+
+// log(1 + e^x), stable.
+__device__ __forceinline__ float softplusf(float x)
+{
+    return x > 0.f ? x + log1pf(__expf(-x)) : log1pf(__expf(x));
+}
+
+// Exclusive prefix sum of one value per thread over a workgroup of kBlock threads.
+// Returns the exclusive prefix; *total receives the workgroup sum.  `lds` needs kBlock / 64 + 1 words.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t *lds, uint32_t *total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = x;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t y = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += y;
+    }
+    __syncthreads();                  // lds may still be read from a previous call
+    if (lane == 63) lds[wave] = incl;
+    __syncthreads();
+    uint32_t base = 0, sum = 0;
+#pragma unroll
+    for (int w = 0; w < kBlock / 64; ++w) {
+        const uint32_t s = lds[w];
+        if (w < wave) base += s;
+        sum += s;
+    }
+    *total = sum;
+    return base + incl - x;
+}
+
+__device__ __forceinline__ uint32_t block_sum(uint32_t x, uint32_t *lds)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+    __syncthreads();
+    if (lane == 0) lds[wave] = x;
+    __syncthreads();
+    uint32_t sum = 0;
+#pragma unroll
+    for (int w = 0; w < kBlock / 64; ++w) sum += lds[w];
+    return sum;
+}
+
+// Adds one value per workgroup to a double accumulator in memory.
+__device__ __forceinline__ void block_add_loss(float x, double *loss, float *lds)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    x = wave_sum(x);
+    if (lane == 0) lds[wave] = x;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double s = 0.0;
+        for (int w = 0; w < kBlock / 64; ++w) s += (double)lds[w];
+        atomicAdd(loss, s);
+    }
+}
+
+__device__ __forceinline__ uint32_t source_key(const KeySource &s, uint32_t i)
+{
+    if (i < s.len[0]) return s.ptr[0][i];
+    i -= s.len[0];
+    if (i < s.len[1]) return s.ptr[1][i];
+    return s.ptr[2][i - s.len[1]];
+}
+
+}  // namespace nups

@@ -1,0 +1,223 @@
+// "Aggregate per key, then push": for every distinct key of a plan, sum the gradient
+// contributions of its accesses and update the row once.  A contribution is a coefficient times
+// a source row (a staged gradient row, or a row of another table); the sum is kept in registers
+// by a 16-lane row group, so each touched row is read once and written once.
+// Short segments take one row group each; long segments (the hot keys of Section 3.2) take a
+// whole workgroup whose 16 groups sum interleaved slices that are then combined in LDS in a
+// fixed order.
+#pragma once
+
+#include "device_utils.h"
+
+namespace nups {
+
+// ---- contribution sources: access i -> (coefficient, source row) ---------------------------
+
+// Row i of a staging array, coefficient one (SGNS input side, MF, KGE subject/object/relation, push).
+struct SrcStaged {
+    const float *stage;
+    __device__ __forceinline__ float coef(uint32_t) const { return 1.0f; }
+    __device__ __forceinline__ const float *row(uint32_t i, int stride) const { return stage + (size_t)i * stride; }
+};
+
+// SGNS output side: access i < B is the context word of pair i, access B + p is negative p (pair p / K).
+// The gradient of the scored row is coef * (input vector of the pair's center word).
+struct SrcSgnsOut {
+    const float *in_table;
+    const uint32_t *center;
+    const float *coefs;   // [B, K + 1]
+    uint32_t B, K, num_in;
+    __device__ __forceinline__ uint32_t pair_of(uint32_t i) const { return i < B ? i : (i - B) / K; }
+    __device__ __forceinline__ float coef(uint32_t i) const
+    {
+        return i < B ? coefs[(size_t)i * (K + 1)] : coefs[(size_t)((i - B) / K) * (K + 1) + 1 + (i - B) % K];
+    }
+    __device__ __forceinline__ const float *row(uint32_t i, int stride) const
+    {
+        return in_table + (size_t)min(center[pair_of(i)], num_in - 1) * stride;
+    }
+};
+
+// KGE entity table: accesses [0,B) subjects and [B,2B) objects take their staged gradient rows;
+// access 2B + p is negative p of triple p / nn and takes coef * (staged direction row of that
+// triple: rows 2B.. for replaced subjects, rows 3B.. for replaced objects).
+struct SrcKgeEntity {
+    const float *stage;
+    const float *coefs;   // [B, nn]
+    uint32_t B, nn, nh;
+    __device__ __forceinline__ float coef(uint32_t i) const { return i < 2 * B ? 1.0f : coefs[i - 2 * B]; }
+    __device__ __forceinline__ const float *row(uint32_t i, int stride) const
+    {
+        if (i < 2 * B) return stage + (size_t)i * stride;
+        const uint32_t p = i - 2 * B, e = p / nn;
+        return stage + (size_t)(((p % nn) < nh ? 2 * B : 3 * B) + e) * stride;
+    }
+};
+
+// ---- update rules ----------------------------------------------------------------------------
+
+struct OptSgd {          // theta <- theta - lr * delta
+    float lr;
+    template <int NV4>
+    __device__ __forceinline__ void apply(float *row, float *, const Row<NV4> &d, int lane) const
+    {
+        Row<NV4> t;
+        load_row(t, row, lane);
+#pragma unroll
+        for (int q = 0; q < NV4; ++q) axpy4(t.v[q], -lr, d.v[q]);
+        store_row(row, t, lane);
+    }
+};
+
+struct OptAdd {          // theta <- theta + delta   (push)
+    template <int NV4>
+    __device__ __forceinline__ void apply(float *row, float *, const Row<NV4> &d, int lane) const
+    {
+        Row<NV4> t;
+        load_row(t, row, lane);
+#pragma unroll
+        for (int q = 0; q < NV4; ++q) axpy4(t.v[q], 1.0f, d.v[q]);
+        store_row(row, t, lane);
+    }
+};
+
+struct OptAdagrad {      // G <- G + delta^2 ; theta <- theta - lr * delta / (sqrt(G) + eps)
+    float lr, eps;
+    __device__ __forceinline__ void one(float &t, float &g, float d) const
+    {
+        g += d * d;
+        t -= lr * d / (sqrtf(g) + eps);
+    }
+    template <int NV4>
+    __device__ __forceinline__ void apply(float *row, float *state_row, const Row<NV4> &d, int lane) const
+    {
+        Row<NV4> t, g;
+        load_row(t, row, lane);
+        load_row(g, state_row, lane);
+#pragma unroll
+        for (int q = 0; q < NV4; ++q) {
+            one(t.v[q].x, g.v[q].x, d.v[q].x);
+            one(t.v[q].y, g.v[q].y, d.v[q].y);
+            one(t.v[q].z, g.v[q].z, d.v[q].z);
+            one(t.v[q].w, g.v[q].w, d.v[q].w);
+        }
+        store_row(state_row, g, lane);
+        store_row(row, t, lane);
+    }
+};
+
+// ---- kernels ---------------------------------------------------------------------------------
+
+struct ApplyArgs {
+    float *table;
+    float *state;
+    const uint32_t *uniq, *seg, *perm, *meta, *long_list;
+    int stride;
+};
+
+// Sums accesses first, first+step, ... < last of a segment into acc (four row loads in flight).
+template <int NV4, class Src>
+__device__ __forceinline__ void sum_segment(Row<NV4> &acc, const Src &src, const uint32_t *perm, uint32_t first,
+                                            uint32_t last, uint32_t step, int stride, int lane)
+{
+    uint32_t t = first;
+    for (; t + 3 * step < last; t += 4 * step) {
+        const uint32_t i0 = perm[t], i1 = perm[t + step], i2 = perm[t + 2 * step], i3 = perm[t + 3 * step];
+        Row<NV4> r0, r1, r2, r3;
+        load_row(r0, src.row(i0, stride), lane);
+        load_row(r1, src.row(i1, stride), lane);
+        load_row(r2, src.row(i2, stride), lane);
+        load_row(r3, src.row(i3, stride), lane);
+        const float c0 = src.coef(i0), c1 = src.coef(i1), c2 = src.coef(i2), c3 = src.coef(i3);
+        axpy_row(acc, c0, r0);
+        axpy_row(acc, c1, r1);
+        axpy_row(acc, c2, r2);
+        axpy_row(acc, c3, r3);
+    }
+    for (; t < last; t += step) {
+        const uint32_t i = perm[t];
+        Row<NV4> r;
+        load_row(r, src.row(i, stride), lane);
+        axpy_row(acc, src.coef(i), r);
+    }
+}
+
+// One 16-lane group per distinct key with at most kLongSegment accesses.
+template <int NV4, class Src, class Opt>
+__global__ void __launch_bounds__(kBlock) k_apply_short(ApplyArgs a, Src src, Opt opt)
+{
+    const int lane = threadIdx.x & (kGroup - 1);
+    const uint32_t u = (blockIdx.x * kBlock + threadIdx.x) / kGroup;
+    if (u >= a.meta[kMetaNumUniq]) return;
+    const uint32_t first = a.seg[u], last = a.seg[u + 1];
+    if (last - first > kLongSegment) return;
+    Row<NV4> acc;
+    zero_row(acc);
+    sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
+    const size_t off = (size_t)a.uniq[u] * a.stride;
+    opt.template apply<NV4>(a.table + off, a.state ? a.state + off : nullptr, acc, lane);
+}
+
+// One workgroup per long segment.
+template <int NV4, class Src, class Opt>
+__global__ void __launch_bounds__(kBlock) k_apply_long(ApplyArgs a, Src src, Opt opt)
+{
+    extern __shared__ float part[];   // [kGroupsPerBlock - 1][stride]
+    if (blockIdx.x >= a.meta[kMetaNumLong]) return;
+    const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
+    const uint32_t u = a.long_list[blockIdx.x];
+    const uint32_t first = a.seg[u], last = a.seg[u + 1];
+    Row<NV4> acc;
+    zero_row(acc);
+    sum_segment<NV4>(acc, src, a.perm, first + group, last, kGroupsPerBlock, a.stride, lane);
+    if (group > 0) store_row(part + (size_t)(group - 1) * a.stride, acc, lane);
+    __syncthreads();
+    if (group == 0) {
+        for (int g = 1; g < kGroupsPerBlock; ++g) {
+            Row<NV4> r;
+            load_row(r, part + (size_t)(g - 1) * a.stride, lane);
+            axpy_row(acc, 1.0f, r);
+        }
+        const size_t off = (size_t)a.uniq[u] * a.stride;
+        opt.template apply<NV4>(a.table + off, a.state ? a.state + off : nullptr, acc, lane);
+    }
+}
+
+template <int NV4, class Src, class Opt>
+static void launch_apply_nv(hipStream_t s, const Plan &pl, float *table, float *state, int stride, const Src &src,
+                            const Opt &opt)
+{
+    const PlanArgs &p = pl.a;
+    if (p.n == 0) return;
+    ApplyArgs a{table, state, p.uniq, p.seg, p.perm, p.meta, p.long_list, stride};
+    const uint32_t groups = p.n;                       // upper bound of the number of distinct keys
+    const uint32_t blocks = (groups + kGroupsPerBlock - 1) / kGroupsPerBlock;
+    hipLaunchKernelGGL((k_apply_short<NV4, Src, Opt>), dim3(blocks), dim3(kBlock), 0, s, a, src, opt);
+    const uint32_t max_long = p.n / (kLongSegment + 1);
+    if (max_long > 0) {
+        const size_t lds = sizeof(float) * (size_t)(kGroupsPerBlock - 1) * stride;
+        hipLaunchKernelGGL((k_apply_long<NV4, Src, Opt>), dim3(max_long), dim3(kBlock), lds, s, a, src, opt);
+    }
+}
+
+// Dispatch on the row length (stride / 64 float4 per lane).
+template <class Src, class Opt>
+static nups_status launch_apply(hipStream_t s, const Plan &pl, float *table, float *state, int stride,
+                                const Src &src, const Opt &opt)
+{
+    switch (stride / 64) {
+    case 1: launch_apply_nv<1>(s, pl, table, state, stride, src, opt); break;
+    case 2: launch_apply_nv<2>(s, pl, table, state, stride, src, opt); break;
+    case 3: launch_apply_nv<3>(s, pl, table, state, stride, src, opt); break;
+    case 4: launch_apply_nv<4>(s, pl, table, state, stride, src, opt); break;
+    case 5: launch_apply_nv<5>(s, pl, table, state, stride, src, opt); break;
+    case 6: launch_apply_nv<6>(s, pl, table, state, stride, src, opt); break;
+    case 8: launch_apply_nv<8>(s, pl, table, state, stride, src, opt); break;
+    case 16: launch_apply_nv<16>(s, pl, table, state, stride, src, opt); break;
+    default: return fail(NUPS_ERR_UNIMPLEMENTED, "row_stride must be 64, 128, 192, 256, 320, 384, 512 or 1024 floats");
+    }
+    NUPS_HIP(hipGetLastError());
+    return NUPS_OK;
+}
+
+}  // namespace nups

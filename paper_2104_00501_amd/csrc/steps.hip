@@ -1,0 +1,455 @@
+// Direct access (pull / push) and the per-task gradient kernels of the minibatch step:
+// skip-gram with negative sampling, matrix factorisation, ComplEx (Section 5.1).  Every
+// kernel reads the tables as they are at the start of the step and writes only coefficients
+// and staged gradient rows; the tables are updated afterwards, once per distinct key
+// (segment_apply.h).
+#include "segment_apply.h"
+
+namespace nups {
+
+// ------------------------------------------------------------------------------------------------
+// pull: values[i, :] = table[keys[i], :]; one thread per float4, zero rows for keys out of range.
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock) k_pull(const float *table, uint32_t num_keys, int stride4,
+                                                 const uint32_t *keys, uint64_t total4, float *values,
+                                                 uint32_t *error_flag)
+{
+    const uint64_t idx = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (idx >= total4) return;
+    const uint64_t i = idx / stride4;
+    const uint32_t q = (uint32_t)(idx % stride4);
+    const uint32_t key = keys[i];
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (key < num_keys) v = reinterpret_cast<const float4 *>(table)[(size_t)key * stride4 + q];
+    else if (q == 0) atomicOr(error_flag, 1u);
+    reinterpret_cast<float4 *>(values)[idx] = v;
+}
+
+nups_status launch_pull(nups_ctx *ctx, const Table &t, const uint32_t *keys, int64_t n, float *values)
+{
+    if (n == 0) return NUPS_OK;
+    PhaseScope scope(ctx, NUPS_PHASE_PULL);
+    const int stride4 = t.stride / 4;
+    const uint64_t total4 = (uint64_t)n * stride4;
+    const uint64_t blocks = (total4 + kBlock - 1) / kBlock;
+    if (blocks > 0x7FFFFFFFull) return fail(NUPS_ERR_ARG, "nups_pull: too many rows for one call");
+    hipLaunchKernelGGL(k_pull, dim3((uint32_t)blocks), dim3(kBlock), 0, ctx->stream, (const float *)t.data,
+                       (uint32_t)t.num_keys, stride4, keys, total4, values, ctx->error_flag);
+    NUPS_HIP(hipGetLastError());
+    return NUPS_OK;
+}
+
+// push: table[k] += sum of the update rows sent for k (plan already built over the keys).
+nups_status launch_push_apply(nups_ctx *ctx, Table &t, const float *updates)
+{
+    PhaseScope scope(ctx, NUPS_PHASE_PUSH);
+    return launch_apply(ctx->stream, t.plan, t.data, nullptr, t.stride, SrcStaged{updates}, OptAdd{});
+}
+
+// ------------------------------------------------------------------------------------------------
+// Skip-gram with negative sampling.  One 16-lane group per (center, context) pair:
+//   z_j = <v, u_j>, g_j = sigma(z_j) - label_j, staged input-side gradient = sum_j g_j u_j.
+// ------------------------------------------------------------------------------------------------
+template <int NV4>
+__global__ void __launch_bounds__(kBlock) k_sgns_grad(const float *in_table, const float *out_table,
+                                                      uint32_t num_in, uint32_t num_out, int stride,
+                                                      const uint32_t *center, const uint32_t *context,
+                                                      const uint32_t *negs, uint32_t B, int K, float *coefs,
+                                                      float *stage, double *loss)
+{
+    __shared__ float lds[kBlock / 64];
+    const int lane = threadIdx.x & (kGroup - 1);
+    const uint32_t e_raw = (blockIdx.x * kBlock + threadIdx.x) / kGroup;
+    const bool active = e_raw < B;
+    const uint32_t e = active ? e_raw : B - 1;
+    Row<NV4> v, acc;
+    load_row(v, in_table + (size_t)min(center[e], num_in - 1) * stride, lane);
+    zero_row(acc);
+    float loss_acc = 0.f;
+    constexpr int JU = 4;
+    for (int j0 = 0; j0 <= K; j0 += JU) {
+        Row<NV4> u[JU];
+#pragma unroll
+        for (int jj = 0; jj < JU; ++jj) {
+            const int j = min(j0 + jj, K);
+            const uint32_t key = (j == 0) ? context[e] : negs[(size_t)e * K + (j - 1)];
+            load_row(u[jj], out_table + (size_t)min(key, num_out - 1) * stride, lane);
+        }
+#pragma unroll
+        for (int jj = 0; jj < JU; ++jj) {
+            const int j = j0 + jj;
+            if (j <= K) {
+                const float z = group_sum(partial_dot(v, u[jj]));
+                const float g = sigmoidf(z) - (j == 0 ? 1.0f : 0.0f);
+                loss_acc += softplusf(j == 0 ? -z : z);
+                if (active && lane == 0) coefs[(size_t)e * (K + 1) + j] = g;
+                axpy_row(acc, g, u[jj]);
+            }
+        }
+    }
+    if (active) store_row(stage + (size_t)e * stride, acc, lane);
+    block_add_loss((active && lane == 0) ? loss_acc : 0.f, loss, lds);
+}
+
+template <int NV4>
+static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b)
+{
+    const Table &tin = ctx->tab[0], &tout = ctx->tab[1];
+    const uint32_t blocks = (uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock);
+    hipLaunchKernelGGL(k_sgns_grad<NV4>, dim3(blocks), dim3(kBlock), 0, ctx->stream, (const float *)tin.data,
+                       (const float *)tout.data, (uint32_t)tin.num_keys, (uint32_t)tout.num_keys, tin.stride, b.k0,
+                       b.k1, b.negs, (uint32_t)b.B, (int)b.n_neg, ctx->coef, ctx->stage, ctx->loss_dev);
+}
+
+#define NUPS_DISPATCH_STRIDE(stride, CALL)                                                        \
+    switch ((stride) / 64) {                                                                      \
+    case 1: CALL(1); break;                                                                       \
+    case 2: CALL(2); break;                                                                       \
+    case 3: CALL(3); break;                                                                       \
+    case 4: CALL(4); break;                                                                       \
+    case 5: CALL(5); break;                                                                       \
+    case 6: CALL(6); break;                                                                       \
+    case 8: CALL(8); break;                                                                       \
+    case 16: CALL(16); break;                                                                     \
+    default:                                                                                      \
+        return fail(NUPS_ERR_UNIMPLEMENTED,                                                       \
+                    "row_stride must be 64, 128, 192, 256, 320, 384, 512 or 1024 floats");        \
+    }
+
+static nups_status zero_loss(nups_ctx *ctx)
+{
+    NUPS_HIP(hipMemsetAsync(ctx->loss_dev, 0, sizeof(double), ctx->stream));
+    return NUPS_OK;
+}
+
+nups_status launch_step_sgns(nups_ctx *ctx, const nups_batch &b)
+{
+    Table &tin = ctx->tab[0], &tout = ctx->tab[1];
+    const uint32_t B = (uint32_t)b.B, K = (uint32_t)b.n_neg;
+    nups_status st;
+    if ((st = ensure_f32(&ctx->coef, &ctx->coef_cap, (size_t)B * (K + 1), ctx->stream)) != NUPS_OK) return st;
+    if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)B * tin.stride, ctx->stream)) != NUPS_OK) return st;
+    if ((st = ensure_plan_capacity(ctx, tin, B)) != NUPS_OK) return st;
+    if ((st = ensure_plan_capacity(ctx, tout, (size_t)B * (K + 1))) != NUPS_OK) return st;
+    if ((st = zero_loss(ctx)) != NUPS_OK) return st;
+    tin.plan.a.src = KeySource{{b.k0, nullptr, nullptr}, {B, 0, 0}};
+    tin.plan.a.n = B;
+    tout.plan.a.src = KeySource{{b.k1, b.negs, nullptr}, {B, B * K, 0}};
+    tout.plan.a.n = B * (K + 1);
+    Plan *plans[2] = {&tin.plan, &tout.plan};
+    if ((st = build_plans(ctx, plans, 2)) != NUPS_OK) return st;
+    if (B == 0) return NUPS_OK;
+    {
+        PhaseScope scope(ctx, NUPS_PHASE_GRAD);
+#define CALL(N) launch_sgns_grad<N>(ctx, b)
+        NUPS_DISPATCH_STRIDE(tin.stride, CALL)
+#undef CALL
+        NUPS_HIP(hipGetLastError());
+    }
+    {   // output side first: it reads the input vectors, which must still be the step's snapshot
+        PhaseScope scope(ctx, NUPS_PHASE_APPLY1);
+        SrcSgnsOut src{tin.data, b.k0, ctx->coef, B, K, (uint32_t)tin.num_keys};
+        if ((st = launch_apply(ctx->stream, tout.plan, tout.data, nullptr, tout.stride, src, OptSgd{b.lr})) != NUPS_OK)
+            return st;
+    }
+    {
+        PhaseScope scope(ctx, NUPS_PHASE_APPLY0);
+        if ((st = launch_apply(ctx->stream, tin.plan, tin.data, nullptr, tin.stride, SrcStaged{ctx->stage},
+                               OptSgd{b.lr})) != NUPS_OK)
+            return st;
+    }
+    return NUPS_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Matrix factorisation.  One group per cell: err = x - <w, h>; staged rows
+//   dW = -2 err h + 2 l2 w   (rows [0, B))      dH = -2 err w + 2 l2 h   (rows [B, 2B)).
+// ------------------------------------------------------------------------------------------------
+template <int NV4>
+__global__ void __launch_bounds__(kBlock) k_mf_grad(const float *W, const float *H, uint32_t n_rows, uint32_t n_cols,
+                                                    int stride, const uint32_t *row, const uint32_t *col,
+                                                    const float *val, uint32_t B, float l2, float *stage,
+                                                    double *loss)
+{
+    __shared__ float lds[kBlock / 64];
+    const int lane = threadIdx.x & (kGroup - 1);
+    const uint32_t c_raw = (blockIdx.x * kBlock + threadIdx.x) / kGroup;
+    const bool active = c_raw < B;
+    const uint32_t c = active ? c_raw : B - 1;
+    Row<NV4> w, h;
+    load_row(w, W + (size_t)min(row[c], n_rows - 1) * stride, lane);
+    load_row(h, H + (size_t)min(col[c], n_cols - 1) * stride, lane);
+    const float dot = group_sum(partial_dot(w, h));
+    const float nw = group_sum(partial_dot(w, w));
+    const float nh = group_sum(partial_dot(h, h));
+    const float err = val[c] - dot;
+    Row<NV4> dw, dh;
+#pragma unroll
+    for (int q = 0; q < NV4; ++q) {
+        dw.v[q] = make_float4(-2.f * err * h.v[q].x + 2.f * l2 * w.v[q].x, -2.f * err * h.v[q].y + 2.f * l2 * w.v[q].y,
+                              -2.f * err * h.v[q].z + 2.f * l2 * w.v[q].z, -2.f * err * h.v[q].w + 2.f * l2 * w.v[q].w);
+        dh.v[q] = make_float4(-2.f * err * w.v[q].x + 2.f * l2 * h.v[q].x, -2.f * err * w.v[q].y + 2.f * l2 * h.v[q].y,
+                              -2.f * err * w.v[q].z + 2.f * l2 * h.v[q].z, -2.f * err * w.v[q].w + 2.f * l2 * h.v[q].w);
+    }
+    if (active) {
+        store_row(stage + (size_t)c * stride, dw, lane);
+        store_row(stage + ((size_t)B + c) * stride, dh, lane);
+    }
+    block_add_loss((active && lane == 0) ? err * err + l2 * (nw + nh) : 0.f, loss, lds);
+}
+
+template <int NV4>
+static void launch_mf_grad(nups_ctx *ctx, const nups_batch &b)
+{
+    const Table &tw = ctx->tab[0], &th = ctx->tab[1];
+    const uint32_t blocks = (uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock);
+    hipLaunchKernelGGL(k_mf_grad<NV4>, dim3(blocks), dim3(kBlock), 0, ctx->stream, (const float *)tw.data,
+                       (const float *)th.data, (uint32_t)tw.num_keys, (uint32_t)th.num_keys, tw.stride, b.k0, b.k1,
+                       b.val, (uint32_t)b.B, b.l2, ctx->stage, ctx->loss_dev);
+}
+
+nups_status launch_step_mf(nups_ctx *ctx, const nups_batch &b)
+{
+    Table &tw = ctx->tab[0], &th = ctx->tab[1];
+    const uint32_t B = (uint32_t)b.B;
+    nups_status st;
+    if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)2 * B * tw.stride, ctx->stream)) != NUPS_OK) return st;
+    if ((st = ensure_plan_capacity(ctx, tw, B)) != NUPS_OK) return st;
+    if ((st = ensure_plan_capacity(ctx, th, B)) != NUPS_OK) return st;
+    if ((st = zero_loss(ctx)) != NUPS_OK) return st;
+    tw.plan.a.src = KeySource{{b.k0, nullptr, nullptr}, {B, 0, 0}};
+    tw.plan.a.n = B;
+    th.plan.a.src = KeySource{{b.k1, nullptr, nullptr}, {B, 0, 0}};
+    th.plan.a.n = B;
+    Plan *plans[2] = {&tw.plan, &th.plan};
+    if ((st = build_plans(ctx, plans, 2)) != NUPS_OK) return st;
+    if (B == 0) return NUPS_OK;
+    {
+        PhaseScope scope(ctx, NUPS_PHASE_GRAD);
+#define CALL(N) launch_mf_grad<N>(ctx, b)
+        NUPS_DISPATCH_STRIDE(tw.stride, CALL)
+#undef CALL
+        NUPS_HIP(hipGetLastError());
+    }
+    {
+        PhaseScope scope(ctx, NUPS_PHASE_APPLY0);
+        if ((st = launch_apply(ctx->stream, tw.plan, tw.data, nullptr, tw.stride, SrcStaged{ctx->stage},
+                               OptSgd{b.lr})) != NUPS_OK)
+            return st;
+    }
+    {
+        PhaseScope scope(ctx, NUPS_PHASE_APPLY1);
+        if ((st = launch_apply(ctx->stream, th.plan, th.data, nullptr, th.stride,
+                               SrcStaged{ctx->stage + (size_t)B * tw.stride}, OptSgd{b.lr})) != NUPS_OK)
+            return st;
+    }
+    return NUPS_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// ComplEx with logistic loss.  A stored row is two halves: real parts from float 0, imaginary parts
+// from float stride / 2; with stride a multiple of 128 a lane owns float4 q of the real half and
+// float4 q + NV4/2 of the imaginary half, i.e. both parts of the same four components.
+//
+// score(s, r, o) = Re(sum s r conj(o)) is linear in each argument:
+//   score = <s, A> with A = d score / d s  (a function of r and o),
+//   score = <o, C> with C = d score / d o  (a function of s and r).
+// One workgroup per triple: every negative is one dot product with A (replaced subject) or C
+// (replaced object); its own gradient is coef * A or coef * C; the triple's subject, object and
+// relation gradients follow from the coefficient-weighted sums of the negatives' rows.
+// Staged rows: [0,B) subject gradient, [B,2B) object gradient, [2B,3B) A, [3B,4B) C, [4B,5B) relation gradient.
+// ------------------------------------------------------------------------------------------------
+// out = d score / d s  given r (conjugate-linear pairing with o):  re = r_re o_re + r_im o_im ; im = r_re o_im - r_im o_re
+template <int NV4>
+__device__ __forceinline__ void grad_subject(Row<NV4> &out, const Row<NV4> &r, const Row<NV4> &o)
+{
+    constexpr int H = NV4 / 2;
+#pragma unroll
+    for (int q = 0; q < H; ++q) {
+        const float4 rr = r.v[q], ri = r.v[q + H], orr = o.v[q], oi = o.v[q + H];
+        out.v[q] = make_float4(rr.x * orr.x + ri.x * oi.x, rr.y * orr.y + ri.y * oi.y, rr.z * orr.z + ri.z * oi.z,
+                               rr.w * orr.w + ri.w * oi.w);
+        out.v[q + H] = make_float4(rr.x * oi.x - ri.x * orr.x, rr.y * oi.y - ri.y * orr.y, rr.z * oi.z - ri.z * orr.z,
+                                   rr.w * oi.w - ri.w * orr.w);
+    }
+}
+
+// out = d score / d o  given s, r:  re = s_re r_re - s_im r_im ; im = s_im r_re + s_re r_im
+template <int NV4>
+__device__ __forceinline__ void grad_object(Row<NV4> &out, const Row<NV4> &s, const Row<NV4> &r)
+{
+    constexpr int H = NV4 / 2;
+#pragma unroll
+    for (int q = 0; q < H; ++q) {
+        const float4 sr = s.v[q], si = s.v[q + H], rr = r.v[q], ri = r.v[q + H];
+        out.v[q] = make_float4(sr.x * rr.x - si.x * ri.x, sr.y * rr.y - si.y * ri.y, sr.z * rr.z - si.z * ri.z,
+                               sr.w * rr.w - si.w * ri.w);
+        out.v[q + H] = make_float4(si.x * rr.x + sr.x * ri.x, si.y * rr.y + sr.y * ri.y, si.z * rr.z + sr.z * ri.z,
+                                   si.w * rr.w + sr.w * ri.w);
+    }
+}
+
+// out += d score / d r  given s, o:  re = s_re o_re + s_im o_im ; im = s_re o_im - s_im o_re
+template <int NV4>
+__device__ __forceinline__ void add_grad_relation(Row<NV4> &out, const Row<NV4> &s, const Row<NV4> &o)
+{
+    constexpr int H = NV4 / 2;
+#pragma unroll
+    for (int q = 0; q < H; ++q) {
+        const float4 sr = s.v[q], si = s.v[q + H], orr = o.v[q], oi = o.v[q + H];
+        out.v[q].x += sr.x * orr.x + si.x * oi.x; out.v[q].y += sr.y * orr.y + si.y * oi.y;
+        out.v[q].z += sr.z * orr.z + si.z * oi.z; out.v[q].w += sr.w * orr.w + si.w * oi.w;
+        out.v[q + H].x += sr.x * oi.x - si.x * orr.x; out.v[q + H].y += sr.y * oi.y - si.y * orr.y;
+        out.v[q + H].z += sr.z * oi.z - si.z * orr.z; out.v[q + H].w += sr.w * oi.w - si.w * orr.w;
+    }
+}
+
+template <int NV4>
+__global__ void __launch_bounds__(kBlock) k_kge_grad(const float *E, const float *R, uint32_t n_ent, uint32_t n_rel,
+                                                     int stride, const uint32_t *subj, const uint32_t *rel,
+                                                     const uint32_t *obj, const uint32_t *negs, uint32_t B, int nh,
+                                                     int nt, float *coefs, float *stage, double *loss)
+{
+    extern __shared__ float part[];   // [kGroupsPerBlock][stride]: per-group weighted row sums
+    __shared__ float lds[kBlock / 64];
+    const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
+    const uint32_t e = blockIdx.x;
+    const int nn = nh + nt;
+    const float *s_ptr = E + (size_t)min(subj[e], n_ent - 1) * stride;
+    const float *o_ptr = E + (size_t)min(obj[e], n_ent - 1) * stride;
+    const float *r_ptr = R + (size_t)min(rel[e], n_rel - 1) * stride;
+    Row<NV4> A, C;
+    {
+        Row<NV4> s, r, o;
+        load_row(s, s_ptr, lane);
+        load_row(r, r_ptr, lane);
+        load_row(o, o_ptr, lane);
+        grad_subject<NV4>(A, r, o);
+        grad_object<NV4>(C, s, r);
+    }
+    Row<NV4> sum_s, sum_o;   // sum of coef * replaced-subject rows / replaced-object rows handled by this group
+    zero_row(sum_s);
+    zero_row(sum_o);
+    float loss_acc = 0.f;
+    for (int i = group; i < nn; i += kGroupsPerBlock) {
+        Row<NV4> x;
+        load_row(x, E + (size_t)min(negs[(size_t)e * nn + i], n_ent - 1) * stride, lane);
+        const bool head = i < nh;
+        const float phi = group_sum(head ? partial_dot(x, A) : partial_dot(x, C));
+        const float g = sigmoidf(phi);               // label -1: d softplus(phi) / d phi
+        loss_acc += softplusf(phi);
+        if (lane == 0) coefs[(size_t)e * nn + i] = g;
+        if (head) axpy_row(sum_s, g, x); else axpy_row(sum_o, g, x);
+    }
+    // weighted row sums over all groups, in a fixed order; the LDS buffer is used twice
+    Row<NV4> ws, wo;                                 // sums of coef * replaced-subject / replaced-object rows
+    zero_row(ws);
+    zero_row(wo);
+    store_row(part + (size_t)group * stride, sum_s, lane);
+    __syncthreads();
+    if (group == 1 || group == 4) {
+        for (int g2 = 0; g2 < kGroupsPerBlock; ++g2) {
+            Row<NV4> t;
+            load_row(t, part + (size_t)g2 * stride, lane);
+            axpy_row(ws, 1.0f, t);
+        }
+    }
+    __syncthreads();
+    store_row(part + (size_t)group * stride, sum_o, lane);
+    __syncthreads();
+    if (group == 0 || group == 4) {
+        for (int g2 = 0; g2 < kGroupsPerBlock; ++g2) {
+            Row<NV4> t;
+            load_row(t, part + (size_t)g2 * stride, lane);
+            axpy_row(wo, 1.0f, t);
+        }
+    }
+    if (group < 5) {
+        Row<NV4> s, r, o;
+        load_row(s, s_ptr, lane);
+        load_row(r, r_ptr, lane);
+        load_row(o, o_ptr, lane);
+        const float phi = group_sum(partial_dot(s, A));
+        const float gp = -sigmoidf(-phi);            // label +1: d softplus(-phi) / d phi
+        if (group == 0) loss_acc += softplusf(-phi);
+        Row<NV4> out;
+        if (group == 0) {            // subject gradient: d score/d s is linear in o
+            axpy_row(wo, gp, o);
+            grad_subject<NV4>(out, r, wo);
+            store_row(stage + (size_t)e * stride, out, lane);
+        } else if (group == 1) {     // object gradient: linear in s
+            axpy_row(ws, gp, s);
+            grad_object<NV4>(out, ws, r);
+            store_row(stage + ((size_t)B + e) * stride, out, lane);
+        } else if (group == 2) {
+            store_row(stage + ((size_t)2 * B + e) * stride, A, lane);
+        } else if (group == 3) {
+            store_row(stage + ((size_t)3 * B + e) * stride, C, lane);
+        } else {                     // relation gradient: bilinear in (s, o)
+            zero_row(out);
+            axpy_row(wo, gp, o);
+            add_grad_relation<NV4>(out, s, wo);      // positive + replaced objects (subject fixed)
+            add_grad_relation<NV4>(out, ws, o);      // replaced subjects (object fixed)
+            store_row(stage + ((size_t)4 * B + e) * stride, out, lane);
+        }
+    }
+    block_add_loss(lane == 0 ? loss_acc : 0.f, loss, lds);
+}
+
+template <int NV4>
+static void launch_kge_grad(nups_ctx *ctx, const nups_batch &b)
+{
+    const Table &te = ctx->tab[0], &tr = ctx->tab[1];
+    const size_t lds = sizeof(float) * kGroupsPerBlock * (size_t)te.stride;
+    hipLaunchKernelGGL(k_kge_grad<NV4>, dim3((uint32_t)b.B), dim3(kBlock), lds, ctx->stream, (const float *)te.data,
+                       (const float *)tr.data, (uint32_t)te.num_keys, (uint32_t)tr.num_keys, te.stride, b.k0, b.k1,
+                       b.k2, b.negs, (uint32_t)b.B, (int)b.n_neg, (int)b.n_neg2, ctx->coef, ctx->stage, ctx->loss_dev);
+}
+
+nups_status launch_step_kge(nups_ctx *ctx, const nups_batch &b)
+{
+    Table &te = ctx->tab[0], &tr = ctx->tab[1];
+    const uint32_t B = (uint32_t)b.B, nh = (uint32_t)b.n_neg, nn = (uint32_t)(b.n_neg + b.n_neg2);
+    if (te.stride % 128 != 0 || te.stride > 512)
+        return fail(NUPS_ERR_UNIMPLEMENTED, "KGE tables need a row_stride of 128, 256, 384 or 512 floats");
+    nups_status st;
+    if ((st = ensure_f32(&ctx->coef, &ctx->coef_cap, (size_t)B * nn + 1, ctx->stream)) != NUPS_OK) return st;
+    if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)5 * B * te.stride, ctx->stream)) != NUPS_OK) return st;
+    if ((st = ensure_plan_capacity(ctx, te, (size_t)B * (2 + nn))) != NUPS_OK) return st;
+    if ((st = ensure_plan_capacity(ctx, tr, B)) != NUPS_OK) return st;
+    if ((st = zero_loss(ctx)) != NUPS_OK) return st;
+    te.plan.a.src = KeySource{{b.k0, b.k2, b.negs}, {B, B, B * nn}};
+    te.plan.a.n = B * (2 + nn);
+    tr.plan.a.src = KeySource{{b.k1, nullptr, nullptr}, {B, 0, 0}};
+    tr.plan.a.n = B;
+    Plan *plans[2] = {&te.plan, &tr.plan};
+    if ((st = build_plans(ctx, plans, 2)) != NUPS_OK) return st;
+    if (B == 0) return NUPS_OK;
+    {
+        PhaseScope scope(ctx, NUPS_PHASE_GRAD);
+        switch (te.stride / 64) {
+        case 2: launch_kge_grad<2>(ctx, b); break;
+        case 4: launch_kge_grad<4>(ctx, b); break;
+        case 6: launch_kge_grad<6>(ctx, b); break;
+        case 8: launch_kge_grad<8>(ctx, b); break;
+        default: return fail(NUPS_ERR_UNIMPLEMENTED, "KGE row_stride");
+        }
+        NUPS_HIP(hipGetLastError());
+    }
+    {
+        PhaseScope scope(ctx, NUPS_PHASE_APPLY0);
+        SrcKgeEntity src{ctx->stage, ctx->coef, B, nn, nh};
+        if ((st = launch_apply(ctx->stream, te.plan, te.data, te.state, te.stride, src,
+                               OptAdagrad{b.lr, b.eps})) != NUPS_OK)
+            return st;
+    }
+    {
+        PhaseScope scope(ctx, NUPS_PHASE_APPLY1);
+        if ((st = launch_apply(ctx->stream, tr.plan, tr.data, tr.state, tr.stride,
+                               SrcStaged{ctx->stage + (size_t)4 * B * te.stride}, OptAdagrad{b.lr, b.eps})) != NUPS_OK)
+            return st;
+    }
+    return NUPS_OK;
+}
+
+}  // namespace nups

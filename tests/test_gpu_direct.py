@@ -1,0 +1,71 @@
+"""GPU parity of direct access: pull (row gather) is a bit-exact copy, push sums duplicates."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2104_00501_amd import binding as nb
+from paper_2104_00501_amd import workloads as wl
+from tests.parity import dev, dev_u32, host_u32, max_rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("V,d,n", [(10_000, 100, 4096), (100_000, 300, 16_389), (3000, 500, 1), (50, 64, 777)])
+def test_pull_is_a_bit_exact_gather(V, d, n):
+    import torch
+    T = wl.uniform_table(V, d, -1, 1, 1)
+    keys = wl.zipf_stream(V, 1.0, n, 2)
+    table = dev(T)
+    ctx = nb.nups_init([table], [d])
+    out = torch.full((n, T.shape[1]), 7.0, dtype=torch.float32, device="cuda")
+    nb.nups_pull(ctx, 0, dev_u32(keys), n, out)
+    nb.nups_pull(ctx, 0, None, 0, None)
+    nb.nups_check(ctx)
+    assert np.array_equal(out.cpu().numpy(), orc.pull(T, keys))
+    nb.nups_destroy(ctx)
+
+
+def test_pull_flags_keys_out_of_range_without_touching_memory():
+    import torch
+    T = wl.uniform_table(100, 64, -1, 1, 1)
+    table = dev(T)
+    ctx = nb.nups_init([table], [64])
+    out = torch.full((3, 64), 7.0, dtype=torch.float32, device="cuda")
+    nb.nups_pull(ctx, 0, dev_u32([5, 100, 0xFFFFFFFF]), 3, out)
+    with pytest.raises(nb.NupsError) as e:
+        nb.nups_check(ctx)
+    assert e.value.status == nb.NUPS_ERR_KEY_RANGE
+    got = out.cpu().numpy()
+    assert np.array_equal(got[0], T[5]) and np.all(got[1:] == 0)
+    nb.nups_check(ctx)          # the flag was consumed
+    nb.nups_destroy(ctx)
+
+
+@pytest.mark.parametrize("V,d,n,s", [(10_000, 100, 20_000, 1.0), (100_000, 300, 30_001, 1.4), (500, 500, 4096, 0.6),
+                                      (1000, 200, 1, 1.0)])
+def test_push_sums_duplicates_and_reports_the_structure(V, d, n, s):
+    import torch
+    T = wl.uniform_table(V, d, -1, 1, 3)
+    keys = wl.zipf_stream(V, s, n, 4)
+    upd = wl.uniform_table(n, d, -1e-2, 1e-2, 5)
+    table = dev(T)
+    ctx = nb.nups_init([table], [d])
+    nb.nups_push(ctx, 0, dev_u32(keys), n, dev(upd))
+    uk = torch.zeros(n, dtype=torch.int32, device="cuda")
+    uc = torch.zeros(n, dtype=torch.int32, device="cuda")
+    nu = nb.nups_debug_structure(ctx, 0, uk, uc)
+    ref = T.copy()
+    orc.push(ref, d, keys, upd)
+    rk, rc = orc.distinct_keys(keys)
+    assert nu == len(rk)
+    assert np.array_equal(host_u32(uk)[:nu], rk) and np.array_equal(host_u32(uc)[:nu], rc)
+    got = table.cpu().numpy()
+    rel, ab = max_rel_err(got, ref, list(range(d)))
+    assert rel < 1e-5, (rel, ab)
+    assert np.all(got[:, d:] == 0)
+    untouched = np.setdiff1d(np.arange(V), rk)
+    assert np.array_equal(got[untouched], T[untouched])
+    nb.nups_push(ctx, 0, None, 0, None)         # empty push is a no-op
+    nb.nups_check(ctx)
+    assert np.array_equal(table.cpu().numpy(), got)
+    nb.nups_destroy(ctx)

@@ -1,0 +1,138 @@
+"""GPU parity of the sampling primitive (PrepareSample / PullSample, Sections 4.3-4.4):
+sampled keys must equal the oracle's bit for bit under every scheme."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2104_00501_amd import binding as nb
+from paper_2104_00501_amd import workloads as wl
+from tests.parity import dev, dev_u32, host_u32
+
+pytestmark = pytest.mark.gpu
+
+
+def _ctx(V, d=100, seed=0):
+    import torch
+    table = dev(wl.uniform_table(V, d, -1, 1, seed))
+    return nb.nups_init([table], [d]), table
+
+
+def _keys_of(handle, n):
+    import torch
+    out = torch.zeros(max(n, 1), dtype=torch.int32, device="cuda")
+    nb.nups_pull_sample(handle, n, out, None)
+    torch.cuda.synchronize()
+    return host_u32(out)[:n]
+
+
+@pytest.mark.parametrize("V,n,step", [(10_000, 20_480, 0), (1_000_000, 49_152, 123), (37, 1000, 2 ** 33 + 5), (5, 1, 1)])
+def test_conform_keys_are_bit_exact(V, n, step):
+    ctx, _ = _ctx(V)
+    w = wl.expected_unigram_weights(V, 1.0, 1e6)
+    w[V // 2] = 0.0
+    dist = nb.nups_register_distribution(ctx, 0, w, nb.NUPS_CONFORM, seed=1234)
+    h = nb.nups_prepare_sample(dist, n, step)
+    got = _keys_of(h, n)
+    ref = orc.sample_conform(orc.alias_build(w), V, 1234, 0, step, n)
+    assert np.array_equal(got, ref)
+    nb.nups_release_sample(h)
+    nb.nups_destroy(ctx)
+
+
+def test_uniform_keys_are_bit_exact_and_dist_id_enters():
+    V, n = 4_600_000, 102_400
+    import torch
+    table = torch.zeros((V, 64), dtype=torch.float32, device="cuda")
+    ctx = nb.nups_init([table], [50])
+    d0 = nb.nups_register_distribution(ctx, 0, None, nb.NUPS_CONFORM, seed=7)
+    d1 = nb.nups_register_distribution(ctx, 0, None, nb.NUPS_CONFORM, seed=7)
+    h0, h1 = nb.nups_prepare_sample(d0, n, 9), nb.nups_prepare_sample(d1, n, 9)
+    k0, k1 = _keys_of(h0, n), _keys_of(h1, n)
+    assert np.array_equal(k0, orc.sample_conform(None, V, 7, 0, 9, n))
+    assert np.array_equal(k1, orc.sample_conform(None, V, 7, 1, 9, n))
+    assert not np.array_equal(k0, k1)
+    nb.nups_destroy(ctx)
+
+
+@pytest.mark.parametrize("V,n,U,G", [(1_000_000, 49_152, 4, 250), (500_000, 40_960, 16, 250), (1000, 999, 4, 7),
+                                      (1000, 50, 8, 250), (1000, 7, 3, 2), (1000, 5, 1, 3), (1000, 5000, 2, 1024)])
+def test_bounded_keys_are_bit_exact(V, n, U, G):
+    ctx, _ = _ctx(V, d=20)
+    w = wl.expected_unigram_weights(V, 1.0, 1e9)
+    dist = nb.nups_register_distribution(ctx, 0, w, nb.NUPS_BOUNDED, U=U, G=G, seed=99)
+    table = orc.alias_build(w)
+    for step in (0, 17):
+        h = nb.nups_prepare_sample(dist, n, step)
+        got = _keys_of(h, n)
+        nb.nups_release_sample(h)
+        assert np.array_equal(got, orc.sample_bounded(table, V, 99, 0, step, n, U, G))
+    nb.nups_destroy(ctx)
+
+
+@pytest.mark.parametrize("P,R", [(1_000_000, 16), (1000, 2), (77, 3), (1, 1)])
+def test_longterm_keys_are_bit_exact_and_the_cursor_advances(P, R):
+    V = 500_000
+    ctx, _ = _ctx(V, d=20)
+    w = wl.expected_unigram_weights(V, 1.0, 2e8)
+    dist = nb.nups_register_distribution(ctx, 0, w, nb.NUPS_LONGTERM, P=P, R=R, seed=5)
+    table = orc.alias_build(w)
+    cursor = 0
+    for n in (40_960, 1, 40_960, 12_345):
+        h = nb.nups_prepare_sample(dist, n, 0)
+        got = _keys_of(h, n)
+        nb.nups_release_sample(h)
+        assert np.array_equal(got, orc.sample_longterm(table, V, 5, 0, P, R, cursor, n))
+        cursor += n
+    nb.nups_destroy(ctx)
+
+
+def test_nonconform_keys_are_bit_exact():
+    V, B, K = 500_000, 8192, 5
+    ctx, _ = _ctx(V, d=20)
+    toks = wl.zipf_stream(V, 1.0, B + 20, 3)
+    _, ctxs = wl.window_pairs(toks, 5, 0, B)
+    other = wl.zipf_stream(V, 1.1, B, 4)
+    ka, kb = dev_u32(ctxs), dev_u32(other)
+    dist = nb.nups_register_distribution(ctx, 0, None, nb.NUPS_NONCONFORM, seed=11)
+    for per_example, split, tile in ((K, K, B), (K, 2, 1000), (100, 50, 256)):
+        n = min(B * per_example, 200_000) // per_example * per_example
+        nb.nups_set_local_keys(dist, ka, kb, B, per_example, split, tile)
+        h = nb.nups_prepare_sample(dist, n, 3)
+        got = _keys_of(h, n)
+        nb.nups_release_sample(h)
+        assert np.array_equal(got, orc.sample_nonconform(ctxs, other, per_example, split, tile, 11, 0, 3, n))
+    nb.nups_destroy(ctx)
+
+
+def test_pull_sample_partial_pulls_values_and_errors():
+    import torch
+    V, d, n = 5000, 100, 1000
+    ctx, table = _ctx(V, d)
+    dist = nb.nups_register_distribution(ctx, 0, np.ones(V), nb.NUPS_CONFORM, seed=3)
+    h = nb.nups_prepare_sample(dist, n, 1)
+    ref = orc.sample_conform(orc.alias_build(np.ones(V)), V, 3, 0, 1, n)
+    keys = torch.zeros(n, dtype=torch.int32, device="cuda")
+    vals = torch.zeros((n, table.shape[1]), dtype=torch.float32, device="cuda")
+    nb.nups_pull_sample(h, 300, keys[:300], vals[:300])
+    nb.nups_pull_sample(h, 0, None, None)
+    nb.nups_pull_sample(h, 699, keys[300:999], vals[300:999])
+    with pytest.raises(nb.NupsError) as e:
+        nb.nups_pull_sample(h, 2, keys[999:], vals[999:])
+    assert e.value.status == nb.NUPS_ERR_OVERPULL
+    nb.nups_pull_sample(h, 1, keys[999:], vals[999:])
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u32(keys), ref)
+    assert np.array_equal(vals.cpu().numpy(), orc.pull(table.cpu().numpy(), ref))
+    addr, total = nb.nups_sample_keys(h)
+    assert total == n and addr != 0
+    nb.nups_release_sample(h)
+    with pytest.raises(nb.NupsError) as e:
+        nb.nups_release_sample(h)
+    assert e.value.status == nb.NUPS_ERR_STATE
+    with pytest.raises(nb.NupsError):
+        nb.nups_register_distribution(ctx, 0, None, nb.NUPS_BOUNDED, U=0, G=4)
+    with pytest.raises(nb.NupsError):
+        nb.nups_register_distribution(ctx, 0, None, nb.NUPS_BOUNDED, U=1, G=0)
+    with pytest.raises(nb.NupsError):
+        nb.nups_register_distribution(ctx, 0, np.zeros(V), nb.NUPS_CONFORM)
+    nb.nups_destroy(ctx)

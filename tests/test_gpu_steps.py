@@ -1,0 +1,209 @@
+"""GPU parity of the minibatch step (sample -> pull -> gradient -> aggregate -> push) against the
+CPU oracle: aggregation structure bit-exact, fp32 parameters within 1e-5 (max relative error,
+denominator floored at 1e-3 * RMS of the table) after one step and 1e-3 after 100 steps."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2104_00501_amd import binding as nb
+from paper_2104_00501_amd import workloads as wl
+from tests.parity import dev, dev_u32, host_u32, max_rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL_ONE_STEP = 1e-5
+TOL_100_STEPS = 1e-3
+
+
+def _structure(ctx, table, n):
+    import torch
+    uk = torch.zeros(max(n, 1), dtype=torch.int32, device="cuda")
+    uc = torch.zeros(max(n, 1), dtype=torch.int32, device="cuda")
+    nu = nb.nups_debug_structure(ctx, table, uk, uc)
+    return host_u32(uk)[:nu], host_u32(uc)[:nu]
+
+
+def _assert_structure(ctx, table, n, ref):
+    k, c = _structure(ctx, table, n)
+    assert np.array_equal(k, ref.keys) and np.array_equal(c, ref.counts)
+
+
+def _assert_close(got, ref, cols, tol, what):
+    rel, ab = max_rel_err(got, ref, cols)
+    assert rel <= tol, "%s: max rel err %.3g (abs %.3g) > %.1g" % (what, rel, ab, tol)
+    pad = np.setdiff1d(np.arange(got.shape[1]), cols)
+    assert np.all(got[:, pad] == 0), what + ": padding lanes changed"
+
+
+# ------------------------------------------------------------------------------------------ SGNS
+def _sgns_setup(V, d, T, window, s, seed):
+    toks = wl.zipf_stream(V, s, T, seed)
+    In, Out = wl.sgns_tables(V, d, seed + 1)
+    Out[:] = wl.uniform_table(V, d, -0.5 / d, 0.5 / d, seed + 2)   # non-zero so the first step exercises every term
+    w = wl.unigram_weights(toks, V)
+    return toks, In, Out, w
+
+
+@pytest.mark.parametrize("V,d,B,K,window,s", [
+    (10_000, 100, 4096, 5, 2, 1.0),      # the small SGNS configuration
+    (50_000, 300, 4100, 3, 5, 1.0),      # d = 300 rows (5 float4 per lane), ragged batch
+    (2_000, 200, 1500, 5, 5, 1.4),       # heavy skew: long segments
+    (300, 64, 37, 0, 1, 0.6),            # no negatives
+    (100, 500, 1, 2, 1, 1.0),            # one pair
+    (1_000, 1000, 200, 2, 2, 1.0),       # paper's word-vector dimension
+])
+def test_sgns_one_step_matches_the_oracle(V, d, B, K, window, s):
+    toks, In, Out, w = _sgns_setup(V, d, B // (2 * window) + 2 * window + 2, window, s, 10)
+    c, o = wl.window_pairs(toks, window, 0, B)
+    B = len(c)
+    tin, tout = dev(In), dev(Out)
+    ctx = nb.nups_init([tin, tout], [d, d])
+    dist = nb.nups_register_distribution(ctx, 1, w, nb.NUPS_CONFORM, seed=77)
+    h = nb.nups_prepare_sample(dist, B * K, 0)
+    negs_addr, _ = nb.nups_sample_keys(h)
+    kc, ko = dev_u32(c), dev_u32(o)
+    batch = nb.make_batch(nb.NUPS_TASK_SGNS, B, kc, ko, n_neg=K, lr=0.025, negs=negs_addr if K else None)
+    loss = nb.nups_step(ctx, batch, want_loss=True)
+    negs = orc.sample_conform(orc.alias_build(w), V, 77, 0, 0, B * K)
+    rin, rout = In.copy(), Out.copy()
+    rloss, s_in, s_out = orc.step_sgns(rin, rout, d, c, o, negs, K, 0.025)
+    _assert_structure(ctx, 0, B, s_in)
+    _assert_structure(ctx, 1, B * (K + 1), s_out)
+    cols = list(range(d))
+    _assert_close(tin.cpu().numpy(), rin, cols, TOL_ONE_STEP, "input table")
+    _assert_close(tout.cpu().numpy(), rout, cols, TOL_ONE_STEP, "output table")
+    assert abs(loss - rloss) <= 1e-5 * abs(rloss)
+    nb.nups_release_sample(h)
+    nb.nups_destroy(ctx)
+
+
+def test_sgns_100_steps_small_configuration():
+    V, d, B, K, window = 10_000, 100, 4096, 5, 2
+    steps = 100
+    toks = wl.zipf_stream(V, 1.0, steps * B // (2 * window) + 2 * window + 8, 1001)
+    In, Out = wl.sgns_tables(V, d, 1001)          # output table starts at zero, as in word2vec
+    w = wl.unigram_weights(toks, V)
+    tin, tout = dev(In), dev(Out)
+    ctx = nb.nups_init([tin, tout], [d, d])
+    dist = nb.nups_register_distribution(ctx, 1, w, nb.NUPS_CONFORM, seed=1001)
+    alias = orc.alias_build(w)
+    rin, rout = In.copy(), Out.copy()
+    for t in range(steps):
+        c, o = wl.window_pairs(toks, window, t * B, B)
+        h = nb.nups_prepare_sample(dist, B * K, t)
+        addr, _ = nb.nups_sample_keys(h)
+        kc, ko = dev_u32(c), dev_u32(o)
+        nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_SGNS, B, kc, ko, n_neg=K, lr=0.025, negs=addr))
+        nb.nups_check(ctx)
+        nb.nups_release_sample(h)
+        negs = orc.sample_conform(alias, V, 1001, 0, t, B * K)
+        orc.step_sgns(rin, rout, d, c, o, negs, K, 0.025)
+    cols = list(range(d))
+    _assert_close(tin.cpu().numpy(), rin, cols, TOL_100_STEPS, "input table after 100 steps")
+    _assert_close(tout.cpu().numpy(), rout, cols, TOL_100_STEPS, "output table after 100 steps")
+    nb.nups_destroy(ctx)
+
+
+def test_sgns_bounded_reuse_step_and_bad_keys():
+    V, d, B, K = 20_000, 300, 2048, 3
+    toks, In, Out, w = _sgns_setup(V, d, B // 10 + 20, 5, 1.0, 5)
+    c, o = wl.window_pairs(toks, 5, 0, B)
+    tin, tout = dev(In), dev(Out)
+    ctx = nb.nups_init([tin, tout], [d, d])
+    dist = nb.nups_register_distribution(ctx, 1, w, nb.NUPS_BOUNDED, U=4, G=250, seed=4)
+    h = nb.nups_prepare_sample(dist, B * K, 3)
+    addr, _ = nb.nups_sample_keys(h)
+    kc, ko = dev_u32(c), dev_u32(o)
+    nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_SGNS, B, kc, ko, n_neg=K, lr=0.025, negs=addr), want_loss=True)
+    negs = orc.sample_bounded(orc.alias_build(w), V, 4, 0, 3, B * K, 4, 250)
+    rin, rout = In.copy(), Out.copy()
+    _, s_in, s_out = orc.step_sgns(rin, rout, d, c, o, negs, K, 0.025)
+    _assert_structure(ctx, 1, B * (K + 1), s_out)
+    _assert_close(tout.cpu().numpy(), rout, list(range(d)), TOL_ONE_STEP, "output table")
+    _assert_close(tin.cpu().numpy(), rin, list(range(d)), TOL_ONE_STEP, "input table")
+    # a key outside the table is reported, and nothing faults
+    bad = c.copy(); bad[5] = V
+    with pytest.raises(nb.NupsError) as e:
+        nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_SGNS, B, dev_u32(bad), ko, n_neg=K, lr=0.0, negs=addr), want_loss=True)
+    assert e.value.status == nb.NUPS_ERR_KEY_RANGE
+    # an empty batch is a no-op
+    before = tin.cpu().numpy()
+    nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_SGNS, 0, None, None, n_neg=K, lr=0.025), want_loss=True)
+    assert np.array_equal(tin.cpu().numpy(), before)
+    nb.nups_release_sample(h)
+    nb.nups_destroy(ctx)
+
+
+# ------------------------------------------------------------------------------------------ MF
+@pytest.mark.parametrize("nr,nc,d,B,s", [(100_000, 10_000, 100, 65_536, 0.8), (500, 300, 100, 5000, 1.1), (50, 40, 10, 1, 0.8)])
+def test_mf_one_step_matches_the_oracle(nr, nc, d, B, s):
+    rows, cols, vals = wl.mf_cells(nr, nc, s, B, 1002)
+    W = wl.uniform_table(nr, d, -0.1, 0.1, 1)
+    H = wl.uniform_table(nc, d, -0.1, 0.1, 2)
+    tw, th = dev(W), dev(H)
+    ctx = nb.nups_init([tw, th], [d, d])
+    batch = nb.make_batch(nb.NUPS_TASK_MF, B, dev_u32(rows), dev_u32(cols), val=dev(vals), lr=0.005, l2=0.01)
+    keep = (batch,)
+    loss = nb.nups_step(ctx, batch, want_loss=True)
+    rw, rh = W.copy(), H.copy()
+    rloss, sw, sh = orc.step_mf(rw, rh, d, rows, cols, vals, 0.005, 0.01)
+    _assert_structure(ctx, 0, B, sw)
+    _assert_structure(ctx, 1, B, sh)
+    _assert_close(tw.cpu().numpy(), rw, list(range(d)), TOL_ONE_STEP, "row factors")
+    _assert_close(th.cpu().numpy(), rh, list(range(d)), TOL_ONE_STEP, "column factors")
+    assert abs(loss - rloss) <= 1e-5 * abs(rloss)
+    nb.nups_destroy(ctx)
+
+
+# ------------------------------------------------------------------------------------------ KGE
+def _ccols(d, stride):
+    return list(range(d // 2)) + list(range(stride // 2, stride // 2 + d // 2))
+
+
+@pytest.mark.parametrize("ne,nrel,d,B,nh,nt", [(200_000, 822, 500, 128, 50, 50), (5_000, 20, 100, 64, 3, 0),
+                                                (5_000, 20, 200, 33, 0, 7), (100, 5, 64, 16, 0, 0), (300, 5, 300, 40, 17, 16)])
+def test_kge_one_step_matches_the_oracle(ne, nrel, d, B, nh, nt):
+    import torch
+    s, r, o = wl.kge_triples(ne, nrel, B, 1003)
+    E = wl.complex_table(ne, d, -0.1, 0.1, 1)
+    R = wl.complex_table(nrel, d, -0.1, 0.1, 2)
+    stride = E.shape[1]
+    rng = np.random.default_rng(3)
+    GE = np.zeros_like(E); GR = np.zeros_like(R)
+    cc = _ccols(d, stride)
+    GE[:, cc] = rng.random((ne, d), dtype=np.float32) * 1e-4       # a non-trivial optimiser state
+    GR[:, cc] = rng.random((nrel, d), dtype=np.float32) * 1e-4
+    te, tge, tr, tgr = dev(E), dev(GE), dev(R), dev(GR)
+    ctx = nb.nups_init([te, tr], [d, d])
+    nb.nups_set_state(ctx, 0, tge)
+    nb.nups_set_state(ctx, 1, tgr)
+    dist = nb.nups_register_distribution(ctx, 0, None, nb.NUPS_CONFORM, seed=8)
+    nn = nh + nt
+    h = nb.nups_prepare_sample(dist, B * nn, 2)
+    addr, _ = nb.nups_sample_keys(h)
+    ks, kr, ko = dev_u32(s), dev_u32(r), dev_u32(o)
+    batch = nb.make_batch(nb.NUPS_TASK_KGE, B, ks, kr, k2=ko, n_neg=nh, n_neg2=nt, lr=0.1, eps=1e-10,
+                          negs=addr if nn else None)
+    loss = nb.nups_step(ctx, batch, want_loss=True)
+    negs = orc.sample_conform(None, ne, 8, 0, 2, B * nn)
+    rE, rGE, rR, rGR = E.copy(), GE.copy(), R.copy(), GR.copy()
+    rloss, se, sr = orc.step_kge(rE, rGE, rR, rGR, d, s, r, o, negs, nh, nt, 0.1, 1e-10)
+    _assert_structure(ctx, 0, B * (2 + nn), se)
+    _assert_structure(ctx, 1, B, sr)
+    _assert_close(te.cpu().numpy(), rE, cc, TOL_ONE_STEP, "entities")
+    _assert_close(tr.cpu().numpy(), rR, cc, TOL_ONE_STEP, "relations")
+    _assert_close(tge.cpu().numpy(), rGE, cc, TOL_ONE_STEP, "entity AdaGrad state")
+    _assert_close(tgr.cpu().numpy(), rGR, cc, TOL_ONE_STEP, "relation AdaGrad state")
+    assert abs(loss - rloss) <= 1e-5 * abs(rloss)
+    nb.nups_release_sample(h)
+    nb.nups_destroy(ctx)
+
+
+def test_kge_needs_state():
+    E = dev(wl.complex_table(10, 64, -1, 1, 1)); R = dev(wl.complex_table(3, 64, -1, 1, 2))
+    ctx = nb.nups_init([E, R], [64, 64])
+    k = dev_u32([1])
+    with pytest.raises(nb.NupsError) as e:
+        nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_KGE, 1, k, k, k2=k, lr=0.1, eps=1e-10))
+    assert e.value.status == nb.NUPS_ERR_STATE
+    nb.nups_destroy(ctx)

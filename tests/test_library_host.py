@@ -1,0 +1,80 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every declared
+symbol, rejects bad arguments, and builds the same alias table as the oracle bit for bit."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2104_00501_amd import binding as nb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_entry_point_is_exported():
+    header = open(os.path.join(ROOT, "include", "nups.h")).read()
+    declared = set(re.findall(r"\b(nups_[a-z_]+)\s*\(", header))
+    declared -= {"nups_status", "nups_scheme", "nups_task"}
+    assert declared == set(nb.EXPORTS)
+    lib = nb.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+@pytest.mark.parametrize("seed,V", [(0, 1), (1, 2), (2, 33), (3, 1000), (4, 50000)])
+def test_alias_table_equals_the_oracles(seed, V):
+    rng = np.random.default_rng(seed)
+    w = rng.random(V) ** 4
+    w[rng.random(V) < 0.3] = 0
+    w[0] = 0.5
+    t1, a1 = nb.nups_build_alias_table(w)
+    t2, a2 = orc.alias_build(w)
+    assert np.array_equal(t1, t2) and np.array_equal(a1, a2)
+
+
+def test_alias_table_zipf_weights_equal_the_oracles():
+    w = (np.arange(1, 200001, dtype=np.float64) ** -1.0 * 1e9) ** 0.75
+    t1, a1 = nb.nups_build_alias_table(w)
+    t2, a2 = orc.alias_build(w)
+    assert np.array_equal(t1, t2) and np.array_equal(a1, a2)
+
+
+def test_alias_table_rejects_bad_weights():
+    for bad in ([0.0, 0.0], [1.0, -1.0], [1.0, float("nan")], [float("inf"), 1.0]):
+        with pytest.raises(nb.NupsError) as e:
+            nb.nups_build_alias_table(np.array(bad))
+        assert e.value.status == nb.NUPS_ERR_ARG
+    assert "weights" in nb.nups_last_error()
+
+
+def test_init_rejects_bad_shapes_before_touching_the_device():
+    lib = nb.lib()
+    ctx = C.c_void_p(None)
+    ptrs = (C.c_void_p * 1)(0x1000)
+    def call(nk, dim, stride, n=1, tables=ptrs):
+        return lib.nups_init(C.byref(ctx), C.c_int(n), tables, (C.c_int64 * 1)(nk), (C.c_int32 * 1)(dim),
+                             (C.c_int32 * 1)(stride), None)
+    assert call(10, 100, 64) == nb.NUPS_ERR_ARG          # dim > row_stride
+    assert call(10, 100, 100) == nb.NUPS_ERR_ARG         # stride not a multiple of 64
+    assert call(10, 100, 2048) == nb.NUPS_ERR_ARG        # stride too large
+    assert call(0, 100, 128) == nb.NUPS_ERR_ARG          # no keys
+    assert call(10, 0, 128) == nb.NUPS_ERR_ARG
+    assert call(10, 100, 128, n=0) == nb.NUPS_ERR_ARG
+    assert call(10, 100, 128, n=5) == nb.NUPS_ERR_ARG
+    assert call(10, 100, 128, tables=(C.c_void_p * 1)(None)) == nb.NUPS_ERR_ARG
+    assert lib.nups_init(None, 1, ptrs, None, None, None, None) == nb.NUPS_ERR_ARG
+    assert ctx.value is None
+
+
+def test_null_objects_are_rejected():
+    lib = nb.lib()
+    assert lib.nups_destroy(None) == nb.NUPS_ERR_ARG
+    assert lib.nups_step(None, None, None) == nb.NUPS_ERR_ARG
+    assert lib.nups_pull(None, 0, None, 0, None) == nb.NUPS_ERR_ARG
+    assert lib.nups_release_sample(None) == nb.NUPS_ERR_ARG
+    assert lib.nups_pull_sample(None, C.c_int64(1), None, None) == nb.NUPS_ERR_ARG
+    assert lib.nups_prepare_sample(None, C.c_int64(1), C.c_uint64(0), C.byref(C.c_void_p())) == nb.NUPS_ERR_ARG
+    assert lib.nups_check(None) == nb.NUPS_ERR_ARG
+    assert nb.nups_phase_name(nb.NUPS_PHASE_GRAD) == "grad" and nb.nups_phase_name(99) == ""
