@@ -11,8 +11,13 @@
  *  - The library never owns table, state, batch or output memory: the caller
  *    allocates it and keeps it alive while the context uses it.  The library owns
  *    only its workspace and the opaque objects it hands out.
- *  - All device work is enqueued on the HIP stream given to nups_init; calls return
- *    without waiting unless they hand a value back to the host (stated per call).
+ *  - Everything that reads or writes table values is enqueued on the HIP stream given to
+ *    nups_init.  Preparatory work that only handles keys (drawing samples, building the
+ *    per-key aggregation structure of a step; the "background" work of Section 4.3) is
+ *    enqueued on a second, library-owned stream of default priority and ordered against the
+ *    caller's stream with events: it starts after what the caller's stream held when the
+ *    prepare call was made, and its consumers on the caller's stream wait for it.  Calls
+ *    return without waiting unless they hand a value back to the host (stated per call).
  *  - A table is a dense [num_keys, row_stride] fp32 array; the first `dim` floats of
  *    a row are the parameter, the rest is padding that stays zero.  row_stride must be
  *    a multiple of 64 floats (at most 1024); keys are uint32 row numbers.
@@ -33,6 +38,7 @@ extern "C" {
 typedef struct nups_ctx nups_ctx;        /* tables + workspace + stream      */
 typedef struct nups_dist nups_dist;      /* a registered target distribution */
 typedef struct nups_sample nups_sample;  /* handle returned by PrepareSample */
+typedef struct nups_prepared nups_prepared; /* a step whose preparatory work has been enqueued */
 
 typedef enum {
     NUPS_OK = 0,
@@ -145,7 +151,8 @@ nups_status nups_prepare_sample(nups_dist *dist, int64_t n, uint64_t step, nups_
  */
 nups_status nups_pull_sample(nups_sample *handle, int64_t n_j, uint32_t *keys_dev, float *values_dev);
 
-/* Device address of all N keys of the handle (valid until release; filled in stream order). */
+/* Device address of all N keys of the handle (valid until release).  Work enqueued on the caller's
+ * stream after this call sees the keys. */
 nups_status nups_sample_keys(nups_sample *handle, const uint32_t **keys_dev, int64_t *n);
 
 /* Gives the handle back; releasing twice is NUPS_ERR_STATE. */
@@ -165,7 +172,11 @@ typedef struct {
     float lr;              /* learning rate                                                       */
     float l2;              /* MF: L2 regularisation weight                                        */
     float eps;             /* KGE: AdaGrad epsilon                                                */
-    const uint32_t *negs;  /* dev [B * (n_neg + n_neg2)] sampled keys, example-major (NULL if none) */
+    const uint32_t *negs;  /* dev [B * (n_neg + n_neg2)] sampled keys, example-major (NULL if none or if
+                              `sample` is given)                                                   */
+    nups_sample *sample;   /* alternatively: the handle whose N >= B * (n_neg + n_neg2) keys are the
+                              negatives (no wait is put on the caller's stream; the step orders itself
+                              after the drawing).  NULL if `negs` is given or there are none.       */
 } nups_batch;
 
 /*
@@ -178,6 +189,18 @@ typedef struct {
  * only enqueues.
  */
 nups_status nups_step(nups_ctx *ctx, const nups_batch *batch, double *loss_sum_host);
+
+/*
+ * The same step in two halves, in the manner of PrepareSample / PullSample (Section 4.3):
+ * nups_prepare_step enqueues the work that depends only on the batch's keys (the per-key
+ * aggregation structure) on the side stream and returns at once; nups_step_prepared runs the
+ * gradient and the updates on the caller's stream once that is ready.  Preparing step t+1 before
+ * running step t lets the two overlap.  The key arrays of the batch (and the sampled keys it
+ * points to) must stay valid until the step has run.  A prepared step is consumed by running it;
+ * running it twice is NUPS_ERR_STATE.  nups_step(batch) is prepare followed by run.
+ */
+nups_status nups_prepare_step(nups_ctx *ctx, const nups_batch *batch, nups_prepared **out);
+nups_status nups_step_prepared(nups_ctx *ctx, nups_prepared *step, double *loss_sum_host);
 
 /*
  * Aggregation structure of the last nups_step / nups_push on `table`: the distinct

@@ -23,7 +23,8 @@ NUPS_TASK_SGNS, NUPS_TASK_MF, NUPS_TASK_KGE = 1, 2, 3
 EXPORTS = [
     "nups_init", "nups_destroy", "nups_set_state", "nups_set_hot_keys", "nups_pull", "nups_push",
     "nups_build_alias_table", "nups_register_distribution", "nups_set_local_keys", "nups_prepare_sample",
-    "nups_pull_sample", "nups_sample_keys", "nups_release_sample", "nups_step", "nups_debug_structure",
+    "nups_pull_sample", "nups_sample_keys", "nups_release_sample", "nups_step", "nups_prepare_step",
+    "nups_step_prepared", "nups_debug_structure",
     "nups_check", "nups_profile", "nups_profile_read", "nups_phase_name", "nups_last_error",
 ]
 
@@ -37,7 +38,7 @@ class NupsError(RuntimeError):
 class nups_batch(C.Structure):
     _fields_ = [("task", C.c_int32), ("B", C.c_int64), ("k0", C.c_void_p), ("k1", C.c_void_p), ("k2", C.c_void_p),
                 ("val", C.c_void_p), ("n_neg", C.c_int32), ("n_neg2", C.c_int32), ("lr", C.c_float),
-                ("l2", C.c_float), ("eps", C.c_float), ("negs", C.c_void_p)]
+                ("l2", C.c_float), ("eps", C.c_float), ("negs", C.c_void_p), ("sample", C.c_void_p)]
 
 
 _lib = None
@@ -173,11 +174,12 @@ def nups_release_sample(handle):
     _check(lib().nups_release_sample(handle))
 
 
-def make_batch(task, B, k0, k1, k2=None, val=None, n_neg=0, n_neg2=0, lr=0.0, l2=0.0, eps=0.0, negs=None):
+def make_batch(task, B, k0, k1, k2=None, val=None, n_neg=0, n_neg2=0, lr=0.0, l2=0.0, eps=0.0, negs=None, sample=None):
     b = nups_batch()
     b.task, b.B = task, B
     b.k0, b.k1, b.k2, b.val, b.negs = (_ptr(x).value for x in (k0, k1, k2, val, negs))
     b.n_neg, b.n_neg2, b.lr, b.l2, b.eps = n_neg, n_neg2, lr, l2, eps
+    b.sample = sample.value if hasattr(sample, "value") else sample
     return b
 
 
@@ -188,6 +190,22 @@ def nups_step(ctx, batch, want_loss=False):
         _check(lib().nups_step(ctx, C.byref(batch), C.byref(loss)))
         return loss.value
     _check(lib().nups_step(ctx, C.byref(batch), None))
+    return None
+
+
+def nups_prepare_step(ctx, batch):
+    """Enqueues the key-only preparatory work of a step on the side stream; returns the prepared step."""
+    p = C.c_void_p(None)
+    _check(lib().nups_prepare_step(ctx, C.byref(batch), C.byref(p)))
+    return p
+
+
+def nups_step_prepared(ctx, prepared, want_loss=False):
+    if want_loss:
+        loss = C.c_double(0.0)
+        _check(lib().nups_step_prepared(ctx, prepared, C.byref(loss)))
+        return loss.value
+    _check(lib().nups_step_prepared(ctx, prepared, None))
     return None
 
 

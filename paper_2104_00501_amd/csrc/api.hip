@@ -1,4 +1,6 @@
-// Host side of the C ABI declared in include/nups.h: argument checks, workspace, object lifetimes.
+// Host side of the C ABI declared in include/nups.h: argument checks, workspace, object lifetimes,
+// and the two-stream schedule: sampling and plan construction ("preparatory work", Section 4.3) run on a
+// library-owned side stream, everything that reads or writes table values runs on the caller's stream.
 #include <algorithm>
 #include <cstring>
 
@@ -35,30 +37,13 @@ nups_status ensure_f32(float **buf, size_t *cap, size_t need, hipStream_t stream
     return NUPS_OK;
 }
 
-static nups_status ensure_u32(uint32_t **buf, size_t *cap, size_t need, hipStream_t stream)
-{
-    if (*cap >= need && *buf) return NUPS_OK;
-    NUPS_HIP(hipStreamSynchronize(stream));
-    if (*buf) NUPS_HIP(hipFree(*buf));
-    *buf = nullptr;
-    const size_t n = need + need / 4 + 1024;
-    NUPS_HIP(hipMalloc((void **)buf, sizeof(uint32_t) * n));
-    *cap = n;
-    return NUPS_OK;
-}
-
-PhaseScope::PhaseScope(nups_ctx *c, int p) : ctx(c), phase(p)
+PhaseScope::PhaseScope(nups_ctx *c, int p, hipStream_t s) : ctx(c), phase(p), stream(s)
 {
     if (!ctx->profiling) return;
     Phase &ph = ctx->phase[phase];
-    auto get = [&]() {
-        hipEvent_t e = nullptr;
-        if (!ph.free_events.empty()) { e = ph.free_events.back(); ph.free_events.pop_back(); }
-        else if (hipEventCreate(&e) != hipSuccess) e = nullptr;
-        return e;
-    };
-    start = get();
-    if (start) (void)hipEventRecord(start, ctx->stream);
+    if (!ph.free_events.empty()) { start = ph.free_events.back(); ph.free_events.pop_back(); }
+    else if (hipEventCreate(&start) != hipSuccess) start = nullptr;
+    if (start) (void)hipEventRecord(start, stream);
 }
 
 PhaseScope::~PhaseScope()
@@ -69,23 +54,14 @@ PhaseScope::~PhaseScope()
     if (!ph.free_events.empty()) { stop = ph.free_events.back(); ph.free_events.pop_back(); }
     else if (hipEventCreate(&stop) != hipSuccess) stop = nullptr;
     if (!stop) { ph.free_events.push_back(start); return; }
-    (void)hipEventRecord(stop, ctx->stream);
+    (void)hipEventRecord(stop, stream);
     ph.pending.emplace_back(start, stop);
-}
-
-static void free_plan(Plan &pl)
-{
-    PlanArgs &a = pl.a;
-    for (uint32_t *p : {a.bitmap, a.word_rank, a.tile_sum, a.uniq, a.count, a.seg, a.slot, a.rank, a.perm,
-                        a.long_list, a.meta})
-        if (p) (void)hipFree(p);
-    pl = Plan{};
 }
 
 static void free_sample(nups_sample *h)
 {
     if (h->keys_dev) (void)hipFree(h->keys_dev);
-    if (h->fresh_dev) (void)hipFree(h->fresh_dev);
+    if (h->ready) (void)hipEventDestroy(h->ready);
     delete h;
 }
 
@@ -98,9 +74,18 @@ static void free_dist(nups_dist *d)
     delete d;
 }
 
-// Waits for the stream and turns a raised device flag into an error.
+static void free_prepared(nups_prepared *p)
+{
+    free_plan_arrays(p->plan[0]);
+    free_plan_arrays(p->plan[1]);
+    if (p->ready) (void)hipEventDestroy(p->ready);
+    delete p;
+}
+
+// Waits for both streams and turns a raised device flag into an error.
 static nups_status sync_and_check(nups_ctx *ctx)
 {
+    NUPS_HIP(hipStreamSynchronize(ctx->side));
     NUPS_HIP(hipMemcpyAsync(ctx->flag_pinned, ctx->error_flag, sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
     NUPS_HIP(hipStreamSynchronize(ctx->stream));
     if (*ctx->flag_pinned != 0) {
@@ -112,6 +97,92 @@ static nups_status sync_and_check(nups_ctx *ctx)
 }
 
 static bool valid_table(const nups_ctx *ctx, int t) { return ctx && t >= 0 && t < ctx->n_tables; }
+
+// Work enqueued on the side stream from here on starts after everything already enqueued on the caller's stream
+// (key arrays written there are complete; buffers consumed there are free again).
+static nups_status side_after_main(nups_ctx *ctx)
+{
+    NUPS_HIP(hipEventRecord(ctx->fork, ctx->stream));
+    NUPS_HIP(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
+    return NUPS_OK;
+}
+
+static nups_status new_event(hipEvent_t *ev)
+{
+    if (*ev) return NUPS_OK;
+    NUPS_HIP(hipEventCreateWithFlags(ev, hipEventDisableTiming));
+    return NUPS_OK;
+}
+
+static nups_status get_prepared(nups_ctx *ctx, nups_prepared **out)
+{
+    nups_prepared *p = nullptr;
+    if (!ctx->prepared_free.empty()) { p = ctx->prepared_free.back(); ctx->prepared_free.pop_back(); }
+    else {
+        p = new nups_prepared();
+        p->ctx = ctx;
+        ctx->prepared_all.push_back(p);
+    }
+    nups_status st = new_event(&p->ready);
+    if (st != NUPS_OK) { ctx->prepared_free.push_back(p); return st; }
+    *out = p;
+    return NUPS_OK;
+}
+
+// A consumed step is recycled once no table's structure query refers to it any more.  Its arrays may still be
+// read by kernels in flight on the caller's stream; the next build waits for those (side_after_main).
+static void retire_prepared(nups_ctx *ctx, nups_prepared *p)
+{
+    p->live = false;
+    p->retired = true;
+    for (int j = 0; j < p->n_plans; ++j) ctx->tab[p->plan[j].table].last_plan = &p->plan[j];
+    for (nups_prepared *q : ctx->prepared_all) {
+        if (!q->retired) continue;
+        bool referenced = false;
+        for (int t = 0; t < kMaxTables; ++t)
+            for (int k = 0; k < 2; ++k) referenced |= (ctx->tab[t].last_plan == &q->plan[k]);
+        if (!referenced) { q->retired = false; ctx->prepared_free.push_back(q); }
+    }
+}
+
+static nups_status check_batch(nups_ctx *ctx, const nups_batch *b)
+{
+    if (!ctx || !b) return fail(NUPS_ERR_ARG, "nups_step: null argument");
+    if (ctx->n_tables < 2) return fail(NUPS_ERR_STATE, "nups_step: the context needs two tables");
+    if (b->B < 0 || b->B > (1ll << 24)) return fail(NUPS_ERR_ARG, "nups_step: batch size out of range");
+    if (b->n_neg < 0 || b->n_neg2 < 0 || b->n_neg > 4096 || b->n_neg2 > 4096)
+        return fail(NUPS_ERR_ARG, "nups_step: negative counts out of range");
+    if (b->B > 0 && (!b->k0 || !b->k1)) return fail(NUPS_ERR_ARG, "nups_step: null key array");
+    const int64_t nn = (int64_t)b->n_neg + b->n_neg2;
+    if (b->B * (nn + 2) > 0x7FFFFFFFll) return fail(NUPS_ERR_ARG, "nups_step: too many accesses for one step");
+    if (ctx->tab[0].stride != ctx->tab[1].stride)
+        return fail(NUPS_ERR_ARG, "nups_step: tables 0 and 1 need equal row_stride");
+    if (b->sample) {
+        if (b->negs) return fail(NUPS_ERR_ARG, "nups_step: give either negs or sample, not both");
+        if (!b->sample->live) return fail(NUPS_ERR_STATE, "nups_step: the sample handle was released");
+        if (b->sample->dist->ctx != ctx) return fail(NUPS_ERR_ARG, "nups_step: the sample handle is of another context");
+        if (b->sample->n < b->B * nn) return fail(NUPS_ERR_ARG, "nups_step: the sample handle holds too few keys");
+    }
+    switch (b->task) {
+    case NUPS_TASK_SGNS:
+        if (b->n_neg2 != 0) return fail(NUPS_ERR_ARG, "nups_step: SGNS uses n_neg only");
+        if (b->B > 0 && b->n_neg > 0 && !b->negs && !b->sample) return fail(NUPS_ERR_ARG, "nups_step: null negatives");
+        break;
+    case NUPS_TASK_MF:
+        if (b->B > 0 && !b->val) return fail(NUPS_ERR_ARG, "nups_step: null cell values");
+        if (nn != 0) return fail(NUPS_ERR_ARG, "nups_step: MF has no sampling access");
+        break;
+    case NUPS_TASK_KGE:
+        if (b->B > 0 && !b->k2) return fail(NUPS_ERR_ARG, "nups_step: null object keys");
+        if (b->B > 0 && nn > 0 && !b->negs && !b->sample) return fail(NUPS_ERR_ARG, "nups_step: null negatives");
+        if (!ctx->tab[0].state || !ctx->tab[1].state)
+            return fail(NUPS_ERR_STATE, "nups_step: KGE needs AdaGrad state on tables 0 and 1 (nups_set_state)");
+        break;
+    default:
+        return fail(NUPS_ERR_ARG, "nups_step: unknown task");
+    }
+    return NUPS_OK;
+}
 
 }  // namespace nups
 
@@ -153,12 +224,15 @@ nups_status nups_init(nups_ctx **out, int n_tables, float *const *tables_dev, co
         ctx->tab[t].dim = dim[t];
         ctx->tab[t].stride = row_stride[t];
     }
-    hipError_t e = hipMalloc((void **)&ctx->loss_dev, sizeof(double));
+    hipError_t e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);   // default priority
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->loss_dev, sizeof(double));
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->error_flag, sizeof(uint32_t));
     if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->loss_pinned, sizeof(double), hipHostMallocDefault);
     if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->flag_pinned, sizeof(uint32_t), hipHostMallocDefault);
     if (e == hipSuccess) e = hipMemsetAsync(ctx->error_flag, 0, sizeof(uint32_t), ctx->stream);
     if (e == hipSuccess) e = hipMemsetAsync(ctx->loss_dev, 0, sizeof(double), ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) {
         hip_ok(e, "nups_init: workspace allocation");
         nups_destroy(ctx);
@@ -171,14 +245,14 @@ nups_status nups_init(nups_ctx **out, int n_tables, float *const *tables_dev, co
 nups_status nups_destroy(nups_ctx *ctx)
 {
     if (!ctx) return fail(NUPS_ERR_ARG, "nups_destroy: null context");
+    if (ctx->side) (void)hipStreamSynchronize(ctx->side);
     (void)hipStreamSynchronize(ctx->stream);
     for (nups_dist *d : ctx->dists) free_dist(d);
-    for (int t = 0; t < kMaxTables; ++t) {
-        free_plan(ctx->tab[t].plan);
-        if (ctx->tab[t].hot_slot_dev) (void)hipFree(ctx->tab[t].hot_slot_dev);
-    }
+    for (nups_prepared *p : ctx->prepared_all) free_prepared(p);
+    for (int t = 0; t < kMaxTables; ++t) free_plan_scratch(ctx->tab[t].scratch);
     if (ctx->coef) (void)hipFree(ctx->coef);
     if (ctx->stage) (void)hipFree(ctx->stage);
+    if (ctx->partial) (void)hipFree(ctx->partial);
     if (ctx->loss_dev) (void)hipFree(ctx->loss_dev);
     if (ctx->error_flag) (void)hipFree(ctx->error_flag);
     if (ctx->loss_pinned) (void)hipHostFree(ctx->loss_pinned);
@@ -187,6 +261,8 @@ nups_status nups_destroy(nups_ctx *ctx)
         for (auto &pr : ph.pending) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
         for (hipEvent_t ev : ph.free_events) (void)hipEventDestroy(ev);
     }
+    if (ctx->fork) (void)hipEventDestroy(ctx->fork);
+    if (ctx->side) (void)hipStreamDestroy(ctx->side);
     delete ctx;
     return NUPS_OK;
 }
@@ -227,14 +303,21 @@ nups_status nups_push(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_
     if (n < 0 || n > 0x7FFFFFFFll || (n > 0 && (!keys_dev || !updates_dev)))
         return fail(NUPS_ERR_ARG, "nups_push: bad arguments");
     Table &t = ctx->tab[table];
-    nups_status st;
-    if ((st = ensure_plan_capacity(ctx, t, (size_t)n)) != NUPS_OK) return st;
-    t.plan.a.src = KeySource{{keys_dev, nullptr, nullptr}, {(uint32_t)n, 0, 0}};
-    t.plan.a.n = (uint32_t)n;
-    Plan *plans[1] = {&t.plan};
-    if ((st = build_plans(ctx, plans, 1)) != NUPS_OK) return st;
-    if (n == 0) return NUPS_OK;
-    return launch_push_apply(ctx, t, updates_dev);
+    nups_prepared *p = nullptr;
+    nups_status st = get_prepared(ctx, &p);
+    if (st != NUPS_OK) return st;
+    p->n_plans = 1;
+    p->plan[0].table = table;
+    if ((st = ensure_plan_capacity(ctx, t, p->plan[0], (size_t)n)) != NUPS_OK) return st;
+    p->plan[0].a.src = KeySource{{keys_dev, nullptr, nullptr}, {(uint32_t)n, 0, 0}};
+    p->plan[0].a.n = (uint32_t)n;
+    if ((st = side_after_main(ctx)) != NUPS_OK) return st;
+    if ((st = build_plans(ctx, p->plan, 1)) != NUPS_OK) return st;
+    NUPS_HIP(hipEventRecord(p->ready, ctx->side));
+    NUPS_HIP(hipStreamWaitEvent(ctx->stream, p->ready, 0));
+    if (n > 0) st = launch_push_apply(ctx, t, p->plan[0], updates_dev);
+    retire_prepared(ctx, p);
+    return st;
 }
 
 nups_status nups_register_distribution(nups_ctx *ctx, int table, const double *weights_host, nups_scheme scheme,
@@ -315,14 +398,24 @@ nups_status nups_prepare_sample(nups_dist *dist, int64_t n, uint64_t step, nups_
     nups_sample *h = nullptr;
     if (!dist->recycled.empty()) { h = dist->recycled.back(); dist->recycled.pop_back(); }
     else { h = new nups_sample(); h->dist = dist; }
-    nups_status st = ensure_u32(&h->keys_dev, &h->cap, (size_t)n, ctx->stream);
-    if (st == NUPS_OK && dist->scheme == NUPS_BOUNDED)
-        st = ensure_u32(&h->fresh_dev, &h->fresh_cap, (size_t)((n + dist->U - 1) / dist->U), ctx->stream);
+    nups_status st = new_event(&h->ready);
+    if (st == NUPS_OK && (h->cap < (size_t)n || !h->keys_dev)) {
+        hipError_t e = hipStreamSynchronize(ctx->side);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        if (e == hipSuccess && h->keys_dev) e = hipFree(h->keys_dev);
+        h->keys_dev = nullptr;
+        h->cap = (size_t)n + (size_t)n / 4 + 1024;
+        if (e == hipSuccess) e = hipMalloc((void **)&h->keys_dev, sizeof(uint32_t) * h->cap);
+        if (e != hipSuccess) { hip_ok(e, "nups_prepare_sample: key buffer"); h->cap = 0; st = NUPS_ERR_DEVICE; }
+    }
+    if (st == NUPS_OK) st = side_after_main(ctx);
     if (st != NUPS_OK) { dist->recycled.push_back(h); return st; }
     h->n = n;
     h->pulled = 0;
     h->live = true;
     st = launch_sample(dist, h, step);
+    if (st == NUPS_OK && hipEventRecord(h->ready, ctx->side) != hipSuccess)
+        st = fail(NUPS_ERR_DEVICE, "nups_prepare_sample: event record failed");
     if (st != NUPS_OK) { h->live = false; dist->recycled.push_back(h); return st; }
     dist->live.push_back(h);
     *out = h;
@@ -337,6 +430,7 @@ nups_status nups_pull_sample(nups_sample *h, int64_t n_j, uint32_t *keys_dev, fl
     if (h->pulled + n_j > h->n) return fail(NUPS_ERR_OVERPULL, "nups_pull_sample: more samples requested than prepared");
     if (n_j == 0) return NUPS_OK;
     nups_ctx *ctx = h->dist->ctx;
+    NUPS_HIP(hipStreamWaitEvent(ctx->stream, h->ready, 0));
     const uint32_t *src = h->keys_dev + h->pulled;
     if (keys_dev)
         NUPS_HIP(hipMemcpyAsync(keys_dev, src, sizeof(uint32_t) * (size_t)n_j, hipMemcpyDeviceToDevice, ctx->stream));
@@ -352,6 +446,7 @@ nups_status nups_sample_keys(nups_sample *h, const uint32_t **keys_dev, int64_t 
 {
     if (!h || !keys_dev) return fail(NUPS_ERR_ARG, "nups_sample_keys: null argument");
     if (!h->live) return fail(NUPS_ERR_STATE, "nups_sample_keys: handle was released");
+    NUPS_HIP(hipStreamWaitEvent(h->dist->ctx->stream, h->ready, 0));   // later work on the caller's stream sees the keys
     *keys_dev = h->keys_dev;
     if (n) *n = h->n;
     return NUPS_OK;
@@ -368,39 +463,47 @@ nups_status nups_release_sample(nups_sample *h)
     return NUPS_OK;
 }
 
-nups_status nups_step(nups_ctx *ctx, const nups_batch *b, double *loss_sum_host)
+nups_status nups_prepare_step(nups_ctx *ctx, const nups_batch *b, nups_prepared **out)
 {
-    if (!ctx || !b) return fail(NUPS_ERR_ARG, "nups_step: null argument");
-    if (ctx->n_tables < 2) return fail(NUPS_ERR_STATE, "nups_step: the context needs two tables");
-    if (b->B < 0 || b->B > (1ll << 24)) return fail(NUPS_ERR_ARG, "nups_step: batch size out of range");
-    if (b->n_neg < 0 || b->n_neg2 < 0 || b->n_neg > 4096 || b->n_neg2 > 4096)
-        return fail(NUPS_ERR_ARG, "nups_step: negative counts out of range");
-    if (b->B > 0 && (!b->k0 || !b->k1)) return fail(NUPS_ERR_ARG, "nups_step: null key array");
-    const int64_t nn = (int64_t)b->n_neg + b->n_neg2;
-    if (b->B * (nn + 2) > 0x7FFFFFFFll) return fail(NUPS_ERR_ARG, "nups_step: too many accesses for one step");
-    if (ctx->tab[0].stride != ctx->tab[1].stride) return fail(NUPS_ERR_ARG, "nups_step: tables 0 and 1 need equal row_stride");
-    nups_status st;
-    switch (b->task) {
-    case NUPS_TASK_SGNS:
-        if (b->n_neg2 != 0) return fail(NUPS_ERR_ARG, "nups_step: SGNS uses n_neg only");
-        if (b->B > 0 && b->n_neg > 0 && !b->negs) return fail(NUPS_ERR_ARG, "nups_step: null negatives");
-        st = launch_step_sgns(ctx, *b);
-        break;
-    case NUPS_TASK_MF:
-        if (b->B > 0 && !b->val) return fail(NUPS_ERR_ARG, "nups_step: null cell values");
-        if (nn != 0) return fail(NUPS_ERR_ARG, "nups_step: MF has no sampling access");
-        st = launch_step_mf(ctx, *b);
-        break;
-    case NUPS_TASK_KGE:
-        if (b->B > 0 && !b->k2) return fail(NUPS_ERR_ARG, "nups_step: null object keys");
-        if (b->B > 0 && nn > 0 && !b->negs) return fail(NUPS_ERR_ARG, "nups_step: null negatives");
-        if (!ctx->tab[0].state || !ctx->tab[1].state)
-            return fail(NUPS_ERR_STATE, "nups_step: KGE needs AdaGrad state on tables 0 and 1 (nups_set_state)");
-        st = launch_step_kge(ctx, *b);
-        break;
-    default:
-        return fail(NUPS_ERR_ARG, "nups_step: unknown task");
+    if (!out) return fail(NUPS_ERR_ARG, "nups_prepare_step: out is null");
+    *out = nullptr;
+    nups_status st = check_batch(ctx, b);
+    if (st != NUPS_OK) return st;
+    nups_prepared *p = nullptr;
+    if ((st = get_prepared(ctx, &p)) != NUPS_OK) return st;
+    p->batch = *b;
+    if (b->sample) {   // drawn on the side stream, i.e. before the build that follows on the same stream
+        p->batch.negs = b->sample->keys_dev;
+        p->batch.sample = nullptr;
     }
+    if ((st = side_after_main(ctx)) == NUPS_OK) {
+        switch (b->task) {
+        case NUPS_TASK_SGNS: st = plan_step_sgns(ctx, *p); break;
+        case NUPS_TASK_MF: st = plan_step_mf(ctx, *p); break;
+        default: st = plan_step_kge(ctx, *p); break;
+        }
+    }
+    if (st == NUPS_OK && hipEventRecord(p->ready, ctx->side) != hipSuccess)
+        st = fail(NUPS_ERR_DEVICE, "nups_prepare_step: event record failed");
+    if (st != NUPS_OK) { ctx->prepared_free.push_back(p); return st; }
+    p->live = true;
+    *out = p;
+    return NUPS_OK;
+}
+
+nups_status nups_step_prepared(nups_ctx *ctx, nups_prepared *p, double *loss_sum_host)
+{
+    if (!ctx || !p) return fail(NUPS_ERR_ARG, "nups_step_prepared: null argument");
+    if (p->ctx != ctx) return fail(NUPS_ERR_ARG, "nups_step_prepared: the step was prepared on another context");
+    if (!p->live) return fail(NUPS_ERR_STATE, "nups_step_prepared: the prepared step was already run");
+    NUPS_HIP(hipStreamWaitEvent(ctx->stream, p->ready, 0));
+    nups_status st;
+    switch (p->batch.task) {
+    case NUPS_TASK_SGNS: st = run_step_sgns(ctx, *p); break;
+    case NUPS_TASK_MF: st = run_step_mf(ctx, *p); break;
+    default: st = run_step_kge(ctx, *p); break;
+    }
+    retire_prepared(ctx, p);
     if (st != NUPS_OK) return st;
     if (loss_sum_host) {
         NUPS_HIP(hipMemcpyAsync(ctx->loss_pinned, ctx->loss_dev, sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
@@ -411,20 +514,29 @@ nups_status nups_step(nups_ctx *ctx, const nups_batch *b, double *loss_sum_host)
     return NUPS_OK;
 }
 
+nups_status nups_step(nups_ctx *ctx, const nups_batch *b, double *loss_sum_host)
+{
+    nups_prepared *p = nullptr;
+    nups_status st = nups_prepare_step(ctx, b, &p);
+    if (st != NUPS_OK) return st;
+    return nups_step_prepared(ctx, p, loss_sum_host);
+}
+
 nups_status nups_debug_structure(nups_ctx *ctx, int table, uint32_t *uniq_keys_dev, uint32_t *counts_dev,
                                  int64_t *n_uniq_host)
 {
     if (!valid_table(ctx, table) || !n_uniq_host) return fail(NUPS_ERR_ARG, "nups_debug_structure: bad arguments");
-    Plan &pl = ctx->tab[table].plan;
-    if (!pl.valid) return fail(NUPS_ERR_STATE, "nups_debug_structure: no step or push has run on this table");
+    const Plan *pl = ctx->tab[table].last_plan;
+    if (!pl) return fail(NUPS_ERR_STATE, "nups_debug_structure: no step or push has run on this table");
+    NUPS_HIP(hipStreamSynchronize(ctx->side));
     uint32_t meta[kMetaWords];
-    NUPS_HIP(hipMemcpyAsync(meta, pl.a.meta, sizeof(meta), hipMemcpyDeviceToHost, ctx->stream));
+    NUPS_HIP(hipMemcpyAsync(meta, pl->a.meta, sizeof(meta), hipMemcpyDeviceToHost, ctx->stream));
     NUPS_HIP(hipStreamSynchronize(ctx->stream));
     const size_t nu = meta[kMetaNumUniq];
     if (uniq_keys_dev)
-        NUPS_HIP(hipMemcpyAsync(uniq_keys_dev, pl.a.uniq, sizeof(uint32_t) * nu, hipMemcpyDeviceToDevice, ctx->stream));
+        NUPS_HIP(hipMemcpyAsync(uniq_keys_dev, pl->a.uniq, sizeof(uint32_t) * nu, hipMemcpyDeviceToDevice, ctx->stream));
     if (counts_dev)
-        NUPS_HIP(hipMemcpyAsync(counts_dev, pl.a.count, sizeof(uint32_t) * nu, hipMemcpyDeviceToDevice, ctx->stream));
+        NUPS_HIP(hipMemcpyAsync(counts_dev, pl->a.count, sizeof(uint32_t) * nu, hipMemcpyDeviceToDevice, ctx->stream));
     *n_uniq_host = (int64_t)nu;
     return sync_and_check(ctx);
 }
@@ -445,6 +557,7 @@ nups_status nups_profile(nups_ctx *ctx, int enable)
 nups_status nups_profile_read(nups_ctx *ctx, int phase, double *ms_total, int64_t *launches)
 {
     if (!ctx || phase < 0 || phase >= NUPS_PHASE_COUNT) return fail(NUPS_ERR_ARG, "nups_profile_read: bad arguments");
+    NUPS_HIP(hipStreamSynchronize(ctx->side));
     NUPS_HIP(hipStreamSynchronize(ctx->stream));
     Phase &ph = ctx->phase[phase];
     for (auto &pr : ph.pending) {

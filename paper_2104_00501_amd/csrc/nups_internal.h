@@ -18,11 +18,12 @@ constexpr int kMaxTables = 4;
 constexpr int kMaxStride = 1024;
 constexpr int kScanItems = 8;         // items per thread in the tile scans
 constexpr int kScanTile = kBlock * kScanItems;
-constexpr uint32_t kLongSegment = 48; // segments with more accesses are summed by a whole workgroup
+constexpr uint32_t kLongSegment = 48; // segments with more accesses are summed by whole workgroups, in chunks
+constexpr uint32_t kChunk = 256;      // accesses of a long segment that one workgroup sums
 constexpr uint32_t kBadIndex = 0xFFFFFFFFu;
 
 // meta words of a plan (device)
-enum { kMetaNumUniq = 0, kMetaNumLong = 1, kMetaTotal = 2, kMetaWords = 4 };
+enum { kMetaNumUniq = 0, kMetaNumChunks = 1, kMetaTotal = 2, kMetaWords = 4 };
 
 // Random streams of the counter-based generator.
 enum { kStreamFresh = 1, kStreamOrder = 2, kStreamLocal = 3, kStreamRoundKey = 4 };
@@ -51,26 +52,36 @@ struct PlanArgs {
     uint32_t words;        // bitmap words = ceil(V / 32)
     uint32_t bitmap_tiles; // ceil(words / kScanTile)
     uint32_t count_tiles;  // ceil(n / kScanTile)
-    uint32_t *bitmap;      // [words]     one bit per key, all zero between steps
+    uint32_t direct_bitmap; // 1: the bitmap scan counts the bits below its tile itself (no tile sums)
+    uint32_t direct_count;  // 1: the count scan sums the counts below its tile itself
+    // build scratch, owned by the table and shared by all plans of that table (builds run one after another)
+    uint32_t *bitmap;      // [words]     one bit per key, all zero between builds
     uint32_t *word_rank;   // [words]     number of distinct keys below each bitmap word
     uint32_t *tile_sum;    // [max(bitmap_tiles, count_tiles)]
+    uint32_t *slot;        // [n]         per access: index of its key among the distinct keys
+    uint32_t *rank;        // [n]         per access: position inside its key's segment
+    // result, owned by the plan
     uint32_t *uniq;        // [n]         distinct keys, ascending
     uint32_t *count;       // [n]         accesses per distinct key
     uint32_t *seg;         // [n + 1]     exclusive prefix sums of count
-    uint32_t *slot;        // [n]         per access: index of its key among the distinct keys
-    uint32_t *rank;        // [n]         per access: position inside its key's segment
     uint32_t *perm;        // [n]         accesses grouped by key
-    uint32_t *long_list;   // [n / kLongSegment + 1] distinct-key indices of long segments
+    uint32_t *chunk_seg;   // [max_chunks]  distinct-key index of the long segment a chunk belongs to
+    uint32_t *chunk_base;  // [max_chunks]  number of the first chunk of that segment
+    uint32_t *chunk_done;  // [max_chunks]  arrival counter per long segment (at its first chunk), zero between steps
     uint32_t *meta;        // [kMetaWords]
     uint32_t *error_flag;  // shared by the context: bit 0 = key out of range
 };
 
 struct Plan {
     PlanArgs a{};
-    size_t cap_n = 0;      // capacity (accesses) of the per-access arrays
-    size_t cap_words = 0;
-    size_t cap_tiles = 0;
-    bool valid = false;    // arrays describe the last build
+    size_t cap_n = 0;      // capacity (accesses) of the result arrays
+    int table = -1;
+};
+
+// Build scratch of one table.
+struct PlanScratch {
+    uint32_t *bitmap = nullptr, *word_rank = nullptr, *tile_sum = nullptr, *slot = nullptr, *rank = nullptr;
+    size_t cap_words = 0, cap_tiles = 0, cap_n = 0;
 };
 
 struct Table {
@@ -80,8 +91,8 @@ struct Table {
     int32_t dim = 0;
     int32_t stride = 0;
     std::vector<uint32_t> hot_keys;   // hottest first
-    uint32_t *hot_slot_dev = nullptr; // [num_keys] slot of a hot key, kBadIndex otherwise (built on demand)
-    Plan plan;
+    PlanScratch scratch;
+    Plan *last_plan = nullptr;        // structure of the last step / push on this table (owned by a prepared step)
 };
 
 struct Phase {
@@ -93,14 +104,28 @@ struct Phase {
 
 }  // namespace nups
 
+// A step whose aggregation structure is being (or has been) built on the side stream.
+struct nups_prepared {
+    nups_ctx *ctx = nullptr;
+    nups_batch batch{};
+    nups::Plan plan[2];
+    int n_plans = 0;
+    hipEvent_t ready = nullptr;    // recorded on the side stream after the build
+    bool live = false;             // prepared, not yet run
+    bool retired = false;          // run, still referenced by a table's structure query
+};
+
 struct nups_ctx {
     int n_tables = 0;
     nups::Table tab[nups::kMaxTables];
-    hipStream_t stream = nullptr;
+    hipStream_t stream = nullptr;   // the caller's stream: everything that touches table values
+    hipStream_t side = nullptr;     // library-owned: sampling and plan construction ("background" work)
+    hipEvent_t fork = nullptr;      // main -> side ordering at every prepare call
     int device = 0;
-    // step workspace
+    // step workspace (main stream only)
     float *coef = nullptr;      size_t coef_cap = 0;      // per (example, scored row) loss derivative
     float *stage = nullptr;     size_t stage_cap = 0;     // staged gradient rows
+    float *partial = nullptr;   size_t partial_cap = 0;   // partial sums of the chunks of long segments
     double *loss_dev = nullptr;                            // batch loss accumulator
     uint32_t *error_flag = nullptr;                        // device word
     double *loss_pinned = nullptr;                         // pinned host copies for read-back
@@ -108,6 +133,8 @@ struct nups_ctx {
     bool profiling = false;
     nups::Phase phase[NUPS_PHASE_COUNT];
     std::vector<nups_dist *> dists;
+    std::vector<nups_prepared *> prepared_all;   // every prepared-step object ever created (owned)
+    std::vector<nups_prepared *> prepared_free;  // run and no longer referenced by a structure query
 };
 
 struct nups_dist {
@@ -133,7 +160,7 @@ struct nups_dist {
 struct nups_sample {
     nups_dist *dist = nullptr;
     uint32_t *keys_dev = nullptr;   size_t cap = 0;
-    uint32_t *fresh_dev = nullptr;  size_t fresh_cap = 0;   // BOUNDED: the fresh draws of the handle
+    hipEvent_t ready = nullptr;     // recorded on the side stream after the keys are drawn
     int64_t n = 0;
     int64_t pulled = 0;
     bool live = false;
@@ -145,20 +172,27 @@ namespace nups {
 struct PhaseScope {
     nups_ctx *ctx;
     int phase;
+    hipStream_t stream;
     hipEvent_t start = nullptr;
-    PhaseScope(nups_ctx *c, int p);
+    PhaseScope(nups_ctx *c, int p, hipStream_t s);
     ~PhaseScope();
 };
 
 // kernels' host-side launchers (defined in the .hip files)
 nups_status launch_sample(nups_dist *d, nups_sample *h, uint64_t step);
-nups_status build_plans(nups_ctx *ctx, Plan **plans, int n_plans);
-nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, size_t n);
+nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n);
+nups_status build_plans(nups_ctx *ctx, Plan *plans, int n_plans);
+void free_plan_arrays(Plan &pl);
+void free_plan_scratch(PlanScratch &sc);
 nups_status launch_pull(nups_ctx *ctx, const Table &t, const uint32_t *keys, int64_t n, float *values);
-nups_status launch_push_apply(nups_ctx *ctx, Table &t, const float *updates);
-nups_status launch_step_sgns(nups_ctx *ctx, const nups_batch &b);
-nups_status launch_step_mf(nups_ctx *ctx, const nups_batch &b);
-nups_status launch_step_kge(nups_ctx *ctx, const nups_batch &b);
+nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, const float *updates);
+nups_status plan_step_sgns(nups_ctx *ctx, nups_prepared &p);
+nups_status plan_step_mf(nups_ctx *ctx, nups_prepared &p);
+nups_status plan_step_kge(nups_ctx *ctx, nups_prepared &p);
+nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p);
+nups_status run_step_mf(nups_ctx *ctx, nups_prepared &p);
+nups_status run_step_kge(nups_ctx *ctx, nups_prepared &p);
 nups_status ensure_f32(float **buf, size_t *cap, size_t need, hipStream_t stream);
+size_t max_chunks(size_t n);
 
 }  // namespace nups

@@ -34,9 +34,8 @@ __global__ void __launch_bounds__(kBlock) k_sample_fresh(DistArgs d, uint64_t st
 
 // Sample reuse: one workgroup emits one pass over one pool.  The order of the pass is the
 // ascending order of (first ORDER-stream word at (fresh id, pass), slot); rank by counting.
-__global__ void __launch_bounds__(kBlock) k_sample_pool_pass(DistArgs d, uint64_t step, const uint32_t *fresh,
-                                                             uint32_t F, uint32_t G, uint32_t U, uint32_t N,
-                                                             uint32_t *out)
+__global__ void __launch_bounds__(kBlock) k_sample_pool_pass(DistArgs d, uint64_t step, uint32_t F, uint32_t G,
+                                                             uint32_t U, uint32_t N, uint32_t *out)
 {
     __shared__ uint32_t word[1024];
     const uint32_t pool = blockIdx.x / U, pass = blockIdx.x % U;
@@ -56,7 +55,7 @@ __global__ void __launch_bounds__(kBlock) k_sample_pool_pass(DistArgs d, uint64_
             rank += (wj < w || (wj == w && j < i)) ? 1u : 0u;
         }
         const uint64_t pos = base + rank;
-        if (pos < N) out[pos] = fresh[first + i];
+        if (pos < N) out[pos] = fresh_key(d, step, first + i);   // every pass redraws the pool's keys itself
     }
 }
 
@@ -123,32 +122,30 @@ nups_status launch_sample(nups_dist *d, nups_sample *h, uint64_t step)
     nups_ctx *ctx = d->ctx;
     const uint32_t n = (uint32_t)h->n;
     if (n == 0) return NUPS_OK;
-    PhaseScope scope(ctx, NUPS_PHASE_SAMPLE);
+    PhaseScope scope(ctx, NUPS_PHASE_SAMPLE, ctx->side);
     DistArgs a{d->uniform ? nullptr : d->thresh_dev, d->alias_dev, (uint64_t)ctx->tab[d->table].num_keys, d->seed,
                d->id};
     const uint32_t blocks = (n + kBlock - 1) / kBlock;
     switch (d->scheme) {
     case NUPS_CONFORM:
-        hipLaunchKernelGGL(k_sample_fresh, dim3(blocks), dim3(kBlock), 0, ctx->stream, a, step, (uint64_t)0, n,
+        hipLaunchKernelGGL(k_sample_fresh, dim3(blocks), dim3(kBlock), 0, ctx->side, a, step, (uint64_t)0, n,
                            h->keys_dev);
         break;
     case NUPS_BOUNDED: {
         const uint32_t U = (uint32_t)d->U, G = (uint32_t)d->G;
         const uint32_t F = (n + U - 1) / U;
         const uint32_t pools = (F + G - 1) / G;
-        hipLaunchKernelGGL(k_sample_fresh, dim3((F + kBlock - 1) / kBlock), dim3(kBlock), 0, ctx->stream, a, step,
-                           (uint64_t)0, F, h->fresh_dev);
-        hipLaunchKernelGGL(k_sample_pool_pass, dim3(pools * U), dim3(kBlock), 0, ctx->stream, a, step,
-                           (const uint32_t *)h->fresh_dev, F, G, U, n, h->keys_dev);
+        hipLaunchKernelGGL(k_sample_pool_pass, dim3(pools * U), dim3(kBlock), 0, ctx->side, a, step, F, G, U, n,
+                           h->keys_dev);
         break;
     }
     case NUPS_LONGTERM:
-        hipLaunchKernelGGL(k_sample_longterm, dim3(blocks), dim3(kBlock), 0, ctx->stream, a, (uint64_t)d->P,
+        hipLaunchKernelGGL(k_sample_longterm, dim3(blocks), dim3(kBlock), 0, ctx->side, a, (uint64_t)d->P,
                            (uint32_t)d->R, d->cursor, n, feistel_half_bits((uint64_t)d->P), h->keys_dev);
         d->cursor += n;
         break;
     case NUPS_NONCONFORM:
-        hipLaunchKernelGGL(k_sample_local, dim3(blocks), dim3(kBlock), 0, ctx->stream, d->local_a, d->local_b,
+        hipLaunchKernelGGL(k_sample_local, dim3(blocks), dim3(kBlock), 0, ctx->side, d->local_a, d->local_b,
                            (uint32_t)d->local_n, (uint32_t)d->per_example, (uint32_t)d->split, (uint32_t)d->tile,
                            d->seed, d->id, step, n, h->keys_dev);
         break;

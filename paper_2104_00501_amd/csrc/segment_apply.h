@@ -2,9 +2,8 @@
 // contributions of its accesses and update the row once.  A contribution is a coefficient times
 // a source row (a staged gradient row, or a row of another table); the sum is kept in registers
 // by a 16-lane row group, so each touched row is read once and written once.
-// Short segments take one row group each; long segments (the hot keys of Section 3.2) take a
-// whole workgroup whose 16 groups sum interleaved slices that are then combined in LDS in a
-// fixed order.
+// Short segments take one row group each; long segments (the hot keys of Section 3.2) are cut into
+// chunks, one workgroup per chunk, whose partial rows are combined in a fixed order.
 #pragma once
 
 #include "device_utils.h"
@@ -111,8 +110,11 @@ struct OptAdagrad {      // G <- G + delta^2 ; theta <- theta - lr * delta / (sq
 struct ApplyArgs {
     float *table;
     float *state;
-    const uint32_t *uniq, *seg, *perm, *meta, *long_list;
+    const uint32_t *uniq, *seg, *perm, *meta, *chunk_seg, *chunk_base;
+    uint32_t *chunk_done;
+    float *partial;        // [max_chunks][stride] partial sums of chunked segments
     int stride;
+    uint32_t short_blocks; // workgroups [0, short_blocks) take short segments, the others one chunk each
 };
 
 // Sums accesses first, first+step, ... < last of a segment into acc (four row loads in flight).
@@ -142,34 +144,37 @@ __device__ __forceinline__ void sum_segment(Row<NV4> &acc, const Src &src, const
     }
 }
 
-// One 16-lane group per distinct key with at most kLongSegment accesses.
+// Workgroups below a.short_blocks: one 16-lane group per distinct key with at most kLongSegment accesses.
+// The other workgroups: one chunk (kChunk accesses) of a long segment each; the 16 groups sum interleaved
+// slices, the slices are combined through LDS in group order, and the workgroup that finishes a segment's
+// last outstanding chunk adds the chunks' partial rows in chunk order and updates the row.
 template <int NV4, class Src, class Opt>
-__global__ void __launch_bounds__(kBlock) k_apply_short(ApplyArgs a, Src src, Opt opt)
-{
-    const int lane = threadIdx.x & (kGroup - 1);
-    const uint32_t u = (blockIdx.x * kBlock + threadIdx.x) / kGroup;
-    if (u >= a.meta[kMetaNumUniq]) return;
-    const uint32_t first = a.seg[u], last = a.seg[u + 1];
-    if (last - first > kLongSegment) return;
-    Row<NV4> acc;
-    zero_row(acc);
-    sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
-    const size_t off = (size_t)a.uniq[u] * a.stride;
-    opt.template apply<NV4>(a.table + off, a.state ? a.state + off : nullptr, acc, lane);
-}
-
-// One workgroup per long segment.
-template <int NV4, class Src, class Opt>
-__global__ void __launch_bounds__(kBlock) k_apply_long(ApplyArgs a, Src src, Opt opt)
+__global__ void __launch_bounds__(kBlock) k_apply(ApplyArgs a, Src src, Opt opt)
 {
     extern __shared__ float part[];   // [kGroupsPerBlock - 1][stride]
-    if (blockIdx.x >= a.meta[kMetaNumLong]) return;
+    __shared__ uint32_t last_arrival;
     const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
-    const uint32_t u = a.long_list[blockIdx.x];
+    if (blockIdx.x < a.short_blocks) {
+        const uint32_t u = blockIdx.x * kGroupsPerBlock + group;
+        if (u >= a.meta[kMetaNumUniq]) return;
+        const uint32_t first = a.seg[u], last = a.seg[u + 1];
+        if (last - first > kLongSegment) return;
+        Row<NV4> acc;
+        zero_row(acc);
+        sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
+        const size_t off = (size_t)a.uniq[u] * a.stride;
+        opt.template apply<NV4>(a.table + off, a.state ? a.state + off : nullptr, acc, lane);
+        return;
+    }
+    const uint32_t id = blockIdx.x - a.short_blocks;
+    if (id >= a.meta[kMetaNumChunks]) return;
+    const uint32_t u = a.chunk_seg[id], base = a.chunk_base[id];
     const uint32_t first = a.seg[u], last = a.seg[u + 1];
+    const uint32_t nch = (last - first + kChunk - 1) / kChunk;
+    const uint32_t cf = first + (id - base) * kChunk, cl = min(cf + kChunk, last);
     Row<NV4> acc;
     zero_row(acc);
-    sum_segment<NV4>(acc, src, a.perm, first + group, last, kGroupsPerBlock, a.stride, lane);
+    sum_segment<NV4>(acc, src, a.perm, cf + group, cl, kGroupsPerBlock, a.stride, lane);
     if (group > 0) store_row(part + (size_t)(group - 1) * a.stride, acc, lane);
     __syncthreads();
     if (group == 0) {
@@ -178,42 +183,61 @@ __global__ void __launch_bounds__(kBlock) k_apply_long(ApplyArgs a, Src src, Opt
             load_row(r, part + (size_t)(g - 1) * a.stride, lane);
             axpy_row(acc, 1.0f, r);
         }
+        if (nch > 1) {
+            store_row(a.partial + (size_t)id * a.stride, acc, lane);
+            __threadfence();          // the partial row is visible before the arrival is counted
+        }
+    }
+    if (nch > 1) {
+        __syncthreads();
+        if (threadIdx.x == 0) last_arrival = (atomicAdd(&a.chunk_done[base], 1u) == nch - 1) ? 1u : 0u;
+        __syncthreads();
+        if (!last_arrival) return;
+        __threadfence();              // the other chunks' partial rows are visible after their arrivals
+        if (group == 0) {
+            zero_row(acc);
+            for (uint32_t ch = 0; ch < nch; ++ch) {
+                Row<NV4> r;
+                load_row(r, a.partial + (size_t)(base + ch) * a.stride, lane);
+                axpy_row(acc, 1.0f, r);
+            }
+        }
+        if (threadIdx.x == 0) a.chunk_done[base] = 0u;   // ready for the next step
+    }
+    if (group == 0) {
         const size_t off = (size_t)a.uniq[u] * a.stride;
         opt.template apply<NV4>(a.table + off, a.state ? a.state + off : nullptr, acc, lane);
     }
 }
 
 template <int NV4, class Src, class Opt>
-static void launch_apply_nv(hipStream_t s, const Plan &pl, float *table, float *state, int stride, const Src &src,
-                            const Opt &opt)
+static void launch_apply_nv(hipStream_t s, const Plan &pl, float *partial, float *table, float *state, int stride,
+                            const Src &src, const Opt &opt)
 {
     const PlanArgs &p = pl.a;
     if (p.n == 0) return;
-    ApplyArgs a{table, state, p.uniq, p.seg, p.perm, p.meta, p.long_list, stride};
-    const uint32_t groups = p.n;                       // upper bound of the number of distinct keys
-    const uint32_t blocks = (groups + kGroupsPerBlock - 1) / kGroupsPerBlock;
-    hipLaunchKernelGGL((k_apply_short<NV4, Src, Opt>), dim3(blocks), dim3(kBlock), 0, s, a, src, opt);
-    const uint32_t max_long = p.n / (kLongSegment + 1);
-    if (max_long > 0) {
-        const size_t lds = sizeof(float) * (size_t)(kGroupsPerBlock - 1) * stride;
-        hipLaunchKernelGGL((k_apply_long<NV4, Src, Opt>), dim3(max_long), dim3(kBlock), lds, s, a, src, opt);
-    }
+    const uint32_t short_blocks = (p.n + kGroupsPerBlock - 1) / kGroupsPerBlock;   // n bounds the distinct keys
+    const uint32_t chunk_blocks = (uint32_t)(p.n / kChunk + p.n / (kLongSegment + 1) + 1);
+    ApplyArgs a{table, state, p.uniq, p.seg, p.perm, p.meta, p.chunk_seg, p.chunk_base, p.chunk_done, partial,
+                stride, short_blocks};
+    const size_t lds = sizeof(float) * (size_t)(kGroupsPerBlock - 1) * stride;
+    hipLaunchKernelGGL((k_apply<NV4, Src, Opt>), dim3(short_blocks + chunk_blocks), dim3(kBlock), lds, s, a, src, opt);
 }
 
 // Dispatch on the row length (stride / 64 float4 per lane).
 template <class Src, class Opt>
-static nups_status launch_apply(hipStream_t s, const Plan &pl, float *table, float *state, int stride,
-                                const Src &src, const Opt &opt)
+static nups_status launch_apply(hipStream_t s, const Plan &pl, float *partial, float *table, float *state,
+                                int stride, const Src &src, const Opt &opt)
 {
     switch (stride / 64) {
-    case 1: launch_apply_nv<1>(s, pl, table, state, stride, src, opt); break;
-    case 2: launch_apply_nv<2>(s, pl, table, state, stride, src, opt); break;
-    case 3: launch_apply_nv<3>(s, pl, table, state, stride, src, opt); break;
-    case 4: launch_apply_nv<4>(s, pl, table, state, stride, src, opt); break;
-    case 5: launch_apply_nv<5>(s, pl, table, state, stride, src, opt); break;
-    case 6: launch_apply_nv<6>(s, pl, table, state, stride, src, opt); break;
-    case 8: launch_apply_nv<8>(s, pl, table, state, stride, src, opt); break;
-    case 16: launch_apply_nv<16>(s, pl, table, state, stride, src, opt); break;
+    case 1: launch_apply_nv<1>(s, pl, partial, table, state, stride, src, opt); break;
+    case 2: launch_apply_nv<2>(s, pl, partial, table, state, stride, src, opt); break;
+    case 3: launch_apply_nv<3>(s, pl, partial, table, state, stride, src, opt); break;
+    case 4: launch_apply_nv<4>(s, pl, partial, table, state, stride, src, opt); break;
+    case 5: launch_apply_nv<5>(s, pl, partial, table, state, stride, src, opt); break;
+    case 6: launch_apply_nv<6>(s, pl, partial, table, state, stride, src, opt); break;
+    case 8: launch_apply_nv<8>(s, pl, partial, table, state, stride, src, opt); break;
+    case 16: launch_apply_nv<16>(s, pl, partial, table, state, stride, src, opt); break;
     default: return fail(NUPS_ERR_UNIMPLEMENTED, "row_stride must be 64, 128, 192, 256, 320, 384, 512 or 1024 floats");
     }
     NUPS_HIP(hipGetLastError());

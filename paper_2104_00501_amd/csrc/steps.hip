@@ -28,7 +28,7 @@ __global__ void __launch_bounds__(kBlock) k_pull(const float *table, uint32_t nu
 nups_status launch_pull(nups_ctx *ctx, const Table &t, const uint32_t *keys, int64_t n, float *values)
 {
     if (n == 0) return NUPS_OK;
-    PhaseScope scope(ctx, NUPS_PHASE_PULL);
+    PhaseScope scope(ctx, NUPS_PHASE_PULL, ctx->stream);
     const int stride4 = t.stride / 4;
     const uint64_t total4 = (uint64_t)n * stride4;
     const uint64_t blocks = (total4 + kBlock - 1) / kBlock;
@@ -40,10 +40,10 @@ nups_status launch_pull(nups_ctx *ctx, const Table &t, const uint32_t *keys, int
 }
 
 // push: table[k] += sum of the update rows sent for k (plan already built over the keys).
-nups_status launch_push_apply(nups_ctx *ctx, Table &t, const float *updates)
+nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, const float *updates)
 {
-    PhaseScope scope(ctx, NUPS_PHASE_PUSH);
-    return launch_apply(ctx->stream, t.plan, t.data, nullptr, t.stride, SrcStaged{updates}, OptAdd{});
+    PhaseScope scope(ctx, NUPS_PHASE_PUSH, ctx->stream);
+    return launch_apply(ctx->stream, pl, ctx->partial, t.data, nullptr, t.stride, SrcStaged{updates}, OptAdd{});
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -122,40 +122,59 @@ static nups_status zero_loss(nups_ctx *ctx)
     return NUPS_OK;
 }
 
-nups_status launch_step_sgns(nups_ctx *ctx, const nups_batch &b)
+// Plan side of a step: which keys each table is accessed with (plan 0: table 0, plan 1: table 1).
+static nups_status plan_two_tables(nups_ctx *ctx, nups_prepared &p, const KeySource &s0, uint32_t n0,
+                                   const KeySource &s1, uint32_t n1)
 {
+    nups_status st;
+    p.n_plans = 2;
+    p.plan[0].table = 0;
+    p.plan[1].table = 1;
+    if ((st = ensure_plan_capacity(ctx, ctx->tab[0], p.plan[0], n0)) != NUPS_OK) return st;
+    if ((st = ensure_plan_capacity(ctx, ctx->tab[1], p.plan[1], n1)) != NUPS_OK) return st;
+    p.plan[0].a.src = s0;
+    p.plan[0].a.n = n0;
+    p.plan[1].a.src = s1;
+    p.plan[1].a.n = n1;
+    return build_plans(ctx, p.plan, 2);
+}
+
+nups_status plan_step_sgns(nups_ctx *ctx, nups_prepared &p)
+{
+    const nups_batch &b = p.batch;
+    const uint32_t B = (uint32_t)b.B, K = (uint32_t)b.n_neg;
+    return plan_two_tables(ctx, p, KeySource{{b.k0, nullptr, nullptr}, {B, 0, 0}}, B,
+                           KeySource{{b.k1, b.negs, nullptr}, {B, B * K, 0}}, B * (K + 1));
+}
+
+nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
+{
+    const nups_batch &b = p.batch;
     Table &tin = ctx->tab[0], &tout = ctx->tab[1];
     const uint32_t B = (uint32_t)b.B, K = (uint32_t)b.n_neg;
     nups_status st;
     if ((st = ensure_f32(&ctx->coef, &ctx->coef_cap, (size_t)B * (K + 1), ctx->stream)) != NUPS_OK) return st;
     if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)B * tin.stride, ctx->stream)) != NUPS_OK) return st;
-    if ((st = ensure_plan_capacity(ctx, tin, B)) != NUPS_OK) return st;
-    if ((st = ensure_plan_capacity(ctx, tout, (size_t)B * (K + 1))) != NUPS_OK) return st;
     if ((st = zero_loss(ctx)) != NUPS_OK) return st;
-    tin.plan.a.src = KeySource{{b.k0, nullptr, nullptr}, {B, 0, 0}};
-    tin.plan.a.n = B;
-    tout.plan.a.src = KeySource{{b.k1, b.negs, nullptr}, {B, B * K, 0}};
-    tout.plan.a.n = B * (K + 1);
-    Plan *plans[2] = {&tin.plan, &tout.plan};
-    if ((st = build_plans(ctx, plans, 2)) != NUPS_OK) return st;
     if (B == 0) return NUPS_OK;
     {
-        PhaseScope scope(ctx, NUPS_PHASE_GRAD);
+        PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
 #define CALL(N) launch_sgns_grad<N>(ctx, b)
         NUPS_DISPATCH_STRIDE(tin.stride, CALL)
 #undef CALL
         NUPS_HIP(hipGetLastError());
     }
     {   // output side first: it reads the input vectors, which must still be the step's snapshot
-        PhaseScope scope(ctx, NUPS_PHASE_APPLY1);
+        PhaseScope scope(ctx, NUPS_PHASE_APPLY1, ctx->stream);
         SrcSgnsOut src{tin.data, b.k0, ctx->coef, B, K, (uint32_t)tin.num_keys};
-        if ((st = launch_apply(ctx->stream, tout.plan, tout.data, nullptr, tout.stride, src, OptSgd{b.lr})) != NUPS_OK)
+        if ((st = launch_apply(ctx->stream, p.plan[1], ctx->partial, tout.data, nullptr, tout.stride, src,
+                               OptSgd{b.lr})) != NUPS_OK)
             return st;
     }
     {
-        PhaseScope scope(ctx, NUPS_PHASE_APPLY0);
-        if ((st = launch_apply(ctx->stream, tin.plan, tin.data, nullptr, tin.stride, SrcStaged{ctx->stage},
-                               OptSgd{b.lr})) != NUPS_OK)
+        PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
+        if ((st = launch_apply(ctx->stream, p.plan[0], ctx->partial, tin.data, nullptr, tin.stride,
+                               SrcStaged{ctx->stage}, OptSgd{b.lr})) != NUPS_OK)
             return st;
     }
     return NUPS_OK;
@@ -208,38 +227,39 @@ static void launch_mf_grad(nups_ctx *ctx, const nups_batch &b)
                        b.val, (uint32_t)b.B, b.l2, ctx->stage, ctx->loss_dev);
 }
 
-nups_status launch_step_mf(nups_ctx *ctx, const nups_batch &b)
+nups_status plan_step_mf(nups_ctx *ctx, nups_prepared &p)
 {
+    const nups_batch &b = p.batch;
+    const uint32_t B = (uint32_t)b.B;
+    return plan_two_tables(ctx, p, KeySource{{b.k0, nullptr, nullptr}, {B, 0, 0}}, B,
+                           KeySource{{b.k1, nullptr, nullptr}, {B, 0, 0}}, B);
+}
+
+nups_status run_step_mf(nups_ctx *ctx, nups_prepared &p)
+{
+    const nups_batch &b = p.batch;
     Table &tw = ctx->tab[0], &th = ctx->tab[1];
     const uint32_t B = (uint32_t)b.B;
     nups_status st;
     if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)2 * B * tw.stride, ctx->stream)) != NUPS_OK) return st;
-    if ((st = ensure_plan_capacity(ctx, tw, B)) != NUPS_OK) return st;
-    if ((st = ensure_plan_capacity(ctx, th, B)) != NUPS_OK) return st;
     if ((st = zero_loss(ctx)) != NUPS_OK) return st;
-    tw.plan.a.src = KeySource{{b.k0, nullptr, nullptr}, {B, 0, 0}};
-    tw.plan.a.n = B;
-    th.plan.a.src = KeySource{{b.k1, nullptr, nullptr}, {B, 0, 0}};
-    th.plan.a.n = B;
-    Plan *plans[2] = {&tw.plan, &th.plan};
-    if ((st = build_plans(ctx, plans, 2)) != NUPS_OK) return st;
     if (B == 0) return NUPS_OK;
     {
-        PhaseScope scope(ctx, NUPS_PHASE_GRAD);
+        PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
 #define CALL(N) launch_mf_grad<N>(ctx, b)
         NUPS_DISPATCH_STRIDE(tw.stride, CALL)
 #undef CALL
         NUPS_HIP(hipGetLastError());
     }
     {
-        PhaseScope scope(ctx, NUPS_PHASE_APPLY0);
-        if ((st = launch_apply(ctx->stream, tw.plan, tw.data, nullptr, tw.stride, SrcStaged{ctx->stage},
-                               OptSgd{b.lr})) != NUPS_OK)
+        PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
+        if ((st = launch_apply(ctx->stream, p.plan[0], ctx->partial, tw.data, nullptr, tw.stride,
+                               SrcStaged{ctx->stage}, OptSgd{b.lr})) != NUPS_OK)
             return st;
     }
     {
-        PhaseScope scope(ctx, NUPS_PHASE_APPLY1);
-        if ((st = launch_apply(ctx->stream, th.plan, th.data, nullptr, th.stride,
+        PhaseScope scope(ctx, NUPS_PHASE_APPLY1, ctx->stream);
+        if ((st = launch_apply(ctx->stream, p.plan[1], ctx->partial, th.data, nullptr, th.stride,
                                SrcStaged{ctx->stage + (size_t)B * tw.stride}, OptSgd{b.lr})) != NUPS_OK)
             return st;
     }
@@ -406,27 +426,28 @@ static void launch_kge_grad(nups_ctx *ctx, const nups_batch &b)
                        b.k2, b.negs, (uint32_t)b.B, (int)b.n_neg, (int)b.n_neg2, ctx->coef, ctx->stage, ctx->loss_dev);
 }
 
-nups_status launch_step_kge(nups_ctx *ctx, const nups_batch &b)
+nups_status plan_step_kge(nups_ctx *ctx, nups_prepared &p)
 {
+    const nups_batch &b = p.batch;
+    const uint32_t B = (uint32_t)b.B, nn = (uint32_t)(b.n_neg + b.n_neg2);
+    if (ctx->tab[0].stride % 128 != 0 || ctx->tab[0].stride > 512)
+        return fail(NUPS_ERR_UNIMPLEMENTED, "KGE tables need a row_stride of 128, 256, 384 or 512 floats");
+    return plan_two_tables(ctx, p, KeySource{{b.k0, b.k2, b.negs}, {B, B, B * nn}}, B * (2 + nn),
+                           KeySource{{b.k1, nullptr, nullptr}, {B, 0, 0}}, B);
+}
+
+nups_status run_step_kge(nups_ctx *ctx, nups_prepared &p)
+{
+    const nups_batch &b = p.batch;
     Table &te = ctx->tab[0], &tr = ctx->tab[1];
     const uint32_t B = (uint32_t)b.B, nh = (uint32_t)b.n_neg, nn = (uint32_t)(b.n_neg + b.n_neg2);
-    if (te.stride % 128 != 0 || te.stride > 512)
-        return fail(NUPS_ERR_UNIMPLEMENTED, "KGE tables need a row_stride of 128, 256, 384 or 512 floats");
     nups_status st;
     if ((st = ensure_f32(&ctx->coef, &ctx->coef_cap, (size_t)B * nn + 1, ctx->stream)) != NUPS_OK) return st;
     if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)5 * B * te.stride, ctx->stream)) != NUPS_OK) return st;
-    if ((st = ensure_plan_capacity(ctx, te, (size_t)B * (2 + nn))) != NUPS_OK) return st;
-    if ((st = ensure_plan_capacity(ctx, tr, B)) != NUPS_OK) return st;
     if ((st = zero_loss(ctx)) != NUPS_OK) return st;
-    te.plan.a.src = KeySource{{b.k0, b.k2, b.negs}, {B, B, B * nn}};
-    te.plan.a.n = B * (2 + nn);
-    tr.plan.a.src = KeySource{{b.k1, nullptr, nullptr}, {B, 0, 0}};
-    tr.plan.a.n = B;
-    Plan *plans[2] = {&te.plan, &tr.plan};
-    if ((st = build_plans(ctx, plans, 2)) != NUPS_OK) return st;
     if (B == 0) return NUPS_OK;
     {
-        PhaseScope scope(ctx, NUPS_PHASE_GRAD);
+        PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
         switch (te.stride / 64) {
         case 2: launch_kge_grad<2>(ctx, b); break;
         case 4: launch_kge_grad<4>(ctx, b); break;
@@ -437,15 +458,15 @@ nups_status launch_step_kge(nups_ctx *ctx, const nups_batch &b)
         NUPS_HIP(hipGetLastError());
     }
     {
-        PhaseScope scope(ctx, NUPS_PHASE_APPLY0);
+        PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
         SrcKgeEntity src{ctx->stage, ctx->coef, B, nn, nh};
-        if ((st = launch_apply(ctx->stream, te.plan, te.data, te.state, te.stride, src,
+        if ((st = launch_apply(ctx->stream, p.plan[0], ctx->partial, te.data, te.state, te.stride, src,
                                OptAdagrad{b.lr, b.eps})) != NUPS_OK)
             return st;
     }
     {
-        PhaseScope scope(ctx, NUPS_PHASE_APPLY1);
-        if ((st = launch_apply(ctx->stream, tr.plan, tr.data, tr.state, tr.stride,
+        PhaseScope scope(ctx, NUPS_PHASE_APPLY1, ctx->stream);
+        if ((st = launch_apply(ctx->stream, p.plan[1], ctx->partial, tr.data, tr.state, tr.stride,
                                SrcStaged{ctx->stage + (size_t)4 * B * te.stride}, OptAdagrad{b.lr, b.eps})) != NUPS_OK)
             return st;
     }

@@ -276,3 +276,45 @@ def test_kge_needs_state():
         nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_KGE, 1, k, k, k2=k, lr=0.1, eps=1e-10))
     assert e.value.status == nb.NUPS_ERR_STATE
     nb.nups_destroy(ctx)
+
+
+def test_sgns_pipelined_steps_match_the_oracle():
+    # step t+1 is prepared (samples drawn, aggregation structure built on the side stream) before step t runs
+    V, d, B, K, window, steps, lr = 30_000, 300, 2048, 3, 5, 12, 0.002
+    toks = wl.zipf_stream(V, 1.0, steps * B // (2 * window) + 2 * window + 8, 21)
+    In, Out = wl.sgns_tables(V, d, 21)
+    Out[:] = wl.uniform_table(V, d, -0.5 / d, 0.5 / d, 22)
+    w = wl.unigram_weights(toks, V)
+    tin, tout = dev(In), dev(Out)
+    ctx = nb.nups_init([tin, tout], [d, d])
+    dist = nb.nups_register_distribution(ctx, 1, w, nb.NUPS_BOUNDED, U=4, G=250, seed=21)
+    pairs = [wl.window_pairs(toks, window, t * B, B) for t in range(steps)]
+    dev_pairs = [(dev_u32(c), dev_u32(o)) for c, o in pairs]
+
+    def prepare(t):
+        h = nb.nups_prepare_sample(dist, B * K, t)
+        b = nb.make_batch(nb.NUPS_TASK_SGNS, B, dev_pairs[t][0], dev_pairs[t][1], n_neg=K, lr=lr, sample=h)
+        return h, nb.nups_prepare_step(ctx, b)
+
+    nxt = prepare(0)
+    for t in range(steps):
+        h, p = nxt
+        if t + 1 < steps:
+            nxt = prepare(t + 1)
+        nb.nups_step_prepared(ctx, p)
+        nb.nups_release_sample(h)
+    with pytest.raises(nb.NupsError) as e:
+        nb.nups_step_prepared(ctx, p)                    # a prepared step runs once
+    assert e.value.status == nb.NUPS_ERR_STATE
+    nb.nups_check(ctx)
+    alias = orc.alias_build(w)
+    rin, rout = In.copy(), Out.copy()
+    for t in range(steps):
+        negs = orc.sample_bounded(alias, V, 21, 0, t, B * K, 4, 250)
+        _, s_in, s_out = orc.step_sgns(rin, rout, d, pairs[t][0], pairs[t][1], negs, K, lr)
+    _assert_structure(ctx, 0, B, s_in)                   # the structure query describes the last step that ran
+    _assert_structure(ctx, 1, B * (K + 1), s_out)
+    cols = list(range(d))
+    _assert_close(tin.cpu().numpy(), rin, cols, 1e-4, "input table after 12 pipelined steps")
+    _assert_close(tout.cpu().numpy(), rout, cols, 1e-4, "output table after 12 pipelined steps")
+    nb.nups_destroy(ctx)
