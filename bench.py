@@ -82,21 +82,19 @@ def main() -> int:
     lrs = [float(wl.linear_lr(cfg["lr0"], t, epoch_steps)) for t in range(total_steps)]
 
     def prepare(t):
-        """PrepareSample + the key-only half of the step, both on the library's side stream."""
-        h = nb.nups_prepare_sample(dist, B * K, t)
+        """The key-only half of step t on the library's side stream: draw the negatives, build the plan."""
         batch = nb.make_batch(nb.NUPS_TASK_SGNS, B, kc.data_ptr() + 4 * t * B, ko.data_ptr() + 4 * t * B,
-                              n_neg=K, lr=lrs[t], sample=h)
-        return h, nb.nups_prepare_step(ctx, batch)
+                              n_neg=K, lr=lrs[t], dist=dist, sample_step=t)
+        return nb.nups_prepare_step(ctx, batch)
 
     def run(first, count):
         # software pipeline: step t+1 is prepared before step t runs, so the two overlap on the GPU
         nxt = prepare(first)
         for t in range(first, first + count):
-            h, p = nxt
+            p = nxt
             if t + 1 < first + count:
                 nxt = prepare(t + 1)
             nb.nups_step_prepared(ctx, p)
-            nb.nups_release_sample(h)
 
     # ---- warm-up, then the timed region ---------------------------------------------------------
     run(0, args.warmup)

@@ -177,6 +177,10 @@ typedef struct {
     nups_sample *sample;   /* alternatively: the handle whose N >= B * (n_neg + n_neg2) keys are the
                               negatives (no wait is put on the caller's stream; the step orders itself
                               after the drawing).  NULL if `negs` is given or there are none.       */
+    nups_dist *dist;       /* alternatively: the step draws its own B * (n_neg + n_neg2) negatives from
+                              this distribution as PrepareSample(dist, N) for step `sample_step` would
+                              (same keys), without a handle.  NULL otherwise.                       */
+    uint64_t sample_step;  /* step number of that drawing (ignored unless `dist` is given)        */
 } nups_batch;
 
 /*

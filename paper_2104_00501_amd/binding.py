@@ -38,7 +38,8 @@ class NupsError(RuntimeError):
 class nups_batch(C.Structure):
     _fields_ = [("task", C.c_int32), ("B", C.c_int64), ("k0", C.c_void_p), ("k1", C.c_void_p), ("k2", C.c_void_p),
                 ("val", C.c_void_p), ("n_neg", C.c_int32), ("n_neg2", C.c_int32), ("lr", C.c_float),
-                ("l2", C.c_float), ("eps", C.c_float), ("negs", C.c_void_p), ("sample", C.c_void_p)]
+                ("l2", C.c_float), ("eps", C.c_float), ("negs", C.c_void_p), ("sample", C.c_void_p),
+                ("dist", C.c_void_p), ("sample_step", C.c_uint64)]
 
 
 _lib = None
@@ -174,12 +175,15 @@ def nups_release_sample(handle):
     _check(lib().nups_release_sample(handle))
 
 
-def make_batch(task, B, k0, k1, k2=None, val=None, n_neg=0, n_neg2=0, lr=0.0, l2=0.0, eps=0.0, negs=None, sample=None):
+def make_batch(task, B, k0, k1, k2=None, val=None, n_neg=0, n_neg2=0, lr=0.0, l2=0.0, eps=0.0, negs=None, sample=None,
+               dist=None, sample_step=0):
     b = nups_batch()
     b.task, b.B = task, B
     b.k0, b.k1, b.k2, b.val, b.negs = (_ptr(x).value for x in (k0, k1, k2, val, negs))
     b.n_neg, b.n_neg2, b.lr, b.l2, b.eps = n_neg, n_neg2, lr, l2, eps
     b.sample = sample.value if hasattr(sample, "value") else sample
+    b.dist = dist.value if hasattr(dist, "value") else dist
+    b.sample_step = sample_step
     return b
 
 

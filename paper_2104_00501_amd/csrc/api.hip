@@ -79,6 +79,8 @@ static void free_prepared(nups_prepared *p)
     free_plan_arrays(p->plan[0]);
     free_plan_arrays(p->plan[1]);
     if (p->ready) (void)hipEventDestroy(p->ready);
+    if (p->loss_dev) (void)hipFree(p->loss_dev);
+    if (p->negs_buf) (void)hipFree(p->negs_buf);
     delete p;
 }
 
@@ -124,6 +126,8 @@ static nups_status get_prepared(nups_ctx *ctx, nups_prepared **out)
         ctx->prepared_all.push_back(p);
     }
     nups_status st = new_event(&p->ready);
+    if (st == NUPS_OK && !p->loss_dev && !hip_ok(hipMalloc((void **)&p->loss_dev, sizeof(double)), "loss accumulator"))
+        st = NUPS_ERR_DEVICE;
     if (st != NUPS_OK) { ctx->prepared_free.push_back(p); return st; }
     *out = p;
     return NUPS_OK;
@@ -157,8 +161,17 @@ static nups_status check_batch(nups_ctx *ctx, const nups_batch *b)
     if (b->B * (nn + 2) > 0x7FFFFFFFll) return fail(NUPS_ERR_ARG, "nups_step: too many accesses for one step");
     if (ctx->tab[0].stride != ctx->tab[1].stride)
         return fail(NUPS_ERR_ARG, "nups_step: tables 0 and 1 need equal row_stride");
+    if ((b->sample != nullptr) + (b->negs != nullptr) + (b->dist != nullptr) > 1)
+        return fail(NUPS_ERR_ARG, "nups_step: give only one of negs, sample and dist");
+    if (b->dist) {
+        if (b->dist->ctx != ctx) return fail(NUPS_ERR_ARG, "nups_step: the distribution is of another context");
+        if (b->dist->scheme == NUPS_NONCONFORM && !b->dist->local_a)
+            return fail(NUPS_ERR_STATE, "nups_step: call nups_set_local_keys first");
+        if (b->dist->scheme == NUPS_NONCONFORM && b->B * nn > b->dist->local_n * (int64_t)b->dist->per_example)
+            return fail(NUPS_ERR_ARG, "nups_step: more samples than examples * per_example");
+        if (b->sample_step >> 48) return fail(NUPS_ERR_ARG, "nups_step: sample_step must be below 2^48");
+    }
     if (b->sample) {
-        if (b->negs) return fail(NUPS_ERR_ARG, "nups_step: give either negs or sample, not both");
         if (!b->sample->live) return fail(NUPS_ERR_STATE, "nups_step: the sample handle was released");
         if (b->sample->dist->ctx != ctx) return fail(NUPS_ERR_ARG, "nups_step: the sample handle is of another context");
         if (b->sample->n < b->B * nn) return fail(NUPS_ERR_ARG, "nups_step: the sample handle holds too few keys");
@@ -166,7 +179,7 @@ static nups_status check_batch(nups_ctx *ctx, const nups_batch *b)
     switch (b->task) {
     case NUPS_TASK_SGNS:
         if (b->n_neg2 != 0) return fail(NUPS_ERR_ARG, "nups_step: SGNS uses n_neg only");
-        if (b->B > 0 && b->n_neg > 0 && !b->negs && !b->sample) return fail(NUPS_ERR_ARG, "nups_step: null negatives");
+        if (b->B > 0 && b->n_neg > 0 && !b->negs && !b->sample && !b->dist) return fail(NUPS_ERR_ARG, "nups_step: null negatives");
         break;
     case NUPS_TASK_MF:
         if (b->B > 0 && !b->val) return fail(NUPS_ERR_ARG, "nups_step: null cell values");
@@ -174,7 +187,7 @@ static nups_status check_batch(nups_ctx *ctx, const nups_batch *b)
         break;
     case NUPS_TASK_KGE:
         if (b->B > 0 && !b->k2) return fail(NUPS_ERR_ARG, "nups_step: null object keys");
-        if (b->B > 0 && nn > 0 && !b->negs && !b->sample) return fail(NUPS_ERR_ARG, "nups_step: null negatives");
+        if (b->B > 0 && nn > 0 && !b->negs && !b->sample && !b->dist) return fail(NUPS_ERR_ARG, "nups_step: null negatives");
         if (!ctx->tab[0].state || !ctx->tab[1].state)
             return fail(NUPS_ERR_STATE, "nups_step: KGE needs AdaGrad state on tables 0 and 1 (nups_set_state)");
         break;
@@ -226,12 +239,10 @@ nups_status nups_init(nups_ctx **out, int n_tables, float *const *tables_dev, co
     }
     hipError_t e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);   // default priority
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipMalloc((void **)&ctx->loss_dev, sizeof(double));
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->error_flag, sizeof(uint32_t));
     if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->loss_pinned, sizeof(double), hipHostMallocDefault);
     if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->flag_pinned, sizeof(uint32_t), hipHostMallocDefault);
     if (e == hipSuccess) e = hipMemsetAsync(ctx->error_flag, 0, sizeof(uint32_t), ctx->stream);
-    if (e == hipSuccess) e = hipMemsetAsync(ctx->loss_dev, 0, sizeof(double), ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) {
         hip_ok(e, "nups_init: workspace allocation");
@@ -253,7 +264,6 @@ nups_status nups_destroy(nups_ctx *ctx)
     if (ctx->coef) (void)hipFree(ctx->coef);
     if (ctx->stage) (void)hipFree(ctx->stage);
     if (ctx->partial) (void)hipFree(ctx->partial);
-    if (ctx->loss_dev) (void)hipFree(ctx->loss_dev);
     if (ctx->error_flag) (void)hipFree(ctx->error_flag);
     if (ctx->loss_pinned) (void)hipHostFree(ctx->loss_pinned);
     if (ctx->flag_pinned) (void)hipHostFree(ctx->flag_pinned);
@@ -311,6 +321,7 @@ nups_status nups_push(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_
     if ((st = ensure_plan_capacity(ctx, t, p->plan[0], (size_t)n)) != NUPS_OK) return st;
     p->plan[0].a.src = KeySource{{keys_dev, nullptr, nullptr}, {(uint32_t)n, 0, 0}};
     p->plan[0].a.n = (uint32_t)n;
+    p->plan[0].a.zero_loss = nullptr;
     if ((st = side_after_main(ctx)) != NUPS_OK) return st;
     if ((st = build_plans(ctx, p->plan, 1)) != NUPS_OK) return st;
     NUPS_HIP(hipEventRecord(p->ready, ctx->side));
@@ -413,7 +424,7 @@ nups_status nups_prepare_sample(nups_dist *dist, int64_t n, uint64_t step, nups_
     h->n = n;
     h->pulled = 0;
     h->live = true;
-    st = launch_sample(dist, h, step);
+    st = launch_sample(dist, h->keys_dev, h->n, step);
     if (st == NUPS_OK && hipEventRecord(h->ready, ctx->side) != hipSuccess)
         st = fail(NUPS_ERR_DEVICE, "nups_prepare_sample: event record failed");
     if (st != NUPS_OK) { h->live = false; dist->recycled.push_back(h); return st; }
@@ -476,7 +487,27 @@ nups_status nups_prepare_step(nups_ctx *ctx, const nups_batch *b, nups_prepared 
         p->batch.negs = b->sample->keys_dev;
         p->batch.sample = nullptr;
     }
-    if ((st = side_after_main(ctx)) == NUPS_OK) {
+    const int64_t n_draw = b->dist ? b->B * ((int64_t)b->n_neg + b->n_neg2) : 0;
+    if (n_draw > 0 && p->negs_cap < (size_t)n_draw) {   // the step draws its own negatives into its own buffer
+        hipError_t e = hipStreamSynchronize(ctx->side);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        if (e == hipSuccess && p->negs_buf) e = hipFree(p->negs_buf);
+        p->negs_buf = nullptr;
+        p->negs_cap = (size_t)n_draw + (size_t)n_draw / 4 + 1024;
+        if (e == hipSuccess) e = hipMalloc((void **)&p->negs_buf, sizeof(uint32_t) * p->negs_cap);
+        if (e != hipSuccess) {
+            hip_ok(e, "nups_prepare_step: negatives buffer");
+            p->negs_cap = 0;
+            ctx->prepared_free.push_back(p);
+            return NUPS_ERR_DEVICE;
+        }
+    }
+    if ((st = side_after_main(ctx)) == NUPS_OK && n_draw > 0) {
+        p->batch.negs = p->negs_buf;
+        p->batch.dist = nullptr;
+        st = launch_sample(b->dist, p->negs_buf, n_draw, b->sample_step);
+    }
+    if (st == NUPS_OK) {
         switch (b->task) {
         case NUPS_TASK_SGNS: st = plan_step_sgns(ctx, *p); break;
         case NUPS_TASK_MF: st = plan_step_mf(ctx, *p); break;
@@ -506,7 +537,7 @@ nups_status nups_step_prepared(nups_ctx *ctx, nups_prepared *p, double *loss_sum
     retire_prepared(ctx, p);
     if (st != NUPS_OK) return st;
     if (loss_sum_host) {
-        NUPS_HIP(hipMemcpyAsync(ctx->loss_pinned, ctx->loss_dev, sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
+        NUPS_HIP(hipMemcpyAsync(ctx->loss_pinned, p->loss_dev, sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
         st = sync_and_check(ctx);
         *loss_sum_host = *ctx->loss_pinned;
         return st;

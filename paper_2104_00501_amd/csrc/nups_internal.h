@@ -16,10 +16,10 @@ constexpr int kBlock = 256;           // threads per workgroup (4 wavefronts, 16
 constexpr int kGroupsPerBlock = kBlock / kGroup;
 constexpr int kMaxTables = 4;
 constexpr int kMaxStride = 1024;
-constexpr int kScanItems = 8;         // items per thread in the tile scans
+constexpr int kScanItems = 2;         // items per thread in the tile scans
 constexpr int kScanTile = kBlock * kScanItems;
-constexpr uint32_t kLongSegment = 48; // segments with more accesses are summed by whole workgroups, in chunks
-constexpr uint32_t kChunk = 256;      // accesses of a long segment that one workgroup sums
+constexpr uint32_t kLongSegment = 16; // segments with more accesses are summed by whole workgroups, in chunks
+constexpr uint32_t kChunk = 128;      // accesses of a long segment that one workgroup sums
 constexpr uint32_t kBadIndex = 0xFFFFFFFFu;
 
 // meta words of a plan (device)
@@ -70,6 +70,7 @@ struct PlanArgs {
     uint32_t *chunk_done;  // [max_chunks]  arrival counter per long segment (at its first chunk), zero between steps
     uint32_t *meta;        // [kMetaWords]
     uint32_t *error_flag;  // shared by the context: bit 0 = key out of range
+    double *zero_loss;     // if not null: loss accumulator that the build resets
 };
 
 struct Plan {
@@ -111,6 +112,9 @@ struct nups_prepared {
     nups::Plan plan[2];
     int n_plans = 0;
     hipEvent_t ready = nullptr;    // recorded on the side stream after the build
+    double *loss_dev = nullptr;    // this step's loss accumulator
+    uint32_t *negs_buf = nullptr;  // negatives drawn by the step itself (batch.dist)
+    size_t negs_cap = 0;
     bool live = false;             // prepared, not yet run
     bool retired = false;          // run, still referenced by a table's structure query
 };
@@ -126,7 +130,7 @@ struct nups_ctx {
     float *coef = nullptr;      size_t coef_cap = 0;      // per (example, scored row) loss derivative
     float *stage = nullptr;     size_t stage_cap = 0;     // staged gradient rows
     float *partial = nullptr;   size_t partial_cap = 0;   // partial sums of the chunks of long segments
-    double *loss_dev = nullptr;                            // batch loss accumulator
+    double *loss_cur = nullptr;                            // loss accumulator of the step being run
     uint32_t *error_flag = nullptr;                        // device word
     double *loss_pinned = nullptr;                         // pinned host copies for read-back
     uint32_t *flag_pinned = nullptr;
@@ -179,7 +183,7 @@ struct PhaseScope {
 };
 
 // kernels' host-side launchers (defined in the .hip files)
-nups_status launch_sample(nups_dist *d, nups_sample *h, uint64_t step);
+nups_status launch_sample(nups_dist *d, uint32_t *keys_out, int64_t n_samples, uint64_t step);
 nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n);
 nups_status build_plans(nups_ctx *ctx, Plan *plans, int n_plans);
 void free_plan_arrays(Plan &pl);

@@ -20,9 +20,11 @@ struct PlanPair {
     PlanArgs p[2];
 };
 
-constexpr int kRankItems = 4;                       // accesses per thread in k_plan_rank
+constexpr int kRankItems = 1;                       // accesses per thread in k_plan_mark / k_plan_rank
 constexpr int kRankTile = kBlock * kRankItems;
-constexpr uint32_t kHashSlots = 2 * kRankTile;      // open-addressing table in LDS, at most half full
+constexpr int kHashBits = 9;
+constexpr uint32_t kHashSlots = 1u << kHashBits;    // open-addressing table in LDS, at most half full
+static_assert(kHashSlots >= 2 * kRankTile, "the LDS hash table must stay at most half full");
 
 // Marks the keys of the step in the bitmap; flags keys outside the table.
 __global__ void __launch_bounds__(kBlock) k_plan_mark(PlanPair pp)
@@ -31,7 +33,10 @@ __global__ void __launch_bounds__(kBlock) k_plan_mark(PlanPair pp)
     // so that a hot word receives one global atomic per workgroup instead of one per access.
     __shared__ uint32_t hword[kHashSlots], hbits[kHashSlots];
     const PlanArgs &a = pp.p[blockIdx.y];
-    if (blockIdx.x == 0 && threadIdx.x == 0) a.meta[kMetaNumChunks] = 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        a.meta[kMetaNumChunks] = 0;
+        if (a.zero_loss) *a.zero_loss = 0.0;   // the step's loss accumulator starts from zero
+    }
     if (blockIdx.x * kRankTile >= a.n) return;
     for (uint32_t s = threadIdx.x; s < kHashSlots; s += kBlock) { hword[s] = kBadIndex; hbits[s] = 0; }
     __syncthreads();
@@ -43,7 +48,7 @@ __global__ void __launch_bounds__(kBlock) k_plan_mark(PlanPair pp)
             const uint32_t key = source_key(a.src, i);
             if (key >= a.num_keys) { bad = true; continue; }
             const uint32_t w = key >> 5;
-            uint32_t s = (w * 2654435761u) >> (32 - 11);
+            uint32_t s = (w * 2654435761u) >> (32 - kHashBits);
             for (;;) {   // ends: at most kRankTile distinct words in 2 * kRankTile slots
                 const uint32_t old = atomicCAS(&hword[s], kBadIndex, w);
                 if (old == kBadIndex || old == w) break;
@@ -151,7 +156,7 @@ __global__ void __launch_bounds__(kBlock) k_plan_rank(PlanPair pp)
                 const uint32_t w = key >> 5, b = key & 31;
                 const uint32_t u = a.word_rank[w] + __popc(a.bitmap[w] & ((1u << b) - 1u));
                 uidx[j] = u;
-                uint32_t s = (u * 2654435761u) >> (32 - 11);      // kHashSlots = 2^11
+                uint32_t s = (u * 2654435761u) >> (32 - kHashBits);
                 for (;;) {   // ends: at most kRankTile distinct keys in 2 * kRankTile slots
                     const uint32_t old = atomicCAS(&hkey[s], kBadIndex, u);
                     if (old == kBadIndex || old == u) break;
@@ -175,7 +180,6 @@ __global__ void __launch_bounds__(kBlock) k_plan_rank(PlanPair pp)
         }
     }
 }
-static_assert(kHashSlots == 2048, "hash shift in k_plan_rank assumes 2^11 slots");
 
 // Sum of each tile of kScanTile access counts (large steps only).
 __global__ void __launch_bounds__(kBlock) k_plan_count_tiles(PlanPair pp)
@@ -330,7 +334,7 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
     a.num_keys = (uint32_t)t.num_keys;
     a.words = (uint32_t)words;
     a.bitmap_tiles = (uint32_t)((words + kScanTile - 1) / kScanTile);
-    a.direct_bitmap = a.bitmap_tiles <= 32 ? 1u : 0u;      // up to 2M keys: 256 KB of bitmap per workgroup at most
+    a.direct_bitmap = words <= 65536 ? 1u : 0u;            // up to 2M keys: 256 KB of bitmap per workgroup at most
     a.error_flag = ctx->error_flag;
     return NUPS_OK;
 }
@@ -347,7 +351,7 @@ nups_status build_plans(nups_ctx *ctx, Plan *plans, int n_plans)
         PlanArgs &a = plans[k].a;
         a.count_tiles = (a.n + kScanTile - 1) / kScanTile;
         if (a.count_tiles == 0) a.count_tiles = 1;   // still writes seg[0] and the totals for an empty step
-        a.direct_count = a.count_tiles <= 64 ? 1u : 0u;
+        a.direct_count = a.n <= 131072 ? 1u : 0u;
         need_bitmap_tiles |= !a.direct_bitmap;
         need_count_tiles |= !a.direct_count;
         pp.p[k] = a;

@@ -117,10 +117,10 @@ static int feistel_half_bits(uint64_t P)
     return half;
 }
 
-nups_status launch_sample(nups_dist *d, nups_sample *h, uint64_t step)
+nups_status launch_sample(nups_dist *d, uint32_t *keys_out, int64_t n_samples, uint64_t step)
 {
     nups_ctx *ctx = d->ctx;
-    const uint32_t n = (uint32_t)h->n;
+    const uint32_t n = (uint32_t)n_samples;
     if (n == 0) return NUPS_OK;
     PhaseScope scope(ctx, NUPS_PHASE_SAMPLE, ctx->side);
     DistArgs a{d->uniform ? nullptr : d->thresh_dev, d->alias_dev, (uint64_t)ctx->tab[d->table].num_keys, d->seed,
@@ -129,25 +129,25 @@ nups_status launch_sample(nups_dist *d, nups_sample *h, uint64_t step)
     switch (d->scheme) {
     case NUPS_CONFORM:
         hipLaunchKernelGGL(k_sample_fresh, dim3(blocks), dim3(kBlock), 0, ctx->side, a, step, (uint64_t)0, n,
-                           h->keys_dev);
+                           keys_out);
         break;
     case NUPS_BOUNDED: {
         const uint32_t U = (uint32_t)d->U, G = (uint32_t)d->G;
         const uint32_t F = (n + U - 1) / U;
         const uint32_t pools = (F + G - 1) / G;
         hipLaunchKernelGGL(k_sample_pool_pass, dim3(pools * U), dim3(kBlock), 0, ctx->side, a, step, F, G, U, n,
-                           h->keys_dev);
+                           keys_out);
         break;
     }
     case NUPS_LONGTERM:
         hipLaunchKernelGGL(k_sample_longterm, dim3(blocks), dim3(kBlock), 0, ctx->side, a, (uint64_t)d->P,
-                           (uint32_t)d->R, d->cursor, n, feistel_half_bits((uint64_t)d->P), h->keys_dev);
+                           (uint32_t)d->R, d->cursor, n, feistel_half_bits((uint64_t)d->P), keys_out);
         d->cursor += n;
         break;
     case NUPS_NONCONFORM:
         hipLaunchKernelGGL(k_sample_local, dim3(blocks), dim3(kBlock), 0, ctx->side, d->local_a, d->local_b,
                            (uint32_t)d->local_n, (uint32_t)d->per_example, (uint32_t)d->split, (uint32_t)d->tile,
-                           d->seed, d->id, step, n, h->keys_dev);
+                           d->seed, d->id, step, n, keys_out);
         break;
     default:
         return fail(NUPS_ERR_ARG, "unknown sampling scheme");

@@ -6,6 +6,8 @@
 // chunks, one workgroup per chunk, whose partial rows are combined in a fixed order.
 #pragma once
 
+#include <algorithm>
+
 #include "device_utils.h"
 
 namespace nups {
@@ -144,71 +146,84 @@ __device__ __forceinline__ void sum_segment(Row<NV4> &acc, const Src &src, const
     }
 }
 
-// Workgroups below a.short_blocks: one 16-lane group per distinct key with at most kLongSegment accesses.
-// The other workgroups: one chunk (kChunk accesses) of a long segment each; the 16 groups sum interleaved
-// slices, the slices are combined through LDS in group order, and the workgroup that finishes a segment's
-// last outstanding chunk adds the chunks' partial rows in chunk order and updates the row.
+// A fixed-size grid walks over the work items of the plan: first one item per 16 distinct keys (one 16-lane
+// group per key with at most kLongSegment accesses), then one item per chunk (kChunk accesses) of a long
+// segment.  For a chunk the 16 groups sum interleaved slices, the slices are combined through LDS in group
+// order, and the workgroup that finishes a segment's last outstanding chunk adds the chunks' partial rows in
+// chunk order and updates the row.  Every workgroup leaves the loop after at most ceil(items / gridDim) turns.
 template <int NV4, class Src, class Opt>
 __global__ void __launch_bounds__(kBlock) k_apply(ApplyArgs a, Src src, Opt opt)
 {
     extern __shared__ float part[];   // [kGroupsPerBlock - 1][stride]
     __shared__ uint32_t last_arrival;
     const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
-    if (blockIdx.x < a.short_blocks) {
-        const uint32_t u = blockIdx.x * kGroupsPerBlock + group;
-        if (u >= a.meta[kMetaNumUniq]) return;
+    const uint32_t nu = a.meta[kMetaNumUniq];
+    const uint32_t short_items = (nu + kGroupsPerBlock - 1) / kGroupsPerBlock;
+    const uint32_t items = short_items + a.meta[kMetaNumChunks];
+    for (uint32_t item = blockIdx.x; item < items; item += gridDim.x) {
+        if (item < short_items) {
+            const uint32_t u = item * kGroupsPerBlock + group;
+            if (u < nu) {
+                const uint32_t first = a.seg[u], last = a.seg[u + 1];
+                if (last - first <= kLongSegment) {
+                    Row<NV4> acc;
+                    zero_row(acc);
+                    sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
+                    const size_t off = (size_t)a.uniq[u] * a.stride;
+                    opt.template apply<NV4>(a.table + off, a.state ? a.state + off : nullptr, acc, lane);
+                }
+            }
+            continue;
+        }
+        const uint32_t id = item - short_items;
+        const uint32_t u = a.chunk_seg[id], base = a.chunk_base[id];
         const uint32_t first = a.seg[u], last = a.seg[u + 1];
-        if (last - first > kLongSegment) return;
+        const uint32_t nch = (last - first + kChunk - 1) / kChunk;
+        const uint32_t cf = first + (id - base) * kChunk, cl = min(cf + kChunk, last);
         Row<NV4> acc;
         zero_row(acc);
-        sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
-        const size_t off = (size_t)a.uniq[u] * a.stride;
-        opt.template apply<NV4>(a.table + off, a.state ? a.state + off : nullptr, acc, lane);
-        return;
-    }
-    const uint32_t id = blockIdx.x - a.short_blocks;
-    if (id >= a.meta[kMetaNumChunks]) return;
-    const uint32_t u = a.chunk_seg[id], base = a.chunk_base[id];
-    const uint32_t first = a.seg[u], last = a.seg[u + 1];
-    const uint32_t nch = (last - first + kChunk - 1) / kChunk;
-    const uint32_t cf = first + (id - base) * kChunk, cl = min(cf + kChunk, last);
-    Row<NV4> acc;
-    zero_row(acc);
-    sum_segment<NV4>(acc, src, a.perm, cf + group, cl, kGroupsPerBlock, a.stride, lane);
-    if (group > 0) store_row(part + (size_t)(group - 1) * a.stride, acc, lane);
-    __syncthreads();
-    if (group == 0) {
-        for (int g = 1; g < kGroupsPerBlock; ++g) {
-            Row<NV4> r;
-            load_row(r, part + (size_t)(g - 1) * a.stride, lane);
-            axpy_row(acc, 1.0f, r);
-        }
-        if (nch > 1) {
-            store_row(a.partial + (size_t)id * a.stride, acc, lane);
-            __threadfence();          // the partial row is visible before the arrival is counted
-        }
-    }
-    if (nch > 1) {
+        sum_segment<NV4>(acc, src, a.perm, cf + group, cl, kGroupsPerBlock, a.stride, lane);
+        __syncthreads();                  // LDS of the previous turn has been read
+        if (group > 0) store_row(part + (size_t)(group - 1) * a.stride, acc, lane);
         __syncthreads();
-        if (threadIdx.x == 0) last_arrival = (atomicAdd(&a.chunk_done[base], 1u) == nch - 1) ? 1u : 0u;
-        __syncthreads();
-        if (!last_arrival) return;
-        __threadfence();              // the other chunks' partial rows are visible after their arrivals
         if (group == 0) {
-            zero_row(acc);
-            for (uint32_t ch = 0; ch < nch; ++ch) {
+            for (int g = 1; g < kGroupsPerBlock; ++g) {
                 Row<NV4> r;
-                load_row(r, a.partial + (size_t)(base + ch) * a.stride, lane);
+                load_row(r, part + (size_t)(g - 1) * a.stride, lane);
                 axpy_row(acc, 1.0f, r);
             }
+            if (nch > 1) {
+                store_row(a.partial + (size_t)id * a.stride, acc, lane);
+                __threadfence();          // the partial row is visible before the arrival is counted
+            }
         }
-        if (threadIdx.x == 0) a.chunk_done[base] = 0u;   // ready for the next step
-    }
-    if (group == 0) {
-        const size_t off = (size_t)a.uniq[u] * a.stride;
-        opt.template apply<NV4>(a.table + off, a.state ? a.state + off : nullptr, acc, lane);
+        bool update = true;
+        if (nch > 1) {
+            __syncthreads();
+            if (threadIdx.x == 0) last_arrival = (atomicAdd(&a.chunk_done[base], 1u) == nch - 1) ? 1u : 0u;
+            __syncthreads();
+            update = last_arrival != 0;
+            if (update) {
+                __threadfence();          // the other chunks' partial rows are visible after their arrivals
+                if (group == 0) {
+                    zero_row(acc);
+                    for (uint32_t ch = 0; ch < nch; ++ch) {
+                        Row<NV4> r;
+                        load_row(r, a.partial + (size_t)(base + ch) * a.stride, lane);
+                        axpy_row(acc, 1.0f, r);
+                    }
+                }
+                if (threadIdx.x == 0) a.chunk_done[base] = 0u;   // ready for the next step
+            }
+        }
+        if (update && group == 0) {
+            const size_t off = (size_t)a.uniq[u] * a.stride;
+            opt.template apply<NV4>(a.table + off, a.state ? a.state + off : nullptr, acc, lane);
+        }
     }
 }
+
+constexpr uint32_t kApplyGrid = 2048;   // workgroups of k_apply (8 per compute unit)
 
 template <int NV4, class Src, class Opt>
 static void launch_apply_nv(hipStream_t s, const Plan &pl, float *partial, float *table, float *state, int stride,
@@ -216,12 +231,12 @@ static void launch_apply_nv(hipStream_t s, const Plan &pl, float *partial, float
 {
     const PlanArgs &p = pl.a;
     if (p.n == 0) return;
-    const uint32_t short_blocks = (p.n + kGroupsPerBlock - 1) / kGroupsPerBlock;   // n bounds the distinct keys
-    const uint32_t chunk_blocks = (uint32_t)(p.n / kChunk + p.n / (kLongSegment + 1) + 1);
+    const uint32_t max_items = (p.n + kGroupsPerBlock - 1) / kGroupsPerBlock + (uint32_t)max_chunks(p.n);
     ApplyArgs a{table, state, p.uniq, p.seg, p.perm, p.meta, p.chunk_seg, p.chunk_base, p.chunk_done, partial,
-                stride, short_blocks};
+                stride, 0};
     const size_t lds = sizeof(float) * (size_t)(kGroupsPerBlock - 1) * stride;
-    hipLaunchKernelGGL((k_apply<NV4, Src, Opt>), dim3(short_blocks + chunk_blocks), dim3(kBlock), lds, s, a, src, opt);
+    hipLaunchKernelGGL((k_apply<NV4, Src, Opt>), dim3(std::min(max_items, kApplyGrid)), dim3(kBlock), lds, s, a, src,
+                       opt);
 }
 
 // Dispatch on the row length (stride / 64 float4 per lane).

@@ -98,7 +98,7 @@ static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b)
     const uint32_t blocks = (uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock);
     hipLaunchKernelGGL(k_sgns_grad<NV4>, dim3(blocks), dim3(kBlock), 0, ctx->stream, (const float *)tin.data,
                        (const float *)tout.data, (uint32_t)tin.num_keys, (uint32_t)tout.num_keys, tin.stride, b.k0,
-                       b.k1, b.negs, (uint32_t)b.B, (int)b.n_neg, ctx->coef, ctx->stage, ctx->loss_dev);
+                       b.k1, b.negs, (uint32_t)b.B, (int)b.n_neg, ctx->coef, ctx->stage, ctx->loss_cur);
 }
 
 #define NUPS_DISPATCH_STRIDE(stride, CALL)                                                        \
@@ -116,12 +116,6 @@ static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b)
                     "row_stride must be 64, 128, 192, 256, 320, 384, 512 or 1024 floats");        \
     }
 
-static nups_status zero_loss(nups_ctx *ctx)
-{
-    NUPS_HIP(hipMemsetAsync(ctx->loss_dev, 0, sizeof(double), ctx->stream));
-    return NUPS_OK;
-}
-
 // Plan side of a step: which keys each table is accessed with (plan 0: table 0, plan 1: table 1).
 static nups_status plan_two_tables(nups_ctx *ctx, nups_prepared &p, const KeySource &s0, uint32_t n0,
                                    const KeySource &s1, uint32_t n1)
@@ -136,6 +130,8 @@ static nups_status plan_two_tables(nups_ctx *ctx, nups_prepared &p, const KeySou
     p.plan[0].a.n = n0;
     p.plan[1].a.src = s1;
     p.plan[1].a.n = n1;
+    p.plan[0].a.zero_loss = p.loss_dev;
+    p.plan[1].a.zero_loss = nullptr;
     return build_plans(ctx, p.plan, 2);
 }
 
@@ -155,7 +151,7 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
     nups_status st;
     if ((st = ensure_f32(&ctx->coef, &ctx->coef_cap, (size_t)B * (K + 1), ctx->stream)) != NUPS_OK) return st;
     if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)B * tin.stride, ctx->stream)) != NUPS_OK) return st;
-    if ((st = zero_loss(ctx)) != NUPS_OK) return st;
+    ctx->loss_cur = p.loss_dev;   // zeroed by the step's plan construction
     if (B == 0) return NUPS_OK;
     {
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
@@ -224,7 +220,7 @@ static void launch_mf_grad(nups_ctx *ctx, const nups_batch &b)
     const uint32_t blocks = (uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock);
     hipLaunchKernelGGL(k_mf_grad<NV4>, dim3(blocks), dim3(kBlock), 0, ctx->stream, (const float *)tw.data,
                        (const float *)th.data, (uint32_t)tw.num_keys, (uint32_t)th.num_keys, tw.stride, b.k0, b.k1,
-                       b.val, (uint32_t)b.B, b.l2, ctx->stage, ctx->loss_dev);
+                       b.val, (uint32_t)b.B, b.l2, ctx->stage, ctx->loss_cur);
 }
 
 nups_status plan_step_mf(nups_ctx *ctx, nups_prepared &p)
@@ -242,7 +238,7 @@ nups_status run_step_mf(nups_ctx *ctx, nups_prepared &p)
     const uint32_t B = (uint32_t)b.B;
     nups_status st;
     if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)2 * B * tw.stride, ctx->stream)) != NUPS_OK) return st;
-    if ((st = zero_loss(ctx)) != NUPS_OK) return st;
+    ctx->loss_cur = p.loss_dev;   // zeroed by the step's plan construction
     if (B == 0) return NUPS_OK;
     {
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
@@ -423,7 +419,7 @@ static void launch_kge_grad(nups_ctx *ctx, const nups_batch &b)
     const size_t lds = sizeof(float) * kGroupsPerBlock * (size_t)te.stride;
     hipLaunchKernelGGL(k_kge_grad<NV4>, dim3((uint32_t)b.B), dim3(kBlock), lds, ctx->stream, (const float *)te.data,
                        (const float *)tr.data, (uint32_t)te.num_keys, (uint32_t)tr.num_keys, te.stride, b.k0, b.k1,
-                       b.k2, b.negs, (uint32_t)b.B, (int)b.n_neg, (int)b.n_neg2, ctx->coef, ctx->stage, ctx->loss_dev);
+                       b.k2, b.negs, (uint32_t)b.B, (int)b.n_neg, (int)b.n_neg2, ctx->coef, ctx->stage, ctx->loss_cur);
 }
 
 nups_status plan_step_kge(nups_ctx *ctx, nups_prepared &p)
@@ -444,7 +440,7 @@ nups_status run_step_kge(nups_ctx *ctx, nups_prepared &p)
     nups_status st;
     if ((st = ensure_f32(&ctx->coef, &ctx->coef_cap, (size_t)B * nn + 1, ctx->stream)) != NUPS_OK) return st;
     if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)5 * B * te.stride, ctx->stream)) != NUPS_OK) return st;
-    if ((st = zero_loss(ctx)) != NUPS_OK) return st;
+    ctx->loss_cur = p.loss_dev;   // zeroed by the step's plan construction
     if (B == 0) return NUPS_OK;
     {
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);

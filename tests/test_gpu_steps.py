@@ -292,7 +292,11 @@ def test_sgns_pipelined_steps_match_the_oracle():
     dev_pairs = [(dev_u32(c), dev_u32(o)) for c, o in pairs]
 
     def prepare(t):
-        h = nb.nups_prepare_sample(dist, B * K, t)
+        if t % 2:       # the step draws its own negatives ...
+            b = nb.make_batch(nb.NUPS_TASK_SGNS, B, dev_pairs[t][0], dev_pairs[t][1], n_neg=K, lr=lr, dist=dist,
+                              sample_step=t)
+            return None, nb.nups_prepare_step(ctx, b)
+        h = nb.nups_prepare_sample(dist, B * K, t)      # ... or takes them from a handle
         b = nb.make_batch(nb.NUPS_TASK_SGNS, B, dev_pairs[t][0], dev_pairs[t][1], n_neg=K, lr=lr, sample=h)
         return h, nb.nups_prepare_step(ctx, b)
 
@@ -302,7 +306,8 @@ def test_sgns_pipelined_steps_match_the_oracle():
         if t + 1 < steps:
             nxt = prepare(t + 1)
         nb.nups_step_prepared(ctx, p)
-        nb.nups_release_sample(h)
+        if h is not None:
+            nb.nups_release_sample(h)
     with pytest.raises(nb.NupsError) as e:
         nb.nups_step_prepared(ctx, p)                    # a prepared step runs once
     assert e.value.status == nb.NUPS_ERR_STATE
