@@ -52,10 +52,10 @@ struct PlanArgs {
     uint32_t words;        // bitmap words = ceil(V / 32)
     uint32_t bitmap_tiles; // ceil(words / kScanTile)
     uint32_t count_tiles;  // ceil(n / kScanTile)
-    uint32_t direct_bitmap; // 1: the bitmap scan counts the bits below its tile itself (no tile sums)
     uint32_t direct_count;  // 1: the count scan sums the counts below its tile itself
     // build scratch, owned by the table and shared by all plans of that table (builds run one after another)
-    uint32_t *bitmap;      // [words]     one bit per key, all zero between builds
+    uint8_t *bytemap;      // [32 * words] one byte per key, all zero between builds
+    uint32_t *bitmap;      // [words]     one bit per key, packed from the byte map by every build
     uint32_t *word_rank;   // [words]     number of distinct keys below each bitmap word
     uint32_t *tile_sum;    // [max(bitmap_tiles, count_tiles)]
     uint32_t *slot;        // [n]         per access: index of its key among the distinct keys
@@ -81,6 +81,7 @@ struct Plan {
 
 // Build scratch of one table.
 struct PlanScratch {
+    uint8_t *bytemap = nullptr;
     uint32_t *bitmap = nullptr, *word_rank = nullptr, *tile_sum = nullptr, *slot = nullptr, *rank = nullptr;
     size_t cap_words = 0, cap_tiles = 0, cap_n = 0;
 };

@@ -1,12 +1,14 @@
 // Per-key aggregation structure of a step (the "aggregate per key" stage): from the list of keys
 // a step accesses in one table, build the distinct keys in ascending order, their access counts
 // and the accesses grouped by key.  Keys are bounded by the table size, so the distinct set is a
-// bitmap over the key space and a key's position among the distinct keys is a prefix population
+// map over the key space and a key's position among the distinct keys is a prefix population
 // count; no comparison sort is needed.  Up to two tables are planned by the same launches
 // (blockIdx.y selects the table).
 //
-// Hot keys (Section 3.2: a few keys take a large share of the accesses) would serialise global
-// atomics, so every workgroup first combines its own accesses to a key in LDS and issues one
+// Marking uses one byte per key and plain stores (idempotent, so no atomics and no contention on
+// hot keys); the bytes are then packed into a bitmap.  Hot keys (Section 3.2: a few keys take a
+// large share of the accesses) would serialise the global atomics that hand out positions inside
+// a segment, so every workgroup first combines its own accesses to a key in LDS and issues one
 // global atomic per distinct key; segments that are too long for one row group are cut into
 // chunks that separate workgroups sum.
 #include <algorithm>
@@ -20,71 +22,52 @@ struct PlanPair {
     PlanArgs p[2];
 };
 
-constexpr int kRankItems = 1;                       // accesses per thread in k_plan_mark / k_plan_rank
+constexpr int kRankItems = 4;                       // accesses per thread in k_plan_rank
 constexpr int kRankTile = kBlock * kRankItems;
-constexpr int kHashBits = 9;
+constexpr int kHashBits = 11;
 constexpr uint32_t kHashSlots = 1u << kHashBits;    // open-addressing table in LDS, at most half full
 static_assert(kHashSlots >= 2 * kRankTile, "the LDS hash table must stay at most half full");
 
-// Marks the keys of the step in the bitmap; flags keys outside the table.
+// Marks the keys of the step in the byte map; flags keys outside the table.
 __global__ void __launch_bounds__(kBlock) k_plan_mark(PlanPair pp)
 {
-    // The bits of one workgroup's keys are first OR-ed together per bitmap word in an LDS hash table,
-    // so that a hot word receives one global atomic per workgroup instead of one per access.
-    __shared__ uint32_t hword[kHashSlots], hbits[kHashSlots];
     const PlanArgs &a = pp.p[blockIdx.y];
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+    if (i == 0) {
         a.meta[kMetaNumChunks] = 0;
         if (a.zero_loss) *a.zero_loss = 0.0;   // the step's loss accumulator starts from zero
     }
-    if (blockIdx.x * kRankTile >= a.n) return;
-    for (uint32_t s = threadIdx.x; s < kHashSlots; s += kBlock) { hword[s] = kBadIndex; hbits[s] = 0; }
-    __syncthreads();
-    bool bad = false;
-#pragma unroll
-    for (int j = 0; j < kRankItems; ++j) {
-        const uint32_t i = blockIdx.x * kRankTile + j * kBlock + threadIdx.x;
-        if (i < a.n) {
-            const uint32_t key = source_key(a.src, i);
-            if (key >= a.num_keys) { bad = true; continue; }
-            const uint32_t w = key >> 5;
-            uint32_t s = (w * 2654435761u) >> (32 - kHashBits);
-            for (;;) {   // ends: at most kRankTile distinct words in 2 * kRankTile slots
-                const uint32_t old = atomicCAS(&hword[s], kBadIndex, w);
-                if (old == kBadIndex || old == w) break;
-                s = (s + 1) & (kHashSlots - 1);
-            }
-            atomicOr(&hbits[s], 1u << (key & 31));
-        }
-    }
-    if (bad) atomicOr(a.error_flag, 1u);
-    __syncthreads();
-    for (uint32_t s = threadIdx.x; s < kHashSlots; s += kBlock)
-        if (hbits[s]) atomicOr(&a.bitmap[hword[s]], hbits[s]);
+    if (i >= a.n) return;
+    const uint32_t key = source_key(a.src, i);
+    if (key >= a.num_keys) { atomicOr(a.error_flag, 1u); return; }
+    a.bytemap[key] = 1;
 }
 
-// Sum of `items[0 .. end)` (popcounts if POPC) over the whole workgroup; every thread gets the result.
+// Sum of `items[0 .. end)` over the whole workgroup; every thread gets the result.
 // `items` is 16-byte aligned; whole uint4 are read, four per thread and iteration, then the tail.
-template <bool POPC>
 __device__ __forceinline__ uint32_t block_sum_range(const uint32_t *items, uint32_t end, uint32_t *lds)
 {
     uint32_t c = 0;
     const uint4 *v = reinterpret_cast<const uint4 *>(items);
     const uint32_t n4 = end / 4;
-    auto add = [&](const uint4 x) {
-        c += POPC ? (__popc(x.x) + __popc(x.y) + __popc(x.z) + __popc(x.w)) : (x.x + x.y + x.z + x.w);
-    };
     uint32_t q = threadIdx.x;
     for (; q + 3 * kBlock < n4; q += 4 * kBlock) {
         const uint4 x0 = v[q], x1 = v[q + kBlock], x2 = v[q + 2 * kBlock], x3 = v[q + 3 * kBlock];
-        add(x0); add(x1); add(x2); add(x3);
+        c += (x0.x + x0.y + x0.z + x0.w) + (x1.x + x1.y + x1.z + x1.w) + (x2.x + x2.y + x2.z + x2.w)
+             + (x3.x + x3.y + x3.z + x3.w);
     }
-    for (; q < n4; q += kBlock) add(v[q]);
-    for (uint32_t w = n4 * 4 + threadIdx.x; w < end; w += kBlock) c += POPC ? __popc(items[w]) : items[w];
+    for (; q < n4; q += kBlock) { const uint4 x = v[q]; c += x.x + x.y + x.z + x.w; }
+    for (uint32_t w = n4 * 4 + threadIdx.x; w < end; w += kBlock) c += items[w];
     return block_sum(c, lds);
 }
 
-// Population count of each tile of kScanTile bitmap words (large key spaces only).
+// Four marker bytes (0 or 1 each) -> four bits.
+__device__ __forceinline__ uint32_t pack4(uint32_t x)
+{
+    return (x & 1u) | ((x >> 7) & 2u) | ((x >> 14) & 4u) | ((x >> 21) & 8u);
+}
+
+// Packs the byte map into bitmap words (32 keys each) and counts the marked keys of each tile of kScanTile words.
 __global__ void __launch_bounds__(kBlock) k_plan_bitmap_tiles(PlanPair pp)
 {
     __shared__ uint32_t lds[kBlock / 64 + 1];
@@ -93,23 +76,27 @@ __global__ void __launch_bounds__(kBlock) k_plan_bitmap_tiles(PlanPair pp)
     const uint32_t w0 = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
     uint32_t c = 0;
 #pragma unroll
-    for (int j = 0; j < kScanItems; ++j)
-        if (w0 + j < a.words) c += __popc(a.bitmap[w0 + j]);
+    for (int j = 0; j < kScanItems; ++j) {
+        if (w0 + j < a.words) {      // the byte map is allocated in whole words of 32 keys
+            const uint4 *src = reinterpret_cast<const uint4 *>(a.bytemap + (size_t)(w0 + j) * 32);
+            const uint4 lo = src[0], hi = src[1];
+            const uint32_t bits = pack4(lo.x) | (pack4(lo.y) << 4) | (pack4(lo.z) << 8) | (pack4(lo.w) << 12)
+                                  | (pack4(hi.x) << 16) | (pack4(hi.y) << 20) | (pack4(hi.z) << 24) | (pack4(hi.w) << 28);
+            a.bitmap[w0 + j] = bits;
+            c += __popc(bits);
+        }
+    }
     const uint32_t s = block_sum(c, lds);
     if (threadIdx.x == 0) a.tile_sum[blockIdx.x] = s;
 }
 
 // Rank of every bitmap word among the distinct keys; emits the distinct keys and clears their counts.
-// With `direct` set each workgroup counts the bits below its tile itself (small key spaces) and
-// k_plan_bitmap_tiles is not needed.
 __global__ void __launch_bounds__(kBlock) k_plan_bitmap_scan(PlanPair pp)
 {
     __shared__ uint32_t lds[kBlock / 64 + 1];
     const PlanArgs &a = pp.p[blockIdx.y];
     if (blockIdx.x >= a.bitmap_tiles) return;
-    uint32_t before;
-    if (a.direct_bitmap) before = block_sum_range<true>(a.bitmap, blockIdx.x * kScanTile, lds);
-    else before = block_sum_range<false>(a.tile_sum, blockIdx.x, lds);
+    const uint32_t before = block_sum_range(a.tile_sum, blockIdx.x, lds);
     const uint32_t w0 = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
     uint32_t bits[kScanItems];
     uint32_t c = 0;
@@ -207,8 +194,8 @@ __global__ void __launch_bounds__(kBlock) k_plan_count_scan(PlanPair pp)
     const uint32_t u0 = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
     if (blockIdx.x * kScanTile >= nu && blockIdx.x != 0) return;
     uint32_t before;
-    if (a.direct_count) before = block_sum_range<false>(a.count, min(blockIdx.x * kScanTile, nu), lds);
-    else before = block_sum_range<false>(a.tile_sum, blockIdx.x, lds);
+    if (a.direct_count) before = block_sum_range(a.count, min(blockIdx.x * kScanTile, nu), lds);
+    else before = block_sum_range(a.tile_sum, blockIdx.x, lds);
     uint32_t cnt[kScanItems];
     uint32_t c = 0;
 #pragma unroll
@@ -239,7 +226,7 @@ __global__ void __launch_bounds__(kBlock) k_plan_count_scan(PlanPair pp)
     }
 }
 
-// Groups the accesses by key and returns the bitmap to all-zero for the next step.
+// Groups the accesses by key and returns the byte map to all-zero for the next step.
 __global__ void __launch_bounds__(kBlock) k_plan_scatter(PlanPair pp)
 {
     const PlanArgs &a = pp.p[blockIdx.y];
@@ -248,7 +235,7 @@ __global__ void __launch_bounds__(kBlock) k_plan_scatter(PlanPair pp)
     const uint32_t u = a.slot[i];
     if (u == kBadIndex) return;
     a.perm[a.seg[u] + a.rank[i]] = i;
-    a.bitmap[source_key(a.src, i) >> 5] = 0u;
+    a.bytemap[source_key(a.src, i)] = 0;
 }
 
 static nups_status grow_u32(uint32_t **buf, size_t n, bool zero, hipStream_t stream)
@@ -274,6 +261,7 @@ void free_plan_scratch(PlanScratch &sc)
 {
     for (uint32_t *p : {sc.bitmap, sc.word_rank, sc.tile_sum, sc.slot, sc.rank})
         if (p) (void)hipFree(p);
+    if (sc.bytemap) (void)hipFree(sc.bytemap);
     sc = PlanScratch{};
 }
 
@@ -296,6 +284,7 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
     if (sc.cap_words < words) {
         if ((st = quiesce(ctx)) != NUPS_OK) return st;
         if ((st = grow_u32(&sc.bitmap, words, true, ctx->side)) != NUPS_OK) return st;
+        if ((st = grow_u32((uint32_t **)&sc.bytemap, words * 8, true, ctx->side)) != NUPS_OK) return st;   // 32 bytes per word
         if ((st = grow_u32(&sc.word_rank, words, false, ctx->side)) != NUPS_OK) return st;
         sc.cap_words = words;
     }
@@ -330,11 +319,11 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
         if ((st = quiesce(ctx)) != NUPS_OK) return st;
         if ((st = ensure_f32(&ctx->partial, &ctx->partial_cap, need_partial, ctx->stream)) != NUPS_OK) return st;
     }
+    a.bytemap = sc.bytemap;
     a.bitmap = sc.bitmap; a.word_rank = sc.word_rank; a.tile_sum = sc.tile_sum; a.slot = sc.slot; a.rank = sc.rank;
     a.num_keys = (uint32_t)t.num_keys;
     a.words = (uint32_t)words;
     a.bitmap_tiles = (uint32_t)((words + kScanTile - 1) / kScanTile);
-    a.direct_bitmap = words <= 65536 ? 1u : 0u;            // up to 2M keys: 256 KB of bitmap per workgroup at most
     a.error_flag = ctx->error_flag;
     return NUPS_OK;
 }
@@ -346,13 +335,12 @@ nups_status build_plans(nups_ctx *ctx, Plan *plans, int n_plans)
     PhaseScope scope(ctx, NUPS_PHASE_PLAN, ctx->side);
     PlanPair pp;
     uint32_t max_n = 0, max_btiles = 0, max_ctiles = 0;
-    bool need_bitmap_tiles = false, need_count_tiles = false;
+    bool need_count_tiles = false;
     for (int k = 0; k < n_plans; ++k) {
         PlanArgs &a = plans[k].a;
         a.count_tiles = (a.n + kScanTile - 1) / kScanTile;
         if (a.count_tiles == 0) a.count_tiles = 1;   // still writes seg[0] and the totals for an empty step
         a.direct_count = a.n <= 131072 ? 1u : 0u;
-        need_bitmap_tiles |= !a.direct_bitmap;
         need_count_tiles |= !a.direct_count;
         pp.p[k] = a;
         max_n = std::max(max_n, a.n);
@@ -364,8 +352,8 @@ nups_status build_plans(nups_ctx *ctx, Plan *plans, int n_plans)
     const uint32_t nblocks = std::max(1u, (max_n + kBlock - 1) / kBlock);
     const uint32_t rblocks = std::max(1u, (max_n + kRankTile - 1) / kRankTile);
     hipStream_t s = ctx->side;
-    hipLaunchKernelGGL(k_plan_mark, dim3(rblocks, n_plans), blk, 0, s, pp);
-    if (need_bitmap_tiles) hipLaunchKernelGGL(k_plan_bitmap_tiles, dim3(max_btiles, n_plans), blk, 0, s, pp);
+    hipLaunchKernelGGL(k_plan_mark, dim3(nblocks, n_plans), blk, 0, s, pp);
+    hipLaunchKernelGGL(k_plan_bitmap_tiles, dim3(max_btiles, n_plans), blk, 0, s, pp);
     hipLaunchKernelGGL(k_plan_bitmap_scan, dim3(max_btiles, n_plans), blk, 0, s, pp);
     hipLaunchKernelGGL(k_plan_rank, dim3(rblocks, n_plans), blk, 0, s, pp);
     if (need_count_tiles) hipLaunchKernelGGL(k_plan_count_tiles, dim3(max_ctiles, n_plans), blk, 0, s, pp);
