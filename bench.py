@@ -132,6 +132,15 @@ def main() -> int:
             phases[nb.nups_phase_name(p)] = {"ms_per_step": ms / steps, "brackets": n}
     nb.nups_profile(ctx, False)
 
+    # a plain copy of known size through the library's own gather kernel (rows 0..n-1 in order): the
+    # reference that hardware byte counters are scaled with
+    n_cal = min(V, 262_144)
+    cal_keys = torch.arange(n_cal, dtype=torch.int32, device="cuda")
+    cal_out = torch.empty((n_cal, stride), dtype=torch.float32, device="cuda")
+    nb.nups_pull(ctx, 0, cal_keys, n_cal, cal_out)
+    torch.cuda.synchronize()
+    del cal_out
+
     # Algorithmic bytes per step under snapshot semantics: every distinct touched row is read once
     # and written once (4 * d bytes each way), plus the key arrays (4 bytes per access).
     row_bytes = 4 * d

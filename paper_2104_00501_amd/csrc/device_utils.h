@@ -172,6 +172,19 @@ __device__ __forceinline__ void block_add_loss(float x, double *loss, float *lds
     }
 }
 
+// Workgroups are handed to the eight accelerator dies (XCDs, each with its own L2) round-robin by
+// workgroup number.  xcd_block() renumbers them so that each die works on one contiguous eighth of the
+// logical workgroups: examples that are neighbours in the batch (same center word, same sample pool)
+// then share an L2 instead of fetching the same rows into several.  The grid must come from xcd_grid().
+constexpr uint32_t kNumXcd = 8;
+
+__device__ __forceinline__ uint32_t xcd_block()
+{
+    return (blockIdx.x % kNumXcd) * (gridDim.x / kNumXcd) + blockIdx.x / kNumXcd;
+}
+
+static inline uint32_t xcd_grid(uint32_t blocks) { return (blocks + kNumXcd - 1) / kNumXcd * kNumXcd; }
+
 __device__ __forceinline__ uint32_t source_key(const KeySource &s, uint32_t i)
 {
     if (i < s.len[0]) return s.ptr[0][i];

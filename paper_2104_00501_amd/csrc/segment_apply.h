@@ -146,9 +146,9 @@ __device__ __forceinline__ void sum_segment(Row<NV4> &acc, const Src &src, const
     }
 }
 
-// A fixed-size grid walks over the work items of the plan: first one item per 16 distinct keys (one 16-lane
-// group per key with at most kLongSegment accesses), then one item per chunk (kChunk accesses) of a long
-// segment.  For a chunk the 16 groups sum interleaved slices, the slices are combined through LDS in group
+// A fixed-size grid walks over the work items of the plan: first one item per chunk (kChunk accesses) of a
+// long segment, then one item per 16 distinct keys (one 16-lane group per key with at most kLongSegment
+// accesses).  For a chunk the 16 groups sum interleaved slices, the slices are combined through LDS in group
 // order, and the workgroup that finishes a segment's last outstanding chunk adds the chunks' partial rows in
 // chunk order and updates the row.  Every workgroup leaves the loop after at most ceil(items / gridDim) turns.
 template <int NV4, class Src, class Opt>
@@ -158,11 +158,11 @@ __global__ void __launch_bounds__(kBlock) k_apply(ApplyArgs a, Src src, Opt opt)
     __shared__ uint32_t last_arrival;
     const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
     const uint32_t nu = a.meta[kMetaNumUniq];
-    const uint32_t short_items = (nu + kGroupsPerBlock - 1) / kGroupsPerBlock;
-    const uint32_t items = short_items + a.meta[kMetaNumChunks];
+    const uint32_t chunk_items = a.meta[kMetaNumChunks];   // taken first: they are the long poles
+    const uint32_t items = chunk_items + (nu + kGroupsPerBlock - 1) / kGroupsPerBlock;
     for (uint32_t item = blockIdx.x; item < items; item += gridDim.x) {
-        if (item < short_items) {
-            const uint32_t u = item * kGroupsPerBlock + group;
+        if (item >= chunk_items) {
+            const uint32_t u = (item - chunk_items) * kGroupsPerBlock + group;
             if (u < nu) {
                 const uint32_t first = a.seg[u], last = a.seg[u + 1];
                 if (last - first <= kLongSegment) {
@@ -175,7 +175,7 @@ __global__ void __launch_bounds__(kBlock) k_apply(ApplyArgs a, Src src, Opt opt)
             }
             continue;
         }
-        const uint32_t id = item - short_items;
+        const uint32_t id = item;
         const uint32_t u = a.chunk_seg[id], base = a.chunk_base[id];
         const uint32_t first = a.seg[u], last = a.seg[u + 1];
         const uint32_t nch = (last - first + kChunk - 1) / kChunk;
@@ -205,11 +205,24 @@ __global__ void __launch_bounds__(kBlock) k_apply(ApplyArgs a, Src src, Opt opt)
             update = last_arrival != 0;
             if (update) {
                 __threadfence();          // the other chunks' partial rows are visible after their arrivals
-                if (group == 0) {
+                if (group == 0) {        // chunk order, four partial rows in flight
                     zero_row(acc);
-                    for (uint32_t ch = 0; ch < nch; ++ch) {
+                    const float *prow = a.partial + (size_t)base * a.stride;
+                    uint32_t ch = 0;
+                    for (; ch + 3 < nch; ch += 4) {
+                        Row<NV4> r0, r1, r2, r3;
+                        load_row(r0, prow + (size_t)ch * a.stride, lane);
+                        load_row(r1, prow + (size_t)(ch + 1) * a.stride, lane);
+                        load_row(r2, prow + (size_t)(ch + 2) * a.stride, lane);
+                        load_row(r3, prow + (size_t)(ch + 3) * a.stride, lane);
+                        axpy_row(acc, 1.0f, r0);
+                        axpy_row(acc, 1.0f, r1);
+                        axpy_row(acc, 1.0f, r2);
+                        axpy_row(acc, 1.0f, r3);
+                    }
+                    for (; ch < nch; ++ch) {
                         Row<NV4> r;
-                        load_row(r, a.partial + (size_t)(base + ch) * a.stride, lane);
+                        load_row(r, prow + (size_t)ch * a.stride, lane);
                         axpy_row(acc, 1.0f, r);
                     }
                 }

@@ -59,14 +59,14 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(const float *in_table, con
 {
     __shared__ float lds[kBlock / 64];
     const int lane = threadIdx.x & (kGroup - 1);
-    const uint32_t e_raw = (blockIdx.x * kBlock + threadIdx.x) / kGroup;
+    const uint32_t e_raw = (xcd_block() * kBlock + threadIdx.x) / kGroup;
     const bool active = e_raw < B;
     const uint32_t e = active ? e_raw : B - 1;
     Row<NV4> v, acc;
     load_row(v, in_table + (size_t)min(center[e], num_in - 1) * stride, lane);
     zero_row(acc);
     float loss_acc = 0.f;
-    constexpr int JU = 4;
+    constexpr int JU = 4;     // rows in flight per group
     for (int j0 = 0; j0 <= K; j0 += JU) {
         Row<NV4> u[JU];
 #pragma unroll
@@ -95,7 +95,7 @@ template <int NV4>
 static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b)
 {
     const Table &tin = ctx->tab[0], &tout = ctx->tab[1];
-    const uint32_t blocks = (uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock);
+    const uint32_t blocks = xcd_grid((uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock));
     hipLaunchKernelGGL(k_sgns_grad<NV4>, dim3(blocks), dim3(kBlock), 0, ctx->stream, (const float *)tin.data,
                        (const float *)tout.data, (uint32_t)tin.num_keys, (uint32_t)tout.num_keys, tin.stride, b.k0,
                        b.k1, b.negs, (uint32_t)b.B, (int)b.n_neg, ctx->coef, ctx->stage, ctx->loss_cur);
@@ -188,7 +188,7 @@ __global__ void __launch_bounds__(kBlock) k_mf_grad(const float *W, const float 
 {
     __shared__ float lds[kBlock / 64];
     const int lane = threadIdx.x & (kGroup - 1);
-    const uint32_t c_raw = (blockIdx.x * kBlock + threadIdx.x) / kGroup;
+    const uint32_t c_raw = (xcd_block() * kBlock + threadIdx.x) / kGroup;
     const bool active = c_raw < B;
     const uint32_t c = active ? c_raw : B - 1;
     Row<NV4> w, h;
@@ -217,7 +217,7 @@ template <int NV4>
 static void launch_mf_grad(nups_ctx *ctx, const nups_batch &b)
 {
     const Table &tw = ctx->tab[0], &th = ctx->tab[1];
-    const uint32_t blocks = (uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock);
+    const uint32_t blocks = xcd_grid((uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock));
     hipLaunchKernelGGL(k_mf_grad<NV4>, dim3(blocks), dim3(kBlock), 0, ctx->stream, (const float *)tw.data,
                        (const float *)th.data, (uint32_t)tw.num_keys, (uint32_t)th.num_keys, tw.stride, b.k0, b.k1,
                        b.val, (uint32_t)b.B, b.l2, ctx->stage, ctx->loss_cur);
