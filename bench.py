@@ -1,12 +1,17 @@
 #!/usr/bin/env python3
 """Throughput of the sparse-SGD minibatch step on one MI355X.
 
-Workload (default): the large skip-gram configuration -- 1M keys, d = 300 (rows padded to 320
+Default workload: the large skip-gram configuration -- 1M keys, d = 300 (rows padded to 320
 floats), 3 negatives per pair from unigram^0.75 under BOUNDED sample reuse (U = 4, pools of 250),
 batches of 16,384 (center, context) pairs cut in stream order from an i.i.d. Zipf(1.0) token
 stream with window 5, learning rate 0.025 linearly decayed.  One step = draw negatives, build the
 per-key aggregation structure, score + gradient, aggregate and push, all inside the timed region;
-inputs (pair arrays, tables, alias table) are resident in HBM before timing starts.
+inputs (example arrays, tables, alias table) are resident in HBM before timing starts.  Steps are
+software-pipelined: the key-only half of step t+1 is enqueued before step t runs.
+
+Other workloads (--workload): the small skip-gram configuration, matrix factorisation
+(10M x 1M, rank 100, 65,536 cells per step) and ComplEx (4.6M entities, d = 500, 1,024 triples
+with 50+50 uniform negatives per step, AdaGrad).
 
 Prints one JSON line: positive examples/s, the roofline figure of the dominant kernel and the
 CPU oracle timed on a bounded prefix of the same workload.
@@ -28,12 +33,211 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
+
+def dev_keys(x):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.uint32).view(np.int32)).cuda()
+
+
+class Sgns:
+    """Skip-gram with negative sampling; tables 0/1 = input/output vectors."""
+
+    def __init__(self, name, V, d, K, U, G, B, window, s, lr0, stream_tokens, seed):
+        self.name, self.V, self.d, self.K, self.U, self.G, self.B = name, V, d, K, U, G, B
+        self.window, self.s, self.lr0, self.stream_tokens, self.seed = window, s, lr0, stream_tokens, seed
+        self.unit = "pairs"
+
+    def setup(self, nb, wl, total_steps):
+        import torch
+        B, window = self.B, self.window
+        n_tokens = min(self.stream_tokens, total_steps * B // (2 * window) + 2 * window + 2)
+        toks = wl.zipf_stream(self.V, self.s, n_tokens, self.seed)
+        self.centers, self.contexts = wl.window_pairs(toks, window, 0, total_steps * B)
+        total_steps = len(self.centers) // B
+        self.weights = wl.expected_unigram_weights(self.V, self.s, self.stream_tokens)
+        self.In, self.Out = wl.sgns_tables(self.V, self.d, self.seed)
+        self.stride = self.In.shape[1]
+        self.tables = [torch.from_numpy(self.In).cuda(), torch.from_numpy(self.Out).cuda()]
+        self.kc, self.ko = dev_keys(self.centers), dev_keys(self.contexts)
+        self.ctx = nb.nups_init(self.tables, [self.d, self.d])
+        scheme = nb.NUPS_BOUNDED if self.U > 1 else nb.NUPS_CONFORM
+        self.dist = nb.nups_register_distribution(self.ctx, 1, self.weights, scheme, U=self.U, G=self.G, seed=self.seed)
+        epoch_steps = max(1, wl.num_window_pairs(self.stream_tokens, window) // B)
+        self.lrs = [float(wl.linear_lr(self.lr0, t, epoch_steps)) for t in range(total_steps)]
+        self.nb = nb
+        return total_steps
+
+    def prepare(self, t):
+        nb, B = self.nb, self.B
+        batch = nb.make_batch(nb.NUPS_TASK_SGNS, B, self.kc.data_ptr() + 4 * t * B, self.ko.data_ptr() + 4 * t * B,
+                              n_neg=self.K, lr=self.lrs[t], dist=self.dist, sample_step=t)
+        return nb.nups_prepare_step(self.ctx, batch)
+
+    def accesses(self):
+        return self.B, self.B * (self.K + 1)
+
+    def algorithmic_bytes(self, nu0, nu1):
+        row, B, K = 4 * self.d, self.B, self.K
+        return {"grad": (nu0 + nu1) * row + 4 * B * (2 + K) + 4 * B * (K + 1),     # rows read once; keys; coefficients
+                "apply0": nu0 * row * 2 + 4 * B,                                    # input rows read + written
+                "apply1": nu1 * row * 2 + 8 * B * (K + 1),                          # output rows read + written
+                "step": (nu0 + nu1) * row * 2 + 4 * B * (2 + K)}
+
+    def logical_bytes(self):
+        return self.B * (2 + self.K) * 4 * self.d * 3
+
+    def oracle_step(self, orc, t):
+        if not hasattr(self, "alias"):
+            self.alias = orc.alias_build(self.weights)
+        B, K = self.B, self.K
+        c, o = self.centers[t * B:(t + 1) * B], self.contexts[t * B:(t + 1) * B]
+        if self.U > 1:
+            ng = orc.sample_bounded(self.alias, self.V, self.seed, 0, t, B * K, self.U, self.G)
+        else:
+            ng = orc.sample_conform(self.alias, self.V, self.seed, 0, t, B * K)
+        orc.step_sgns(self.In, self.Out, self.d, c, o, ng, K, self.lrs[t])
+
+    def config(self):
+        return {"workload": self.name, "task": "SGNS", "num_keys": self.V, "dim": self.d, "row_stride": self.stride,
+                "negatives": self.K, "scheme": "BOUNDED U=%d G=%d" % (self.U, self.G) if self.U > 1 else "CONFORM",
+                "batch": self.B, "window": self.window, "zipf_s": self.s, "lr0": self.lr0, "pairs": "stream order"}
+
+
+class Mf:
+    """Matrix factorisation; tables 0/1 = row / column factors."""
+
+    def __init__(self, name, n_rows, n_cols, d, B, s, lr, l2, seed):
+        self.name, self.n_rows, self.n_cols, self.d, self.B, self.s = name, n_rows, n_cols, d, B, s
+        self.lr, self.l2, self.seed = lr, l2, seed
+        self.unit = "cells"
+
+    def setup(self, nb, wl, total_steps):
+        import torch
+        B = self.B
+        self.rows, self.cols, self.vals = wl.mf_cells(self.n_rows, self.n_cols, self.s, total_steps * B, self.seed)
+        self.stride = wl.padded_stride(self.d)
+        g = torch.Generator(device="cuda").manual_seed(self.seed)
+
+        def table(n):
+            t = torch.zeros((n, self.stride), dtype=torch.float32, device="cuda")
+            t[:, :self.d] = torch.rand((n, self.d), generator=g, device="cuda") * 0.2 - 0.1
+            return t
+
+        self.tables = [table(self.n_rows), table(self.n_cols)]
+        self.kr, self.kcol = dev_keys(self.rows), dev_keys(self.cols)
+        self.kv = torch.from_numpy(self.vals).cuda()
+        self.ctx = nb.nups_init(self.tables, [self.d, self.d])
+        self.nb = nb
+        return total_steps
+
+    def prepare(self, t):
+        nb, B = self.nb, self.B
+        batch = nb.make_batch(nb.NUPS_TASK_MF, B, self.kr.data_ptr() + 4 * t * B, self.kcol.data_ptr() + 4 * t * B,
+                              val=self.kv.data_ptr() + 4 * t * B, lr=self.lr, l2=self.l2)
+        return nb.nups_prepare_step(self.ctx, batch)
+
+    def accesses(self):
+        return self.B, self.B
+
+    def algorithmic_bytes(self, nu0, nu1):
+        row, B = 4 * self.d, self.B
+        return {"grad": (nu0 + nu1) * row + 12 * B, "apply0": nu0 * row * 2 + 4 * B, "apply1": nu1 * row * 2 + 4 * B,
+                "step": (nu0 + nu1) * row * 2 + 12 * B}
+
+    def logical_bytes(self):
+        return self.B * 2 * 4 * self.d * 3
+
+    def oracle_step(self, orc, t):
+        if not hasattr(self, "host"):
+            self.host = [x.cpu().numpy() for x in self.tables_initial]
+        B = self.B
+        sl = slice(t * B, (t + 1) * B)
+        orc.step_mf(self.host[0], self.host[1], self.d, self.rows[sl], self.cols[sl], self.vals[sl], self.lr, self.l2)
+
+    def config(self):
+        return {"workload": self.name, "task": "MF", "rows": self.n_rows, "cols": self.n_cols, "dim": self.d,
+                "row_stride": self.stride, "batch": self.B, "zipf_s": self.s, "lr": self.lr, "l2": self.l2}
+
+
+class Kge:
+    """ComplEx with AdaGrad; tables 0/1 = entities / relations, each with a state table."""
+
+    def __init__(self, name, n_ent, n_rel, d, B, nh, nt, lr, eps, seed):
+        self.name, self.n_ent, self.n_rel, self.d, self.B, self.nh, self.nt = name, n_ent, n_rel, d, B, nh, nt
+        self.lr, self.eps, self.seed = lr, eps, seed
+        self.unit = "triples"
+
+    def setup(self, nb, wl, total_steps):
+        import torch
+        B = self.B
+        self.s, self.r, self.o = wl.kge_triples(self.n_ent, self.n_rel, total_steps * B, self.seed)
+        self.stride = wl.padded_stride(self.d)
+        if self.stride % 128:
+            self.stride += 64
+        g = torch.Generator(device="cuda").manual_seed(self.seed)
+        half = self.d // 2
+
+        def table(n):
+            t = torch.zeros((n, self.stride), dtype=torch.float32, device="cuda")
+            t[:, :half] = torch.rand((n, half), generator=g, device="cuda") * 0.2 - 0.1
+            t[:, self.stride // 2:self.stride // 2 + half] = torch.rand((n, half), generator=g, device="cuda") * 0.2 - 0.1
+            return t
+
+        self.tables = [table(self.n_ent), table(self.n_rel)]
+        self.states = [torch.zeros_like(self.tables[0]), torch.zeros_like(self.tables[1])]
+        for st in self.states:                                  # a warmed-up accumulator on the logical lanes
+            st[:, :half] = 1e-3
+            st[:, self.stride // 2:self.stride // 2 + half] = 1e-3
+        self.ks, self.kr, self.ko = dev_keys(self.s), dev_keys(self.r), dev_keys(self.o)
+        self.ctx = nb.nups_init(self.tables, [self.d, self.d])
+        nb.nups_set_state(self.ctx, 0, self.states[0])
+        nb.nups_set_state(self.ctx, 1, self.states[1])
+        self.dist = nb.nups_register_distribution(self.ctx, 0, None, nb.NUPS_CONFORM, seed=self.seed)
+        self.nb = nb
+        return total_steps
+
+    def prepare(self, t):
+        nb, B = self.nb, self.B
+        batch = nb.make_batch(nb.NUPS_TASK_KGE, B, self.ks.data_ptr() + 4 * t * B, self.kr.data_ptr() + 4 * t * B,
+                              k2=self.ko.data_ptr() + 4 * t * B, n_neg=self.nh, n_neg2=self.nt, lr=self.lr,
+                              eps=self.eps, dist=self.dist, sample_step=t)
+        return nb.nups_prepare_step(self.ctx, batch)
+
+    def accesses(self):
+        return self.B * (2 + self.nh + self.nt), self.B
+
+    def algorithmic_bytes(self, nu0, nu1):
+        row, B, nn = 4 * self.d, self.B, self.nh + self.nt
+        return {"grad": (nu0 + nu1) * row + 4 * B * (3 + nn) + 4 * B * nn,
+                "apply0": nu0 * row * 4 + 8 * B * nn,              # value and state rows, read + written
+                "apply1": nu1 * row * 4 + 4 * B,
+                "step": (nu0 + nu1) * row * 4 + 4 * B * (3 + nn)}
+
+    def logical_bytes(self):
+        return self.B * (3 + self.nh + self.nt) * 4 * self.d * 5
+
+    def oracle_step(self, orc, t):
+        if not hasattr(self, "host"):
+            self.host = [x.cpu().numpy() for x in self.tables_initial] + [x.cpu().numpy() for x in self.states_initial]
+        B, nn = self.B, self.nh + self.nt
+        sl = slice(t * B, (t + 1) * B)
+        negs = orc.sample_conform(None, self.n_ent, self.seed, 0, t, B * nn)
+        orc.step_kge(self.host[0], self.host[2], self.host[1], self.host[3], self.d, self.s[sl], self.r[sl],
+                     self.o[sl], negs, self.nh, self.nt, self.lr, self.eps)
+
+    def config(self):
+        return {"workload": self.name, "task": "KGE (ComplEx, AdaGrad)", "entities": self.n_ent,
+                "relations": self.n_rel, "dim": self.d, "row_stride": self.stride, "batch": self.B,
+                "negatives": "%d subject + %d object, uniform" % (self.nh, self.nt), "lr": self.lr}
+
+
 WORKLOADS = {
-    # name: V, d, K, scheme, U, G, B, window, zipf s, lr0, tokens in the full stream
-    "sgns_1m_d300_bounded_u4": dict(V=1_000_000, d=300, K=3, U=4, G=250, B=16_384, window=5, s=1.0, lr0=0.025,
-                                    stream_tokens=1_000_000_000, seed=1004),
-    "sgns_10k_d100_conform": dict(V=10_000, d=100, K=5, U=1, G=1, B=4096, window=2, s=1.0, lr0=0.025,
-                                  stream_tokens=1_000_000, seed=1001),
+    "sgns_1m_d300_bounded_u4": lambda: Sgns("sgns_1m_d300_bounded_u4", 1_000_000, 300, 3, 4, 250, 16_384, 5, 1.0,
+                                            0.025, 1_000_000_000, 1004),
+    "sgns_10k_d100_conform": lambda: Sgns("sgns_10k_d100_conform", 10_000, 100, 5, 1, 1, 4096, 2, 1.0, 0.025,
+                                          1_000_000, 1001),
+    "mf_10m_1m_d100": lambda: Mf("mf_10m_1m_d100", 10_000_000, 1_000_000, 100, 65_536, 0.8, 0.005, 0.01, 1002),
+    "kge_4p6m_d500": lambda: Kge("kge_4p6m_d500", 4_600_000, 822, 500, 1024, 50, 50, 0.1, 1e-10, 1003),
 }
 
 
@@ -54,52 +258,29 @@ def main() -> int:
     from paper_2104_00501_amd import binding as nb
     from paper_2104_00501_amd import workloads as wl
 
-    cfg = WORKLOADS[args.workload]
-    V, d, K, U, G, B, window = cfg["V"], cfg["d"], cfg["K"], cfg["U"], cfg["G"], cfg["B"], cfg["window"]
-    total_steps = args.warmup + args.steps
-    epoch_steps = max(1, wl.num_window_pairs(cfg["stream_tokens"], window) // B)
     torch.cuda.set_device(0)
-
-    # ---- inputs, generated once and made resident --------------------------------------------
-    n_tokens = min(cfg["stream_tokens"], total_steps * B // (2 * window) + 2 * window + 2)
-    toks = wl.zipf_stream(V, cfg["s"], n_tokens, cfg["seed"])
-    centers, contexts = wl.window_pairs(toks, window, 0, total_steps * B)
-    total_steps = len(centers) // B
+    w = WORKLOADS[args.workload]()
+    total_steps = w.setup(nb, wl, args.warmup + args.steps)
     steps = total_steps - args.warmup
-    assert steps > 0, "not enough pairs for the requested steps"
-    weights = wl.expected_unigram_weights(V, cfg["s"], cfg["stream_tokens"])
-    In, Out = wl.sgns_tables(V, d, cfg["seed"])
-    stride = In.shape[1]
-
-    def keys(x):
-        return torch.from_numpy(np.ascontiguousarray(x, dtype=np.uint32).view(np.int32)).cuda()
-
-    tin, tout = torch.from_numpy(In).cuda(), torch.from_numpy(Out).cuda()
-    kc, ko = keys(centers), keys(contexts)
-    ctx = nb.nups_init([tin, tout], [d, d])
-    scheme = nb.NUPS_BOUNDED if U > 1 else nb.NUPS_CONFORM
-    dist = nb.nups_register_distribution(ctx, 1, weights, scheme, U=U, G=G, seed=cfg["seed"])
-    lrs = [float(wl.linear_lr(cfg["lr0"], t, epoch_steps)) for t in range(total_steps)]
-
-    def prepare(t):
-        """The key-only half of step t on the library's side stream: draw the negatives, build the plan."""
-        batch = nb.make_batch(nb.NUPS_TASK_SGNS, B, kc.data_ptr() + 4 * t * B, ko.data_ptr() + 4 * t * B,
-                              n_neg=K, lr=lrs[t], dist=dist, sample_step=t)
-        return nb.nups_prepare_step(ctx, batch)
+    assert steps > 0, "not enough examples for the requested steps"
+    ctx, B = w.ctx, w.B
+    if args.cpu_steps != 0 and not isinstance(w, Sgns):       # the oracle starts from the same initial tables
+        w.tables_initial = [t.clone() for t in w.tables]
+        if hasattr(w, "states"):
+            w.states_initial = [t.clone() for t in w.states]
 
     def run(first, count):
         # software pipeline: step t+1 is prepared before step t runs, so the two overlap on the GPU
-        nxt = prepare(first)
+        nxt = w.prepare(first)
         for t in range(first, first + count):
             p = nxt
             if t + 1 < first + count:
-                nxt = prepare(t + 1)
+                nxt = w.prepare(t + 1)
             nb.nups_step_prepared(ctx, p)
 
     # ---- warm-up, then the timed region ---------------------------------------------------------
     run(0, args.warmup)
     nb.nups_check(ctx)
-    snap_in, snap_out = tin.clone(), tout.clone()       # state after warm-up, for the profiling pass
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run(args.warmup, steps)
@@ -108,91 +289,77 @@ def main() -> int:
     nb.nups_check(ctx)
     ms_per_step = 1e3 * elapsed / steps
     value = steps * B / elapsed
+    finite = all(bool(torch.isfinite(t).all().item()) for t in w.tables)
 
-    # ---- per-kernel pass: same steps, HIP events around every phase on the library's stream -----
-    tin.copy_(snap_in)
-    tout.copy_(snap_out)
-    torch.cuda.synchronize()
+    # ---- per-kernel pass: the last steps again, unpipelined, HIP events around every phase on its stream ---
+    n_prof = min(steps, 64)
+    first_prof = total_steps - n_prof
     nb.nups_profile(ctx, True)
-    uk = torch.zeros(B * (K + 1), dtype=torch.int32, device="cuda")
-    uc = torch.zeros(B * (K + 1), dtype=torch.int32, device="cuda")
-    n_struct = min(steps, 32)
-    nu_in = nu_out = 0
-    for t in range(args.warmup, args.warmup + steps):
+    n0, n1 = w.accesses()
+    uk = torch.zeros(max(n0, n1), dtype=torch.int32, device="cuda")
+    uc = torch.zeros(max(n0, n1), dtype=torch.int32, device="cuda")
+    nu0 = nu1 = 0
+    for t in range(first_prof, first_prof + n_prof):
         run(t, 1)
-        if t - args.warmup < n_struct:                   # distinct rows per step, for the algorithmic bytes
-            nu_in += nb.nups_debug_structure(ctx, 0, uk, uc)
-            nu_out += nb.nups_debug_structure(ctx, 1, uk, uc)
-    nu_in /= n_struct
-    nu_out /= n_struct
+        nu0 += nb.nups_debug_structure(ctx, 0, uk, uc)      # distinct rows per step, for the algorithmic bytes
+        nu1 += nb.nups_debug_structure(ctx, 1, uk, uc)
+    nu0 /= n_prof
+    nu1 /= n_prof
     phases = {}
     for p in range(nb.NUPS_PHASE_COUNT):
         ms, n = nb.nups_profile_read(ctx, p)
         if n:
-            phases[nb.nups_phase_name(p)] = {"ms_per_step": ms / steps, "brackets": n}
+            phases[nb.nups_phase_name(p)] = ms / n_prof
     nb.nups_profile(ctx, False)
 
     # a plain copy of known size through the library's own gather kernel (rows 0..n-1 in order): the
     # reference that hardware byte counters are scaled with
-    n_cal = min(V, 262_144)
+    n_cal = min(int(w.tables[0].shape[0]), 262_144)
     cal_keys = torch.arange(n_cal, dtype=torch.int32, device="cuda")
-    cal_out = torch.empty((n_cal, stride), dtype=torch.float32, device="cuda")
+    cal_out = torch.empty((n_cal, w.stride), dtype=torch.float32, device="cuda")
     nb.nups_pull(ctx, 0, cal_keys, n_cal, cal_out)
     torch.cuda.synchronize()
     del cal_out
 
-    # Algorithmic bytes per step under snapshot semantics: every distinct touched row is read once
-    # and written once (4 * d bytes each way), plus the key arrays (4 bytes per access).
-    row_bytes = 4 * d
-    alg = {
-        "grad": (nu_in + nu_out) * row_bytes + 4 * B * (2 + K) + 4 * B * (K + 1),   # read rows, keys; write coefficients
-        "apply0": nu_in * row_bytes * 2 + 4 * B,                                      # input table read-modify-write
-        "apply1": nu_out * row_bytes * 2 + 4 * B * (K + 1) * 2,                       # output table rmw, keys + coefficients
-    }
-    step_alg_bytes = (nu_in + nu_out) * row_bytes * 2 + 4 * B * (2 + K)
-    dominant = max((p for p in alg if p in phases), key=lambda p: phases[p]["ms_per_step"])
-    dom_ms = phases[dominant]["ms_per_step"]
+    # Algorithmic bytes under snapshot semantics: every distinct touched row is read once and written
+    # once (4 * d bytes each way; twice that with optimiser state), plus the key arrays.
+    alg = w.algorithmic_bytes(nu0, nu1)
+    dominant = max((p for p in ("grad", "apply0", "apply1") if p in phases), key=lambda p: phases[p])
+    dom_ms = phases[dominant]
     achieved = alg[dominant] / (dom_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                 "algorithmic_bytes_per_launch": alg[dominant], "kernel_ms": dom_ms,
-                "whole_step_algorithmic_GBps": step_alg_bytes / (ms_per_step * 1e-3) / 1e9,
-                "whole_step_logical_GBps": B * (2 + K) * row_bytes * 3 / (ms_per_step * 1e-3) / 1e9,
-                "distinct_rows_per_step": {"input": nu_in, "output": nu_out}}
+                "per_kernel_GBps": {p: alg[p] / (phases[p] * 1e-3) / 1e9 for p in ("grad", "apply0", "apply1")
+                                    if p in phases},
+                "whole_step_algorithmic_GBps": alg["step"] / (ms_per_step * 1e-3) / 1e9,
+                "whole_step_logical_GBps": w.logical_bytes() / (ms_per_step * 1e-3) / 1e9,
+                "distinct_rows_per_step": {"table0": nu0, "table1": nu1}}
 
     # ---- CPU baseline: the oracle, as it stands, on a prefix of the same steps -------------------
     cpu = None
     if args.cpu_steps != 0:
         from oracle import oracle as orc
-        alias = orc.alias_build(weights)
-        oin, oout = In, Out                              # host tables (fresh initial values)
         n_cpu = args.cpu_steps if args.cpu_steps > 0 else 10 ** 9
-        done, t_cpu = 0, time.perf_counter()
-        while done < min(n_cpu, total_steps):
-            c, o = centers[done * B:(done + 1) * B], contexts[done * B:(done + 1) * B]
-            if U > 1:
-                ng = orc.sample_bounded(alias, V, cfg["seed"], 0, done, B * K, U, G)
-            else:
-                ng = orc.sample_conform(alias, V, cfg["seed"], 0, done, B * K)
-            orc.step_sgns(oin, oout, d, c, o, ng, K, lrs[done])
+        w.oracle_step(orc, 0)                                # first call also builds tables / alias table
+        done, t_cpu = 1, time.perf_counter()
+        while done < min(n_cpu + 1, total_steps):
+            w.oracle_step(orc, done)
             done += 1
             if args.cpu_steps < 0 and time.perf_counter() - t_cpu > 15.0:
                 break
         dt = time.perf_counter() - t_cpu
-        cpu = {"value": done * B / dt, "unit": "positive examples/s", "cores": 1, "kind": "oracle",
-               "sample": "first %d steps of the same workload (%d pairs), single thread, %.1f s" % (done, done * B, dt),
+        cpu = {"value": (done - 1) * B / dt, "unit": "positive examples/s", "cores": 1, "kind": "oracle",
+               "sample": "steps 1..%d of the same workload (%d %s), single thread, %.1f s"
+                         % (done - 1, (done - 1) * B, w.unit, dt),
                "host_cores_available": os.cpu_count()}
 
     out = {
         "metric": "positive examples/sec per step (pull+grad+push)", "value": value, "unit": "positive examples/s",
         "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "num_keys": V, "dim": d, "row_stride": stride, "negatives": K,
-                   "scheme": "BOUNDED U=%d G=%d" % (U, G) if U > 1 else "CONFORM", "batch": B, "window": window,
-                   "zipf_s": cfg["s"], "lr0": cfg["lr0"], "pairs": "stream order"},
-        "roofline": roofline, "phases_ms_per_step": {k: v["ms_per_step"] for k, v in phases.items()},
-        "cpu_baseline": cpu,
-        "finite": bool(torch.isfinite(tin).all().item() and torch.isfinite(tout).all().item()),
+        "config": w.config(), "roofline": roofline, "phases_ms_per_step": phases, "cpu_baseline": cpu,
+        "finite": finite,
     }
     nb.nups_destroy(ctx)
     print(json.dumps(out))
