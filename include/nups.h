@@ -87,8 +87,13 @@ nups_status nups_set_state(nups_ctx *ctx, int table, float *state_dev);
 /*
  * Declares the hot keys of a table (Section 3.2: frequently accessed keys get the
  * technique for hot spots, the long tail the other one).  keys_host holds k distinct
- * keys, hottest first; k = 0 switches the hot path off at no cost.  The set changes
- * how updates are aggregated, never the result beyond fp32 summation order.
+ * keys, hottest first.  Without a declaration the library decides per step: a key whose
+ * accesses in the step exceed a threshold has its updates summed by several workgroups
+ * (LDS pre-aggregation, partial rows combined once), every other key by one row group.
+ * With a declaration only declared keys can take the hot path; k = 0 switches it off
+ * altogether (every key is summed by one row group, nothing extra is launched).  The set
+ * changes how updates are aggregated, never the result beyond fp32 summation order.
+ * Waits for both streams (the set is uploaded synchronously).
  */
 nups_status nups_set_hot_keys(nups_ctx *ctx, int table, const uint32_t *keys_host, int64_t k);
 

@@ -260,7 +260,10 @@ nups_status nups_destroy(nups_ctx *ctx)
     (void)hipStreamSynchronize(ctx->stream);
     for (nups_dist *d : ctx->dists) free_dist(d);
     for (nups_prepared *p : ctx->prepared_all) free_prepared(p);
-    for (int t = 0; t < kMaxTables; ++t) free_plan_scratch(ctx->tab[t].scratch);
+    for (int t = 0; t < kMaxTables; ++t) {
+        free_plan_scratch(ctx->tab[t].scratch);
+        if (ctx->tab[t].hot_bits_dev) (void)hipFree(ctx->tab[t].hot_bits_dev);
+    }
     if (ctx->coef) (void)hipFree(ctx->coef);
     if (ctx->stage) (void)hipFree(ctx->stage);
     if (ctx->partial) (void)hipFree(ctx->partial);
@@ -296,6 +299,14 @@ nups_status nups_set_hot_keys(nups_ctx *ctx, int table, const uint32_t *keys_hos
     if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end())
         return fail(NUPS_ERR_ARG, "nups_set_hot_keys: keys must be distinct");
     if (k > 0 && (int64_t)sorted.back() >= t.num_keys) return fail(NUPS_ERR_KEY_RANGE, "nups_set_hot_keys: key out of range");
+    // membership bitmap on the device; plans built from now on consult it
+    const size_t words = (size_t)((t.num_keys + 31) / 32);
+    std::vector<uint32_t> bits(words, 0u);
+    for (uint32_t key : keys) bits[key >> 5] |= 1u << (key & 31);
+    NUPS_HIP(hipStreamSynchronize(ctx->side));
+    NUPS_HIP(hipStreamSynchronize(ctx->stream));
+    if (!t.hot_bits_dev) NUPS_HIP(hipMalloc((void **)&t.hot_bits_dev, sizeof(uint32_t) * words));
+    NUPS_HIP(hipMemcpy(t.hot_bits_dev, bits.data(), sizeof(uint32_t) * words, hipMemcpyHostToDevice));
     t.hot_keys.swap(keys);
     return NUPS_OK;
 }

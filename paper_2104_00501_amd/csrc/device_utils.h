@@ -158,7 +158,8 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t x, uint32_t *lds)
     return sum;
 }
 
-// Adds one value per workgroup to a double accumulator in memory.
+// Adds one value per workgroup (of WAVES wavefronts) to a double accumulator in memory.
+template <int WAVES = kBlock / 64>
 __device__ __forceinline__ void block_add_loss(float x, double *loss, float *lds)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -167,7 +168,7 @@ __device__ __forceinline__ void block_add_loss(float x, double *loss, float *lds
     __syncthreads();
     if (threadIdx.x == 0) {
         double s = 0.0;
-        for (int w = 0; w < kBlock / 64; ++w) s += (double)lds[w];
+        for (int w = 0; w < WAVES; ++w) s += (double)lds[w];
         atomicAdd(loss, s);
     }
 }
@@ -184,6 +185,15 @@ __device__ __forceinline__ uint32_t xcd_block()
 }
 
 static inline uint32_t xcd_grid(uint32_t blocks) { return (blocks + kNumXcd - 1) / kNumXcd * kNumXcd; }
+
+// Which technique a key gets (Section 3.2: hot spots and the long tail are managed differently).  A segment of
+// `count` accesses is cut into chunks for several workgroups if it is long and, when the caller declared a
+// hot-key set, the key is in it; every other segment is summed by a single row group.
+__device__ __forceinline__ bool takes_hot_path(uint32_t count, uint32_t key, const uint32_t *hot_bits)
+{
+    if (count <= kLongSegment) return false;
+    return hot_bits == nullptr || ((hot_bits[key >> 5] >> (key & 31)) & 1u) != 0;
+}
 
 __device__ __forceinline__ uint32_t source_key(const KeySource &s, uint32_t i)
 {

@@ -58,19 +58,20 @@ struct PlanArgs {
     uint32_t *bitmap;      // [words]     one bit per key, packed from the byte map by every build
     uint32_t *word_rank;   // [words]     number of distinct keys below each bitmap word
     uint32_t *tile_sum;    // [max(bitmap_tiles, count_tiles)]
-    uint32_t *slot;        // [n]         per access: index of its key among the distinct keys
-    uint32_t *rank;        // [n]         per access: position inside its key's segment
     // result, owned by the plan
     uint32_t *uniq;        // [n]         distinct keys, ascending
     uint32_t *count;       // [n]         accesses per distinct key
     uint32_t *seg;         // [n + 1]     exclusive prefix sums of count
     uint32_t *perm;        // [n]         accesses grouped by key
+    uint32_t *slot;        // [n]         per access: index of its key among the distinct keys
+    uint32_t *rank;        // [n]         per access: position inside its key's segment
     uint32_t *chunk_seg;   // [max_chunks]  distinct-key index of the long segment a chunk belongs to
     uint32_t *chunk_base;  // [max_chunks]  number of the first chunk of that segment
     uint32_t *chunk_done;  // [max_chunks]  arrival counter per long segment (at its first chunk), zero between steps
     uint32_t *meta;        // [kMetaWords]
     uint32_t *error_flag;  // shared by the context: bit 0 = key out of range
     double *zero_loss;     // if not null: loss accumulator that the build resets
+    const uint32_t *hot_bits; // explicit hot-key set of the table (one bit per key), or null: decide by segment length
 };
 
 struct Plan {
@@ -82,7 +83,7 @@ struct Plan {
 // Build scratch of one table.
 struct PlanScratch {
     uint8_t *bytemap = nullptr;
-    uint32_t *bitmap = nullptr, *word_rank = nullptr, *tile_sum = nullptr, *slot = nullptr, *rank = nullptr;
+    uint32_t *bitmap = nullptr, *word_rank = nullptr, *tile_sum = nullptr;
     size_t cap_words = 0, cap_tiles = 0, cap_n = 0;
 };
 
@@ -92,7 +93,8 @@ struct Table {
     int64_t num_keys = 0;
     int32_t dim = 0;
     int32_t stride = 0;
-    std::vector<uint32_t> hot_keys;   // hottest first
+    std::vector<uint32_t> hot_keys;   // hottest first (as declared by the caller)
+    uint32_t *hot_bits_dev = nullptr; // [ceil(V/32)] membership bitmap of the declared set; null = none declared
     PlanScratch scratch;
     Plan *last_plan = nullptr;        // structure of the last step / push on this table (owned by a prepared step)
 };

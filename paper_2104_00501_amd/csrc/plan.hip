@@ -209,7 +209,7 @@ __global__ void __launch_bounds__(kBlock) k_plan_count_scan(PlanPair pp)
     for (int j = 0; j < kScanItems; ++j) {
         if (u0 + j < nu) {
             a.seg[u0 + j] = run;
-            if (cnt[j] > kLongSegment) {
+            if (takes_hot_path(cnt[j], a.uniq[u0 + j], a.hot_bits)) {
                 const uint32_t nch = (cnt[j] + kChunk - 1) / kChunk;
                 const uint32_t base = atomicAdd(&a.meta[kMetaNumChunks], nch);
                 for (uint32_t ch = 0; ch < nch; ++ch) {
@@ -252,14 +252,14 @@ size_t max_chunks(size_t n) { return n / kChunk + n / (kLongSegment + 1) + 2; }
 void free_plan_arrays(Plan &pl)
 {
     PlanArgs &a = pl.a;
-    for (uint32_t *p : {a.uniq, a.count, a.seg, a.perm, a.chunk_seg, a.chunk_base, a.chunk_done, a.meta})
+    for (uint32_t *p : {a.uniq, a.count, a.seg, a.perm, a.slot, a.rank, a.chunk_seg, a.chunk_base, a.chunk_done, a.meta})
         if (p) (void)hipFree(p);
     pl = Plan{};
 }
 
 void free_plan_scratch(PlanScratch &sc)
 {
-    for (uint32_t *p : {sc.bitmap, sc.word_rank, sc.tile_sum, sc.slot, sc.rank})
+    for (uint32_t *p : {sc.bitmap, sc.word_rank, sc.tile_sum})
         if (p) (void)hipFree(p);
     if (sc.bytemap) (void)hipFree(sc.bytemap);
     sc = PlanScratch{};
@@ -288,17 +288,11 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
         if ((st = grow_u32(&sc.word_rank, words, false, ctx->side)) != NUPS_OK) return st;
         sc.cap_words = words;
     }
-    if (sc.cap_n < n || sc.cap_n == 0) {
-        if ((st = quiesce(ctx)) != NUPS_OK) return st;
-        const size_t cap = n + n / 4 + 1024;
-        if ((st = grow_u32(&sc.slot, cap, false, ctx->side)) != NUPS_OK) return st;
-        if ((st = grow_u32(&sc.rank, cap, false, ctx->side)) != NUPS_OK) return st;
-        sc.cap_n = cap;
-    }
+    if (sc.cap_n < n || sc.cap_n == 0) sc.cap_n = n + n / 4 + 1024;   // sizes the tile sums below
     if (pl.cap_n < n || pl.cap_n == 0) {
         if ((st = quiesce(ctx)) != NUPS_OK) return st;
         const size_t cap = n + n / 4 + 1024;
-        for (uint32_t **b : {&a.uniq, &a.count, &a.perm})
+        for (uint32_t **b : {&a.uniq, &a.count, &a.perm, &a.slot, &a.rank})
             if ((st = grow_u32(b, cap, false, ctx->side)) != NUPS_OK) return st;
         if ((st = grow_u32(&a.seg, cap + 1, false, ctx->side)) != NUPS_OK) return st;
         if ((st = grow_u32(&a.chunk_seg, max_chunks(cap), false, ctx->side)) != NUPS_OK) return st;
@@ -307,7 +301,8 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
         if ((st = grow_u32(&a.meta, kMetaWords, true, ctx->side)) != NUPS_OK) return st;
         pl.cap_n = cap;
     }
-    const size_t tiles = std::max((words + kScanTile - 1) / kScanTile, (sc.cap_n + kScanTile - 1) / kScanTile);
+    const size_t tiles = std::max((words + kScanTile - 1) / kScanTile,
+                                  (std::max(sc.cap_n, pl.cap_n) + kScanTile - 1) / kScanTile);
     if (sc.cap_tiles < tiles) {
         if ((st = quiesce(ctx)) != NUPS_OK) return st;
         if ((st = grow_u32(&sc.tile_sum, tiles, false, ctx->side)) != NUPS_OK) return st;
@@ -320,11 +315,12 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
         if ((st = ensure_f32(&ctx->partial, &ctx->partial_cap, need_partial, ctx->stream)) != NUPS_OK) return st;
     }
     a.bytemap = sc.bytemap;
-    a.bitmap = sc.bitmap; a.word_rank = sc.word_rank; a.tile_sum = sc.tile_sum; a.slot = sc.slot; a.rank = sc.rank;
+    a.bitmap = sc.bitmap; a.word_rank = sc.word_rank; a.tile_sum = sc.tile_sum;
     a.num_keys = (uint32_t)t.num_keys;
     a.words = (uint32_t)words;
     a.bitmap_tiles = (uint32_t)((words + kScanTile - 1) / kScanTile);
     a.error_flag = ctx->error_flag;
+    a.hot_bits = t.hot_bits_dev;
     return NUPS_OK;
 }
 

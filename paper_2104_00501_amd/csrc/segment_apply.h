@@ -56,14 +56,21 @@ struct SrcKgeEntity {
 };
 
 // ---- update rules ----------------------------------------------------------------------------
+// An update is split in two so that the row (and its state) can be requested from memory before the
+// gradient contributions are summed: load() issues the reads, finish() combines and writes back.
 
 struct OptSgd {          // theta <- theta - lr * delta
     float lr;
+    static constexpr bool kHasState = false;
     template <int NV4>
-    __device__ __forceinline__ void apply(float *row, float *, const Row<NV4> &d, int lane) const
+    __device__ __forceinline__ void load(Row<NV4> &t, Row<NV4> &, const float *row, const float *, int lane) const
     {
-        Row<NV4> t;
         load_row(t, row, lane);
+    }
+    template <int NV4>
+    __device__ __forceinline__ void finish(Row<NV4> &t, Row<NV4> &, float *row, float *, const Row<NV4> &d,
+                                           int lane) const
+    {
 #pragma unroll
         for (int q = 0; q < NV4; ++q) axpy4(t.v[q], -lr, d.v[q]);
         store_row(row, t, lane);
@@ -71,11 +78,16 @@ struct OptSgd {          // theta <- theta - lr * delta
 };
 
 struct OptAdd {          // theta <- theta + delta   (push)
+    static constexpr bool kHasState = false;
     template <int NV4>
-    __device__ __forceinline__ void apply(float *row, float *, const Row<NV4> &d, int lane) const
+    __device__ __forceinline__ void load(Row<NV4> &t, Row<NV4> &, const float *row, const float *, int lane) const
     {
-        Row<NV4> t;
         load_row(t, row, lane);
+    }
+    template <int NV4>
+    __device__ __forceinline__ void finish(Row<NV4> &t, Row<NV4> &, float *row, float *, const Row<NV4> &d,
+                                           int lane) const
+    {
 #pragma unroll
         for (int q = 0; q < NV4; ++q) axpy4(t.v[q], 1.0f, d.v[q]);
         store_row(row, t, lane);
@@ -84,17 +96,23 @@ struct OptAdd {          // theta <- theta + delta   (push)
 
 struct OptAdagrad {      // G <- G + delta^2 ; theta <- theta - lr * delta / (sqrt(G) + eps)
     float lr, eps;
+    static constexpr bool kHasState = true;
     __device__ __forceinline__ void one(float &t, float &g, float d) const
     {
         g += d * d;
         t -= lr * d / (sqrtf(g) + eps);
     }
     template <int NV4>
-    __device__ __forceinline__ void apply(float *row, float *state_row, const Row<NV4> &d, int lane) const
+    __device__ __forceinline__ void load(Row<NV4> &t, Row<NV4> &g, const float *row, const float *state_row,
+                                         int lane) const
     {
-        Row<NV4> t, g;
         load_row(t, row, lane);
         load_row(g, state_row, lane);
+    }
+    template <int NV4>
+    __device__ __forceinline__ void finish(Row<NV4> &t, Row<NV4> &g, float *row, float *state_row,
+                                           const Row<NV4> &d, int lane) const
+    {
 #pragma unroll
         for (int q = 0; q < NV4; ++q) {
             one(t.v[q].x, g.v[q].x, d.v[q].x);
@@ -112,11 +130,13 @@ struct OptAdagrad {      // G <- G + delta^2 ; theta <- theta - lr * delta / (sq
 struct ApplyArgs {
     float *table;
     float *state;
-    const uint32_t *uniq, *seg, *perm, *meta, *chunk_seg, *chunk_base;
+    KeySource keys;        // the accesses' keys (access i -> key), as given to the plan
+    const uint32_t *hot_bits; // the table's declared hot-key set or null (see takes_hot_path)
+    const uint32_t *uniq, *seg, *perm, *slot, *rank, *meta, *chunk_seg, *chunk_base;
     uint32_t *chunk_done;
     float *partial;        // [max_chunks][stride] partial sums of chunked segments
     int stride;
-    uint32_t short_blocks; // workgroups [0, short_blocks) take short segments, the others one chunk each
+    uint32_t n;            // accesses of the plan
 };
 
 // Sums accesses first, first+step, ... < last of a segment into acc (four row loads in flight).
@@ -147,10 +167,16 @@ __device__ __forceinline__ void sum_segment(Row<NV4> &acc, const Src &src, const
 }
 
 // A fixed-size grid walks over the work items of the plan: first one item per chunk (kChunk accesses) of a
-// long segment, then one item per 16 distinct keys (one 16-lane group per key with at most kLongSegment
-// accesses).  For a chunk the 16 groups sum interleaved slices, the slices are combined through LDS in group
-// order, and the workgroup that finishes a segment's last outstanding chunk adds the chunks' partial rows in
-// chunk order and updates the row.  Every workgroup leaves the loop after at most ceil(items / gridDim) turns.
+// long segment, then the short segments (at most kLongSegment accesses), one 16-lane group each.
+// The short segments are walked in one of two orders, chosen from the plan's statistics:
+//  - few repeats (distinct keys > accesses / 2): in access order.  The access that received position 0 of
+//    its segment stands for the segment, its key comes straight from the key array, so the row (and state)
+//    is requested after one dependent read instead of four, and neighbouring accesses (same triple, same
+//    center word) find their source rows in cache.
+//  - many repeats: in key order, one item per 16 distinct keys.
+// For a chunk the 16 groups sum interleaved slices, the slices are combined through LDS in group order, and
+// the workgroup that finishes a segment's last outstanding chunk adds the chunks' partial rows in chunk
+// order and updates the row.  Every workgroup leaves the loop after at most ceil(items / gridDim) turns.
 template <int NV4, class Src, class Opt>
 __global__ void __launch_bounds__(kBlock) k_apply(ApplyArgs a, Src src, Opt opt)
 {
@@ -158,19 +184,39 @@ __global__ void __launch_bounds__(kBlock) k_apply(ApplyArgs a, Src src, Opt opt)
     __shared__ uint32_t last_arrival;
     const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
     const uint32_t nu = a.meta[kMetaNumUniq];
+    const bool access_order = 2 * nu > a.n;
     const uint32_t chunk_items = a.meta[kMetaNumChunks];   // taken first: they are the long poles
-    const uint32_t items = chunk_items + (nu + kGroupsPerBlock - 1) / kGroupsPerBlock;
+    const uint32_t items = chunk_items + ((access_order ? a.n : nu) + kGroupsPerBlock - 1) / kGroupsPerBlock;
     for (uint32_t item = blockIdx.x; item < items; item += gridDim.x) {
         if (item >= chunk_items) {
-            const uint32_t u = (item - chunk_items) * kGroupsPerBlock + group;
-            if (u < nu) {
+            const uint32_t w = (item - chunk_items) * kGroupsPerBlock + group;
+            uint32_t u = kBadIndex, key = 0, only = kBadIndex;
+            if (access_order) {
+                if (w < a.n) {
+                    key = source_key(a.keys, w);
+                    if (a.rank[w] == 0) u = a.slot[w];       // kBadIndex for a key outside the table
+                    only = w;
+                }
+            } else if (w < nu) {
+                u = w;
+                key = a.uniq[w];
+            }
+            if (u != kBadIndex) {
+                const size_t off = (size_t)key * a.stride;
+                Row<NV4> t, g;
+                opt.template load<NV4>(t, g, a.table + off, Opt::kHasState ? a.state + off : nullptr, lane);
                 const uint32_t first = a.seg[u], last = a.seg[u + 1];
-                if (last - first <= kLongSegment) {
+                if (!takes_hot_path(last - first, key, a.hot_bits)) {
                     Row<NV4> acc;
                     zero_row(acc);
-                    sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
-                    const size_t off = (size_t)a.uniq[u] * a.stride;
-                    opt.template apply<NV4>(a.table + off, a.state ? a.state + off : nullptr, acc, lane);
+                    if (last - first == 1 && only != kBadIndex) {      // the segment is this access alone
+                        Row<NV4> r;
+                        load_row(r, src.row(only, a.stride), lane);
+                        axpy_row(acc, src.coef(only), r);
+                    } else {
+                        sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
+                    }
+                    opt.template finish<NV4>(t, g, a.table + off, Opt::kHasState ? a.state + off : nullptr, acc, lane);
                 }
             }
             continue;
@@ -231,7 +277,9 @@ __global__ void __launch_bounds__(kBlock) k_apply(ApplyArgs a, Src src, Opt opt)
         }
         if (update && group == 0) {
             const size_t off = (size_t)a.uniq[u] * a.stride;
-            opt.template apply<NV4>(a.table + off, a.state ? a.state + off : nullptr, acc, lane);
+            Row<NV4> t, g;
+            opt.template load<NV4>(t, g, a.table + off, Opt::kHasState ? a.state + off : nullptr, lane);
+            opt.template finish<NV4>(t, g, a.table + off, Opt::kHasState ? a.state + off : nullptr, acc, lane);
         }
     }
 }
@@ -245,8 +293,8 @@ static void launch_apply_nv(hipStream_t s, const Plan &pl, float *partial, float
     const PlanArgs &p = pl.a;
     if (p.n == 0) return;
     const uint32_t max_items = (p.n + kGroupsPerBlock - 1) / kGroupsPerBlock + (uint32_t)max_chunks(p.n);
-    ApplyArgs a{table, state, p.uniq, p.seg, p.perm, p.meta, p.chunk_seg, p.chunk_base, p.chunk_done, partial,
-                stride, 0};
+    ApplyArgs a{table, state, p.src, p.hot_bits, p.uniq, p.seg, p.perm, p.slot, p.rank, p.meta, p.chunk_seg, p.chunk_base,
+                p.chunk_done, partial, stride, p.n};
     const size_t lds = sizeof(float) * (size_t)(kGroupsPerBlock - 1) * stride;
     hipLaunchKernelGGL((k_apply<NV4, Src, Opt>), dim3(std::min(max_items, kApplyGrid)), dim3(kBlock), lds, s, a, src,
                        opt);

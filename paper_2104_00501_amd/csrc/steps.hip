@@ -320,74 +320,85 @@ __device__ __forceinline__ void add_grad_relation(Row<NV4> &out, const Row<NV4> 
     }
 }
 
-template <int NV4>
-__global__ void __launch_bounds__(kBlock) k_kge_grad(const float *E, const float *R, uint32_t n_ent, uint32_t n_rel,
+// GB = row groups per workgroup (GB * 16 threads); one workgroup per triple.
+template <int NV4, int GB>
+__global__ void __launch_bounds__(GB * kGroup) k_kge_grad(const float *E, const float *R, uint32_t n_ent, uint32_t n_rel,
                                                      int stride, const uint32_t *subj, const uint32_t *rel,
                                                      const uint32_t *obj, const uint32_t *negs, uint32_t B, int nh,
                                                      int nt, float *coefs, float *stage, double *loss)
 {
-    extern __shared__ float part[];   // [kGroupsPerBlock][stride]: per-group weighted row sums
+    extern __shared__ float part[];   // [GB][stride]: per-group weighted row sums
     __shared__ float lds[kBlock / 64];
+    constexpr int kHalf = GB / 2;
+    static_assert(GB >= 8 && GB % 8 == 0, "whole wavefronts per role, at least five groups for the last stage");
     const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
     const uint32_t e = blockIdx.x;
     const int nn = nh + nt;
     const float *s_ptr = E + (size_t)min(subj[e], n_ent - 1) * stride;
     const float *o_ptr = E + (size_t)min(obj[e], n_ent - 1) * stride;
     const float *r_ptr = R + (size_t)min(rel[e], n_rel - 1) * stride;
-    Row<NV4> A, C;
+    // The first half of the groups scores the replaced subjects (dot products with A), the second half the
+    // replaced objects (with C);
+    // each keeps one direction row and one accumulator, and four negative rows in flight.
+    const bool head = group < kHalf;
+    Row<NV4> dir;
     {
         Row<NV4> s, r, o;
+        load_row(r, r_ptr, lane);
+        if (head) { load_row(o, o_ptr, lane); grad_subject<NV4>(dir, r, o); }
+        else { load_row(s, s_ptr, lane); grad_object<NV4>(dir, s, r); }
+    }
+    Row<NV4> wsum;                     // sum of coef * negative row over this group's negatives
+    zero_row(wsum);
+    float loss_acc = 0.f;
+    const int lo = head ? 0 : nh, hi = head ? nh : nn;
+    const uint32_t *my_negs = negs + (size_t)e * nn;
+    for (int i = lo + (group % kHalf); i < hi; i += 4 * kHalf) {
+        const int i1 = i + kHalf, i2 = i + 2 * kHalf, i3 = i + 3 * kHalf;
+        Row<NV4> x0, x1, x2, x3;
+        load_row(x0, E + (size_t)min(my_negs[i], n_ent - 1) * stride, lane);
+        load_row(x1, E + (size_t)min(my_negs[min(i1, hi - 1)], n_ent - 1) * stride, lane);
+        load_row(x2, E + (size_t)min(my_negs[min(i2, hi - 1)], n_ent - 1) * stride, lane);
+        load_row(x3, E + (size_t)min(my_negs[min(i3, hi - 1)], n_ent - 1) * stride, lane);
+        auto one = [&](const Row<NV4> &x, int idx) {
+            const float phi = group_sum(partial_dot(x, dir));
+            const float g = sigmoidf(phi);           // label -1: d softplus(phi) / d phi
+            loss_acc += softplusf(phi);
+            if (lane == 0) coefs[(size_t)e * nn + idx] = g;
+            axpy_row(wsum, g, x);
+        };
+        one(x0, i);
+        if (i1 < hi) one(x1, i1);
+        if (i2 < hi) one(x2, i2);
+        if (i3 < hi) one(x3, i3);
+    }
+    store_row(part + (size_t)group * stride, wsum, lane);
+    __syncthreads();
+    if (group < 5) {
+        Row<NV4> s, r, o, A;
         load_row(s, s_ptr, lane);
         load_row(r, r_ptr, lane);
         load_row(o, o_ptr, lane);
         grad_subject<NV4>(A, r, o);
-        grad_object<NV4>(C, s, r);
-    }
-    Row<NV4> sum_s, sum_o;   // sum of coef * replaced-subject rows / replaced-object rows handled by this group
-    zero_row(sum_s);
-    zero_row(sum_o);
-    float loss_acc = 0.f;
-    for (int i = group; i < nn; i += kGroupsPerBlock) {
-        Row<NV4> x;
-        load_row(x, E + (size_t)min(negs[(size_t)e * nn + i], n_ent - 1) * stride, lane);
-        const bool head = i < nh;
-        const float phi = group_sum(head ? partial_dot(x, A) : partial_dot(x, C));
-        const float g = sigmoidf(phi);               // label -1: d softplus(phi) / d phi
-        loss_acc += softplusf(phi);
-        if (lane == 0) coefs[(size_t)e * nn + i] = g;
-        if (head) axpy_row(sum_s, g, x); else axpy_row(sum_o, g, x);
-    }
-    // weighted row sums over all groups, in a fixed order; the LDS buffer is used twice
-    Row<NV4> ws, wo;                                 // sums of coef * replaced-subject / replaced-object rows
-    zero_row(ws);
-    zero_row(wo);
-    store_row(part + (size_t)group * stride, sum_s, lane);
-    __syncthreads();
-    if (group == 1 || group == 4) {
-        for (int g2 = 0; g2 < kGroupsPerBlock; ++g2) {
-            Row<NV4> t;
-            load_row(t, part + (size_t)g2 * stride, lane);
-            axpy_row(ws, 1.0f, t);
-        }
-    }
-    __syncthreads();
-    store_row(part + (size_t)group * stride, sum_o, lane);
-    __syncthreads();
-    if (group == 0 || group == 4) {
-        for (int g2 = 0; g2 < kGroupsPerBlock; ++g2) {
-            Row<NV4> t;
-            load_row(t, part + (size_t)g2 * stride, lane);
-            axpy_row(wo, 1.0f, t);
-        }
-    }
-    if (group < 5) {
-        Row<NV4> s, r, o;
-        load_row(s, s_ptr, lane);
-        load_row(r, r_ptr, lane);
-        load_row(o, o_ptr, lane);
         const float phi = group_sum(partial_dot(s, A));
         const float gp = -sigmoidf(-phi);            // label +1: d softplus(-phi) / d phi
         if (group == 0) loss_acc += softplusf(-phi);
+        // weighted sums of the replaced-subject rows (first half of the groups) and replaced-object rows, fixed order
+        Row<NV4> ws, wo;
+        zero_row(ws);
+        zero_row(wo);
+        if (group == 1 || group == 4)
+            for (int g2 = 0; g2 < kHalf; ++g2) {
+                Row<NV4> t;
+                load_row(t, part + (size_t)g2 * stride, lane);
+                axpy_row(ws, 1.0f, t);
+            }
+        if (group == 0 || group == 4)
+            for (int g2 = kHalf; g2 < GB; ++g2) {
+                Row<NV4> t;
+                load_row(t, part + (size_t)g2 * stride, lane);
+                axpy_row(wo, 1.0f, t);
+            }
         Row<NV4> out;
         if (group == 0) {            // subject gradient: d score/d s is linear in o
             axpy_row(wo, gp, o);
@@ -400,7 +411,8 @@ __global__ void __launch_bounds__(kBlock) k_kge_grad(const float *E, const float
         } else if (group == 2) {
             store_row(stage + ((size_t)2 * B + e) * stride, A, lane);
         } else if (group == 3) {
-            store_row(stage + ((size_t)3 * B + e) * stride, C, lane);
+            grad_object<NV4>(out, s, r);
+            store_row(stage + ((size_t)3 * B + e) * stride, out, lane);
         } else {                     // relation gradient: bilinear in (s, o)
             zero_row(out);
             axpy_row(wo, gp, o);
@@ -409,15 +421,18 @@ __global__ void __launch_bounds__(kBlock) k_kge_grad(const float *E, const float
             store_row(stage + ((size_t)4 * B + e) * stride, out, lane);
         }
     }
-    block_add_loss(lane == 0 ? loss_acc : 0.f, loss, lds);
+    block_add_loss<GB * kGroup / 64>(lane == 0 ? loss_acc : 0.f, loss, lds);
 }
 
 template <int NV4>
 static void launch_kge_grad(nups_ctx *ctx, const nups_batch &b)
 {
+    // 128-thread workgroups: at two wavefronts per SIMD (the kernel needs ~250 registers for four rows in
+    // flight) the 1,024 triples of a step are then all resident at once instead of in two rounds.
+    constexpr int GB = 8;
     const Table &te = ctx->tab[0], &tr = ctx->tab[1];
-    const size_t lds = sizeof(float) * kGroupsPerBlock * (size_t)te.stride;
-    hipLaunchKernelGGL(k_kge_grad<NV4>, dim3((uint32_t)b.B), dim3(kBlock), lds, ctx->stream, (const float *)te.data,
+    const size_t lds = sizeof(float) * GB * (size_t)te.stride;
+    hipLaunchKernelGGL((k_kge_grad<NV4, GB>), dim3((uint32_t)b.B), dim3(GB * kGroup), lds, ctx->stream, (const float *)te.data,
                        (const float *)tr.data, (uint32_t)te.num_keys, (uint32_t)tr.num_keys, te.stride, b.k0, b.k1,
                        b.k2, b.negs, (uint32_t)b.B, (int)b.n_neg, (int)b.n_neg2, ctx->coef, ctx->stage, ctx->loss_cur);
 }

@@ -323,3 +323,78 @@ def test_sgns_pipelined_steps_match_the_oracle():
     _assert_close(tin.cpu().numpy(), rin, cols, 1e-4, "input table after 12 pipelined steps")
     _assert_close(tout.cpu().numpy(), rout, cols, 1e-4, "output table after 12 pipelined steps")
     nb.nups_destroy(ctx)
+
+
+@pytest.mark.parametrize("s", [0.6, 1.4])
+def test_hot_key_set_changes_speed_not_results(s):
+    # skew sweep shape: 500k keys, d = 200, 5 negatives, B = 8192; hot sets of 0, 1k, 16k keys and no declaration
+    V, d, B, K, window = 500_000, 200, 8192, 5, 5
+    toks = wl.zipf_stream(V, s, B // (2 * window) + 2 * window + 2, 1005)
+    c, o = wl.window_pairs(toks, window, 0, B)
+    w = wl.expected_unigram_weights(V, s, 2e8)
+    In, Out = wl.sgns_tables(V, d, 1005)
+    Out[:] = wl.uniform_table(V, d, -0.5 / d, 0.5 / d, 1006)
+    negs = orc.sample_conform(orc.alias_build(w), V, 5, 0, 0, B * K)
+    rin, rout = In.copy(), Out.copy()
+    _, s_in, s_out = orc.step_sgns(rin, rout, d, c, o, negs, K, 0.001)
+    assert s_in.counts.max() > 16                       # there are hot keys in the batch
+    results = []
+    for hot in (None, 0, 1000, 16_000):
+        tin, tout = dev(In), dev(Out)
+        ctx = nb.nups_init([tin, tout], [d, d])
+        if hot is not None:
+            nb.nups_set_hot_keys(ctx, 0, np.arange(hot, dtype=np.uint32))     # keys are frequency ranks
+            nb.nups_set_hot_keys(ctx, 1, np.arange(hot, dtype=np.uint32))
+        kc, ko, kn = dev_u32(c), dev_u32(o), dev_u32(negs)
+        nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_SGNS, B, kc, ko, n_neg=K, lr=0.001, negs=kn), want_loss=True)
+        _assert_structure(ctx, 0, B, s_in)
+        _assert_structure(ctx, 1, B * (K + 1), s_out)
+        gi, go = tin.cpu().numpy(), tout.cpu().numpy()
+        # with the hot path switched off one row group adds up thousands of contributions to the hottest key one
+        # after the other in fp32: the rounding error of that long chain is what the looser bar allows for
+        tol = TOL_ONE_STEP if hot != 0 else 1e-4
+        _assert_close(gi, rin, list(range(d)), tol, "input table, hot set %s" % hot, In if hot != 0 else None)
+        _assert_close(go, rout, list(range(d)), tol, "output table, hot set %s" % hot, Out if hot != 0 else None)
+        results.append((gi, go))
+        nb.nups_destroy(ctx)
+    with pytest.raises(nb.NupsError):
+        ctx = nb.nups_init([dev(In[:10]), dev(Out[:10])], [d, d])
+        try:
+            nb.nups_set_hot_keys(ctx, 0, np.array([3, 3], dtype=np.uint32))   # duplicates are rejected
+        finally:
+            nb.nups_destroy(ctx)
+
+
+@pytest.mark.parametrize("scheme", ["longterm", "nonconform"])
+def test_sgns_step_with_the_other_sampling_schemes(scheme):
+    V, d, B, K, window, lr = 20_000, 200, 4096, 5, 5, 0.002
+    toks = wl.zipf_stream(V, 1.0, 3 * B // (2 * window) + 2 * window + 2, 31)
+    w = wl.unigram_weights(toks, V)
+    In, Out = wl.sgns_tables(V, d, 31)
+    Out[:] = wl.uniform_table(V, d, -0.5 / d, 0.5 / d, 32)
+    tin, tout = dev(In), dev(Out)
+    ctx = nb.nups_init([tin, tout], [d, d])
+    alias = orc.alias_build(w)
+    rin, rout = In.copy(), Out.copy()
+    if scheme == "longterm":
+        P, R = 10_000, 4
+        dist = nb.nups_register_distribution(ctx, 1, w, nb.NUPS_LONGTERM, P=P, R=R, seed=9)
+    else:
+        dist = nb.nups_register_distribution(ctx, 1, None, nb.NUPS_NONCONFORM, seed=9)
+    for t in range(3):
+        c, o = wl.window_pairs(toks, window, t * B, B)
+        kc, ko = dev_u32(c), dev_u32(o)
+        if scheme == "longterm":
+            negs = orc.sample_longterm(alias, V, 9, 0, P, R, t * B * K, B * K)
+        else:
+            nb.nups_set_local_keys(dist, ko, ko, B, K, K, 1024)
+            negs = orc.sample_nonconform(o, o, K, K, 1024, 9, 0, t, B * K)
+            assert set(negs) <= set(o)
+        loss = nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_SGNS, B, kc, ko, n_neg=K, lr=lr, dist=dist, sample_step=t),
+                            want_loss=True)
+        rloss, s_in, s_out = orc.step_sgns(rin, rout, d, c, o, negs, K, lr)
+        _assert_structure(ctx, 1, B * (K + 1), s_out)
+        assert abs(loss - rloss) <= 1e-5 * abs(rloss)
+    _assert_close(tin.cpu().numpy(), rin, list(range(d)), 3e-5, "input table, %s" % scheme)
+    _assert_close(tout.cpu().numpy(), rout, list(range(d)), 3e-5, "output table, %s" % scheme)
+    nb.nups_destroy(ctx)
