@@ -42,9 +42,12 @@ def dev_keys(x):
 class Sgns:
     """Skip-gram with negative sampling; tables 0/1 = input/output vectors."""
 
-    def __init__(self, name, V, d, K, U, G, B, window, s, lr0, stream_tokens, seed):
+    def __init__(self, name, V, d, K, U, G, B, window, s, lr0, stream_tokens, seed, scheme=None, hot=None,
+                 decay=True):
         self.name, self.V, self.d, self.K, self.U, self.G, self.B = name, V, d, K, U, G, B
         self.window, self.s, self.lr0, self.stream_tokens, self.seed = window, s, lr0, stream_tokens, seed
+        self.scheme = scheme or ("BOUNDED" if U > 1 else "CONFORM")
+        self.hot, self.decay = hot, decay       # hot: None = decided per step, else the top-`hot` keys are declared
         self.unit = "pairs"
 
     def setup(self, nb, wl, total_steps):
@@ -60,15 +63,24 @@ class Sgns:
         self.tables = [torch.from_numpy(self.In).cuda(), torch.from_numpy(self.Out).cuda()]
         self.kc, self.ko = dev_keys(self.centers), dev_keys(self.contexts)
         self.ctx = nb.nups_init(self.tables, [self.d, self.d])
-        scheme = nb.NUPS_BOUNDED if self.U > 1 else nb.NUPS_CONFORM
-        self.dist = nb.nups_register_distribution(self.ctx, 1, self.weights, scheme, U=self.U, G=self.G, seed=self.seed)
+        code = {"CONFORM": nb.NUPS_CONFORM, "BOUNDED": nb.NUPS_BOUNDED, "LONGTERM": nb.NUPS_LONGTERM,
+                "NONCONFORM": nb.NUPS_NONCONFORM}[self.scheme]
+        self.dist = nb.nups_register_distribution(self.ctx, 1, None if code == nb.NUPS_NONCONFORM else self.weights,
+                                                  code, U=self.U, G=self.G, P=1_000_000, R=16, seed=self.seed)
+        if self.hot is not None:                 # keys are frequency ranks: the top-k keys are 0..k-1
+            for table in (0, 1):
+                nb.nups_set_hot_keys(self.ctx, table, np.arange(self.hot, dtype=np.uint32))
         epoch_steps = max(1, wl.num_window_pairs(self.stream_tokens, window) // B)
-        self.lrs = [float(wl.linear_lr(self.lr0, t, epoch_steps)) for t in range(total_steps)]
+        self.lrs = [float(wl.linear_lr(self.lr0, t, epoch_steps)) if self.decay else self.lr0
+                    for t in range(total_steps)]
         self.nb = nb
         return total_steps
 
     def prepare(self, t):
         nb, B = self.nb, self.B
+        if self.scheme == "NONCONFORM":          # negatives are context words of other pairs of the batch
+            nb.nups_set_local_keys(self.dist, self.ko.data_ptr() + 4 * t * B, self.ko.data_ptr() + 4 * t * B, B,
+                                   self.K, self.K, B)
         batch = nb.make_batch(nb.NUPS_TASK_SGNS, B, self.kc.data_ptr() + 4 * t * B, self.ko.data_ptr() + 4 * t * B,
                               n_neg=self.K, lr=self.lrs[t], dist=self.dist, sample_step=t)
         return nb.nups_prepare_step(self.ctx, batch)
@@ -91,15 +103,21 @@ class Sgns:
             self.alias = orc.alias_build(self.weights)
         B, K = self.B, self.K
         c, o = self.centers[t * B:(t + 1) * B], self.contexts[t * B:(t + 1) * B]
-        if self.U > 1:
+        if self.scheme == "BOUNDED":
             ng = orc.sample_bounded(self.alias, self.V, self.seed, 0, t, B * K, self.U, self.G)
+        elif self.scheme == "LONGTERM":
+            ng = orc.sample_longterm(self.alias, self.V, self.seed, 0, 1_000_000, 16, t * B * K, B * K)
+        elif self.scheme == "NONCONFORM":
+            ng = orc.sample_nonconform(o, o, K, K, B, self.seed, 0, t, B * K)
         else:
             ng = orc.sample_conform(self.alias, self.V, self.seed, 0, t, B * K)
         orc.step_sgns(self.In, self.Out, self.d, c, o, ng, K, self.lrs[t])
 
     def config(self):
         return {"workload": self.name, "task": "SGNS", "num_keys": self.V, "dim": self.d, "row_stride": self.stride,
-                "negatives": self.K, "scheme": "BOUNDED U=%d G=%d" % (self.U, self.G) if self.U > 1 else "CONFORM",
+                "negatives": self.K, "hot_keys": "per step" if self.hot is None else self.hot,
+                "scheme": {"BOUNDED": "BOUNDED U=%d G=%d" % (self.U, self.G), "LONGTERM": "LONG-TERM P=1e6 R=16"}.get(
+                    self.scheme, self.scheme),
                 "batch": self.B, "window": self.window, "zipf_s": self.s, "lr0": self.lr0, "pairs": "stream order"}
 
 
@@ -231,6 +249,19 @@ class Kge:
                 "negatives": "%d subject + %d object, uniform" % (self.nh, self.nt), "lr": self.lr}
 
 
+def _sweep_workloads():
+    """The skew / technique / scheme grid: 500k keys, d = 200, 5 negatives, batches of 8,192 pairs."""
+    out = {}
+    for s_exp in (0.6, 1.0, 1.4):
+        for hot in (0, 1000, 16000):
+            for scheme, U in (("CONFORM", 1), ("BOUNDED", 16), ("LONGTERM", 1), ("NONCONFORM", 1)):
+                name = "sweep_s%.1f_top%d_%s" % (s_exp, hot, scheme.lower())
+                out[name] = (lambda n=name, s_=s_exp, h=hot, sc=scheme, u=U:
+                             Sgns(n, 500_000, 200, 5, u, 250, 8192, 5, s_, 0.025, 200_000_000, 1005, scheme=sc, hot=h,
+                                  decay=False))
+    return out
+
+
 WORKLOADS = {
     "sgns_1m_d300_bounded_u4": lambda: Sgns("sgns_1m_d300_bounded_u4", 1_000_000, 300, 3, 4, 250, 16_384, 5, 1.0,
                                             0.025, 1_000_000_000, 1004),
@@ -239,6 +270,7 @@ WORKLOADS = {
     "mf_10m_1m_d100": lambda: Mf("mf_10m_1m_d100", 10_000_000, 1_000_000, 100, 65_536, 0.8, 0.005, 0.01, 1002),
     "kge_4p6m_d500": lambda: Kge("kge_4p6m_d500", 4_600_000, 822, 500, 1024, 50, 50, 0.1, 1e-10, 1003),
 }
+WORKLOADS.update(_sweep_workloads())
 
 
 def main() -> int:
