@@ -356,14 +356,16 @@ def main() -> int:
     # Algorithmic bytes under snapshot semantics: every distinct touched row is read once and written
     # once (4 * d bytes each way; twice that with optimiser state), plus the key arrays.
     alg = w.algorithmic_bytes(nu0, nu1)
-    dominant = max((p for p in ("grad", "apply0", "apply1") if p in phases), key=lambda p: phases[p])
+    if "apply1" not in phases:        # both tables are updated by one launch, timed as "apply0"
+        alg["apply0"] += alg.pop("apply1")
+    dominant = max((p for p in ("grad", "apply0", "apply1") if p in phases and p in alg), key=lambda p: phases[p])
     dom_ms = phases[dominant]
     achieved = alg[dominant] / (dom_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                 "algorithmic_bytes_per_launch": alg[dominant], "kernel_ms": dom_ms,
                 "per_kernel_GBps": {p: alg[p] / (phases[p] * 1e-3) / 1e9 for p in ("grad", "apply0", "apply1")
-                                    if p in phases},
+                                    if p in phases and p in alg},
                 "whole_step_algorithmic_GBps": alg["step"] / (ms_per_step * 1e-3) / 1e9,
                 "whole_step_logical_GBps": w.logical_bytes() / (ms_per_step * 1e-3) / 1e9,
                 "distinct_rows_per_step": {"table0": nu0, "table1": nu1}}

@@ -333,6 +333,7 @@ nups_status nups_push(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_
     p->plan[0].a.src = KeySource{{keys_dev, nullptr, nullptr}, {(uint32_t)n, 0, 0}};
     p->plan[0].a.n = (uint32_t)n;
     p->plan[0].a.zero_loss = nullptr;
+    if ((st = ensure_partial(ctx, max_chunks(p->plan[0].cap_n) * (size_t)t.stride)) != NUPS_OK) return st;
     if ((st = side_after_main(ctx)) != NUPS_OK) return st;
     if ((st = build_plans(ctx, p->plan, 1)) != NUPS_OK) return st;
     NUPS_HIP(hipEventRecord(p->ready, ctx->side));

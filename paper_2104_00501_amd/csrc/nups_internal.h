@@ -201,5 +201,6 @@ nups_status run_step_mf(nups_ctx *ctx, nups_prepared &p);
 nups_status run_step_kge(nups_ctx *ctx, nups_prepared &p);
 nups_status ensure_f32(float **buf, size_t *cap, size_t need, hipStream_t stream);
 size_t max_chunks(size_t n);
+nups_status ensure_partial(nups_ctx *ctx, size_t need);
 
 }  // namespace nups

@@ -249,6 +249,14 @@ static nups_status grow_u32(uint32_t **buf, size_t n, bool zero, hipStream_t str
 
 size_t max_chunks(size_t n) { return n / kChunk + n / (kLongSegment + 1) + 2; }
 
+// Room for `need` floats of partial rows of chunked segments; growing waits for both streams.
+nups_status ensure_partial(nups_ctx *ctx, size_t need)
+{
+    if (ctx->partial_cap >= need && ctx->partial) return NUPS_OK;
+    NUPS_HIP(hipStreamSynchronize(ctx->side));
+    return ensure_f32(&ctx->partial, &ctx->partial_cap, need, ctx->stream);
+}
+
 void free_plan_arrays(Plan &pl)
 {
     PlanArgs &a = pl.a;
@@ -307,12 +315,6 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
         if ((st = quiesce(ctx)) != NUPS_OK) return st;
         if ((st = grow_u32(&sc.tile_sum, tiles, false, ctx->side)) != NUPS_OK) return st;
         sc.cap_tiles = tiles;
-    }
-    // partial rows of chunked segments (one buffer per context: the tables' updates run one after another)
-    const size_t need_partial = max_chunks(pl.cap_n) * (size_t)t.stride;
-    if (ctx->partial_cap < need_partial) {
-        if ((st = quiesce(ctx)) != NUPS_OK) return st;
-        if ((st = ensure_f32(&ctx->partial, &ctx->partial_cap, need_partial, ctx->stream)) != NUPS_OK) return st;
     }
     a.bytemap = sc.bytemap;
     a.bitmap = sc.bitmap; a.word_rank = sc.word_rank; a.tile_sum = sc.tile_sum;

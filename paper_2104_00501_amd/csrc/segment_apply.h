@@ -22,12 +22,14 @@ struct SrcStaged {
 };
 
 // SGNS output side: access i < B is the context word of pair i, access B + p is negative p (pair p / K).
-// The gradient of the scored row is coef * (input vector of the pair's center word).
+// The gradient of the scored row is coef * (input vector of the pair's center word, as it was at the start of
+// the step).  Those vectors are read from a staged copy, one row per distinct center word (row number = the
+// pair's slot in the input table's plan), so that the input table may be updated at the same time.
 struct SrcSgnsOut {
-    const float *in_table;
-    const uint32_t *center;
-    const float *coefs;   // [B, K + 1]
-    uint32_t B, K, num_in;
+    const float *center_rows;     // [distinct centers][stride]
+    const uint32_t *center_slot;  // [B] slot of each pair's center word
+    const float *coefs;           // [B, K + 1]
+    uint32_t B, K;
     __device__ __forceinline__ uint32_t pair_of(uint32_t i) const { return i < B ? i : (i - B) / K; }
     __device__ __forceinline__ float coef(uint32_t i) const
     {
@@ -35,7 +37,8 @@ struct SrcSgnsOut {
     }
     __device__ __forceinline__ const float *row(uint32_t i, int stride) const
     {
-        return in_table + (size_t)min(center[pair_of(i)], num_in - 1) * stride;
+        const uint32_t slot = center_slot[pair_of(i)];
+        return center_rows + (size_t)(slot == kBadIndex ? 0u : slot) * stride;   // bad center key: flagged, row 0 used
     }
 };
 
@@ -166,156 +169,251 @@ __device__ __forceinline__ void sum_segment(Row<NV4> &acc, const Src &src, const
     }
 }
 
-// A fixed-size grid walks over the work items of the plan: first one item per chunk (kChunk accesses) of a
-// long segment, then the short segments (at most kLongSegment accesses), one 16-lane group each.
+// Work items of a plan: one per chunk (kChunk accesses) of a long segment, and the short segments (at most
+// kLongSegment accesses, or any length if the key is not in a declared hot set), one 16-lane group each.
 // The short segments are walked in one of two orders, chosen from the plan's statistics:
 //  - few repeats (distinct keys > accesses / 2): in access order.  The access that received position 0 of
 //    its segment stands for the segment, its key comes straight from the key array, so the row (and state)
 //    is requested after one dependent read instead of four, and neighbouring accesses (same triple, same
 //    center word) find their source rows in cache.
 //  - many repeats: in key order, one item per 16 distinct keys.
-// For a chunk the 16 groups sum interleaved slices, the slices are combined through LDS in group order, and
-// the workgroup that finishes a segment's last outstanding chunk adds the chunks' partial rows in chunk
-// order and updates the row.  Every workgroup leaves the loop after at most ceil(items / gridDim) turns.
+struct ApplyShape {
+    uint32_t nu, chunk_items, short_items;
+    bool access_order;
+};
+
+__device__ __forceinline__ ApplyShape apply_shape(const ApplyArgs &a)
+{
+    ApplyShape sh;
+    sh.nu = a.meta[kMetaNumUniq];
+    sh.chunk_items = a.meta[kMetaNumChunks];
+    sh.access_order = 2 * sh.nu > a.n;
+    sh.short_items = ((sh.access_order ? a.n : sh.nu) + kGroupsPerBlock - 1) / kGroupsPerBlock;
+    return sh;
+}
+
+// One item of short segments: this group's segment, if it has one.
+template <int NV4, class Src, class Opt>
+__device__ __forceinline__ void apply_short_item(const ApplyArgs &a, const Src &src, const Opt &opt,
+                                                 const ApplyShape &sh, uint32_t item, int lane, int group)
+{
+    const uint32_t w = item * kGroupsPerBlock + group;
+    uint32_t u = kBadIndex, key = 0, only = kBadIndex;
+    if (sh.access_order) {
+        if (w < a.n) {
+            key = source_key(a.keys, w);
+            if (a.rank[w] == 0) u = a.slot[w];       // kBadIndex for a key outside the table
+            only = w;
+        }
+    } else if (w < sh.nu) {
+        u = w;
+        key = a.uniq[w];
+    }
+    if (u == kBadIndex) return;
+    const size_t off = (size_t)key * a.stride;
+    float *row = a.table + off, *state_row = Opt::kHasState ? a.state + off : nullptr;
+    const uint32_t first = a.seg[u], last = a.seg[u + 1];
+    if (takes_hot_path(last - first, key, a.hot_bits)) return;   // summed by chunk items
+    Row<NV4> acc, t, g;
+    zero_row(acc);
+    if (last - first == 1 && only != kBadIndex) {
+        // the segment is this access alone: the row, its state and the source row are requested together
+        opt.template load<NV4>(t, g, row, state_row, lane);
+        Row<NV4> r;
+        load_row(r, src.row(only, a.stride), lane);
+        axpy_row(acc, src.coef(only), r);
+    } else {
+        sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
+        opt.template load<NV4>(t, g, row, state_row, lane);
+    }
+    opt.template finish<NV4>(t, g, row, state_row, acc, lane);
+}
+
+// One chunk of a long segment, by the whole workgroup: the 16 groups sum interleaved slices, the slices are
+// combined through LDS in group order, and the workgroup that finishes a segment's last outstanding chunk adds
+// the chunks' partial rows in chunk order and updates the row.  Contains workgroup barriers: every thread of
+// the workgroup must call it with the same `id`.
+template <int NV4, class Src, class Opt>
+__device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &src, const Opt &opt, uint32_t id,
+                                                 float *part, uint32_t *last_arrival, int lane, int group)
+{
+    const uint32_t u = a.chunk_seg[id], base = a.chunk_base[id];
+    const uint32_t first = a.seg[u], last = a.seg[u + 1];
+    const uint32_t nch = (last - first + kChunk - 1) / kChunk;
+    const uint32_t cf = first + (id - base) * kChunk, cl = min(cf + kChunk, last);
+    Row<NV4> acc;
+    zero_row(acc);
+    sum_segment<NV4>(acc, src, a.perm, cf + group, cl, kGroupsPerBlock, a.stride, lane);
+    __syncthreads();                  // LDS of the previous item has been read
+    if (group > 0) store_row(part + (size_t)(group - 1) * a.stride, acc, lane);
+    __syncthreads();
+    if (group == 0) {
+        for (int g = 1; g < kGroupsPerBlock; ++g) {
+            Row<NV4> r;
+            load_row(r, part + (size_t)(g - 1) * a.stride, lane);
+            axpy_row(acc, 1.0f, r);
+        }
+        if (nch > 1) {
+            store_row(a.partial + (size_t)id * a.stride, acc, lane);
+            __threadfence();          // the partial row is visible before the arrival is counted
+        }
+    }
+    bool update = true;
+    if (nch > 1) {
+        __syncthreads();
+        if (threadIdx.x == 0) *last_arrival = (atomicAdd(&a.chunk_done[base], 1u) == nch - 1) ? 1u : 0u;
+        __syncthreads();
+        update = *last_arrival != 0;
+        if (update) {
+            __threadfence();          // the other chunks' partial rows are visible after their arrivals
+            if (group == 0) {        // chunk order, four partial rows in flight
+                zero_row(acc);
+                const float *prow = a.partial + (size_t)base * a.stride;
+                uint32_t ch = 0;
+                for (; ch + 3 < nch; ch += 4) {
+                    Row<NV4> r0, r1, r2, r3;
+                    load_row(r0, prow + (size_t)ch * a.stride, lane);
+                    load_row(r1, prow + (size_t)(ch + 1) * a.stride, lane);
+                    load_row(r2, prow + (size_t)(ch + 2) * a.stride, lane);
+                    load_row(r3, prow + (size_t)(ch + 3) * a.stride, lane);
+                    axpy_row(acc, 1.0f, r0);
+                    axpy_row(acc, 1.0f, r1);
+                    axpy_row(acc, 1.0f, r2);
+                    axpy_row(acc, 1.0f, r3);
+                }
+                for (; ch < nch; ++ch) {
+                    Row<NV4> r;
+                    load_row(r, prow + (size_t)ch * a.stride, lane);
+                    axpy_row(acc, 1.0f, r);
+                }
+            }
+            if (threadIdx.x == 0) a.chunk_done[base] = 0u;   // ready for the next step
+        }
+    }
+    if (update && group == 0) {
+        const size_t off = (size_t)a.uniq[u] * a.stride;
+        Row<NV4> t, g;
+        opt.template load<NV4>(t, g, a.table + off, Opt::kHasState ? a.state + off : nullptr, lane);
+        opt.template finish<NV4>(t, g, a.table + off, Opt::kHasState ? a.state + off : nullptr, acc, lane);
+    }
+}
+
+// Updates one table.  A fixed-size grid walks over the items, chunks first (they are the long poles); every
+// workgroup leaves the loop after at most ceil(items / gridDim) turns.
 template <int NV4, class Src, class Opt>
 __global__ void __launch_bounds__(kBlock) k_apply(ApplyArgs a, Src src, Opt opt)
 {
     extern __shared__ float part[];   // [kGroupsPerBlock - 1][stride]
     __shared__ uint32_t last_arrival;
     const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
-    const uint32_t nu = a.meta[kMetaNumUniq];
-    const bool access_order = 2 * nu > a.n;
-    const uint32_t chunk_items = a.meta[kMetaNumChunks];   // taken first: they are the long poles
-    const uint32_t items = chunk_items + ((access_order ? a.n : nu) + kGroupsPerBlock - 1) / kGroupsPerBlock;
+    const ApplyShape sh = apply_shape(a);
+    const uint32_t items = sh.chunk_items + sh.short_items;
     for (uint32_t item = blockIdx.x; item < items; item += gridDim.x) {
-        if (item >= chunk_items) {
-            const uint32_t w = (item - chunk_items) * kGroupsPerBlock + group;
-            uint32_t u = kBadIndex, key = 0, only = kBadIndex;
-            if (access_order) {
-                if (w < a.n) {
-                    key = source_key(a.keys, w);
-                    if (a.rank[w] == 0) u = a.slot[w];       // kBadIndex for a key outside the table
-                    only = w;
-                }
-            } else if (w < nu) {
-                u = w;
-                key = a.uniq[w];
-            }
-            if (u != kBadIndex) {
-                const size_t off = (size_t)key * a.stride;
-                Row<NV4> t, g;
-                opt.template load<NV4>(t, g, a.table + off, Opt::kHasState ? a.state + off : nullptr, lane);
-                const uint32_t first = a.seg[u], last = a.seg[u + 1];
-                if (!takes_hot_path(last - first, key, a.hot_bits)) {
-                    Row<NV4> acc;
-                    zero_row(acc);
-                    if (last - first == 1 && only != kBadIndex) {      // the segment is this access alone
-                        Row<NV4> r;
-                        load_row(r, src.row(only, a.stride), lane);
-                        axpy_row(acc, src.coef(only), r);
-                    } else {
-                        sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
-                    }
-                    opt.template finish<NV4>(t, g, a.table + off, Opt::kHasState ? a.state + off : nullptr, acc, lane);
-                }
-            }
-            continue;
-        }
-        const uint32_t id = item;
-        const uint32_t u = a.chunk_seg[id], base = a.chunk_base[id];
-        const uint32_t first = a.seg[u], last = a.seg[u + 1];
-        const uint32_t nch = (last - first + kChunk - 1) / kChunk;
-        const uint32_t cf = first + (id - base) * kChunk, cl = min(cf + kChunk, last);
-        Row<NV4> acc;
-        zero_row(acc);
-        sum_segment<NV4>(acc, src, a.perm, cf + group, cl, kGroupsPerBlock, a.stride, lane);
-        __syncthreads();                  // LDS of the previous turn has been read
-        if (group > 0) store_row(part + (size_t)(group - 1) * a.stride, acc, lane);
-        __syncthreads();
-        if (group == 0) {
-            for (int g = 1; g < kGroupsPerBlock; ++g) {
-                Row<NV4> r;
-                load_row(r, part + (size_t)(g - 1) * a.stride, lane);
-                axpy_row(acc, 1.0f, r);
-            }
-            if (nch > 1) {
-                store_row(a.partial + (size_t)id * a.stride, acc, lane);
-                __threadfence();          // the partial row is visible before the arrival is counted
-            }
-        }
-        bool update = true;
-        if (nch > 1) {
-            __syncthreads();
-            if (threadIdx.x == 0) last_arrival = (atomicAdd(&a.chunk_done[base], 1u) == nch - 1) ? 1u : 0u;
-            __syncthreads();
-            update = last_arrival != 0;
-            if (update) {
-                __threadfence();          // the other chunks' partial rows are visible after their arrivals
-                if (group == 0) {        // chunk order, four partial rows in flight
-                    zero_row(acc);
-                    const float *prow = a.partial + (size_t)base * a.stride;
-                    uint32_t ch = 0;
-                    for (; ch + 3 < nch; ch += 4) {
-                        Row<NV4> r0, r1, r2, r3;
-                        load_row(r0, prow + (size_t)ch * a.stride, lane);
-                        load_row(r1, prow + (size_t)(ch + 1) * a.stride, lane);
-                        load_row(r2, prow + (size_t)(ch + 2) * a.stride, lane);
-                        load_row(r3, prow + (size_t)(ch + 3) * a.stride, lane);
-                        axpy_row(acc, 1.0f, r0);
-                        axpy_row(acc, 1.0f, r1);
-                        axpy_row(acc, 1.0f, r2);
-                        axpy_row(acc, 1.0f, r3);
-                    }
-                    for (; ch < nch; ++ch) {
-                        Row<NV4> r;
-                        load_row(r, prow + (size_t)ch * a.stride, lane);
-                        axpy_row(acc, 1.0f, r);
-                    }
-                }
-                if (threadIdx.x == 0) a.chunk_done[base] = 0u;   // ready for the next step
-            }
-        }
-        if (update && group == 0) {
-            const size_t off = (size_t)a.uniq[u] * a.stride;
-            Row<NV4> t, g;
-            opt.template load<NV4>(t, g, a.table + off, Opt::kHasState ? a.state + off : nullptr, lane);
-            opt.template finish<NV4>(t, g, a.table + off, Opt::kHasState ? a.state + off : nullptr, acc, lane);
-        }
+        if (item < sh.chunk_items) apply_chunk_item<NV4>(a, src, opt, item, part, &last_arrival, lane, group);
+        else apply_short_item<NV4>(a, src, opt, sh, item - sh.chunk_items, lane, group);
     }
 }
 
-constexpr uint32_t kApplyGrid = 2048;   // workgroups of k_apply (8 per compute unit)
+// Updates the two tables of a step in one launch (their updates are independent of each other: both read
+// staged rows only).  Item order: chunks of table 0, chunks of table 1, short segments of 0, of 1.
+template <int NV4, class Src0, class Opt0, class Src1, class Opt1>
+__global__ void __launch_bounds__(kBlock) k_apply2(ApplyArgs a0, Src0 src0, Opt0 opt0, ApplyArgs a1, Src1 src1,
+                                                   Opt1 opt1)
+{
+    extern __shared__ float part[];   // [kGroupsPerBlock - 1][stride]
+    __shared__ uint32_t last_arrival;
+    const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
+    const ApplyShape s0 = apply_shape(a0), s1 = apply_shape(a1);
+    const uint32_t e0 = s0.chunk_items, e1 = e0 + s1.chunk_items, e2 = e1 + s0.short_items,
+                   e3 = e2 + s1.short_items;
+    for (uint32_t item = blockIdx.x; item < e3; item += gridDim.x) {
+        if (item < e0) apply_chunk_item<NV4>(a0, src0, opt0, item, part, &last_arrival, lane, group);
+        else if (item < e1) apply_chunk_item<NV4>(a1, src1, opt1, item - e0, part, &last_arrival, lane, group);
+        else if (item < e2) apply_short_item<NV4>(a0, src0, opt0, s0, item - e1, lane, group);
+        else apply_short_item<NV4>(a1, src1, opt1, s1, item - e2, lane, group);
+    }
+}
+
+constexpr uint32_t kApplyGrid = 2048;   // workgroups of the apply kernels (8 per compute unit)
+
+static inline ApplyArgs make_apply_args(const Plan &pl, float *partial, float *table, float *state, int stride)
+{
+    const PlanArgs &p = pl.a;
+    return ApplyArgs{table, state, p.src, p.hot_bits, p.uniq, p.seg, p.perm, p.slot, p.rank, p.meta, p.chunk_seg,
+                     p.chunk_base, p.chunk_done, partial, stride, p.n};
+}
+
+static inline uint32_t max_apply_items(const Plan &pl)
+{
+    return (pl.a.n + kGroupsPerBlock - 1) / kGroupsPerBlock + (uint32_t)max_chunks(pl.a.n);
+}
 
 template <int NV4, class Src, class Opt>
 static void launch_apply_nv(hipStream_t s, const Plan &pl, float *partial, float *table, float *state, int stride,
                             const Src &src, const Opt &opt)
 {
-    const PlanArgs &p = pl.a;
-    if (p.n == 0) return;
-    const uint32_t max_items = (p.n + kGroupsPerBlock - 1) / kGroupsPerBlock + (uint32_t)max_chunks(p.n);
-    ApplyArgs a{table, state, p.src, p.hot_bits, p.uniq, p.seg, p.perm, p.slot, p.rank, p.meta, p.chunk_seg, p.chunk_base,
-                p.chunk_done, partial, stride, p.n};
+    if (pl.a.n == 0) return;
+    const ApplyArgs a = make_apply_args(pl, partial, table, state, stride);
     const size_t lds = sizeof(float) * (size_t)(kGroupsPerBlock - 1) * stride;
-    hipLaunchKernelGGL((k_apply<NV4, Src, Opt>), dim3(std::min(max_items, kApplyGrid)), dim3(kBlock), lds, s, a, src,
-                       opt);
+    hipLaunchKernelGGL((k_apply<NV4, Src, Opt>), dim3(std::min(max_apply_items(pl), kApplyGrid)), dim3(kBlock), lds, s,
+                       a, src, opt);
 }
 
-// Dispatch on the row length (stride / 64 float4 per lane).
+#define NUPS_FOR_EACH_ROW_WIDTH(stride, CALL)                                                     \
+    switch ((stride) / 64) {                                                                      \
+    case 1: CALL(1); break;                                                                       \
+    case 2: CALL(2); break;                                                                       \
+    case 3: CALL(3); break;                                                                       \
+    case 4: CALL(4); break;                                                                       \
+    case 5: CALL(5); break;                                                                       \
+    case 6: CALL(6); break;                                                                       \
+    case 8: CALL(8); break;                                                                       \
+    case 16: CALL(16); break;                                                                     \
+    default:                                                                                      \
+        return fail(NUPS_ERR_UNIMPLEMENTED,                                                       \
+                    "row_stride must be 64, 128, 192, 256, 320, 384, 512 or 1024 floats");        \
+    }
+
+// One table: dispatch on the row length (stride / 64 float4 per lane).
 template <class Src, class Opt>
 static nups_status launch_apply(hipStream_t s, const Plan &pl, float *partial, float *table, float *state,
                                 int stride, const Src &src, const Opt &opt)
 {
-    switch (stride / 64) {
-    case 1: launch_apply_nv<1>(s, pl, partial, table, state, stride, src, opt); break;
-    case 2: launch_apply_nv<2>(s, pl, partial, table, state, stride, src, opt); break;
-    case 3: launch_apply_nv<3>(s, pl, partial, table, state, stride, src, opt); break;
-    case 4: launch_apply_nv<4>(s, pl, partial, table, state, stride, src, opt); break;
-    case 5: launch_apply_nv<5>(s, pl, partial, table, state, stride, src, opt); break;
-    case 6: launch_apply_nv<6>(s, pl, partial, table, state, stride, src, opt); break;
-    case 8: launch_apply_nv<8>(s, pl, partial, table, state, stride, src, opt); break;
-    case 16: launch_apply_nv<16>(s, pl, partial, table, state, stride, src, opt); break;
-    default: return fail(NUPS_ERR_UNIMPLEMENTED, "row_stride must be 64, 128, 192, 256, 320, 384, 512 or 1024 floats");
-    }
+#define NUPS_CALL(N) launch_apply_nv<N>(s, pl, partial, table, state, stride, src, opt)
+    NUPS_FOR_EACH_ROW_WIDTH(stride, NUPS_CALL)
+#undef NUPS_CALL
+    NUPS_HIP(hipGetLastError());
+    return NUPS_OK;
+}
+
+// What one table's update needs besides its plan.
+template <class Src, class Opt>
+struct TableUpdate {
+    const Plan *plan;
+    float *partial, *table, *state;
+    Src src;
+    Opt opt;
+};
+
+template <int NV4, class U0, class U1>
+static void launch_apply2_nv(hipStream_t s, int stride, const U0 &u0, const U1 &u1)
+{
+    const ApplyArgs a0 = make_apply_args(*u0.plan, u0.partial, u0.table, u0.state, stride);
+    const ApplyArgs a1 = make_apply_args(*u1.plan, u1.partial, u1.table, u1.state, stride);
+    const uint32_t items = max_apply_items(*u0.plan) + max_apply_items(*u1.plan);
+    const size_t lds = sizeof(float) * (size_t)(kGroupsPerBlock - 1) * stride;
+    hipLaunchKernelGGL((k_apply2<NV4, decltype(u0.src), decltype(u0.opt), decltype(u1.src), decltype(u1.opt)>),
+                       dim3(std::min(items, kApplyGrid)), dim3(kBlock), lds, s, a0, u0.src, u0.opt, a1, u1.src, u1.opt);
+}
+
+// Both tables of a step in one launch (both strides are equal).
+template <class U0, class U1>
+static nups_status launch_apply2(hipStream_t s, int stride, const U0 &u0, const U1 &u1)
+{
+    if (u0.plan->a.n == 0 && u1.plan->a.n == 0) return NUPS_OK;
+#define NUPS_CALL(N) launch_apply2_nv<N>(s, stride, u0, u1)
+    NUPS_FOR_EACH_ROW_WIDTH(stride, NUPS_CALL)
+#undef NUPS_CALL
     NUPS_HIP(hipGetLastError());
     return NUPS_OK;
 }

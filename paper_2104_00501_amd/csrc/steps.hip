@@ -55,7 +55,8 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(const float *in_table, con
                                                       uint32_t num_in, uint32_t num_out, int stride,
                                                       const uint32_t *center, const uint32_t *context,
                                                       const uint32_t *negs, uint32_t B, int K, float *coefs,
-                                                      float *stage, double *loss)
+                                                      float *stage, const uint32_t *center_slot,
+                                                      const uint32_t *center_rank, float *center_rows, double *loss)
 {
     __shared__ float lds[kBlock / 64];
     const int lane = threadIdx.x & (kGroup - 1);
@@ -64,6 +65,9 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(const float *in_table, con
     const uint32_t e = active ? e_raw : B - 1;
     Row<NV4> v, acc;
     load_row(v, in_table + (size_t)min(center[e], num_in - 1) * stride, lane);
+    // the first pair of every distinct center word keeps a copy of the input vector for the output-side update
+    if (active && center_slot[e] != kBadIndex && center_rank[e] == 0)
+        store_row(center_rows + (size_t)center_slot[e] * stride, v, lane);
     zero_row(acc);
     float loss_acc = 0.f;
     constexpr int JU = 4;     // rows in flight per group
@@ -92,29 +96,15 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(const float *in_table, con
 }
 
 template <int NV4>
-static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b)
+static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b, const Plan &in_plan, float *center_rows)
 {
     const Table &tin = ctx->tab[0], &tout = ctx->tab[1];
     const uint32_t blocks = xcd_grid((uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock));
     hipLaunchKernelGGL(k_sgns_grad<NV4>, dim3(blocks), dim3(kBlock), 0, ctx->stream, (const float *)tin.data,
                        (const float *)tout.data, (uint32_t)tin.num_keys, (uint32_t)tout.num_keys, tin.stride, b.k0,
-                       b.k1, b.negs, (uint32_t)b.B, (int)b.n_neg, ctx->coef, ctx->stage, ctx->loss_cur);
+                       b.k1, b.negs, (uint32_t)b.B, (int)b.n_neg, ctx->coef, ctx->stage, in_plan.a.slot,
+                       in_plan.a.rank, center_rows, ctx->loss_cur);
 }
-
-#define NUPS_DISPATCH_STRIDE(stride, CALL)                                                        \
-    switch ((stride) / 64) {                                                                      \
-    case 1: CALL(1); break;                                                                       \
-    case 2: CALL(2); break;                                                                       \
-    case 3: CALL(3); break;                                                                       \
-    case 4: CALL(4); break;                                                                       \
-    case 5: CALL(5); break;                                                                       \
-    case 6: CALL(6); break;                                                                       \
-    case 8: CALL(8); break;                                                                       \
-    case 16: CALL(16); break;                                                                     \
-    default:                                                                                      \
-        return fail(NUPS_ERR_UNIMPLEMENTED,                                                       \
-                    "row_stride must be 64, 128, 192, 256, 320, 384, 512 or 1024 floats");        \
-    }
 
 // Plan side of a step: which keys each table is accessed with (plan 0: table 0, plan 1: table 1).
 static nups_status plan_two_tables(nups_ctx *ctx, nups_prepared &p, const KeySource &s0, uint32_t n0,
@@ -132,6 +122,9 @@ static nups_status plan_two_tables(nups_ctx *ctx, nups_prepared &p, const KeySou
     p.plan[1].a.n = n1;
     p.plan[0].a.zero_loss = p.loss_dev;
     p.plan[1].a.zero_loss = nullptr;
+    // partial rows of chunked segments: one region per table, the two updates run in the same launch
+    const size_t need = (max_chunks(p.plan[0].cap_n) + max_chunks(p.plan[1].cap_n)) * (size_t)ctx->tab[0].stride;
+    if ((st = ensure_partial(ctx, need)) != NUPS_OK) return st;
     return build_plans(ctx, p.plan, 2);
 }
 
@@ -143,6 +136,12 @@ nups_status plan_step_sgns(nups_ctx *ctx, nups_prepared &p)
                            KeySource{{b.k1, b.negs, nullptr}, {B, B * K, 0}}, B * (K + 1));
 }
 
+// Where table 1's partial rows start inside the context's partial buffer.
+static float *partial_of(nups_ctx *ctx, const nups_prepared &p, int k)
+{
+    return k == 0 ? ctx->partial : ctx->partial + max_chunks(p.plan[0].cap_n) * (size_t)ctx->tab[0].stride;
+}
+
 nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
 {
     const nups_batch &b = p.batch;
@@ -150,28 +149,26 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
     const uint32_t B = (uint32_t)b.B, K = (uint32_t)b.n_neg;
     nups_status st;
     if ((st = ensure_f32(&ctx->coef, &ctx->coef_cap, (size_t)B * (K + 1), ctx->stream)) != NUPS_OK) return st;
-    if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)B * tin.stride, ctx->stream)) != NUPS_OK) return st;
+    // staged rows: [0, B) per-pair input-side gradients, [B, 2B) input vectors of the distinct center words
+    if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)2 * B * tin.stride, ctx->stream)) != NUPS_OK) return st;
     ctx->loss_cur = p.loss_dev;   // zeroed by the step's plan construction
     if (B == 0) return NUPS_OK;
+    float *center_rows = ctx->stage + (size_t)B * tin.stride;
     {
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
-#define CALL(N) launch_sgns_grad<N>(ctx, b)
-        NUPS_DISPATCH_STRIDE(tin.stride, CALL)
+#define CALL(N) launch_sgns_grad<N>(ctx, b, p.plan[0], center_rows)
+        NUPS_FOR_EACH_ROW_WIDTH(tin.stride, CALL)
 #undef CALL
         NUPS_HIP(hipGetLastError());
     }
-    {   // output side first: it reads the input vectors, which must still be the step's snapshot
-        PhaseScope scope(ctx, NUPS_PHASE_APPLY1, ctx->stream);
-        SrcSgnsOut src{tin.data, b.k0, ctx->coef, B, K, (uint32_t)tin.num_keys};
-        if ((st = launch_apply(ctx->stream, p.plan[1], ctx->partial, tout.data, nullptr, tout.stride, src,
-                               OptSgd{b.lr})) != NUPS_OK)
-            return st;
-    }
-    {
+    {   // both tables in one launch: the output side reads the staged center rows, not the input table
         PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
-        if ((st = launch_apply(ctx->stream, p.plan[0], ctx->partial, tin.data, nullptr, tin.stride,
-                               SrcStaged{ctx->stage}, OptSgd{b.lr})) != NUPS_OK)
-            return st;
+        const TableUpdate<SrcStaged, OptSgd> uin{&p.plan[0], partial_of(ctx, p, 0), tin.data, nullptr,
+                                                 SrcStaged{ctx->stage}, OptSgd{b.lr}};
+        const TableUpdate<SrcSgnsOut, OptSgd> uout{&p.plan[1], partial_of(ctx, p, 1), tout.data, nullptr,
+                                                   SrcSgnsOut{center_rows, p.plan[0].a.slot, ctx->coef, B, K},
+                                                   OptSgd{b.lr}};
+        if ((st = launch_apply2(ctx->stream, tin.stride, uin, uout)) != NUPS_OK) return st;
     }
     return NUPS_OK;
 }
@@ -243,21 +240,17 @@ nups_status run_step_mf(nups_ctx *ctx, nups_prepared &p)
     {
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
 #define CALL(N) launch_mf_grad<N>(ctx, b)
-        NUPS_DISPATCH_STRIDE(tw.stride, CALL)
+        NUPS_FOR_EACH_ROW_WIDTH(tw.stride, CALL)
 #undef CALL
         NUPS_HIP(hipGetLastError());
     }
     {
         PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
-        if ((st = launch_apply(ctx->stream, p.plan[0], ctx->partial, tw.data, nullptr, tw.stride,
-                               SrcStaged{ctx->stage}, OptSgd{b.lr})) != NUPS_OK)
-            return st;
-    }
-    {
-        PhaseScope scope(ctx, NUPS_PHASE_APPLY1, ctx->stream);
-        if ((st = launch_apply(ctx->stream, p.plan[1], ctx->partial, th.data, nullptr, th.stride,
-                               SrcStaged{ctx->stage + (size_t)B * tw.stride}, OptSgd{b.lr})) != NUPS_OK)
-            return st;
+        const TableUpdate<SrcStaged, OptSgd> uw{&p.plan[0], partial_of(ctx, p, 0), tw.data, nullptr,
+                                                SrcStaged{ctx->stage}, OptSgd{b.lr}};
+        const TableUpdate<SrcStaged, OptSgd> uh{&p.plan[1], partial_of(ctx, p, 1), th.data, nullptr,
+                                                SrcStaged{ctx->stage + (size_t)B * tw.stride}, OptSgd{b.lr}};
+        if ((st = launch_apply2(ctx->stream, tw.stride, uw, uh)) != NUPS_OK) return st;
     }
     return NUPS_OK;
 }
@@ -470,16 +463,13 @@ nups_status run_step_kge(nups_ctx *ctx, nups_prepared &p)
     }
     {
         PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
-        SrcKgeEntity src{ctx->stage, ctx->coef, B, nn, nh};
-        if ((st = launch_apply(ctx->stream, p.plan[0], ctx->partial, te.data, te.state, te.stride, src,
-                               OptAdagrad{b.lr, b.eps})) != NUPS_OK)
-            return st;
-    }
-    {
-        PhaseScope scope(ctx, NUPS_PHASE_APPLY1, ctx->stream);
-        if ((st = launch_apply(ctx->stream, p.plan[1], ctx->partial, tr.data, tr.state, tr.stride,
-                               SrcStaged{ctx->stage + (size_t)4 * B * te.stride}, OptAdagrad{b.lr, b.eps})) != NUPS_OK)
-            return st;
+        const TableUpdate<SrcKgeEntity, OptAdagrad> ue{&p.plan[0], partial_of(ctx, p, 0), te.data, te.state,
+                                                       SrcKgeEntity{ctx->stage, ctx->coef, B, nn, nh},
+                                                       OptAdagrad{b.lr, b.eps}};
+        const TableUpdate<SrcStaged, OptAdagrad> ur{&p.plan[1], partial_of(ctx, p, 1), tr.data, tr.state,
+                                                    SrcStaged{ctx->stage + (size_t)4 * B * te.stride},
+                                                    OptAdagrad{b.lr, b.eps}};
+        if ((st = launch_apply2(ctx->stream, te.stride, ue, ur)) != NUPS_OK) return st;
     }
     return NUPS_OK;
 }
