@@ -1,6 +1,8 @@
 // Host side of the C ABI declared in include/nups.h: argument checks, workspace, object lifetimes,
 // and the two-stream schedule: sampling and plan construction ("preparatory work", Section 4.3) run on a
 // library-owned side stream, everything that reads or writes table values runs on the caller's stream.
+// The side stream's work for prepared steps is issued by a background thread of the library, so that the
+// calling thread spends its time on its own stream only.
 #include <algorithm>
 #include <cstring>
 
@@ -34,6 +36,68 @@ nups_status ensure_f32(float **buf, size_t *cap, size_t need, hipStream_t stream
     const size_t n = need + need / 4 + 1024;
     NUPS_HIP(hipMalloc((void **)buf, sizeof(float) * n));
     *cap = n;
+    return NUPS_OK;
+}
+
+// ---- background thread --------------------------------------------------------------------------------------
+
+static void worker_main(nups_ctx *ctx)
+{
+    (void)hipSetDevice(ctx->device);
+    Worker &w = *ctx->worker;
+    std::unique_lock<std::mutex> lock(w.mutex);
+    for (;;) {
+        w.has_job.wait(lock, [&] { return w.stop || !w.jobs.empty(); });
+        if (w.jobs.empty()) return;   // asked to stop, nothing left to issue
+        std::function<void()> job = std::move(w.jobs.front());
+        w.jobs.pop_front();
+        w.busy = true;
+        lock.unlock();
+        job();
+        lock.lock();
+        w.busy = false;
+        w.job_done.notify_all();
+    }
+}
+
+static void worker_submit(nups_ctx *ctx, std::function<void()> job)
+{
+    Worker &w = *ctx->worker;
+    {
+        std::lock_guard<std::mutex> lock(w.mutex);
+        w.jobs.push_back(std::move(job));
+    }
+    w.has_job.notify_one();
+}
+
+// Returns once the background thread has issued everything handed to it.
+void worker_drain(nups_ctx *ctx)
+{
+    if (!ctx->worker) return;
+    Worker &w = *ctx->worker;
+    std::unique_lock<std::mutex> lock(w.mutex);
+    w.job_done.wait(lock, [&] { return w.jobs.empty() && !w.busy; });
+}
+
+static void worker_stop(nups_ctx *ctx)
+{
+    if (!ctx->worker) return;
+    Worker &w = *ctx->worker;
+    {
+        std::lock_guard<std::mutex> lock(w.mutex);
+        w.stop = true;
+    }
+    w.has_job.notify_one();
+    if (w.thread.joinable()) w.thread.join();
+    delete ctx->worker;
+    ctx->worker = nullptr;
+}
+
+// Waits until the side stream has finished everything prepared so far.
+nups_status sync_side(nups_ctx *ctx)
+{
+    worker_drain(ctx);
+    NUPS_HIP(hipStreamSynchronize(ctx->side));
     return NUPS_OK;
 }
 
@@ -79,6 +143,7 @@ static void free_prepared(nups_prepared *p)
     free_plan_arrays(p->plan[0]);
     free_plan_arrays(p->plan[1]);
     if (p->ready) (void)hipEventDestroy(p->ready);
+    if (p->fork) (void)hipEventDestroy(p->fork);
     if (p->loss_dev) (void)hipFree(p->loss_dev);
     if (p->negs_buf) (void)hipFree(p->negs_buf);
     delete p;
@@ -87,7 +152,8 @@ static void free_prepared(nups_prepared *p)
 // Waits for both streams and turns a raised device flag into an error.
 static nups_status sync_and_check(nups_ctx *ctx)
 {
-    NUPS_HIP(hipStreamSynchronize(ctx->side));
+    nups_status side = sync_side(ctx);
+    if (side != NUPS_OK) return side;
     NUPS_HIP(hipMemcpyAsync(ctx->flag_pinned, ctx->error_flag, sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
     NUPS_HIP(hipStreamSynchronize(ctx->stream));
     if (*ctx->flag_pinned != 0) {
@@ -101,9 +167,11 @@ static nups_status sync_and_check(nups_ctx *ctx)
 static bool valid_table(const nups_ctx *ctx, int t) { return ctx && t >= 0 && t < ctx->n_tables; }
 
 // Work enqueued on the side stream from here on starts after everything already enqueued on the caller's stream
-// (key arrays written there are complete; buffers consumed there are free again).
+// (key arrays written there are complete; buffers consumed there are free again).  For work the calling thread
+// enqueues itself: the background thread must be idle.
 static nups_status side_after_main(nups_ctx *ctx)
 {
+    worker_drain(ctx);
     NUPS_HIP(hipEventRecord(ctx->fork, ctx->stream));
     NUPS_HIP(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
     return NUPS_OK;
@@ -126,6 +194,9 @@ static nups_status get_prepared(nups_ctx *ctx, nups_prepared **out)
         ctx->prepared_all.push_back(p);
     }
     nups_status st = new_event(&p->ready);
+    if (st == NUPS_OK) st = new_event(&p->fork);
+    p->submitted.store(0, std::memory_order_relaxed);
+    p->error.clear();
     if (st == NUPS_OK && !p->loss_dev && !hip_ok(hipMalloc((void **)&p->loss_dev, sizeof(double)), "loss accumulator"))
         st = NUPS_ERR_DEVICE;
     if (st != NUPS_OK) { ctx->prepared_free.push_back(p); return st; }
@@ -249,6 +320,8 @@ nups_status nups_init(nups_ctx **out, int n_tables, float *const *tables_dev, co
         nups_destroy(ctx);
         return NUPS_ERR_DEVICE;
     }
+    ctx->worker = new Worker();
+    ctx->worker->thread = std::thread(worker_main, ctx);
     *out = ctx;
     return NUPS_OK;
 }
@@ -256,6 +329,7 @@ nups_status nups_init(nups_ctx **out, int n_tables, float *const *tables_dev, co
 nups_status nups_destroy(nups_ctx *ctx)
 {
     if (!ctx) return fail(NUPS_ERR_ARG, "nups_destroy: null context");
+    worker_stop(ctx);
     if (ctx->side) (void)hipStreamSynchronize(ctx->side);
     (void)hipStreamSynchronize(ctx->stream);
     for (nups_dist *d : ctx->dists) free_dist(d);
@@ -303,7 +377,8 @@ nups_status nups_set_hot_keys(nups_ctx *ctx, int table, const uint32_t *keys_hos
     const size_t words = (size_t)((t.num_keys + 31) / 32);
     std::vector<uint32_t> bits(words, 0u);
     for (uint32_t key : keys) bits[key >> 5] |= 1u << (key & 31);
-    NUPS_HIP(hipStreamSynchronize(ctx->side));
+    nups_status side = sync_side(ctx);
+    if (side != NUPS_OK) return side;
     NUPS_HIP(hipStreamSynchronize(ctx->stream));
     if (!t.hot_bits_dev) NUPS_HIP(hipMalloc((void **)&t.hot_bits_dev, sizeof(uint32_t) * words));
     NUPS_HIP(hipMemcpy(t.hot_bits_dev, bits.data(), sizeof(uint32_t) * words, hipMemcpyHostToDevice));
@@ -423,6 +498,7 @@ nups_status nups_prepare_sample(nups_dist *dist, int64_t n, uint64_t step, nups_
     else { h = new nups_sample(); h->dist = dist; }
     nups_status st = new_event(&h->ready);
     if (st == NUPS_OK && (h->cap < (size_t)n || !h->keys_dev)) {
+        worker_drain(ctx);
         hipError_t e = hipStreamSynchronize(ctx->side);
         if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
         if (e == hipSuccess && h->keys_dev) e = hipFree(h->keys_dev);
@@ -436,7 +512,8 @@ nups_status nups_prepare_sample(nups_dist *dist, int64_t n, uint64_t step, nups_
     h->n = n;
     h->pulled = 0;
     h->live = true;
-    st = launch_sample(dist, h->keys_dev, h->n, step);
+    st = launch_sample(ctx, ctx->side, sample_spec(dist), h->keys_dev, h->n, step);
+    if (dist->scheme == NUPS_LONGTERM) dist->cursor += (uint64_t)n;
     if (st == NUPS_OK && hipEventRecord(h->ready, ctx->side) != hipSuccess)
         st = fail(NUPS_ERR_DEVICE, "nups_prepare_sample: event record failed");
     if (st != NUPS_OK) { h->live = false; dist->recycled.push_back(h); return st; }
@@ -486,7 +563,22 @@ nups_status nups_release_sample(nups_sample *h)
     return NUPS_OK;
 }
 
-nups_status nups_prepare_step(nups_ctx *ctx, const nups_batch *b, nups_prepared **out)
+// The side-stream part of a prepared step: after what the caller's stream held when the step was prepared, draw
+// the step's own negatives if it has any, build the plans, and signal readiness.
+static void issue_side_work(nups_ctx *ctx, nups_prepared *p, const SampleSpec &spec, int64_t n_draw, uint64_t step)
+{
+    nups_status st = NUPS_OK;
+    if (hipStreamWaitEvent(ctx->side, p->fork, 0) != hipSuccess) st = fail(NUPS_ERR_DEVICE, "prepared step: stream wait failed");
+    if (st == NUPS_OK && n_draw > 0) st = launch_sample(ctx, ctx->side, spec, p->negs_buf, n_draw, step);
+    if (st == NUPS_OK) st = build_plans(ctx, p->plan, p->n_plans);
+    if (st == NUPS_OK && hipEventRecord(p->ready, ctx->side) != hipSuccess)
+        st = fail(NUPS_ERR_DEVICE, "prepared step: event record failed");
+    if (st != NUPS_OK) p->error = nups_last_error();
+    p->submitted.store(st == NUPS_OK ? 1 : (int)st, std::memory_order_release);
+}
+
+// background: the side-stream work is handed to the library's thread; otherwise the calling thread issues it.
+static nups_status prepare_step(nups_ctx *ctx, const nups_batch *b, nups_prepared **out, bool background)
 {
     if (!out) return fail(NUPS_ERR_ARG, "nups_prepare_step: out is null");
     *out = nullptr;
@@ -501,6 +593,7 @@ nups_status nups_prepare_step(nups_ctx *ctx, const nups_batch *b, nups_prepared 
     }
     const int64_t n_draw = b->dist ? b->B * ((int64_t)b->n_neg + b->n_neg2) : 0;
     if (n_draw > 0 && p->negs_cap < (size_t)n_draw) {   // the step draws its own negatives into its own buffer
+        worker_drain(ctx);
         hipError_t e = hipStreamSynchronize(ctx->side);
         if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
         if (e == hipSuccess && p->negs_buf) e = hipFree(p->negs_buf);
@@ -514,24 +607,41 @@ nups_status nups_prepare_step(nups_ctx *ctx, const nups_batch *b, nups_prepared 
             return NUPS_ERR_DEVICE;
         }
     }
-    if ((st = side_after_main(ctx)) == NUPS_OK && n_draw > 0) {
+    SampleSpec spec{};
+    if (n_draw > 0) {
+        spec = sample_spec(b->dist);
+        if (b->dist->scheme == NUPS_LONGTERM) b->dist->cursor += (uint64_t)n_draw;
         p->batch.negs = p->negs_buf;
         p->batch.dist = nullptr;
-        st = launch_sample(b->dist, p->negs_buf, n_draw, b->sample_step);
     }
-    if (st == NUPS_OK) {
-        switch (b->task) {
-        case NUPS_TASK_SGNS: st = plan_step_sgns(ctx, *p); break;
-        case NUPS_TASK_MF: st = plan_step_mf(ctx, *p); break;
-        default: st = plan_step_kge(ctx, *p); break;
-        }
+    switch (b->task) {   // capacities and plan arguments
+    case NUPS_TASK_SGNS: st = plan_step_sgns(ctx, *p); break;
+    case NUPS_TASK_MF: st = plan_step_mf(ctx, *p); break;
+    default: st = plan_step_kge(ctx, *p); break;
     }
-    if (st == NUPS_OK && hipEventRecord(p->ready, ctx->side) != hipSuccess)
+    if (st == NUPS_OK && hipEventRecord(p->fork, ctx->stream) != hipSuccess)
         st = fail(NUPS_ERR_DEVICE, "nups_prepare_step: event record failed");
     if (st != NUPS_OK) { ctx->prepared_free.push_back(p); return st; }
+    const uint64_t step = b->sample_step;
+    if (background && !ctx->profiling) {
+        worker_submit(ctx, [ctx, p, spec, n_draw, step] { issue_side_work(ctx, p, spec, n_draw, step); });
+    } else {
+        worker_drain(ctx);
+        issue_side_work(ctx, p, spec, n_draw, step);
+        if (p->submitted.load(std::memory_order_acquire) != 1) {
+            st = fail((nups_status)p->submitted.load(), p->error);
+            ctx->prepared_free.push_back(p);
+            return st;
+        }
+    }
     p->live = true;
     *out = p;
     return NUPS_OK;
+}
+
+nups_status nups_prepare_step(nups_ctx *ctx, const nups_batch *b, nups_prepared **out)
+{
+    return prepare_step(ctx, b, out, true);
 }
 
 nups_status nups_step_prepared(nups_ctx *ctx, nups_prepared *p, double *loss_sum_host)
@@ -539,6 +649,16 @@ nups_status nups_step_prepared(nups_ctx *ctx, nups_prepared *p, double *loss_sum
     if (!ctx || !p) return fail(NUPS_ERR_ARG, "nups_step_prepared: null argument");
     if (p->ctx != ctx) return fail(NUPS_ERR_ARG, "nups_step_prepared: the step was prepared on another context");
     if (!p->live) return fail(NUPS_ERR_STATE, "nups_step_prepared: the prepared step was already run");
+    if (p->submitted.load(std::memory_order_acquire) == 0) {   // the background thread has not got to it yet
+        Worker &w = *ctx->worker;
+        std::unique_lock<std::mutex> lock(w.mutex);
+        w.job_done.wait(lock, [&] { return p->submitted.load(std::memory_order_acquire) != 0; });
+    }
+    if (p->submitted.load(std::memory_order_acquire) != 1) {
+        const nups_status failed = fail((nups_status)p->submitted.load(), p->error);
+        retire_prepared(ctx, p);
+        return failed;
+    }
     NUPS_HIP(hipStreamWaitEvent(ctx->stream, p->ready, 0));
     nups_status st;
     switch (p->batch.task) {
@@ -560,7 +680,7 @@ nups_status nups_step_prepared(nups_ctx *ctx, nups_prepared *p, double *loss_sum
 nups_status nups_step(nups_ctx *ctx, const nups_batch *b, double *loss_sum_host)
 {
     nups_prepared *p = nullptr;
-    nups_status st = nups_prepare_step(ctx, b, &p);
+    nups_status st = prepare_step(ctx, b, &p, false);
     if (st != NUPS_OK) return st;
     return nups_step_prepared(ctx, p, loss_sum_host);
 }
@@ -571,7 +691,8 @@ nups_status nups_debug_structure(nups_ctx *ctx, int table, uint32_t *uniq_keys_d
     if (!valid_table(ctx, table) || !n_uniq_host) return fail(NUPS_ERR_ARG, "nups_debug_structure: bad arguments");
     const Plan *pl = ctx->tab[table].last_plan;
     if (!pl) return fail(NUPS_ERR_STATE, "nups_debug_structure: no step or push has run on this table");
-    NUPS_HIP(hipStreamSynchronize(ctx->side));
+    nups_status side = sync_side(ctx);
+    if (side != NUPS_OK) return side;
     uint32_t meta[kMetaWords];
     NUPS_HIP(hipMemcpyAsync(meta, pl->a.meta, sizeof(meta), hipMemcpyDeviceToHost, ctx->stream));
     NUPS_HIP(hipStreamSynchronize(ctx->stream));
@@ -600,7 +721,8 @@ nups_status nups_profile(nups_ctx *ctx, int enable)
 nups_status nups_profile_read(nups_ctx *ctx, int phase, double *ms_total, int64_t *launches)
 {
     if (!ctx || phase < 0 || phase >= NUPS_PHASE_COUNT) return fail(NUPS_ERR_ARG, "nups_profile_read: bad arguments");
-    NUPS_HIP(hipStreamSynchronize(ctx->side));
+    nups_status side = sync_side(ctx);
+    if (side != NUPS_OK) return side;
     NUPS_HIP(hipStreamSynchronize(ctx->stream));
     Phase &ph = ctx->phase[phase];
     for (auto &pr : ph.pending) {

@@ -4,7 +4,13 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+#include <condition_variable>
+#include <deque>
+#include <functional>
+#include <mutex>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/nups.h"
@@ -99,6 +105,31 @@ struct Table {
     Plan *last_plan = nullptr;        // structure of the last step / push on this table (owned by a prepared step)
 };
 
+// Everything a sampling kernel needs, copied when the call is made (the distribution object may change
+// afterwards: cursor, batch-local key arrays).
+struct SampleSpec {
+    nups_scheme scheme;
+    const uint32_t *thresh, *alias;   // null thresh: uniform
+    uint64_t num_keys, seed, cursor;
+    uint32_t dist_id;
+    int32_t U, G, R;
+    int64_t P;
+    const uint32_t *local_a, *local_b;
+    int64_t local_n;
+    int32_t per_example, split, tile;
+};
+
+// The library's background thread (the "background thread" of Section 4.4): it issues the side stream's work so
+// that the calling thread only pays for what goes on its own stream.
+struct Worker {
+    std::thread thread;
+    std::mutex mutex;
+    std::condition_variable has_job, job_done;
+    std::deque<std::function<void()>> jobs;
+    bool stop = false;
+    bool busy = false;
+};
+
 struct Phase {
     std::vector<std::pair<hipEvent_t, hipEvent_t>> pending;
     std::vector<hipEvent_t> free_events;
@@ -118,8 +149,11 @@ struct nups_prepared {
     double *loss_dev = nullptr;    // this step's loss accumulator
     uint32_t *negs_buf = nullptr;  // negatives drawn by the step itself (batch.dist)
     size_t negs_cap = 0;
+    hipEvent_t fork = nullptr;     // recorded on the caller's stream when the step was prepared
     bool live = false;             // prepared, not yet run
     bool retired = false;          // run, still referenced by a table's structure query
+    std::atomic<int> submitted{0}; // 0: the side-stream work is still queued; 1: enqueued; < 0: it failed (status)
+    std::string error;             // message of that failure
 };
 
 struct nups_ctx {
@@ -127,8 +161,9 @@ struct nups_ctx {
     nups::Table tab[nups::kMaxTables];
     hipStream_t stream = nullptr;   // the caller's stream: everything that touches table values
     hipStream_t side = nullptr;     // library-owned: sampling and plan construction ("background" work)
-    hipEvent_t fork = nullptr;      // main -> side ordering at every prepare call
+    hipEvent_t fork = nullptr;      // main -> side ordering for work enqueued by the calling thread itself
     int device = 0;
+    nups::Worker *worker = nullptr; // issues the side-stream work of prepared steps
     // step workspace (main stream only)
     float *coef = nullptr;      size_t coef_cap = 0;      // per (example, scored row) loss derivative
     float *stage = nullptr;     size_t stage_cap = 0;     // staged gradient rows
@@ -186,14 +221,18 @@ struct PhaseScope {
 };
 
 // kernels' host-side launchers (defined in the .hip files)
-nups_status launch_sample(nups_dist *d, uint32_t *keys_out, int64_t n_samples, uint64_t step);
+SampleSpec sample_spec(const nups_dist *d);
+nups_status launch_sample(nups_ctx *ctx, hipStream_t stream, const SampleSpec &d, uint32_t *keys_out, int64_t n_samples,
+                          uint64_t step);
+void worker_drain(nups_ctx *ctx);
+nups_status sync_side(nups_ctx *ctx);
 nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n);
 nups_status build_plans(nups_ctx *ctx, Plan *plans, int n_plans);
 void free_plan_arrays(Plan &pl);
 void free_plan_scratch(PlanScratch &sc);
 nups_status launch_pull(nups_ctx *ctx, const Table &t, const uint32_t *keys, int64_t n, float *values);
 nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, const float *updates);
-nups_status plan_step_sgns(nups_ctx *ctx, nups_prepared &p);
+nups_status plan_step_sgns(nups_ctx *ctx, nups_prepared &p);   // capacity + plan arguments (calling thread)
 nups_status plan_step_mf(nups_ctx *ctx, nups_prepared &p);
 nups_status plan_step_kge(nups_ctx *ctx, nups_prepared &p);
 nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p);

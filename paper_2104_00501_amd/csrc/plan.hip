@@ -253,7 +253,8 @@ size_t max_chunks(size_t n) { return n / kChunk + n / (kLongSegment + 1) + 2; }
 nups_status ensure_partial(nups_ctx *ctx, size_t need)
 {
     if (ctx->partial_cap >= need && ctx->partial) return NUPS_OK;
-    NUPS_HIP(hipStreamSynchronize(ctx->side));
+    nups_status st = sync_side(ctx);
+    if (st != NUPS_OK) return st;
     return ensure_f32(&ctx->partial, &ctx->partial_cap, need, ctx->stream);
 }
 
@@ -276,7 +277,8 @@ void free_plan_scratch(PlanScratch &sc)
 // Both streams are idle after this (buffers may then be replaced).
 static nups_status quiesce(nups_ctx *ctx)
 {
-    NUPS_HIP(hipStreamSynchronize(ctx->side));
+    nups_status st = sync_side(ctx);
+    if (st != NUPS_OK) return st;
     NUPS_HIP(hipStreamSynchronize(ctx->stream));
     return NUPS_OK;
 }

@@ -117,37 +117,52 @@ static int feistel_half_bits(uint64_t P)
     return half;
 }
 
-nups_status launch_sample(nups_dist *d, uint32_t *keys_out, int64_t n_samples, uint64_t step)
+SampleSpec sample_spec(const nups_dist *d)
 {
-    nups_ctx *ctx = d->ctx;
+    SampleSpec sp{};
+    sp.scheme = d->scheme;
+    sp.thresh = d->uniform ? nullptr : d->thresh_dev;
+    sp.alias = d->alias_dev;
+    sp.num_keys = (uint64_t)d->ctx->tab[d->table].num_keys;
+    sp.seed = d->seed;
+    sp.cursor = d->cursor;
+    sp.dist_id = d->id;
+    sp.U = d->U; sp.G = d->G; sp.R = d->R; sp.P = d->P;
+    sp.local_a = d->local_a; sp.local_b = d->local_b; sp.local_n = d->local_n;
+    sp.per_example = d->per_example; sp.split = d->split; sp.tile = d->tile;
+    return sp;
+}
+
+// Enqueues the drawing of n_samples keys on `stream`.
+nups_status launch_sample(nups_ctx *ctx, hipStream_t stream, const SampleSpec &d, uint32_t *keys_out, int64_t n_samples,
+                          uint64_t step)
+{
     const uint32_t n = (uint32_t)n_samples;
     if (n == 0) return NUPS_OK;
-    PhaseScope scope(ctx, NUPS_PHASE_SAMPLE, ctx->side);
-    DistArgs a{d->uniform ? nullptr : d->thresh_dev, d->alias_dev, (uint64_t)ctx->tab[d->table].num_keys, d->seed,
-               d->id};
+    PhaseScope scope(ctx, NUPS_PHASE_SAMPLE, stream);
+    DistArgs a{d.thresh, d.alias, d.num_keys, d.seed, d.dist_id};
     const uint32_t blocks = (n + kBlock - 1) / kBlock;
-    switch (d->scheme) {
+    switch (d.scheme) {
     case NUPS_CONFORM:
-        hipLaunchKernelGGL(k_sample_fresh, dim3(blocks), dim3(kBlock), 0, ctx->side, a, step, (uint64_t)0, n,
+        hipLaunchKernelGGL(k_sample_fresh, dim3(blocks), dim3(kBlock), 0, stream, a, step, (uint64_t)0, n,
                            keys_out);
         break;
     case NUPS_BOUNDED: {
-        const uint32_t U = (uint32_t)d->U, G = (uint32_t)d->G;
+        const uint32_t U = (uint32_t)d.U, G = (uint32_t)d.G;
         const uint32_t F = (n + U - 1) / U;
         const uint32_t pools = (F + G - 1) / G;
-        hipLaunchKernelGGL(k_sample_pool_pass, dim3(pools * U), dim3(kBlock), 0, ctx->side, a, step, F, G, U, n,
+        hipLaunchKernelGGL(k_sample_pool_pass, dim3(pools * U), dim3(kBlock), 0, stream, a, step, F, G, U, n,
                            keys_out);
         break;
     }
     case NUPS_LONGTERM:
-        hipLaunchKernelGGL(k_sample_longterm, dim3(blocks), dim3(kBlock), 0, ctx->side, a, (uint64_t)d->P,
-                           (uint32_t)d->R, d->cursor, n, feistel_half_bits((uint64_t)d->P), keys_out);
-        d->cursor += n;
+        hipLaunchKernelGGL(k_sample_longterm, dim3(blocks), dim3(kBlock), 0, stream, a, (uint64_t)d.P,
+                           (uint32_t)d.R, d.cursor, n, feistel_half_bits((uint64_t)d.P), keys_out);
         break;
     case NUPS_NONCONFORM:
-        hipLaunchKernelGGL(k_sample_local, dim3(blocks), dim3(kBlock), 0, ctx->side, d->local_a, d->local_b,
-                           (uint32_t)d->local_n, (uint32_t)d->per_example, (uint32_t)d->split, (uint32_t)d->tile,
-                           d->seed, d->id, step, n, keys_out);
+        hipLaunchKernelGGL(k_sample_local, dim3(blocks), dim3(kBlock), 0, stream, d.local_a, d.local_b,
+                           (uint32_t)d.local_n, (uint32_t)d.per_example, (uint32_t)d.split, (uint32_t)d.tile,
+                           d.seed, d.dist_id, step, n, keys_out);
         break;
     default:
         return fail(NUPS_ERR_ARG, "unknown sampling scheme");

@@ -106,7 +106,8 @@ static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b, const Plan &in_
                        in_plan.a.rank, center_rows, ctx->loss_cur);
 }
 
-// Plan side of a step: which keys each table is accessed with (plan 0: table 0, plan 1: table 1).
+// Plan side of a step: which keys each table is accessed with (plan 0: table 0, plan 1: table 1).  Sizes the
+// arrays and fills in the arguments; the construction itself is enqueued by build_plans.
 static nups_status plan_two_tables(nups_ctx *ctx, nups_prepared &p, const KeySource &s0, uint32_t n0,
                                    const KeySource &s1, uint32_t n1)
 {
@@ -124,8 +125,7 @@ static nups_status plan_two_tables(nups_ctx *ctx, nups_prepared &p, const KeySou
     p.plan[1].a.zero_loss = nullptr;
     // partial rows of chunked segments: one region per table, the two updates run in the same launch
     const size_t need = (max_chunks(p.plan[0].cap_n) + max_chunks(p.plan[1].cap_n)) * (size_t)ctx->tab[0].stride;
-    if ((st = ensure_partial(ctx, need)) != NUPS_OK) return st;
-    return build_plans(ctx, p.plan, 2);
+    return ensure_partial(ctx, need);
 }
 
 nups_status plan_step_sgns(nups_ctx *ctx, nups_prepared &p)
