@@ -197,7 +197,7 @@ static nups_status get_prepared(nups_ctx *ctx, nups_prepared **out)
     if (st == NUPS_OK) st = new_event(&p->fork);
     p->submitted.store(0, std::memory_order_relaxed);
     p->error.clear();
-    if (st == NUPS_OK && !p->loss_dev && !hip_ok(hipMalloc((void **)&p->loss_dev, sizeof(double)), "loss accumulator"))
+    if (st == NUPS_OK && !p->loss_dev && !hip_ok(hipMalloc((void **)&p->loss_dev, sizeof(double) * kLossSlots * kLossStride), "loss accumulator"))
         st = NUPS_ERR_DEVICE;
     if (st != NUPS_OK) { ctx->prepared_free.push_back(p); return st; }
     *out = p;
@@ -311,7 +311,7 @@ nups_status nups_init(nups_ctx **out, int n_tables, float *const *tables_dev, co
     hipError_t e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);   // default priority
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->error_flag, sizeof(uint32_t));
-    if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->loss_pinned, sizeof(double), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->loss_pinned, sizeof(double) * kLossSlots * kLossStride, hipHostMallocDefault);
     if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->flag_pinned, sizeof(uint32_t), hipHostMallocDefault);
     if (e == hipSuccess) e = hipMemsetAsync(ctx->error_flag, 0, sizeof(uint32_t), ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
@@ -669,9 +669,12 @@ nups_status nups_step_prepared(nups_ctx *ctx, nups_prepared *p, double *loss_sum
     retire_prepared(ctx, p);
     if (st != NUPS_OK) return st;
     if (loss_sum_host) {
-        NUPS_HIP(hipMemcpyAsync(ctx->loss_pinned, p->loss_dev, sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
+        NUPS_HIP(hipMemcpyAsync(ctx->loss_pinned, p->loss_dev, sizeof(double) * kLossSlots * kLossStride,
+                                hipMemcpyDeviceToHost, ctx->stream));
         st = sync_and_check(ctx);
-        *loss_sum_host = *ctx->loss_pinned;
+        double total = 0.0;
+        for (int s = 0; s < kLossSlots; ++s) total += ctx->loss_pinned[s * kLossStride];
+        *loss_sum_host = total;
         return st;
     }
     return NUPS_OK;

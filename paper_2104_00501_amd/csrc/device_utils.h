@@ -158,7 +158,7 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t x, uint32_t *lds)
     return sum;
 }
 
-// Adds one value per workgroup (of WAVES wavefronts) to a double accumulator in memory.
+// Adds one value per workgroup (of WAVES wavefronts) to the step's loss accumulator: the slot is chosen by workgroup number.
 template <int WAVES = kBlock / 64>
 __device__ __forceinline__ void block_add_loss(float x, double *loss, float *lds)
 {
@@ -169,7 +169,7 @@ __device__ __forceinline__ void block_add_loss(float x, double *loss, float *lds
     if (threadIdx.x == 0) {
         double s = 0.0;
         for (int w = 0; w < WAVES; ++w) s += (double)lds[w];
-        atomicAdd(loss, s);
+        atomicAdd(loss + (blockIdx.x % kLossSlots) * kLossStride, s);
     }
 }
 

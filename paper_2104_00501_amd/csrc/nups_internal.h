@@ -24,6 +24,10 @@ constexpr int kMaxTables = 4;
 constexpr int kMaxStride = 1024;
 constexpr int kScanItems = 2;         // items per thread in the tile scans
 constexpr int kScanTile = kBlock * kScanItems;
+// A step's loss is accumulated in kLossSlots partial sums, each on a cache line of its own (kLossStride doubles
+// apart): thousands of workgroups adding to one address would queue up behind each other.  The host adds the slots.
+constexpr int kLossSlots = 64;
+constexpr int kLossStride = 16;
 constexpr uint32_t kLongSegment = 16; // segments with more accesses are summed by whole workgroups, in chunks
 constexpr uint32_t kChunk = 128;      // accesses of a long segment that one workgroup sums
 constexpr uint32_t kBadIndex = 0xFFFFFFFFu;
@@ -76,7 +80,7 @@ struct PlanArgs {
     uint32_t *chunk_done;  // [max_chunks]  arrival counter per long segment (at its first chunk), zero between steps
     uint32_t *meta;        // [kMetaWords]
     uint32_t *error_flag;  // shared by the context: bit 0 = key out of range
-    double *zero_loss;     // if not null: loss accumulator that the build resets
+    double *zero_loss;     // if not null: loss accumulator (kLossSlots slots) that the build resets
     const uint32_t *hot_bits; // explicit hot-key set of the table (one bit per key), or null: decide by segment length
 };
 
@@ -146,7 +150,7 @@ struct nups_prepared {
     nups::Plan plan[2];
     int n_plans = 0;
     hipEvent_t ready = nullptr;    // recorded on the side stream after the build
-    double *loss_dev = nullptr;    // this step's loss accumulator
+    double *loss_dev = nullptr;    // this step's loss accumulator: kLossSlots partial sums, kLossStride doubles apart
     uint32_t *negs_buf = nullptr;  // negatives drawn by the step itself (batch.dist)
     size_t negs_cap = 0;
     hipEvent_t fork = nullptr;     // recorded on the caller's stream when the step was prepared

@@ -35,8 +35,8 @@ __global__ void __launch_bounds__(kBlock) k_plan_mark(PlanPair pp)
     const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
     if (i == 0) {
         a.meta[kMetaNumChunks] = 0;
-        if (a.zero_loss) *a.zero_loss = 0.0;   // the step's loss accumulator starts from zero
     }
+    if (i < kLossSlots && a.zero_loss) a.zero_loss[i * kLossStride] = 0.0;   // the step's loss starts from zero
     if (i >= a.n) return;
     const uint32_t key = source_key(a.src, i);
     if (key >= a.num_keys) { atomicOr(a.error_flag, 1u); return; }
