@@ -65,9 +65,12 @@ struct PlanArgs {
     uint32_t direct_count;  // 1: the count scan sums the counts below its tile itself
     // build scratch, owned by the table and shared by all plans of that table (builds run one after another)
     uint8_t *bytemap;      // [32 * words] one byte per key, all zero between builds
-    uint32_t *bitmap;      // [words]     one bit per key, packed from the byte map by every build
-    uint32_t *word_rank;   // [words]     number of distinct keys below each bitmap word
+    uint8_t *wordmap;      // [words]     one byte per bitmap word: some key of the word is marked; zero between builds
+    uint32_t *bitmap;      // [words]     one bit per key; only the words with a marked key are written by a build
+    uint32_t *word_rank;   // [words]     distinct keys below the word inside its tile (written for the same words)
     uint32_t *tile_sum;    // [max(bitmap_tiles, count_tiles)]
+    uint32_t *tile_prefix; // [bitmap_tiles] distinct keys below each tile (tables with very many tiles only)
+    uint32_t *cnt_work;    // [n]         per distinct key: positions handed out so far, zero between builds
     // result, owned by the plan
     uint32_t *uniq;        // [n]         distinct keys, ascending
     uint32_t *count;       // [n]         accesses per distinct key
@@ -92,8 +95,9 @@ struct Plan {
 
 // Build scratch of one table.
 struct PlanScratch {
-    uint8_t *bytemap = nullptr;
-    uint32_t *bitmap = nullptr, *word_rank = nullptr, *tile_sum = nullptr;
+    uint8_t *bytemap = nullptr, *wordmap = nullptr;
+    uint32_t *bitmap = nullptr, *word_rank = nullptr, *tile_sum = nullptr, *tile_prefix = nullptr,
+             *cnt_work = nullptr;
     size_t cap_words = 0, cap_tiles = 0, cap_n = 0;
 };
 

@@ -5,8 +5,9 @@
 // count; no comparison sort is needed.  Up to two tables are planned by the same launches
 // (blockIdx.y selects the table).
 //
-// Marking uses one byte per key and plain stores (idempotent, so no atomics and no contention on
-// hot keys); the bytes are then packed into a bitmap.  Hot keys (Section 3.2: a few keys take a
+// Marking uses one byte per key, and one byte per group of 32 keys, and plain stores (idempotent, so no
+// atomics and no contention on hot keys); only the groups that hold a marked key are then packed into
+// bitmap words, so a build reads 1/32 byte per key of the table plus 32 bytes per group in use.  Hot keys (Section 3.2: a few keys take a
 // large share of the accesses) would serialise the global atomics that hand out positions inside
 // a segment, so every workgroup first combines its own accesses to a key in LDS and issues one
 // global atomic per distinct key; segments that are too long for one row group are cut into
@@ -26,6 +27,7 @@ constexpr int kRankItems = 4;                       // accesses per thread in k_
 constexpr int kRankTile = kBlock * kRankItems;
 constexpr int kHashBits = 11;
 constexpr uint32_t kHashSlots = 1u << kHashBits;    // open-addressing table in LDS, at most half full
+constexpr uint32_t kLdsTiles = 2048;                // tile counts that k_plan_rank scans by itself (64M keys)
 static_assert(kHashSlots >= 2 * kRankTile, "the LDS hash table must stay at most half full");
 
 // Marks the keys of the step in the byte map; flags keys outside the table.
@@ -41,6 +43,7 @@ __global__ void __launch_bounds__(kBlock) k_plan_mark(PlanPair pp)
     const uint32_t key = source_key(a.src, i);
     if (key >= a.num_keys) { atomicOr(a.error_flag, 1u); return; }
     a.bytemap[key] = 1;
+    a.wordmap[key >> 5] = 1;
 }
 
 // Sum of `items[0 .. end)` over the whole workgroup; every thread gets the result.
@@ -67,69 +70,82 @@ __device__ __forceinline__ uint32_t pack4(uint32_t x)
     return (x & 1u) | ((x >> 7) & 2u) | ((x >> 14) & 4u) | ((x >> 21) & 8u);
 }
 
-// Packs the byte map into bitmap words (32 keys each) and counts the marked keys of each tile of kScanTile words.
+// For every tile of kScanTile bitmap words: packs the marked groups of the byte map into bitmap words, ranks each
+// word's distinct keys inside the tile and counts the tile's distinct keys.
 __global__ void __launch_bounds__(kBlock) k_plan_bitmap_tiles(PlanPair pp)
 {
     __shared__ uint32_t lds[kBlock / 64 + 1];
     const PlanArgs &a = pp.p[blockIdx.y];
     if (blockIdx.x >= a.bitmap_tiles) return;
     const uint32_t w0 = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
-    uint32_t c = 0;
-#pragma unroll
-    for (int j = 0; j < kScanItems; ++j) {
-        if (w0 + j < a.words) {      // the byte map is allocated in whole words of 32 keys
-            const uint4 *src = reinterpret_cast<const uint4 *>(a.bytemap + (size_t)(w0 + j) * 32);
-            const uint4 lo = src[0], hi = src[1];
-            const uint32_t bits = pack4(lo.x) | (pack4(lo.y) << 4) | (pack4(lo.z) << 8) | (pack4(lo.w) << 12)
-                                  | (pack4(hi.x) << 16) | (pack4(hi.y) << 20) | (pack4(hi.z) << 24) | (pack4(hi.w) << 28);
-            a.bitmap[w0 + j] = bits;
-            c += __popc(bits);
-        }
-    }
-    const uint32_t s = block_sum(c, lds);
-    if (threadIdx.x == 0) a.tile_sum[blockIdx.x] = s;
-}
-
-// Rank of every bitmap word among the distinct keys; emits the distinct keys and clears their counts.
-__global__ void __launch_bounds__(kBlock) k_plan_bitmap_scan(PlanPair pp)
-{
-    __shared__ uint32_t lds[kBlock / 64 + 1];
-    const PlanArgs &a = pp.p[blockIdx.y];
-    if (blockIdx.x >= a.bitmap_tiles) return;
-    const uint32_t before = block_sum_range(a.tile_sum, blockIdx.x, lds);
-    const uint32_t w0 = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
     uint32_t bits[kScanItems];
     uint32_t c = 0;
 #pragma unroll
     for (int j = 0; j < kScanItems; ++j) {
-        bits[j] = (w0 + j < a.words) ? a.bitmap[w0 + j] : 0u;
-        c += __popc(bits[j]);
-    }
-    uint32_t total;
-    uint32_t run = before + block_exclusive_scan(c, lds, &total);
-#pragma unroll
-    for (int j = 0; j < kScanItems; ++j) {
-        if (w0 + j < a.words) a.word_rank[w0 + j] = run;
-        uint32_t b = bits[j];
-        while (b) {
-            const uint32_t bit = __ffs(b) - 1;
-            b &= b - 1;
-            a.uniq[run] = (w0 + j) * 32 + bit;
-            a.count[run] = 0;
-            ++run;
+        bits[j] = 0;
+        if (w0 + j < a.words && a.wordmap[w0 + j]) {   // the byte map is allocated in whole words of 32 keys
+            const uint4 *src = reinterpret_cast<const uint4 *>(a.bytemap + (size_t)(w0 + j) * 32);
+            const uint4 lo = src[0], hi = src[1];
+            bits[j] = pack4(lo.x) | (pack4(lo.y) << 4) | (pack4(lo.z) << 8) | (pack4(lo.w) << 12)
+                      | (pack4(hi.x) << 16) | (pack4(hi.y) << 20) | (pack4(hi.z) << 24) | (pack4(hi.w) << 28);
+            a.bitmap[w0 + j] = bits[j];
+            a.wordmap[w0 + j] = 0;
+            c += __popc(bits[j]);
         }
     }
-    if (blockIdx.x == a.bitmap_tiles - 1 && threadIdx.x == 0) a.meta[kMetaNumUniq] = before + total;
+    uint32_t total;
+    uint32_t run = block_exclusive_scan(c, lds, &total);
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        if (bits[j]) a.word_rank[w0 + j] = run;
+        run += __popc(bits[j]);
+    }
+    if (threadIdx.x == 0) a.tile_sum[blockIdx.x] = total;
+}
+
+// Exclusive prefix sums of the tile counts into `prefix` (LDS or global); returns the number of distinct keys.
+__device__ __forceinline__ uint32_t scan_tile_sums(const PlanArgs &a, uint32_t *prefix, uint32_t *lds)
+{
+    uint32_t carry = 0;
+    for (uint32_t base = 0; base < a.bitmap_tiles; base += kBlock) {
+        const uint32_t t = base + threadIdx.x;
+        const uint32_t v = t < a.bitmap_tiles ? a.tile_sum[t] : 0u;
+        uint32_t sum;
+        const uint32_t before = block_exclusive_scan(v, lds, &sum);
+        if (t < a.bitmap_tiles) prefix[t] = carry + before;
+        carry += sum;
+    }
+    return carry;
+}
+
+// Tables with more tiles than k_plan_rank scans by itself: the number of distinct keys below each tile, in memory.
+__global__ void __launch_bounds__(kBlock) k_plan_tile_prefix(PlanPair pp)
+{
+    __shared__ uint32_t lds[kBlock / 64 + 1];
+    const PlanArgs &a = pp.p[blockIdx.y];
+    if (a.bitmap_tiles <= kLdsTiles) return;
+    const uint32_t nu = scan_tile_sums(a, a.tile_prefix, lds);
+    if (threadIdx.x == 0) a.meta[kMetaNumUniq] = nu;
 }
 
 // Per access: which distinct key it belongs to and its position inside that key's segment.
 // The workgroup's accesses are first grouped by key in an LDS hash table; one global atomic per
-// distinct key and workgroup reserves a run of positions, which the LDS counts subdivide.
+// distinct key and workgroup reserves a run of positions, which the LDS counts subdivide.  Also
+// emits the distinct keys (every workgroup writes the keys it met; equal values where they meet).
 __global__ void __launch_bounds__(kBlock) k_plan_rank(PlanPair pp)
 {
-    __shared__ uint32_t hkey[kHashSlots], hcnt[kHashSlots], hbase[kHashSlots];
+    __shared__ uint32_t hkey[kHashSlots], hcnt[kHashSlots], hbase[kHashSlots], hval[kHashSlots];
+    __shared__ uint32_t tile_prefix_lds[kLdsTiles];
+    __shared__ uint32_t lds[kBlock / 64 + 1];
     const PlanArgs &a = pp.p[blockIdx.y];
-    if (blockIdx.x * kRankTile >= a.n) return;
+    if (blockIdx.x * kRankTile >= a.n && blockIdx.x != 0) return;
+    // distinct keys below each bitmap tile: every workgroup scans the tile counts for itself
+    const uint32_t *tile_prefix = a.tile_prefix;
+    if (a.bitmap_tiles <= kLdsTiles) {
+        const uint32_t nu = scan_tile_sums(a, tile_prefix_lds, lds);
+        if (blockIdx.x == 0 && threadIdx.x == 0) a.meta[kMetaNumUniq] = nu;
+        tile_prefix = tile_prefix_lds;
+    }
     for (uint32_t s = threadIdx.x; s < kHashSlots; s += kBlock) { hkey[s] = kBadIndex; hcnt[s] = 0; }
     __syncthreads();
     uint32_t slot_of[kRankItems], local[kRankItems], uidx[kRankItems];
@@ -141,7 +157,7 @@ __global__ void __launch_bounds__(kBlock) k_plan_rank(PlanPair pp)
             const uint32_t key = source_key(a.src, i);
             if (key < a.num_keys) {
                 const uint32_t w = key >> 5, b = key & 31;
-                const uint32_t u = a.word_rank[w] + __popc(a.bitmap[w] & ((1u << b) - 1u));
+                const uint32_t u = tile_prefix[w / kScanTile] + a.word_rank[w] + __popc(a.bitmap[w] & ((1u << b) - 1u));
                 uidx[j] = u;
                 uint32_t s = (u * 2654435761u) >> (32 - kHashBits);
                 for (;;) {   // ends: at most kRankTile distinct keys in 2 * kRankTile slots
@@ -150,13 +166,17 @@ __global__ void __launch_bounds__(kBlock) k_plan_rank(PlanPair pp)
                     s = (s + 1) & (kHashSlots - 1);
                 }
                 slot_of[j] = s;
+                hval[s] = key;
                 local[j] = atomicAdd(&hcnt[s], 1u);
             }
         }
     }
     __syncthreads();
     for (uint32_t s = threadIdx.x; s < kHashSlots; s += kBlock)
-        if (hcnt[s]) hbase[s] = atomicAdd(&a.count[hkey[s]], hcnt[s]);
+        if (hcnt[s]) {
+            hbase[s] = atomicAdd(&a.cnt_work[hkey[s]], hcnt[s]);
+            a.uniq[hkey[s]] = hval[s];
+        }
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < kRankItems; ++j) {
@@ -179,7 +199,7 @@ __global__ void __launch_bounds__(kBlock) k_plan_count_tiles(PlanPair pp)
     uint32_t c = 0;
 #pragma unroll
     for (int j = 0; j < kScanItems; ++j)
-        if (u0 + j < nu) c += a.count[u0 + j];
+        if (u0 + j < nu) c += a.cnt_work[u0 + j];
     const uint32_t s = block_sum(c, lds);
     if (threadIdx.x == 0) a.tile_sum[blockIdx.x] = s;
 }
@@ -194,13 +214,13 @@ __global__ void __launch_bounds__(kBlock) k_plan_count_scan(PlanPair pp)
     const uint32_t u0 = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
     if (blockIdx.x * kScanTile >= nu && blockIdx.x != 0) return;
     uint32_t before;
-    if (a.direct_count) before = block_sum_range(a.count, min(blockIdx.x * kScanTile, nu), lds);
+    if (a.direct_count) before = block_sum_range(a.cnt_work, min(blockIdx.x * kScanTile, nu), lds);
     else before = block_sum_range(a.tile_sum, blockIdx.x, lds);
     uint32_t cnt[kScanItems];
     uint32_t c = 0;
 #pragma unroll
     for (int j = 0; j < kScanItems; ++j) {
-        cnt[j] = (u0 + j < nu) ? a.count[u0 + j] : 0u;
+        cnt[j] = (u0 + j < nu) ? a.cnt_work[u0 + j] : 0u;
         c += cnt[j];
     }
     uint32_t total;
@@ -209,6 +229,7 @@ __global__ void __launch_bounds__(kBlock) k_plan_count_scan(PlanPair pp)
     for (int j = 0; j < kScanItems; ++j) {
         if (u0 + j < nu) {
             a.seg[u0 + j] = run;
+            a.count[u0 + j] = cnt[j];
             if (takes_hot_path(cnt[j], a.uniq[u0 + j], a.hot_bits)) {
                 const uint32_t nch = (cnt[j] + kChunk - 1) / kChunk;
                 const uint32_t base = atomicAdd(&a.meta[kMetaNumChunks], nch);
@@ -226,7 +247,7 @@ __global__ void __launch_bounds__(kBlock) k_plan_count_scan(PlanPair pp)
     }
 }
 
-// Groups the accesses by key and returns the byte map to all-zero for the next step.
+// Groups the accesses by key and returns the byte map and the position counters to all-zero for the next step.
 __global__ void __launch_bounds__(kBlock) k_plan_scatter(PlanPair pp)
 {
     const PlanArgs &a = pp.p[blockIdx.y];
@@ -234,8 +255,10 @@ __global__ void __launch_bounds__(kBlock) k_plan_scatter(PlanPair pp)
     if (i >= a.n) return;
     const uint32_t u = a.slot[i];
     if (u == kBadIndex) return;
-    a.perm[a.seg[u] + a.rank[i]] = i;
+    const uint32_t r = a.rank[i];
+    a.perm[a.seg[u] + r] = i;
     a.bytemap[source_key(a.src, i)] = 0;
+    if (r == 0) a.cnt_work[u] = 0;
 }
 
 static nups_status grow_u32(uint32_t **buf, size_t n, bool zero, hipStream_t stream)
@@ -268,9 +291,10 @@ void free_plan_arrays(Plan &pl)
 
 void free_plan_scratch(PlanScratch &sc)
 {
-    for (uint32_t *p : {sc.bitmap, sc.word_rank, sc.tile_sum})
+    for (uint32_t *p : {sc.bitmap, sc.word_rank, sc.tile_sum, sc.tile_prefix, sc.cnt_work})
         if (p) (void)hipFree(p);
     if (sc.bytemap) (void)hipFree(sc.bytemap);
+    if (sc.wordmap) (void)hipFree(sc.wordmap);
     sc = PlanScratch{};
 }
 
@@ -295,10 +319,15 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
         if ((st = quiesce(ctx)) != NUPS_OK) return st;
         if ((st = grow_u32(&sc.bitmap, words, true, ctx->side)) != NUPS_OK) return st;
         if ((st = grow_u32((uint32_t **)&sc.bytemap, words * 8, true, ctx->side)) != NUPS_OK) return st;   // 32 bytes per word
+        if ((st = grow_u32((uint32_t **)&sc.wordmap, (words + 3) / 4, true, ctx->side)) != NUPS_OK) return st;
         if ((st = grow_u32(&sc.word_rank, words, false, ctx->side)) != NUPS_OK) return st;
         sc.cap_words = words;
     }
-    if (sc.cap_n < n || sc.cap_n == 0) sc.cap_n = n + n / 4 + 1024;   // sizes the tile sums below
+    if (sc.cap_n < n || sc.cap_n == 0) {
+        if ((st = quiesce(ctx)) != NUPS_OK) return st;
+        sc.cap_n = n + n / 4 + 1024;                       // also sizes the tile sums below
+        if ((st = grow_u32(&sc.cnt_work, sc.cap_n, true, ctx->side)) != NUPS_OK) return st;
+    }
     if (pl.cap_n < n || pl.cap_n == 0) {
         if ((st = quiesce(ctx)) != NUPS_OK) return st;
         const size_t cap = n + n / 4 + 1024;
@@ -316,10 +345,12 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
     if (sc.cap_tiles < tiles) {
         if ((st = quiesce(ctx)) != NUPS_OK) return st;
         if ((st = grow_u32(&sc.tile_sum, tiles, false, ctx->side)) != NUPS_OK) return st;
+        if ((st = grow_u32(&sc.tile_prefix, tiles, false, ctx->side)) != NUPS_OK) return st;
         sc.cap_tiles = tiles;
     }
-    a.bytemap = sc.bytemap;
-    a.bitmap = sc.bitmap; a.word_rank = sc.word_rank; a.tile_sum = sc.tile_sum;
+    a.bytemap = sc.bytemap; a.wordmap = sc.wordmap;
+    a.bitmap = sc.bitmap; a.word_rank = sc.word_rank; a.tile_sum = sc.tile_sum; a.tile_prefix = sc.tile_prefix;
+    a.cnt_work = sc.cnt_work;
     a.num_keys = (uint32_t)t.num_keys;
     a.words = (uint32_t)words;
     a.bitmap_tiles = (uint32_t)((words + kScanTile - 1) / kScanTile);
@@ -354,7 +385,7 @@ nups_status build_plans(nups_ctx *ctx, Plan *plans, int n_plans)
     hipStream_t s = ctx->side;
     hipLaunchKernelGGL(k_plan_mark, dim3(nblocks, n_plans), blk, 0, s, pp);
     hipLaunchKernelGGL(k_plan_bitmap_tiles, dim3(max_btiles, n_plans), blk, 0, s, pp);
-    hipLaunchKernelGGL(k_plan_bitmap_scan, dim3(max_btiles, n_plans), blk, 0, s, pp);
+    if (max_btiles > kLdsTiles) hipLaunchKernelGGL(k_plan_tile_prefix, dim3(1, n_plans), blk, 0, s, pp);
     hipLaunchKernelGGL(k_plan_rank, dim3(rblocks, n_plans), blk, 0, s, pp);
     if (need_count_tiles) hipLaunchKernelGGL(k_plan_count_tiles, dim3(max_ctiles, n_plans), blk, 0, s, pp);
     hipLaunchKernelGGL(k_plan_count_scan, dim3(max_ctiles, n_plans), blk, 0, s, pp);
