@@ -28,6 +28,8 @@ constexpr int kScanTile = kBlock * kScanItems;
 // apart): thousands of workgroups adding to one address would queue up behind each other.  The host adds the slots.
 constexpr int kLossSlots = 64;
 constexpr int kLossStride = 16;
+// Flag in rank[i]: access i is the only access of its key in this step (its position is then 0).
+constexpr uint32_t kSingleAccess = 0x80000000u;
 constexpr uint32_t kLongSegment = 16; // segments with more accesses are summed by whole workgroups, in chunks
 constexpr uint32_t kChunk = 128;      // accesses of a long segment that one workgroup sums
 constexpr uint32_t kBadIndex = 0xFFFFFFFFu;
@@ -77,7 +79,7 @@ struct PlanArgs {
     uint32_t *seg;         // [n + 1]     exclusive prefix sums of count
     uint32_t *perm;        // [n]         accesses grouped by key
     uint32_t *slot;        // [n]         per access: index of its key among the distinct keys
-    uint32_t *rank;        // [n]         per access: position inside its key's segment
+    uint32_t *rank;        // [n]         per access: position inside its key's segment (| kSingleAccess)
     uint32_t *chunk_seg;   // [max_chunks]  distinct-key index of the long segment a chunk belongs to
     uint32_t *chunk_base;  // [max_chunks]  number of the first chunk of that segment
     uint32_t *chunk_done;  // [max_chunks]  arrival counter per long segment (at its first chunk), zero between steps

@@ -139,6 +139,22 @@ __global__ void __launch_bounds__(kBlock) k_plan_rank(PlanPair pp)
     __shared__ uint32_t lds[kBlock / 64 + 1];
     const PlanArgs &a = pp.p[blockIdx.y];
     if (blockIdx.x * kRankTile >= a.n && blockIdx.x != 0) return;
+    uint32_t slot_of[kRankItems], local[kRankItems], uidx[kRankItems], key[kRankItems];
+    // all loads are issued before the first use (keys, then their bitmap words and word ranks), and before the
+    // scan below, which hides their latency
+#pragma unroll
+    for (int j = 0; j < kRankItems; ++j) {
+        const uint32_t i = blockIdx.x * kRankTile + j * kBlock + threadIdx.x;
+        key[j] = i < a.n ? source_key(a.src, i) : kBadIndex;
+        if (key[j] >= a.num_keys) key[j] = kBadIndex;     // outside the table: flagged when it was marked
+    }
+    uint32_t below[kRankItems], bits[kRankItems];
+#pragma unroll
+    for (int j = 0; j < kRankItems; ++j) {
+        const uint32_t w = key[j] >> 5;
+        below[j] = key[j] != kBadIndex ? a.word_rank[w] : 0u;
+        bits[j] = key[j] != kBadIndex ? a.bitmap[w] : 0u;
+    }
     // distinct keys below each bitmap tile: every workgroup scans the tile counts for itself
     const uint32_t *tile_prefix = a.tile_prefix;
     if (a.bitmap_tiles <= kLdsTiles) {
@@ -148,35 +164,42 @@ __global__ void __launch_bounds__(kBlock) k_plan_rank(PlanPair pp)
     }
     for (uint32_t s = threadIdx.x; s < kHashSlots; s += kBlock) { hkey[s] = kBadIndex; hcnt[s] = 0; }
     __syncthreads();
-    uint32_t slot_of[kRankItems], local[kRankItems], uidx[kRankItems];
 #pragma unroll
     for (int j = 0; j < kRankItems; ++j) {
-        const uint32_t i = blockIdx.x * kRankTile + j * kBlock + threadIdx.x;
         uidx[j] = kBadIndex;
-        if (i < a.n) {
-            const uint32_t key = source_key(a.src, i);
-            if (key < a.num_keys) {
-                const uint32_t w = key >> 5, b = key & 31;
-                const uint32_t u = tile_prefix[w / kScanTile] + a.word_rank[w] + __popc(a.bitmap[w] & ((1u << b) - 1u));
-                uidx[j] = u;
-                uint32_t s = (u * 2654435761u) >> (32 - kHashBits);
-                for (;;) {   // ends: at most kRankTile distinct keys in 2 * kRankTile slots
-                    const uint32_t old = atomicCAS(&hkey[s], kBadIndex, u);
-                    if (old == kBadIndex || old == u) break;
-                    s = (s + 1) & (kHashSlots - 1);
-                }
-                slot_of[j] = s;
-                hval[s] = key;
-                local[j] = atomicAdd(&hcnt[s], 1u);
+        if (key[j] != kBadIndex) {
+            const uint32_t w = key[j] >> 5, b = key[j] & 31;
+            const uint32_t u = tile_prefix[w / kScanTile] + below[j] + __popc(bits[j] & ((1u << b) - 1u));
+            uidx[j] = u;
+            uint32_t s = (u * 2654435761u) >> (32 - kHashBits);
+            for (;;) {   // ends: at most kRankTile distinct keys in 2 * kRankTile slots
+                const uint32_t old = atomicCAS(&hkey[s], kBadIndex, u);
+                if (old == kBadIndex || old == u) break;
+                s = (s + 1) & (kHashSlots - 1);
             }
+            slot_of[j] = s;
+            hval[s] = key[j];
+            local[j] = atomicAdd(&hcnt[s], 1u);
         }
     }
     __syncthreads();
-    for (uint32_t s = threadIdx.x; s < kHashSlots; s += kBlock)
-        if (hcnt[s]) {
-            hbase[s] = atomicAdd(&a.cnt_work[hkey[s]], hcnt[s]);
-            a.uniq[hkey[s]] = hval[s];
+    {   // one global atomic per distinct key of the workgroup; all of a thread's atomics are in flight together
+        constexpr int kPerThread = kHashSlots / kBlock;
+        uint32_t base[kPerThread], cnt[kPerThread];
+#pragma unroll
+        for (int q = 0; q < kPerThread; ++q) {
+            const uint32_t s = q * kBlock + threadIdx.x;
+            cnt[q] = hcnt[s];
+            base[q] = 0;
+            if (cnt[q]) {
+                base[q] = atomicAdd(&a.cnt_work[hkey[s]], cnt[q]);
+                a.uniq[hkey[s]] = hval[s];
+            }
         }
+#pragma unroll
+        for (int q = 0; q < kPerThread; ++q)
+            if (cnt[q]) hbase[q * kBlock + threadIdx.x] = base[q];
+    }
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < kRankItems; ++j) {
@@ -256,9 +279,13 @@ __global__ void __launch_bounds__(kBlock) k_plan_scatter(PlanPair pp)
     const uint32_t u = a.slot[i];
     if (u == kBadIndex) return;
     const uint32_t r = a.rank[i];
-    a.perm[a.seg[u] + r] = i;
+    const uint32_t first = a.seg[u], next = a.seg[u + 1];
+    a.perm[first + r] = i;
     a.bytemap[source_key(a.src, i)] = 0;
-    if (r == 0) a.cnt_work[u] = 0;
+    if (r == 0) {
+        a.cnt_work[u] = 0;
+        if (next - first == 1) a.rank[i] = kSingleAccess;   // lets the update skip the segment lookup
+    }
 }
 
 static nups_status grow_u32(uint32_t **buf, size_t n, bool zero, hipStream_t stream)

@@ -198,12 +198,14 @@ __device__ __forceinline__ void apply_short_item(const ApplyArgs &a, const Src &
                                                  const ApplyShape &sh, uint32_t item, int lane, int group)
 {
     const uint32_t w = item * kGroupsPerBlock + group;
-    uint32_t u = kBadIndex, key = 0, only = kBadIndex;
+    uint32_t u = kBadIndex, key = 0;
+    bool single = false;
     if (sh.access_order) {
         if (w < a.n) {
             key = source_key(a.keys, w);
-            if (a.rank[w] == 0) u = a.slot[w];       // kBadIndex for a key outside the table
-            only = w;
+            const uint32_t r = a.rank[w], s = a.slot[w];   // s: kBadIndex for a key outside the table
+            if ((r & ~kSingleAccess) == 0) u = s;
+            single = (r & kSingleAccess) != 0;
         }
     } else if (w < sh.nu) {
         u = w;
@@ -212,17 +214,18 @@ __device__ __forceinline__ void apply_short_item(const ApplyArgs &a, const Src &
     if (u == kBadIndex) return;
     const size_t off = (size_t)key * a.stride;
     float *row = a.table + off, *state_row = Opt::kHasState ? a.state + off : nullptr;
-    const uint32_t first = a.seg[u], last = a.seg[u + 1];
-    if (takes_hot_path(last - first, key, a.hot_bits)) return;   // summed by chunk items
     Row<NV4> acc, t, g;
     zero_row(acc);
-    if (last - first == 1 && only != kBadIndex) {
-        // the segment is this access alone: the row, its state and the source row are requested together
+    if (single) {
+        // the segment is this access alone (never a chunked one): the row, its state and the source row are
+        // requested together, two dependent reads after the start
         opt.template load<NV4>(t, g, row, state_row, lane);
         Row<NV4> r;
-        load_row(r, src.row(only, a.stride), lane);
-        axpy_row(acc, src.coef(only), r);
+        load_row(r, src.row(w, a.stride), lane);
+        axpy_row(acc, src.coef(w), r);
     } else {
+        const uint32_t first = a.seg[u], last = a.seg[u + 1];
+        if (takes_hot_path(last - first, key, a.hot_bits)) return;   // summed by chunk items
         sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
         opt.template load<NV4>(t, g, row, state_row, lane);
     }

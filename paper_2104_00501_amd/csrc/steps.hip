@@ -66,7 +66,7 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(const float *in_table, con
     Row<NV4> v, acc;
     load_row(v, in_table + (size_t)min(center[e], num_in - 1) * stride, lane);
     // the first pair of every distinct center word keeps a copy of the input vector for the output-side update
-    if (active && center_slot[e] != kBadIndex && center_rank[e] == 0)
+    if (active && center_slot[e] != kBadIndex && (center_rank[e] & ~kSingleAccess) == 0)
         store_row(center_rows + (size_t)center_slot[e] * stride, v, lane);
     zero_row(acc);
     float loss_acc = 0.f;
