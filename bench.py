@@ -279,6 +279,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="sgns_1m_d300_bounded_u4", choices=sorted(WORKLOADS))
+    ap.add_argument("--depth", type=int, default=1, help="steps prepared ahead of the one that runs")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: about 15 s worth, 0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -302,13 +303,14 @@ def main() -> int:
             w.states_initial = [t.clone() for t in w.states]
 
     def run(first, count):
-        # software pipeline: step t+1 is prepared before step t runs, so the two overlap on the GPU
-        nxt = w.prepare(first)
-        for t in range(first, first + count):
-            p = nxt
-            if t + 1 < first + count:
-                nxt = w.prepare(t + 1)
-            nb.nups_step_prepared(ctx, p)
+        # software pipeline: steps t+1 .. t+depth are prepared before step t runs, so that sampling and the
+        # aggregation structure of later steps overlap the table work of step t on the GPU
+        last = first + count
+        queue = [w.prepare(t) for t in range(first, min(first + args.depth, last))]
+        for t in range(first, last):
+            if t + args.depth < last:
+                queue.append(w.prepare(t + args.depth))
+            nb.nups_step_prepared(ctx, queue.pop(0))
 
     # ---- warm-up, then the timed region ---------------------------------------------------------
     run(0, args.warmup)

@@ -98,6 +98,7 @@ nups_status sync_side(nups_ctx *ctx)
 {
     worker_drain(ctx);
     NUPS_HIP(hipStreamSynchronize(ctx->side));
+    NUPS_HIP(hipStreamSynchronize(ctx->side1));
     return NUPS_OK;
 }
 
@@ -309,6 +310,7 @@ nups_status nups_init(nups_ctx **out, int n_tables, float *const *tables_dev, co
         ctx->tab[t].stride = row_stride[t];
     }
     hipError_t e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);   // default priority
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->side1, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->error_flag, sizeof(uint32_t));
     if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->loss_pinned, sizeof(double) * kLossSlots * kLossStride, hipHostMallocDefault);
@@ -331,11 +333,12 @@ nups_status nups_destroy(nups_ctx *ctx)
     if (!ctx) return fail(NUPS_ERR_ARG, "nups_destroy: null context");
     worker_stop(ctx);
     if (ctx->side) (void)hipStreamSynchronize(ctx->side);
+    if (ctx->side1) (void)hipStreamSynchronize(ctx->side1);
     (void)hipStreamSynchronize(ctx->stream);
     for (nups_dist *d : ctx->dists) free_dist(d);
     for (nups_prepared *p : ctx->prepared_all) free_prepared(p);
     for (int t = 0; t < kMaxTables; ++t) {
-        free_plan_scratch(ctx->tab[t].scratch);
+        for (int l = 0; l < kLanes; ++l) free_plan_scratch(ctx->tab[t].scratch[l]);
         if (ctx->tab[t].hot_bits_dev) (void)hipFree(ctx->tab[t].hot_bits_dev);
     }
     if (ctx->coef) (void)hipFree(ctx->coef);
@@ -350,6 +353,7 @@ nups_status nups_destroy(nups_ctx *ctx)
     }
     if (ctx->fork) (void)hipEventDestroy(ctx->fork);
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
+    if (ctx->side1) (void)hipStreamDestroy(ctx->side1);
     delete ctx;
     return NUPS_OK;
 }
@@ -404,13 +408,14 @@ nups_status nups_push(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_
     if (st != NUPS_OK) return st;
     p->n_plans = 1;
     p->plan[0].table = table;
-    if ((st = ensure_plan_capacity(ctx, t, p->plan[0], (size_t)n)) != NUPS_OK) return st;
+    p->lane = 0;
+    if ((st = ensure_plan_capacity(ctx, t, p->plan[0], (size_t)n, 0)) != NUPS_OK) return st;
     p->plan[0].a.src = KeySource{{keys_dev, nullptr, nullptr}, {(uint32_t)n, 0, 0}};
     p->plan[0].a.n = (uint32_t)n;
     p->plan[0].a.zero_loss = nullptr;
     if ((st = ensure_partial(ctx, max_chunks(p->plan[0].cap_n) * (size_t)t.stride)) != NUPS_OK) return st;
     if ((st = side_after_main(ctx)) != NUPS_OK) return st;
-    if ((st = build_plans(ctx, p->plan, 1)) != NUPS_OK) return st;
+    if ((st = build_plans(ctx, ctx->side, p->plan, 1)) != NUPS_OK) return st;
     NUPS_HIP(hipEventRecord(p->ready, ctx->side));
     NUPS_HIP(hipStreamWaitEvent(ctx->stream, p->ready, 0));
     if (n > 0) st = launch_push_apply(ctx, t, p->plan[0], updates_dev);
@@ -500,6 +505,7 @@ nups_status nups_prepare_sample(nups_dist *dist, int64_t n, uint64_t step, nups_
     if (st == NUPS_OK && (h->cap < (size_t)n || !h->keys_dev)) {
         worker_drain(ctx);
         hipError_t e = hipStreamSynchronize(ctx->side);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->side1);
         if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
         if (e == hipSuccess && h->keys_dev) e = hipFree(h->keys_dev);
         h->keys_dev = nullptr;
@@ -568,10 +574,13 @@ nups_status nups_release_sample(nups_sample *h)
 static void issue_side_work(nups_ctx *ctx, nups_prepared *p, const SampleSpec &spec, int64_t n_draw, uint64_t step)
 {
     nups_status st = NUPS_OK;
-    if (hipStreamWaitEvent(ctx->side, p->fork, 0) != hipSuccess) st = fail(NUPS_ERR_DEVICE, "prepared step: stream wait failed");
-    if (st == NUPS_OK && n_draw > 0) st = launch_sample(ctx, ctx->side, spec, p->negs_buf, n_draw, step);
-    if (st == NUPS_OK) st = build_plans(ctx, p->plan, p->n_plans);
-    if (st == NUPS_OK && hipEventRecord(p->ready, ctx->side) != hipSuccess)
+    hipStream_t side = side_stream(ctx, p->lane);
+    if (hipStreamWaitEvent(side, p->fork, 0) != hipSuccess) st = fail(NUPS_ERR_DEVICE, "prepared step: stream wait failed");
+    if (st == NUPS_OK && p->after && hipStreamWaitEvent(side, p->after, 0) != hipSuccess)
+        st = fail(NUPS_ERR_DEVICE, "prepared step: stream wait failed");
+    if (st == NUPS_OK && n_draw > 0) st = launch_sample(ctx, side, spec, p->negs_buf, n_draw, step);
+    if (st == NUPS_OK) st = build_plans(ctx, side, p->plan, p->n_plans);
+    if (st == NUPS_OK && hipEventRecord(p->ready, side) != hipSuccess)
         st = fail(NUPS_ERR_DEVICE, "prepared step: event record failed");
     if (st != NUPS_OK) p->error = nups_last_error();
     p->submitted.store(st == NUPS_OK ? 1 : (int)st, std::memory_order_release);
@@ -587,14 +596,18 @@ static nups_status prepare_step(nups_ctx *ctx, const nups_batch *b, nups_prepare
     nups_prepared *p = nullptr;
     if ((st = get_prepared(ctx, &p)) != NUPS_OK) return st;
     p->batch = *b;
-    if (b->sample) {   // drawn on the side stream, i.e. before the build that follows on the same stream
+    p->after = nullptr;
+    p->lane = background ? (ctx->next_lane ^= 1) : 0;   // consecutive prepared steps build on different side streams
+    if (b->sample) {   // drawn on side stream 0: the build waits for the handle's event
         p->batch.negs = b->sample->keys_dev;
         p->batch.sample = nullptr;
+        p->after = b->sample->ready;
     }
     const int64_t n_draw = b->dist ? b->B * ((int64_t)b->n_neg + b->n_neg2) : 0;
     if (n_draw > 0 && p->negs_cap < (size_t)n_draw) {   // the step draws its own negatives into its own buffer
         worker_drain(ctx);
         hipError_t e = hipStreamSynchronize(ctx->side);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->side1);
         if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
         if (e == hipSuccess && p->negs_buf) e = hipFree(p->negs_buf);
         p->negs_buf = nullptr;

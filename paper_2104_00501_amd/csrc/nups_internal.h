@@ -21,6 +21,7 @@ constexpr int kGroup = 16;            // lanes that cooperate on one row (one DP
 constexpr int kBlock = 256;           // threads per workgroup (4 wavefronts, 16 row groups)
 constexpr int kGroupsPerBlock = kBlock / kGroup;
 constexpr int kMaxTables = 4;
+constexpr int kLanes = 2;              // side streams: the structures of consecutive prepared steps are built concurrently
 constexpr int kMaxStride = 1024;
 constexpr int kScanItems = 2;         // items per thread in the tile scans
 constexpr int kScanTile = kBlock * kScanItems;
@@ -111,7 +112,7 @@ struct Table {
     int32_t stride = 0;
     std::vector<uint32_t> hot_keys;   // hottest first (as declared by the caller)
     uint32_t *hot_bits_dev = nullptr; // [ceil(V/32)] membership bitmap of the declared set; null = none declared
-    PlanScratch scratch;
+    PlanScratch scratch[kLanes];      // one per side stream
     Plan *last_plan = nullptr;        // structure of the last step / push on this table (owned by a prepared step)
 };
 
@@ -160,6 +161,8 @@ struct nups_prepared {
     uint32_t *negs_buf = nullptr;  // negatives drawn by the step itself (batch.dist)
     size_t negs_cap = 0;
     hipEvent_t fork = nullptr;     // recorded on the caller's stream when the step was prepared
+    hipEvent_t after = nullptr;    // borrowed: the sample handle's event that the build also waits for, or null
+    int lane = 0;                  // side stream (and table scratch) that builds this step's structure
     bool live = false;             // prepared, not yet run
     bool retired = false;          // run, still referenced by a table's structure query
     std::atomic<int> submitted{0}; // 0: the side-stream work is still queued; 1: enqueued; < 0: it failed (status)
@@ -170,7 +173,9 @@ struct nups_ctx {
     int n_tables = 0;
     nups::Table tab[nups::kMaxTables];
     hipStream_t stream = nullptr;   // the caller's stream: everything that touches table values
-    hipStream_t side = nullptr;     // library-owned: sampling and plan construction ("background" work)
+    hipStream_t side = nullptr;     // library-owned: sampling and plan construction ("background" work), lane 0
+    hipStream_t side1 = nullptr;    // lane 1
+    int next_lane = 0;
     hipEvent_t fork = nullptr;      // main -> side ordering for work enqueued by the calling thread itself
     int device = 0;
     nups::Worker *worker = nullptr; // issues the side-stream work of prepared steps
@@ -236,8 +241,9 @@ nups_status launch_sample(nups_ctx *ctx, hipStream_t stream, const SampleSpec &d
                           uint64_t step);
 void worker_drain(nups_ctx *ctx);
 nups_status sync_side(nups_ctx *ctx);
-nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n);
-nups_status build_plans(nups_ctx *ctx, Plan *plans, int n_plans);
+nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n, int lane);
+nups_status build_plans(nups_ctx *ctx, hipStream_t stream, Plan *plans, int n_plans);
+inline hipStream_t side_stream(const nups_ctx *ctx, int lane) { return lane == 0 ? ctx->side : ctx->side1; }
 void free_plan_arrays(Plan &pl);
 void free_plan_scratch(PlanScratch &sc);
 nups_status launch_pull(nups_ctx *ctx, const Table &t, const uint32_t *keys, int64_t n, float *values);

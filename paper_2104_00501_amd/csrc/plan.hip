@@ -288,12 +288,13 @@ __global__ void __launch_bounds__(kBlock) k_plan_scatter(PlanPair pp)
     }
 }
 
-static nups_status grow_u32(uint32_t **buf, size_t n, bool zero, hipStream_t stream)
+// (Re)allocates; all streams are idle when this is called, and the clearing has finished when it returns.
+static nups_status grow_u32(uint32_t **buf, size_t n, bool zero, hipStream_t)
 {
     if (*buf) NUPS_HIP(hipFree(*buf));
     *buf = nullptr;
     NUPS_HIP(hipMalloc((void **)buf, sizeof(uint32_t) * (n ? n : 1)));
-    if (zero) NUPS_HIP(hipMemsetAsync(*buf, 0, sizeof(uint32_t) * (n ? n : 1), stream));
+    if (zero) NUPS_HIP(hipMemset(*buf, 0, sizeof(uint32_t) * (n ? n : 1)));
     return NUPS_OK;
 }
 
@@ -336,9 +337,9 @@ static nups_status quiesce(nups_ctx *ctx)
 
 // Makes the table's build scratch and the plan's result arrays large enough for n accesses and
 // fills in the plan's pointers and shape fields.  Growing waits for both streams.
-nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
+nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n, int lane)
 {
-    PlanScratch &sc = t.scratch;
+    PlanScratch &sc = t.scratch[lane];
     PlanArgs &a = pl.a;
     nups_status st;
     const size_t words = (size_t)((t.num_keys + 31) / 32);
@@ -386,11 +387,11 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
     return NUPS_OK;
 }
 
-// Enqueues, on the side stream, the plan construction for one or two tables (a.src, a.n set by the caller).
-nups_status build_plans(nups_ctx *ctx, Plan *plans, int n_plans)
+// Enqueues, on side stream `s`, the plan construction for one or two tables (a.src, a.n set by the caller).
+nups_status build_plans(nups_ctx *ctx, hipStream_t s, Plan *plans, int n_plans)
 {
     if (n_plans < 1 || n_plans > 2) return fail(NUPS_ERR_ARG, "build_plans: one or two plans");
-    PhaseScope scope(ctx, NUPS_PHASE_PLAN, ctx->side);
+    PhaseScope scope(ctx, NUPS_PHASE_PLAN, s);
     PlanPair pp;
     uint32_t max_n = 0, max_btiles = 0, max_ctiles = 0;
     bool need_count_tiles = false;
@@ -409,7 +410,6 @@ nups_status build_plans(nups_ctx *ctx, Plan *plans, int n_plans)
     const dim3 blk(kBlock);
     const uint32_t nblocks = std::max(1u, (max_n + kBlock - 1) / kBlock);
     const uint32_t rblocks = std::max(1u, (max_n + kRankTile - 1) / kRankTile);
-    hipStream_t s = ctx->side;
     hipLaunchKernelGGL(k_plan_mark, dim3(nblocks, n_plans), blk, 0, s, pp);
     hipLaunchKernelGGL(k_plan_bitmap_tiles, dim3(max_btiles, n_plans), blk, 0, s, pp);
     if (max_btiles > kLdsTiles) hipLaunchKernelGGL(k_plan_tile_prefix, dim3(1, n_plans), blk, 0, s, pp);

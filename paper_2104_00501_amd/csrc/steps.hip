@@ -115,8 +115,8 @@ static nups_status plan_two_tables(nups_ctx *ctx, nups_prepared &p, const KeySou
     p.n_plans = 2;
     p.plan[0].table = 0;
     p.plan[1].table = 1;
-    if ((st = ensure_plan_capacity(ctx, ctx->tab[0], p.plan[0], n0)) != NUPS_OK) return st;
-    if ((st = ensure_plan_capacity(ctx, ctx->tab[1], p.plan[1], n1)) != NUPS_OK) return st;
+    if ((st = ensure_plan_capacity(ctx, ctx->tab[0], p.plan[0], n0, p.lane)) != NUPS_OK) return st;
+    if ((st = ensure_plan_capacity(ctx, ctx->tab[1], p.plan[1], n1, p.lane)) != NUPS_OK) return st;
     p.plan[0].a.src = s0;
     p.plan[0].a.n = n0;
     p.plan[1].a.src = s1;
