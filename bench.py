@@ -273,13 +273,42 @@ WORKLOADS = {
 WORKLOADS.update(_sweep_workloads())
 
 
+def kernel_sources_digest():
+    """sha256 over the library's kernel sources, in name order."""
+    import hashlib
+    csrc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2104_00501_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            with open(os.path.join(csrc, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()
+
+
+def recorded_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the hardware-counter runs summarised in profiles/hbm_traffic.txt
+    (fetch bytes already scaled by the calibration copy), or None when no line matches the workload, the
+    kernel and the present kernel sources: counters taken before a kernel changed say nothing about it."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    digest = kernel_sources_digest()
+    with open(path) as f:
+        for line in f:
+            parts = line.split()
+            if len(parts) == 5 and not line.startswith("#") and parts[0] == workload and parts[1] == kernel \
+                    and parts[4] == digest:
+                return float(parts[2]) + float(parts[3])
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="sgns_1m_d300_bounded_u4", choices=sorted(WORKLOADS))
-    ap.add_argument("--depth", type=int, default=1, help="steps prepared ahead of the one that runs")
+    ap.add_argument("--depth", type=int, default=2, help="steps prepared ahead of the one that runs")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: about 15 s worth, 0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -364,7 +393,7 @@ def main() -> int:
     dom_ms = phases[dominant]
     achieved = alg[dominant] / (dom_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": recorded_traffic(args.workload, dominant),
                 "algorithmic_bytes_per_launch": alg[dominant], "kernel_ms": dom_ms,
                 "per_kernel_GBps": {p: alg[p] / (phases[p] * 1e-3) / 1e9 for p in ("grad", "apply0", "apply1")
                                     if p in phases and p in alg},

@@ -313,8 +313,9 @@ __device__ __forceinline__ void add_grad_relation(Row<NV4> &out, const Row<NV4> 
     }
 }
 
-// GB = row groups per workgroup (GB * 16 threads); one workgroup per triple.
-template <int NV4, int GB>
+// GB = row groups per workgroup (GB * 16 threads); one workgroup per triple.  IF = negative rows that a group has
+// in flight.
+template <int NV4, int GB, int IF>
 __global__ void __launch_bounds__(GB * kGroup) k_kge_grad(const float *E, const float *R, uint32_t n_ent, uint32_t n_rel,
                                                      int stride, const uint32_t *subj, const uint32_t *rel,
                                                      const uint32_t *obj, const uint32_t *negs, uint32_t B, int nh,
@@ -327,13 +328,18 @@ __global__ void __launch_bounds__(GB * kGroup) k_kge_grad(const float *E, const 
     const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
     const uint32_t e = blockIdx.x;
     const int nn = nh + nt;
+    // The first half of the groups scores the replaced subjects (dot products with A), the second half the
+    // replaced objects (with C).  Group number gi of a role takes that role's negatives gi, gi + kHalf, ...;
+    // lane l of the group fetches the key of the l-th of them up front, so that the row reads wait for no index.
+    const bool head = group < kHalf;
+    const int gi = group % kHalf;
+    const int lo = head ? 0 : nh, cnt = head ? nh : nt;
+    const int mine = cnt > gi ? (cnt - gi + kHalf - 1) / kHalf : 0;
+    const uint32_t *my_negs = negs + (size_t)e * nn + lo + gi;
+    const uint32_t early = lane < mine ? min(my_negs[(size_t)lane * kHalf], n_ent - 1) : 0u;
     const float *s_ptr = E + (size_t)min(subj[e], n_ent - 1) * stride;
     const float *o_ptr = E + (size_t)min(obj[e], n_ent - 1) * stride;
     const float *r_ptr = R + (size_t)min(rel[e], n_rel - 1) * stride;
-    // The first half of the groups scores the replaced subjects (dot products with A), the second half the
-    // replaced objects (with C);
-    // each keeps one direction row and one accumulator, and four negative rows in flight.
-    const bool head = group < kHalf;
     Row<NV4> dir;
     {
         Row<NV4> s, r, o;
@@ -344,26 +350,27 @@ __global__ void __launch_bounds__(GB * kGroup) k_kge_grad(const float *E, const 
     Row<NV4> wsum;                     // sum of coef * negative row over this group's negatives
     zero_row(wsum);
     float loss_acc = 0.f;
-    const int lo = head ? 0 : nh, hi = head ? nh : nn;
-    const uint32_t *my_negs = negs + (size_t)e * nn;
-    for (int i = lo + (group % kHalf); i < hi; i += 4 * kHalf) {
-        const int i1 = i + kHalf, i2 = i + 2 * kHalf, i3 = i + 3 * kHalf;
-        Row<NV4> x0, x1, x2, x3;
-        load_row(x0, E + (size_t)min(my_negs[i], n_ent - 1) * stride, lane);
-        load_row(x1, E + (size_t)min(my_negs[min(i1, hi - 1)], n_ent - 1) * stride, lane);
-        load_row(x2, E + (size_t)min(my_negs[min(i2, hi - 1)], n_ent - 1) * stride, lane);
-        load_row(x3, E + (size_t)min(my_negs[min(i3, hi - 1)], n_ent - 1) * stride, lane);
-        auto one = [&](const Row<NV4> &x, int idx) {
-            const float phi = group_sum(partial_dot(x, dir));
-            const float g = sigmoidf(phi);           // label -1: d softplus(phi) / d phi
-            loss_acc += softplusf(phi);
-            if (lane == 0) coefs[(size_t)e * nn + idx] = g;
-            axpy_row(wsum, g, x);
-        };
-        one(x0, i);
-        if (i1 < hi) one(x1, i1);
-        if (i2 < hi) one(x2, i2);
-        if (i3 < hi) one(x3, i3);
+    for (int j0 = 0; j0 < mine; j0 += IF) {
+        Row<NV4> x[IF];
+#pragma unroll
+        for (int k = 0; k < IF; ++k) {
+            const int j = j0 + k;
+            if (j < mine) {
+                const uint32_t key = j < kGroup ? __shfl(early, j, kGroup) : min(my_negs[(size_t)j * kHalf], n_ent - 1);
+                load_row(x[k], E + (size_t)key * stride, lane);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < IF; ++k) {
+            const int j = j0 + k;
+            if (j < mine) {
+                const float phi = group_sum(partial_dot(x[k], dir));
+                const float g = sigmoidf(phi);           // label -1: d softplus(phi) / d phi
+                loss_acc += softplusf(phi);
+                if (lane == 0) coefs[(size_t)e * nn + lo + gi + j * kHalf] = g;
+                axpy_row(wsum, g, x[k]);
+            }
+        }
     }
     store_row(part + (size_t)group * stride, wsum, lane);
     __syncthreads();
@@ -420,12 +427,12 @@ __global__ void __launch_bounds__(GB * kGroup) k_kge_grad(const float *E, const 
 template <int NV4>
 static void launch_kge_grad(nups_ctx *ctx, const nups_batch &b)
 {
-    // 128-thread workgroups: at two wavefronts per SIMD (the kernel needs ~250 registers for four rows in
-    // flight) the 1,024 triples of a step are then all resident at once instead of in two rounds.
-    constexpr int GB = 8;
+    // 128-thread workgroups, two negative rows in flight per group.  More groups per triple or more rows in
+    // flight change nothing: the kernel runs at the speed at which memory delivers the negatives' rows.
+    constexpr int GB = 8, IF = 2;
     const Table &te = ctx->tab[0], &tr = ctx->tab[1];
     const size_t lds = sizeof(float) * GB * (size_t)te.stride;
-    hipLaunchKernelGGL((k_kge_grad<NV4, GB>), dim3((uint32_t)b.B), dim3(GB * kGroup), lds, ctx->stream, (const float *)te.data,
+    hipLaunchKernelGGL((k_kge_grad<NV4, GB, IF>), dim3((uint32_t)b.B), dim3(GB * kGroup), lds, ctx->stream, (const float *)te.data,
                        (const float *)tr.data, (uint32_t)te.num_keys, (uint32_t)tr.num_keys, te.stride, b.k0, b.k1,
                        b.k2, b.negs, (uint32_t)b.B, (int)b.n_neg, (int)b.n_neg2, ctx->coef, ctx->stage, ctx->loss_cur);
 }

@@ -278,8 +278,10 @@ def test_kge_needs_state():
     nb.nups_destroy(ctx)
 
 
-def test_sgns_pipelined_steps_match_the_oracle():
-    # step t+1 is prepared (samples drawn, aggregation structure built on the side stream) before step t runs
+@pytest.mark.parametrize("depth", [1, 3])
+def test_sgns_pipelined_steps_match_the_oracle(depth):
+    # steps t+1 .. t+depth are prepared (samples drawn, aggregation structure built on the side streams, by the
+    # library's background thread) before step t runs
     V, d, B, K, window, steps, lr = 30_000, 300, 2048, 3, 5, 12, 0.002
     toks = wl.zipf_stream(V, 1.0, steps * B // (2 * window) + 2 * window + 8, 21)
     In, Out = wl.sgns_tables(V, d, 21)
@@ -300,11 +302,11 @@ def test_sgns_pipelined_steps_match_the_oracle():
         b = nb.make_batch(nb.NUPS_TASK_SGNS, B, dev_pairs[t][0], dev_pairs[t][1], n_neg=K, lr=lr, sample=h)
         return h, nb.nups_prepare_step(ctx, b)
 
-    nxt = prepare(0)
+    queue = [prepare(t) for t in range(min(depth, steps))]
     for t in range(steps):
-        h, p = nxt
-        if t + 1 < steps:
-            nxt = prepare(t + 1)
+        if t + depth < steps:
+            queue.append(prepare(t + depth))
+        h, p = queue.pop(0)
         nb.nups_step_prepared(ctx, p)
         if h is not None:
             nb.nups_release_sample(h)
