@@ -88,6 +88,40 @@ __device__ __forceinline__ void store_row(float *base, const Row<NV4> &r, int la
     for (int q = 0; q < NV4; ++q) p[q * kGroup] = r.v[q];
 }
 
+// A row that another workgroup of the same launch reads (or has written): every word moves as a device-scope
+// atomic access, which is performed where all compute dies see it, so no cache write-back or invalidation is
+// needed around it.  all_stores_performed() returns once this wavefront's earlier stores have been acknowledged;
+// an arrival counter incremented after it orders them before the reader's loads.
+template <int NV4>
+__device__ __forceinline__ void store_row_device_scope(float *base, const Row<NV4> &r, int lane)
+{
+    float *p = base + 4 * lane;
+#pragma unroll
+    for (int q = 0; q < NV4; ++q) {
+        float *w = p + q * 4 * kGroup;
+        __hip_atomic_store(w + 0, r.v[q].x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(w + 1, r.v[q].y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(w + 2, r.v[q].z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(w + 3, r.v[q].w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+template <int NV4>
+__device__ __forceinline__ void load_row_device_scope(Row<NV4> &r, const float *base, int lane)
+{
+    const float *p = base + 4 * lane;
+#pragma unroll
+    for (int q = 0; q < NV4; ++q) {
+        const float *w = p + q * 4 * kGroup;
+        r.v[q].x = __hip_atomic_load(w + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        r.v[q].y = __hip_atomic_load(w + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        r.v[q].z = __hip_atomic_load(w + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        r.v[q].w = __hip_atomic_load(w + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+__device__ __forceinline__ void all_stores_performed() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 template <int NV4>
 __device__ __forceinline__ void zero_row(Row<NV4> &r)
 {

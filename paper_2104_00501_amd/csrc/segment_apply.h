@@ -257,8 +257,8 @@ __device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &
             axpy_row(acc, 1.0f, r);
         }
         if (nch > 1) {
-            store_row(a.partial + (size_t)id * a.stride, acc, lane);
-            __threadfence();          // the partial row is visible before the arrival is counted
+            store_row_device_scope(a.partial + (size_t)id * a.stride, acc, lane);
+            all_stores_performed();   // the partial row is in place before the arrival is counted (same wavefront)
         }
     }
     bool update = true;
@@ -268,17 +268,16 @@ __device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &
         __syncthreads();
         update = *last_arrival != 0;
         if (update) {
-            __threadfence();          // the other chunks' partial rows are visible after their arrivals
-            if (group == 0) {        // chunk order, four partial rows in flight
+            if (group == 0) {        // chunk order, four partial rows in flight; every chunk has arrived
                 zero_row(acc);
                 const float *prow = a.partial + (size_t)base * a.stride;
                 uint32_t ch = 0;
                 for (; ch + 3 < nch; ch += 4) {
                     Row<NV4> r0, r1, r2, r3;
-                    load_row(r0, prow + (size_t)ch * a.stride, lane);
-                    load_row(r1, prow + (size_t)(ch + 1) * a.stride, lane);
-                    load_row(r2, prow + (size_t)(ch + 2) * a.stride, lane);
-                    load_row(r3, prow + (size_t)(ch + 3) * a.stride, lane);
+                    load_row_device_scope(r0, prow + (size_t)ch * a.stride, lane);
+                    load_row_device_scope(r1, prow + (size_t)(ch + 1) * a.stride, lane);
+                    load_row_device_scope(r2, prow + (size_t)(ch + 2) * a.stride, lane);
+                    load_row_device_scope(r3, prow + (size_t)(ch + 3) * a.stride, lane);
                     axpy_row(acc, 1.0f, r0);
                     axpy_row(acc, 1.0f, r1);
                     axpy_row(acc, 1.0f, r2);
@@ -286,7 +285,7 @@ __device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &
                 }
                 for (; ch < nch; ++ch) {
                     Row<NV4> r;
-                    load_row(r, prow + (size_t)ch * a.stride, lane);
+                    load_row_device_scope(r, prow + (size_t)ch * a.stride, lane);
                     axpy_row(acc, 1.0f, r);
                 }
             }
