@@ -308,7 +308,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="sgns_1m_d300_bounded_u4", choices=sorted(WORKLOADS))
-    ap.add_argument("--depth", type=int, default=2, help="steps prepared ahead of the one that runs")
+    ap.add_argument("--depth", type=int, default=3, help="steps prepared ahead of the one that runs")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: about 15 s worth, 0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:

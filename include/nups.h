@@ -11,13 +11,13 @@
  *  - The library never owns table, state, batch or output memory: the caller
  *    allocates it and keeps it alive while the context uses it.  The library owns
  *    only its workspace and the opaque objects it hands out.
- *  - Everything that reads or writes table values is enqueued on the HIP stream given to
- *    nups_init.  Preparatory work that only handles keys (drawing samples, building the
- *    per-key aggregation structure of a step; the "background" work of Section 4.3) is
- *    enqueued on a second, library-owned stream of default priority and ordered against the
- *    caller's stream with events: it starts after what the caller's stream held when the
- *    prepare call was made, and its consumers on the caller's stream wait for it.  Calls
- *    return without waiting unless they hand a value back to the host (stated per call).
+ *  - All device work is enqueued on the HIP stream given to nups_init; the library creates
+ *    no stream, event or thread.  Preparatory work that only handles keys (drawing samples,
+ *    building the per-key aggregation structure of a step; the "background" work of Section
+ *    4.3) does not get launches of its own when steps are prepared ahead: it rides in spare
+ *    workgroups of the gradient and update launches of the steps that run before (see
+ *    nups_prepare_step).  Calls return without waiting unless they hand a value back to the
+ *    host (stated per call).
  *  - A table is a dense [num_keys, row_stride] fp32 array; the first `dim` floats of
  *    a row are the parameter, the rest is padding that stays zero.  row_stride must be
  *    a multiple of 64 floats (at most 1024); keys are uint32 row numbers.
@@ -93,7 +93,8 @@ nups_status nups_set_state(nups_ctx *ctx, int table, float *state_dev);
  * With a declaration only declared keys can take the hot path; k = 0 switches it off
  * altogether (every key is summed by one row group, nothing extra is launched).  The set
  * changes how updates are aggregated, never the result beyond fp32 summation order.
- * Waits for both streams (the set is uploaded synchronously).
+ * Waits for the stream (the set is uploaded synchronously).  NUPS_ERR_STATE while prepared
+ * steps are outstanding: their structures were begun under the previous set.
  */
 nups_status nups_set_hot_keys(nups_ctx *ctx, int table, const uint32_t *keys_host, int64_t k);
 
@@ -141,8 +142,8 @@ nups_status nups_set_local_keys(nups_dist *dist, const uint32_t *keys_a_dev, con
                                 int64_t n_examples, int32_t per_example, int32_t split, int32_t tile);
 
 /*
- * PrepareSample(dist, N): enqueues the drawing of N sample keys for step `step` and
- * returns at once.  For NUPS_LONGTERM the distribution's cursor advances by N (step
+ * PrepareSample(dist, N): enqueues the drawing of N sample keys for step `step` (one
+ * launch on the stream) and returns at once.  For NUPS_LONGTERM the distribution's cursor advances by N (step
  * is ignored).  The handle must be released with nups_release_sample.
  */
 nups_status nups_prepare_sample(nups_dist *dist, int64_t n, uint64_t step, nups_sample **out);
@@ -156,8 +157,8 @@ nups_status nups_prepare_sample(nups_dist *dist, int64_t n, uint64_t step, nups_
  */
 nups_status nups_pull_sample(nups_sample *handle, int64_t n_j, uint32_t *keys_dev, float *values_dev);
 
-/* Device address of all N keys of the handle (valid until release).  Work enqueued on the caller's
- * stream after this call sees the keys. */
+/* Device address of all N keys of the handle (valid until release).  Work enqueued on the stream
+ * after nups_prepare_sample sees the keys. */
 nups_status nups_sample_keys(nups_sample *handle, const uint32_t **keys_dev, int64_t *n);
 
 /* Gives the handle back; releasing twice is NUPS_ERR_STATE. */
@@ -180,11 +181,11 @@ typedef struct {
     const uint32_t *negs;  /* dev [B * (n_neg + n_neg2)] sampled keys, example-major (NULL if none or if
                               `sample` is given)                                                   */
     nups_sample *sample;   /* alternatively: the handle whose N >= B * (n_neg + n_neg2) keys are the
-                              negatives (no wait is put on the caller's stream; the step orders itself
-                              after the drawing).  NULL if `negs` is given or there are none.       */
+                              negatives.  NULL if `negs` is given or there are none.              */
     nups_dist *dist;       /* alternatively: the step draws its own B * (n_neg + n_neg2) negatives from
                               this distribution as PrepareSample(dist, N) for step `sample_step` would
-                              (same keys), without a handle.  NULL otherwise.                       */
+                              (same keys), without a handle, as part of its preparatory work.  NULL
+                              otherwise.                                                           */
     uint64_t sample_step;  /* step number of that drawing (ignored unless `dist` is given)        */
 } nups_batch;
 
@@ -200,13 +201,21 @@ typedef struct {
 nups_status nups_step(nups_ctx *ctx, const nups_batch *batch, double *loss_sum_host);
 
 /*
- * The same step in two halves, in the manner of PrepareSample / PullSample (Section 4.3):
- * nups_prepare_step enqueues the work that depends only on the batch's keys (the per-key
- * aggregation structure) on the side stream and returns at once; nups_step_prepared runs the
- * gradient and the updates on the caller's stream once that is ready.  Preparing step t+1 before
- * running step t lets the two overlap.  The key arrays of the batch (and the sampled keys it
- * points to) must stay valid until the step has run.  A prepared step is consumed by running it;
- * running it twice is NUPS_ERR_STATE.  nups_step(batch) is prepare followed by run.
+ * The same step in two halves, in the manner of PrepareSample / PullSample (Section 4.3).
+ * nups_prepare_step hands the batch to the library and returns at once, without enqueuing
+ * anything: the work that depends only on the batch's keys (drawing the step's own negatives,
+ * the per-key aggregation structure) is a chain of six short phases (seven for more than
+ * 131,072 accesses to a table), and every gradient or update launch of a step that runs
+ * afterwards carries one phase of each of the three oldest prepared steps in spare workgroups.
+ * nups_step_prepared first enqueues, as launches of their own, whatever phases of this step
+ * have not been carried yet, then the step's two launches.  So with steps prepared three
+ * ahead (prepare t+3, run t) a step costs two launches and its preparatory work hides inside
+ * earlier steps; prepared less far ahead, part of it runs on its own; nups_step(batch) is
+ * prepare followed by run and runs all of it on its own.  The results are the same in every
+ * case.  The key arrays of the batch (and the sampled keys or batch-local key arrays it
+ * points to) must stay valid and unchanged until the step has run; arrays written by work
+ * enqueued on the stream before nups_prepare_step are seen complete.  A prepared step is
+ * consumed by running it; running it twice is NUPS_ERR_STATE.
  */
 nups_status nups_prepare_step(nups_ctx *ctx, const nups_batch *batch, nups_prepared **out);
 nups_status nups_step_prepared(nups_ctx *ctx, nups_prepared *step, double *loss_sum_host);

@@ -1,8 +1,9 @@
-// Host side of the C ABI declared in include/nups.h: argument checks, workspace, object lifetimes,
-// and the two-stream schedule: sampling and plan construction ("preparatory work", Section 4.3) run on a
-// library-owned side stream, everything that reads or writes table values runs on the caller's stream.
-// The side stream's work for prepared steps is issued by a background thread of the library, so that the
-// calling thread spends its time on its own stream only.
+// Host side of the C ABI declared in include/nups.h: argument checks, workspace, object lifetimes, and the
+// schedule of preparatory work (Section 4.3: sampling and what else a step needs before it can run).  All device
+// work goes to the caller's stream.  The preparatory work of a prepared step is a list of phases; each launch of
+// a gradient or update kernel carries one phase of each of the next few prepared steps in spare workgroups, so a
+// step that was prepared three steps ahead finds its samples drawn and its structure built when it runs, and
+// nothing but the steps' own two launches is ever enqueued.
 #include <algorithm>
 #include <cstring>
 
@@ -39,69 +40,6 @@ nups_status ensure_f32(float **buf, size_t *cap, size_t need, hipStream_t stream
     return NUPS_OK;
 }
 
-// ---- background thread --------------------------------------------------------------------------------------
-
-static void worker_main(nups_ctx *ctx)
-{
-    (void)hipSetDevice(ctx->device);
-    Worker &w = *ctx->worker;
-    std::unique_lock<std::mutex> lock(w.mutex);
-    for (;;) {
-        w.has_job.wait(lock, [&] { return w.stop || !w.jobs.empty(); });
-        if (w.jobs.empty()) return;   // asked to stop, nothing left to issue
-        std::function<void()> job = std::move(w.jobs.front());
-        w.jobs.pop_front();
-        w.busy = true;
-        lock.unlock();
-        job();
-        lock.lock();
-        w.busy = false;
-        w.job_done.notify_all();
-    }
-}
-
-static void worker_submit(nups_ctx *ctx, std::function<void()> job)
-{
-    Worker &w = *ctx->worker;
-    {
-        std::lock_guard<std::mutex> lock(w.mutex);
-        w.jobs.push_back(std::move(job));
-    }
-    w.has_job.notify_one();
-}
-
-// Returns once the background thread has issued everything handed to it.
-void worker_drain(nups_ctx *ctx)
-{
-    if (!ctx->worker) return;
-    Worker &w = *ctx->worker;
-    std::unique_lock<std::mutex> lock(w.mutex);
-    w.job_done.wait(lock, [&] { return w.jobs.empty() && !w.busy; });
-}
-
-static void worker_stop(nups_ctx *ctx)
-{
-    if (!ctx->worker) return;
-    Worker &w = *ctx->worker;
-    {
-        std::lock_guard<std::mutex> lock(w.mutex);
-        w.stop = true;
-    }
-    w.has_job.notify_one();
-    if (w.thread.joinable()) w.thread.join();
-    delete ctx->worker;
-    ctx->worker = nullptr;
-}
-
-// Waits until the side stream has finished everything prepared so far.
-nups_status sync_side(nups_ctx *ctx)
-{
-    worker_drain(ctx);
-    NUPS_HIP(hipStreamSynchronize(ctx->side));
-    NUPS_HIP(hipStreamSynchronize(ctx->side1));
-    return NUPS_OK;
-}
-
 PhaseScope::PhaseScope(nups_ctx *c, int p, hipStream_t s) : ctx(c), phase(p), stream(s)
 {
     if (!ctx->profiling) return;
@@ -126,7 +64,6 @@ PhaseScope::~PhaseScope()
 static void free_sample(nups_sample *h)
 {
     if (h->keys_dev) (void)hipFree(h->keys_dev);
-    if (h->ready) (void)hipEventDestroy(h->ready);
     delete h;
 }
 
@@ -143,18 +80,14 @@ static void free_prepared(nups_prepared *p)
 {
     free_plan_arrays(p->plan[0]);
     free_plan_arrays(p->plan[1]);
-    if (p->ready) (void)hipEventDestroy(p->ready);
-    if (p->fork) (void)hipEventDestroy(p->fork);
     if (p->loss_dev) (void)hipFree(p->loss_dev);
     if (p->negs_buf) (void)hipFree(p->negs_buf);
     delete p;
 }
 
-// Waits for both streams and turns a raised device flag into an error.
+// Waits for the stream and turns a raised device flag into an error.
 static nups_status sync_and_check(nups_ctx *ctx)
 {
-    nups_status side = sync_side(ctx);
-    if (side != NUPS_OK) return side;
     NUPS_HIP(hipMemcpyAsync(ctx->flag_pinned, ctx->error_flag, sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
     NUPS_HIP(hipStreamSynchronize(ctx->stream));
     if (*ctx->flag_pinned != 0) {
@@ -167,24 +100,6 @@ static nups_status sync_and_check(nups_ctx *ctx)
 
 static bool valid_table(const nups_ctx *ctx, int t) { return ctx && t >= 0 && t < ctx->n_tables; }
 
-// Work enqueued on the side stream from here on starts after everything already enqueued on the caller's stream
-// (key arrays written there are complete; buffers consumed there are free again).  For work the calling thread
-// enqueues itself: the background thread must be idle.
-static nups_status side_after_main(nups_ctx *ctx)
-{
-    worker_drain(ctx);
-    NUPS_HIP(hipEventRecord(ctx->fork, ctx->stream));
-    NUPS_HIP(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
-    return NUPS_OK;
-}
-
-static nups_status new_event(hipEvent_t *ev)
-{
-    if (*ev) return NUPS_OK;
-    NUPS_HIP(hipEventCreateWithFlags(ev, hipEventDisableTiming));
-    return NUPS_OK;
-}
-
 static nups_status get_prepared(nups_ctx *ctx, nups_prepared **out)
 {
     nups_prepared *p = nullptr;
@@ -194,11 +109,10 @@ static nups_status get_prepared(nups_ctx *ctx, nups_prepared **out)
         p->ctx = ctx;
         ctx->prepared_all.push_back(p);
     }
-    nups_status st = new_event(&p->ready);
-    if (st == NUPS_OK) st = new_event(&p->fork);
-    p->submitted.store(0, std::memory_order_relaxed);
-    p->error.clear();
-    if (st == NUPS_OK && !p->loss_dev && !hip_ok(hipMalloc((void **)&p->loss_dev, sizeof(double) * kLossSlots * kLossStride), "loss accumulator"))
+    nups_status st = NUPS_OK;
+    p->phases.clear();
+    p->next_phase = 0;
+    if (!p->loss_dev && !hip_ok(hipMalloc((void **)&p->loss_dev, sizeof(double) * kLossSlots * kLossStride), "loss accumulator"))
         st = NUPS_ERR_DEVICE;
     if (st != NUPS_OK) { ctx->prepared_free.push_back(p); return st; }
     *out = p;
@@ -206,7 +120,7 @@ static nups_status get_prepared(nups_ctx *ctx, nups_prepared **out)
 }
 
 // A consumed step is recycled once no table's structure query refers to it any more.  Its arrays may still be
-// read by kernels in flight on the caller's stream; the next build waits for those (side_after_main).
+// read by kernels in flight; whatever reuses them is enqueued behind those on the same stream.
 static void retire_prepared(nups_ctx *ctx, nups_prepared *p)
 {
     p->live = false;
@@ -309,10 +223,7 @@ nups_status nups_init(nups_ctx **out, int n_tables, float *const *tables_dev, co
         ctx->tab[t].dim = dim[t];
         ctx->tab[t].stride = row_stride[t];
     }
-    hipError_t e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);   // default priority
-    if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->side1, hipStreamNonBlocking);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipMalloc((void **)&ctx->error_flag, sizeof(uint32_t));
+    hipError_t e = hipMalloc((void **)&ctx->error_flag, sizeof(uint32_t));
     if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->loss_pinned, sizeof(double) * kLossSlots * kLossStride, hipHostMallocDefault);
     if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->flag_pinned, sizeof(uint32_t), hipHostMallocDefault);
     if (e == hipSuccess) e = hipMemsetAsync(ctx->error_flag, 0, sizeof(uint32_t), ctx->stream);
@@ -322,8 +233,6 @@ nups_status nups_init(nups_ctx **out, int n_tables, float *const *tables_dev, co
         nups_destroy(ctx);
         return NUPS_ERR_DEVICE;
     }
-    ctx->worker = new Worker();
-    ctx->worker->thread = std::thread(worker_main, ctx);
     *out = ctx;
     return NUPS_OK;
 }
@@ -331,16 +240,11 @@ nups_status nups_init(nups_ctx **out, int n_tables, float *const *tables_dev, co
 nups_status nups_destroy(nups_ctx *ctx)
 {
     if (!ctx) return fail(NUPS_ERR_ARG, "nups_destroy: null context");
-    worker_stop(ctx);
-    if (ctx->side) (void)hipStreamSynchronize(ctx->side);
-    if (ctx->side1) (void)hipStreamSynchronize(ctx->side1);
     (void)hipStreamSynchronize(ctx->stream);
     for (nups_dist *d : ctx->dists) free_dist(d);
     for (nups_prepared *p : ctx->prepared_all) free_prepared(p);
-    for (int t = 0; t < kMaxTables; ++t) {
-        for (int l = 0; l < kLanes; ++l) free_plan_scratch(ctx->tab[t].scratch[l]);
+    for (int t = 0; t < kMaxTables; ++t)
         if (ctx->tab[t].hot_bits_dev) (void)hipFree(ctx->tab[t].hot_bits_dev);
-    }
     if (ctx->coef) (void)hipFree(ctx->coef);
     if (ctx->stage) (void)hipFree(ctx->stage);
     if (ctx->partial) (void)hipFree(ctx->partial);
@@ -351,9 +255,6 @@ nups_status nups_destroy(nups_ctx *ctx)
         for (auto &pr : ph.pending) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
         for (hipEvent_t ev : ph.free_events) (void)hipEventDestroy(ev);
     }
-    if (ctx->fork) (void)hipEventDestroy(ctx->fork);
-    if (ctx->side) (void)hipStreamDestroy(ctx->side);
-    if (ctx->side1) (void)hipStreamDestroy(ctx->side1);
     delete ctx;
     return NUPS_OK;
 }
@@ -381,8 +282,8 @@ nups_status nups_set_hot_keys(nups_ctx *ctx, int table, const uint32_t *keys_hos
     const size_t words = (size_t)((t.num_keys + 31) / 32);
     std::vector<uint32_t> bits(words, 0u);
     for (uint32_t key : keys) bits[key >> 5] |= 1u << (key & 31);
-    nups_status side = sync_side(ctx);
-    if (side != NUPS_OK) return side;
+    for (nups_prepared *q : ctx->prepared_all)
+        if (q->live) return fail(NUPS_ERR_STATE, "nups_set_hot_keys: prepared steps are outstanding");
     NUPS_HIP(hipStreamSynchronize(ctx->stream));
     if (!t.hot_bits_dev) NUPS_HIP(hipMalloc((void **)&t.hot_bits_dev, sizeof(uint32_t) * words));
     NUPS_HIP(hipMemcpy(t.hot_bits_dev, bits.data(), sizeof(uint32_t) * words, hipMemcpyHostToDevice));
@@ -408,17 +309,14 @@ nups_status nups_push(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_
     if (st != NUPS_OK) return st;
     p->n_plans = 1;
     p->plan[0].table = table;
-    p->lane = 0;
-    if ((st = ensure_plan_capacity(ctx, t, p->plan[0], (size_t)n, 0)) != NUPS_OK) return st;
+    if ((st = ensure_plan_capacity(ctx, t, p->plan[0], (size_t)n)) != NUPS_OK) return st;
     p->plan[0].a.src = KeySource{{keys_dev, nullptr, nullptr}, {(uint32_t)n, 0, 0}};
-    p->plan[0].a.n = (uint32_t)n;
+    p->plan[0].a.n = p->plan[0].a.mark_n = (uint32_t)n;
     p->plan[0].a.zero_loss = nullptr;
     if ((st = ensure_partial(ctx, max_chunks(p->plan[0].cap_n) * (size_t)t.stride)) != NUPS_OK) return st;
-    if ((st = side_after_main(ctx)) != NUPS_OK) return st;
-    if ((st = build_plans(ctx, ctx->side, p->plan, 1)) != NUPS_OK) return st;
-    NUPS_HIP(hipEventRecord(p->ready, ctx->side));
-    NUPS_HIP(hipStreamWaitEvent(ctx->stream, p->ready, 0));
-    if (n > 0) st = launch_push_apply(ctx, t, p->plan[0], updates_dev);
+    build_phases(*p, SampleArgs{}, -1);
+    st = flush_side_work(ctx, p);
+    if (st == NUPS_OK && n > 0) st = launch_push_apply(ctx, t, p->plan[0], updates_dev);
     retire_prepared(ctx, p);
     return st;
 }
@@ -501,27 +399,30 @@ nups_status nups_prepare_sample(nups_dist *dist, int64_t n, uint64_t step, nups_
     nups_sample *h = nullptr;
     if (!dist->recycled.empty()) { h = dist->recycled.back(); dist->recycled.pop_back(); }
     else { h = new nups_sample(); h->dist = dist; }
-    nups_status st = new_event(&h->ready);
-    if (st == NUPS_OK && (h->cap < (size_t)n || !h->keys_dev)) {
-        worker_drain(ctx);
-        hipError_t e = hipStreamSynchronize(ctx->side);
-        if (e == hipSuccess) e = hipStreamSynchronize(ctx->side1);
-        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    nups_status st = NUPS_OK;
+    if (h->cap < (size_t)n || !h->keys_dev) {
+        hipError_t e = hipStreamSynchronize(ctx->stream);
         if (e == hipSuccess && h->keys_dev) e = hipFree(h->keys_dev);
         h->keys_dev = nullptr;
         h->cap = (size_t)n + (size_t)n / 4 + 1024;
         if (e == hipSuccess) e = hipMalloc((void **)&h->keys_dev, sizeof(uint32_t) * h->cap);
         if (e != hipSuccess) { hip_ok(e, "nups_prepare_sample: key buffer"); h->cap = 0; st = NUPS_ERR_DEVICE; }
     }
-    if (st == NUPS_OK) st = side_after_main(ctx);
     if (st != NUPS_OK) { dist->recycled.push_back(h); return st; }
     h->n = n;
     h->pulled = 0;
     h->live = true;
-    st = launch_sample(ctx, ctx->side, sample_spec(dist), h->keys_dev, h->n, step);
+    if (n > 0) {   // the drawing alone, enqueued now: PullSample and steps that use the handle follow it on the stream
+        SideItem it{};
+        it.phase = kSideDraw;
+        it.n_plans = 0;
+        it.blocks_per_plan = 1;
+        it.draw = sample_args(dist, h->keys_dev, n, step);
+        it.blocks = it.draw.blocks;
+        PhaseScope scope(ctx, NUPS_PHASE_SAMPLE, ctx->stream);
+        st = launch_side(ctx, it);
+    }
     if (dist->scheme == NUPS_LONGTERM) dist->cursor += (uint64_t)n;
-    if (st == NUPS_OK && hipEventRecord(h->ready, ctx->side) != hipSuccess)
-        st = fail(NUPS_ERR_DEVICE, "nups_prepare_sample: event record failed");
     if (st != NUPS_OK) { h->live = false; dist->recycled.push_back(h); return st; }
     dist->live.push_back(h);
     *out = h;
@@ -536,7 +437,6 @@ nups_status nups_pull_sample(nups_sample *h, int64_t n_j, uint32_t *keys_dev, fl
     if (h->pulled + n_j > h->n) return fail(NUPS_ERR_OVERPULL, "nups_pull_sample: more samples requested than prepared");
     if (n_j == 0) return NUPS_OK;
     nups_ctx *ctx = h->dist->ctx;
-    NUPS_HIP(hipStreamWaitEvent(ctx->stream, h->ready, 0));
     const uint32_t *src = h->keys_dev + h->pulled;
     if (keys_dev)
         NUPS_HIP(hipMemcpyAsync(keys_dev, src, sizeof(uint32_t) * (size_t)n_j, hipMemcpyDeviceToDevice, ctx->stream));
@@ -552,7 +452,6 @@ nups_status nups_sample_keys(nups_sample *h, const uint32_t **keys_dev, int64_t 
 {
     if (!h || !keys_dev) return fail(NUPS_ERR_ARG, "nups_sample_keys: null argument");
     if (!h->live) return fail(NUPS_ERR_STATE, "nups_sample_keys: handle was released");
-    NUPS_HIP(hipStreamWaitEvent(h->dist->ctx->stream, h->ready, 0));   // later work on the caller's stream sees the keys
     *keys_dev = h->keys_dev;
     if (n) *n = h->n;
     return NUPS_OK;
@@ -569,25 +468,7 @@ nups_status nups_release_sample(nups_sample *h)
     return NUPS_OK;
 }
 
-// The side-stream part of a prepared step: after what the caller's stream held when the step was prepared, draw
-// the step's own negatives if it has any, build the plans, and signal readiness.
-static void issue_side_work(nups_ctx *ctx, nups_prepared *p, const SampleSpec &spec, int64_t n_draw, uint64_t step)
-{
-    nups_status st = NUPS_OK;
-    hipStream_t side = side_stream(ctx, p->lane);
-    if (hipStreamWaitEvent(side, p->fork, 0) != hipSuccess) st = fail(NUPS_ERR_DEVICE, "prepared step: stream wait failed");
-    if (st == NUPS_OK && p->after && hipStreamWaitEvent(side, p->after, 0) != hipSuccess)
-        st = fail(NUPS_ERR_DEVICE, "prepared step: stream wait failed");
-    if (st == NUPS_OK && n_draw > 0) st = launch_sample(ctx, side, spec, p->negs_buf, n_draw, step);
-    if (st == NUPS_OK) st = build_plans(ctx, side, p->plan, p->n_plans);
-    if (st == NUPS_OK && hipEventRecord(p->ready, side) != hipSuccess)
-        st = fail(NUPS_ERR_DEVICE, "prepared step: event record failed");
-    if (st != NUPS_OK) p->error = nups_last_error();
-    p->submitted.store(st == NUPS_OK ? 1 : (int)st, std::memory_order_release);
-}
-
-// background: the side-stream work is handed to the library's thread; otherwise the calling thread issues it.
-static nups_status prepare_step(nups_ctx *ctx, const nups_batch *b, nups_prepared **out, bool background)
+nups_status nups_prepare_step(nups_ctx *ctx, const nups_batch *b, nups_prepared **out)
 {
     if (!out) return fail(NUPS_ERR_ARG, "nups_prepare_step: out is null");
     *out = nullptr;
@@ -596,19 +477,13 @@ static nups_status prepare_step(nups_ctx *ctx, const nups_batch *b, nups_prepare
     nups_prepared *p = nullptr;
     if ((st = get_prepared(ctx, &p)) != NUPS_OK) return st;
     p->batch = *b;
-    p->after = nullptr;
-    p->lane = background ? (ctx->next_lane ^= 1) : 0;   // consecutive prepared steps build on different side streams
-    if (b->sample) {   // drawn on side stream 0: the build waits for the handle's event
+    if (b->sample) {   // drawn when the handle was prepared, i.e. earlier on the stream
         p->batch.negs = b->sample->keys_dev;
         p->batch.sample = nullptr;
-        p->after = b->sample->ready;
     }
     const int64_t n_draw = b->dist ? b->B * ((int64_t)b->n_neg + b->n_neg2) : 0;
     if (n_draw > 0 && p->negs_cap < (size_t)n_draw) {   // the step draws its own negatives into its own buffer
-        worker_drain(ctx);
-        hipError_t e = hipStreamSynchronize(ctx->side);
-        if (e == hipSuccess) e = hipStreamSynchronize(ctx->side1);
-        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        hipError_t e = hipStreamSynchronize(ctx->stream);
         if (e == hipSuccess && p->negs_buf) e = hipFree(p->negs_buf);
         p->negs_buf = nullptr;
         p->negs_cap = (size_t)n_draw + (size_t)n_draw / 4 + 1024;
@@ -620,41 +495,35 @@ static nups_status prepare_step(nups_ctx *ctx, const nups_batch *b, nups_prepare
             return NUPS_ERR_DEVICE;
         }
     }
-    SampleSpec spec{};
+    SampleArgs draw{};
+    int mark_plan = -1;
     if (n_draw > 0) {
-        spec = sample_spec(b->dist);
+        draw = sample_args(b->dist, p->negs_buf, n_draw, b->sample_step);
         if (b->dist->scheme == NUPS_LONGTERM) b->dist->cursor += (uint64_t)n_draw;
         p->batch.negs = p->negs_buf;
         p->batch.dist = nullptr;
     }
     switch (b->task) {   // capacities and plan arguments
-    case NUPS_TASK_SGNS: st = plan_step_sgns(ctx, *p); break;
+    case NUPS_TASK_SGNS: st = plan_step_sgns(ctx, *p); mark_plan = 1; break;
     case NUPS_TASK_MF: st = plan_step_mf(ctx, *p); break;
-    default: st = plan_step_kge(ctx, *p); break;
+    default: st = plan_step_kge(ctx, *p); mark_plan = 0; break;
     }
-    if (st == NUPS_OK && hipEventRecord(p->fork, ctx->stream) != hipSuccess)
-        st = fail(NUPS_ERR_DEVICE, "nups_prepare_step: event record failed");
     if (st != NUPS_OK) { ctx->prepared_free.push_back(p); return st; }
-    const uint64_t step = b->sample_step;
-    if (background && !ctx->profiling) {
-        worker_submit(ctx, [ctx, p, spec, n_draw, step] { issue_side_work(ctx, p, spec, n_draw, step); });
-    } else {
-        worker_drain(ctx);
-        issue_side_work(ctx, p, spec, n_draw, step);
-        if (p->submitted.load(std::memory_order_acquire) != 1) {
-            st = fail((nups_status)p->submitted.load(), p->error);
-            ctx->prepared_free.push_back(p);
-            return st;
-        }
+    if (n_draw > 0) {
+        // the drawn keys are marked as they are drawn (if they index the table that the plan is for); the plan's own
+        // first phase marks the keys before them
+        if (b->dist->table == p->plan[mark_plan].table) p->plan[mark_plan].a.mark_n -= (uint32_t)n_draw;
+        else mark_plan = -1;
     }
+    build_phases(*p, draw, mark_plan);
     p->live = true;
+    if (ctx->profiling) {   // every phase as a launch of its own, timed
+        if ((st = flush_side_work(ctx, p)) != NUPS_OK) { p->live = false; ctx->prepared_free.push_back(p); return st; }
+    } else {
+        ctx->pending.push_back(p);
+    }
     *out = p;
     return NUPS_OK;
-}
-
-nups_status nups_prepare_step(nups_ctx *ctx, const nups_batch *b, nups_prepared **out)
-{
-    return prepare_step(ctx, b, out, true);
 }
 
 nups_status nups_step_prepared(nups_ctx *ctx, nups_prepared *p, double *loss_sum_host)
@@ -662,22 +531,13 @@ nups_status nups_step_prepared(nups_ctx *ctx, nups_prepared *p, double *loss_sum
     if (!ctx || !p) return fail(NUPS_ERR_ARG, "nups_step_prepared: null argument");
     if (p->ctx != ctx) return fail(NUPS_ERR_ARG, "nups_step_prepared: the step was prepared on another context");
     if (!p->live) return fail(NUPS_ERR_STATE, "nups_step_prepared: the prepared step was already run");
-    if (p->submitted.load(std::memory_order_acquire) == 0) {   // the background thread has not got to it yet
-        Worker &w = *ctx->worker;
-        std::unique_lock<std::mutex> lock(w.mutex);
-        w.job_done.wait(lock, [&] { return p->submitted.load(std::memory_order_acquire) != 0; });
-    }
-    if (p->submitted.load(std::memory_order_acquire) != 1) {
-        const nups_status failed = fail((nups_status)p->submitted.load(), p->error);
-        retire_prepared(ctx, p);
-        return failed;
-    }
-    NUPS_HIP(hipStreamWaitEvent(ctx->stream, p->ready, 0));
-    nups_status st;
-    switch (p->batch.task) {
-    case NUPS_TASK_SGNS: st = run_step_sgns(ctx, *p); break;
-    case NUPS_TASK_MF: st = run_step_mf(ctx, *p); break;
-    default: st = run_step_kge(ctx, *p); break;
+    nups_status st = flush_side_work(ctx, p);   // whatever earlier launches have not carried
+    if (st == NUPS_OK) {
+        switch (p->batch.task) {
+        case NUPS_TASK_SGNS: st = run_step_sgns(ctx, *p); break;
+        case NUPS_TASK_MF: st = run_step_mf(ctx, *p); break;
+        default: st = run_step_kge(ctx, *p); break;
+        }
     }
     retire_prepared(ctx, p);
     if (st != NUPS_OK) return st;
@@ -696,7 +556,7 @@ nups_status nups_step_prepared(nups_ctx *ctx, nups_prepared *p, double *loss_sum
 nups_status nups_step(nups_ctx *ctx, const nups_batch *b, double *loss_sum_host)
 {
     nups_prepared *p = nullptr;
-    nups_status st = prepare_step(ctx, b, &p, false);
+    nups_status st = nups_prepare_step(ctx, b, &p);
     if (st != NUPS_OK) return st;
     return nups_step_prepared(ctx, p, loss_sum_host);
 }
@@ -707,8 +567,6 @@ nups_status nups_debug_structure(nups_ctx *ctx, int table, uint32_t *uniq_keys_d
     if (!valid_table(ctx, table) || !n_uniq_host) return fail(NUPS_ERR_ARG, "nups_debug_structure: bad arguments");
     const Plan *pl = ctx->tab[table].last_plan;
     if (!pl) return fail(NUPS_ERR_STATE, "nups_debug_structure: no step or push has run on this table");
-    nups_status side = sync_side(ctx);
-    if (side != NUPS_OK) return side;
     uint32_t meta[kMetaWords];
     NUPS_HIP(hipMemcpyAsync(meta, pl->a.meta, sizeof(meta), hipMemcpyDeviceToHost, ctx->stream));
     NUPS_HIP(hipStreamSynchronize(ctx->stream));
@@ -737,8 +595,6 @@ nups_status nups_profile(nups_ctx *ctx, int enable)
 nups_status nups_profile_read(nups_ctx *ctx, int phase, double *ms_total, int64_t *launches)
 {
     if (!ctx || phase < 0 || phase >= NUPS_PHASE_COUNT) return fail(NUPS_ERR_ARG, "nups_profile_read: bad arguments");
-    nups_status side = sync_side(ctx);
-    if (side != NUPS_OK) return side;
     NUPS_HIP(hipStreamSynchronize(ctx->stream));
     Phase &ph = ctx->phase[phase];
     for (auto &pr : ph.pending) {

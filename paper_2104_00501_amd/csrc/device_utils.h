@@ -210,13 +210,17 @@ __device__ __forceinline__ void block_add_loss(float x, double *loss, float *lds
 // Workgroups are handed to the eight accelerator dies (XCDs, each with its own L2) round-robin by
 // workgroup number.  xcd_block() renumbers them so that each die works on one contiguous eighth of the
 // logical workgroups: examples that are neighbours in the batch (same center word, same sample pool)
-// then share an L2 instead of fetching the same rows into several.  The grid must come from xcd_grid().
+// then share an L2 instead of fetching the same rows into several.  The grid must come from xcd_grid(); a
+// launch that carries side work in its first workgroups passes its own workgroup number and count, and pads the
+// side work to a multiple of kNumXcd workgroups.
 constexpr uint32_t kNumXcd = 8;
 
-__device__ __forceinline__ uint32_t xcd_block()
+__device__ __forceinline__ uint32_t xcd_block(uint32_t block, uint32_t blocks)
 {
-    return (blockIdx.x % kNumXcd) * (gridDim.x / kNumXcd) + blockIdx.x / kNumXcd;
+    return (block % kNumXcd) * (blocks / kNumXcd) + block / kNumXcd;
 }
+
+__device__ __forceinline__ uint32_t xcd_block() { return xcd_block(blockIdx.x, gridDim.x); }
 
 static inline uint32_t xcd_grid(uint32_t blocks) { return (blocks + kNumXcd - 1) / kNumXcd * kNumXcd; }
 

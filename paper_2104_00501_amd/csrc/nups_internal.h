@@ -4,13 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include <atomic>
-#include <condition_variable>
 #include <deque>
-#include <functional>
-#include <mutex>
 #include <string>
-#include <thread>
 #include <vector>
 
 #include "../../include/nups.h"
@@ -21,7 +16,7 @@ constexpr int kGroup = 16;            // lanes that cooperate on one row (one DP
 constexpr int kBlock = 256;           // threads per workgroup (4 wavefronts, 16 row groups)
 constexpr int kGroupsPerBlock = kBlock / kGroup;
 constexpr int kMaxTables = 4;
-constexpr int kLanes = 2;              // side streams: the structures of consecutive prepared steps are built concurrently
+constexpr int kMaxSide = 3;            // later steps whose preparatory work one launch can carry (one phase each)
 constexpr int kMaxStride = 1024;
 constexpr int kScanItems = 2;         // items per thread in the tile scans
 constexpr int kScanTile = kBlock * kScanItems;
@@ -34,6 +29,13 @@ constexpr uint32_t kSingleAccess = 0x80000000u;
 constexpr uint32_t kLongSegment = 16; // segments with more accesses are summed by whole workgroups, in chunks
 constexpr uint32_t kChunk = 128;      // accesses of a long segment that one workgroup sums
 constexpr uint32_t kBadIndex = 0xFFFFFFFFu;
+constexpr int kRankItems = 2;                       // accesses per thread in the rank phase of the preparatory work
+constexpr int kRankTile = kBlock * kRankItems;
+constexpr int kHashBits = 10;
+constexpr uint32_t kHashSlots = 1u << kHashBits;    // open-addressing table in LDS, at most half full
+constexpr size_t kRankLdsBytes = 4 * kHashSlots * sizeof(uint32_t);
+constexpr uint32_t kMaxPool = 1024;                 // BOUNDED: largest pool (its order words are kept in LDS)
+constexpr size_t kDrawLdsBytes = kMaxPool * sizeof(uint32_t);
 
 // meta words of a plan (device)
 enum { kMetaNumUniq = 0, kMetaNumChunks = 1, kMetaTotal = 2, kMetaWords = 4 };
@@ -61,18 +63,20 @@ struct KeySource {
 struct PlanArgs {
     KeySource src;
     uint32_t n;            // accesses (sum of src.len)
+    uint32_t mark_n;       // the first mark_n accesses are marked by the structure's own first phase; the rest
+                           // (samples that the step draws itself) are marked as they are drawn
     uint32_t num_keys;     // V
     uint32_t words;        // bitmap words = ceil(V / 32)
     uint32_t bitmap_tiles; // ceil(words / kScanTile)
     uint32_t count_tiles;  // ceil(n / kScanTile)
     uint32_t direct_count;  // 1: the count scan sums the counts below its tile itself
-    // build scratch, owned by the table and shared by all plans of that table (builds run one after another)
+    // build scratch, owned by the plan (the structures of several later steps are under construction at a time)
     uint8_t *bytemap;      // [32 * words] one byte per key, all zero between builds
     uint8_t *wordmap;      // [words]     one byte per bitmap word: some key of the word is marked; zero between builds
     uint32_t *bitmap;      // [words]     one bit per key; only the words with a marked key are written by a build
     uint32_t *word_rank;   // [words]     distinct keys below the word inside its tile (written for the same words)
     uint32_t *tile_sum;    // [max(bitmap_tiles, count_tiles)]
-    uint32_t *tile_prefix; // [bitmap_tiles] distinct keys below each tile (tables with very many tiles only)
+    uint32_t *tile_prefix; // [bitmap_tiles] distinct keys below each tile
     uint32_t *cnt_work;    // [n]         per distinct key: positions handed out so far, zero between builds
     // result, owned by the plan
     uint32_t *uniq;        // [n]         distinct keys, ascending
@@ -92,16 +96,10 @@ struct PlanArgs {
 
 struct Plan {
     PlanArgs a{};
-    size_t cap_n = 0;      // capacity (accesses) of the result arrays
+    size_t cap_n = 0;      // capacity (accesses) of the result arrays and of cnt_work
+    size_t cap_words = 0;  // capacity (bitmap words) of the maps
+    size_t cap_tiles = 0;  // capacity of the tile arrays
     int table = -1;
-};
-
-// Build scratch of one table.
-struct PlanScratch {
-    uint8_t *bytemap = nullptr, *wordmap = nullptr;
-    uint32_t *bitmap = nullptr, *word_rank = nullptr, *tile_sum = nullptr, *tile_prefix = nullptr,
-             *cnt_work = nullptr;
-    size_t cap_words = 0, cap_tiles = 0, cap_n = 0;
 };
 
 struct Table {
@@ -112,33 +110,47 @@ struct Table {
     int32_t stride = 0;
     std::vector<uint32_t> hot_keys;   // hottest first (as declared by the caller)
     uint32_t *hot_bits_dev = nullptr; // [ceil(V/32)] membership bitmap of the declared set; null = none declared
-    PlanScratch scratch[kLanes];      // one per side stream
     Plan *last_plan = nullptr;        // structure of the last step / push on this table (owned by a prepared step)
 };
 
-// Everything a sampling kernel needs, copied when the call is made (the distribution object may change
-// afterwards: cursor, batch-local key arrays).
-struct SampleSpec {
-    nups_scheme scheme;
+// Everything the drawing of one batch of samples needs (device-side view, filled in when the call is made: the
+// distribution object may change afterwards: cursor, batch-local key arrays).
+struct SampleArgs {
+    int32_t scheme;                   // nups_scheme; 0: nothing to draw
     const uint32_t *thresh, *alias;   // null thresh: uniform
-    uint64_t num_keys, seed, cursor;
-    uint32_t dist_id;
-    int32_t U, G, R;
-    int64_t P;
+    uint64_t num_keys, seed, step, cursor, P;
+    uint32_t dist_id, n, U, G, F, R;
+    int32_t half;                     // LONG-TERM: bits per half of the Feistel domain
     const uint32_t *local_a, *local_b;
-    int64_t local_n;
-    int32_t per_example, split, tile;
+    uint32_t local_n, per_example, split, tile;
+    uint32_t *out;                    // [n] sample keys
+    uint32_t blocks;                  // workgroups that the drawing needs
+    uint8_t *bytemap, *wordmap;       // maps of the step's structure to mark the keys in, or null
+    uint32_t mark_keys;               // size of that structure's table
+    uint32_t *error_flag;
 };
 
-// The library's background thread (the "background thread" of Section 4.4): it issues the side stream's work so
-// that the calling thread only pays for what goes on its own stream.
-struct Worker {
-    std::thread thread;
-    std::mutex mutex;
-    std::condition_variable has_job, job_done;
-    std::deque<std::function<void()>> jobs;
-    bool stop = false;
-    bool busy = false;
+// Phases of a step's preparatory work, in order (side_work.h).
+enum SidePhase : int32_t {
+    kSideDraw = 0, kSideTiles, kSidePrefix, kSideRank, kSideCountTiles, kSideCounts, kSideScatter
+};
+
+// One phase of one step: units block0 .. block0 + blocks - 1 of it.
+struct SideItem {
+    int32_t phase;
+    int32_t n_plans;
+    uint32_t block0, blocks;          // units of work, each sized for one workgroup
+    uint32_t wgs;                     // workgroups that share them (unit w, w + wgs, ... to workgroup w); set per launch
+    uint32_t blocks_per_plan;         // units per plan (after the drawing's own, in kSideDraw)
+    PlanArgs plan[2];
+    SampleArgs draw;                  // kSideDraw only
+};
+
+// What a launch carries in its first `blocks` workgroups.
+struct SideWork {
+    int32_t n;
+    uint32_t blocks;                  // sum of the items' wgs, rounded up to a multiple of the die count
+    SideItem item[kMaxSide];
 };
 
 struct Phase {
@@ -150,36 +162,29 @@ struct Phase {
 
 }  // namespace nups
 
-// A step whose aggregation structure is being (or has been) built on the side stream.
+// A step that has been handed to the library: its preparatory work is a list of phases, carried one per launch by
+// the gradient and update kernels of the steps that run before it (or launched on their own when it runs sooner).
 struct nups_prepared {
     nups_ctx *ctx = nullptr;
     nups_batch batch{};
     nups::Plan plan[2];
     int n_plans = 0;
-    hipEvent_t ready = nullptr;    // recorded on the side stream after the build
+    std::vector<nups::SideItem> phases;
+    size_t next_phase = 0;         // phases before this one have been enqueued
     double *loss_dev = nullptr;    // this step's loss accumulator: kLossSlots partial sums, kLossStride doubles apart
     uint32_t *negs_buf = nullptr;  // negatives drawn by the step itself (batch.dist)
     size_t negs_cap = 0;
-    hipEvent_t fork = nullptr;     // recorded on the caller's stream when the step was prepared
-    hipEvent_t after = nullptr;    // borrowed: the sample handle's event that the build also waits for, or null
-    int lane = 0;                  // side stream (and table scratch) that builds this step's structure
     bool live = false;             // prepared, not yet run
     bool retired = false;          // run, still referenced by a table's structure query
-    std::atomic<int> submitted{0}; // 0: the side-stream work is still queued; 1: enqueued; < 0: it failed (status)
-    std::string error;             // message of that failure
 };
 
 struct nups_ctx {
     int n_tables = 0;
     nups::Table tab[nups::kMaxTables];
-    hipStream_t stream = nullptr;   // the caller's stream: everything that touches table values
-    hipStream_t side = nullptr;     // library-owned: sampling and plan construction ("background" work), lane 0
-    hipStream_t side1 = nullptr;    // lane 1
-    int next_lane = 0;
-    hipEvent_t fork = nullptr;      // main -> side ordering for work enqueued by the calling thread itself
+    hipStream_t stream = nullptr;   // the caller's stream: all device work is enqueued here
     int device = 0;
-    nups::Worker *worker = nullptr; // issues the side-stream work of prepared steps
-    // step workspace (main stream only)
+    std::deque<nups_prepared *> pending;   // prepared steps with phases left, oldest first
+    // step workspace
     float *coef = nullptr;      size_t coef_cap = 0;      // per (example, scored row) loss derivative
     float *stage = nullptr;     size_t stage_cap = 0;     // staged gradient rows
     float *partial = nullptr;   size_t partial_cap = 0;   // partial sums of the chunks of long segments
@@ -217,7 +222,6 @@ struct nups_dist {
 struct nups_sample {
     nups_dist *dist = nullptr;
     uint32_t *keys_dev = nullptr;   size_t cap = 0;
-    hipEvent_t ready = nullptr;     // recorded on the side stream after the keys are drawn
     int64_t n = 0;
     int64_t pulled = 0;
     bool live = false;
@@ -235,20 +239,18 @@ struct PhaseScope {
     ~PhaseScope();
 };
 
-// kernels' host-side launchers (defined in the .hip files)
-SampleSpec sample_spec(const nups_dist *d);
-nups_status launch_sample(nups_ctx *ctx, hipStream_t stream, const SampleSpec &d, uint32_t *keys_out, int64_t n_samples,
-                          uint64_t step);
-void worker_drain(nups_ctx *ctx);
-nups_status sync_side(nups_ctx *ctx);
-nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n, int lane);
-nups_status build_plans(nups_ctx *ctx, hipStream_t stream, Plan *plans, int n_plans);
-inline hipStream_t side_stream(const nups_ctx *ctx, int lane) { return lane == 0 ? ctx->side : ctx->side1; }
+// host-side helpers and launchers (defined in the .hip files)
+SampleArgs sample_args(const nups_dist *d, uint32_t *keys_out, int64_t n_samples, uint64_t step);
+nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n);
+void build_phases(nups_prepared &p, const SampleArgs &draw, int mark_plan);
+size_t side_lds_bytes(const SideItem &it);
+SideWork take_side_work(nups_ctx *ctx, size_t *lds_bytes, uint32_t max_wgs_per_phase);
+nups_status flush_side_work(nups_ctx *ctx, nups_prepared *p);
+nups_status launch_side(nups_ctx *ctx, const SideItem &it);
 void free_plan_arrays(Plan &pl);
-void free_plan_scratch(PlanScratch &sc);
 nups_status launch_pull(nups_ctx *ctx, const Table &t, const uint32_t *keys, int64_t n, float *values);
 nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, const float *updates);
-nups_status plan_step_sgns(nups_ctx *ctx, nups_prepared &p);   // capacity + plan arguments (calling thread)
+nups_status plan_step_sgns(nups_ctx *ctx, nups_prepared &p);   // capacity + plan arguments
 nups_status plan_step_mf(nups_ctx *ctx, nups_prepared &p);
 nups_status plan_step_kge(nups_ctx *ctx, nups_prepared &p);
 nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p);

@@ -8,7 +8,7 @@
 
 #include <algorithm>
 
-#include "device_utils.h"
+#include "side_work.h"
 
 namespace nups {
 
@@ -317,18 +317,21 @@ __global__ void __launch_bounds__(kBlock) k_apply(ApplyArgs a, Src src, Opt opt)
 }
 
 // Updates the two tables of a step in one launch (their updates are independent of each other: both read
-// staged rows only).  Item order: chunks of table 0, chunks of table 1, short segments of 0, of 1.
+// staged rows only).  Item order: chunks of table 0, chunks of table 1, short segments of 0, of 1.  The first
+// sw.blocks workgroups do preparatory work of later steps instead.
 template <int NV4, class Src0, class Opt0, class Src1, class Opt1>
 __global__ void __launch_bounds__(kBlock) k_apply2(ApplyArgs a0, Src0 src0, Opt0 opt0, ApplyArgs a1, Src1 src1,
-                                                   Opt1 opt1)
+                                                   Opt1 opt1, SideWork sw)
 {
     extern __shared__ float part[];   // [kGroupsPerBlock - 1][stride]
     __shared__ uint32_t last_arrival;
+    if (side_work_block(sw)) return;
+    const uint32_t first_item = blockIdx.x - sw.blocks, item_step = gridDim.x - sw.blocks;
     const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
     const ApplyShape s0 = apply_shape(a0), s1 = apply_shape(a1);
     const uint32_t e0 = s0.chunk_items, e1 = e0 + s1.chunk_items, e2 = e1 + s0.short_items,
                    e3 = e2 + s1.short_items;
-    for (uint32_t item = blockIdx.x; item < e3; item += gridDim.x) {
+    for (uint32_t item = first_item; item < e3; item += item_step) {
         if (item < e0) apply_chunk_item<NV4>(a0, src0, opt0, item, part, &last_arrival, lane, group);
         else if (item < e1) apply_chunk_item<NV4>(a1, src1, opt1, item - e0, part, &last_arrival, lane, group);
         else if (item < e2) apply_short_item<NV4>(a0, src0, opt0, s0, item - e1, lane, group);
@@ -398,22 +401,23 @@ struct TableUpdate {
 };
 
 template <int NV4, class U0, class U1>
-static void launch_apply2_nv(hipStream_t s, int stride, const U0 &u0, const U1 &u1)
+static void launch_apply2_nv(hipStream_t s, int stride, const U0 &u0, const U1 &u1, const SideWork &sw, size_t side_lds)
 {
     const ApplyArgs a0 = make_apply_args(*u0.plan, u0.partial, u0.table, u0.state, stride);
     const ApplyArgs a1 = make_apply_args(*u1.plan, u1.partial, u1.table, u1.state, stride);
     const uint32_t items = max_apply_items(*u0.plan) + max_apply_items(*u1.plan);
-    const size_t lds = sizeof(float) * (size_t)(kGroupsPerBlock - 1) * stride;
+    const size_t lds = std::max(sizeof(float) * (size_t)(kGroupsPerBlock - 1) * stride, side_lds);
     hipLaunchKernelGGL((k_apply2<NV4, decltype(u0.src), decltype(u0.opt), decltype(u1.src), decltype(u1.opt)>),
-                       dim3(std::min(items, kApplyGrid)), dim3(kBlock), lds, s, a0, u0.src, u0.opt, a1, u1.src, u1.opt);
+                       dim3(sw.blocks + std::max(1u, std::min(items, kApplyGrid))), dim3(kBlock), lds, s, a0, u0.src,
+                       u0.opt, a1, u1.src, u1.opt, sw);
 }
 
-// Both tables of a step in one launch (both strides are equal).
+// Both tables of a step in one launch (both strides are equal), plus the side work `sw`.
 template <class U0, class U1>
-static nups_status launch_apply2(hipStream_t s, int stride, const U0 &u0, const U1 &u1)
+static nups_status launch_apply2(hipStream_t s, int stride, const U0 &u0, const U1 &u1, const SideWork &sw,
+                                 size_t side_lds)
 {
-    if (u0.plan->a.n == 0 && u1.plan->a.n == 0) return NUPS_OK;
-#define NUPS_CALL(N) launch_apply2_nv<N>(s, stride, u0, u1)
+#define NUPS_CALL(N) launch_apply2_nv<N>(s, stride, u0, u1, sw, side_lds)
     NUPS_FOR_EACH_ROW_WIDTH(stride, NUPS_CALL)
 #undef NUPS_CALL
     NUPS_HIP(hipGetLastError());

@@ -1,0 +1,413 @@
+// Preparatory work of a step (Section 4.3: drawing the samples; and the per-key aggregation structure that the
+// update needs) as device functions that run in spare workgroups of other kernels' launches.
+//
+// The work of one step is a chain of phases, each of which needs everything the previous one wrote:
+//   draw    the step's own sample keys (Section 4.4 schemes) + marks every key the step accesses
+//   tiles   packs the marked key groups into bitmap words, ranks the words inside tiles, counts per tile
+//   prefix  distinct keys below each tile
+//   rank    per access: index of its key among the distinct keys, position inside that key's segment
+//   counts  segment offsets (prefix sums of the per-key counts), chunk lists of long segments
+//   scatter accesses grouped by key; the scratch maps return to all-zero
+// A launch of a gradient or update kernel carries, in its first workgroups, one phase each of up to kMaxSide later
+// steps: the phases depend on key arrays and random numbers only, never on table values, so they may run while
+// earlier steps still update the tables, and kernel boundaries on one stream order consecutive phases.
+//
+// Keys are bounded by the table size, so the distinct set is a map over the key space and a key's position among
+// the distinct keys is a prefix population count; no comparison sort is needed.  Marking uses one byte per key,
+// and one byte per group of 32 keys, and plain stores (idempotent, so no atomics and no contention on hot keys);
+// only the groups that hold a marked key are then packed into bitmap words.  Hot keys (Section 3.2: a few keys
+// take a large share of the accesses) would serialise the global atomics that hand out positions inside a
+// segment, so every workgroup first combines its own accesses to a key in an LDS hash table and issues one global
+// atomic per distinct key; segments that are too long for one row group are cut into chunks.
+#pragma once
+
+#include "device_utils.h"
+
+namespace nups {
+
+static_assert(kHashSlots >= 2 * kRankTile, "the LDS hash table must stay at most half full");
+
+// ---- drawing ---------------------------------------------------------------------------------------------------
+
+// One fresh draw from pi: bucket = floor((x0 + 2^32 x1) * V / 2^64); keep it if x2 < thresh[bucket].
+__device__ __forceinline__ uint32_t fresh_key(const SampleArgs &d, uint64_t step, uint64_t draw)
+{
+    const Words w = draw_words(d.seed, kStreamFresh, d.dist_id, step, draw);
+    const uint64_t u = (uint64_t)w.x0 | ((uint64_t)w.x1 << 32);
+    const uint32_t b = (uint32_t)__umul64hi(u, d.num_keys);
+    if (d.thresh == nullptr) return b;
+    return (w.x2 < d.thresh[b]) ? b : d.alias[b];
+}
+
+__device__ __forceinline__ uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x85EBCA6Bu;
+    x ^= x >> 13; x *= 0xC2B2AE35u;
+    x ^= x >> 16;
+    return x;
+}
+
+// Stores sample `pos` and, if the drawing feeds a step directly, marks its key in that step's maps.
+__device__ __forceinline__ void emit_sample(const SampleArgs &d, uint64_t pos, uint32_t key)
+{
+    d.out[pos] = key;
+    if (d.bytemap == nullptr) return;
+    if (key >= d.mark_keys) { atomicOr(d.error_flag, 1u); return; }   // batch-local keys can be anything
+    d.bytemap[key] = 1;
+    d.wordmap[key >> 5] = 1;
+}
+
+// Workgroup `vb` of a drawing of d.n samples; `word` is LDS for 1024 words.
+__device__ __forceinline__ void draw_block(const SampleArgs &d, uint32_t vb, uint32_t *word)
+{
+    const uint32_t i = vb * kBlock + threadIdx.x;
+    switch (d.scheme) {
+    case NUPS_CONFORM:      // independent sampling: sample i is draw i of the step
+        if (i < d.n) emit_sample(d, i, fresh_key(d, d.step, i));
+        break;
+    case NUPS_BOUNDED: {    // sample reuse: one workgroup emits one pass over one pool.  The order of the pass is the
+                            // ascending order of (first ORDER-stream word at (fresh id, pass), slot); rank by counting.
+        const uint32_t pool = vb / d.U, pass = vb % d.U;
+        const uint32_t first = pool * d.G;
+        const uint32_t g = min(d.G, d.F - first);
+        // position of this pass in the sequence: full pools emit U * G samples each
+        const uint64_t base = (uint64_t)pool * d.U * d.G + (uint64_t)pass * g;
+        if (base >= d.n) return;
+        for (uint32_t s = threadIdx.x; s < g; s += kBlock)
+            word[s] = draw_words(d.seed, kStreamOrder, d.dist_id, d.step, (uint64_t)(first + s) | ((uint64_t)pass << 32)).x0;
+        __syncthreads();
+        for (uint32_t s = threadIdx.x; s < g; s += kBlock) {
+            const uint32_t w = word[s];
+            uint32_t rank = 0;
+            for (uint32_t j = 0; j < g; ++j) {
+                const uint32_t wj = word[j];
+                rank += (wj < w || (wj == w && j < s)) ? 1u : 0u;
+            }
+            const uint64_t pos = base + rank;
+            if (pos < d.n) emit_sample(d, pos, fresh_key(d, d.step, first + s));   // every pass redraws the pool's keys
+        }
+        break;
+    }
+    case NUPS_LONGTERM: {   // reuse over a long-lived pool: the sample at global position g is slot perm(rank) of the
+                            // pool of its epoch, perm a four-round Feistel permutation of 0..P-1 (cycle walking)
+        if (i >= d.n) return;
+        const uint64_t g = d.cursor + i;
+        const uint64_t per_epoch = d.P * (uint64_t)d.R;
+        const uint64_t epoch = g / per_epoch, within = g % per_epoch;
+        const uint64_t pass = within / d.P;
+        uint64_t x = within % d.P;
+        const int half = d.half;
+        const uint32_t mask = (half >= 32) ? 0xFFFFFFFFu : ((1u << half) - 1u);
+        const Words k = draw_words(d.seed, kStreamRoundKey, d.dist_id, epoch, pass);
+        const uint32_t rk[4] = {k.x0, k.x1, k.x2, k.x3};
+        do {   // ends: the walk follows a cycle of a permutation of the 2^(2 half) domain that contains x < P
+            uint32_t L = (uint32_t)(x >> half) & mask, Rr = (uint32_t)x & mask;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const uint32_t nR = L ^ (mix32(Rr ^ rk[t]) & mask);
+                L = Rr; Rr = nR;
+            }
+            x = ((uint64_t)L << half) | Rr;
+        } while (x >= d.P);
+        emit_sample(d, i, fresh_key(d, epoch, x));
+        break;
+    }
+    case NUPS_NONCONFORM: { // direct-access repurposing: sample p takes the key that a uniformly chosen example of
+                            // its tile contributes
+        if (i >= d.n) return;
+        const uint32_t e = i / d.per_example;
+        const uint32_t base = (e / d.tile) * d.tile;
+        const uint32_t t = min(d.tile, d.local_n - base);
+        const Words w = draw_words(d.seed, kStreamLocal, d.dist_id, d.step, i);
+        const uint32_t pick = base + __umulhi(w.x0, t);
+        emit_sample(d, i, ((i % d.per_example) < d.split) ? d.local_a[pick] : d.local_b[pick]);
+        break;
+    }
+    default:
+        break;
+    }
+}
+
+// ---- the aggregation structure -----------------------------------------------------------------------------------
+
+// Marks the first mark_n keys of the step in the maps (the rest were marked when they were drawn); flags keys
+// outside the table.  Workgroup 0 also resets the step's counters.
+__device__ __forceinline__ void mark_block(const PlanArgs &a, uint32_t vb)
+{
+    const uint32_t i = vb * kBlock + threadIdx.x;
+    if (i == 0) a.meta[kMetaNumChunks] = 0;
+    if (i < kLossSlots && a.zero_loss) a.zero_loss[i * kLossStride] = 0.0;   // the step's loss starts from zero
+    if (i >= a.mark_n) return;
+    const uint32_t key = source_key(a.src, i);
+    if (key >= a.num_keys) { atomicOr(a.error_flag, 1u); return; }
+    a.bytemap[key] = 1;
+    a.wordmap[key >> 5] = 1;
+}
+
+// Sum of `items[0 .. end)` over the whole workgroup; every thread gets the result.
+// `items` is 16-byte aligned; whole uint4 are read, four per thread and iteration, then the tail.
+__device__ __forceinline__ uint32_t block_sum_range(const uint32_t *items, uint32_t end, uint32_t *lds)
+{
+    uint32_t c = 0;
+    const uint4 *v = reinterpret_cast<const uint4 *>(items);
+    const uint32_t n4 = end / 4;
+    uint32_t q = threadIdx.x;
+    for (; q + 3 * kBlock < n4; q += 4 * kBlock) {
+        const uint4 x0 = v[q], x1 = v[q + kBlock], x2 = v[q + 2 * kBlock], x3 = v[q + 3 * kBlock];
+        c += (x0.x + x0.y + x0.z + x0.w) + (x1.x + x1.y + x1.z + x1.w) + (x2.x + x2.y + x2.z + x2.w)
+             + (x3.x + x3.y + x3.z + x3.w);
+    }
+    for (; q < n4; q += kBlock) { const uint4 x = v[q]; c += x.x + x.y + x.z + x.w; }
+    for (uint32_t w = n4 * 4 + threadIdx.x; w < end; w += kBlock) c += items[w];
+    return block_sum(c, lds);
+}
+
+// Four marker bytes (0 or 1 each) -> four bits.
+__device__ __forceinline__ uint32_t pack4(uint32_t x)
+{
+    return (x & 1u) | ((x >> 7) & 2u) | ((x >> 14) & 4u) | ((x >> 21) & 8u);
+}
+
+// Tile `vb` of kScanTile bitmap words: packs the marked groups of the byte map into bitmap words, ranks each
+// word's distinct keys inside the tile and counts the tile's distinct keys.
+__device__ __forceinline__ void tiles_block(const PlanArgs &a, uint32_t vb, uint32_t *lds)
+{
+    if (vb >= a.bitmap_tiles) return;
+    const uint32_t w0 = vb * kScanTile + threadIdx.x * kScanItems;
+    uint32_t bits[kScanItems];
+    uint32_t c = 0;
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        bits[j] = 0;
+        if (w0 + j < a.words && a.wordmap[w0 + j]) {   // the byte map is allocated in whole words of 32 keys
+            const uint4 *src = reinterpret_cast<const uint4 *>(a.bytemap + (size_t)(w0 + j) * 32);
+            const uint4 lo = src[0], hi = src[1];
+            bits[j] = pack4(lo.x) | (pack4(lo.y) << 4) | (pack4(lo.z) << 8) | (pack4(lo.w) << 12)
+                      | (pack4(hi.x) << 16) | (pack4(hi.y) << 20) | (pack4(hi.z) << 24) | (pack4(hi.w) << 28);
+            a.bitmap[w0 + j] = bits[j];
+            a.wordmap[w0 + j] = 0;
+            c += __popc(bits[j]);
+        }
+    }
+    uint32_t total;
+    uint32_t run = block_exclusive_scan(c, lds, &total);
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        if (bits[j]) a.word_rank[w0 + j] = run;
+        run += __popc(bits[j]);
+    }
+    if (threadIdx.x == 0) a.tile_sum[vb] = total;
+}
+
+// One workgroup: exclusive prefix sums of the tile counts, and the number of distinct keys.
+__device__ __forceinline__ void prefix_block(const PlanArgs &a, uint32_t *lds)
+{
+    uint32_t carry = 0;
+    for (uint32_t base = 0; base < a.bitmap_tiles; base += kBlock) {
+        const uint32_t t = base + threadIdx.x;
+        const uint32_t v = t < a.bitmap_tiles ? a.tile_sum[t] : 0u;
+        uint32_t sum;
+        const uint32_t before = block_exclusive_scan(v, lds, &sum);
+        if (t < a.bitmap_tiles) a.tile_prefix[t] = carry + before;
+        carry += sum;
+    }
+    if (threadIdx.x == 0) a.meta[kMetaNumUniq] = carry;
+}
+
+// Accesses [vb * kRankTile, ...): which distinct key each belongs to and its position inside that key's segment.
+// The workgroup's accesses are first grouped by key in an LDS hash table (`hash`: 4 * kHashSlots words); one
+// global atomic per distinct key and workgroup reserves a run of positions, which the LDS counts subdivide.  Also
+// emits the distinct keys (every workgroup writes the keys it met; equal values where they meet).
+__device__ __forceinline__ void rank_block(const PlanArgs &a, uint32_t vb, uint32_t *hash)
+{
+    if (vb * kRankTile >= a.n) return;
+    uint32_t *hkey = hash, *hcnt = hash + kHashSlots, *hbase = hash + 2 * kHashSlots, *hval = hash + 3 * kHashSlots;
+    uint32_t slot_of[kRankItems], local[kRankItems], uidx[kRankItems], key[kRankItems];
+    // all loads are issued before the first use: keys, then their bitmap words and ranks
+#pragma unroll
+    for (int j = 0; j < kRankItems; ++j) {
+        const uint32_t i = vb * kRankTile + j * kBlock + threadIdx.x;
+        key[j] = i < a.n ? source_key(a.src, i) : kBadIndex;
+        if (key[j] >= a.num_keys) key[j] = kBadIndex;     // outside the table: flagged when it was marked
+    }
+    uint32_t below[kRankItems], bits[kRankItems];
+#pragma unroll
+    for (int j = 0; j < kRankItems; ++j) {
+        const uint32_t w = key[j] >> 5;
+        below[j] = key[j] != kBadIndex ? a.tile_prefix[w / kScanTile] + a.word_rank[w] : 0u;
+        bits[j] = key[j] != kBadIndex ? a.bitmap[w] : 0u;
+    }
+    for (uint32_t s = threadIdx.x; s < kHashSlots; s += kBlock) { hkey[s] = kBadIndex; hcnt[s] = 0; }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kRankItems; ++j) {
+        uidx[j] = kBadIndex;
+        if (key[j] != kBadIndex) {
+            const uint32_t u = below[j] + __popc(bits[j] & ((1u << (key[j] & 31)) - 1u));
+            uidx[j] = u;
+            uint32_t s = (u * 2654435761u) >> (32 - kHashBits);
+            for (;;) {   // ends: at most kRankTile distinct keys in 2 * kRankTile slots
+                const uint32_t old = atomicCAS(&hkey[s], kBadIndex, u);
+                if (old == kBadIndex || old == u) break;
+                s = (s + 1) & (kHashSlots - 1);
+            }
+            slot_of[j] = s;
+            hval[s] = key[j];
+            local[j] = atomicAdd(&hcnt[s], 1u);
+        }
+    }
+    __syncthreads();
+    {   // one global atomic per distinct key of the workgroup; all of a thread's atomics are in flight together
+        constexpr int kPerThread = kHashSlots / kBlock;
+        uint32_t base[kPerThread], cnt[kPerThread];
+#pragma unroll
+        for (int q = 0; q < kPerThread; ++q) {
+            const uint32_t s = q * kBlock + threadIdx.x;
+            cnt[q] = hcnt[s];
+            base[q] = 0;
+            if (cnt[q]) {
+                base[q] = atomicAdd(&a.cnt_work[hkey[s]], cnt[q]);
+                a.uniq[hkey[s]] = hval[s];
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < kPerThread; ++q)
+            if (cnt[q]) hbase[q * kBlock + threadIdx.x] = base[q];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kRankItems; ++j) {
+        const uint32_t i = vb * kRankTile + j * kBlock + threadIdx.x;
+        if (i < a.n) {
+            a.slot[i] = uidx[j];
+            if (uidx[j] != kBadIndex) a.rank[i] = hbase[slot_of[j]] + local[j];
+        }
+    }
+}
+
+// Sum of each tile of kScanTile access counts (large steps only).
+__device__ __forceinline__ void count_tiles_block(const PlanArgs &a, uint32_t vb, uint32_t *lds)
+{
+    if (vb >= a.count_tiles) return;
+    const uint32_t nu = a.meta[kMetaNumUniq];
+    const uint32_t u0 = vb * kScanTile + threadIdx.x * kScanItems;
+    uint32_t c = 0;
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j)
+        if (u0 + j < nu) c += a.cnt_work[u0 + j];
+    const uint32_t s = block_sum(c, lds);
+    if (threadIdx.x == 0) a.tile_sum[vb] = s;
+}
+
+// Segment offsets = exclusive prefix sums of the counts; cuts long segments into chunks.
+__device__ __forceinline__ void counts_block(const PlanArgs &a, uint32_t vb, uint32_t *lds)
+{
+    if (vb >= a.count_tiles) return;
+    const uint32_t nu = a.meta[kMetaNumUniq];
+    const uint32_t u0 = vb * kScanTile + threadIdx.x * kScanItems;
+    if (vb * kScanTile >= nu && vb != 0) return;
+    uint32_t before;
+    if (a.direct_count) before = block_sum_range(a.cnt_work, min(vb * kScanTile, nu), lds);
+    else before = block_sum_range(a.tile_sum, vb, lds);
+    uint32_t cnt[kScanItems];
+    uint32_t c = 0;
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        cnt[j] = (u0 + j < nu) ? a.cnt_work[u0 + j] : 0u;
+        c += cnt[j];
+    }
+    uint32_t total;
+    uint32_t run = before + block_exclusive_scan(c, lds, &total);
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        if (u0 + j < nu) {
+            a.seg[u0 + j] = run;
+            a.count[u0 + j] = cnt[j];
+            if (takes_hot_path(cnt[j], a.uniq[u0 + j], a.hot_bits)) {
+                const uint32_t nch = (cnt[j] + kChunk - 1) / kChunk;
+                const uint32_t base = atomicAdd(&a.meta[kMetaNumChunks], nch);
+                for (uint32_t ch = 0; ch < nch; ++ch) {
+                    a.chunk_seg[base + ch] = u0 + j;
+                    a.chunk_base[base + ch] = base;
+                }
+            }
+        }
+        run += cnt[j];
+        if (u0 + j + 1 == nu || (nu == 0 && u0 + j == 0)) {   // end marker seg[nu]
+            a.seg[nu] = run;
+            a.meta[kMetaTotal] = run;
+        }
+    }
+}
+
+// Groups the accesses by key and returns the byte map and the position counters to all-zero for the next step.
+__device__ __forceinline__ void scatter_block(const PlanArgs &a, uint32_t vb)
+{
+    const uint32_t i = vb * kBlock + threadIdx.x;
+    if (i >= a.n) return;
+    const uint32_t u = a.slot[i];
+    if (u == kBadIndex) return;
+    const uint32_t r = a.rank[i];
+    const uint32_t first = a.seg[u], next = a.seg[u + 1];
+    a.perm[first + r] = i;
+    a.bytemap[source_key(a.src, i)] = 0;
+    if (r == 0) {
+        a.cnt_work[u] = 0;
+        if (next - first == 1) a.rank[i] = kSingleAccess;   // lets the update skip the segment lookup
+    }
+}
+
+// ---- dispatch ------------------------------------------------------------------------------------------------------
+
+// Unit `vb` of one phase.  Dynamic LDS of the launch: at least side_lds_bytes(item.phase).
+__device__ __forceinline__ void side_item_unit(const SideItem &it, uint32_t vb)
+{
+    extern __shared__ uint32_t side_dyn[];
+    __shared__ uint32_t side_lds[kBlock / 64 + 1];
+    vb += it.block0;
+    if (it.phase == kSideDraw) {
+        if (vb < it.draw.blocks) { draw_block(it.draw, vb, side_dyn); return; }
+        vb -= it.draw.blocks;
+    }
+    const uint32_t plan = vb / it.blocks_per_plan;
+    if (plan >= (uint32_t)it.n_plans) return;
+    const PlanArgs &a = it.plan[plan];
+    vb -= plan * it.blocks_per_plan;
+    switch (it.phase) {
+    case kSideDraw: mark_block(a, vb); break;
+    case kSideTiles: tiles_block(a, vb, side_lds); break;
+    case kSidePrefix: prefix_block(a, side_lds); break;
+    case kSideRank: rank_block(a, vb, side_dyn); break;
+    case kSideCountTiles: count_tiles_block(a, vb, side_lds); break;
+    case kSideCounts: counts_block(a, vb, side_lds); break;
+    case kSideScatter: scatter_block(a, vb); break;
+    default: break;
+    }
+}
+
+// True if this workgroup belongs to the side work of the launch (and has done it).  The remaining workgroups,
+// numbered from sw.blocks on, are the launch's own.
+__device__ __forceinline__ bool side_work_block(const SideWork &sw)
+{
+    if (blockIdx.x >= sw.blocks) return false;
+    uint32_t vb = blockIdx.x;
+#pragma unroll
+    for (int k = 0; k < kMaxSide; ++k) {
+        if (k < sw.n) {
+            if (vb < sw.item[k].wgs) {
+                for (uint32_t unit = vb; unit < sw.item[k].blocks; unit += sw.item[k].wgs) {
+                    side_item_unit(sw.item[k], unit);
+                    __syncthreads();   // LDS is reused by the next unit
+                }
+                return true;
+            }
+            vb -= sw.item[k].wgs;
+        }
+    }
+    return true;   // padding workgroup
+}
+
+// Preparatory work on its own (a step that is run before later launches could carry all of its phases; push).
+__global__ void __launch_bounds__(kBlock) k_side(SideWork sw) { (void)side_work_block(sw); }
+
+}  // namespace nups

@@ -1,4 +1,5 @@
-// Direct access (pull / push) and the per-task gradient kernels of the minibatch step:
+// Direct access (pull / push), the per-task gradient kernels of the minibatch step and the scheduling of
+// preparatory work:
 // skip-gram with negative sampling, matrix factorisation, ComplEx (Section 5.1).  Every
 // kernel reads the tables as they are at the start of the step and writes only coefficients
 // and staged gradient rows; the tables are updated afterwards, once per distinct key
@@ -6,6 +7,80 @@
 #include "segment_apply.h"
 
 namespace nups {
+
+// ------------------------------------------------------------------------------------------------
+// Preparatory work of prepared steps: carried by the launches below, or launched on its own.
+// ------------------------------------------------------------------------------------------------
+
+// Workgroups per phase of side work in a carrier with many resident workgroups (narrow rows) or few (wide rows).
+constexpr uint32_t kSideWgsNarrow = 1024, kSideWgsWide = 64;
+
+// One phase on its own.
+nups_status launch_side(nups_ctx *ctx, const SideItem &it)
+{
+    if (it.blocks == 0) return NUPS_OK;
+    SideWork sw{};
+    sw.n = 1;
+    sw.blocks = it.blocks;
+    sw.item[0] = it;
+    sw.item[0].wgs = it.blocks;
+    hipLaunchKernelGGL(k_side, dim3(it.blocks), dim3(kBlock), side_lds_bytes(it), ctx->stream, sw);
+    NUPS_HIP(hipGetLastError());
+    return NUPS_OK;
+}
+
+// The next phase of each of the oldest prepared steps (at most kMaxSide), for the launch that is about to be
+// enqueued; *lds_bytes: dynamic LDS that the phases need.  A phase gets at most max_wgs_per_phase workgroups:
+// a side workgroup takes the registers of one of the carrier's own, so carriers with few resident workgroups
+// (wide rows) give the side work a few workgroups that loop, and have the time for it.
+SideWork take_side_work(nups_ctx *ctx, size_t *lds_bytes, uint32_t max_wgs_per_phase)
+{
+    SideWork sw{};
+    size_t lds = 0;
+    for (auto it = ctx->pending.begin(); it != ctx->pending.end() && sw.n < kMaxSide;) {
+        nups_prepared *p = *it;
+        const SideItem &ph = p->phases[p->next_phase++];
+        sw.item[sw.n] = ph;
+        sw.item[sw.n].wgs = std::min(ph.blocks, max_wgs_per_phase);
+        sw.blocks += sw.item[sw.n].wgs;
+        ++sw.n;
+        lds = std::max(lds, side_lds_bytes(ph));
+        if (p->next_phase == p->phases.size()) it = ctx->pending.erase(it);
+        else ++it;
+    }
+    sw.blocks = (sw.blocks + kNumXcd - 1) / kNumXcd * kNumXcd;   // keeps the carrier's own workgroups die-aligned
+    *lds_bytes = lds;
+    return sw;
+}
+
+// Enqueues, as launches of their own, the phases of p that no launch has carried yet.
+nups_status flush_side_work(nups_ctx *ctx, nups_prepared *p)
+{
+    for (auto it = ctx->pending.begin(); it != ctx->pending.end(); ++it)
+        if (*it == p) { ctx->pending.erase(it); break; }
+    nups_status st = NUPS_OK;
+    while (st == NUPS_OK && p->next_phase < p->phases.size()) {
+        const SideItem &ph = p->phases[p->next_phase++];
+        if (ph.phase == kSideDraw && ph.draw.blocks > 0) {   // the drawing is timed as its own phase
+            SideItem draw = ph, mark = ph;
+            draw.blocks = ph.draw.blocks;
+            mark.block0 = ph.draw.blocks;
+            mark.blocks = ph.blocks - ph.draw.blocks;
+            {
+                PhaseScope scope(ctx, NUPS_PHASE_SAMPLE, ctx->stream);
+                st = launch_side(ctx, draw);
+            }
+            if (st == NUPS_OK) {
+                PhaseScope scope(ctx, NUPS_PHASE_PLAN, ctx->stream);
+                st = launch_side(ctx, mark);
+            }
+        } else {
+            PhaseScope scope(ctx, NUPS_PHASE_PLAN, ctx->stream);
+            st = launch_side(ctx, ph);
+        }
+    }
+    return st;
+}
 
 // ------------------------------------------------------------------------------------------------
 // pull: values[i, :] = table[keys[i], :]; one thread per float4, zero rows for keys out of range.
@@ -56,11 +131,13 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(const float *in_table, con
                                                       const uint32_t *center, const uint32_t *context,
                                                       const uint32_t *negs, uint32_t B, int K, float *coefs,
                                                       float *stage, const uint32_t *center_slot,
-                                                      const uint32_t *center_rank, float *center_rows, double *loss)
+                                                      const uint32_t *center_rank, float *center_rows, double *loss,
+                                                      SideWork sw)
 {
     __shared__ float lds[kBlock / 64];
+    if (side_work_block(sw)) return;   // the first sw.blocks workgroups prepare later steps
     const int lane = threadIdx.x & (kGroup - 1);
-    const uint32_t e_raw = (xcd_block() * kBlock + threadIdx.x) / kGroup;
+    const uint32_t e_raw = (xcd_block(blockIdx.x - sw.blocks, gridDim.x - sw.blocks) * kBlock + threadIdx.x) / kGroup;
     const bool active = e_raw < B;
     const uint32_t e = active ? e_raw : B - 1;
     Row<NV4> v, acc;
@@ -96,18 +173,19 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(const float *in_table, con
 }
 
 template <int NV4>
-static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b, const Plan &in_plan, float *center_rows)
+static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b, const Plan &in_plan, float *center_rows,
+                             const SideWork &sw, size_t side_lds)
 {
     const Table &tin = ctx->tab[0], &tout = ctx->tab[1];
     const uint32_t blocks = xcd_grid((uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock));
-    hipLaunchKernelGGL(k_sgns_grad<NV4>, dim3(blocks), dim3(kBlock), 0, ctx->stream, (const float *)tin.data,
-                       (const float *)tout.data, (uint32_t)tin.num_keys, (uint32_t)tout.num_keys, tin.stride, b.k0,
-                       b.k1, b.negs, (uint32_t)b.B, (int)b.n_neg, ctx->coef, ctx->stage, in_plan.a.slot,
-                       in_plan.a.rank, center_rows, ctx->loss_cur);
+    hipLaunchKernelGGL(k_sgns_grad<NV4>, dim3(sw.blocks + blocks), dim3(kBlock), side_lds, ctx->stream,
+                       (const float *)tin.data, (const float *)tout.data, (uint32_t)tin.num_keys,
+                       (uint32_t)tout.num_keys, tin.stride, b.k0, b.k1, b.negs, (uint32_t)b.B, (int)b.n_neg, ctx->coef,
+                       ctx->stage, in_plan.a.slot, in_plan.a.rank, center_rows, ctx->loss_cur, sw);
 }
 
 // Plan side of a step: which keys each table is accessed with (plan 0: table 0, plan 1: table 1).  Sizes the
-// arrays and fills in the arguments; the construction itself is enqueued by build_plans.
+// arrays and fills in the arguments; the caller then lists the phases of the construction (build_phases).
 static nups_status plan_two_tables(nups_ctx *ctx, nups_prepared &p, const KeySource &s0, uint32_t n0,
                                    const KeySource &s1, uint32_t n1)
 {
@@ -115,12 +193,12 @@ static nups_status plan_two_tables(nups_ctx *ctx, nups_prepared &p, const KeySou
     p.n_plans = 2;
     p.plan[0].table = 0;
     p.plan[1].table = 1;
-    if ((st = ensure_plan_capacity(ctx, ctx->tab[0], p.plan[0], n0, p.lane)) != NUPS_OK) return st;
-    if ((st = ensure_plan_capacity(ctx, ctx->tab[1], p.plan[1], n1, p.lane)) != NUPS_OK) return st;
+    if ((st = ensure_plan_capacity(ctx, ctx->tab[0], p.plan[0], n0)) != NUPS_OK) return st;
+    if ((st = ensure_plan_capacity(ctx, ctx->tab[1], p.plan[1], n1)) != NUPS_OK) return st;
     p.plan[0].a.src = s0;
-    p.plan[0].a.n = n0;
+    p.plan[0].a.n = p.plan[0].a.mark_n = n0;
     p.plan[1].a.src = s1;
-    p.plan[1].a.n = n1;
+    p.plan[1].a.n = p.plan[1].a.mark_n = n1;
     p.plan[0].a.zero_loss = p.loss_dev;
     p.plan[1].a.zero_loss = nullptr;
     // partial rows of chunked segments: one region per table, the two updates run in the same launch
@@ -154,21 +232,24 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
     ctx->loss_cur = p.loss_dev;   // zeroed by the step's plan construction
     if (B == 0) return NUPS_OK;
     float *center_rows = ctx->stage + (size_t)B * tin.stride;
+    size_t side_lds = 0;
     {
+        const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
-#define CALL(N) launch_sgns_grad<N>(ctx, b, p.plan[0], center_rows)
+#define CALL(N) launch_sgns_grad<N>(ctx, b, p.plan[0], center_rows, sw, side_lds)
         NUPS_FOR_EACH_ROW_WIDTH(tin.stride, CALL)
 #undef CALL
         NUPS_HIP(hipGetLastError());
     }
     {   // both tables in one launch: the output side reads the staged center rows, not the input table
+        const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
         const TableUpdate<SrcStaged, OptSgd> uin{&p.plan[0], partial_of(ctx, p, 0), tin.data, nullptr,
                                                  SrcStaged{ctx->stage}, OptSgd{b.lr}};
         const TableUpdate<SrcSgnsOut, OptSgd> uout{&p.plan[1], partial_of(ctx, p, 1), tout.data, nullptr,
                                                    SrcSgnsOut{center_rows, p.plan[0].a.slot, ctx->coef, B, K},
                                                    OptSgd{b.lr}};
-        if ((st = launch_apply2(ctx->stream, tin.stride, uin, uout)) != NUPS_OK) return st;
+        if ((st = launch_apply2(ctx->stream, tin.stride, uin, uout, sw, side_lds)) != NUPS_OK) return st;
     }
     return NUPS_OK;
 }
@@ -181,11 +262,12 @@ template <int NV4>
 __global__ void __launch_bounds__(kBlock) k_mf_grad(const float *W, const float *H, uint32_t n_rows, uint32_t n_cols,
                                                     int stride, const uint32_t *row, const uint32_t *col,
                                                     const float *val, uint32_t B, float l2, float *stage,
-                                                    double *loss)
+                                                    double *loss, SideWork sw)
 {
     __shared__ float lds[kBlock / 64];
+    if (side_work_block(sw)) return;   // the first sw.blocks workgroups prepare later steps
     const int lane = threadIdx.x & (kGroup - 1);
-    const uint32_t c_raw = (xcd_block() * kBlock + threadIdx.x) / kGroup;
+    const uint32_t c_raw = (xcd_block(blockIdx.x - sw.blocks, gridDim.x - sw.blocks) * kBlock + threadIdx.x) / kGroup;
     const bool active = c_raw < B;
     const uint32_t c = active ? c_raw : B - 1;
     Row<NV4> w, h;
@@ -211,13 +293,13 @@ __global__ void __launch_bounds__(kBlock) k_mf_grad(const float *W, const float 
 }
 
 template <int NV4>
-static void launch_mf_grad(nups_ctx *ctx, const nups_batch &b)
+static void launch_mf_grad(nups_ctx *ctx, const nups_batch &b, const SideWork &sw, size_t side_lds)
 {
     const Table &tw = ctx->tab[0], &th = ctx->tab[1];
     const uint32_t blocks = xcd_grid((uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock));
-    hipLaunchKernelGGL(k_mf_grad<NV4>, dim3(blocks), dim3(kBlock), 0, ctx->stream, (const float *)tw.data,
-                       (const float *)th.data, (uint32_t)tw.num_keys, (uint32_t)th.num_keys, tw.stride, b.k0, b.k1,
-                       b.val, (uint32_t)b.B, b.l2, ctx->stage, ctx->loss_cur);
+    hipLaunchKernelGGL(k_mf_grad<NV4>, dim3(sw.blocks + blocks), dim3(kBlock), side_lds, ctx->stream,
+                       (const float *)tw.data, (const float *)th.data, (uint32_t)tw.num_keys, (uint32_t)th.num_keys,
+                       tw.stride, b.k0, b.k1, b.val, (uint32_t)b.B, b.l2, ctx->stage, ctx->loss_cur, sw);
 }
 
 nups_status plan_step_mf(nups_ctx *ctx, nups_prepared &p)
@@ -237,20 +319,23 @@ nups_status run_step_mf(nups_ctx *ctx, nups_prepared &p)
     if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)2 * B * tw.stride, ctx->stream)) != NUPS_OK) return st;
     ctx->loss_cur = p.loss_dev;   // zeroed by the step's plan construction
     if (B == 0) return NUPS_OK;
+    size_t side_lds = 0;
     {
+        const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
-#define CALL(N) launch_mf_grad<N>(ctx, b)
+#define CALL(N) launch_mf_grad<N>(ctx, b, sw, side_lds)
         NUPS_FOR_EACH_ROW_WIDTH(tw.stride, CALL)
 #undef CALL
         NUPS_HIP(hipGetLastError());
     }
     {
+        const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
         const TableUpdate<SrcStaged, OptSgd> uw{&p.plan[0], partial_of(ctx, p, 0), tw.data, nullptr,
                                                 SrcStaged{ctx->stage}, OptSgd{b.lr}};
         const TableUpdate<SrcStaged, OptSgd> uh{&p.plan[1], partial_of(ctx, p, 1), th.data, nullptr,
                                                 SrcStaged{ctx->stage + (size_t)B * tw.stride}, OptSgd{b.lr}};
-        if ((st = launch_apply2(ctx->stream, tw.stride, uw, uh)) != NUPS_OK) return st;
+        if ((st = launch_apply2(ctx->stream, tw.stride, uw, uh, sw, side_lds)) != NUPS_OK) return st;
     }
     return NUPS_OK;
 }
@@ -313,20 +398,26 @@ __device__ __forceinline__ void add_grad_relation(Row<NV4> &out, const Row<NV4> 
     }
 }
 
-// GB = row groups per workgroup (GB * 16 threads); one workgroup per triple.  IF = negative rows that a group has
-// in flight.
+// GB = row groups per triple (GB * 16 threads); a workgroup of kBlock threads takes kBlock / (GB * 16) triples.
+// IF = negative rows that a group has in flight.  The first sw.blocks workgroups prepare later steps instead.
 template <int NV4, int GB, int IF>
-__global__ void __launch_bounds__(GB * kGroup) k_kge_grad(const float *E, const float *R, uint32_t n_ent, uint32_t n_rel,
+__global__ void __launch_bounds__(kBlock) k_kge_grad(const float *E, const float *R, uint32_t n_ent, uint32_t n_rel,
                                                      int stride, const uint32_t *subj, const uint32_t *rel,
                                                      const uint32_t *obj, const uint32_t *negs, uint32_t B, int nh,
-                                                     int nt, float *coefs, float *stage, double *loss)
+                                                     int nt, float *coefs, float *stage, double *loss, SideWork sw)
 {
-    extern __shared__ float part[];   // [GB][stride]: per-group weighted row sums
+    extern __shared__ float part_all[];   // [triples per workgroup][GB][stride]: per-group weighted row sums
     __shared__ float lds[kBlock / 64];
+    if (side_work_block(sw)) return;
     constexpr int kHalf = GB / 2;
+    constexpr int kTriples = kBlock / (GB * kGroup);
     static_assert(GB >= 8 && GB % 8 == 0, "whole wavefronts per role, at least five groups for the last stage");
-    const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
-    const uint32_t e = blockIdx.x;
+    static_assert(kTriples >= 1 && kBlock % (GB * kGroup) == 0, "whole triples per workgroup");
+    const int lane = threadIdx.x & (kGroup - 1), group = (threadIdx.x / kGroup) % GB, which = threadIdx.x / (GB * kGroup);
+    const uint32_t e_raw = (blockIdx.x - sw.blocks) * kTriples + which;
+    const bool active = e_raw < B;      // a workgroup's last triples may be beyond the batch: they repeat triple B - 1
+    const uint32_t e = active ? e_raw : B - 1;   // and write nothing
+    float *part = part_all + (size_t)which * GB * stride;
     const int nn = nh + nt;
     // The first half of the groups scores the replaced subjects (dot products with A), the second half the
     // replaced objects (with C).  Group number gi of a role takes that role's negatives gi, gi + kHalf, ...;
@@ -367,14 +458,14 @@ __global__ void __launch_bounds__(GB * kGroup) k_kge_grad(const float *E, const 
                 const float phi = group_sum(partial_dot(x[k], dir));
                 const float g = sigmoidf(phi);           // label -1: d softplus(phi) / d phi
                 loss_acc += softplusf(phi);
-                if (lane == 0) coefs[(size_t)e * nn + lo + gi + j * kHalf] = g;
+                if (active && lane == 0) coefs[(size_t)e * nn + lo + gi + j * kHalf] = g;
                 axpy_row(wsum, g, x[k]);
             }
         }
     }
     store_row(part + (size_t)group * stride, wsum, lane);
     __syncthreads();
-    if (group < 5) {
+    if (group < 5 && active) {
         Row<NV4> s, r, o, A;
         load_row(s, s_ptr, lane);
         load_row(r, r_ptr, lane);
@@ -421,20 +512,23 @@ __global__ void __launch_bounds__(GB * kGroup) k_kge_grad(const float *E, const 
             store_row(stage + ((size_t)4 * B + e) * stride, out, lane);
         }
     }
-    block_add_loss<GB * kGroup / 64>(lane == 0 ? loss_acc : 0.f, loss, lds);
+    block_add_loss((active && lane == 0) ? loss_acc : 0.f, loss, lds);
 }
 
 template <int NV4>
-static void launch_kge_grad(nups_ctx *ctx, const nups_batch &b)
+static void launch_kge_grad(nups_ctx *ctx, const nups_batch &b, const SideWork &sw, size_t side_lds)
 {
-    // 128-thread workgroups, two negative rows in flight per group.  More groups per triple or more rows in
+    // Eight groups per triple, two negative rows in flight per group.  More groups per triple or more rows in
     // flight change nothing: the kernel runs at the speed at which memory delivers the negatives' rows.
     constexpr int GB = 8, IF = 2;
+    constexpr int kTriples = kBlock / (GB * kGroup);
     const Table &te = ctx->tab[0], &tr = ctx->tab[1];
-    const size_t lds = sizeof(float) * GB * (size_t)te.stride;
-    hipLaunchKernelGGL((k_kge_grad<NV4, GB, IF>), dim3((uint32_t)b.B), dim3(GB * kGroup), lds, ctx->stream, (const float *)te.data,
-                       (const float *)tr.data, (uint32_t)te.num_keys, (uint32_t)tr.num_keys, te.stride, b.k0, b.k1,
-                       b.k2, b.negs, (uint32_t)b.B, (int)b.n_neg, (int)b.n_neg2, ctx->coef, ctx->stage, ctx->loss_cur);
+    const size_t lds = std::max(sizeof(float) * kTriples * GB * (size_t)te.stride, side_lds);
+    const uint32_t blocks = (uint32_t)((b.B + kTriples - 1) / kTriples);
+    hipLaunchKernelGGL((k_kge_grad<NV4, GB, IF>), dim3(sw.blocks + blocks), dim3(kBlock), lds, ctx->stream,
+                       (const float *)te.data, (const float *)tr.data, (uint32_t)te.num_keys, (uint32_t)tr.num_keys,
+                       te.stride, b.k0, b.k1, b.k2, b.negs, (uint32_t)b.B, (int)b.n_neg, (int)b.n_neg2, ctx->coef,
+                       ctx->stage, ctx->loss_cur, sw);
 }
 
 nups_status plan_step_kge(nups_ctx *ctx, nups_prepared &p)
@@ -457,18 +551,21 @@ nups_status run_step_kge(nups_ctx *ctx, nups_prepared &p)
     if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)5 * B * te.stride, ctx->stream)) != NUPS_OK) return st;
     ctx->loss_cur = p.loss_dev;   // zeroed by the step's plan construction
     if (B == 0) return NUPS_OK;
+    size_t side_lds = 0;
     {
+        const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsWide);
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
         switch (te.stride / 64) {
-        case 2: launch_kge_grad<2>(ctx, b); break;
-        case 4: launch_kge_grad<4>(ctx, b); break;
-        case 6: launch_kge_grad<6>(ctx, b); break;
-        case 8: launch_kge_grad<8>(ctx, b); break;
+        case 2: launch_kge_grad<2>(ctx, b, sw, side_lds); break;
+        case 4: launch_kge_grad<4>(ctx, b, sw, side_lds); break;
+        case 6: launch_kge_grad<6>(ctx, b, sw, side_lds); break;
+        case 8: launch_kge_grad<8>(ctx, b, sw, side_lds); break;
         default: return fail(NUPS_ERR_UNIMPLEMENTED, "KGE row_stride");
         }
         NUPS_HIP(hipGetLastError());
     }
     {
+        const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsWide);
         PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
         const TableUpdate<SrcKgeEntity, OptAdagrad> ue{&p.plan[0], partial_of(ctx, p, 0), te.data, te.state,
                                                        SrcKgeEntity{ctx->stage, ctx->coef, B, nn, nh},
@@ -476,7 +573,7 @@ nups_status run_step_kge(nups_ctx *ctx, nups_prepared &p)
         const TableUpdate<SrcStaged, OptAdagrad> ur{&p.plan[1], partial_of(ctx, p, 1), tr.data, tr.state,
                                                     SrcStaged{ctx->stage + (size_t)4 * B * te.stride},
                                                     OptAdagrad{b.lr, b.eps}};
-        if ((st = launch_apply2(ctx->stream, te.stride, ue, ur)) != NUPS_OK) return st;
+        if ((st = launch_apply2(ctx->stream, te.stride, ue, ur, sw, side_lds)) != NUPS_OK) return st;
     }
     return NUPS_OK;
 }
