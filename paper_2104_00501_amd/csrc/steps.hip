@@ -58,27 +58,25 @@ nups_status flush_side_work(nups_ctx *ctx, nups_prepared *p)
 {
     for (auto it = ctx->pending.begin(); it != ctx->pending.end(); ++it)
         if (*it == p) { ctx->pending.erase(it); break; }
+    if (p->next_phase >= p->phases.size()) return NUPS_OK;
     nups_status st = NUPS_OK;
-    while (st == NUPS_OK && p->next_phase < p->phases.size()) {
-        const SideItem &ph = p->phases[p->next_phase++];
-        if (ph.phase == kSideDraw && ph.draw.blocks > 0) {   // the drawing is timed as its own phase
-            SideItem draw = ph, mark = ph;
-            draw.blocks = ph.draw.blocks;
-            mark.block0 = ph.draw.blocks;
-            mark.blocks = ph.blocks - ph.draw.blocks;
-            {
-                PhaseScope scope(ctx, NUPS_PHASE_SAMPLE, ctx->stream);
-                st = launch_side(ctx, draw);
-            }
-            if (st == NUPS_OK) {
-                PhaseScope scope(ctx, NUPS_PHASE_PLAN, ctx->stream);
-                st = launch_side(ctx, mark);
-            }
-        } else {
-            PhaseScope scope(ctx, NUPS_PHASE_PLAN, ctx->stream);
-            st = launch_side(ctx, ph);
-        }
+    const SideItem &first = p->phases[p->next_phase];
+    const bool draws = first.phase == kSideDraw && first.draw.blocks > 0;
+    if (draws) {   // the drawing is timed as a phase of its own, apart from the marking that shares its launch
+        SideItem draw = first;
+        draw.blocks = first.draw.blocks;
+        PhaseScope scope(ctx, NUPS_PHASE_SAMPLE, ctx->stream);
+        st = launch_side(ctx, draw);
     }
+    PhaseScope scope(ctx, NUPS_PHASE_PLAN, ctx->stream);
+    if (draws && st == NUPS_OK) {
+        SideItem mark = first;
+        mark.block0 = first.draw.blocks;
+        mark.blocks = first.blocks - first.draw.blocks;
+        st = launch_side(ctx, mark);
+        ++p->next_phase;
+    }
+    while (st == NUPS_OK && p->next_phase < p->phases.size()) st = launch_side(ctx, p->phases[p->next_phase++]);
     return st;
 }
 

@@ -214,6 +214,80 @@ def test_kge_one_step_matches_the_oracle(ne, nrel, d, B, nh, nt):
     nb.nups_destroy(ctx)
 
 
+def _run_pipelined(ctx, batches, depth):
+    """prepare steps t+1 .. t+depth, then run step t (depth 0: plain nups_step)"""
+    if depth == 0:
+        for b in batches:
+            nb.nups_step(ctx, b)
+        return
+    queue = [nb.nups_prepare_step(ctx, b) for b in batches[:depth]]
+    for t in range(len(batches)):
+        if t + depth < len(batches):
+            queue.append(nb.nups_prepare_step(ctx, batches[t + depth]))
+        nb.nups_step_prepared(ctx, queue.pop(0))
+
+
+@pytest.mark.parametrize("depth", [0, 3])
+def test_mf_pipelined_steps_match_the_oracle(depth):
+    # the preparatory work of later steps rides in the gradient and update launches of earlier ones
+    nr, nc, d, B, steps = 200_000, 20_000, 100, 8192, 7
+    rows, cols, vals = wl.mf_cells(nr, nc, 0.8, B * steps, 31)
+    W = wl.uniform_table(nr, d, -0.1, 0.1, 1)
+    H = wl.uniform_table(nc, d, -0.1, 0.1, 2)
+    tw, th = dev(W), dev(H)
+    ctx = nb.nups_init([tw, th], [d, d])
+    kr, kc, kv = dev_u32(rows), dev_u32(cols), dev(vals)
+    batches = [nb.make_batch(nb.NUPS_TASK_MF, B, kr.data_ptr() + 4 * t * B, kc.data_ptr() + 4 * t * B,
+                             val=kv.data_ptr() + 4 * t * B, lr=0.005, l2=0.01) for t in range(steps)]
+    _run_pipelined(ctx, batches, depth)
+    nb.nups_check(ctx)
+    rw, rh = W.copy(), H.copy()
+    for t in range(steps):
+        sl = slice(t * B, (t + 1) * B)
+        _, sw, sh = orc.step_mf(rw, rh, d, rows[sl], cols[sl], vals[sl], 0.005, 0.01)
+    _assert_structure(ctx, 0, B, sw)
+    _assert_structure(ctx, 1, B, sh)
+    _assert_close(tw.cpu().numpy(), rw, list(range(d)), 1e-4, "row factors after %d steps" % steps, W)
+    _assert_close(th.cpu().numpy(), rh, list(range(d)), 1e-4, "column factors after %d steps" % steps, H)
+    nb.nups_destroy(ctx)
+
+
+@pytest.mark.parametrize("depth", [1, 3])
+def test_kge_pipelined_steps_match_the_oracle(depth):
+    # every step draws its own negatives (uniform, fresh draws), marked in its structure as they are drawn
+    ne, nrel, d, B, nh, nt, steps = 100_000, 50, 500, 65, 50, 50, 6     # odd batch: a workgroup takes two triples
+    s, r, o = wl.kge_triples(ne, nrel, B * steps, 41)
+    E = wl.complex_table(ne, d, -0.1, 0.1, 1)
+    R = wl.complex_table(nrel, d, -0.1, 0.1, 2)
+    cc = _ccols(d, E.shape[1])
+    rng = np.random.default_rng(5)
+    GE = np.zeros_like(E); GR = np.zeros_like(R)
+    GE[:, cc] = (1.0 + rng.random((ne, d), dtype=np.float32)) * 1e-3
+    GR[:, cc] = (1.0 + rng.random((nrel, d), dtype=np.float32)) * 1e-3
+    te, tge, tr, tgr = dev(E), dev(GE), dev(R), dev(GR)
+    ctx = nb.nups_init([te, tr], [d, d])
+    nb.nups_set_state(ctx, 0, tge)
+    nb.nups_set_state(ctx, 1, tgr)
+    dist = nb.nups_register_distribution(ctx, 0, None, nb.NUPS_CONFORM, seed=9)
+    ks, kr, ko = dev_u32(s), dev_u32(r), dev_u32(o)
+    batches = [nb.make_batch(nb.NUPS_TASK_KGE, B, ks.data_ptr() + 4 * t * B, kr.data_ptr() + 4 * t * B,
+                             k2=ko.data_ptr() + 4 * t * B, n_neg=nh, n_neg2=nt, lr=0.05, eps=1e-10, dist=dist,
+                             sample_step=t) for t in range(steps)]
+    _run_pipelined(ctx, batches, depth)
+    nb.nups_check(ctx)
+    rE, rGE, rR, rGR = E.copy(), GE.copy(), R.copy(), GR.copy()
+    for t in range(steps):
+        sl = slice(t * B, (t + 1) * B)
+        negs = orc.sample_conform(None, ne, 9, 0, t, B * (nh + nt))
+        _, se, sr = orc.step_kge(rE, rGE, rR, rGR, d, s[sl], r[sl], o[sl], negs, nh, nt, 0.05, 1e-10)
+    _assert_structure(ctx, 0, B * (2 + nh + nt), se)
+    _assert_structure(ctx, 1, B, sr)
+    _assert_close(te.cpu().numpy(), rE, cc, 1e-4, "entities after %d steps" % steps, E)
+    _assert_close(tr.cpu().numpy(), rR, cc, 1e-4, "relations after %d steps" % steps, R)
+    _assert_close(tge.cpu().numpy(), rGE, cc, 1e-4, "entity AdaGrad state after %d steps" % steps, GE)
+    nb.nups_destroy(ctx)
+
+
 def test_kge_first_step_from_zero_state():
     # From G = 0 the move is lr * delta / (|delta| + eps): where |delta| is at rounding level the sign is
     # undetermined, so parameters are compared where the oracle's |delta| = sqrt(G_new) is well above that.
