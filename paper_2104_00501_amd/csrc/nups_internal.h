@@ -35,7 +35,7 @@ constexpr int kHashBits = 10;
 constexpr uint32_t kHashSlots = 1u << kHashBits;    // open-addressing table in LDS, at most half full
 constexpr size_t kRankLdsBytes = 4 * kHashSlots * sizeof(uint32_t);
 constexpr uint32_t kMaxPool = 1024;                 // BOUNDED: largest pool (its order words are kept in LDS)
-constexpr size_t kDrawLdsBytes = kMaxPool * sizeof(uint32_t);
+constexpr size_t kDrawLdsBytes = (kMaxPool + 8) * sizeof(uint32_t);
 
 // meta words of a plan (device)
 enum { kMetaNumUniq = 0, kMetaNumChunks = 1, kMetaTotal = 2, kMetaWords = 4 };

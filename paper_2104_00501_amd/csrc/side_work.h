@@ -57,7 +57,7 @@ __device__ __forceinline__ void emit_sample(const SampleArgs &d, uint64_t pos, u
     d.wordmap[key >> 5] = 1;
 }
 
-// Workgroup `vb` of a drawing of d.n samples; `word` is LDS for 1024 words.
+// Workgroup `vb` of a drawing of d.n samples; `word` is LDS for kMaxPool + 8 words, 16-byte aligned.
 __device__ __forceinline__ void draw_block(const SampleArgs &d, uint32_t vb, uint32_t *word)
 {
     const uint32_t i = vb * kBlock + threadIdx.x;
@@ -73,15 +73,27 @@ __device__ __forceinline__ void draw_block(const SampleArgs &d, uint32_t vb, uin
         // position of this pass in the sequence: full pools emit U * G samples each
         const uint64_t base = (uint64_t)pool * d.U * d.G + (uint64_t)pass * g;
         if (base >= d.n) return;
-        for (uint32_t s = threadIdx.x; s < g; s += kBlock)
-            word[s] = draw_words(d.seed, kStreamOrder, d.dist_id, d.step, (uint64_t)(first + s) | ((uint64_t)pass << 32)).x0;
+        const uint32_t g8 = (g + 7) & ~7u;    // padded with words that rank after every real one
+        for (uint32_t s = threadIdx.x; s < g8; s += kBlock)
+            word[s] = s < g ? draw_words(d.seed, kStreamOrder, d.dist_id, d.step,
+                                         (uint64_t)(first + s) | ((uint64_t)pass << 32)).x0
+                            : 0xFFFFFFFFu;
         __syncthreads();
+        const uint4 *word4 = reinterpret_cast<const uint4 *>(word);
         for (uint32_t s = threadIdx.x; s < g; s += kBlock) {
             const uint32_t w = word[s];
             uint32_t rank = 0;
-            for (uint32_t j = 0; j < g; ++j) {
-                const uint32_t wj = word[j];
-                rank += (wj < w || (wj == w && j < s)) ? 1u : 0u;
+#pragma unroll 4
+            for (uint32_t j = 0; j < g8; j += 8) {   // eight words per turn: the reads' latency overlaps
+                const uint4 a = word4[j / 4], b = word4[j / 4 + 1];
+                rank += (a.x < w || (a.x == w && j + 0 < s)) ? 1u : 0u;
+                rank += (a.y < w || (a.y == w && j + 1 < s)) ? 1u : 0u;
+                rank += (a.z < w || (a.z == w && j + 2 < s)) ? 1u : 0u;
+                rank += (a.w < w || (a.w == w && j + 3 < s)) ? 1u : 0u;
+                rank += (b.x < w || (b.x == w && j + 4 < s)) ? 1u : 0u;
+                rank += (b.y < w || (b.y == w && j + 5 < s)) ? 1u : 0u;
+                rank += (b.z < w || (b.z == w && j + 6 < s)) ? 1u : 0u;
+                rank += (b.w < w || (b.w == w && j + 7 < s)) ? 1u : 0u;
             }
             const uint64_t pos = base + rank;
             if (pos < d.n) emit_sample(d, pos, fresh_key(d, d.step, first + s));   // every pass redraws the pool's keys
@@ -362,7 +374,7 @@ __device__ __forceinline__ void scatter_block(const PlanArgs &a, uint32_t vb)
 // Unit `vb` of one phase.  Dynamic LDS of the launch: at least side_lds_bytes(item.phase).
 __device__ __forceinline__ void side_item_unit(const SideItem &it, uint32_t vb)
 {
-    extern __shared__ uint32_t side_dyn[];
+    extern __shared__ __align__(16) uint32_t side_dyn[];
     __shared__ uint32_t side_lds[kBlock / 64 + 1];
     vb += it.block0;
     if (it.phase == kSideDraw) {
