@@ -401,6 +401,59 @@ def test_sgns_pipelined_steps_match_the_oracle(depth):
     nb.nups_destroy(ctx)
 
 
+def test_prepared_steps_far_ahead_with_other_calls_in_between():
+    # five steps prepared ahead (more than one launch can carry), an empty batch among them, a push and a pull
+    # between runs, and a hot-key declaration refused while prepared steps are outstanding
+    V, d, B, K, window, steps, lr = 20_000, 100, 1024, 5, 2, 9, 0.002
+    toks = wl.zipf_stream(V, 1.0, steps * B // (2 * window) + 2 * window + 8, 51)
+    In, Out = wl.sgns_tables(V, d, 51)
+    Out[:] = wl.uniform_table(V, d, -0.5 / d, 0.5 / d, 52)
+    w = wl.unigram_weights(toks, V)
+    tin, tout = dev(In), dev(Out)
+    ctx = nb.nups_init([tin, tout], [d, d])
+    dist = nb.nups_register_distribution(ctx, 1, w, nb.NUPS_CONFORM, seed=51)
+    pairs = [wl.window_pairs(toks, window, t * B, B) for t in range(steps)]
+    sizes = [B if t != 4 else 0 for t in range(steps)]                  # step 4 is empty
+    dev_pairs = [(dev_u32(c), dev_u32(o)) for c, o in pairs]
+    batches = [nb.make_batch(nb.NUPS_TASK_SGNS, sizes[t], dev_pairs[t][0], dev_pairs[t][1], n_neg=K, lr=lr, dist=dist,
+                             sample_step=t) for t in range(steps)]
+    push_keys = np.array([3, 7, 3, 19_999], dtype=np.uint32)
+    push_rows = wl.uniform_table(4, d, -0.01, 0.01, 53)
+    kp, vp = dev_u32(push_keys), dev(push_rows)
+    depth = 5
+    queue = [nb.nups_prepare_step(ctx, b) for b in batches[:depth]]
+    with pytest.raises(nb.NupsError) as e:
+        nb.nups_set_hot_keys(ctx, 0, np.arange(10, dtype=np.uint32))
+    assert e.value.status == nb.NUPS_ERR_STATE
+    import torch
+    pulled = torch.zeros((4, tin.shape[1]), dtype=torch.float32, device="cuda")
+    for t in range(steps):
+        if t + depth < steps:
+            queue.append(nb.nups_prepare_step(ctx, batches[t + depth]))
+        nb.nups_step_prepared(ctx, queue.pop(0))
+        if t == 2:
+            nb.nups_push(ctx, 0, kp, 4, vp)                             # between two runs, on the same stream
+        if t == 5:
+            nb.nups_pull(ctx, 0, kp, 4, pulled)
+    nb.nups_check(ctx)
+    alias = orc.alias_build(w)
+    rin, rout = In.copy(), Out.copy()
+    at5 = None
+    for t in range(steps):
+        n = sizes[t]
+        negs = orc.sample_conform(alias, V, 51, 0, t, n * K)
+        orc.step_sgns(rin, rout, d, pairs[t][0][:n], pairs[t][1][:n], negs, K, lr)
+        if t == 2:
+            orc.push(rin, d, push_keys, push_rows)
+        if t == 5:
+            at5 = rin[push_keys].copy()
+    cols = list(range(d))
+    _assert_close(tin.cpu().numpy(), rin, cols, 1e-4, "input table")
+    _assert_close(tout.cpu().numpy(), rout, cols, 1e-4, "output table")
+    _assert_close(pulled.cpu().numpy(), at5, cols, 1e-4, "rows pulled after step 5")
+    nb.nups_destroy(ctx)
+
+
 @pytest.mark.parametrize("s", [0.6, 1.4])
 def test_hot_key_set_changes_speed_not_results(s):
     # skew sweep shape: 500k keys, d = 200, 5 negatives, B = 8192; hot sets of 0, 1k, 16k keys and no declaration
