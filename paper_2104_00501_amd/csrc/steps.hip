@@ -154,6 +154,7 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(const float *in_table, con
             const uint32_t key = (j == 0) ? context[e] : negs[(size_t)e * K + (j - 1)];
             load_row(u[jj], out_table + (size_t)min(key, num_out - 1) * stride, lane);
         }
+        float g_mine = 0.f;   // lane jj of the group keeps coefficient j0 + jj: one store for the JU of them
 #pragma unroll
         for (int jj = 0; jj < JU; ++jj) {
             const int j = j0 + jj;
@@ -161,10 +162,11 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(const float *in_table, con
                 const float z = group_sum(partial_dot(v, u[jj]));
                 const float g = sigmoidf(z) - (j == 0 ? 1.0f : 0.0f);
                 loss_acc += softplusf(j == 0 ? -z : z);
-                if (active && lane == 0) coefs[(size_t)e * (K + 1) + j] = g;
+                if (lane == jj) g_mine = g;
                 axpy_row(acc, g, u[jj]);
             }
         }
+        if (active && lane < JU && j0 + lane <= K) coefs[(size_t)e * (K + 1) + j0 + lane] = g_mine;
     }
     if (active) store_row(stage + (size_t)e * stride, acc, lane);
     block_add_loss((active && lane == 0) ? loss_acc : 0.f, loss, lds);
