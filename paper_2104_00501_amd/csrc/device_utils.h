@@ -39,13 +39,22 @@ __device__ __forceinline__ Words draw_words(uint64_t seed, uint32_t stream, uint
                          (uint32_t)(seed >> 32));
 }
 
-// Sum over the 16 lanes of a row group; every lane of the group receives the total.
+// x as lane `ctrl` of the same 16-lane row holds it (a data-parallel-primitive move inside the vector unit: no LDS
+// traffic, unlike a general shuffle).
+template <int kCtrl>
+__device__ __forceinline__ float row_move(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), kCtrl, 0xF, 0xF, false));
+}
+
+// Sum over the 16 lanes of a row group; every lane of the group receives the total.  Neighbour in the pair, other
+// pair of the quad, mirror image in the half row (the other quad), mirror image in the row (the other half).
 __device__ __forceinline__ float group_sum(float x)
 {
-    x += __shfl_xor(x, 1, kGroup);
-    x += __shfl_xor(x, 2, kGroup);
-    x += __shfl_xor(x, 4, kGroup);
-    x += __shfl_xor(x, 8, kGroup);
+    x += row_move<0xB1>(x);    // quad_perm [1,0,3,2]
+    x += row_move<0x4E>(x);    // quad_perm [2,3,0,1]
+    x += row_move<0x141>(x);   // row_half_mirror
+    x += row_move<0x140>(x);   // row_mirror
     return x;
 }
 
