@@ -34,6 +34,8 @@ constexpr int kRankTile = kBlock * kRankItems;
 constexpr int kHashBits = 10;
 constexpr uint32_t kHashSlots = 1u << kHashBits;    // open-addressing table in LDS, at most half full
 constexpr size_t kRankLdsBytes = 4 * kHashSlots * sizeof(uint32_t);
+constexpr uint32_t kLdsTiles = 2048;                // tile counts that a workgroup scans in LDS by itself (64M keys)
+constexpr size_t kSlotLdsBytes = kLdsTiles * sizeof(uint32_t);
 constexpr uint32_t kMaxPool = 1024;                 // BOUNDED: largest pool (its order words are kept in LDS)
 constexpr size_t kDrawLdsBytes = (kMaxPool + 8) * sizeof(uint32_t);
 
@@ -76,7 +78,7 @@ struct PlanArgs {
     uint32_t *bitmap;      // [words]     one bit per key; only the words with a marked key are written by a build
     uint32_t *word_rank;   // [words]     distinct keys below the word inside its tile (written for the same words)
     uint32_t *tile_sum;    // [max(bitmap_tiles, count_tiles)]
-    uint32_t *tile_prefix; // [bitmap_tiles] distinct keys below each tile
+    uint32_t *tile_prefix; // [bitmap_tiles] distinct keys below each tile (tables with more than kLdsTiles tiles only)
     uint32_t *cnt_work;    // [n]         per distinct key: positions handed out so far, zero between builds
     // result, owned by the plan
     uint32_t *uniq;        // [n]         distinct keys, ascending
@@ -132,7 +134,7 @@ struct SampleArgs {
 
 // Phases of a step's preparatory work, in order (side_work.h).
 enum SidePhase : int32_t {
-    kSideDraw = 0, kSideTiles, kSidePrefix, kSideRank, kSideCountTiles, kSideCounts, kSideScatter
+    kSideDraw = 0, kSideTiles, kSidePrefix, kSideSlot, kSideRank, kSideCountTiles, kSideCounts, kSideScatter
 };
 
 // One phase of one step: units block0 .. block0 + blocks - 1 of it.

@@ -83,6 +83,7 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
 size_t side_lds_bytes(const SideItem &it)
 {
     if (it.phase == kSideRank) return kRankLdsBytes;
+    if (it.phase == kSideSlot) return kSlotLdsBytes;
     if (it.phase == kSideDraw && it.draw.scheme == NUPS_BOUNDED) return kDrawLdsBytes;
     return 0;
 }
@@ -126,7 +127,8 @@ void build_phases(nups_prepared &p, const SampleArgs &draw, int mark_plan)
     add(kSideDraw, std::max(1u, (max_mark + kBlock - 1) / kBlock), draw_blocks);
     it.draw = SampleArgs{};
     add(kSideTiles, max_btiles, 0);
-    add(kSidePrefix, 1, 0);
+    if (max_btiles > kLdsTiles) add(kSidePrefix, 1, 0);   // else every workgroup of the next phase scans the tile counts
+    add(kSideSlot, std::max(1u, (max_n + kRankTile - 1) / kRankTile), 0);
     add(kSideRank, std::max(1u, (max_n + kRankTile - 1) / kRankTile), 0);
     if (need_count_tiles) add(kSideCountTiles, max_ctiles, 0);
     add(kSideCounts, max_ctiles, 0);

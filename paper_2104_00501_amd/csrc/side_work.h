@@ -4,8 +4,9 @@
 // The work of one step is a chain of phases, each of which needs everything the previous one wrote:
 //   draw    the step's own sample keys (Section 4.4 schemes) + marks every key the step accesses
 //   tiles   packs the marked key groups into bitmap words, ranks the words inside tiles, counts per tile
-//   prefix  distinct keys below each tile
-//   rank    per access: index of its key among the distinct keys, position inside that key's segment
+//   slot    per access: index of its key among the distinct keys (tile counts scanned by every workgroup; tables
+//           with very many tiles get a phase of their own for that scan before)
+//   rank    per access: position inside its key's segment; the distinct keys
 //   counts  segment offsets (prefix sums of the per-key counts), chunk lists of long segments
 //   scatter accesses grouped by key; the scratch maps return to all-zero
 // A launch of a gradient or update kernel carries, in its first workgroups, one phase each of up to kMaxSide later
@@ -211,8 +212,8 @@ __device__ __forceinline__ void tiles_block(const PlanArgs &a, uint32_t vb, uint
     if (threadIdx.x == 0) a.tile_sum[vb] = total;
 }
 
-// One workgroup: exclusive prefix sums of the tile counts, and the number of distinct keys.
-__device__ __forceinline__ void prefix_block(const PlanArgs &a, uint32_t *lds)
+// Exclusive prefix sums of the tile counts into `prefix` (LDS or global); returns the number of distinct keys.
+__device__ __forceinline__ uint32_t scan_tile_sums(const PlanArgs &a, uint32_t *prefix, uint32_t *lds)
 {
     uint32_t carry = 0;
     for (uint32_t base = 0; base < a.bitmap_tiles; base += kBlock) {
@@ -220,43 +221,80 @@ __device__ __forceinline__ void prefix_block(const PlanArgs &a, uint32_t *lds)
         const uint32_t v = t < a.bitmap_tiles ? a.tile_sum[t] : 0u;
         uint32_t sum;
         const uint32_t before = block_exclusive_scan(v, lds, &sum);
-        if (t < a.bitmap_tiles) a.tile_prefix[t] = carry + before;
+        if (t < a.bitmap_tiles) prefix[t] = carry + before;
         carry += sum;
     }
-    if (threadIdx.x == 0) a.meta[kMetaNumUniq] = carry;
+    return carry;
 }
 
-// Accesses [vb * kRankTile, ...): which distinct key each belongs to and its position inside that key's segment.
-// The workgroup's accesses are first grouped by key in an LDS hash table (`hash`: 4 * kHashSlots words); one
-// global atomic per distinct key and workgroup reserves a run of positions, which the LDS counts subdivide.  Also
-// emits the distinct keys (every workgroup writes the keys it met; equal values where they meet).
-__device__ __forceinline__ void rank_block(const PlanArgs &a, uint32_t vb, uint32_t *hash)
+// Tables with more tiles than a workgroup scans by itself: one workgroup writes the distinct keys below each tile
+// to memory, and the number of distinct keys.
+__device__ __forceinline__ void prefix_block(const PlanArgs &a, uint32_t *lds)
 {
-    if (vb * kRankTile >= a.n) return;
-    uint32_t *hkey = hash, *hcnt = hash + kHashSlots, *hbase = hash + 2 * kHashSlots, *hval = hash + 3 * kHashSlots;
-    uint32_t slot_of[kRankItems], local[kRankItems], uidx[kRankItems], key[kRankItems];
-    // all loads are issued before the first use: keys, then their bitmap words and ranks
+    if (a.bitmap_tiles <= kLdsTiles) return;
+    const uint32_t nu = scan_tile_sums(a, a.tile_prefix, lds);
+    if (threadIdx.x == 0) a.meta[kMetaNumUniq] = nu;
+}
+
+// Accesses [vb * kRankTile, ...): the index of each access's key among the distinct keys = distinct keys below
+// its tile + below its word inside the tile + below its bit inside the word.  `scan`: LDS for kLdsTiles words.
+__device__ __forceinline__ void slot_block(const PlanArgs &a, uint32_t vb, uint32_t *scan, uint32_t *lds)
+{
+    if (vb * kRankTile >= a.n && vb != 0) return;
+    uint32_t key[kRankItems], below[kRankItems], bits[kRankItems];
+    // the keys and their bitmap words are requested before the scan, which hides their latency
 #pragma unroll
     for (int j = 0; j < kRankItems; ++j) {
         const uint32_t i = vb * kRankTile + j * kBlock + threadIdx.x;
         key[j] = i < a.n ? source_key(a.src, i) : kBadIndex;
         if (key[j] >= a.num_keys) key[j] = kBadIndex;     // outside the table: flagged when it was marked
     }
-    uint32_t below[kRankItems], bits[kRankItems];
 #pragma unroll
     for (int j = 0; j < kRankItems; ++j) {
         const uint32_t w = key[j] >> 5;
-        below[j] = key[j] != kBadIndex ? a.tile_prefix[w / kScanTile] + a.word_rank[w] : 0u;
+        below[j] = key[j] != kBadIndex ? a.word_rank[w] : 0u;
         bits[j] = key[j] != kBadIndex ? a.bitmap[w] : 0u;
+    }
+    const uint32_t *tile_prefix = a.tile_prefix;
+    if (a.bitmap_tiles <= kLdsTiles) {
+        const uint32_t nu = scan_tile_sums(a, scan, lds);
+        if (vb == 0 && threadIdx.x == 0) a.meta[kMetaNumUniq] = nu;
+        tile_prefix = scan;
+        __syncthreads();
+    }
+#pragma unroll
+    for (int j = 0; j < kRankItems; ++j) {
+        const uint32_t i = vb * kRankTile + j * kBlock + threadIdx.x;
+        if (i < a.n) {
+            const uint32_t w = key[j] >> 5;
+            a.slot[i] = key[j] != kBadIndex
+                            ? tile_prefix[w / kScanTile] + below[j] + __popc(bits[j] & ((1u << (key[j] & 31)) - 1u))
+                            : kBadIndex;
+        }
+    }
+}
+
+// Accesses [vb * kRankTile, ...): the position of each inside its key's segment.  The workgroup's accesses are
+// first grouped by key in an LDS hash table (`hash`: 4 * kHashSlots words); one global atomic per distinct key and
+// workgroup reserves a run of positions, which the LDS counts subdivide.  Also emits the distinct keys (every
+// workgroup writes the keys it met; equal values where they meet).
+__device__ __forceinline__ void rank_block(const PlanArgs &a, uint32_t vb, uint32_t *hash)
+{
+    if (vb * kRankTile >= a.n) return;
+    uint32_t *hkey = hash, *hcnt = hash + kHashSlots, *hbase = hash + 2 * kHashSlots, *hval = hash + 3 * kHashSlots;
+    uint32_t slot_of[kRankItems], local[kRankItems], uidx[kRankItems], key[kRankItems];
+#pragma unroll
+    for (int j = 0; j < kRankItems; ++j) {
+        const uint32_t i = vb * kRankTile + j * kBlock + threadIdx.x;
+        uidx[j] = i < a.n ? a.slot[i] : kBadIndex;
+        key[j] = i < a.n ? source_key(a.src, i) : kBadIndex;
     }
     for (uint32_t s = threadIdx.x; s < kHashSlots; s += kBlock) { hkey[s] = kBadIndex; hcnt[s] = 0; }
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < kRankItems; ++j) {
-        uidx[j] = kBadIndex;
-        if (key[j] != kBadIndex) {
-            const uint32_t u = below[j] + __popc(bits[j] & ((1u << (key[j] & 31)) - 1u));
-            uidx[j] = u;
+        if (uidx[j] != kBadIndex) {
+            const uint32_t u = uidx[j];
             uint32_t s = (u * 2654435761u) >> (32 - kHashBits);
             for (;;) {   // ends: at most kRankTile distinct keys in 2 * kRankTile slots
                 const uint32_t old = atomicCAS(&hkey[s], kBadIndex, u);
@@ -290,10 +328,7 @@ __device__ __forceinline__ void rank_block(const PlanArgs &a, uint32_t vb, uint3
 #pragma unroll
     for (int j = 0; j < kRankItems; ++j) {
         const uint32_t i = vb * kRankTile + j * kBlock + threadIdx.x;
-        if (i < a.n) {
-            a.slot[i] = uidx[j];
-            if (uidx[j] != kBadIndex) a.rank[i] = hbase[slot_of[j]] + local[j];
-        }
+        if (i < a.n && uidx[j] != kBadIndex) a.rank[i] = hbase[slot_of[j]] + local[j];
     }
 }
 
@@ -389,6 +424,7 @@ __device__ __forceinline__ void side_item_unit(const SideItem &it, uint32_t vb)
     case kSideDraw: mark_block(a, vb); break;
     case kSideTiles: tiles_block(a, vb, side_lds); break;
     case kSidePrefix: prefix_block(a, side_lds); break;
+    case kSideSlot: slot_block(a, vb, side_dyn, side_lds); break;
     case kSideRank: rank_block(a, vb, side_dyn); break;
     case kSideCountTiles: count_tiles_block(a, vb, side_lds); break;
     case kSideCounts: counts_block(a, vb, side_lds); break;
