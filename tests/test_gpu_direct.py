@@ -42,7 +42,8 @@ def test_pull_flags_keys_out_of_range_without_touching_memory():
 
 
 @pytest.mark.parametrize("V,d,n,s", [(10_000, 100, 20_000, 1.0), (100_000, 300, 30_001, 1.4), (500, 500, 4096, 0.6),
-                                      (1000, 200, 1, 1.0)])
+                                      (1000, 200, 1, 1.0),
+                                      (200_000, 64, 300_000, 0.8)])      # > 131,072 accesses: tiled count sums
 def test_push_sums_duplicates_and_reports_the_structure(V, d, n, s):
     import torch
     T = wl.uniform_table(V, d, -1, 1, 3)
@@ -68,4 +69,32 @@ def test_push_sums_duplicates_and_reports_the_structure(V, d, n, s):
     nb.nups_push(ctx, 0, None, 0, None)         # empty push is a no-op
     nb.nups_check(ctx)
     assert np.array_equal(table.cpu().numpy(), got)
+    nb.nups_destroy(ctx)
+
+
+def test_push_into_a_table_with_more_tiles_than_a_workgroup_scans():
+    # 40M keys = 2,442 bitmap tiles: the distinct keys below each tile come from a phase of their own
+    import torch
+    V, d, n = 40_000_000, 64, 6000
+    table = torch.zeros((V, 64), dtype=torch.float32, device="cuda")
+    rng = np.random.default_rng(7)
+    keys = rng.integers(0, V, size=n, dtype=np.int64).astype(np.uint32)
+    keys[100:200] = keys[:100]                       # duplicates
+    keys[-1] = V - 1
+    upd = wl.uniform_table(n, d, -1, 1, 8)
+    ctx = nb.nups_init([table], [d])
+    nb.nups_push(ctx, 0, dev_u32(keys), n, dev(upd))
+    uk = torch.zeros(n, dtype=torch.int32, device="cuda")
+    uc = torch.zeros(n, dtype=torch.int32, device="cuda")
+    nu = nb.nups_debug_structure(ctx, 0, uk, uc)
+    rk, rc = np.unique(keys, return_counts=True)
+    assert nu == len(rk)
+    assert np.array_equal(host_u32(uk)[:nu], rk) and np.array_equal(host_u32(uc)[:nu], rc.astype(np.uint32))
+    expect = np.zeros((len(rk), 64), dtype=np.float64)
+    np.add.at(expect, np.searchsorted(rk, keys), upd.astype(np.float64))
+    got = torch.zeros((len(rk), 64), dtype=torch.float32, device="cuda")
+    nb.nups_pull(ctx, 0, dev_u32(rk), len(rk), got)
+    nb.nups_check(ctx)
+    assert np.abs(got.cpu().numpy() - expect).max() < 1e-5
+    assert float(table.abs().sum().item()) == pytest.approx(float(np.abs(expect.astype(np.float32)).sum()), rel=1e-4)
     nb.nups_destroy(ctx)
