@@ -17,6 +17,7 @@ namespace nups {
 // Row i of a staging array, coefficient one (SGNS input side, MF, KGE subject/object/relation, push).
 struct SrcStaged {
     const float *stage;
+    __device__ __forceinline__ bool done_already(uint32_t) const { return false; }
     __device__ __forceinline__ float coef(uint32_t) const { return 1.0f; }
     __device__ __forceinline__ const float *row(uint32_t i, int stride) const { return stage + (size_t)i * stride; }
 };
@@ -30,6 +31,7 @@ struct SrcSgnsOut {
     const uint32_t *center_slot;  // [B] slot of each pair's center word
     const float *coefs;           // [B, K + 1]
     uint32_t B, K;
+    __device__ __forceinline__ bool done_already(uint32_t) const { return false; }
     __device__ __forceinline__ uint32_t pair_of(uint32_t i) const { return i < B ? i : (i - B) / K; }
     __device__ __forceinline__ float coef(uint32_t i) const
     {
@@ -44,11 +46,14 @@ struct SrcSgnsOut {
 
 // KGE entity table: accesses [0,B) subjects and [B,2B) objects take their staged gradient rows;
 // access 2B + p is negative p of triple p / nn and takes coef * (staged direction row of that
-// triple: rows 2B.. for replaced subjects, rows 3B.. for replaced objects).
+// triple: rows 2B.. for replaced subjects, rows 3B.. for replaced objects).  A negative that is its entity's only
+// access of the step was updated by the gradient kernel.
 struct SrcKgeEntity {
     const float *stage;
     const float *coefs;   // [B, nn]
     uint32_t B, nn, nh;
+    // i: the only access of its key
+    __device__ __forceinline__ bool done_already(uint32_t i) const { return i >= 2 * B; }
     __device__ __forceinline__ float coef(uint32_t i) const { return i < 2 * B ? 1.0f : coefs[i - 2 * B]; }
     __device__ __forceinline__ const float *row(uint32_t i, int stride) const
     {
@@ -100,10 +105,13 @@ struct OptAdd {          // theta <- theta + delta   (push)
 struct OptAdagrad {      // G <- G + delta^2 ; theta <- theta - lr * delta / (sqrt(G) + eps)
     float lr, eps;
     static constexpr bool kHasState = true;
+    // The hardware square root and reciprocal (one unit in the last place each) instead of the correctly rounded
+    // sequences: the update is a product of rounded factors anyway, and the row update is arithmetic-bound otherwise
+    // (a 2 KB row is 512 square roots and divisions).
     __device__ __forceinline__ void one(float &t, float &g, float d) const
     {
         g += d * d;
-        t -= lr * d / (sqrtf(g) + eps);
+        t -= lr * d * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(g) + eps);
     }
     template <int NV4>
     __device__ __forceinline__ void load(Row<NV4> &t, Row<NV4> &g, const float *row, const float *state_row,
@@ -216,6 +224,7 @@ __device__ __forceinline__ void apply_short_item(const ApplyArgs &a, const Src &
     float *row = a.table + off, *state_row = Opt::kHasState ? a.state + off : nullptr;
     Row<NV4> acc, t, g;
     zero_row(acc);
+    if (single && src.done_already(w)) return;
     if (single) {
         // the segment is this access alone (never a chunked one): the row, its state and the source row are
         // requested together, two dependent reads after the start
@@ -226,6 +235,7 @@ __device__ __forceinline__ void apply_short_item(const ApplyArgs &a, const Src &
     } else {
         const uint32_t first = a.seg[u], last = a.seg[u + 1];
         if (takes_hot_path(last - first, key, a.hot_bits)) return;   // summed by chunk items
+        if (last - first == 1 && src.done_already(a.perm[first])) return;
         sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
         opt.template load<NV4>(t, g, row, state_row, lane);
     }

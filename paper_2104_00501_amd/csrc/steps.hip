@@ -400,11 +400,18 @@ __device__ __forceinline__ void add_grad_relation(Row<NV4> &out, const Row<NV4> 
 
 // GB = row groups per triple (GB * 16 threads); a workgroup of kBlock threads takes kBlock / (GB * 16) triples.
 // IF = negative rows that a group has in flight.  The first sw.blocks workgroups prepare later steps instead.
+//
+// A negative whose entity nothing else accesses in this step (the plan flags it: a segment of one access) is
+// updated right here: its row is in registers, its gradient is coef * direction, nobody else reads the row, so the
+// AdaGrad step is exact under the step's snapshot semantics and the row is not read a second time by the update
+// kernel, which skips these accesses.  With uniform negatives over millions of entities that is nearly all of them.
 template <int NV4, int GB, int IF>
-__global__ void __launch_bounds__(kBlock) k_kge_grad(const float *E, const float *R, uint32_t n_ent, uint32_t n_rel,
+__global__ void __launch_bounds__(kBlock) k_kge_grad(float *E, const float *R, uint32_t n_ent, uint32_t n_rel,
                                                      int stride, const uint32_t *subj, const uint32_t *rel,
                                                      const uint32_t *obj, const uint32_t *negs, uint32_t B, int nh,
-                                                     int nt, float *coefs, float *stage, double *loss, SideWork sw)
+                                                     int nt, float *coefs, float *stage, double *loss,
+                                                     float *E_state, const uint32_t *entity_rank, OptAdagrad opt,
+                                                     SideWork sw)
 {
     extern __shared__ float part_all[];   // [triples per workgroup][GB][stride]: per-group weighted row sums
     __shared__ float lds[kBlock / 64];
@@ -427,7 +434,13 @@ __global__ void __launch_bounds__(kBlock) k_kge_grad(const float *E, const float
     const int lo = head ? 0 : nh, cnt = head ? nh : nt;
     const int mine = cnt > gi ? (cnt - gi + kHalf - 1) / kHalf : 0;
     const uint32_t *my_negs = negs + (size_t)e * nn + lo + gi;
-    const uint32_t early = lane < mine ? min(my_negs[(size_t)lane * kHalf], n_ent - 1) : 0u;
+    const uint32_t *my_rank = entity_rank + (size_t)2 * B + (size_t)e * nn + lo + gi;   // negatives follow s and o
+    uint32_t early = 0u, early_alone = 0u;
+    if (lane < mine) {
+        const uint32_t raw = my_negs[(size_t)lane * kHalf];
+        early = min(raw, n_ent - 1);
+        early_alone = (active && raw < n_ent && (my_rank[(size_t)lane * kHalf] & kSingleAccess)) ? 1u : 0u;
+    }
     const float *s_ptr = E + (size_t)min(subj[e], n_ent - 1) * stride;
     const float *o_ptr = E + (size_t)min(obj[e], n_ent - 1) * stride;
     const float *r_ptr = R + (size_t)min(rel[e], n_rel - 1) * stride;
@@ -442,13 +455,24 @@ __global__ void __launch_bounds__(kBlock) k_kge_grad(const float *E, const float
     zero_row(wsum);
     float loss_acc = 0.f;
     for (int j0 = 0; j0 < mine; j0 += IF) {
-        Row<NV4> x[IF];
+        Row<NV4> x[IF], gs[IF];
+        uint32_t key[IF];
+        bool alone[IF];
 #pragma unroll
         for (int k = 0; k < IF; ++k) {
             const int j = j0 + k;
+            alone[k] = false;
             if (j < mine) {
-                const uint32_t key = j < kGroup ? __shfl(early, j, kGroup) : min(my_negs[(size_t)j * kHalf], n_ent - 1);
-                load_row(x[k], E + (size_t)key * stride, lane);
+                if (j < kGroup) {
+                    key[k] = __shfl(early, j, kGroup);
+                    alone[k] = __shfl(early_alone, j, kGroup) != 0u;
+                } else {
+                    const uint32_t raw = my_negs[(size_t)j * kHalf];
+                    key[k] = min(raw, n_ent - 1);
+                    alone[k] = active && raw < n_ent && (my_rank[(size_t)j * kHalf] & kSingleAccess);
+                }
+                load_row(x[k], E + (size_t)key[k] * stride, lane);
+                if (alone[k]) load_row(gs[k], E_state + (size_t)key[k] * stride, lane);
             }
         }
 #pragma unroll
@@ -459,7 +483,14 @@ __global__ void __launch_bounds__(kBlock) k_kge_grad(const float *E, const float
                 const float g = sigmoidf(phi);           // label -1: d softplus(phi) / d phi
                 loss_acc += softplusf(phi);
                 if (active && lane == 0) coefs[(size_t)e * nn + lo + gi + j * kHalf] = g;
-                axpy_row(wsum, g, x[k]);
+                axpy_row(wsum, g, x[k]);                 // the row as it was at the start of the step
+                if (alone[k]) {                          // its whole update: gradient g * direction
+                    Row<NV4> delta;
+                    zero_row(delta);
+                    axpy_row(delta, g, dir);
+                    float *row = E + (size_t)key[k] * stride, *state_row = E_state + (size_t)key[k] * stride;
+                    opt.template finish<NV4>(x[k], gs[k], row, state_row, delta, lane);
+                }
             }
         }
     }
@@ -516,7 +547,8 @@ __global__ void __launch_bounds__(kBlock) k_kge_grad(const float *E, const float
 }
 
 template <int NV4>
-static void launch_kge_grad(nups_ctx *ctx, const nups_batch &b, const SideWork &sw, size_t side_lds)
+static void launch_kge_grad(nups_ctx *ctx, const nups_batch &b, const Plan &entity_plan, const SideWork &sw,
+                            size_t side_lds)
 {
     // Eight groups per triple, two negative rows in flight per group.  More groups per triple or more rows in
     // flight change nothing: the kernel runs at the speed at which memory delivers the negatives' rows.
@@ -525,10 +557,10 @@ static void launch_kge_grad(nups_ctx *ctx, const nups_batch &b, const SideWork &
     const Table &te = ctx->tab[0], &tr = ctx->tab[1];
     const size_t lds = std::max(sizeof(float) * kTriples * GB * (size_t)te.stride, side_lds);
     const uint32_t blocks = (uint32_t)((b.B + kTriples - 1) / kTriples);
-    hipLaunchKernelGGL((k_kge_grad<NV4, GB, IF>), dim3(sw.blocks + blocks), dim3(kBlock), lds, ctx->stream,
-                       (const float *)te.data, (const float *)tr.data, (uint32_t)te.num_keys, (uint32_t)tr.num_keys,
-                       te.stride, b.k0, b.k1, b.k2, b.negs, (uint32_t)b.B, (int)b.n_neg, (int)b.n_neg2, ctx->coef,
-                       ctx->stage, ctx->loss_cur, sw);
+    hipLaunchKernelGGL((k_kge_grad<NV4, GB, IF>), dim3(sw.blocks + blocks), dim3(kBlock), lds, ctx->stream, te.data,
+                       (const float *)tr.data, (uint32_t)te.num_keys, (uint32_t)tr.num_keys, te.stride, b.k0, b.k1,
+                       b.k2, b.negs, (uint32_t)b.B, (int)b.n_neg, (int)b.n_neg2, ctx->coef, ctx->stage, ctx->loss_cur,
+                       te.state, (const uint32_t *)entity_plan.a.rank, OptAdagrad{b.lr, b.eps}, sw);
 }
 
 nups_status plan_step_kge(nups_ctx *ctx, nups_prepared &p)
@@ -556,10 +588,10 @@ nups_status run_step_kge(nups_ctx *ctx, nups_prepared &p)
         const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsWide);
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
         switch (te.stride / 64) {
-        case 2: launch_kge_grad<2>(ctx, b, sw, side_lds); break;
-        case 4: launch_kge_grad<4>(ctx, b, sw, side_lds); break;
-        case 6: launch_kge_grad<6>(ctx, b, sw, side_lds); break;
-        case 8: launch_kge_grad<8>(ctx, b, sw, side_lds); break;
+        case 2: launch_kge_grad<2>(ctx, b, p.plan[0], sw, side_lds); break;
+        case 4: launch_kge_grad<4>(ctx, b, p.plan[0], sw, side_lds); break;
+        case 6: launch_kge_grad<6>(ctx, b, p.plan[0], sw, side_lds); break;
+        case 8: launch_kge_grad<8>(ctx, b, p.plan[0], sw, side_lds); break;
         default: return fail(NUPS_ERR_UNIMPLEMENTED, "KGE row_stride");
         }
         NUPS_HIP(hipGetLastError());
