@@ -224,10 +224,20 @@ class Kge:
     def accesses(self):
         return self.B * (2 + self.nh + self.nt), self.B
 
+    def note_structure(self, t, keys, counts):
+        """Entities that the gradient kernel updates itself: accessed once in step t, by a negative."""
+        sl = slice(t * self.B, (t + 1) * self.B)
+        once = keys[counts == 1]
+        self.alone = getattr(self, "alone", []) + [int(np.isin(once, np.concatenate([self.s[sl], self.o[sl]]),
+                                                               invert=True).sum())]
+
     def algorithmic_bytes(self, nu0, nu1):
         row, B, nn = 4 * self.d, self.B, self.nh + self.nt
-        return {"grad": (nu0 + nu1) * row + 4 * B * (3 + nn) + 4 * B * nn,
-                "apply0": nu0 * row * 4 + 8 * B * nn,              # value and state rows, read + written
+        alone = float(np.mean(self.alone)) if getattr(self, "alone", None) else 0.0
+        # value and state rows, read + written: by the gradient kernel for negatives that are their entity's only
+        # access, by the update kernel for every other distinct row
+        return {"grad": alone * row * 4 + (nu0 - alone + nu1) * row + 4 * B * (3 + nn) + 4 * B * nn,
+                "apply0": (nu0 - alone) * row * 4 + 8 * B * nn,
                 "apply1": nu1 * row * 4 + 4 * B,
                 "step": (nu0 + nu1) * row * 4 + 4 * B * (3 + nn)}
 
@@ -364,7 +374,10 @@ def main() -> int:
     nu0 = nu1 = 0
     for t in range(first_prof, first_prof + n_prof):
         run(t, 1)
-        nu0 += nb.nups_debug_structure(ctx, 0, uk, uc)      # distinct rows per step, for the algorithmic bytes
+        n0_t = nb.nups_debug_structure(ctx, 0, uk, uc)      # distinct rows per step, for the algorithmic bytes
+        if hasattr(w, "note_structure"):
+            w.note_structure(t, uk[:n0_t].cpu().numpy().view(np.uint32), uc[:n0_t].cpu().numpy().view(np.uint32))
+        nu0 += n0_t
         nu1 += nb.nups_debug_structure(ctx, 1, uk, uc)
     nu0 /= n_prof
     nu1 /= n_prof
