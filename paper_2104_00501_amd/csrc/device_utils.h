@@ -154,7 +154,8 @@ __device__ __forceinline__ void axpy_row(Row<NV4> &acc, float a, const Row<NV4> 
     for (int q = 0; q < NV4; ++q) axpy4(acc.v[q], a, x.v[q]);
 }
 
-__device__ __forceinline__ float sigmoidf(float z) { return 1.0f / (1.0f + __expf(-z)); }
+// hardware exponential and reciprocal: a unit in the last place each
+__device__ __forceinline__ float sigmoidf(float z) { return __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
 
 // log(1 + e^x), stable.  Only the reported loss uses it: the hardware logarithm of 1 + t is within 1e-7 absolute
 // of log1p(t), which is the rounding level of a loss term anyway.
