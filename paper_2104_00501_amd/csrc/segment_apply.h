@@ -349,7 +349,10 @@ __global__ void __launch_bounds__(kBlock) k_apply2(ApplyArgs a0, Src0 src0, Opt0
     }
 }
 
-constexpr uint32_t kApplyGrid = 2048;   // workgroups of the apply kernels (8 per compute unit)
+// Workgroups of the update kernels: 8 per compute unit; narrow rows (many short items, little state per
+// workgroup) do better with one item per workgroup, up to 32 per compute unit.
+template <int NV4>
+constexpr uint32_t kApplyGrid = NV4 <= 2 ? 8192 : 2048;
 
 static inline ApplyArgs make_apply_args(const Plan &pl, float *partial, float *table, float *state, int stride)
 {
@@ -370,7 +373,7 @@ static void launch_apply_nv(hipStream_t s, const Plan &pl, float *partial, float
     if (pl.a.n == 0) return;
     const ApplyArgs a = make_apply_args(pl, partial, table, state, stride);
     const size_t lds = sizeof(float) * (size_t)(kGroupsPerBlock - 1) * stride;
-    hipLaunchKernelGGL((k_apply<NV4, Src, Opt>), dim3(std::min(max_apply_items(pl), kApplyGrid)), dim3(kBlock), lds, s,
+    hipLaunchKernelGGL((k_apply<NV4, Src, Opt>), dim3(std::min(max_apply_items(pl), kApplyGrid<NV4>)), dim3(kBlock), lds, s,
                        a, src, opt);
 }
 
@@ -418,7 +421,7 @@ static void launch_apply2_nv(hipStream_t s, int stride, const U0 &u0, const U1 &
     const uint32_t items = max_apply_items(*u0.plan) + max_apply_items(*u1.plan);
     const size_t lds = std::max(sizeof(float) * (size_t)(kGroupsPerBlock - 1) * stride, side_lds);
     hipLaunchKernelGGL((k_apply2<NV4, decltype(u0.src), decltype(u0.opt), decltype(u1.src), decltype(u1.opt)>),
-                       dim3(sw.blocks + std::max(1u, std::min(items, kApplyGrid))), dim3(kBlock), lds, s, a0, u0.src,
+                       dim3(sw.blocks + std::max(1u, std::min(items, kApplyGrid<NV4>))), dim3(kBlock), lds, s, a0, u0.src,
                        u0.opt, a1, u1.src, u1.opt, sw);
 }
 
