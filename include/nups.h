@@ -234,11 +234,15 @@ nups_status nups_check(nups_ctx *ctx);
 
 /* ---- measurement ------------------------------------------------------------------ */
 
-/* Phases whose device time can be recorded with HIP events around their launches. */
+/* Phases whose device time can be recorded with HIP events around their launches: drawing a step's
+ * samples, building its aggregation structure, the gradient kernel, the update of both tables (APPLY0; APPLY1 is
+ * kept for callers that number the phases and stays empty), pull, push. */
 enum { NUPS_PHASE_SAMPLE = 0, NUPS_PHASE_PLAN = 1, NUPS_PHASE_GRAD = 2, NUPS_PHASE_APPLY0 = 3,
        NUPS_PHASE_APPLY1 = 4, NUPS_PHASE_PULL = 5, NUPS_PHASE_PUSH = 6, NUPS_PHASE_COUNT = 7 };
 
-/* Switches per-phase event timing on or off (off by default; it adds event records to the stream). */
+/* Switches per-phase event timing on or off (off by default; it adds event records to the stream).  While it
+ * is on, nups_prepare_step enqueues the step's preparatory phases at once as launches of their own, so that
+ * each phase is timed bare and the gradient and update launches carry nothing. */
 nups_status nups_profile(nups_ctx *ctx, int enable);
 
 /* Waits for the stream; returns accumulated milliseconds and launch count of a phase and resets them. */

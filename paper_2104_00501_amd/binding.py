@@ -198,7 +198,8 @@ def nups_step(ctx, batch, want_loss=False):
 
 
 def nups_prepare_step(ctx, batch):
-    """Enqueues the key-only preparatory work of a step on the side stream; returns the prepared step."""
+    """Hands a step to the library ahead of time: its key-only preparatory work then rides in the launches of the
+    steps that run before it; returns the prepared step."""
     p = C.c_void_p(None)
     _check(lib().nups_prepare_step(ctx, C.byref(batch), C.byref(p)))
     return p

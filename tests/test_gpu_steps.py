@@ -354,8 +354,8 @@ def test_kge_needs_state():
 
 @pytest.mark.parametrize("depth", [1, 3])
 def test_sgns_pipelined_steps_match_the_oracle(depth):
-    # steps t+1 .. t+depth are prepared (samples drawn, aggregation structure built on the side streams, by the
-    # library's background thread) before step t runs
+    # steps t+1 .. t+depth are prepared before step t runs: their samples are drawn and their aggregation
+    # structures built in spare workgroups of the launches of the steps before them
     V, d, B, K, window, steps, lr = 30_000, 300, 2048, 3, 5, 12, 0.002
     toks = wl.zipf_stream(V, 1.0, steps * B // (2 * window) + 2 * window + 8, 21)
     In, Out = wl.sgns_tables(V, d, 21)
