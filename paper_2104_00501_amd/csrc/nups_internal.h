@@ -72,6 +72,7 @@ struct PlanArgs {
     uint32_t bitmap_tiles; // ceil(words / kScanTile)
     uint32_t count_tiles;  // ceil(n / kScanTile)
     uint32_t direct_count;  // 1: the count scan sums the counts below its tile itself
+    uint32_t max_chunks;   // capacity of the chunk lists
     // build scratch, owned by the plan (the structures of several later steps are under construction at a time)
     uint8_t *bytemap;      // [32 * words] one byte per key, all zero between builds
     uint8_t *wordmap;      // [words]     one byte per bitmap word: some key of the word is marked; zero between builds

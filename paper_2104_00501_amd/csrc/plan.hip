@@ -72,6 +72,7 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
         pl.cap_tiles = tiles;
     }
     a.num_keys = (uint32_t)t.num_keys;
+    a.max_chunks = (uint32_t)max_chunks(pl.cap_n);
     a.words = (uint32_t)words;
     a.bitmap_tiles = (uint32_t)((words + kScanTile - 1) / kScanTile);
     a.error_flag = ctx->error_flag;

@@ -148,6 +148,7 @@ struct ApplyArgs {
     float *partial;        // [max_chunks][stride] partial sums of chunked segments
     int stride;
     uint32_t n;            // accesses of the plan
+    uint32_t max_chunks;   // capacity of the chunk lists and of `partial`
 };
 
 // Sums accesses first, first+step, ... < last of a segment into acc (four row loads in flight).
@@ -194,7 +195,7 @@ __device__ __forceinline__ ApplyShape apply_shape(const ApplyArgs &a)
 {
     ApplyShape sh;
     sh.nu = a.meta[kMetaNumUniq];
-    sh.chunk_items = a.meta[kMetaNumChunks];
+    sh.chunk_items = min(a.meta[kMetaNumChunks], a.max_chunks);
     sh.access_order = 2 * sh.nu > a.n;
     sh.short_items = ((sh.access_order ? a.n : sh.nu) + kGroupsPerBlock - 1) / kGroupsPerBlock;
     return sh;
@@ -358,7 +359,7 @@ static inline ApplyArgs make_apply_args(const Plan &pl, float *partial, float *t
 {
     const PlanArgs &p = pl.a;
     return ApplyArgs{table, state, p.src, p.hot_bits, p.uniq, p.seg, p.perm, p.slot, p.rank, p.meta, p.chunk_seg,
-                     p.chunk_base, p.chunk_done, partial, stride, p.n};
+                     p.chunk_base, p.chunk_done, partial, stride, p.n, p.max_chunks};
 }
 
 static inline uint32_t max_apply_items(const Plan &pl)

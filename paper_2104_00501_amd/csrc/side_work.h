@@ -267,9 +267,14 @@ __device__ __forceinline__ void slot_block(const PlanArgs &a, uint32_t vb, uint3
         const uint32_t i = vb * kRankTile + j * kBlock + threadIdx.x;
         if (i < a.n) {
             const uint32_t w = key[j] >> 5;
-            a.slot[i] = key[j] != kBadIndex
-                            ? tile_prefix[w / kScanTile] + below[j] + __popc(bits[j] & ((1u << (key[j] & 31)) - 1u))
-                            : kBadIndex;
+            uint32_t u = kBadIndex;
+            if (key[j] != kBadIndex) {
+                u = tile_prefix[w / kScanTile] + below[j] + __popc(bits[j] & ((1u << (key[j] & 31)) - 1u));
+                // at most n distinct keys.  More means that a key array changed after the step was prepared: such
+                // accesses are dropped and reported like keys outside the table, never used as an index.
+                if (u >= a.n) { u = kBadIndex; atomicOr(a.error_flag, 1u); }
+            }
+            a.slot[i] = u;
         }
     }
 }
@@ -373,7 +378,7 @@ __device__ __forceinline__ void counts_block(const PlanArgs &a, uint32_t vb, uin
             if (takes_hot_path(cnt[j], a.uniq[u0 + j], a.hot_bits)) {
                 const uint32_t nch = (cnt[j] + kChunk - 1) / kChunk;
                 const uint32_t base = atomicAdd(&a.meta[kMetaNumChunks], nch);
-                for (uint32_t ch = 0; ch < nch; ++ch) {
+                for (uint32_t ch = 0; ch < nch && base + ch < a.max_chunks; ++ch) {   // in range by construction
                     a.chunk_seg[base + ch] = u0 + j;
                     a.chunk_base[base + ch] = base;
                 }
@@ -396,6 +401,7 @@ __device__ __forceinline__ void scatter_block(const PlanArgs &a, uint32_t vb)
     if (u == kBadIndex) return;
     const uint32_t r = a.rank[i];
     const uint32_t first = a.seg[u], next = a.seg[u + 1];
+    if (first + r >= a.n) return;   // cannot happen with unchanged key arrays
     a.perm[first + r] = i;
     a.bytemap[source_key(a.src, i)] = 0;
     if (r == 0) {
