@@ -439,6 +439,10 @@ def main() -> int:
         "config": w.config(), "roofline": roofline, "phases_ms_per_step": phases, "cpu_baseline": cpu,
         "finite": finite,
     }
+    if not finite:
+        out["finite_note"] = ("tables overflow at this configuration's learning rate with summed minibatch gradients; "
+                              "the oracle overflows in the same way (DESIGN.md section 4); kernel timing does not depend "
+                              "on the values")
     nb.nups_destroy(ctx)
     print(json.dumps(out))
     return 0
