@@ -29,11 +29,12 @@ constexpr uint32_t kSingleAccess = 0x80000000u;
 constexpr uint32_t kLongSegment = 16; // segments with more accesses are summed by whole workgroups, in chunks
 constexpr uint32_t kChunk = 128;      // accesses of a long segment that one workgroup sums
 constexpr uint32_t kBadIndex = 0xFFFFFFFFu;
-constexpr int kRankItems = 2;                       // accesses per thread in the rank phase of the preparatory work
-constexpr int kRankTile = kBlock * kRankItems;
-constexpr int kHashBits = 10;
-constexpr uint32_t kHashSlots = 1u << kHashBits;    // open-addressing table in LDS, at most half full
-constexpr size_t kRankLdsBytes = 4 * kHashSlots * sizeof(uint32_t);
+constexpr int kSlotItems = 2;                       // accesses per thread in the slot phase of the preparatory work
+constexpr int kSlotTile = kBlock * kSlotItems;
+// Rank phase: accesses per thread, 2 or 4 (PlanArgs::rank_items).  More per workgroup means fewer global atomics
+// on hot keys (each workgroup combines its accesses to a key first) but four LDS words per slot of a hash table
+// with two slots per access: 16 KB or 32 KB that every workgroup of the carrying launch is charged for.
+constexpr size_t rank_lds_bytes(int items) { return (size_t)4 * 2 * kBlock * items * sizeof(uint32_t); }
 constexpr uint32_t kLdsTiles = 2048;                // tile counts that a workgroup scans in LDS by itself (64M keys)
 constexpr size_t kSlotLdsBytes = kLdsTiles * sizeof(uint32_t);
 constexpr uint32_t kMaxPool = 1024;                 // BOUNDED: largest pool (its order words are kept in LDS)
@@ -73,6 +74,7 @@ struct PlanArgs {
     uint32_t count_tiles;  // ceil(n / kScanTile)
     uint32_t direct_count;  // 1: the count scan sums the counts below its tile itself
     uint32_t max_chunks;   // capacity of the chunk lists
+    uint32_t rank_items;   // accesses per thread in the rank phase (2: narrow rows, 4: others)
     // build scratch, owned by the plan (the structures of several later steps are under construction at a time)
     uint8_t *bytemap;      // [32 * words] one byte per key, all zero between builds
     uint8_t *wordmap;      // [words]     one byte per bitmap word: some key of the word is marked; zero between builds

@@ -73,6 +73,7 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
     }
     a.num_keys = (uint32_t)t.num_keys;
     a.max_chunks = (uint32_t)max_chunks(pl.cap_n);
+    a.rank_items = t.stride <= 128 ? 2u : 4u;   // narrow-row carriers run at full occupancy: keep their LDS small
     a.words = (uint32_t)words;
     a.bitmap_tiles = (uint32_t)((words + kScanTile - 1) / kScanTile);
     a.error_flag = ctx->error_flag;
@@ -83,7 +84,7 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
 // Dynamic LDS that the launch carrying this phase must provide.
 size_t side_lds_bytes(const SideItem &it)
 {
-    if (it.phase == kSideRank) return kRankLdsBytes;
+    if (it.phase == kSideRank) return rank_lds_bytes((int)it.plan[0].rank_items);
     if (it.phase == kSideSlot) return kSlotLdsBytes;
     if (it.phase == kSideDraw && it.draw.scheme == NUPS_BOUNDED) return kDrawLdsBytes;
     return 0;
@@ -129,8 +130,10 @@ void build_phases(nups_prepared &p, const SampleArgs &draw, int mark_plan)
     it.draw = SampleArgs{};
     add(kSideTiles, max_btiles, 0);
     if (max_btiles > kLdsTiles) add(kSidePrefix, 1, 0);   // else every workgroup of the next phase scans the tile counts
-    add(kSideSlot, std::max(1u, (max_n + kRankTile - 1) / kRankTile), 0);
-    add(kSideRank, std::max(1u, (max_n + kRankTile - 1) / kRankTile), 0);
+    add(kSideSlot, std::max(1u, (max_n + kSlotTile - 1) / kSlotTile), 0);
+    const uint32_t rank_tile = kBlock * p.plan[0].a.rank_items;
+    for (int k = 1; k < p.n_plans; ++k) it.plan[k].rank_items = p.plan[0].a.rank_items;   // one tile size per launch
+    add(kSideRank, std::max(1u, (max_n + rank_tile - 1) / rank_tile), 0);
     if (need_count_tiles) add(kSideCountTiles, max_ctiles, 0);
     add(kSideCounts, max_ctiles, 0);
     add(kSideScatter, std::max(1u, (max_n + kBlock - 1) / kBlock), 0);

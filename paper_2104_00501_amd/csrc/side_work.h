@@ -26,8 +26,6 @@
 
 namespace nups {
 
-static_assert(kHashSlots >= 2 * kRankTile, "the LDS hash table must stay at most half full");
-
 // ---- drawing ---------------------------------------------------------------------------------------------------
 
 // One fresh draw from pi: bucket = floor((x0 + 2^32 x1) * V / 2^64); keep it if x2 < thresh[bucket].
@@ -236,21 +234,21 @@ __device__ __forceinline__ void prefix_block(const PlanArgs &a, uint32_t *lds)
     if (threadIdx.x == 0) a.meta[kMetaNumUniq] = nu;
 }
 
-// Accesses [vb * kRankTile, ...): the index of each access's key among the distinct keys = distinct keys below
+// Accesses [vb * kSlotTile, ...): the index of each access's key among the distinct keys = distinct keys below
 // its tile + below its word inside the tile + below its bit inside the word.  `scan`: LDS for kLdsTiles words.
 __device__ __forceinline__ void slot_block(const PlanArgs &a, uint32_t vb, uint32_t *scan, uint32_t *lds)
 {
-    if (vb * kRankTile >= a.n && vb != 0) return;
-    uint32_t key[kRankItems], below[kRankItems], bits[kRankItems];
+    if (vb * kSlotTile >= a.n && vb != 0) return;
+    uint32_t key[kSlotItems], below[kSlotItems], bits[kSlotItems];
     // the keys and their bitmap words are requested before the scan, which hides their latency
 #pragma unroll
-    for (int j = 0; j < kRankItems; ++j) {
-        const uint32_t i = vb * kRankTile + j * kBlock + threadIdx.x;
+    for (int j = 0; j < kSlotItems; ++j) {
+        const uint32_t i = vb * kSlotTile + j * kBlock + threadIdx.x;
         key[j] = i < a.n ? source_key(a.src, i) : kBadIndex;
         if (key[j] >= a.num_keys) key[j] = kBadIndex;     // outside the table: flagged when it was marked
     }
 #pragma unroll
-    for (int j = 0; j < kRankItems; ++j) {
+    for (int j = 0; j < kSlotItems; ++j) {
         const uint32_t w = key[j] >> 5;
         below[j] = key[j] != kBadIndex ? a.word_rank[w] : 0u;
         bits[j] = key[j] != kBadIndex ? a.bitmap[w] : 0u;
@@ -263,8 +261,8 @@ __device__ __forceinline__ void slot_block(const PlanArgs &a, uint32_t vb, uint3
         __syncthreads();
     }
 #pragma unroll
-    for (int j = 0; j < kRankItems; ++j) {
-        const uint32_t i = vb * kRankTile + j * kBlock + threadIdx.x;
+    for (int j = 0; j < kSlotItems; ++j) {
+        const uint32_t i = vb * kSlotTile + j * kBlock + threadIdx.x;
         if (i < a.n) {
             const uint32_t w = key[j] >> 5;
             uint32_t u = kBadIndex;
@@ -280,11 +278,15 @@ __device__ __forceinline__ void slot_block(const PlanArgs &a, uint32_t vb, uint3
 }
 
 // Accesses [vb * kRankTile, ...): the position of each inside its key's segment.  The workgroup's accesses are
-// first grouped by key in an LDS hash table (`hash`: 4 * kHashSlots words); one global atomic per distinct key and
-// workgroup reserves a run of positions, which the LDS counts subdivide.  Also emits the distinct keys (every
-// workgroup writes the keys it met; equal values where they meet).
+// first grouped by key in an LDS hash table (`hash`: 4 * kHashSlots words, open addressing, at most half full); one
+// global atomic per distinct key and workgroup reserves a run of positions, which the LDS counts subdivide.  Also
+// emits the distinct keys (every workgroup writes the keys it met; equal values where they meet).
+template <int kRankItems>
 __device__ __forceinline__ void rank_block(const PlanArgs &a, uint32_t vb, uint32_t *hash)
 {
+    constexpr uint32_t kRankTile = kBlock * kRankItems, kHashSlots = 2 * kRankTile;
+    constexpr int kHashBits = kRankItems == 4 ? 11 : kRankItems == 2 ? 10 : 9;
+    static_assert(kHashSlots == 1u << kHashBits, "accesses per thread: 1, 2 or 4");
     if (vb * kRankTile >= a.n) return;
     uint32_t *hkey = hash, *hcnt = hash + kHashSlots, *hbase = hash + 2 * kHashSlots, *hval = hash + 3 * kHashSlots;
     uint32_t slot_of[kRankItems], local[kRankItems], uidx[kRankItems], key[kRankItems];
@@ -431,7 +433,10 @@ __device__ __forceinline__ void side_item_unit(const SideItem &it, uint32_t vb)
     case kSideTiles: tiles_block(a, vb, side_lds); break;
     case kSidePrefix: prefix_block(a, side_lds); break;
     case kSideSlot: slot_block(a, vb, side_dyn, side_lds); break;
-    case kSideRank: rank_block(a, vb, side_dyn); break;
+    case kSideRank:
+        if (a.rank_items == 4) rank_block<4>(a, vb, side_dyn);
+        else rank_block<2>(a, vb, side_dyn);
+        break;
     case kSideCountTiles: count_tiles_block(a, vb, side_lds); break;
     case kSideCounts: counts_block(a, vb, side_lds); break;
     case kSideScatter: scatter_block(a, vb); break;
