@@ -372,19 +372,30 @@ __device__ __forceinline__ void counts_block(const PlanArgs &a, uint32_t vb, uin
     }
     uint32_t total;
     uint32_t run = before + block_exclusive_scan(c, lds, &total);
+    // chunks of this workgroup's long segments: one reservation per workgroup in the step's chunk list (a
+    // reservation per hot key would queue up on that one counter)
+    uint32_t nch[kScanItems], my_chunks = 0;
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        nch[j] = (u0 + j < nu && takes_hot_path(cnt[j], a.uniq[u0 + j], a.hot_bits)) ? (cnt[j] + kChunk - 1) / kChunk : 0u;
+        my_chunks += nch[j];
+    }
+    uint32_t block_chunks;
+    uint32_t chunk = block_exclusive_scan(my_chunks, lds, &block_chunks);
+    __shared__ uint32_t chunk_base_of_block;
+    if (threadIdx.x == 0) chunk_base_of_block = block_chunks ? atomicAdd(&a.meta[kMetaNumChunks], block_chunks) : 0u;
+    __syncthreads();
+    chunk += chunk_base_of_block;
 #pragma unroll
     for (int j = 0; j < kScanItems; ++j) {
         if (u0 + j < nu) {
             a.seg[u0 + j] = run;
             a.count[u0 + j] = cnt[j];
-            if (takes_hot_path(cnt[j], a.uniq[u0 + j], a.hot_bits)) {
-                const uint32_t nch = (cnt[j] + kChunk - 1) / kChunk;
-                const uint32_t base = atomicAdd(&a.meta[kMetaNumChunks], nch);
-                for (uint32_t ch = 0; ch < nch && base + ch < a.max_chunks; ++ch) {   // in range by construction
-                    a.chunk_seg[base + ch] = u0 + j;
-                    a.chunk_base[base + ch] = base;
-                }
+            for (uint32_t ch = 0; ch < nch[j] && chunk + ch < a.max_chunks; ++ch) {   // in range by construction
+                a.chunk_seg[chunk + ch] = u0 + j;
+                a.chunk_base[chunk + ch] = chunk;
             }
+            chunk += nch[j];
         }
         run += cnt[j];
         if (u0 + j + 1 == nu || (nu == 0 && u0 + j == 0)) {   // end marker seg[nu]
