@@ -215,16 +215,18 @@ def test_kge_one_step_matches_the_oracle(ne, nrel, d, B, nh, nt):
 
 
 def _run_pipelined(ctx, batches, depth):
-    """prepare steps t+1 .. t+depth, then run step t (depth 0: plain nups_step)"""
+    """prepare steps t+1 .. t+depth, then run step t (depth 0: plain nups_step); returns the last step's loss"""
+    loss = None
     if depth == 0:
-        for b in batches:
-            nb.nups_step(ctx, b)
-        return
+        for t, b in enumerate(batches):
+            loss = nb.nups_step(ctx, b, want_loss=(t == len(batches) - 1))
+        return loss
     queue = [nb.nups_prepare_step(ctx, b) for b in batches[:depth]]
     for t in range(len(batches)):
         if t + depth < len(batches):
             queue.append(nb.nups_prepare_step(ctx, batches[t + depth]))
-        nb.nups_step_prepared(ctx, queue.pop(0))
+        loss = nb.nups_step_prepared(ctx, queue.pop(0), want_loss=(t == len(batches) - 1))
+    return loss
 
 
 @pytest.mark.parametrize("depth", [0, 3])
@@ -239,12 +241,13 @@ def test_mf_pipelined_steps_match_the_oracle(depth):
     kr, kc, kv = dev_u32(rows), dev_u32(cols), dev(vals)
     batches = [nb.make_batch(nb.NUPS_TASK_MF, B, kr.data_ptr() + 4 * t * B, kc.data_ptr() + 4 * t * B,
                              val=kv.data_ptr() + 4 * t * B, lr=0.005, l2=0.01) for t in range(steps)]
-    _run_pipelined(ctx, batches, depth)
+    loss = _run_pipelined(ctx, batches, depth)
     nb.nups_check(ctx)
     rw, rh = W.copy(), H.copy()
     for t in range(steps):
         sl = slice(t * B, (t + 1) * B)
-        _, sw, sh = orc.step_mf(rw, rh, d, rows[sl], cols[sl], vals[sl], 0.005, 0.01)
+        rloss, sw, sh = orc.step_mf(rw, rh, d, rows[sl], cols[sl], vals[sl], 0.005, 0.01)
+    assert abs(loss - rloss) <= 1e-4 * abs(rloss)       # the last step's loss: its accumulator was reset long before
     _assert_structure(ctx, 0, B, sw)
     _assert_structure(ctx, 1, B, sh)
     _assert_close(tw.cpu().numpy(), rw, list(range(d)), 1e-4, "row factors after %d steps" % steps, W)
@@ -273,13 +276,14 @@ def test_kge_pipelined_steps_match_the_oracle(depth):
     batches = [nb.make_batch(nb.NUPS_TASK_KGE, B, ks.data_ptr() + 4 * t * B, kr.data_ptr() + 4 * t * B,
                              k2=ko.data_ptr() + 4 * t * B, n_neg=nh, n_neg2=nt, lr=0.05, eps=1e-10, dist=dist,
                              sample_step=t) for t in range(steps)]
-    _run_pipelined(ctx, batches, depth)
+    loss = _run_pipelined(ctx, batches, depth)
     nb.nups_check(ctx)
     rE, rGE, rR, rGR = E.copy(), GE.copy(), R.copy(), GR.copy()
     for t in range(steps):
         sl = slice(t * B, (t + 1) * B)
         negs = orc.sample_conform(None, ne, 9, 0, t, B * (nh + nt))
-        _, se, sr = orc.step_kge(rE, rGE, rR, rGR, d, s[sl], r[sl], o[sl], negs, nh, nt, 0.05, 1e-10)
+        rloss, se, sr = orc.step_kge(rE, rGE, rR, rGR, d, s[sl], r[sl], o[sl], negs, nh, nt, 0.05, 1e-10)
+    assert abs(loss - rloss) <= 1e-4 * abs(rloss)
     _assert_structure(ctx, 0, B * (2 + nh + nt), se)
     _assert_structure(ctx, 1, B, sr)
     _assert_close(te.cpu().numpy(), rE, cc, 1e-4, "entities after %d steps" % steps, E)
