@@ -324,6 +324,8 @@ def main() -> int:
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         return 2
+    from paper_2104_00501_amd.build import ensure_built
+    ensure_built()          # loads the in-tree library; compiles it only if it is not there
 
     import torch
 

@@ -40,6 +40,11 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Builds the library only if there is none (tests, smoke and bench load what is there)."""
+    return LIB if os.path.exists(LIB) else build(verbose=False)
+
+
 if __name__ == "__main__":
     build()
     print("built", LIB)

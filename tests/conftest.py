@@ -12,6 +12,11 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    from paper_2104_00501_amd.build import ensure_built
+    ensure_built()          # the tests load the in-tree library; it is compiled here only if it is not there
+
+
 def pytest_collection_modifyitems(config, items):
     try:
         import torch
