@@ -141,9 +141,8 @@ struct OptAdagrad {      // G <- G + delta^2 ; theta <- theta - lr * delta / (sq
 struct ApplyArgs {
     float *table;
     float *state;
-    KeySource keys;        // the accesses' keys (access i -> key), as given to the plan
     const uint32_t *hot_bits; // the table's declared hot-key set or null (see takes_hot_path)
-    const uint32_t *uniq, *seg, *perm, *slot, *rank, *meta, *chunk_seg, *chunk_base;
+    const uint32_t *uniq, *seg, *perm, *meta, *chunk_seg, *chunk_base;
     uint32_t *chunk_done;
     float *partial;        // [max_chunks][stride] partial sums of chunked segments
     int stride;
@@ -179,16 +178,12 @@ __device__ __forceinline__ void sum_segment(Row<NV4> &acc, const Src &src, const
 }
 
 // Work items of a plan: one per chunk (kChunk accesses) of a long segment, and the short segments (at most
-// kLongSegment accesses, or any length if the key is not in a declared hot set), one 16-lane group each.
-// The short segments are walked in one of two orders, chosen from the plan's statistics:
-//  - few repeats (distinct keys > accesses / 2): in access order.  The access that received position 0 of
-//    its segment stands for the segment, its key comes straight from the key array, so the row (and state)
-//    is requested after one dependent read instead of four, and neighbouring accesses (same triple, same
-//    center word) find their source rows in cache.
-//  - many repeats: in key order, one item per 16 distinct keys.
+// kLongSegment accesses, or any length if the key is not in a declared hot set), one 16-lane group each, in key
+// order: rows are then visited in ascending address order and every group of an item has a segment.  (Walking
+// the accesses instead, with the key straight from the key array, saves two dependent reads per row but leaves
+// the groups of repeated accesses idle and visits rows in batch order; it measured slower on every workload.)
 struct ApplyShape {
     uint32_t nu, chunk_items, short_items;
-    bool access_order;
 };
 
 __device__ __forceinline__ ApplyShape apply_shape(const ApplyArgs &a)
@@ -196,8 +191,7 @@ __device__ __forceinline__ ApplyShape apply_shape(const ApplyArgs &a)
     ApplyShape sh;
     sh.nu = a.meta[kMetaNumUniq];
     sh.chunk_items = min(a.meta[kMetaNumChunks], a.max_chunks);
-    sh.access_order = 2 * sh.nu > a.n;
-    sh.short_items = ((sh.access_order ? a.n : sh.nu) + kGroupsPerBlock - 1) / kGroupsPerBlock;
+    sh.short_items = (sh.nu + kGroupsPerBlock - 1) / kGroupsPerBlock;
     return sh;
 }
 
@@ -206,40 +200,18 @@ template <int NV4, class Src, class Opt>
 __device__ __forceinline__ void apply_short_item(const ApplyArgs &a, const Src &src, const Opt &opt,
                                                  const ApplyShape &sh, uint32_t item, int lane, int group)
 {
-    const uint32_t w = item * kGroupsPerBlock + group;
-    uint32_t u = kBadIndex, key = 0;
-    bool single = false;
-    if (sh.access_order) {
-        if (w < a.n) {
-            key = source_key(a.keys, w);
-            const uint32_t r = a.rank[w], s = a.slot[w];   // s: kBadIndex for a key outside the table
-            if ((r & ~kSingleAccess) == 0) u = s;
-            single = (r & kSingleAccess) != 0;
-        }
-    } else if (w < sh.nu) {
-        u = w;
-        key = a.uniq[w];
-    }
-    if (u == kBadIndex) return;
+    const uint32_t u = item * kGroupsPerBlock + group;
+    if (u >= sh.nu) return;
+    const uint32_t key = a.uniq[u];
+    const uint32_t first = a.seg[u], last = a.seg[u + 1];
+    if (takes_hot_path(last - first, key, a.hot_bits)) return;   // summed by chunk items
+    if (last - first == 1 && src.done_already(a.perm[first])) return;
     const size_t off = (size_t)key * a.stride;
     float *row = a.table + off, *state_row = Opt::kHasState ? a.state + off : nullptr;
     Row<NV4> acc, t, g;
     zero_row(acc);
-    if (single && src.done_already(w)) return;
-    if (single) {
-        // the segment is this access alone (never a chunked one): the row, its state and the source row are
-        // requested together, two dependent reads after the start
-        opt.template load<NV4>(t, g, row, state_row, lane);
-        Row<NV4> r;
-        load_row(r, src.row(w, a.stride), lane);
-        axpy_row(acc, src.coef(w), r);
-    } else {
-        const uint32_t first = a.seg[u], last = a.seg[u + 1];
-        if (takes_hot_path(last - first, key, a.hot_bits)) return;   // summed by chunk items
-        if (last - first == 1 && src.done_already(a.perm[first])) return;
-        sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
-        opt.template load<NV4>(t, g, row, state_row, lane);
-    }
+    sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
+    opt.template load<NV4>(t, g, row, state_row, lane);
     opt.template finish<NV4>(t, g, row, state_row, acc, lane);
 }
 
@@ -358,8 +330,8 @@ constexpr uint32_t kApplyGrid = NV4 <= 2 ? 8192 : 2048;
 static inline ApplyArgs make_apply_args(const Plan &pl, float *partial, float *table, float *state, int stride)
 {
     const PlanArgs &p = pl.a;
-    return ApplyArgs{table, state, p.src, p.hot_bits, p.uniq, p.seg, p.perm, p.slot, p.rank, p.meta, p.chunk_seg,
-                     p.chunk_base, p.chunk_done, partial, stride, p.n, p.max_chunks};
+    return ApplyArgs{table, state, p.hot_bits, p.uniq, p.seg, p.perm, p.meta, p.chunk_seg, p.chunk_base, p.chunk_done,
+                     partial, stride, p.n, p.max_chunks};
 }
 
 static inline uint32_t max_apply_items(const Plan &pl)
