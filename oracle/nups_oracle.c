@@ -415,6 +415,43 @@ static void apply_sgd(float *table, int32_t stride, int32_t dim, const uint32_t 
 }
 
 /*
+ * Norm clipping of the updates of hot keys (Section 5.1, implementation paragraph: for the replicated
+ * parameters of the word-vector and factorisation tasks, an update whose norm exceeds the average norm
+ * by more than a factor is clipped; the construction is that of Pascanu, Mikolov, Bengio 2013: an update
+ * that is too long keeps its direction and is shortened to the bound).
+ *
+ * Reading used here, the paper gives no more than that sentence:
+ *  - "update" = the summed gradient of one key in one step, `acc` row u; its norm is Euclidean, over `dim`;
+ *  - "replicated parameters" = the keys with hot[key] != 0 (one flag per key of the table);
+ *  - "average norm" = the mean of the norms, before clipping, of all hot-key updates of this table in the
+ *    steps before this one: stats[0] = their sum, stats[1] = their number.  A step never looks at its own
+ *    norms, so its result does not depend on the order of its keys; while no norm has been seen nothing is clipped;
+ *  - a hot key's update of norm n > factor * mean is multiplied by factor * mean / n.
+ * After the step, stats include this step's norms (as they were before clipping).
+ * hot == NULL, stats == NULL or factor <= 0: nothing happens.
+ */
+static void clip_hot_updates(double *acc, const uint32_t *uniq, int64_t nu, int32_t dim, const uint8_t *hot,
+                             double factor, double *stats)
+{
+    if (!hot || !stats || !(factor > 0.0)) return;
+    const double seen = stats[1];
+    const double bound = seen > 0.0 ? factor * (stats[0] / seen) : INFINITY;
+    for (int64_t u = 0; u < nu; ++u) {
+        if (!hot[uniq[u]]) continue;
+        double *a = acc + u * dim;
+        double sq = 0.0;
+        for (int32_t m = 0; m < dim; ++m) sq += a[m] * a[m];
+        const double norm = sqrt(sq);
+        stats[0] += norm;
+        stats[1] += 1.0;
+        if (norm > bound) {
+            const double shrink = bound / norm;
+            for (int32_t m = 0; m < dim; ++m) a[m] *= shrink;
+        }
+    }
+}
+
+/*
  * AdaGrad (Duchi, Hazan, Singer 2011) on the summed gradient of the step, elementwise:
  * G <- fl32(G + delta^2); theta <- fl32(theta - lr * delta / (sqrt(G) + eps)) with the new G.
  * Rows that the step does not touch keep value and state (sparse AdaGrad).
@@ -457,11 +494,13 @@ void nor_apply_adagrad_rows(float *table, float *state, int32_t stride, int32_t 
  * Outputs (any may be NULL): loss summed over the batch; for each table the distinct
  * keys ascending with their access counts (buffers of B and B*(K+1) entries).
  */
-int nor_step_sgns(float *In, float *Out, int64_t V_in, int64_t V_out, int32_t stride, int32_t dim,
-                  const uint32_t *center, const uint32_t *context, const uint32_t *negs,
-                  int64_t B, int32_t K, float lr, double *loss_out,
-                  uint32_t *uniq_in, uint32_t *count_in, int64_t *n_uniq_in,
-                  uint32_t *uniq_out, uint32_t *count_out, int64_t *n_uniq_out)
+static int step_sgns(float *In, float *Out, int64_t V_in, int64_t V_out, int32_t stride, int32_t dim,
+                     const uint32_t *center, const uint32_t *context, const uint32_t *negs,
+                     int64_t B, int32_t K, float lr, double *loss_out,
+                     uint32_t *uniq_in, uint32_t *count_in, int64_t *n_uniq_in,
+                     uint32_t *uniq_out, uint32_t *count_out, int64_t *n_uniq_out,
+                     const uint8_t *hot_in, const uint8_t *hot_out, double clip_factor,
+                     double *clip_stats_in, double *clip_stats_out)
 {
     if (!In || !Out || V_in <= 0 || V_out <= 0 || stride <= 0 || dim <= 0 || dim > stride || B < 0 || K < 0
         || (B > 0 && (!center || !context)) || (B > 0 && K > 0 && !negs)) return NOR_ERR_ARG;
@@ -506,6 +545,8 @@ int nor_step_sgns(float *In, float *Out, int64_t V_in, int64_t V_out, int32_t st
             }
         }
     }
+    clip_hot_updates(acc_in, ui, nui, dim, hot_in, clip_factor, clip_stats_in);
+    clip_hot_updates(acc_out, uo, nuo, dim, hot_out, clip_factor, clip_stats_out);
     apply_sgd(In, stride, dim, ui, nui, acc_in, lr);
     apply_sgd(Out, stride, dim, uo, nuo, acc_out, lr);
     if (loss_out) *loss_out = loss;
@@ -519,6 +560,28 @@ int nor_step_sgns(float *In, float *Out, int64_t V_in, int64_t V_out, int32_t st
 done:
     free(okeys); free(ui); free(ci); free(uo); free(co); free(acc_in); free(acc_out);
     return rc;
+}
+
+int nor_step_sgns(float *In, float *Out, int64_t V_in, int64_t V_out, int32_t stride, int32_t dim,
+                  const uint32_t *center, const uint32_t *context, const uint32_t *negs,
+                  int64_t B, int32_t K, float lr, double *loss_out,
+                  uint32_t *uniq_in, uint32_t *count_in, int64_t *n_uniq_in,
+                  uint32_t *uniq_out, uint32_t *count_out, int64_t *n_uniq_out)
+{
+    return step_sgns(In, Out, V_in, V_out, stride, dim, center, context, negs, B, K, lr, loss_out, uniq_in, count_in,
+                     n_uniq_in, uniq_out, count_out, n_uniq_out, NULL, NULL, 0.0, NULL, NULL);
+}
+
+/* The same step with the updates of hot keys clipped (see clip_hot_updates): hot_* are one byte per key of the
+ * table (NULL: no hot keys), clip_stats_* the table's {sum of norms, number of norms} so far, updated in place. */
+int nor_step_sgns_clipped(float *In, float *Out, int64_t V_in, int64_t V_out, int32_t stride, int32_t dim,
+                          const uint32_t *center, const uint32_t *context, const uint32_t *negs,
+                          int64_t B, int32_t K, float lr, double *loss_out,
+                          const uint8_t *hot_in, const uint8_t *hot_out, double clip_factor,
+                          double *clip_stats_in, double *clip_stats_out)
+{
+    return step_sgns(In, Out, V_in, V_out, stride, dim, center, context, negs, B, K, lr, loss_out, NULL, NULL, NULL,
+                     NULL, NULL, NULL, hot_in, hot_out, clip_factor, clip_stats_in, clip_stats_out);
 }
 
 /* Loss of a batch at the current table values, nothing updated (for finite differences). */
@@ -550,11 +613,13 @@ double nor_loss_sgns(const float *In, const float *Out, int32_t stride, int32_t 
  *   dloss/dW_i = -2 err H_j + 2 l2 W_i,   dloss/dH_j = -2 err W_i + 2 l2 H_j.
  * Duplicate cells are kept.  Gradients are summed over the batch.
  */
-int nor_step_mf(float *W, float *H, int64_t n_rows, int64_t n_cols, int32_t stride, int32_t dim,
-                const uint32_t *row, const uint32_t *col, const float *val, int64_t B,
-                float lr, float l2, double *loss_out,
-                uint32_t *uniq_w, uint32_t *count_w, int64_t *n_uniq_w,
-                uint32_t *uniq_h, uint32_t *count_h, int64_t *n_uniq_h)
+static int step_mf(float *W, float *H, int64_t n_rows, int64_t n_cols, int32_t stride, int32_t dim,
+                   const uint32_t *row, const uint32_t *col, const float *val, int64_t B,
+                   float lr, float l2, double *loss_out,
+                   uint32_t *uniq_w, uint32_t *count_w, int64_t *n_uniq_w,
+                   uint32_t *uniq_h, uint32_t *count_h, int64_t *n_uniq_h,
+                   const uint8_t *hot_w, const uint8_t *hot_h, double clip_factor,
+                   double *clip_stats_w, double *clip_stats_h)
 {
     if (!W || !H || n_rows <= 0 || n_cols <= 0 || stride <= 0 || dim <= 0 || dim > stride || B < 0
         || (B > 0 && (!row || !col || !val))) return NOR_ERR_ARG;
@@ -591,6 +656,8 @@ int nor_step_mf(float *W, float *H, int64_t n_rows, int64_t n_cols, int32_t stri
             ah[m] += -2.0 * err * (double)w[m] + 2.0 * (double)l2 * (double)h[m];
         }
     }
+    clip_hot_updates(acc_w, uw, nuw, dim, hot_w, clip_factor, clip_stats_w);
+    clip_hot_updates(acc_h, uh, nuh, dim, hot_h, clip_factor, clip_stats_h);
     apply_sgd(W, stride, dim, uw, nuw, acc_w, lr);
     apply_sgd(H, stride, dim, uh, nuh, acc_h, lr);
     if (loss_out) *loss_out = loss;
@@ -604,6 +671,27 @@ int nor_step_mf(float *W, float *H, int64_t n_rows, int64_t n_cols, int32_t stri
 done:
     free(uw); free(cw); free(uh); free(ch); free(acc_w); free(acc_h);
     return rc;
+}
+
+int nor_step_mf(float *W, float *H, int64_t n_rows, int64_t n_cols, int32_t stride, int32_t dim,
+                const uint32_t *row, const uint32_t *col, const float *val, int64_t B,
+                float lr, float l2, double *loss_out,
+                uint32_t *uniq_w, uint32_t *count_w, int64_t *n_uniq_w,
+                uint32_t *uniq_h, uint32_t *count_h, int64_t *n_uniq_h)
+{
+    return step_mf(W, H, n_rows, n_cols, stride, dim, row, col, val, B, lr, l2, loss_out, uniq_w, count_w, n_uniq_w,
+                   uniq_h, count_h, n_uniq_h, NULL, NULL, 0.0, NULL, NULL);
+}
+
+/* The same step with the updates of hot rows and columns clipped (see clip_hot_updates). */
+int nor_step_mf_clipped(float *W, float *H, int64_t n_rows, int64_t n_cols, int32_t stride, int32_t dim,
+                        const uint32_t *row, const uint32_t *col, const float *val, int64_t B,
+                        float lr, float l2, double *loss_out,
+                        const uint8_t *hot_w, const uint8_t *hot_h, double clip_factor,
+                        double *clip_stats_w, double *clip_stats_h)
+{
+    return step_mf(W, H, n_rows, n_cols, stride, dim, row, col, val, B, lr, l2, loss_out, NULL, NULL, NULL, NULL, NULL,
+                   NULL, hot_w, hot_h, clip_factor, clip_stats_w, clip_stats_h);
 }
 
 double nor_loss_mf(const float *W, const float *H, int32_t stride, int32_t dim,

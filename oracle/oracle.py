@@ -186,6 +186,33 @@ def step_sgns(In, Out, dim, center, context, negs, K, lr):
         Structure(uo[:no.value].copy(), co[:no.value].copy())
 
 
+def _hot_flags(num_keys, hot_keys):
+    """One byte per key: 1 for the keys of the hot set."""
+    flags = np.zeros(num_keys, dtype=np.uint8)
+    if hot_keys is not None and len(hot_keys):
+        flags[np.asarray(hot_keys, dtype=np.int64)] = 1
+    return flags
+
+
+def step_sgns_clipped(In, Out, dim, center, context, negs, K, lr, hot_in, hot_out, factor, stats_in, stats_out):
+    """step_sgns with the updates of the hot keys clipped at `factor` times their average norm so far.
+    hot_*: key lists; stats_*: float64 arrays {sum of norms, number of norms}, updated in place.  Returns the loss."""
+    In, Out = _table(In), _table(Out)
+    c, o, ng = _u32(center), _u32(context), _u32(negs)
+    B = len(c)
+    assert len(o) == B and len(ng) == B * K and In.shape[1] == Out.shape[1]
+    assert stats_in.dtype == np.float64 and stats_out.dtype == np.float64 and len(stats_in) == len(stats_out) == 2
+    hi, ho = _hot_flags(In.shape[0], hot_in), _hot_flags(Out.shape[0], hot_out)
+    loss = C.c_double(0.0)
+    _check(lib().nor_step_sgns_clipped(_p(In, C.c_float), _p(Out, C.c_float), C.c_int64(In.shape[0]),
+                                       C.c_int64(Out.shape[0]), C.c_int32(In.shape[1]), C.c_int32(dim),
+                                       _p(c, C.c_uint32), _p(o, C.c_uint32), _p(ng, C.c_uint32), C.c_int64(B),
+                                       C.c_int32(K), C.c_float(lr), C.byref(loss), _p(hi, C.c_uint8),
+                                       _p(ho, C.c_uint8), C.c_double(factor), _p(stats_in, C.c_double),
+                                       _p(stats_out, C.c_double)), "step_sgns_clipped")
+    return loss.value
+
+
 def loss_sgns(In, Out, dim, center, context, negs, K):
     In, Out = _table(In), _table(Out)
     c, o, ng = _u32(center), _u32(context), _u32(negs)
@@ -209,6 +236,23 @@ def step_mf(W, H, dim, row, col, val, lr, l2):
                              _p(uh, C.c_uint32), _p(ch, C.c_uint32), C.byref(nh)), "step_mf")
     return loss.value, Structure(uw[:nw.value].copy(), cw[:nw.value].copy()), \
         Structure(uh[:nh.value].copy(), ch[:nh.value].copy())
+
+
+def step_mf_clipped(W, H, dim, row, col, val, lr, l2, hot_w, hot_h, factor, stats_w, stats_h):
+    """step_mf with the updates of the hot rows / columns clipped (see step_sgns_clipped).  Returns the loss."""
+    W, H = _table(W), _table(H)
+    r, c = _u32(row), _u32(col)
+    v = np.ascontiguousarray(val, dtype=np.float32)
+    assert stats_w.dtype == np.float64 and stats_h.dtype == np.float64 and len(stats_w) == len(stats_h) == 2
+    hw, hh = _hot_flags(W.shape[0], hot_w), _hot_flags(H.shape[0], hot_h)
+    loss = C.c_double(0.0)
+    _check(lib().nor_step_mf_clipped(_p(W, C.c_float), _p(H, C.c_float), C.c_int64(W.shape[0]),
+                                     C.c_int64(H.shape[0]), C.c_int32(W.shape[1]), C.c_int32(dim),
+                                     _p(r, C.c_uint32), _p(c, C.c_uint32), _p(v, C.c_float), C.c_int64(len(r)),
+                                     C.c_float(lr), C.c_float(l2), C.byref(loss), _p(hw, C.c_uint8),
+                                     _p(hh, C.c_uint8), C.c_double(factor), _p(stats_w, C.c_double),
+                                     _p(stats_h, C.c_double)), "step_mf_clipped")
+    return loss.value
 
 
 def loss_mf(W, H, dim, row, col, val, l2):
