@@ -7,11 +7,14 @@ batches of 16,384 (center, context) pairs cut in stream order from an i.i.d. Zip
 stream with window 5, learning rate 0.025 linearly decayed.  One step = draw negatives, build the
 per-key aggregation structure, score + gradient, aggregate and push, all inside the timed region;
 inputs (example arrays, tables, alias table) are resident in HBM before timing starts.  Steps are
-software-pipelined: the key-only half of step t+1 is enqueued before step t runs.
+software-pipelined: the key-only halves of steps t+1 .. t+3 are enqueued before step t runs (--depth).
 
 Other workloads (--workload): the small skip-gram configuration, matrix factorisation
 (10M x 1M, rank 100, 65,536 cells per step) and ComplEx (4.6M entities, d = 500, 1,024 triples
 with 50+50 uniform negatives per step, AdaGrad).
+
+--clip F runs an SGD workload with the updates of its hot keys clipped at F times their mean norm
+(Section 5.1 of the paper uses 2); the default is the plain summed-gradient step.
 
 Prints one JSON line: positive examples/s, the roofline figure of the dominant kernel and the
 CPU oracle timed on a bounded prefix of the same workload.
@@ -48,6 +51,7 @@ class Sgns:
         self.window, self.s, self.lr0, self.stream_tokens, self.seed = window, s, lr0, stream_tokens, seed
         self.scheme = scheme or ("BOUNDED" if U > 1 else "CONFORM")
         self.hot, self.decay = hot, decay       # hot: None = decided per step, else the top-`hot` keys are declared
+        self.clip = 0.0                         # factor of the norm clipping of hot-key updates, 0 = off
         self.unit = "pairs"
 
     def setup(self, nb, wl, total_steps):
@@ -70,6 +74,8 @@ class Sgns:
         if self.hot is not None:                 # keys are frequency ranks: the top-k keys are 0..k-1
             for table in (0, 1):
                 nb.nups_set_hot_keys(self.ctx, table, np.arange(self.hot, dtype=np.uint32))
+        if self.clip > 0.0:
+            nb.nups_set_update_clipping(self.ctx, self.clip)
         epoch_steps = max(1, wl.num_window_pairs(self.stream_tokens, window) // B)
         self.lrs = [float(wl.linear_lr(self.lr0, t, epoch_steps)) if self.decay else self.lr0
                     for t in range(total_steps)]
@@ -111,14 +117,22 @@ class Sgns:
             ng = orc.sample_nonconform(o, o, K, K, B, self.seed, 0, t, B * K)
         else:
             ng = orc.sample_conform(self.alias, self.V, self.seed, 0, t, B * K)
-        orc.step_sgns(self.In, self.Out, self.d, c, o, ng, K, self.lrs[t])
+        if self.clip > 0.0:
+            if not hasattr(self, "clip_stats"):
+                self.clip_stats = np.zeros(2), np.zeros(2)
+            hot = np.arange(self.hot, dtype=np.uint32)
+            orc.step_sgns_clipped(self.In, self.Out, self.d, c, o, ng, K, self.lrs[t], hot, hot, self.clip,
+                                  *self.clip_stats)
+        else:
+            orc.step_sgns(self.In, self.Out, self.d, c, o, ng, K, self.lrs[t])
 
     def config(self):
         return {"workload": self.name, "task": "SGNS", "num_keys": self.V, "dim": self.d, "row_stride": self.stride,
                 "negatives": self.K, "hot_keys": "per step" if self.hot is None else self.hot,
                 "scheme": {"BOUNDED": "BOUNDED U=%d G=%d" % (self.U, self.G), "LONGTERM": "LONG-TERM P=1e6 R=16"}.get(
                     self.scheme, self.scheme),
-                "batch": self.B, "window": self.window, "zipf_s": self.s, "lr0": self.lr0, "pairs": "stream order"}
+                "batch": self.B, "window": self.window, "zipf_s": self.s, "lr0": self.lr0, "pairs": "stream order",
+                "update_clipping": self.clip or "off"}
 
 
 class Mf:
@@ -127,6 +141,7 @@ class Mf:
     def __init__(self, name, n_rows, n_cols, d, B, s, lr, l2, seed):
         self.name, self.n_rows, self.n_cols, self.d, self.B, self.s = name, n_rows, n_cols, d, B, s
         self.lr, self.l2, self.seed = lr, l2, seed
+        self.hot, self.clip = None, 0.0         # declared hot rows / columns (top-k by frequency rank); clipping factor
         self.unit = "cells"
 
     def setup(self, nb, wl, total_steps):
@@ -145,6 +160,11 @@ class Mf:
         self.kr, self.kcol = dev_keys(self.rows), dev_keys(self.cols)
         self.kv = torch.from_numpy(self.vals).cuda()
         self.ctx = nb.nups_init(self.tables, [self.d, self.d])
+        if self.hot is not None:                 # keys are frequency ranks: the top-k keys are 0..k-1
+            for table in (0, 1):
+                nb.nups_set_hot_keys(self.ctx, table, np.arange(self.hot, dtype=np.uint32))
+        if self.clip > 0.0:
+            nb.nups_set_update_clipping(self.ctx, self.clip)
         self.nb = nb
         return total_steps
 
@@ -170,11 +190,20 @@ class Mf:
             self.host = [x.cpu().numpy() for x in self.tables_initial]
         B = self.B
         sl = slice(t * B, (t + 1) * B)
-        orc.step_mf(self.host[0], self.host[1], self.d, self.rows[sl], self.cols[sl], self.vals[sl], self.lr, self.l2)
+        if self.clip > 0.0:
+            if not hasattr(self, "clip_stats"):
+                self.clip_stats = np.zeros(2), np.zeros(2)
+            hot = np.arange(self.hot, dtype=np.uint32)
+            orc.step_mf_clipped(self.host[0], self.host[1], self.d, self.rows[sl], self.cols[sl], self.vals[sl],
+                                self.lr, self.l2, hot, hot, self.clip, *self.clip_stats)
+        else:
+            orc.step_mf(self.host[0], self.host[1], self.d, self.rows[sl], self.cols[sl], self.vals[sl], self.lr,
+                        self.l2)
 
     def config(self):
         return {"workload": self.name, "task": "MF", "rows": self.n_rows, "cols": self.n_cols, "dim": self.d,
-                "row_stride": self.stride, "batch": self.B, "zipf_s": self.s, "lr": self.lr, "l2": self.l2}
+                "row_stride": self.stride, "batch": self.B, "zipf_s": self.s, "lr": self.lr, "l2": self.l2,
+                "hot_keys": "per step" if self.hot is None else self.hot, "update_clipping": self.clip or "off"}
 
 
 class Kge:
@@ -320,6 +349,9 @@ def main() -> int:
     ap.add_argument("--workload", default="sgns_1m_d300_bounded_u4", choices=sorted(WORKLOADS))
     ap.add_argument("--depth", type=int, default=3, help="steps prepared ahead of the one that runs")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: about 15 s worth, 0: skip)")
+    ap.add_argument("--clip", type=float, default=0.0,
+                    help="SGD workloads: clip hot-key updates at this factor times their mean norm (0: off); "
+                         "declares the 1,000 most frequent keys of each table as hot if the workload declares none")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -334,6 +366,13 @@ def main() -> int:
 
     torch.cuda.set_device(0)
     w = WORKLOADS[args.workload]()
+    if args.clip > 0.0:
+        if isinstance(w, Kge):
+            print("--clip applies to the SGD workloads; the AdaGrad steps are never clipped", file=sys.stderr)
+            return 2
+        w.clip = args.clip
+        if not w.hot:
+            w.hot = 1000
     total_steps = w.setup(nb, wl, args.warmup + args.steps)
     steps = total_steps - args.warmup
     assert steps > 0, "not enough examples for the requested steps"
@@ -443,8 +482,8 @@ def main() -> int:
     }
     if not finite:
         out["finite_note"] = ("tables overflow at this configuration's learning rate with summed minibatch gradients; "
-                              "the oracle overflows in the same way (DESIGN.md section 4); kernel timing does not depend "
-                              "on the values")
+                              "the oracle overflows in the same way; kernel timing does not depend on the values (--clip 2 "
+                              "runs the same workload with the paper's remedy, norm clipping of hot-key updates)")
     nb.nups_destroy(ctx)
     print(json.dumps(out))
     return 0

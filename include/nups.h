@@ -98,6 +98,28 @@ nups_status nups_set_state(nups_ctx *ctx, int table, float *state_dev);
  */
 nups_status nups_set_hot_keys(nups_ctx *ctx, int table, const uint32_t *keys_host, int64_t k);
 
+/*
+ * Norm clipping of the updates of hot keys (Section 5.1, implementation paragraph: for the
+ * replicated parameters of the word-vector and factorisation tasks, updates that exceed the
+ * average norm by more than a factor, 2 in the paper, are clipped, to keep summed gradients of
+ * hot keys from exploding).  factor > 0 switches it on for the SGD steps (NUPS_TASK_SGNS,
+ * NUPS_TASK_MF) of tables 0 and 1, factor = 0 off (the default); steps with AdaGrad and
+ * nups_push are never clipped.  It acts on the keys of a table's declared hot set
+ * (nups_set_hot_keys) only.  Per table the library keeps the sum and the number of the Euclidean
+ * norms, before clipping, of all hot-key updates (an update = the summed gradient of one key in
+ * one step) since clipping was switched on.  A step compares against the mean of the steps
+ * before it: a hot key's update of norm n > factor * mean is multiplied by factor * mean / n;
+ * while no norm has been recorded nothing is clipped.  Switching on (from off) resets the
+ * statistics; calling again with another factor keeps them.  Takes effect for steps run after
+ * the call, including steps already prepared.  Waits for the stream when it allocates or resets.
+ * NUPS_ERR_ARG: factor negative or not finite.
+ */
+nups_status nups_set_update_clipping(nups_ctx *ctx, float factor);
+
+/* Reads a table's clipping statistics (waits for the stream): the sum of the recorded norms and
+ * their number.  Either pointer may be null.  NUPS_ERR_STATE if clipping was never switched on. */
+nups_status nups_get_update_clipping(nups_ctx *ctx, int table, double *norm_sum, double *norm_count);
+
 /* ---- direct access (Section 3.1) ------------------------------------------------- */
 
 /* pull: values_dev[i, :] = table[keys_dev[i], :] for i < n (whole stored rows, row_stride floats each).

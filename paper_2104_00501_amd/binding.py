@@ -21,7 +21,8 @@ NUPS_TASK_SGNS, NUPS_TASK_MF, NUPS_TASK_KGE = 1, 2, 3
  NUPS_PHASE_PUSH, NUPS_PHASE_COUNT) = range(8)
 
 EXPORTS = [
-    "nups_init", "nups_destroy", "nups_set_state", "nups_set_hot_keys", "nups_pull", "nups_push",
+    "nups_init", "nups_destroy", "nups_set_state", "nups_set_hot_keys", "nups_set_update_clipping",
+    "nups_get_update_clipping", "nups_pull", "nups_push",
     "nups_build_alias_table", "nups_register_distribution", "nups_set_local_keys", "nups_prepare_sample",
     "nups_pull_sample", "nups_sample_keys", "nups_release_sample", "nups_step", "nups_prepare_step",
     "nups_step_prepared", "nups_debug_structure",
@@ -118,6 +119,17 @@ def nups_set_hot_keys(ctx, table, keys_host):
     import numpy as np
     k = np.ascontiguousarray(keys_host, dtype=np.uint32)
     _check(lib().nups_set_hot_keys(ctx, C.c_int(table), _ptr(k) if len(k) else C.c_void_p(None), C.c_int64(len(k))))
+
+
+def nups_set_update_clipping(ctx, factor):
+    _check(lib().nups_set_update_clipping(ctx, C.c_float(factor)))
+
+
+def nups_get_update_clipping(ctx, table):
+    """Returns (sum of the recorded norms, their number)."""
+    norm_sum, norm_count = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().nups_get_update_clipping(ctx, C.c_int(table), C.byref(norm_sum), C.byref(norm_count)))
+    return norm_sum.value, norm_count.value
 
 
 def nups_pull(ctx, table, keys, n, values):

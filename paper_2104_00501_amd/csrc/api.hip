@@ -5,6 +5,7 @@
 // step that was prepared three steps ahead finds its samples drawn and its structure built when it runs, and
 // nothing but the steps' own two launches is ever enqueued.
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 
 #include "nups_internal.h"
@@ -245,6 +246,8 @@ nups_status nups_destroy(nups_ctx *ctx)
     for (nups_prepared *p : ctx->prepared_all) free_prepared(p);
     for (int t = 0; t < kMaxTables; ++t)
         if (ctx->tab[t].hot_bits_dev) (void)hipFree(ctx->tab[t].hot_bits_dev);
+    if (ctx->clip_stats) (void)hipFree(ctx->clip_stats);
+    if (ctx->clip_bound) (void)hipFree(ctx->clip_bound);
     if (ctx->coef) (void)hipFree(ctx->coef);
     if (ctx->stage) (void)hipFree(ctx->stage);
     if (ctx->partial) (void)hipFree(ctx->partial);
@@ -288,6 +291,42 @@ nups_status nups_set_hot_keys(nups_ctx *ctx, int table, const uint32_t *keys_hos
     if (!t.hot_bits_dev) NUPS_HIP(hipMalloc((void **)&t.hot_bits_dev, sizeof(uint32_t) * words));
     NUPS_HIP(hipMemcpy(t.hot_bits_dev, bits.data(), sizeof(uint32_t) * words, hipMemcpyHostToDevice));
     t.hot_keys.swap(keys);
+    return NUPS_OK;
+}
+
+nups_status nups_set_update_clipping(nups_ctx *ctx, float factor)
+{
+    if (!ctx) return fail(NUPS_ERR_ARG, "nups_set_update_clipping: null context");
+    if (!(factor >= 0.0f) || !std::isfinite(factor))
+        return fail(NUPS_ERR_ARG, "nups_set_update_clipping: factor must be finite and not negative");
+    const size_t stats_bytes = sizeof(double) * kMaxTables * kLossSlots * kLossStride;
+    if (factor > 0.0f && !(ctx->clip_factor > 0.0f)) {   // switched on: statistics start from nothing
+        if (!ctx->clip_stats) {
+            NUPS_HIP(hipMalloc((void **)&ctx->clip_stats, stats_bytes));
+            NUPS_HIP(hipMalloc((void **)&ctx->clip_bound, sizeof(float) * kMaxTables));
+        }
+        NUPS_HIP(hipStreamSynchronize(ctx->stream));
+        NUPS_HIP(hipMemset(ctx->clip_stats, 0, stats_bytes));
+    }
+    ctx->clip_factor = factor;
+    return NUPS_OK;
+}
+
+nups_status nups_get_update_clipping(nups_ctx *ctx, int table, double *norm_sum, double *norm_count)
+{
+    if (!valid_table(ctx, table)) return fail(NUPS_ERR_ARG, "nups_get_update_clipping: bad context or table");
+    if (!ctx->clip_stats) return fail(NUPS_ERR_STATE, "nups_get_update_clipping: clipping was never switched on");
+    std::vector<double> slots((size_t)kLossSlots * kLossStride);
+    NUPS_HIP(hipStreamSynchronize(ctx->stream));
+    NUPS_HIP(hipMemcpy(slots.data(), ctx->clip_stats + (size_t)table * slots.size(), sizeof(double) * slots.size(),
+                       hipMemcpyDeviceToHost));
+    double sum = 0.0, count = 0.0;
+    for (int s = 0; s < kLossSlots; ++s) {
+        sum += slots[(size_t)s * kLossStride];
+        count += slots[(size_t)s * kLossStride + 1];
+    }
+    if (norm_sum) *norm_sum = sum;
+    if (norm_count) *norm_count = count;
     return NUPS_OK;
 }
 

@@ -239,10 +239,15 @@ static inline uint32_t xcd_grid(uint32_t blocks) { return (blocks + kNumXcd - 1)
 // Which technique a key gets (Section 3.2: hot spots and the long tail are managed differently).  A segment of
 // `count` accesses is cut into chunks for several workgroups if it is long and, when the caller declared a
 // hot-key set, the key is in it; every other segment is summed by a single row group.
+__device__ __forceinline__ bool in_hot_set(uint32_t key, const uint32_t *hot_bits)
+{
+    return ((hot_bits[key >> 5] >> (key & 31)) & 1u) != 0;
+}
+
 __device__ __forceinline__ bool takes_hot_path(uint32_t count, uint32_t key, const uint32_t *hot_bits)
 {
     if (count <= kLongSegment) return false;
-    return hot_bits == nullptr || ((hot_bits[key >> 5] >> (key & 31)) & 1u) != 0;
+    return hot_bits == nullptr || in_hot_set(key, hot_bits);
 }
 
 __device__ __forceinline__ uint32_t source_key(const KeySource &s, uint32_t i)

@@ -197,6 +197,10 @@ struct nups_ctx {
     uint32_t *error_flag = nullptr;                        // device word
     double *loss_pinned = nullptr;                         // pinned host copies for read-back
     uint32_t *flag_pinned = nullptr;
+    // norm clipping of hot-key updates (Section 5.1); factor 0: off
+    float clip_factor = 0.0f;
+    double *clip_stats = nullptr;   // [kMaxTables][kLossSlots * kLossStride]: per slot {sum of norms, number of norms}
+    float *clip_bound = nullptr;    // [kMaxTables] factor x mean norm, refreshed before each update launch
     bool profiling = false;
     nups::Phase phase[NUPS_PHASE_COUNT];
     std::vector<nups_dist *> dists;

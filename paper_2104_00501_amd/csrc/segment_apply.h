@@ -69,7 +69,39 @@ struct SrcKgeEntity {
 
 struct OptSgd {          // theta <- theta - lr * delta
     float lr;
+    // Norm clipping of the updates of hot keys (Section 5.1: updates of replicated parameters that exceed the
+    // average norm by more than a factor are clipped).  clip_bound: factor x the mean norm of the hot-key updates
+    // of earlier steps (+inf while there are none), computed before the launch; null: no clipping.  clip_stats:
+    // kLossSlots pairs {sum of norms, number of norms}, kLossStride doubles apart, which this step adds to.
+    const float *clip_bound = nullptr;
+    double *clip_stats = nullptr;
     static constexpr bool kHasState = false;
+    __device__ __forceinline__ bool clips() const { return clip_bound != nullptr; }
+    // d: the summed gradient of a hot key, held by one row group.  Records its norm and shortens it to the bound.
+    template <int NV4>
+    __device__ __forceinline__ void clip(Row<NV4> &d, int lane) const
+    {
+        float sq = 0.0f;
+#pragma unroll
+        for (int q = 0; q < NV4; ++q) sq += d.v[q].x * d.v[q].x + d.v[q].y * d.v[q].y + d.v[q].z * d.v[q].z + d.v[q].w * d.v[q].w;
+        const float norm = sqrtf(group_sum(sq));
+        if (lane == 0) {
+            double *slot = clip_stats + (blockIdx.x % kLossSlots) * kLossStride;
+            atomicAdd(slot, (double)norm);
+            atomicAdd(slot + 1, 1.0);
+        }
+        const float bound = *clip_bound;
+        if (norm > bound) {
+            const float shrink = bound / norm;
+#pragma unroll
+            for (int q = 0; q < NV4; ++q) {
+                d.v[q].x *= shrink;
+                d.v[q].y *= shrink;
+                d.v[q].z *= shrink;
+                d.v[q].w *= shrink;
+            }
+        }
+    }
     template <int NV4>
     __device__ __forceinline__ void load(Row<NV4> &t, Row<NV4> &, const float *row, const float *, int lane) const
     {
@@ -87,6 +119,9 @@ struct OptSgd {          // theta <- theta - lr * delta
 
 struct OptAdd {          // theta <- theta + delta   (push)
     static constexpr bool kHasState = false;
+    __device__ __forceinline__ bool clips() const { return false; }
+    template <int NV4>
+    __device__ __forceinline__ void clip(Row<NV4> &, int) const {}
     template <int NV4>
     __device__ __forceinline__ void load(Row<NV4> &t, Row<NV4> &, const float *row, const float *, int lane) const
     {
@@ -105,6 +140,9 @@ struct OptAdd {          // theta <- theta + delta   (push)
 struct OptAdagrad {      // G <- G + delta^2 ; theta <- theta - lr * delta / (sqrt(G) + eps)
     float lr, eps;
     static constexpr bool kHasState = true;
+    __device__ __forceinline__ bool clips() const { return false; }
+    template <int NV4>
+    __device__ __forceinline__ void clip(Row<NV4> &, int) const {}
     // The hardware square root and reciprocal (one unit in the last place each) instead of the correctly rounded
     // sequences: the update is a product of rounded factors anyway, and the row update is arithmetic-bound otherwise
     // (a 2 KB row is 512 square roots and divisions).
@@ -212,6 +250,7 @@ __device__ __forceinline__ void apply_short_item(const ApplyArgs &a, const Src &
     zero_row(acc);
     sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
     opt.template load<NV4>(t, g, row, state_row, lane);
+    if (opt.clips() && a.hot_bits != nullptr && in_hot_set(key, a.hot_bits)) opt.template clip<NV4>(acc, lane);
     opt.template finish<NV4>(t, g, row, state_row, acc, lane);
 }
 
@@ -279,6 +318,7 @@ __device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &
         const size_t off = (size_t)a.uniq[u] * a.stride;
         Row<NV4> t, g;
         opt.template load<NV4>(t, g, a.table + off, Opt::kHasState ? a.state + off : nullptr, lane);
+        if (opt.clips() && a.hot_bits != nullptr) opt.template clip<NV4>(acc, lane);   // chunked and declared: a hot key
         opt.template finish<NV4>(t, g, a.table + off, Opt::kHasState ? a.state + off : nullptr, acc, lane);
     }
 }

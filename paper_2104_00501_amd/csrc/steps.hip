@@ -81,6 +81,46 @@ nups_status flush_side_work(nups_ctx *ctx, nups_prepared *p)
 }
 
 // ------------------------------------------------------------------------------------------------
+// Norm clipping of hot-key updates (Section 5.1).  Before the update launch of a step, one wavefront per table
+// adds up the table's slots of {sum of norms, number of norms} and leaves the bound for this step: factor x
+// mean, +inf while no norm has been recorded.  The update kernel then adds this step's norms to the slots.
+// ------------------------------------------------------------------------------------------------
+static_assert(kLossSlots == 64, "one lane per slot");
+
+__global__ void __launch_bounds__(64) k_clip_bounds(const double *stats, float factor, float *bound)
+{
+    const double *slot = stats + ((size_t)blockIdx.x * kLossSlots + threadIdx.x) * kLossStride;
+    double sum = slot[0], seen = slot[1];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        sum += __shfl_xor(sum, o, 64);
+        seen += __shfl_xor(seen, o, 64);
+    }
+    if (threadIdx.x == 0) bound[blockIdx.x] = seen > 0.0 ? (float)((double)factor * (sum / seen)) : INFINITY;
+}
+
+// The update rule of table `table` for a step with learning rate lr; with clipping on, the bounds of tables
+// 0 and 1 must have been refreshed on the stream (refresh_clip_bounds) before the update kernel runs.
+static OptSgd sgd_rule(const nups_ctx *ctx, int table, float lr)
+{
+    OptSgd opt{lr};
+    if (ctx->clip_factor > 0.0f) {
+        opt.clip_bound = ctx->clip_bound + table;
+        opt.clip_stats = ctx->clip_stats + (size_t)table * kLossSlots * kLossStride;
+    }
+    return opt;
+}
+
+static nups_status refresh_clip_bounds(nups_ctx *ctx)
+{
+    if (!(ctx->clip_factor > 0.0f)) return NUPS_OK;
+    hipLaunchKernelGGL(k_clip_bounds, dim3(2), dim3(64), 0, ctx->stream, (const double *)ctx->clip_stats,
+                       ctx->clip_factor, ctx->clip_bound);
+    NUPS_HIP(hipGetLastError());
+    return NUPS_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
 // pull: values[i, :] = table[keys[i], :]; one thread per float4, zero rows for keys out of range.
 // ------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kBlock) k_pull(const float *table, uint32_t num_keys, int stride4,
@@ -244,11 +284,12 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
     {   // both tables in one launch: the output side reads the staged center rows, not the input table
         const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
+        if ((st = refresh_clip_bounds(ctx)) != NUPS_OK) return st;
         const TableUpdate<SrcStaged, OptSgd> uin{&p.plan[0], partial_of(ctx, p, 0), tin.data, nullptr,
-                                                 SrcStaged{ctx->stage}, OptSgd{b.lr}};
+                                                 SrcStaged{ctx->stage}, sgd_rule(ctx, 0, b.lr)};
         const TableUpdate<SrcSgnsOut, OptSgd> uout{&p.plan[1], partial_of(ctx, p, 1), tout.data, nullptr,
                                                    SrcSgnsOut{center_rows, p.plan[0].a.slot, ctx->coef, B, K},
-                                                   OptSgd{b.lr}};
+                                                   sgd_rule(ctx, 1, b.lr)};
         if ((st = launch_apply2(ctx->stream, tin.stride, uin, uout, sw, side_lds)) != NUPS_OK) return st;
     }
     return NUPS_OK;
@@ -331,10 +372,11 @@ nups_status run_step_mf(nups_ctx *ctx, nups_prepared &p)
     {
         const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
+        if ((st = refresh_clip_bounds(ctx)) != NUPS_OK) return st;
         const TableUpdate<SrcStaged, OptSgd> uw{&p.plan[0], partial_of(ctx, p, 0), tw.data, nullptr,
-                                                SrcStaged{ctx->stage}, OptSgd{b.lr}};
+                                                SrcStaged{ctx->stage}, sgd_rule(ctx, 0, b.lr)};
         const TableUpdate<SrcStaged, OptSgd> uh{&p.plan[1], partial_of(ctx, p, 1), th.data, nullptr,
-                                                SrcStaged{ctx->stage + (size_t)B * tw.stride}, OptSgd{b.lr}};
+                                                SrcStaged{ctx->stage + (size_t)B * tw.stride}, sgd_rule(ctx, 1, b.lr)};
         if ((st = launch_apply2(ctx->stream, tw.stride, uw, uh, sw, side_lds)) != NUPS_OK) return st;
     }
     return NUPS_OK;
