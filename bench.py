@@ -62,9 +62,16 @@ class Sgns:
         self.centers, self.contexts = wl.window_pairs(toks, window, 0, total_steps * B)
         total_steps = len(self.centers) // B
         self.weights = wl.expected_unigram_weights(self.V, self.s, self.stream_tokens)
-        self.In, self.Out = wl.sgns_tables(self.V, self.d, self.seed)
-        self.stride = self.In.shape[1]
-        self.tables = [torch.from_numpy(self.In).cuda(), torch.from_numpy(self.Out).cuda()]
+        self.stride = wl.padded_stride(self.d)
+        if self.V * self.stride * 4 > (2 << 30):      # large tables are filled on the device
+            g = torch.Generator(device="cuda").manual_seed(self.seed)
+            tin = torch.zeros((self.V, self.stride), dtype=torch.float32, device="cuda")
+            tin[:, :self.d] = (torch.rand((self.V, self.d), generator=g, device="cuda") - 0.5) / self.d
+            self.tables = [tin, torch.zeros_like(tin)]
+            self.In = self.Out = None                  # host copies are made when the oracle leg asks for them
+        else:
+            self.In, self.Out = wl.sgns_tables(self.V, self.d, self.seed)
+            self.tables = [torch.from_numpy(self.In).cuda(), torch.from_numpy(self.Out).cuda()]
         self.kc, self.ko = dev_keys(self.centers), dev_keys(self.contexts)
         self.ctx = nb.nups_init(self.tables, [self.d, self.d])
         code = {"CONFORM": nb.NUPS_CONFORM, "BOUNDED": nb.NUPS_BOUNDED, "LONGTERM": nb.NUPS_LONGTERM,
@@ -107,6 +114,8 @@ class Sgns:
     def oracle_step(self, orc, t):
         if not hasattr(self, "alias"):
             self.alias = orc.alias_build(self.weights)
+            if self.In is None:
+                self.In, self.Out = [x.cpu().numpy() for x in self.tables_initial]
         B, K = self.B, self.K
         c, o = self.centers[t * B:(t + 1) * B], self.contexts[t * B:(t + 1) * B]
         if self.scheme == "BOUNDED":
@@ -138,16 +147,22 @@ class Sgns:
 class Mf:
     """Matrix factorisation; tables 0/1 = row / column factors."""
 
-    def __init__(self, name, n_rows, n_cols, d, B, s, lr, l2, seed):
+    def __init__(self, name, n_rows, n_cols, d, B, s, lr, l2, seed, by_column=False):
         self.name, self.n_rows, self.n_cols, self.d, self.B, self.s = name, n_rows, n_cols, d, B, s
         self.lr, self.l2, self.seed = lr, l2, seed
+        self.by_column = by_column              # cells in the paper's visiting order instead of generation order
         self.hot, self.clip = None, 0.0         # declared hot rows / columns (top-k by frequency rank); clipping factor
         self.unit = "cells"
 
     def setup(self, nb, wl, total_steps):
         import torch
         B = self.B
-        self.rows, self.cols, self.vals = wl.mf_cells(self.n_rows, self.n_cols, self.s, total_steps * B, self.seed)
+        if self.by_column:      # 64 workers, each column by column; the least loaded worker ends the run
+            cells = wl.mf_cells(self.n_rows, self.n_cols, self.s, int(2.5 * total_steps * B), self.seed)
+            self.rows, self.cols, self.vals = wl.mf_visit_by_column(*cells, B, self.seed + 3)
+            assert len(self.rows) >= total_steps * B, "not enough cells for the requested steps"
+        else:
+            self.rows, self.cols, self.vals = wl.mf_cells(self.n_rows, self.n_cols, self.s, total_steps * B, self.seed)
         self.stride = wl.padded_stride(self.d)
         g = torch.Generator(device="cuda").manual_seed(self.seed)
 
@@ -203,7 +218,8 @@ class Mf:
     def config(self):
         return {"workload": self.name, "task": "MF", "rows": self.n_rows, "cols": self.n_cols, "dim": self.d,
                 "row_stride": self.stride, "batch": self.B, "zipf_s": self.s, "lr": self.lr, "l2": self.l2,
-                "hot_keys": "per step" if self.hot is None else self.hot, "update_clipping": self.clip or "off"}
+                "hot_keys": "per step" if self.hot is None else self.hot, "update_clipping": self.clip or "off",
+                "cells": "64 workers, each column by column" if self.by_column else "generation order"}
 
 
 class Kge:
@@ -309,6 +325,19 @@ WORKLOADS = {
     "mf_10m_1m_d100": lambda: Mf("mf_10m_1m_d100", 10_000_000, 1_000_000, 100, 65_536, 0.8, 0.005, 0.01, 1002),
     "kge_4p6m_d500": lambda: Kge("kge_4p6m_d500", 4_600_000, 822, 500, 1024, 50, 50, 0.1, 1e-10, 1003),
 }
+# The paper's own shapes (Table 1, Section 5.1) where they differ from the configurations above: word vectors of
+# dimension 1000 over 1.9M words under the untuned configuration's BOUNDED reuse (U = 16); factorisation of rank
+# 1000 with Zipf(1.1) ids, visited by column; ComplEx with 100 + 100 negatives over 4.8M entities and 828 relations.
+WORKLOADS.update({
+    "sgns_1p9m_d1000_bounded_u16": lambda: Sgns("sgns_1p9m_d1000_bounded_u16", 1_900_000, 1000, 3, 16, 250, 16_384,
+                                                5, 1.0, 0.025, 375_000_000, 1006),
+    "mf_10m_1m_rank1000_by_column": lambda: Mf("mf_10m_1m_rank1000_by_column", 10_000_000, 1_000_000, 1000, 65_536,
+                                               1.1, 0.005, 0.01, 1007, by_column=True),
+    "mf_10m_1m_d100_by_column": lambda: Mf("mf_10m_1m_d100_by_column", 10_000_000, 1_000_000, 100, 65_536, 0.8,
+                                           0.005, 0.01, 1002, by_column=True),
+    "kge_4p8m_d500_neg100_100": lambda: Kge("kge_4p8m_d500_neg100_100", 4_818_679, 828, 500, 1024, 100, 100, 0.1,
+                                            1e-10, 1008),
+})
 WORKLOADS.update(_sweep_workloads())
 
 
@@ -377,7 +406,7 @@ def main() -> int:
     steps = total_steps - args.warmup
     assert steps > 0, "not enough examples for the requested steps"
     ctx, B = w.ctx, w.B
-    if args.cpu_steps != 0 and not isinstance(w, Sgns):       # the oracle starts from the same initial tables
+    if args.cpu_steps != 0 and getattr(w, "In", None) is None:   # the oracle starts from the same initial tables
         w.tables_initial = [t.clone() for t in w.tables]
         if hasattr(w, "states"):
             w.states_initial = [t.clone() for t in w.states]

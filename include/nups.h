@@ -152,6 +152,37 @@ nups_status nups_build_alias_table(const double *weights_host, int64_t num_keys,
 nups_status nups_register_distribution(nups_ctx *ctx, int table, const double *weights_host,
                                        nups_scheme scheme, int32_t U, int32_t G, int64_t P, int32_t R,
                                        uint64_t seed, nups_dist **out);
+nups_status nups_register_distribution(nups_ctx *ctx, int table, const double *weights_host,
+                                       nups_scheme scheme, int32_t U, int32_t G, int64_t P, int32_t R,
+                                       uint64_t seed, nups_dist **out);
+
+/*
+ * The same with a conformity level in place of a scheme (Section 4.1: L1 CONFORM, L2
+ * BOUNDED, L3 LONG-TERM; a fourth value stands for "no guarantee asked", NON-CONFORM):
+ * the library picks the cheapest scheme that the level admits (Table 2, Section 4.4) with
+ * the parameters of the paper's untuned configuration (Section 5.1):
+ *   NUPS_CONFORM    -> independent sampling;
+ *   NUPS_BOUNDED    -> sample reuse, U = 16, pools of G = 250;
+ *   NUPS_LONGTERM   -> sample reuse from a persistent pool of P = 1,000,000 draws, R = 16 passes;
+ *   NUPS_NONCONFORM -> local sampling (the caller supplies the batch's keys, nups_set_local_keys).
+ * The level is passed as the nups_scheme value of the same name.
+ */
+nups_status nups_register_distribution_at_level(nups_ctx *ctx, int table, const double *weights_host,
+                                                nups_scheme level, uint64_t seed, nups_dist **out);
+
+/*
+ * Host-only helper, needs no GPU: the management-technique heuristic of the paper's untuned
+ * configuration (Section 5.1): a key is hot (replicated there; given the hot path here) if its
+ * access frequency exceeds `factor` (the paper: 100) times the mean access frequency over all
+ * num_keys keys.  frequency_host holds one non-negative number per key (counts or relative
+ * frequencies, from dataset statistics).  Writes the hot keys, most frequent first (ties: smaller
+ * key first), to keys_out_host, at most `capacity` of them, and their total number to *k_out (which
+ * may exceed capacity: call again with a larger array).  The result is what nups_set_hot_keys takes.
+ * Errors: NUPS_ERR_ARG for null pointers, num_keys < 1, a negative capacity, factor not positive,
+ * negative / NaN / infinite frequencies.
+ */
+nups_status nups_select_hot_keys(const double *frequency_host, int64_t num_keys, double factor,
+                                 uint32_t *keys_out_host, int64_t capacity, int64_t *k_out);
 
 /*
  * NUPS_NONCONFORM only: the keys the minibatch accesses anyway, from which samples are

@@ -23,7 +23,8 @@ NUPS_TASK_SGNS, NUPS_TASK_MF, NUPS_TASK_KGE = 1, 2, 3
 EXPORTS = [
     "nups_init", "nups_destroy", "nups_set_state", "nups_set_hot_keys", "nups_set_update_clipping",
     "nups_get_update_clipping", "nups_pull", "nups_push",
-    "nups_build_alias_table", "nups_register_distribution", "nups_set_local_keys", "nups_prepare_sample",
+    "nups_build_alias_table", "nups_register_distribution", "nups_register_distribution_at_level",
+    "nups_select_hot_keys", "nups_set_local_keys", "nups_prepare_sample",
     "nups_pull_sample", "nups_sample_keys", "nups_release_sample", "nups_step", "nups_prepare_step",
     "nups_step_prepared", "nups_debug_structure",
     "nups_check", "nups_profile", "nups_profile_read", "nups_phase_name", "nups_last_error",
@@ -158,6 +159,28 @@ def nups_register_distribution(ctx, table, weights_host, scheme, U=1, G=1, P=1, 
                                             C.c_int32(G), C.c_int64(P), C.c_int32(R), C.c_uint64(seed),
                                             C.byref(dist)))
     return dist
+
+
+def nups_register_distribution_at_level(ctx, table, weights_host, level, seed=0):
+    import numpy as np
+    w = None if weights_host is None else np.ascontiguousarray(weights_host, dtype=np.float64)
+    dist = C.c_void_p(None)
+    _check(lib().nups_register_distribution_at_level(ctx, C.c_int(table), _ptr(w), C.c_int(level), C.c_uint64(seed),
+                                                     C.byref(dist)))
+    return dist
+
+
+def nups_select_hot_keys(frequency_host, factor=100.0):
+    """Host only.  Returns the hot keys, most frequent first, as a uint32 numpy array."""
+    import numpy as np
+    f = np.ascontiguousarray(frequency_host, dtype=np.float64)
+    k = C.c_int64(0)
+    _check(lib().nups_select_hot_keys(_ptr(f), C.c_int64(len(f)), C.c_double(factor), C.c_void_p(None), C.c_int64(0),
+                                      C.byref(k)))
+    keys = np.zeros(max(k.value, 1), dtype=np.uint32)
+    _check(lib().nups_select_hot_keys(_ptr(f), C.c_int64(len(f)), C.c_double(factor), _ptr(keys), C.c_int64(k.value),
+                                      C.byref(k)))
+    return keys[:k.value]
 
 
 def nups_set_local_keys(dist, keys_a, keys_b, n_examples, per_example, split, tile):

@@ -405,6 +405,36 @@ nups_status nups_register_distribution(nups_ctx *ctx, int table, const double *w
     return NUPS_OK;
 }
 
+nups_status nups_register_distribution_at_level(nups_ctx *ctx, int table, const double *weights_host,
+                                                nups_scheme level, uint64_t seed, nups_dist **out)
+{
+    // the untuned configuration's parameters (Section 5.1): use frequency 16, pools of 250
+    return nups_register_distribution(ctx, table, weights_host, level, 16, 250, 1000000, 16, seed, out);
+}
+
+nups_status nups_select_hot_keys(const double *frequency_host, int64_t num_keys, double factor,
+                                 uint32_t *keys_out_host, int64_t capacity, int64_t *k_out)
+{
+    if (!frequency_host || !k_out || num_keys < 1 || num_keys > 0xFFFFFFFFll || capacity < 0
+        || (capacity > 0 && !keys_out_host) || !(factor > 0.0) || !std::isfinite(factor))
+        return fail(NUPS_ERR_ARG, "nups_select_hot_keys: bad arguments");
+    double total = 0.0;
+    for (int64_t k = 0; k < num_keys; ++k) {
+        if (!(frequency_host[k] >= 0.0) || !std::isfinite(frequency_host[k]))
+            return fail(NUPS_ERR_ARG, "nups_select_hot_keys: frequencies must be finite and not negative");
+        total += frequency_host[k];
+    }
+    const double bar = factor * (total / (double)num_keys);
+    std::vector<uint32_t> hot;
+    for (int64_t k = 0; k < num_keys; ++k)
+        if (frequency_host[k] > bar) hot.push_back((uint32_t)k);
+    std::stable_sort(hot.begin(), hot.end(),
+                     [&](uint32_t a, uint32_t b) { return frequency_host[a] > frequency_host[b]; });
+    *k_out = (int64_t)hot.size();
+    for (int64_t i = 0; i < std::min<int64_t>(capacity, (int64_t)hot.size()); ++i) keys_out_host[i] = hot[(size_t)i];
+    return NUPS_OK;
+}
+
 nups_status nups_set_local_keys(nups_dist *dist, const uint32_t *keys_a_dev, const uint32_t *keys_b_dev,
                                 int64_t n_examples, int32_t per_example, int32_t split, int32_t tile)
 {

@@ -141,6 +141,33 @@ def mf_cells(num_rows: int, num_cols: int, s: float, n: int, seed: int,
     return rows, cols, vals.astype(np.float32)
 
 
+def mf_visit_by_column(rows: np.ndarray, cols: np.ndarray, vals: np.ndarray, batch: int, seed: int,
+                       nodes: int = 8, workers_per_node: int = 8):
+    """Reorders cells into the visiting order of the factorisation task (Section 5.1): cells are
+    partitioned to nodes by row and to the workers of a node by column (here: id modulo the number
+    of parts, so that the frequent ids, which are the small ones, spread evenly); each worker
+    walks its cells column by column, columns in random order, the cells of a column in random
+    order.  Batch t is the t-th slice of batch / (nodes * workers_per_node) cells of every
+    worker, concatenated in worker order; the run ends when the first worker runs out of cells.
+    Returns (rows, cols, vals) of steps * batch cells.
+    """
+    workers = nodes * workers_per_node
+    assert batch % workers == 0, "the batch is shared evenly among the workers"
+    per = batch // workers
+    rng = np.random.default_rng(seed)
+    n = len(rows)
+    worker = (rows % nodes).astype(np.int64) * workers_per_node + (cols % workers_per_node).astype(np.int64)
+    column_order = rng.permutation(int(cols.max()) + 1 if n else 1)
+    order = np.lexsort((rng.random(n), column_order[cols], worker))   # by worker, column order, then at random
+    counts = np.bincount(worker, minlength=workers)
+    steps = int(counts.min()) // per
+    starts = np.concatenate([[0], np.cumsum(counts)[:-1]])
+    idx = (starts[None, :, None] + np.arange(steps, dtype=np.int64)[:, None, None] * per
+           + np.arange(per, dtype=np.int64)[None, None, :])
+    sel = order[idx.reshape(-1)]
+    return rows[sel], cols[sel], vals[sel]
+
+
 def kge_triples(num_entities: int, num_relations: int, n: int, seed: int,
                 s_entity: float = 1.1, s_relation: float = 1.5):
     """n triples: head and tail i.i.d. Zipf(s_entity), relation i.i.d. Zipf(s_relation)."""

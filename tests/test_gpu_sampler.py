@@ -136,3 +136,26 @@ def test_pull_sample_partial_pulls_values_and_errors():
     with pytest.raises(nb.NupsError):
         nb.nups_register_distribution(ctx, 0, np.zeros(V), nb.NUPS_CONFORM)
     nb.nups_destroy(ctx)
+
+
+def test_a_conformity_level_selects_the_scheme_of_the_untuned_configuration():
+    # Section 4.3: register_distribution(pi, L); Section 5.1: BOUNDED with U = 16 (pools of 250) untuned
+    V, n = 200_000, 30_000
+    ctx, _ = _ctx(V, d=20)
+    w = wl.expected_unigram_weights(V, 1.0, 1e9)
+    table = orc.alias_build(w)
+    expect = {nb.NUPS_CONFORM: lambda i, step: orc.sample_conform(table, V, 31, i, step, n),
+              nb.NUPS_BOUNDED: lambda i, step: orc.sample_bounded(table, V, 31, i, step, n, 16, 250),
+              nb.NUPS_LONGTERM: lambda i, step: orc.sample_longterm(table, V, 31, i, 1_000_000, 16, 0, n)}
+    for i, level in enumerate((nb.NUPS_CONFORM, nb.NUPS_BOUNDED, nb.NUPS_LONGTERM)):
+        dist = nb.nups_register_distribution_at_level(ctx, 0, w, level, seed=31)
+        h = nb.nups_prepare_sample(dist, n, 4)
+        assert np.array_equal(_keys_of(h, n), expect[level](i, 4))
+        nb.nups_release_sample(h)
+    dist = nb.nups_register_distribution_at_level(ctx, 0, None, nb.NUPS_NONCONFORM, seed=31)
+    with pytest.raises(nb.NupsError):                      # local sampling needs the batch's keys first
+        nb.nups_prepare_sample(dist, n, 0)
+    with pytest.raises(nb.NupsError) as e:
+        nb.nups_register_distribution_at_level(ctx, 0, w, 7, seed=31)
+    assert e.value.status == nb.NUPS_ERR_ARG
+    nb.nups_destroy(ctx)

@@ -149,9 +149,16 @@ def test_sgns_bounded_reuse_step_and_bad_keys():
 
 
 # ------------------------------------------------------------------------------------------ MF
-@pytest.mark.parametrize("nr,nc,d,B,s", [(100_000, 10_000, 100, 65_536, 0.8), (500, 300, 100, 5000, 1.1), (50, 40, 10, 1, 0.8)])
-def test_mf_one_step_matches_the_oracle(nr, nc, d, B, s):
-    rows, cols, vals = wl.mf_cells(nr, nc, s, B, 1002)
+@pytest.mark.parametrize("nr,nc,d,B,s,by_column", [
+    (100_000, 10_000, 100, 65_536, 0.8, False), (500, 300, 100, 5000, 1.1, False), (50, 40, 10, 1, 0.8, False),
+    (4_000, 3_000, 1000, 3_000, 1.1, False),     # the paper's rank (Table 1): 1,024-float rows
+    (50_000, 5_000, 100, 8_192, 1.1, True),      # the paper's visiting order: a batch holds few, long column segments
+])
+def test_mf_one_step_matches_the_oracle(nr, nc, d, B, s, by_column):
+    rows, cols, vals = wl.mf_cells(nr, nc, s, B * (16 if by_column else 1), 1002)
+    if by_column:
+        rows, cols, vals = [x[2 * B:3 * B].copy() for x in wl.mf_visit_by_column(rows, cols, vals, B, 7)]
+        assert np.bincount(cols).max() > 128         # several chunks per hot column
     W = wl.uniform_table(nr, d, -0.1, 0.1, 1)
     H = wl.uniform_table(nc, d, -0.1, 0.1, 2)
     tw, th = dev(W), dev(H)
@@ -174,7 +181,8 @@ def _ccols(d, stride):
     return list(range(d // 2)) + list(range(stride // 2, stride // 2 + d // 2))
 
 
-@pytest.mark.parametrize("ne,nrel,d,B,nh,nt", [(200_000, 822, 500, 128, 50, 50), (5_000, 20, 100, 64, 3, 0),
+@pytest.mark.parametrize("ne,nrel,d,B,nh,nt", [(200_000, 822, 500, 128, 50, 50), (50_000, 828, 500, 96, 100, 100),
+                                                (5_000, 20, 100, 64, 3, 0),
                                                 (5_000, 20, 200, 33, 0, 7), (100, 5, 64, 16, 0, 0), (300, 5, 300, 40, 17, 16)])
 def test_kge_one_step_matches_the_oracle(ne, nrel, d, B, nh, nt):
     import torch

@@ -78,3 +78,28 @@ def test_null_objects_are_rejected():
     assert lib.nups_prepare_sample(None, C.c_int64(1), C.c_uint64(0), C.byref(C.c_void_p())) == nb.NUPS_ERR_ARG
     assert lib.nups_check(None) == nb.NUPS_ERR_ARG
     assert nb.nups_phase_name(nb.NUPS_PHASE_GRAD) == "grad" and nb.nups_phase_name(99) == ""
+
+
+def test_hot_key_heuristic_against_brute_force_and_the_zipf_closed_form():
+    # Section 5.1, untuned configuration: hot = access frequency above 100 x the mean access frequency
+    rng = np.random.default_rng(4)
+    f = rng.pareto(0.7, 5000)
+    f[[10, 20, 30]] = f.max() * 2                          # ties among the most frequent keys
+    hot = nb.nups_select_hot_keys(f, 20.0)
+    brute = [k for k in range(len(f)) if f[k] > 20.0 * f.sum() / len(f)]
+    assert sorted(hot.tolist()) == brute and len(hot) > 5
+    assert hot[:3].tolist() == [10, 20, 30]                # most frequent first, ties by key
+    assert np.all(np.diff(f[hot]) <= 0)
+    # Zipf(1) over V keys: p_k = 1 / (k H_V), mean 1 / V: key of rank k is hot iff k < V / (100 H_V)
+    V = 1_000_000
+    p = 1.0 / np.arange(1, V + 1)
+    H_V = p.sum()
+    hot = nb.nups_select_hot_keys(p / H_V)
+    assert len(hot) == int(np.ceil(V / (100.0 * H_V))) - 1 and np.array_equal(hot, np.arange(len(hot)))
+    assert len(nb.nups_select_hot_keys(np.ones(1000))) == 0          # uniform access: nothing is hot
+    for bad in ([1.0, -1.0], [float("nan"), 1.0]):
+        with pytest.raises(nb.NupsError) as e:
+            nb.nups_select_hot_keys(np.array(bad))
+        assert e.value.status == nb.NUPS_ERR_ARG
+    with pytest.raises(nb.NupsError):
+        nb.nups_select_hot_keys(np.ones(4), 0.0)
