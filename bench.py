@@ -192,9 +192,20 @@ class Mf:
     def accesses(self):
         return self.B, self.B
 
+    def note_structure(self, t, table, keys, counts):
+        """Rows / columns that the gradient kernel updates itself: those with one access in step t."""
+        if self.clip > 0.0:         # with clipping on every update goes through the update kernel
+            return
+        self.alone = getattr(self, "alone", [[], []])
+        self.alone[table].append(int((counts == 1).sum()))
+
     def algorithmic_bytes(self, nu0, nu1):
         row, B = 4 * self.d, self.B
-        return {"grad": (nu0 + nu1) * row + 12 * B, "apply0": nu0 * row * 2 + 4 * B, "apply1": nu1 * row * 2 + 4 * B,
+        a0, a1 = [float(np.mean(x)) if x else 0.0 for x in getattr(self, "alone", [[], []])]
+        # every distinct row read once and written once: written by the gradient kernel if the row has a single
+        # access, by the update kernel (which reads it again) otherwise
+        return {"grad": (nu0 + nu1) * row + (a0 + a1) * row + 12 * B,
+                "apply0": (nu0 - a0) * row * 2 + 4 * B, "apply1": (nu1 - a1) * row * 2 + 4 * B,
                 "step": (nu0 + nu1) * row * 2 + 12 * B}
 
     def logical_bytes(self):
@@ -269,8 +280,10 @@ class Kge:
     def accesses(self):
         return self.B * (2 + self.nh + self.nt), self.B
 
-    def note_structure(self, t, keys, counts):
+    def note_structure(self, t, table, keys, counts):
         """Entities that the gradient kernel updates itself: accessed once in step t, by a negative."""
+        if table != 0:
+            return
         sl = slice(t * self.B, (t + 1) * self.B)
         once = keys[counts == 1]
         self.alone = getattr(self, "alone", []) + [int(np.isin(once, np.concatenate([self.s[sl], self.o[sl]]),
@@ -444,11 +457,12 @@ def main() -> int:
     nu0 = nu1 = 0
     for t in range(first_prof, first_prof + n_prof):
         run(t, 1)
-        n0_t = nb.nups_debug_structure(ctx, 0, uk, uc)      # distinct rows per step, for the algorithmic bytes
-        if hasattr(w, "note_structure"):
-            w.note_structure(t, uk[:n0_t].cpu().numpy().view(np.uint32), uc[:n0_t].cpu().numpy().view(np.uint32))
-        nu0 += n0_t
-        nu1 += nb.nups_debug_structure(ctx, 1, uk, uc)
+        for table in (0, 1):                                # distinct rows per step, for the algorithmic bytes
+            n_t = nb.nups_debug_structure(ctx, table, uk, uc)
+            if hasattr(w, "note_structure"):
+                w.note_structure(t, table, uk[:n_t].cpu().numpy().view(np.uint32),
+                                 uc[:n_t].cpu().numpy().view(np.uint32))
+            nu0, nu1 = (nu0 + n_t, nu1) if table == 0 else (nu0, nu1 + n_t)
     nu0 /= n_prof
     nu1 /= n_prof
     phases = {}

@@ -17,7 +17,8 @@ namespace nups {
 // Row i of a staging array, coefficient one (SGNS input side, MF, KGE subject/object/relation, push).
 struct SrcStaged {
     const float *stage;
-    __device__ __forceinline__ bool done_already(uint32_t) const { return false; }
+    bool singles_done = false;   // the gradient kernel has updated the keys with a single access itself
+    __device__ __forceinline__ bool done_already(uint32_t) const { return singles_done; }
     __device__ __forceinline__ float coef(uint32_t) const { return 1.0f; }
     __device__ __forceinline__ const float *row(uint32_t i, int stride) const { return stage + (size_t)i * stride; }
 };

@@ -419,7 +419,7 @@ __device__ __forceinline__ void scatter_block(const PlanArgs &a, uint32_t vb)
     a.bytemap[source_key(a.src, i)] = 0;
     if (r == 0) {
         a.cnt_work[u] = 0;
-        if (next - first == 1) a.rank[i] = kSingleAccess;   // lets the update skip the segment lookup
+        if (next - first == 1) a.rank[i] = kSingleAccess;   // the key's only access: a gradient kernel may update the row itself
     }
 }
 

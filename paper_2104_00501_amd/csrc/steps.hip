@@ -298,11 +298,16 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
 // ------------------------------------------------------------------------------------------------
 // Matrix factorisation.  One group per cell: err = x - <w, h>; staged rows
 //   dW = -2 err h + 2 l2 w   (rows [0, B))      dH = -2 err w + 2 l2 h   (rows [B, 2B)).
+// A row (or column) whose only access of the step is this cell is updated here instead, theta <- theta - lr d,
+// while it is in registers: nobody else reads it in this step, so every gradient is still taken at the values of
+// the step's start, and the row is read once and written once in all, with no staged copy (most rows of a long
+// tail are of this kind).  rank_w / rank_h: the plans' per-access flags (kSingleAccess); null: stage everything.
 // ------------------------------------------------------------------------------------------------
 template <int NV4>
-__global__ void __launch_bounds__(kBlock) k_mf_grad(const float *W, const float *H, uint32_t n_rows, uint32_t n_cols,
+__global__ void __launch_bounds__(kBlock) k_mf_grad(float *W, float *H, uint32_t n_rows, uint32_t n_cols,
                                                     int stride, const uint32_t *row, const uint32_t *col,
-                                                    const float *val, uint32_t B, float l2, float *stage,
+                                                    const float *val, uint32_t B, float l2, float lr,
+                                                    const uint32_t *rank_w, const uint32_t *rank_h, float *stage,
                                                     double *loss, SideWork sw)
 {
     __shared__ float lds[kBlock / 64];
@@ -312,8 +317,12 @@ __global__ void __launch_bounds__(kBlock) k_mf_grad(const float *W, const float 
     const bool active = c_raw < B;
     const uint32_t c = active ? c_raw : B - 1;
     Row<NV4> w, h;
-    load_row(w, W + (size_t)min(row[c], n_rows - 1) * stride, lane);
-    load_row(h, H + (size_t)min(col[c], n_cols - 1) * stride, lane);
+    const uint32_t rk = row[c], ck = col[c];
+    const bool alone_w = rank_w != nullptr && rk < n_rows && (rank_w[c] & kSingleAccess) != 0;
+    const bool alone_h = rank_h != nullptr && ck < n_cols && (rank_h[c] & kSingleAccess) != 0;
+    float *w_row = W + (size_t)min(rk, n_rows - 1) * stride, *h_row = H + (size_t)min(ck, n_cols - 1) * stride;
+    load_row(w, w_row, lane);
+    load_row(h, h_row, lane);
     const float dot = group_sum(partial_dot(w, h));
     const float nw = group_sum(partial_dot(w, w));
     const float nh = group_sum(partial_dot(h, h));
@@ -327,20 +336,33 @@ __global__ void __launch_bounds__(kBlock) k_mf_grad(const float *W, const float 
                               -2.f * err * w.v[q].z + 2.f * l2 * h.v[q].z, -2.f * err * w.v[q].w + 2.f * l2 * h.v[q].w);
     }
     if (active) {
-        store_row(stage + (size_t)c * stride, dw, lane);
-        store_row(stage + ((size_t)B + c) * stride, dh, lane);
+        if (alone_w) {
+#pragma unroll
+            for (int q = 0; q < NV4; ++q) axpy4(w.v[q], -lr, dw.v[q]);
+            store_row(w_row, w, lane);
+        } else {
+            store_row(stage + (size_t)c * stride, dw, lane);
+        }
+        if (alone_h) {
+#pragma unroll
+            for (int q = 0; q < NV4; ++q) axpy4(h.v[q], -lr, dh.v[q]);
+            store_row(h_row, h, lane);
+        } else {
+            store_row(stage + ((size_t)B + c) * stride, dh, lane);
+        }
     }
     block_add_loss((active && lane == 0) ? err * err + l2 * (nw + nh) : 0.f, loss, lds);
 }
 
 template <int NV4>
-static void launch_mf_grad(nups_ctx *ctx, const nups_batch &b, const SideWork &sw, size_t side_lds)
+static void launch_mf_grad(nups_ctx *ctx, const nups_batch &b, const uint32_t *rank_w, const uint32_t *rank_h,
+                           const SideWork &sw, size_t side_lds)
 {
     const Table &tw = ctx->tab[0], &th = ctx->tab[1];
     const uint32_t blocks = xcd_grid((uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock));
-    hipLaunchKernelGGL(k_mf_grad<NV4>, dim3(sw.blocks + blocks), dim3(kBlock), side_lds, ctx->stream,
-                       (const float *)tw.data, (const float *)th.data, (uint32_t)tw.num_keys, (uint32_t)th.num_keys,
-                       tw.stride, b.k0, b.k1, b.val, (uint32_t)b.B, b.l2, ctx->stage, ctx->loss_cur, sw);
+    hipLaunchKernelGGL(k_mf_grad<NV4>, dim3(sw.blocks + blocks), dim3(kBlock), side_lds, ctx->stream, tw.data, th.data,
+                       (uint32_t)tw.num_keys, (uint32_t)th.num_keys, tw.stride, b.k0, b.k1, b.val, (uint32_t)b.B, b.l2,
+                       b.lr, rank_w, rank_h, ctx->stage, ctx->loss_cur, sw);
 }
 
 nups_status plan_step_mf(nups_ctx *ctx, nups_prepared &p)
@@ -361,10 +383,15 @@ nups_status run_step_mf(nups_ctx *ctx, nups_prepared &p)
     ctx->loss_cur = p.loss_dev;   // zeroed by the step's plan construction
     if (B == 0) return NUPS_OK;
     size_t side_lds = 0;
+    // Rows and columns with a single access are updated by the gradient kernel; with norm clipping on, every
+    // update goes through the update kernel, which measures and clips the hot keys' updates.
+    const bool singles_in_place = !(ctx->clip_factor > 0.0f);
+    const uint32_t *rank_w = singles_in_place ? p.plan[0].a.rank : nullptr;
+    const uint32_t *rank_h = singles_in_place ? p.plan[1].a.rank : nullptr;
     {
         const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
-#define CALL(N) launch_mf_grad<N>(ctx, b, sw, side_lds)
+#define CALL(N) launch_mf_grad<N>(ctx, b, rank_w, rank_h, sw, side_lds)
         NUPS_FOR_EACH_ROW_WIDTH(tw.stride, CALL)
 #undef CALL
         NUPS_HIP(hipGetLastError());
@@ -374,9 +401,10 @@ nups_status run_step_mf(nups_ctx *ctx, nups_prepared &p)
         PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
         if ((st = refresh_clip_bounds(ctx)) != NUPS_OK) return st;
         const TableUpdate<SrcStaged, OptSgd> uw{&p.plan[0], partial_of(ctx, p, 0), tw.data, nullptr,
-                                                SrcStaged{ctx->stage}, sgd_rule(ctx, 0, b.lr)};
+                                                SrcStaged{ctx->stage, singles_in_place}, sgd_rule(ctx, 0, b.lr)};
         const TableUpdate<SrcStaged, OptSgd> uh{&p.plan[1], partial_of(ctx, p, 1), th.data, nullptr,
-                                                SrcStaged{ctx->stage + (size_t)B * tw.stride}, sgd_rule(ctx, 1, b.lr)};
+                                                SrcStaged{ctx->stage + (size_t)B * tw.stride, singles_in_place},
+                                                sgd_rule(ctx, 1, b.lr)};
         if ((st = launch_apply2(ctx->stream, tw.stride, uw, uh, sw, side_lds)) != NUPS_OK) return st;
     }
     return NUPS_OK;
