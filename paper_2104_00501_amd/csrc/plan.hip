@@ -73,7 +73,7 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
     }
     a.num_keys = (uint32_t)t.num_keys;
     a.max_chunks = (uint32_t)max_chunks(pl.cap_n);
-    a.rank_items = t.stride <= 128 ? 2u : 4u;   // narrow-row carriers run at full occupancy: keep their LDS small
+    a.rank_items = 4u;   // accesses per thread of the rank phase (2 measured slower, also in narrow-row carriers)
     a.words = (uint32_t)words;
     a.bitmap_tiles = (uint32_t)((words + kScanTile - 1) / kScanTile);
     a.error_flag = ctx->error_flag;
