@@ -250,7 +250,7 @@ __device__ __forceinline__ void apply_short_item(const ApplyArgs &a, const Src &
     Row<NV4> acc, t, g;
     zero_row(acc);
     sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
-    opt.template load<NV4>(t, g, row, state_row, lane);
+    opt.template load<NV4>(t, g, row, state_row, lane);   // after the sum: requesting it before costs registers, measured slower
     if (opt.clips() && a.hot_bits != nullptr && in_hot_set(key, a.hot_bits)) opt.template clip<NV4>(acc, lane);
     opt.template finish<NV4>(t, g, row, state_row, acc, lane);
 }
@@ -291,9 +291,25 @@ __device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &
         __syncthreads();
         update = *last_arrival != 0;
         if (update) {
-            if (group == 0) {        // chunk order, four partial rows in flight; every chunk has arrived
+            const float *prow = a.partial + (size_t)base * a.stride;
+            if (nch > 8) {           // many chunks: every group adds an interleaved share, combined in group order
                 zero_row(acc);
-                const float *prow = a.partial + (size_t)base * a.stride;
+                for (uint32_t ch = group; ch < nch; ch += kGroupsPerBlock) {
+                    Row<NV4> r;
+                    load_row_device_scope(r, prow + (size_t)ch * a.stride, lane);
+                    axpy_row(acc, 1.0f, r);
+                }
+                if (group > 0) store_row(part + (size_t)(group - 1) * a.stride, acc, lane);   // LDS is free again
+                __syncthreads();
+                if (group == 0) {
+                    for (int g = 1; g < kGroupsPerBlock; ++g) {
+                        Row<NV4> r;
+                        load_row(r, part + (size_t)(g - 1) * a.stride, lane);
+                        axpy_row(acc, 1.0f, r);
+                    }
+                }
+            } else if (group == 0) { // chunk order, four partial rows in flight; every chunk has arrived
+                zero_row(acc);
                 uint32_t ch = 0;
                 for (; ch + 3 < nch; ch += 4) {
                     Row<NV4> r0, r1, r2, r3;
