@@ -47,6 +47,19 @@ __device__ __forceinline__ float row_move(float x)
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), kCtrl, 0xF, 0xF, false));
 }
 
+// Lane kLane's x of each 16-lane row, to every lane of that row.
+template <int kLane>
+__device__ __forceinline__ uint32_t group_share(uint32_t x)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x150 + kLane, 0xF, 0xF, false);   // row_newbcast
+}
+
+template <int kLane>
+__device__ __forceinline__ float group_share(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x150 + kLane, 0xF, 0xF, false));
+}
+
 // Sum over the 16 lanes of a row group; every lane of the group receives the total.  Neighbour in the pair, other
 // pair of the quad, mirror image in the half row (the other quad), mirror image in the row (the other half).
 __device__ __forceinline__ float group_sum(float x)

@@ -20,7 +20,8 @@ struct SrcStaged {
     bool singles_done = false;   // the gradient kernel has updated the keys with a single access itself
     __device__ __forceinline__ bool done_already(uint32_t) const { return singles_done; }
     __device__ __forceinline__ float coef(uint32_t) const { return 1.0f; }
-    __device__ __forceinline__ const float *row(uint32_t i, int stride) const { return stage + (size_t)i * stride; }
+    __device__ __forceinline__ const float *rows() const { return stage; }
+    __device__ __forceinline__ uint32_t row_number(uint32_t i) const { return i; }
 };
 
 // SGNS output side: access i < B is the context word of pair i, access B + p is negative p (pair p / K).
@@ -38,10 +39,11 @@ struct SrcSgnsOut {
     {
         return i < B ? coefs[(size_t)i * (K + 1)] : coefs[(size_t)((i - B) / K) * (K + 1) + 1 + (i - B) % K];
     }
-    __device__ __forceinline__ const float *row(uint32_t i, int stride) const
+    __device__ __forceinline__ const float *rows() const { return center_rows; }
+    __device__ __forceinline__ uint32_t row_number(uint32_t i) const
     {
         const uint32_t slot = center_slot[pair_of(i)];
-        return center_rows + (size_t)(slot == kBadIndex ? 0u : slot) * stride;   // bad center key: flagged, row 0 used
+        return slot == kBadIndex ? 0u : slot;   // bad center key: flagged, row 0 used
     }
 };
 
@@ -56,11 +58,12 @@ struct SrcKgeEntity {
     // i: the only access of its key
     __device__ __forceinline__ bool done_already(uint32_t i) const { return i >= 2 * B; }
     __device__ __forceinline__ float coef(uint32_t i) const { return i < 2 * B ? 1.0f : coefs[i - 2 * B]; }
-    __device__ __forceinline__ const float *row(uint32_t i, int stride) const
+    __device__ __forceinline__ const float *rows() const { return stage; }
+    __device__ __forceinline__ uint32_t row_number(uint32_t i) const
     {
-        if (i < 2 * B) return stage + (size_t)i * stride;
+        if (i < 2 * B) return i;
         const uint32_t p = i - 2 * B, e = p / nn;
-        return stage + (size_t)(((p % nn) < nh ? 2 * B : 3 * B) + e) * stride;
+        return ((p % nn) < nh ? 2 * B : 3 * B) + e;
     }
 };
 
@@ -189,30 +192,50 @@ struct ApplyArgs {
     uint32_t max_chunks;   // capacity of the chunk lists and of `partial`
 };
 
-// Sums accesses first, first+step, ... < last of a segment into acc (four row loads in flight).
+// Four accesses of a batch of sixteen: their coefficients and source row numbers sit in lanes kFirst .. kFirst + 3
+// of the group (c, r); m = accesses in the batch, kFirst < m.  The rows are requested together.
+template <int NV4, int kFirst>
+__device__ __forceinline__ void sum_four(Row<NV4> &acc, const float *rows, uint32_t r, float c, uint32_t m, int stride,
+                                         int lane)
+{
+    const uint32_t i0 = group_share<kFirst>(r), i1 = group_share<kFirst + 1>(r), i2 = group_share<kFirst + 2>(r),
+                   i3 = group_share<kFirst + 3>(r);
+    Row<NV4> r0, r1, r2, r3;
+    load_row(r0, rows + (size_t)i0 * stride, lane);
+    if (kFirst + 1 < m) load_row(r1, rows + (size_t)i1 * stride, lane);
+    if (kFirst + 2 < m) load_row(r2, rows + (size_t)i2 * stride, lane);
+    if (kFirst + 3 < m) load_row(r3, rows + (size_t)i3 * stride, lane);
+    const float c0 = group_share<kFirst>(c), c1 = group_share<kFirst + 1>(c), c2 = group_share<kFirst + 2>(c),
+                c3 = group_share<kFirst + 3>(c);
+    axpy_row(acc, c0, r0);
+    if (kFirst + 1 < m) axpy_row(acc, c1, r1);
+    if (kFirst + 2 < m) axpy_row(acc, c2, r2);
+    if (kFirst + 3 < m) axpy_row(acc, c3, r3);
+}
+
+// Sums accesses first, first + step, ... < last of a segment into acc, sixteen at a time: lane l of the group
+// fetches the l-th access's number, coefficient and source row number, so the dependent reads that lead to a row's
+// address are paid once per sixteen accesses rather than once per access; the rows are then read four at a time.
+// Every lane of the group must call it with the same arguments.
 template <int NV4, class Src>
 __device__ __forceinline__ void sum_segment(Row<NV4> &acc, const Src &src, const uint32_t *perm, uint32_t first,
                                             uint32_t last, uint32_t step, int stride, int lane)
 {
-    uint32_t t = first;
-    for (; t + 3 * step < last; t += 4 * step) {
-        const uint32_t i0 = perm[t], i1 = perm[t + step], i2 = perm[t + 2 * step], i3 = perm[t + 3 * step];
-        Row<NV4> r0, r1, r2, r3;
-        load_row(r0, src.row(i0, stride), lane);
-        load_row(r1, src.row(i1, stride), lane);
-        load_row(r2, src.row(i2, stride), lane);
-        load_row(r3, src.row(i3, stride), lane);
-        const float c0 = src.coef(i0), c1 = src.coef(i1), c2 = src.coef(i2), c3 = src.coef(i3);
-        axpy_row(acc, c0, r0);
-        axpy_row(acc, c1, r1);
-        axpy_row(acc, c2, r2);
-        axpy_row(acc, c3, r3);
-    }
-    for (; t < last; t += step) {
-        const uint32_t i = perm[t];
-        Row<NV4> r;
-        load_row(r, src.row(i, stride), lane);
-        axpy_row(acc, src.coef(i), r);
+    const float *rows = src.rows();
+    for (uint32_t t0 = first; t0 < last; t0 += kGroup * step) {
+        const uint32_t t = t0 + (uint32_t)lane * step;
+        uint32_t r = 0;
+        float c = 0.0f;
+        if (t < last) {
+            const uint32_t i = perm[t];
+            c = src.coef(i);
+            r = src.row_number(i);
+        }
+        const uint32_t m = min((uint32_t)kGroup, (last - t0 + step - 1) / step);
+        sum_four<NV4, 0>(acc, rows, r, c, m, stride, lane);
+        if (m > 4) sum_four<NV4, 4>(acc, rows, r, c, m, stride, lane);
+        if (m > 8) sum_four<NV4, 8>(acc, rows, r, c, m, stride, lane);
+        if (m > 12) sum_four<NV4, 12>(acc, rows, r, c, m, stride, lane);
     }
 }
 
@@ -250,7 +273,7 @@ __device__ __forceinline__ void apply_short_item(const ApplyArgs &a, const Src &
     Row<NV4> acc, t, g;
     zero_row(acc);
     sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
-    opt.template load<NV4>(t, g, row, state_row, lane);   // after the sum: requesting it before costs registers, measured slower
+    opt.template load<NV4>(t, g, row, state_row, lane);   // after the sum: results are waited for in issue order, an early request of the cold row holds up the sum's first reads
     if (opt.clips() && a.hot_bits != nullptr && in_hot_set(key, a.hot_bits)) opt.template clip<NV4>(acc, lane);
     opt.template finish<NV4>(t, g, row, state_row, acc, lane);
 }
