@@ -27,7 +27,7 @@ constexpr int kLossStride = 16;
 // Flag in rank[i]: access i is the only access of its key in this step (its position is then 0).
 constexpr uint32_t kSingleAccess = 0x80000000u;
 constexpr uint32_t kLongSegment = 16; // segments with more accesses are summed by whole workgroups, in chunks
-constexpr uint32_t kChunk = 128;      // accesses of a long segment that one workgroup sums
+constexpr uint32_t kChunk = 256;      // accesses of a long segment that one workgroup sums
 constexpr uint32_t kBadIndex = 0xFFFFFFFFu;
 constexpr int kSlotItems = 2;                       // accesses per thread in the slot phase of the preparatory work
 constexpr int kSlotTile = kBlock * kSlotItems;
