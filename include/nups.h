@@ -264,7 +264,10 @@ nups_status nups_step(nups_ctx *ctx, const nups_batch *batch, double *loss_sum_h
  * have not been carried yet, then the step's two launches.  So with steps prepared three
  * ahead (prepare t+3, run t) a step costs two launches and its preparatory work hides inside
  * earlier steps; prepared less far ahead, part of it runs on its own; nups_step(batch) is
- * prepare followed by run and runs all of it on its own.  The results are the same in every
+ * prepare followed by run and runs all of it on its own.  A NUPS_TASK_MF step that is prepared
+ * while three others are still under construction (steps prepared four ahead) starts its chain
+ * one launch later, which puts its long phases into the gradient launches (its update kernel is
+ * short); that is the fastest arrangement for this task.  The results are the same in every
  * case.  The key arrays of the batch (and the sampled keys or batch-local key arrays it
  * points to) must stay valid and unchanged until the step has run; arrays written by work
  * enqueued on the stream before nups_prepare_step are seen complete.  A prepared step is

@@ -113,6 +113,7 @@ static nups_status get_prepared(nups_ctx *ctx, nups_prepared **out)
     nups_status st = NUPS_OK;
     p->phases.clear();
     p->next_phase = 0;
+    p->lead_launches = 0;
     if (!p->loss_dev && !hip_ok(hipMalloc((void **)&p->loss_dev, sizeof(double) * kLossSlots * kLossStride), "loss accumulator"))
         st = NUPS_ERR_DEVICE;
     if (st != NUPS_OK) { ctx->prepared_free.push_back(p); return st; }
@@ -589,6 +590,11 @@ nups_status nups_prepare_step(nups_ctx *ctx, const nups_batch *b, nups_prepared 
     if (ctx->profiling) {   // every phase as a launch of its own, timed
         if ((st = flush_side_work(ctx, p)) != NUPS_OK) { p->live = false; ctx->prepared_free.push_back(p); return st; }
     } else {
+        // Which launch carries which phase matters.  A factorisation step's update kernel is much shorter than the
+        // rank phase, which by default rides in the update launch of the next step but one; when the caller prepares
+        // four steps ahead (three are still under construction), the chain starts one launch later, so that the long
+        // phases (tiles, rank, scatter) ride in the gradient launches and the short ones in the update launches.
+        p->lead_launches = (b->task == NUPS_TASK_MF && ctx->pending.size() >= 3) ? 1 : 0;
         ctx->pending.push_back(p);
     }
     *out = p;

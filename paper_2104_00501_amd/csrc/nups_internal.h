@@ -176,6 +176,7 @@ struct nups_prepared {
     int n_plans = 0;
     std::vector<nups::SideItem> phases;
     size_t next_phase = 0;         // phases before this one have been enqueued
+    int lead_launches = 0;         // launches that pass before the first phase rides in one (see nups_prepare_step)
     double *loss_dev = nullptr;    // this step's loss accumulator: kLossSlots partial sums, kLossStride doubles apart
     uint32_t *negs_buf = nullptr;  // negatives drawn by the step itself (batch.dist)
     size_t negs_cap = 0;

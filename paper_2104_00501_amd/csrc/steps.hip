@@ -39,6 +39,11 @@ SideWork take_side_work(nups_ctx *ctx, size_t *lds_bytes, uint32_t max_wgs_per_p
     size_t lds = 0;
     for (auto it = ctx->pending.begin(); it != ctx->pending.end() && sw.n < kMaxSide;) {
         nups_prepared *p = *it;
+        if (p->lead_launches > 0) {   // this step's phases start one launch later
+            --p->lead_launches;
+            ++it;
+            continue;
+        }
         const SideItem &ph = p->phases[p->next_phase++];
         sw.item[sw.n] = ph;
         sw.item[sw.n].wgs = std::min(ph.blocks, max_wgs_per_phase);

@@ -237,7 +237,7 @@ def _run_pipelined(ctx, batches, depth):
     return loss
 
 
-@pytest.mark.parametrize("depth", [0, 3])
+@pytest.mark.parametrize("depth", [0, 3, 4, 6])
 def test_mf_pipelined_steps_match_the_oracle(depth):
     # the preparatory work of later steps rides in the gradient and update launches of earlier ones
     nr, nc, d, B, steps = 200_000, 20_000, 100, 8192, 7
