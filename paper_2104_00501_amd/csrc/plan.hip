@@ -56,7 +56,7 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
         const size_t cap = n + n / 4 + 1024;
         for (uint32_t **b : {&a.uniq, &a.count, &a.perm, &a.slot, &a.rank})
             if ((st = grow_u32(b, cap, false)) != NUPS_OK) return st;
-        if ((st = grow_u32(&a.cnt_work, cap, true)) != NUPS_OK) return st;
+        if ((st = grow_u32(&a.cnt_work, (cap + kScanTile - 1) / kScanTile * kScanTile, true)) != NUPS_OK) return st;   // whole tiles
         if ((st = grow_u32(&a.seg, cap + 1, false)) != NUPS_OK) return st;
         if ((st = grow_u32(&a.chunk_seg, max_chunks(cap), false)) != NUPS_OK) return st;
         if ((st = grow_u32(&a.chunk_base, max_chunks(cap), false)) != NUPS_OK) return st;
