@@ -20,7 +20,11 @@
  *    host (stated per call).
  *  - A table is a dense [num_keys, row_stride] fp32 array; the first `dim` floats of
  *    a row are the parameter, the rest is padding that stays zero.  row_stride must be
- *    a multiple of 64 floats (at most 1024); keys are uint32 row numbers.
+ *    64, 128, 192, 256, 320, 384, 512 or 1024 floats (the row widths that kernels are
+ *    built for; pad narrower rows up to the next of them); keys are uint32 row numbers.
+ *    nups_step works on tables 0 and 1, which must have the same row_stride; for
+ *    NUPS_TASK_KGE (complex rows: real parts from float 0, imaginary parts from float
+ *    row_stride / 2) it must be 128, 256, 384 or 512.
  *  - Keys outside [0, num_keys) never cause an out-of-range access: the kernels skip
  *    or clamp them, raise a device-side flag, and the next call that synchronises
  *    (nups_step with a loss pointer, nups_debug_structure, nups_check) returns
@@ -68,7 +72,7 @@ typedef enum { NUPS_TASK_SGNS = 1, NUPS_TASK_MF = 2, NUPS_TASK_KGE = 3 } nups_ta
  * store of Section 3.1).  tables_dev[t] is the device address of table t,
  * num_keys[t] x row_stride[t] floats.  hip_stream is a hipStream_t (NULL = the
  * default stream).  Errors: NUPS_ERR_ARG on null pointers, dim <= 0, dim > row_stride,
- * row_stride not a multiple of 64 or > 1024, num_keys outside 1..2^32-1;
+ * a row_stride that is not one of the supported widths, num_keys outside 1..2^32-1;
  * NUPS_ERR_DEVICE if no device is usable.
  */
 nups_status nups_init(nups_ctx **out, int n_tables, float *const *tables_dev, const int64_t *num_keys,
@@ -149,9 +153,6 @@ nups_status nups_build_alias_table(const double *weights_host, int64_t num_keys,
  * NUPS_LONGTERM; ignored otherwise.  seed keys the counter-based generator: sample
  * i of the handle prepared for step t is a pure function of (seed, dist, t, i).
  */
-nups_status nups_register_distribution(nups_ctx *ctx, int table, const double *weights_host,
-                                       nups_scheme scheme, int32_t U, int32_t G, int64_t P, int32_t R,
-                                       uint64_t seed, nups_dist **out);
 nups_status nups_register_distribution(nups_ctx *ctx, int table, const double *weights_host,
                                        nups_scheme scheme, int32_t U, int32_t G, int64_t P, int32_t R,
                                        uint64_t seed, nups_dist **out);

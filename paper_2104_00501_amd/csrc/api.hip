@@ -86,6 +86,28 @@ static void free_prepared(nups_prepared *p)
     delete p;
 }
 
+// After a bad key (or a key array changed behind a prepared step) the scratch maps of a structure may hold marks
+// of accesses that were dropped, which the phases do not find again to clear.  Returns the maps and counters of
+// every structure that is not under construction to all-zero, the state that the next build starts from.
+static nups_status reset_idle_plans(nups_ctx *ctx)
+{
+    for (nups_prepared *q : ctx->prepared_all) {
+        if (q->live) continue;   // under construction or waiting to run: its marks are in use
+        for (Plan &pl : q->plan) {
+            PlanArgs &a = pl.a;
+            if (pl.cap_words) {
+                NUPS_HIP(hipMemsetAsync(a.bytemap, 0, pl.cap_words * 32, ctx->stream));
+                NUPS_HIP(hipMemsetAsync(a.wordmap, 0, pl.cap_words, ctx->stream));
+            }
+            if (pl.cap_n) {
+                NUPS_HIP(hipMemsetAsync(a.cnt_work, 0, sizeof(uint32_t) * ((pl.cap_n + kScanTile - 1) / kScanTile * kScanTile), ctx->stream));
+                NUPS_HIP(hipMemsetAsync(a.chunk_done, 0, sizeof(uint32_t) * max_chunks(pl.cap_n), ctx->stream));
+            }
+        }
+    }
+    return NUPS_OK;
+}
+
 // Waits for the stream and turns a raised device flag into an error.
 static nups_status sync_and_check(nups_ctx *ctx)
 {
@@ -93,6 +115,8 @@ static nups_status sync_and_check(nups_ctx *ctx)
     NUPS_HIP(hipStreamSynchronize(ctx->stream));
     if (*ctx->flag_pinned != 0) {
         NUPS_HIP(hipMemsetAsync(ctx->error_flag, 0, sizeof(uint32_t), ctx->stream));
+        nups_status st = reset_idle_plans(ctx);
+        if (st != NUPS_OK) return st;
         NUPS_HIP(hipStreamSynchronize(ctx->stream));
         return fail(NUPS_ERR_KEY_RANGE, "a key was outside its table (it was skipped)");
     }
@@ -153,6 +177,11 @@ static nups_status check_batch(nups_ctx *ctx, const nups_batch *b)
         return fail(NUPS_ERR_ARG, "nups_step: give only one of negs, sample and dist");
     if (b->dist) {
         if (b->dist->ctx != ctx) return fail(NUPS_ERR_ARG, "nups_step: the distribution is of another context");
+        // the drawn keys index the table that the task's negatives live in (Section 2.2: output vectors; entities)
+        if (b->task == NUPS_TASK_SGNS && b->dist->table != 1)
+            return fail(NUPS_ERR_ARG, "nups_step: SGNS negatives index table 1: register the distribution there");
+        if (b->task == NUPS_TASK_KGE && b->dist->table != 0)
+            return fail(NUPS_ERR_ARG, "nups_step: KGE negatives index table 0: register the distribution there");
         if (b->dist->scheme == NUPS_NONCONFORM && !b->dist->local_a)
             return fail(NUPS_ERR_STATE, "nups_step: call nups_set_local_keys first");
         if (b->dist->scheme == NUPS_NONCONFORM && b->B * nn > b->dist->local_n * (int64_t)b->dist->per_example)
@@ -210,8 +239,9 @@ nups_status nups_init(nups_ctx **out, int n_tables, float *const *tables_dev, co
         if (!tables_dev[t]) return fail(NUPS_ERR_ARG, "nups_init: null table");
         if (num_keys[t] < 1 || num_keys[t] > 0xFFFFFFFFll) return fail(NUPS_ERR_ARG, "nups_init: num_keys out of range");
         if (dim[t] < 1 || dim[t] > row_stride[t]) return fail(NUPS_ERR_ARG, "nups_init: need 1 <= dim <= row_stride");
-        if (row_stride[t] % 64 != 0 || row_stride[t] > kMaxStride)
-            return fail(NUPS_ERR_ARG, "nups_init: row_stride must be a multiple of 64 floats, at most 1024");
+        const int w = row_stride[t] / 64;   // float4 per lane of a row group: the widths that kernels are built for
+        if (row_stride[t] % 64 != 0 || !(w == 1 || w == 2 || w == 3 || w == 4 || w == 5 || w == 6 || w == 8 || w == 16))
+            return fail(NUPS_ERR_ARG, "nups_init: row_stride must be 64, 128, 192, 256, 320, 384, 512 or 1024 floats");
     }
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(NUPS_ERR_DEVICE, "nups_init: no HIP device");
@@ -349,11 +379,12 @@ nups_status nups_push(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_
     if (st != NUPS_OK) return st;
     p->n_plans = 1;
     p->plan[0].table = table;
-    if ((st = ensure_plan_capacity(ctx, t, p->plan[0], (size_t)n)) != NUPS_OK) return st;
+    if ((st = ensure_plan_capacity(ctx, t, p->plan[0], (size_t)n)) == NUPS_OK)
+        st = ensure_partial(ctx, max_chunks(p->plan[0].cap_n) * (size_t)t.stride);
+    if (st != NUPS_OK) { ctx->prepared_free.push_back(p); return st; }   // nothing was enqueued: the object is free again
     p->plan[0].a.src = KeySource{{keys_dev, nullptr, nullptr}, {(uint32_t)n, 0, 0}};
     p->plan[0].a.n = p->plan[0].a.mark_n = (uint32_t)n;
     p->plan[0].a.zero_loss = nullptr;
-    if ((st = ensure_partial(ctx, max_chunks(p->plan[0].cap_n) * (size_t)t.stride)) != NUPS_OK) return st;
     build_phases(*p, SampleArgs{}, -1);
     st = flush_side_work(ctx, p);
     if (st == NUPS_OK && n > 0) st = launch_push_apply(ctx, t, p->plan[0], updates_dev);
@@ -579,12 +610,10 @@ nups_status nups_prepare_step(nups_ctx *ctx, const nups_batch *b, nups_prepared 
     default: st = plan_step_kge(ctx, *p); mark_plan = 0; break;
     }
     if (st != NUPS_OK) { ctx->prepared_free.push_back(p); return st; }
-    if (n_draw > 0) {
-        // the drawn keys are marked as they are drawn (if they index the table that the plan is for); the plan's own
-        // first phase marks the keys before them
-        if (b->dist->table == p->plan[mark_plan].table) p->plan[mark_plan].a.mark_n -= (uint32_t)n_draw;
-        else mark_plan = -1;
-    }
+    // the drawn keys are marked as they are drawn (check_batch: they index the table that plan `mark_plan` is for);
+    // the plan's own first phase marks the keys before them
+    if (n_draw > 0) p->plan[mark_plan].a.mark_n -= (uint32_t)n_draw;
+    else mark_plan = -1;
     build_phases(*p, draw, mark_plan);
     p->live = true;
     if (ctx->profiling) {   // every phase as a launch of its own, timed

@@ -420,13 +420,14 @@ __device__ __forceinline__ void scatter_block(const PlanArgs &a, uint32_t vb)
 {
     const uint32_t i = vb * kBlock + threadIdx.x;
     if (i >= a.n) return;
+    const uint32_t key = source_key(a.src, i);
+    if (key < a.num_keys) a.bytemap[key] = 0;   // also for an access that is dropped below
     const uint32_t u = a.slot[i];
     if (u == kBadIndex) return;
     const uint32_t r = a.rank[i];
     const uint32_t first = a.seg[u], next = a.seg[u + 1];
     if (first + r >= a.n) return;   // cannot happen with unchanged key arrays
     a.perm[first + r] = i;
-    a.bytemap[source_key(a.src, i)] = 0;
     if (r == 0) {
         a.cnt_work[counter_index(u)] = 0;
         if (next - first == 1) a.rank[i] = kSingleAccess;   // the key's only access: a gradient kernel may update the row itself

@@ -126,33 +126,39 @@ static nups_status refresh_clip_bounds(nups_ctx *ctx)
 }
 
 // ------------------------------------------------------------------------------------------------
-// pull: values[i, :] = table[keys[i], :]; one thread per float4, zero rows for keys out of range.
+// pull: values[i, :] = table[keys[i], :] (Section 3.1).  One 16-lane group per row: a load instruction of a group
+// reads 256 contiguous bytes, a wavefront keeps four rows in flight; zero rows for keys out of range.
 // ------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kBlock) k_pull(const float *table, uint32_t num_keys, int stride4,
-                                                 const uint32_t *keys, uint64_t total4, float *values,
+template <int NV4>
+__global__ void __launch_bounds__(kBlock) k_pull(const float *table, uint32_t num_keys, int stride,
+                                                 const uint32_t *keys, uint32_t n, float *values,
                                                  uint32_t *error_flag)
 {
-    const uint64_t idx = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (idx >= total4) return;
-    const uint64_t i = idx / stride4;
-    const uint32_t q = (uint32_t)(idx % stride4);
+    const int lane = threadIdx.x & (kGroup - 1);
+    const uint32_t i = (blockIdx.x * kBlock + threadIdx.x) / kGroup;
+    if (i >= n) return;
     const uint32_t key = keys[i];
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (key < num_keys) v = reinterpret_cast<const float4 *>(table)[(size_t)key * stride4 + q];
-    else if (q == 0) atomicOr(error_flag, 1u);
-    reinterpret_cast<float4 *>(values)[idx] = v;
+    Row<NV4> r;
+    if (key < num_keys) {
+        load_row(r, table + (size_t)key * stride, lane);
+    } else {
+        zero_row(r);
+        if (lane == 0) atomicOr(error_flag, 1u);
+    }
+    store_row(values + (size_t)i * stride, r, lane);
 }
 
 nups_status launch_pull(nups_ctx *ctx, const Table &t, const uint32_t *keys, int64_t n, float *values)
 {
     if (n == 0) return NUPS_OK;
     PhaseScope scope(ctx, NUPS_PHASE_PULL, ctx->stream);
-    const int stride4 = t.stride / 4;
-    const uint64_t total4 = (uint64_t)n * stride4;
-    const uint64_t blocks = (total4 + kBlock - 1) / kBlock;
-    if (blocks > 0x7FFFFFFFull) return fail(NUPS_ERR_ARG, "nups_pull: too many rows for one call");
-    hipLaunchKernelGGL(k_pull, dim3((uint32_t)blocks), dim3(kBlock), 0, ctx->stream, (const float *)t.data,
-                       (uint32_t)t.num_keys, stride4, keys, total4, values, ctx->error_flag);
+    if (n > 0x7FFFFFFFll) return fail(NUPS_ERR_ARG, "nups_pull: too many rows for one call");
+    const uint32_t blocks = (uint32_t)((n + kGroupsPerBlock - 1) / kGroupsPerBlock);
+#define CALL(N)                                                                                                   \
+    hipLaunchKernelGGL(k_pull<N>, dim3(blocks), dim3(kBlock), 0, ctx->stream, (const float *)t.data,              \
+                       (uint32_t)t.num_keys, t.stride, keys, (uint32_t)n, values, ctx->error_flag)
+    NUPS_FOR_EACH_ROW_WIDTH(t.stride, CALL)
+#undef CALL
     NUPS_HIP(hipGetLastError());
     return NUPS_OK;
 }

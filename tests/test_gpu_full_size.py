@@ -1,13 +1,14 @@
 """GPU parity at the full sizes of the benchmark configurations, run the way bench.py runs them (steps prepared
-ahead, the preparatory work riding in earlier launches): every row that the steps touch is compared with the
-oracle's, and every other row of the tables must be bit-identical to what it was."""
+ahead, the preparatory work riding in earlier launches), over 100 steps each: every row that the steps touch is
+compared with the oracle's to the 100-step bar (1e-3, element by element with a floor per row, tests/parity.py),
+and every other row of the tables must be bit-identical to what it was."""
 import numpy as np
 import pytest
 
 from oracle import oracle as orc
 from paper_2104_00501_amd import binding as nb
 from paper_2104_00501_amd import workloads as wl
-from tests.parity import dev, dev_u32, max_rel_err
+from tests.parity import TOL_100_STEPS, dev, dev_u32, param_err, update_err
 
 pytestmark = pytest.mark.gpu
 
@@ -17,12 +18,15 @@ def _touched_rows_match(t_dev, init_dev, ref_host, touched, cols, tol, what):
     touched = np.unique(np.asarray(touched, dtype=np.int64))
     changed = (t_dev != init_dev).any(dim=1).nonzero().ravel().cpu().numpy()
     assert np.isin(changed, touched).all(), what + ": a row outside the steps' keys changed"
-    got = t_dev[torch.from_numpy(touched).cuda()].cpu().numpy()
+    index = torch.from_numpy(touched).cuda()
+    got, before = t_dev[index].cpu().numpy(), init_dev[index].cpu().numpy()
     ref = ref_host[touched]
-    rel, ab = max_rel_err(got, ref, cols)
-    print("%s: %d touched rows of %d, %d changed; max rel err %.3g, max abs err %.3g"
-          % (what, len(touched), t_dev.shape[0], len(changed), rel, ab))
-    assert rel <= tol, "%s: max rel err %.3g (abs %.3g) > %.1g" % (what, rel, ab, tol)
+    rel, ab = param_err(got, ref, before, cols)
+    ue = update_err(got, ref, before, cols)
+    print("%s: %d touched rows of %d, %d changed; parameter err %.3g (abs %.3g), update err %.3g"
+          % (what, len(touched), t_dev.shape[0], len(changed), rel, ab, ue))
+    assert rel <= tol, "%s: parameter error %.3g (abs %.3g) > %.1g" % (what, rel, ab, tol)
+    assert ue <= tol, "%s: error of the total update %.3g > %.1g" % (what, ue, tol)
     pad = np.setdiff1d(np.arange(got.shape[1]), cols)
     assert np.all(got[:, pad] == 0), what + ": padding lanes changed"
 
@@ -39,17 +43,25 @@ def _run(ctx, batches, depth):
 
 
 def test_word_vectors_1m_keys_d300_bounded_reuse():
-    # the default benchmark workload: 1M keys, d = 300, 3 negatives under BOUNDED U = 4, G = 250, B = 16,384
-    V, d, B, K, U, G, window, steps, seed = 1_000_000, 300, 16_384, 3, 4, 250, 5, 5, 1004
+    # the default benchmark workload: 1M keys, d = 300, 3 negatives under BOUNDED U = 4, G = 250, B = 16,384.
+    # With summed batch gradients the plain step overflows at this configuration's learning rate well within 100
+    # steps (the oracle too: the hottest words collect over a thousand contributions per step), so the 100 steps
+    # run with the paper's remedy (Section 5.1): the updates of the 1,000 most frequent words are clipped at
+    # twice their mean norm.
+    V, d, B, K, U, G, window, steps, seed = 1_000_000, 300, 16_384, 3, 4, 250, 5, 100, 1004
     toks = wl.zipf_stream(V, 1.0, steps * B // (2 * window) + 2 * window + 2, seed)
     centers, contexts = wl.window_pairs(toks, window, 0, steps * B)
     w = wl.expected_unigram_weights(V, 1.0, 1e9)
     In = wl.uniform_table(V, d, -0.5 / d, 0.5 / d, seed)
-    Out = wl.uniform_table(V, d, -0.5 / d, 0.5 / d, seed + 1)
+    Out = np.zeros_like(In)                       # output vectors start at zero, as the configuration says
     tin, tout = dev(In), dev(Out)
     init_in, init_out = tin.clone(), tout.clone()
     ctx = nb.nups_init([tin, tout], [d, d])
     dist = nb.nups_register_distribution(ctx, 1, w, nb.NUPS_BOUNDED, U=U, G=G, seed=seed)
+    hot = np.arange(1000, dtype=np.uint32)        # keys are frequency ranks
+    nb.nups_set_hot_keys(ctx, 0, hot)
+    nb.nups_set_hot_keys(ctx, 1, hot)
+    nb.nups_set_update_clipping(ctx, 2.0)
     kc, ko = dev_u32(centers), dev_u32(contexts)
     lrs = [float(wl.linear_lr(0.025, t, 610_000)) for t in range(steps)]
     batches = [nb.make_batch(nb.NUPS_TASK_SGNS, B, kc.data_ptr() + 4 * t * B, ko.data_ptr() + 4 * t * B, n_neg=K,
@@ -57,22 +69,25 @@ def test_word_vectors_1m_keys_d300_bounded_reuse():
     loss = _run(ctx, batches, 3)
     alias = orc.alias_build(w)
     negs_all = []
+    stats_in, stats_out = np.zeros(2), np.zeros(2)
     for t in range(steps):
         sl = slice(t * B, (t + 1) * B)
         negs = orc.sample_bounded(alias, V, seed, 0, t, B * K, U, G)
         negs_all.append(negs)
-        rloss = orc.step_sgns(In, Out, d, centers[sl], contexts[sl], negs, K, lrs[t])[0]
-    assert abs(loss - rloss) <= 1e-4 * abs(rloss)
+        rloss = orc.step_sgns_clipped(In, Out, d, centers[sl], contexts[sl], negs, K, lrs[t], hot, hot, 2.0,
+                                      stats_in, stats_out)
+    assert np.isfinite(In).all() and np.isfinite(Out).all() and np.abs(In).max() < 100
+    assert abs(loss - rloss) <= TOL_100_STEPS * abs(rloss)
     cols = list(range(d))
-    _touched_rows_match(tin, init_in, In, centers, cols, 1e-4, "input vectors")
-    _touched_rows_match(tout, init_out, Out, np.concatenate([contexts] + negs_all), cols, 1e-4, "output vectors")
+    _touched_rows_match(tin, init_in, In, centers, cols, TOL_100_STEPS, "input vectors")
+    _touched_rows_match(tout, init_out, Out, np.concatenate([contexts] + negs_all), cols, TOL_100_STEPS, "output vectors")
     nb.nups_destroy(ctx)
 
 
 def test_factorisation_10m_by_1m_rank_100():
     # 10M x 1M, rank 100, 65,536 cells per step, prepared four ahead as bench.py does for this task
     import torch
-    n_rows, n_cols, d, B, steps = 10_000_000, 1_000_000, 100, 65_536, 6
+    n_rows, n_cols, d, B, steps = 10_000_000, 1_000_000, 100, 65_536, 100
     rows, cols, vals = wl.mf_cells(n_rows, n_cols, 0.8, steps * B, 1002)
     stride = wl.padded_stride(d)
     g = torch.Generator(device="cuda").manual_seed(1002)
@@ -93,16 +108,16 @@ def test_factorisation_10m_by_1m_rank_100():
     for t in range(steps):
         sl = slice(t * B, (t + 1) * B)
         rloss = orc.step_mf(W, H, d, rows[sl], cols[sl], vals[sl], 0.005, 0.01)[0]
-    assert abs(loss - rloss) <= 1e-4 * abs(rloss)
-    _touched_rows_match(tw, init_w, W, rows, list(range(d)), 1e-4, "row factors")
-    _touched_rows_match(th, init_h, H, cols, list(range(d)), 1e-4, "column factors")
+    assert abs(loss - rloss) <= TOL_100_STEPS * abs(rloss)
+    _touched_rows_match(tw, init_w, W, rows, list(range(d)), TOL_100_STEPS, "row factors")
+    _touched_rows_match(th, init_h, H, cols, list(range(d)), TOL_100_STEPS, "column factors")
     nb.nups_destroy(ctx)
 
 
 def test_complex_4p6m_entities_d500_adagrad():
     # 4.6M entities, d = 500 with AdaGrad state, 1,024 triples with 50 + 50 uniform negatives per step
     import torch
-    n_ent, n_rel, d, B, nh, nt, steps, seed = 4_600_000, 822, 500, 1024, 50, 50, 3, 1003
+    n_ent, n_rel, d, B, nh, nt, steps, seed = 4_600_000, 822, 500, 1024, 50, 50, 100, 1003
     s, r, o = wl.kge_triples(n_ent, n_rel, steps * B, seed)
     stride, half = 512, d // 2
     g = torch.Generator(device="cuda").manual_seed(seed)
@@ -120,7 +135,7 @@ def test_complex_4p6m_entities_d500_adagrad():
         return t
 
     te, tr, ge, gr = table(n_ent), table(n_rel), state(n_ent), state(n_rel)
-    init_e, init_g = te.clone(), ge.clone()
+    init_e, init_g, init_r, init_gr = te.clone(), ge.clone(), tr.clone(), gr.clone()
     E, R, GE, GR = te.cpu().numpy(), tr.cpu().numpy(), ge.cpu().numpy(), gr.cpu().numpy()
     ctx = nb.nups_init([te, tr], [d, d])
     nb.nups_set_state(ctx, 0, ge)
@@ -137,13 +152,11 @@ def test_complex_4p6m_entities_d500_adagrad():
         negs = orc.sample_conform(None, n_ent, seed, 0, t, B * (nh + nt))
         negs_all.append(negs)
         rloss = orc.step_kge(E, GE, R, GR, d, s[sl], r[sl], o[sl], negs, nh, nt, 0.1, 1e-10)[0]
-    assert abs(loss - rloss) <= 1e-4 * abs(rloss)
+    assert abs(loss - rloss) <= TOL_100_STEPS * abs(rloss)
     cols = list(range(half)) + list(range(stride // 2, stride // 2 + half))
     touched = np.concatenate([s, o] + negs_all)
-    _touched_rows_match(te, init_e, E, touched, cols, 1e-4, "entity rows")
-    _touched_rows_match(ge, init_g, GE, touched, cols, 1e-4, "entity state rows")
-    rel, _ = max_rel_err(tr.cpu().numpy(), R, cols)
-    assert rel <= 1e-4, "relation rows: max rel err %.3g" % rel
-    rel, _ = max_rel_err(gr.cpu().numpy(), GR, cols)
-    assert rel <= 1e-4, "relation state rows: max rel err %.3g" % rel
+    _touched_rows_match(te, init_e, E, touched, cols, TOL_100_STEPS, "entity rows")
+    _touched_rows_match(ge, init_g, GE, touched, cols, TOL_100_STEPS, "entity state rows")
+    _touched_rows_match(tr, init_r, R, r, cols, TOL_100_STEPS, "relation rows")
+    _touched_rows_match(gr, init_gr, GR, r, cols, TOL_100_STEPS, "relation state rows")
     nb.nups_destroy(ctx)

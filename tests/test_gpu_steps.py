@@ -1,19 +1,16 @@
 """GPU parity of the minibatch step (sample -> pull -> gradient -> aggregate -> push) against the
-CPU oracle: aggregation structure bit-exact, fp32 parameters within 1e-5 (max relative error,
-denominator floored at the RMS of the table) after one step and 1e-3 after 100 steps; the
-applied update itself within 1e-3 of the RMS update."""
+CPU oracle: aggregation structure bit-exact, fp32 parameters within 1e-5 after one step and 1e-3
+after 100 steps, the applied update within 2e-5 after one step; both errors are taken element by
+element with a floor per row (tests/parity.py), and rows that a step does not touch are bit-identical."""
 import numpy as np
 import pytest
 
 from oracle import oracle as orc
 from paper_2104_00501_amd import binding as nb
 from paper_2104_00501_amd import workloads as wl
-from tests.parity import dev, dev_u32, host_u32, max_rel_err, update_err
+from tests.parity import TOL_100_STEPS, TOL_ONE_STEP, TOL_UPDATE, assert_table, dev, dev_u32, host_u32
 
 pytestmark = pytest.mark.gpu
-
-TOL_ONE_STEP = 1e-5
-TOL_100_STEPS = 1e-3
 
 
 def _structure(ctx, table, n):
@@ -29,19 +26,9 @@ def _assert_structure(ctx, table, n, ref):
     assert np.array_equal(k, ref.keys) and np.array_equal(c, ref.counts)
 
 
-TOL_UPDATE = 1e-3
-
-
-def _assert_close(got, ref, cols, tol, what, before=None):
-    rel, ab = max_rel_err(got, ref, cols)
-    print("%s: max rel err %.3g, max abs err %.3g" % (what, rel, ab))
-    assert rel <= tol, "%s: max rel err %.3g (abs %.3g) > %.1g" % (what, rel, ab, tol)
-    if before is not None:
-        ue = update_err(got, ref, before, cols)
-        print("%s: update err %.3g" % (what, ue))
-        assert ue <= TOL_UPDATE, "%s: update error %.3g of the RMS update" % (what, ue)
-    pad = np.setdiff1d(np.arange(got.shape[1]), cols)
-    assert np.all(got[:, pad] == 0), what + ": padding lanes changed"
+def _assert_close(got, ref, cols, tol, what, before):
+    """`before`: the table before the step(s).  One step: the update bar is TOL_UPDATE; several: the parameters' bar."""
+    assert_table(got, ref, before, cols, tol, what, tol_update=TOL_UPDATE if tol <= TOL_ONE_STEP else tol)
 
 
 # ------------------------------------------------------------------------------------------ SGNS
@@ -112,8 +99,8 @@ def test_sgns_100_steps_small_configuration():
         orc.step_sgns(rin, rout, d, c, o, negs, K, lr)
     assert np.isfinite(rin).all() and np.abs(rin).max() < 10 and np.abs(rout).max() > 0.01
     cols = list(range(d))
-    _assert_close(tin.cpu().numpy(), rin, cols, TOL_100_STEPS, "input table after 100 steps")
-    _assert_close(tout.cpu().numpy(), rout, cols, TOL_100_STEPS, "output table after 100 steps")
+    _assert_close(tin.cpu().numpy(), rin, cols, TOL_100_STEPS, "input table after 100 steps", In)
+    _assert_close(tout.cpu().numpy(), rout, cols, TOL_100_STEPS, "output table after 100 steps", Out)
     nb.nups_destroy(ctx)
 
 
@@ -132,8 +119,8 @@ def test_sgns_bounded_reuse_step_and_bad_keys():
     rin, rout = In.copy(), Out.copy()
     _, s_in, s_out = orc.step_sgns(rin, rout, d, c, o, negs, K, 0.025)
     _assert_structure(ctx, 1, B * (K + 1), s_out)
-    _assert_close(tout.cpu().numpy(), rout, list(range(d)), TOL_ONE_STEP, "output table")
-    _assert_close(tin.cpu().numpy(), rin, list(range(d)), TOL_ONE_STEP, "input table")
+    _assert_close(tout.cpu().numpy(), rout, list(range(d)), TOL_ONE_STEP, "output table", Out)
+    _assert_close(tin.cpu().numpy(), rin, list(range(d)), TOL_ONE_STEP, "input table", In)
     # a key outside the table is reported, and nothing faults
     bad = c.copy(); bad[5] = V
     kbad = dev_u32(bad)
@@ -318,7 +305,7 @@ def test_kge_first_step_from_zero_state():
     rE, rGE, rR, rGR = E.copy(), np.zeros_like(E), R.copy(), np.zeros_like(R)
     orc.step_kge(rE, rGE, rR, rGR, d, s, r, o, negs, nh, nt, 0.1, 1e-10)
     for got, ref, gref, gst in ((te, rE, rGE, tge), (tr, rR, rGR, tgr)):
-        _assert_close(gst.cpu().numpy(), gref, cc, TOL_ONE_STEP, "AdaGrad state from zero")
+        _assert_close(gst.cpu().numpy(), gref, cc, TOL_ONE_STEP, "AdaGrad state from zero", np.zeros_like(gref))
         clear = np.sqrt(gref[:, cc]) > 1e-5
         diff = np.abs(got.cpu().numpy()[:, cc] - ref[:, cc])[clear]
         assert diff.max() <= 1e-5 * 0.1
@@ -342,13 +329,14 @@ def test_sgns_large_configuration_one_step_full_size():
     lr = float(wl.linear_lr(0.025, 7, 610_000))
     loss = nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_SGNS, B, kc, ko, n_neg=K, lr=lr, negs=addr), want_loss=True)
     negs = orc.sample_bounded(orc.alias_build(w), V, 1004, 0, 7, B * K, 4, 250)
+    In0, Out0 = In.copy(), Out.copy()
     rloss, s_in, s_out = orc.step_sgns(In, Out, d, c, o, negs, K, lr)      # in place: In, Out become the reference
     _assert_structure(ctx, 0, B, s_in)
     _assert_structure(ctx, 1, B * (K + 1), s_out)
     assert max(np.unique(negs, return_counts=True)[1]) >= 4               # reuse really happens
     cols = list(range(d))
-    _assert_close(tin.cpu().numpy(), In, cols, TOL_ONE_STEP, "input table (1M x 300)")
-    _assert_close(tout.cpu().numpy(), Out, cols, TOL_ONE_STEP, "output table (1M x 300)")
+    _assert_close(tin.cpu().numpy(), In, cols, TOL_ONE_STEP, "input table (1M x 300)", In0)
+    _assert_close(tout.cpu().numpy(), Out, cols, TOL_ONE_STEP, "output table (1M x 300)", Out0)
     assert abs(loss - rloss) <= 1e-5 * abs(rloss)
     nb.nups_release_sample(h)
     nb.nups_destroy(ctx)
@@ -408,8 +396,8 @@ def test_sgns_pipelined_steps_match_the_oracle(depth):
     _assert_structure(ctx, 0, B, s_in)                   # the structure query describes the last step that ran
     _assert_structure(ctx, 1, B * (K + 1), s_out)
     cols = list(range(d))
-    _assert_close(tin.cpu().numpy(), rin, cols, 1e-4, "input table after 12 pipelined steps")
-    _assert_close(tout.cpu().numpy(), rout, cols, 1e-4, "output table after 12 pipelined steps")
+    _assert_close(tin.cpu().numpy(), rin, cols, 1e-4, "input table after 12 pipelined steps", In)
+    _assert_close(tout.cpu().numpy(), rout, cols, 1e-4, "output table after 12 pipelined steps", Out)
     nb.nups_destroy(ctx)
 
 
@@ -460,9 +448,9 @@ def test_prepared_steps_far_ahead_with_other_calls_in_between():
         if t == 5:
             at5 = rin[push_keys].copy()
     cols = list(range(d))
-    _assert_close(tin.cpu().numpy(), rin, cols, 1e-4, "input table")
-    _assert_close(tout.cpu().numpy(), rout, cols, 1e-4, "output table")
-    _assert_close(pulled.cpu().numpy(), at5, cols, 1e-4, "rows pulled after step 5")
+    _assert_close(tin.cpu().numpy(), rin, cols, 1e-4, "input table", In)
+    _assert_close(tout.cpu().numpy(), rout, cols, 1e-4, "output table", Out)
+    _assert_close(pulled.cpu().numpy(), at5, cols, 1e-4, "rows pulled after step 5", In[push_keys])
     nb.nups_destroy(ctx)
 
 
@@ -491,11 +479,10 @@ def test_hot_key_set_changes_speed_not_results(s):
         _assert_structure(ctx, 0, B, s_in)
         _assert_structure(ctx, 1, B * (K + 1), s_out)
         gi, go = tin.cpu().numpy(), tout.cpu().numpy()
-        # with the hot path switched off one row group adds up thousands of contributions to the hottest key one
-        # after the other in fp32: the rounding error of that long chain is what the looser bar allows for
-        tol = TOL_ONE_STEP if hot != 0 else 1e-4
-        _assert_close(gi, rin, list(range(d)), tol, "input table, hot set %s" % hot, In if hot != 0 else None)
-        _assert_close(go, rout, list(range(d)), tol, "output table, hot set %s" % hot, Out if hot != 0 else None)
+        # the same bars with the hot path switched off: a row group that adds up thousands of contributions keeps
+        # a running total of sums of sixteen, not one long fp32 chain
+        _assert_close(gi, rin, list(range(d)), TOL_ONE_STEP, "input table, hot set %s" % hot, In)
+        _assert_close(go, rout, list(range(d)), TOL_ONE_STEP, "output table, hot set %s" % hot, Out)
         results.append((gi, go))
         nb.nups_destroy(ctx)
     with pytest.raises(nb.NupsError):
@@ -536,6 +523,6 @@ def test_sgns_step_with_the_other_sampling_schemes(scheme):
         rloss, s_in, s_out = orc.step_sgns(rin, rout, d, c, o, negs, K, lr)
         _assert_structure(ctx, 1, B * (K + 1), s_out)
         assert abs(loss - rloss) <= 1e-5 * abs(rloss)
-    _assert_close(tin.cpu().numpy(), rin, list(range(d)), 3e-5, "input table, %s" % scheme)
-    _assert_close(tout.cpu().numpy(), rout, list(range(d)), 3e-5, "output table, %s" % scheme)
+    _assert_close(tin.cpu().numpy(), rin, list(range(d)), 3e-5, "input table, %s" % scheme, In)
+    _assert_close(tout.cpu().numpy(), rout, list(range(d)), 3e-5, "output table, %s" % scheme, Out)
     nb.nups_destroy(ctx)
