@@ -387,7 +387,7 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="sgns_1m_d300_bounded_u4", choices=sorted(WORKLOADS))
     ap.add_argument("--depth", type=int, default=None,
                     help="steps prepared ahead of the one that runs (default 3; 4 for matrix factorisation)")
@@ -418,37 +418,64 @@ def main() -> int:
         w.clip = args.clip
         if not w.hot:
             w.hot = 1000
-    total_steps = w.setup(nb, wl, args.warmup + args.steps)
-    steps = total_steps - args.warmup
-    assert steps > 0, "not enough examples for the requested steps"
+    n_windows = 5                                    # further timed windows after the headline region
+    window = max(20, min(args.steps, 100))
+    total_steps = w.setup(nb, wl, args.warmup + args.steps + n_windows * window)
+    steps = args.steps
+    assert total_steps >= args.warmup + steps, "not enough examples for the requested steps"
+    n_windows = min(n_windows, (total_steps - args.warmup - steps) // window)
     ctx, B = w.ctx, w.B
     if args.cpu_steps != 0 and getattr(w, "In", None) is None:   # the oracle starts from the same initial tables
         w.tables_initial = [t.clone() for t in w.tables]
         if hasattr(w, "states"):
             w.states_initial = [t.clone() for t in w.states]
 
-    def run(first, count):
-        # software pipeline: steps t+1 .. t+depth are prepared before step t runs, so that sampling and the
-        # aggregation structure of later steps overlap the table work of step t on the GPU
-        last = first + count
-        queue = [w.prepare(t) for t in range(first, min(first + args.depth, last))]
-        for t in range(first, last):
-            if t + args.depth < last:
-                queue.append(w.prepare(t + args.depth))
-            nb.nups_step_prepared(ctx, queue.pop(0))
+    class Pipeline:
+        """Software pipeline: steps t+1 .. t+depth are prepared before step t runs, so that sampling and the
+        aggregation structure of later steps ride in the launches of step t and its neighbours."""
 
-    # ---- warm-up, then the timed region ---------------------------------------------------------
-    run(0, args.warmup)
+        def __init__(self, first, last):
+            self.next_run, self.next_prepare, self.last = first, first, last
+            self.queue = []
+            self.fill()
+
+        def fill(self):
+            while self.next_prepare < min(self.next_run + args.depth + 1, self.last):
+                self.queue.append(w.prepare(self.next_prepare))
+                self.next_prepare += 1
+
+        def run(self, count):
+            for _ in range(count):
+                nb.nups_step_prepared(ctx, self.queue.pop(0))
+                self.next_run += 1
+                self.fill()
+
+    def run(first, count):                           # a pipeline of its own (the per-kernel pass)
+        Pipeline(first, first + count).run(count)
+
+    # ---- warm-up, then the timed region: one pipeline runs through both, so that the timed steps find their
+    # preparatory work carried by the launches before them, as in steady state --------------------------------
+    pipe = Pipeline(0, args.warmup + steps + n_windows * window)
+    pipe.run(args.warmup)
     nb.nups_check(ctx)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run(args.warmup, steps)
+    pipe.run(steps)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     nb.nups_check(ctx)
     ms_per_step = 1e3 * elapsed / steps
     value = steps * B / elapsed
+    window_ms = []
+    for _ in range(n_windows):                       # the same measurement again, several times: its spread
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        pipe.run(window)
+        torch.cuda.synchronize()
+        window_ms.append(1e3 * (time.perf_counter() - t1) / window)
+    nb.nups_check(ctx)
     finite = all(bool(torch.isfinite(t).all().item()) for t in w.tables)
+    total_steps = args.warmup + steps + n_windows * window
 
     # ---- per-kernel pass: the last steps again, unpipelined, HIP events around every phase on its stream ---
     n_prof = min(steps, 64)
@@ -525,6 +552,8 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": w.config(), "roofline": roofline, "phases_ms_per_step": phases, "cpu_baseline": cpu,
         "finite": finite,
+        "windows_ms_per_step": {"steps_per_window": window, "median": float(np.median(window_ms)) if window_ms else None,
+                                "min": min(window_ms) if window_ms else None, "max": max(window_ms) if window_ms else None},
     }
     if not finite:
         out["finite_note"] = ("tables overflow at this configuration's learning rate with summed minibatch gradients; "

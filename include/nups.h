@@ -103,6 +103,19 @@ nups_status nups_set_state(nups_ctx *ctx, int table, float *state_dev);
 nups_status nups_set_hot_keys(nups_ctx *ctx, int table, const uint32_t *keys_host, int64_t k);
 
 /*
+ * Reproducible aggregation (the push of Section 3.1 sums the updates sent for a key; in which order is left
+ * open).  By default the accesses of a key are listed in the order in which positions were handed out by
+ * atomic operations, so the fp32 sum of a key's contributions can differ in its last bits from run to run and
+ * with the declared hot set.  enable != 0: structures built from now on also list every key's accesses in
+ * ascending order (one more phase of preparatory work, quadratic in the longest segment), and the update
+ * kernels add them in a fixed tree over that order (blocks of 16, super-blocks of 256, then in order), whichever
+ * technique a key gets: tables are then bit-identical between runs and between hot sets.  The reported loss and
+ * the clipping statistics are still accumulated with atomic additions (their last bits may vary).
+ * NUPS_ERR_STATE while prepared steps are outstanding.
+ */
+nups_status nups_set_deterministic(nups_ctx *ctx, int enable);
+
+/*
  * Norm clipping of the updates of hot keys (Section 5.1, implementation paragraph: for the
  * replicated parameters of the word-vector and factorisation tasks, updates that exceed the
  * average norm by more than a factor, 2 in the paper, are clipped, to keep summed gradients of

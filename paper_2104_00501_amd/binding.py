@@ -21,7 +21,8 @@ NUPS_TASK_SGNS, NUPS_TASK_MF, NUPS_TASK_KGE = 1, 2, 3
  NUPS_PHASE_PUSH, NUPS_PHASE_COUNT) = range(8)
 
 EXPORTS = [
-    "nups_init", "nups_destroy", "nups_set_state", "nups_set_hot_keys", "nups_set_update_clipping",
+    "nups_init", "nups_destroy", "nups_set_state", "nups_set_hot_keys", "nups_set_deterministic",
+    "nups_set_update_clipping",
     "nups_get_update_clipping", "nups_pull", "nups_push",
     "nups_build_alias_table", "nups_register_distribution", "nups_register_distribution_at_level",
     "nups_select_hot_keys", "nups_set_local_keys", "nups_prepare_sample",
@@ -120,6 +121,10 @@ def nups_set_hot_keys(ctx, table, keys_host):
     import numpy as np
     k = np.ascontiguousarray(keys_host, dtype=np.uint32)
     _check(lib().nups_set_hot_keys(ctx, C.c_int(table), _ptr(k) if len(k) else C.c_void_p(None), C.c_int64(len(k))))
+
+
+def nups_set_deterministic(ctx, enable):
+    _check(lib().nups_set_deterministic(ctx, C.c_int(1 if enable else 0)))
 
 
 def nups_set_update_clipping(ctx, factor):

@@ -325,6 +325,15 @@ nups_status nups_set_hot_keys(nups_ctx *ctx, int table, const uint32_t *keys_hos
     return NUPS_OK;
 }
 
+nups_status nups_set_deterministic(nups_ctx *ctx, int enable)
+{
+    if (!ctx) return fail(NUPS_ERR_ARG, "nups_set_deterministic: null context");
+    for (nups_prepared *q : ctx->prepared_all)
+        if (q->live) return fail(NUPS_ERR_STATE, "nups_set_deterministic: prepared steps are outstanding");
+    ctx->deterministic = enable != 0;
+    return NUPS_OK;
+}
+
 nups_status nups_set_update_clipping(nups_ctx *ctx, float factor)
 {
     if (!ctx) return fail(NUPS_ERR_ARG, "nups_set_update_clipping: null context");
@@ -387,7 +396,7 @@ nups_status nups_push(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_
     p->plan[0].a.zero_loss = nullptr;
     build_phases(*p, SampleArgs{}, -1);
     st = flush_side_work(ctx, p);
-    if (st == NUPS_OK && n > 0) st = launch_push_apply(ctx, t, p->plan[0], updates_dev);
+    if (st == NUPS_OK && n > 0) st = launch_push_apply(ctx, t, p->plan[0], ctx->partial, updates_dev);
     retire_prepared(ctx, p);
     return st;
 }

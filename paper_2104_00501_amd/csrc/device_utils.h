@@ -71,6 +71,31 @@ __device__ __forceinline__ float group_sum(float x)
     return x;
 }
 
+template <int kCtrl>
+__device__ __forceinline__ uint32_t row_move(uint32_t x)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, kCtrl, 0xF, 0xF, false);
+}
+
+// Smallest and largest x over the 16 lanes of a row group, to every lane of the group (same moves as group_sum).
+__device__ __forceinline__ uint32_t group_min(uint32_t x)
+{
+    x = min(x, row_move<0xB1>(x));
+    x = min(x, row_move<0x4E>(x));
+    x = min(x, row_move<0x141>(x));
+    x = min(x, row_move<0x140>(x));
+    return x;
+}
+
+__device__ __forceinline__ uint32_t group_max(uint32_t x)
+{
+    x = max(x, row_move<0xB1>(x));
+    x = max(x, row_move<0x4E>(x));
+    x = max(x, row_move<0x141>(x));
+    x = max(x, row_move<0x140>(x));
+    return x;
+}
+
 __device__ __forceinline__ float wave_sum(float x)
 {
 #pragma unroll

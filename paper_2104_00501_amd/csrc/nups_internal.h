@@ -75,6 +75,7 @@ struct PlanArgs {
     uint32_t direct_count;  // 1: the count scan sums the counts below its tile itself
     uint32_t max_chunks;   // capacity of the chunk lists
     uint32_t rank_items;   // accesses per thread in the rank phase (2: narrow rows, 4: others)
+    uint32_t deterministic; // 1: the accesses of a segment are also listed in ascending order (perm_sorted)
     // build scratch, owned by the plan (the structures of several later steps are under construction at a time)
     uint8_t *bytemap;      // [32 * words] one byte per key, all zero between builds
     uint8_t *wordmap;      // [words]     one byte per bitmap word: some key of the word is marked; zero between builds
@@ -87,7 +88,8 @@ struct PlanArgs {
     uint32_t *uniq;        // [n]         distinct keys, ascending
     uint32_t *count;       // [n]         accesses per distinct key
     uint32_t *seg;         // [n + 1]     exclusive prefix sums of count
-    uint32_t *perm;        // [n]         accesses grouped by key
+    uint32_t *perm;        // [n]         accesses grouped by key (inside a segment: in the order positions were handed out)
+    uint32_t *perm_sorted; // [n]         the same with every segment in ascending order (deterministic mode only)
     uint32_t *slot;        // [n]         per access: index of its key among the distinct keys
     uint32_t *rank;        // [n]         per access: position inside its key's segment (| kSingleAccess)
     uint32_t *chunk_seg;   // [max_chunks]  distinct-key index of the long segment a chunk belongs to
@@ -137,7 +139,7 @@ struct SampleArgs {
 
 // Phases of a step's preparatory work, in order (side_work.h).
 enum SidePhase : int32_t {
-    kSideDraw = 0, kSideTiles, kSidePrefix, kSideSlot, kSideRank, kSideCountTiles, kSideCounts, kSideScatter
+    kSideDraw = 0, kSideTiles, kSidePrefix, kSideSlot, kSideRank, kSideCountTiles, kSideCounts, kSideScatter, kSideSort
 };
 
 // One phase of one step: units block0 .. block0 + blocks - 1 of it.
@@ -202,6 +204,7 @@ struct nups_ctx {
     float clip_factor = 0.0f;
     double *clip_stats = nullptr;   // [kMaxTables][kLossSlots * kLossStride]: per slot {sum of norms, number of norms}
     float *clip_bound = nullptr;    // [kMaxTables] factor x mean norm, refreshed before each update launch
+    bool deterministic = false;     // structures built from now on list every segment's accesses in ascending order
     bool profiling = false;
     nups::Phase phase[NUPS_PHASE_COUNT];
     std::vector<nups_dist *> dists;
@@ -252,6 +255,7 @@ struct PhaseScope {
 // host-side helpers and launchers (defined in the .hip files)
 SampleArgs sample_args(const nups_dist *d, uint32_t *keys_out, int64_t n_samples, uint64_t step);
 nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n);
+void set_plan_shape(const nups_ctx *ctx, const Table &t, Plan &pl);
 void build_phases(nups_prepared &p, const SampleArgs &draw, int mark_plan);
 size_t side_lds_bytes(const SideItem &it);
 SideWork take_side_work(nups_ctx *ctx, size_t *lds_bytes, uint32_t max_wgs_per_phase);
@@ -259,7 +263,7 @@ nups_status flush_side_work(nups_ctx *ctx, nups_prepared *p);
 nups_status launch_side(nups_ctx *ctx, const SideItem &it);
 void free_plan_arrays(Plan &pl);
 nups_status launch_pull(nups_ctx *ctx, const Table &t, const uint32_t *keys, int64_t n, float *values);
-nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, const float *updates);
+nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, float *partial, const float *updates);
 nups_status plan_step_sgns(nups_ctx *ctx, nups_prepared &p);   // capacity + plan arguments
 nups_status plan_step_mf(nups_ctx *ctx, nups_prepared &p);
 nups_status plan_step_kge(nups_ctx *ctx, nups_prepared &p);

@@ -28,7 +28,7 @@ nups_status ensure_partial(nups_ctx *ctx, size_t need)
 void free_plan_arrays(Plan &pl)
 {
     PlanArgs &a = pl.a;
-    for (uint32_t *p : {a.uniq, a.count, a.seg, a.perm, a.slot, a.rank, a.chunk_seg, a.chunk_base, a.chunk_done, a.meta,
+    for (uint32_t *p : {a.uniq, a.count, a.seg, a.perm, a.perm_sorted, a.slot, a.rank, a.chunk_seg, a.chunk_base, a.chunk_done, a.meta,
                         a.bitmap, a.word_rank, a.tile_sum, a.tile_prefix, a.cnt_work})
         if (p) (void)hipFree(p);
     if (a.bytemap) (void)hipFree(a.bytemap);
@@ -54,7 +54,7 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
     if (pl.cap_n < n || pl.cap_n == 0) {
         NUPS_HIP(hipStreamSynchronize(ctx->stream));
         const size_t cap = n + n / 4 + 1024;
-        for (uint32_t **b : {&a.uniq, &a.count, &a.perm, &a.slot, &a.rank})
+        for (uint32_t **b : {&a.uniq, &a.count, &a.perm, &a.perm_sorted, &a.slot, &a.rank})
             if ((st = grow_u32(b, cap, false)) != NUPS_OK) return st;
         if ((st = grow_u32(&a.cnt_work, (cap + kScanTile - 1) / kScanTile * kScanTile, true)) != NUPS_OK) return st;   // whole tiles
         if ((st = grow_u32(&a.seg, cap + 1, false)) != NUPS_OK) return st;
@@ -71,6 +71,15 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
         if ((st = grow_u32(&a.tile_prefix, tiles, false)) != NUPS_OK) return st;
         pl.cap_tiles = tiles;
     }
+    set_plan_shape(ctx, t, pl);
+    return NUPS_OK;
+}
+
+// The shape fields of a plan whose arrays are in place (cap_n set) for table t.
+void set_plan_shape(const nups_ctx *ctx, const Table &t, Plan &pl)
+{
+    PlanArgs &a = pl.a;
+    const size_t words = (size_t)((t.num_keys + 31) / 32);
     a.num_keys = (uint32_t)t.num_keys;
     a.max_chunks = (uint32_t)max_chunks(pl.cap_n);
     a.rank_items = 4u;   // accesses per thread of the rank phase (2 measured slower, also in narrow-row carriers)
@@ -78,7 +87,7 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
     a.bitmap_tiles = (uint32_t)((words + kScanTile - 1) / kScanTile);
     a.error_flag = ctx->error_flag;
     a.hot_bits = t.hot_bits_dev;
-    return NUPS_OK;
+    a.deterministic = ctx->deterministic ? 1u : 0u;
 }
 
 // Dynamic LDS that the launch carrying this phase must provide.
@@ -137,6 +146,7 @@ void build_phases(nups_prepared &p, const SampleArgs &draw, int mark_plan)
     if (need_count_tiles) add(kSideCountTiles, max_ctiles, 0);
     add(kSideCounts, max_ctiles, 0);
     add(kSideScatter, std::max(1u, (max_n + kBlock - 1) / kBlock), 0);
+    if (p.plan[0].a.deterministic) add(kSideSort, std::max(1u, (max_n + kBlock - 1) / kBlock), 0);
 }
 
 }  // namespace nups

@@ -3,7 +3,14 @@
 // a source row (a staged gradient row, or a row of another table); the sum is kept in registers
 // by a 16-lane row group, so each touched row is read once and written once.
 // Short segments take one row group each; long segments (the hot keys of Section 3.2) are cut into
-// chunks, one workgroup per chunk, whose partial rows are combined in a fixed order.
+// chunks, one workgroup per chunk, whose partial rows are combined by the workgroup that finishes last.
+//
+// The order of the additions is a fixed tree over the positions of a segment, whichever path sums it: sixteen
+// consecutive accesses are added one after the other (a block), sixteen consecutive block sums one after the other
+// (a super-block of kChunk = 256 accesses: what one workgroup sums of a chunked segment), and the super-block
+// sums one after the other.  A long chain of fp32 additions never forms (the error of a sum of n terms grows with
+// sqrt(16) + sqrt(16) + sqrt(n / 256) rather than sqrt(n)), and with the accesses of a segment in ascending order
+// (a plan built in deterministic mode) the result does not depend on the run or on which keys are declared hot.
 #pragma once
 
 #include <algorithm>
@@ -19,9 +26,43 @@ struct SrcStaged {
     const float *stage;
     bool singles_done = false;   // the gradient kernel has updated the keys with a single access itself
     __device__ __forceinline__ bool done_already(uint32_t) const { return singles_done; }
+    __device__ __forceinline__ bool segment_done(const uint32_t *perm, uint32_t first, uint32_t last, int) const
+    {
+        return last - first == 1 && done_already(perm[first]);
+    }
     __device__ __forceinline__ float coef(uint32_t) const { return 1.0f; }
     __device__ __forceinline__ const float *rows() const { return stage; }
     __device__ __forceinline__ uint32_t row_number(uint32_t i) const { return i; }
+};
+
+// SGNS input side: access i is pair i, its key the pair's center word.  The gradient kernel has added up the
+// input-side gradients of each run of pairs with the same center word inside one of its workgroups (kGroupsPerBlock
+// consecutive pairs) and staged the sum at the row of the run's first pair; the other pairs of a run contribute
+// nothing more and point at a row of zeros.  A center word whose pairs are all in one run was updated by the
+// gradient kernel itself (runs_done), which had the sum and the row in registers.
+struct SrcSgnsIn {
+    const float *stage;       // [B] run sums at the rows of the runs' first pairs, [zero_row] all zero
+    const uint32_t *center;   // [B]
+    uint32_t zero_row;
+    bool runs_done;
+    __device__ __forceinline__ bool run_head(uint32_t i) const
+    {
+        return i % kGroupsPerBlock == 0 || center[i - 1] != center[i];
+    }
+    // Every lane of the group calls it.  The segment is one run iff its access numbers are consecutive and within
+    // one workgroup of the gradient kernel.
+    __device__ __forceinline__ bool segment_done(const uint32_t *perm, uint32_t first, uint32_t last, int lane) const
+    {
+        const uint32_t n = last - first;
+        if (!runs_done || n > (uint32_t)kGroupsPerBlock) return false;
+        const bool mine = (uint32_t)lane < n;
+        const uint32_t i = mine ? perm[first + lane] : 0u;
+        const uint32_t lo = group_min(mine ? i : 0xFFFFFFFFu), hi = group_max(i);
+        return hi - lo + 1 == n && lo / kGroupsPerBlock == hi / kGroupsPerBlock;
+    }
+    __device__ __forceinline__ float coef(uint32_t) const { return 1.0f; }
+    __device__ __forceinline__ const float *rows() const { return stage; }
+    __device__ __forceinline__ uint32_t row_number(uint32_t i) const { return run_head(i) ? i : zero_row; }
 };
 
 // SGNS output side: access i < B is the context word of pair i, access B + p is negative p (pair p / K).
@@ -33,7 +74,7 @@ struct SrcSgnsOut {
     const uint32_t *center_slot;  // [B] slot of each pair's center word
     const float *coefs;           // [B, K + 1]
     uint32_t B, K;
-    __device__ __forceinline__ bool done_already(uint32_t) const { return false; }
+    __device__ __forceinline__ bool segment_done(const uint32_t *, uint32_t, uint32_t, int) const { return false; }
     __device__ __forceinline__ uint32_t pair_of(uint32_t i) const { return i < B ? i : (i - B) / K; }
     __device__ __forceinline__ float coef(uint32_t i) const
     {
@@ -57,6 +98,10 @@ struct SrcKgeEntity {
     uint32_t B, nn, nh;
     // i: the only access of its key
     __device__ __forceinline__ bool done_already(uint32_t i) const { return i >= 2 * B; }
+    __device__ __forceinline__ bool segment_done(const uint32_t *perm, uint32_t first, uint32_t last, int) const
+    {
+        return last - first == 1 && done_already(perm[first]);
+    }
     __device__ __forceinline__ float coef(uint32_t i) const { return i < 2 * B ? 1.0f : coefs[i - 2 * B]; }
     __device__ __forceinline__ const float *rows() const { return stage; }
     __device__ __forceinline__ uint32_t row_number(uint32_t i) const
@@ -190,10 +235,16 @@ struct ApplyArgs {
     int stride;
     uint32_t n;            // accesses of the plan
     uint32_t max_chunks;   // capacity of the chunk lists and of `partial`
+    uint32_t deterministic; // the chunks' partial rows are added in chunk order by one group, however many
 };
 
-// Four accesses of a batch of sixteen: their coefficients and source row numbers sit in lanes kFirst .. kFirst + 3
-// of the group (c, r); m = accesses in the batch, kFirst < m.  The rows are requested together.
+// LDS of the update kernels: two rows per row group.  Row `group` of the first half holds a group's block sum
+// while a chunk is combined, or the running super-block sum of a long segment that one group sums by itself;
+// row `group` of the second half that segment's running total.
+__host__ __device__ constexpr size_t apply_lds_bytes(int stride) { return sizeof(float) * 2 * kGroupsPerBlock * (size_t)stride; }
+
+// Four accesses of a block of sixteen: their coefficients and source row numbers sit in lanes kFirst .. kFirst + 3
+// of the group (c, r); m = accesses in the block, kFirst < m.  The rows are requested together and added in order.
 template <int NV4, int kFirst>
 __device__ __forceinline__ void sum_four(Row<NV4> &acc, const float *rows, uint32_t r, float c, uint32_t m, int stride,
                                          int lane)
@@ -213,30 +264,70 @@ __device__ __forceinline__ void sum_four(Row<NV4> &acc, const float *rows, uint3
     if (kFirst + 3 < m) axpy_row(acc, c3, r3);
 }
 
-// Sums accesses first, first + step, ... < last of a segment into acc, sixteen at a time: lane l of the group
-// fetches the l-th access's number, coefficient and source row number, so the dependent reads that lead to a row's
-// address are paid once per sixteen accesses rather than once per access; the rows are then read four at a time.
-// Every lane of the group must call it with the same arguments.
+// acc += the contributions of accesses t0 .. min(t0 + 16, last) - 1 of a segment, in that order (one block):
+// lane l of the group fetches the l-th access's number, coefficient and source row number, so the dependent reads
+// that lead to a row's address are paid once per sixteen accesses rather than once per access; the rows are then
+// read four at a time.  Every lane of the group must call it with the same arguments; t0 < last.
 template <int NV4, class Src>
-__device__ __forceinline__ void sum_segment(Row<NV4> &acc, const Src &src, const uint32_t *perm, uint32_t first,
-                                            uint32_t last, uint32_t step, int stride, int lane)
+__device__ __forceinline__ void sum_block(Row<NV4> &acc, const Src &src, const uint32_t *perm, uint32_t t0,
+                                          uint32_t last, int stride, int lane)
 {
     const float *rows = src.rows();
-    for (uint32_t t0 = first; t0 < last; t0 += kGroup * step) {
-        const uint32_t t = t0 + (uint32_t)lane * step;
-        uint32_t r = 0;
-        float c = 0.0f;
-        if (t < last) {
-            const uint32_t i = perm[t];
-            c = src.coef(i);
-            r = src.row_number(i);
-        }
-        const uint32_t m = min((uint32_t)kGroup, (last - t0 + step - 1) / step);
-        sum_four<NV4, 0>(acc, rows, r, c, m, stride, lane);
-        if (m > 4) sum_four<NV4, 4>(acc, rows, r, c, m, stride, lane);
-        if (m > 8) sum_four<NV4, 8>(acc, rows, r, c, m, stride, lane);
-        if (m > 12) sum_four<NV4, 12>(acc, rows, r, c, m, stride, lane);
+    const uint32_t t = t0 + (uint32_t)lane;
+    uint32_t r = 0;
+    float c = 0.0f;
+    if (t < last) {
+        const uint32_t i = perm[t];
+        c = src.coef(i);
+        r = src.row_number(i);
     }
+    const uint32_t m = min((uint32_t)kGroup, last - t0);
+    sum_four<NV4, 0>(acc, rows, r, c, m, stride, lane);
+    if (m > 4) sum_four<NV4, 4>(acc, rows, r, c, m, stride, lane);
+    if (m > 8) sum_four<NV4, 8>(acc, rows, r, c, m, stride, lane);
+    if (m > 12) sum_four<NV4, 12>(acc, rows, r, c, m, stride, lane);
+}
+
+// lds_row <- x if `first`, else lds_row + x; each lane touches its own words only, so no barrier is involved.
+template <int NV4>
+__device__ __forceinline__ void lds_accumulate(float *lds_row, const Row<NV4> &x, bool first, int lane)
+{
+    if (first) {
+        store_row(lds_row, x, lane);
+    } else {
+        Row<NV4> t;
+        load_row(t, lds_row, lane);
+        axpy_row(t, 1.0f, x);
+        store_row(lds_row, t, lane);
+    }
+}
+
+// acc = sum of the whole segment [first, last) by one group, in the fixed tree (blocks, super-blocks, total).
+// lds: the workgroup's two-rows-per-group area; only this group's two rows are used.
+template <int NV4, class Src>
+__device__ __forceinline__ void sum_segment(Row<NV4> &acc, const Src &src, const uint32_t *perm, uint32_t first,
+                                            uint32_t last, int stride, int lane, int group, float *lds)
+{
+    zero_row(acc);
+    if (last - first <= (uint32_t)kGroup) {
+        if (first < last) sum_block<NV4>(acc, src, perm, first, last, stride, lane);
+        return;
+    }
+    float *super_row = lds + (size_t)group * stride, *total_row = lds + (size_t)(kGroupsPerBlock + group) * stride;
+    const bool several = last - first > kChunk;
+    for (uint32_t s0 = first; s0 < last; s0 += kChunk) {
+        const uint32_t s1 = min(s0 + kChunk, last);
+        for (uint32_t t0 = s0; t0 < s1; t0 += kGroup) {
+            zero_row(acc);
+            sum_block<NV4>(acc, src, perm, t0, s1, stride, lane);
+            lds_accumulate(super_row, acc, t0 == s0, lane);
+        }
+        if (several) {
+            load_row(acc, super_row, lane);
+            lds_accumulate(total_row, acc, s0 == first, lane);
+        }
+    }
+    load_row(acc, several ? total_row : super_row, lane);
 }
 
 // Work items of a plan: one per chunk (kChunk accesses) of a long segment, and the short segments (at most
@@ -260,28 +351,42 @@ __device__ __forceinline__ ApplyShape apply_shape(const ApplyArgs &a)
 // One item of short segments: this group's segment, if it has one.
 template <int NV4, class Src, class Opt>
 __device__ __forceinline__ void apply_short_item(const ApplyArgs &a, const Src &src, const Opt &opt,
-                                                 const ApplyShape &sh, uint32_t item, int lane, int group)
+                                                 const ApplyShape &sh, uint32_t item, float *lds, int lane, int group)
 {
     const uint32_t u = item * kGroupsPerBlock + group;
     if (u >= sh.nu) return;
     const uint32_t key = a.uniq[u];
     const uint32_t first = a.seg[u], last = a.seg[u + 1];
     if (takes_hot_path(last - first, key, a.hot_bits)) return;   // summed by chunk items
-    if (last - first == 1 && src.done_already(a.perm[first])) return;
+    if (src.segment_done(a.perm, first, last, lane)) return;     // the gradient kernel has updated this row itself
     const size_t off = (size_t)key * a.stride;
     float *row = a.table + off, *state_row = Opt::kHasState ? a.state + off : nullptr;
     Row<NV4> acc, t, g;
-    zero_row(acc);
-    sum_segment<NV4>(acc, src, a.perm, first, last, 1, a.stride, lane);
+    sum_segment<NV4>(acc, src, a.perm, first, last, a.stride, lane, group, lds);
     opt.template load<NV4>(t, g, row, state_row, lane);   // after the sum: results are waited for in issue order, an early request of the cold row holds up the sum's first reads
     if (opt.clips() && a.hot_bits != nullptr && in_hot_set(key, a.hot_bits)) opt.template clip<NV4>(acc, lane);
     opt.template finish<NV4>(t, g, row, state_row, acc, lane);
 }
 
-// One chunk of a long segment, by the whole workgroup: the 16 groups sum interleaved slices, the slices are
-// combined through LDS in group order, and the workgroup that finishes a segment's last outstanding chunk adds
-// the chunks' partial rows in chunk order and updates the row.  Contains workgroup barriers: every thread of
-// the workgroup must call it with the same `id`.
+// The counter of a chunked segment: how many of its chunks have left their partial row.  The partial rows travel
+// as device-scope word accesses (device_utils.h), which are performed at the memory side of the dies' caches; the
+// storing wavefront waits for their acknowledgement before it counts itself in, and the workgroup that sees the
+// last count reads them with device-scope loads after its barrier: no cache write-back or invalidation is needed
+// (a release fence at device scope writes back the whole L2 of the die, which holds the step's updated rows:
+// measured at 8.6 us of a 32 us launch).  NUPS_HANDOFF_RELEASE_ACQUIRE builds the formally ordered variant.
+__device__ __forceinline__ uint32_t count_chunk_in(uint32_t *counter)
+{
+#if defined(NUPS_HANDOFF_RELEASE_ACQUIRE)
+    return __hip_atomic_fetch_add(counter, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+#else
+    return __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#endif
+}
+
+// One chunk (super-block) of a long segment, by the whole workgroup: group g sums block g of the chunk, the
+// block sums are added in block order through LDS, and the workgroup that finishes a segment's last outstanding
+// chunk adds the chunks' partial rows and updates the row.  Contains workgroup barriers: every thread of the
+// workgroup must call it with the same `id`.
 template <int NV4, class Src, class Opt>
 __device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &src, const Opt &opt, uint32_t id,
                                                  float *part, uint32_t *last_arrival, int lane, int group)
@@ -290,16 +395,17 @@ __device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &
     const uint32_t first = a.seg[u], last = a.seg[u + 1];
     const uint32_t nch = (last - first + kChunk - 1) / kChunk;
     const uint32_t cf = first + (id - base) * kChunk, cl = min(cf + kChunk, last);
+    const uint32_t blocks = (cl - cf + kGroup - 1) / kGroup;     // non-empty blocks of this chunk
     Row<NV4> acc;
     zero_row(acc);
-    sum_segment<NV4>(acc, src, a.perm, cf + group, cl, kGroupsPerBlock, a.stride, lane);
+    if ((uint32_t)group < blocks) sum_block<NV4>(acc, src, a.perm, cf + (uint32_t)group * kGroup, cl, a.stride, lane);
     __syncthreads();                  // LDS of the previous item has been read
-    if (group > 0) store_row(part + (size_t)(group - 1) * a.stride, acc, lane);
+    if (group > 0 && (uint32_t)group < blocks) store_row(part + (size_t)group * a.stride, acc, lane);
     __syncthreads();
     if (group == 0) {
-        for (int g = 1; g < kGroupsPerBlock; ++g) {
+        for (uint32_t g = 1; g < blocks; ++g) {
             Row<NV4> r;
-            load_row(r, part + (size_t)(g - 1) * a.stride, lane);
+            load_row(r, part + (size_t)g * a.stride, lane);
             axpy_row(acc, 1.0f, r);
         }
         if (nch > 1) {
@@ -310,24 +416,24 @@ __device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &
     bool update = true;
     if (nch > 1) {
         __syncthreads();
-        if (threadIdx.x == 0) *last_arrival = (atomicAdd(&a.chunk_done[base], 1u) == nch - 1) ? 1u : 0u;
+        if (threadIdx.x == 0) *last_arrival = (count_chunk_in(&a.chunk_done[base]) == nch - 1) ? 1u : 0u;
         __syncthreads();
         update = *last_arrival != 0;
         if (update) {
             const float *prow = a.partial + (size_t)base * a.stride;
-            if (nch > 8) {           // many chunks: every group adds an interleaved share, combined in group order
+            if (nch > 8 && !a.deterministic) {   // many chunks: every group adds an interleaved share, combined in group order
                 zero_row(acc);
                 for (uint32_t ch = group; ch < nch; ch += kGroupsPerBlock) {
                     Row<NV4> r;
                     load_row_device_scope(r, prow + (size_t)ch * a.stride, lane);
                     axpy_row(acc, 1.0f, r);
                 }
-                if (group > 0) store_row(part + (size_t)(group - 1) * a.stride, acc, lane);   // LDS is free again
+                if (group > 0) store_row(part + (size_t)group * a.stride, acc, lane);   // LDS is free again
                 __syncthreads();
                 if (group == 0) {
                     for (int g = 1; g < kGroupsPerBlock; ++g) {
                         Row<NV4> r;
-                        load_row(r, part + (size_t)(g - 1) * a.stride, lane);
+                        load_row(r, part + (size_t)g * a.stride, lane);
                         axpy_row(acc, 1.0f, r);
                     }
                 }
@@ -361,6 +467,7 @@ __device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &
         if (opt.clips() && a.hot_bits != nullptr) opt.template clip<NV4>(acc, lane);   // chunked and declared: a hot key
         opt.template finish<NV4>(t, g, a.table + off, Opt::kHasState ? a.state + off : nullptr, acc, lane);
     }
+    __syncthreads();                  // the block sums in LDS have been read: the groups' rows are theirs again
 }
 
 // Updates one table.  A fixed-size grid walks over the items, chunks first (they are the long poles); every
@@ -368,14 +475,14 @@ __device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &
 template <int NV4, class Src, class Opt>
 __global__ void __launch_bounds__(kBlock) k_apply(ApplyArgs a, Src src, Opt opt)
 {
-    extern __shared__ float part[];   // [kGroupsPerBlock - 1][stride]
+    extern __shared__ float part[];   // apply_lds_bytes(stride)
     __shared__ uint32_t last_arrival;
     const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
     const ApplyShape sh = apply_shape(a);
     const uint32_t items = sh.chunk_items + sh.short_items;
     for (uint32_t item = blockIdx.x; item < items; item += gridDim.x) {
         if (item < sh.chunk_items) apply_chunk_item<NV4>(a, src, opt, item, part, &last_arrival, lane, group);
-        else apply_short_item<NV4>(a, src, opt, sh, item - sh.chunk_items, lane, group);
+        else apply_short_item<NV4>(a, src, opt, sh, item - sh.chunk_items, part, lane, group);
     }
 }
 
@@ -386,7 +493,7 @@ template <int NV4, class Src0, class Opt0, class Src1, class Opt1>
 __global__ void __launch_bounds__(kBlock) k_apply2(ApplyArgs a0, Src0 src0, Opt0 opt0, ApplyArgs a1, Src1 src1,
                                                    Opt1 opt1, SideWork sw)
 {
-    extern __shared__ float part[];   // [kGroupsPerBlock - 1][stride]
+    extern __shared__ float part[];   // apply_lds_bytes(stride)
     __shared__ uint32_t last_arrival;
     if (side_work_block(sw)) return;
     const uint32_t first_item = blockIdx.x - sw.blocks, item_step = gridDim.x - sw.blocks;
@@ -397,8 +504,8 @@ __global__ void __launch_bounds__(kBlock) k_apply2(ApplyArgs a0, Src0 src0, Opt0
     for (uint32_t item = first_item; item < e3; item += item_step) {
         if (item < e0) apply_chunk_item<NV4>(a0, src0, opt0, item, part, &last_arrival, lane, group);
         else if (item < e1) apply_chunk_item<NV4>(a1, src1, opt1, item - e0, part, &last_arrival, lane, group);
-        else if (item < e2) apply_short_item<NV4>(a0, src0, opt0, s0, item - e1, lane, group);
-        else apply_short_item<NV4>(a1, src1, opt1, s1, item - e2, lane, group);
+        else if (item < e2) apply_short_item<NV4>(a0, src0, opt0, s0, item - e1, part, lane, group);
+        else apply_short_item<NV4>(a1, src1, opt1, s1, item - e2, part, lane, group);
     }
 }
 
@@ -410,13 +517,23 @@ constexpr uint32_t kApplyGrid = NV4 <= 2 ? 8192 : 2048;
 static inline ApplyArgs make_apply_args(const Plan &pl, float *partial, float *table, float *state, int stride)
 {
     const PlanArgs &p = pl.a;
-    return ApplyArgs{table, state, p.hot_bits, p.uniq, p.seg, p.perm, p.meta, p.chunk_seg, p.chunk_base, p.chunk_done,
-                     partial, stride, p.n, p.max_chunks};
+    return ApplyArgs{table, state, p.hot_bits, p.uniq, p.seg, p.deterministic ? p.perm_sorted : p.perm, p.meta,
+                     p.chunk_seg, p.chunk_base, p.chunk_done, partial, stride, p.n, p.max_chunks, p.deterministic};
 }
 
 static inline uint32_t max_apply_items(const Plan &pl)
 {
     return (pl.a.n + kGroupsPerBlock - 1) / kGroupsPerBlock + (uint32_t)max_chunks(pl.a.n);
+}
+
+// Workgroups that ask for more dynamic LDS than the default limit of 64 KB (wide rows) say so first; the device
+// has 160 KB per compute unit.  `allowed`: what this kernel has been granted so far (one variable per kernel).
+template <class Kernel>
+static void allow_lds(Kernel kernel, size_t lds, size_t *allowed)
+{
+    if (lds <= 48 * 1024 || lds <= *allowed) return;
+    if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess)
+        *allowed = lds;
 }
 
 template <int NV4, class Src, class Opt>
@@ -425,7 +542,9 @@ static void launch_apply_nv(hipStream_t s, const Plan &pl, float *partial, float
 {
     if (pl.a.n == 0) return;
     const ApplyArgs a = make_apply_args(pl, partial, table, state, stride);
-    const size_t lds = sizeof(float) * (size_t)(kGroupsPerBlock - 1) * stride;
+    const size_t lds = apply_lds_bytes(stride);
+    static size_t allowed = 0;
+    allow_lds(k_apply<NV4, Src, Opt>, lds, &allowed);
     hipLaunchKernelGGL((k_apply<NV4, Src, Opt>), dim3(std::min(max_apply_items(pl), kApplyGrid<NV4>)), dim3(kBlock), lds, s,
                        a, src, opt);
 }
@@ -472,7 +591,9 @@ static void launch_apply2_nv(hipStream_t s, int stride, const U0 &u0, const U1 &
     const ApplyArgs a0 = make_apply_args(*u0.plan, u0.partial, u0.table, u0.state, stride);
     const ApplyArgs a1 = make_apply_args(*u1.plan, u1.partial, u1.table, u1.state, stride);
     const uint32_t items = max_apply_items(*u0.plan) + max_apply_items(*u1.plan);
-    const size_t lds = std::max(sizeof(float) * (size_t)(kGroupsPerBlock - 1) * stride, side_lds);
+    const size_t lds = std::max(apply_lds_bytes(stride), side_lds);
+    static size_t allowed = 0;
+    allow_lds(k_apply2<NV4, decltype(u0.src), decltype(u0.opt), decltype(u1.src), decltype(u1.opt)>, lds, &allowed);
     hipLaunchKernelGGL((k_apply2<NV4, decltype(u0.src), decltype(u0.opt), decltype(u1.src), decltype(u1.opt)>),
                        dim3(sw.blocks + std::max(1u, std::min(items, kApplyGrid<NV4>))), dim3(kBlock), lds, s, a0, u0.src,
                        u0.opt, a1, u1.src, u1.opt, sw);

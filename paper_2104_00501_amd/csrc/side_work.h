@@ -9,6 +9,7 @@
 //   rank    per access: position inside its key's segment; the distinct keys
 //   counts  segment offsets (prefix sums of the per-key counts), chunk lists of long segments
 //   scatter accesses grouped by key; the scratch maps return to all-zero
+//   sort    (deterministic mode only) every segment's accesses in ascending order
 // A launch of a gradient or update kernel carries, in its first workgroups, one phase each of up to kMaxSide later
 // steps: the phases depend on key arrays and random numbers only, never on table values, so they may run while
 // earlier steps still update the tables, and kernel boundaries on one stream order consecutive phases.
@@ -434,6 +435,21 @@ __device__ __forceinline__ void scatter_block(const PlanArgs &a, uint32_t vb)
     }
 }
 
+// Deterministic mode: every segment's accesses once more, in ascending order.  The position of an access is the
+// number of smaller access numbers in its segment, counted by its own thread (quadratic in the segment length, and
+// free of any dependence on the order in which the rank phase's atomics were served).
+__device__ __forceinline__ void sort_block(const PlanArgs &a, uint32_t vb)
+{
+    const uint32_t i = vb * kBlock + threadIdx.x;
+    if (i >= a.n) return;
+    const uint32_t u = a.slot[i];
+    if (u == kBadIndex) return;
+    const uint32_t first = a.seg[u], last = min(a.seg[u + 1], a.n);
+    uint32_t below = 0;
+    for (uint32_t t = first; t < last; ++t) below += a.perm[t] < i ? 1u : 0u;
+    if (first + below < a.n) a.perm_sorted[first + below] = i;   // in range by construction with unchanged key arrays
+}
+
 // ---- dispatch ------------------------------------------------------------------------------------------------------
 
 // Unit `vb` of one phase.  Dynamic LDS of the launch: at least side_lds_bytes(item.phase).
@@ -462,6 +478,7 @@ __device__ __forceinline__ void side_item_unit(const SideItem &it, uint32_t vb)
     case kSideCountTiles: count_tiles_block(a, vb, side_lds); break;
     case kSideCounts: counts_block(a, vb, side_lds); break;
     case kSideScatter: scatter_block(a, vb); break;
+    case kSideSort: sort_block(a, vb); break;
     default: break;
     }
 }

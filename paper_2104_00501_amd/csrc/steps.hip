@@ -164,36 +164,57 @@ nups_status launch_pull(nups_ctx *ctx, const Table &t, const uint32_t *keys, int
 }
 
 // push: table[k] += sum of the update rows sent for k (plan already built over the keys).
-nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, const float *updates)
+nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, float *partial, const float *updates)
 {
     PhaseScope scope(ctx, NUPS_PHASE_PUSH, ctx->stream);
-    return launch_apply(ctx->stream, pl, ctx->partial, t.data, nullptr, t.stride, SrcStaged{updates}, OptAdd{});
+    return launch_apply(ctx->stream, pl, partial, t.data, nullptr, t.stride, SrcStaged{updates}, OptAdd{});
 }
 
 // ------------------------------------------------------------------------------------------------
 // Skip-gram with negative sampling.  One 16-lane group per (center, context) pair:
-//   z_j = <v, u_j>, g_j = sigma(z_j) - label_j, staged input-side gradient = sum_j g_j u_j.
+//   z_j = <v, u_j>, g_j = sigma(z_j) - label_j, input-side gradient of the pair = sum_j g_j u_j.
+// The input-side gradients of a run of consecutive pairs with the same center word (in stream order a word's 2 x
+// window pairs follow each other) are added up inside the workgroup, through LDS, by the group of the run's first
+// pair, in pair order.  If the run holds every pair of its center word in this step (the word's segment in the
+// input table's structure is as long as the run), that group updates the input row right away: it has the row in
+// registers, nobody else reads it in this step, and the output side works from the staged copy of the row.
+// Otherwise the run's sum is staged at the row of its first pair and the update kernel adds the runs of the word.
+// So a staged gradient row is written per run that shares its word with other runs, not per pair.
 // ------------------------------------------------------------------------------------------------
 template <int NV4>
-__global__ void __launch_bounds__(kBlock) k_sgns_grad(const float *in_table, const float *out_table,
+__global__ void __launch_bounds__(kBlock) k_sgns_grad(float *in_table, const float *out_table,
                                                       uint32_t num_in, uint32_t num_out, int stride,
                                                       const uint32_t *center, const uint32_t *context,
-                                                      const uint32_t *negs, uint32_t B, int K, float *coefs,
-                                                      float *stage, const uint32_t *center_slot,
-                                                      const uint32_t *center_rank, float *center_rows, double *loss,
+                                                      const uint32_t *negs, uint32_t B, int K, float lr, float *coefs,
+                                                      float *stage, uint32_t zeros_at, int update_whole_runs,
+                                                      const uint32_t *center_slot, const uint32_t *center_rank,
+                                                      const uint32_t *center_seg, float *center_rows, double *loss,
                                                       SideWork sw)
 {
+    extern __shared__ float run_rows[];   // [kGroupsPerBlock][stride]: the pairs' input-side gradients
     __shared__ float lds[kBlock / 64];
+    __shared__ uint32_t run_key[kGroupsPerBlock];
     if (side_work_block(sw)) return;   // the first sw.blocks workgroups prepare later steps
-    const int lane = threadIdx.x & (kGroup - 1);
-    const uint32_t e_raw = (xcd_block(blockIdx.x - sw.blocks, gridDim.x - sw.blocks) * kBlock + threadIdx.x) / kGroup;
+    const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
+    const uint32_t own_block = blockIdx.x - sw.blocks;
+    const uint32_t e_raw = (xcd_block(own_block, gridDim.x - sw.blocks) * kBlock + threadIdx.x) / kGroup;
     const bool active = e_raw < B;
     const uint32_t e = active ? e_raw : B - 1;
+    if (own_block == 0 && group == kGroupsPerBlock - 1) {   // the row of zeros that pairs inside a run point at
+        Row<NV4> z;
+        zero_row(z);
+        store_row(stage + (size_t)zeros_at * stride, z, lane);
+    }
+    const uint32_t ckey = center[e];
+    const uint32_t slot = center_slot[e];          // kBadIndex: the center key is outside the table
+    uint32_t seg_len = 0;
+    if (slot != kBadIndex) seg_len = center_seg[slot + 1] - center_seg[slot];
     Row<NV4> v, acc;
-    load_row(v, in_table + (size_t)min(center[e], num_in - 1) * stride, lane);
+    float *v_row = in_table + (size_t)min(ckey, num_in - 1) * stride;
+    load_row(v, v_row, lane);
     // the first pair of every distinct center word keeps a copy of the input vector for the output-side update
-    if (active && center_slot[e] != kBadIndex && (center_rank[e] & ~kSingleAccess) == 0)
-        store_row(center_rows + (size_t)center_slot[e] * stride, v, lane);
+    if (active && slot != kBadIndex && (center_rank[e] & ~kSingleAccess) == 0)
+        store_row(center_rows + (size_t)slot * stride, v, lane);
     zero_row(acc);
     float loss_acc = 0.f;
     constexpr int JU = 4;     // rows in flight per group
@@ -219,20 +240,43 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(const float *in_table, con
         }
         if (active && lane < JU && j0 + lane <= K) coefs[(size_t)e * (K + 1) + j0 + lane] = g_mine;
     }
-    if (active) store_row(stage + (size_t)e * stride, acc, lane);
+    // runs of equal center words inside the workgroup (pairs beyond the batch belong to no run)
+    if (lane == 0) run_key[group] = active ? ckey : kBadIndex;
+    store_row(run_rows + (size_t)group * stride, acc, lane);
+    __syncthreads();
+    if (active && slot != kBadIndex && (group == 0 || run_key[group - 1] != ckey)) {
+        uint32_t len = 1;
+        while (group + len < (uint32_t)kGroupsPerBlock && run_key[group + len] == ckey) {
+            Row<NV4> r;
+            load_row(r, run_rows + (size_t)(group + len) * stride, lane);
+            axpy_row(acc, 1.0f, r);
+            ++len;
+        }
+        if (update_whole_runs && len == seg_len) {
+#pragma unroll
+            for (int q = 0; q < NV4; ++q) axpy4(v.v[q], -lr, acc.v[q]);
+            store_row(v_row, v, lane);
+        } else {
+            store_row(stage + (size_t)e * stride, acc, lane);
+        }
+    }
     block_add_loss((active && lane == 0) ? loss_acc : 0.f, loss, lds);
 }
 
 template <int NV4>
 static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b, const Plan &in_plan, float *center_rows,
-                             const SideWork &sw, size_t side_lds)
+                             uint32_t zero_row, bool update_whole_runs, const SideWork &sw, size_t side_lds)
 {
     const Table &tin = ctx->tab[0], &tout = ctx->tab[1];
     const uint32_t blocks = xcd_grid((uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock));
-    hipLaunchKernelGGL(k_sgns_grad<NV4>, dim3(sw.blocks + blocks), dim3(kBlock), side_lds, ctx->stream,
-                       (const float *)tin.data, (const float *)tout.data, (uint32_t)tin.num_keys,
-                       (uint32_t)tout.num_keys, tin.stride, b.k0, b.k1, b.negs, (uint32_t)b.B, (int)b.n_neg, ctx->coef,
-                       ctx->stage, in_plan.a.slot, in_plan.a.rank, center_rows, ctx->loss_cur, sw);
+    const size_t lds = std::max(sizeof(float) * kGroupsPerBlock * (size_t)tin.stride, side_lds);
+    static size_t allowed = 0;
+    allow_lds(k_sgns_grad<NV4>, lds, &allowed);
+    hipLaunchKernelGGL(k_sgns_grad<NV4>, dim3(sw.blocks + blocks), dim3(kBlock), lds, ctx->stream, tin.data,
+                       (const float *)tout.data, (uint32_t)tin.num_keys, (uint32_t)tout.num_keys, tin.stride, b.k0, b.k1,
+                       b.negs, (uint32_t)b.B, (int)b.n_neg, b.lr, ctx->coef, ctx->stage, zero_row, update_whole_runs ? 1 : 0,
+                       (const uint32_t *)in_plan.a.slot, (const uint32_t *)in_plan.a.rank,
+                       (const uint32_t *)in_plan.a.seg, center_rows, ctx->loss_cur, sw);
 }
 
 // Plan side of a step: which keys each table is accessed with (plan 0: table 0, plan 1: table 1).  Sizes the
@@ -278,16 +322,20 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
     const uint32_t B = (uint32_t)b.B, K = (uint32_t)b.n_neg;
     nups_status st;
     if ((st = ensure_f32(&ctx->coef, &ctx->coef_cap, (size_t)B * (K + 1), ctx->stream)) != NUPS_OK) return st;
-    // staged rows: [0, B) per-pair input-side gradients, [B, 2B) input vectors of the distinct center words
-    if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)2 * B * tin.stride, ctx->stream)) != NUPS_OK) return st;
+    // staged rows: [0, B) input-side gradient sums of runs of pairs (at the runs' first pairs), [B, 2B) input
+    // vectors of the distinct center words, row 2B all zero
+    if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, ((size_t)2 * B + 1) * tin.stride, ctx->stream)) != NUPS_OK) return st;
     ctx->loss_cur = p.loss_dev;   // zeroed by the step's plan construction
     if (B == 0) return NUPS_OK;
     float *center_rows = ctx->stage + (size_t)B * tin.stride;
+    const uint32_t zero_row = 2 * B;
+    // With norm clipping on, every update goes through the update kernel, which measures and clips the hot keys'.
+    const bool update_whole_runs = !(ctx->clip_factor > 0.0f);
     size_t side_lds = 0;
     {
         const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
-#define CALL(N) launch_sgns_grad<N>(ctx, b, p.plan[0], center_rows, sw, side_lds)
+#define CALL(N) launch_sgns_grad<N>(ctx, b, p.plan[0], center_rows, zero_row, update_whole_runs, sw, side_lds)
         NUPS_FOR_EACH_ROW_WIDTH(tin.stride, CALL)
 #undef CALL
         NUPS_HIP(hipGetLastError());
@@ -296,8 +344,9 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
         const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
         if ((st = refresh_clip_bounds(ctx)) != NUPS_OK) return st;
-        const TableUpdate<SrcStaged, OptSgd> uin{&p.plan[0], partial_of(ctx, p, 0), tin.data, nullptr,
-                                                 SrcStaged{ctx->stage}, sgd_rule(ctx, 0, b.lr)};
+        const TableUpdate<SrcSgnsIn, OptSgd> uin{&p.plan[0], partial_of(ctx, p, 0), tin.data, nullptr,
+                                                 SrcSgnsIn{ctx->stage, b.k0, zero_row, update_whole_runs},
+                                                 sgd_rule(ctx, 0, b.lr)};
         const TableUpdate<SrcSgnsOut, OptSgd> uout{&p.plan[1], partial_of(ctx, p, 1), tout.data, nullptr,
                                                    SrcSgnsOut{center_rows, p.plan[0].a.slot, ctx->coef, B, K},
                                                    sgd_rule(ctx, 1, b.lr)};

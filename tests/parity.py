@@ -12,7 +12,10 @@ skewed keys a table-wide scale is set by the hot rows and would hide errors in t
   tauD_r = RMS over the row's logical lanes of dref, ulp_i = 2^-23 max(|ref_i|, |before_i|): the stored fp32
   parameter quantises the applied update by up to one unit in its last place, whatever the gradient's accuracy;
   beyond that the update (learning rate x summed gradient) must itself be right to the bar.  This is the check
-  that sees a wrong gradient behind a large parameter.
+  that sees a wrong gradient behind a large parameter.  Where contributions to one element cancel (a negative
+  that equals the context word: coefficients near +1/2 and -1/2 on the same source row), the net update says
+  nothing about the size of what was added up; a test may then pass `gross`, an element-wise bound on
+  learning rate x sum of |source rows| (coefficients bounded by one), as a further floor.
 
 Rows that the oracle leaves untouched must be bit-identical to `before`.
 """
@@ -40,10 +43,11 @@ def param_err(got: np.ndarray, ref: np.ndarray, before: np.ndarray, cols=None):
     return float(np.max(diff / den)), float(np.max(diff))
 
 
-def update_err(got: np.ndarray, ref: np.ndarray, before: np.ndarray, cols=None):
+def update_err(got: np.ndarray, ref: np.ndarray, before: np.ndarray, cols=None, gross=None):
     """Max error of the applied update (table - before) with the per-row floor, net of one ulp of the parameter."""
     if cols is not None:
         got, ref, before = got[:, cols], ref[:, cols], before[:, cols]
+        gross = None if gross is None else gross[:, cols]
     if got.size == 0:
         return 0.0
     got, ref, before = (x.astype(np.float64) for x in (got, ref, before))
@@ -54,7 +58,20 @@ def update_err(got: np.ndarray, ref: np.ndarray, before: np.ndarray, cols=None):
     dref, dgot, mag = dref[touched], dgot[touched], np.maximum(np.abs(ref), np.abs(before))[touched]
     excess = np.maximum(np.abs(dgot - dref) - mag * 2.0 ** -23, 0.0)
     den = np.maximum(np.abs(dref), np.maximum(_rows_rms(dref), 1e-30))
+    if gross is not None:
+        den = np.maximum(den, gross[touched])
     return float(np.max(excess / den))
+
+
+def sgns_gross_updates(In, Out, center, context, negs, K, lr):
+    """Element-wise bound on what one SGNS step adds up per row: lr x sum of |source row| over the row's
+    accesses (every coefficient sigma(z) - label is below one in magnitude).  Only a scale for update_err."""
+    B = len(center)
+    okeys = np.concatenate([np.asarray(context).reshape(B, 1), np.asarray(negs).reshape(B, K)], axis=1)
+    g_in, g_out = np.zeros(In.shape), np.zeros(Out.shape)
+    np.add.at(g_in, np.repeat(center, K + 1), np.abs(Out[okeys.ravel()]))
+    np.add.at(g_out, okeys.ravel(), np.abs(In[np.repeat(center, K + 1)]))
+    return lr * g_in, lr * g_out
 
 
 def untouched_rows_identical(got: np.ndarray, ref: np.ndarray, before: np.ndarray) -> bool:
@@ -63,10 +80,10 @@ def untouched_rows_identical(got: np.ndarray, ref: np.ndarray, before: np.ndarra
     return bool(np.array_equal(got[same], before[same]))
 
 
-def assert_table(got, ref, before, cols, tol, what, tol_update=TOL_UPDATE):
+def assert_table(got, ref, before, cols, tol, what, tol_update=TOL_UPDATE, gross=None):
     """Both checks, the untouched rows and the padding lanes; prints the measured figures."""
     rel, ab = param_err(got, ref, before, cols)
-    ue = update_err(got, ref, before, cols)
+    ue = update_err(got, ref, before, cols, gross)
     print("%s: parameter err %.3g (abs %.3g), update err %.3g" % (what, rel, ab, ue))
     assert rel <= tol, "%s: parameter error %.3g (abs %.3g) > %.1g" % (what, rel, ab, tol)
     if tol_update is not None:

@@ -96,3 +96,35 @@ def test_push_into_a_table_with_more_tiles_than_a_workgroup_scans():
     assert np.abs(got.cpu().numpy() - expect).max() < 1e-5
     assert float(table.abs().sum().item()) == pytest.approx(float(np.abs(expect.astype(np.float32)).sum()), rel=1e-4)
     nb.nups_destroy(ctx)
+
+
+def test_push_with_hundreds_of_segments_of_many_chunks():
+    # 400 keys with about 5,000 updates each: every segment is cut into about twenty chunks whose partial rows
+    # travel between workgroups; the workgroup that counts a segment's last chunk in adds them up
+    import torch
+    V, d, n, hot = 50_000, 64, 2_000_000, 400
+    rng = np.random.default_rng(12)
+    keys = (rng.integers(0, hot, n) * 101 % V).astype(np.uint32)
+    assert np.bincount(keys).max() > 8 * 256 and len(np.unique(keys)) == hot
+    upd = wl.uniform_table(n, d, -1e-2, 1e-2, 13)
+    T = wl.uniform_table(V, d, -1.0, 1.0, 14)
+    for deterministic in (False, True):
+        table = dev(T)
+        ctx = nb.nups_init([table], [d])
+        nb.nups_set_deterministic(ctx, deterministic)
+        nb.nups_push(ctx, 0, dev_u32(keys), n, dev(upd))
+        nb.nups_check(ctx)
+        ref = T.copy()
+        orc.push(ref, d, keys, upd)
+        got = table.cpu().numpy()
+        assert_table(got, ref, T, list(range(d)), TOL_ONE_STEP, "table after a push of long segments")
+        if deterministic:
+            table2 = dev(T)
+            ctx2 = nb.nups_init([table2], [d])
+            nb.nups_set_deterministic(ctx2, True)
+            nb.nups_set_hot_keys(ctx2, 0, np.zeros(0, dtype=np.uint32))     # every segment by one row group
+            nb.nups_push(ctx2, 0, dev_u32(keys), n, dev(upd))
+            nb.nups_check(ctx2)
+            assert np.array_equal(table2.cpu().numpy(), got)
+            nb.nups_destroy(ctx2)
+        nb.nups_destroy(ctx)
