@@ -147,6 +147,22 @@ nups_status nups_pull(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_
  * within one call add up, each key is written once).  updates_dev is [n, row_stride]. */
 nups_status nups_push(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_t n, const float *updates_dev);
 
+/*
+ * The same push for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid it): nups_push_static calls no hipMalloc / hipFree and no allocating
+ * library routine.  Its workspace is one file-scope device array of fixed size (about 6 MB, held by every GPU the
+ * library runs on until the process ends), which limits it to n <= NUPS_STATIC_MAX_PUSH keys per call and tables
+ * of at most NUPS_STATIC_MAX_KEYS keys (any supported row_stride); beyond either, NUPS_ERR_ARG, and nups_push is
+ * the call to use.  Same arguments, same result as nups_push (to fp32 summation order; identical bits in
+ * deterministic mode); nups_debug_structure describes it afterwards like any push.  Every call on a GPU,
+ * from whichever context, shares that GPU's array: calls whose kernels overlap on one GPU (different streams)
+ * race; calls on one stream are ordered and safe.  The part of the array that must start at zero is cleared by a
+ * kernel at the start of every call.
+ */
+#define NUPS_STATIC_MAX_PUSH 16384
+#define NUPS_STATIC_MAX_KEYS 1048576
+nups_status nups_push_static(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_t n, const float *updates_dev);
+
 /* ---- sampling access (Sections 4.3, 4.4) ---------------------------------------- */
 
 /*

@@ -17,13 +17,14 @@ NUPS_OK, NUPS_ERR_ARG, NUPS_ERR_KEY_RANGE, NUPS_ERR_OVERPULL = 0, -1, -2, -3
 NUPS_ERR_STATE, NUPS_ERR_DEVICE, NUPS_ERR_UNIMPLEMENTED = -4, -5, -6
 NUPS_CONFORM, NUPS_BOUNDED, NUPS_LONGTERM, NUPS_NONCONFORM = 1, 2, 3, 4
 NUPS_TASK_SGNS, NUPS_TASK_MF, NUPS_TASK_KGE = 1, 2, 3
+NUPS_STATIC_MAX_PUSH, NUPS_STATIC_MAX_KEYS = 16384, 1048576
 (NUPS_PHASE_SAMPLE, NUPS_PHASE_PLAN, NUPS_PHASE_GRAD, NUPS_PHASE_APPLY0, NUPS_PHASE_APPLY1, NUPS_PHASE_PULL,
  NUPS_PHASE_PUSH, NUPS_PHASE_COUNT) = range(8)
 
 EXPORTS = [
     "nups_init", "nups_destroy", "nups_set_state", "nups_set_hot_keys", "nups_set_deterministic",
     "nups_set_update_clipping",
-    "nups_get_update_clipping", "nups_pull", "nups_push",
+    "nups_get_update_clipping", "nups_pull", "nups_push", "nups_push_static",
     "nups_build_alias_table", "nups_register_distribution", "nups_register_distribution_at_level",
     "nups_select_hot_keys", "nups_set_local_keys", "nups_prepare_sample",
     "nups_pull_sample", "nups_sample_keys", "nups_release_sample", "nups_step", "nups_prepare_step",
@@ -140,6 +141,10 @@ def nups_get_update_clipping(ctx, table):
 
 def nups_pull(ctx, table, keys, n, values):
     _check(lib().nups_pull(ctx, C.c_int(table), _ptr(keys), C.c_int64(n), _ptr(values)))
+
+
+def nups_push_static(ctx, table, keys, n, updates):
+    _check(lib().nups_push_static(ctx, C.c_int(table), _ptr(keys), C.c_int64(n), _ptr(updates)))
 
 
 def nups_push(ctx, table, keys, n, updates):

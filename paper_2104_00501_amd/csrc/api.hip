@@ -265,6 +265,10 @@ nups_status nups_init(nups_ctx **out, int n_tables, float *const *tables_dev, co
         nups_destroy(ctx);
         return NUPS_ERR_DEVICE;
     }
+    if (static_scratch_setup(ctx->device) != NUPS_OK) {   // the address of this device's copy of the static scratch
+        nups_destroy(ctx);
+        return NUPS_ERR_DEVICE;
+    }
     *out = ctx;
     return NUPS_OK;
 }
@@ -275,6 +279,7 @@ nups_status nups_destroy(nups_ctx *ctx)
     (void)hipStreamSynchronize(ctx->stream);
     for (nups_dist *d : ctx->dists) free_dist(d);
     for (nups_prepared *p : ctx->prepared_all) free_prepared(p);
+    delete ctx->static_push;   // its arrays are not its own
     for (int t = 0; t < kMaxTables; ++t)
         if (ctx->tab[t].hot_bits_dev) (void)hipFree(ctx->tab[t].hot_bits_dev);
     if (ctx->clip_stats) (void)hipFree(ctx->clip_stats);

@@ -210,6 +210,7 @@ struct nups_ctx {
     std::vector<nups_dist *> dists;
     std::vector<nups_prepared *> prepared_all;   // every prepared-step object ever created (owned)
     std::vector<nups_prepared *> prepared_free;  // run and no longer referenced by a structure query
+    nups_prepared *static_push = nullptr;        // the structure of nups_push_static: its arrays are the static scratch
 };
 
 struct nups_dist {
@@ -256,6 +257,7 @@ struct PhaseScope {
 SampleArgs sample_args(const nups_dist *d, uint32_t *keys_out, int64_t n_samples, uint64_t step);
 nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n);
 void set_plan_shape(const nups_ctx *ctx, const Table &t, Plan &pl);
+nups_status static_scratch_setup(int device);   // once per device, with that device current
 void build_phases(nups_prepared &p, const SampleArgs &draw, int mark_plan);
 size_t side_lds_bytes(const SideItem &it);
 SideWork take_side_work(nups_ctx *ctx, size_t *lds_bytes, uint32_t max_wgs_per_phase);

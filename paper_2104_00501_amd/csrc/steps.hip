@@ -4,6 +4,8 @@
 // kernel reads the tables as they are at the start of the step and writes only coefficients
 // and staged gradient rows; the tables are updated afterwards, once per distinct key
 // (segment_apply.h).
+#include <mutex>
+
 #include "segment_apply.h"
 
 namespace nups {
@@ -741,3 +743,144 @@ nups_status run_step_kge(nups_ctx *ctx, nups_prepared &p)
 }
 
 }  // namespace nups
+
+// ------------------------------------------------------------------------------------------------
+// nups_push_static: the push for callers that cannot allocate.  Everything that nups_push keeps in allocated
+// workspace (the scratch maps and result arrays of the per-key structure, the partial rows of chunked segments)
+// lives in one file-scope device array of a fixed size.  Host code never uses the array's name as an address: the
+// address of a device's copy is asked for once (static_scratch_setup) and kept per device.
+// ------------------------------------------------------------------------------------------------
+namespace nups {
+
+constexpr size_t kStaticKeys = NUPS_STATIC_MAX_KEYS, kStaticPush = NUPS_STATIC_MAX_PUSH;
+constexpr size_t kStaticWordsOfMap = (kStaticKeys + 31) / 32;
+constexpr size_t kStaticChunks = kStaticPush / kChunk + kStaticPush / (kLongSegment + 1) + 2;   // max_chunks(kStaticPush)
+constexpr size_t kStaticTiles = (kStaticWordsOfMap > kStaticPush ? kStaticWordsOfMap : kStaticPush) / kScanTile + 1;
+constexpr size_t align64(size_t words) { return (words + 63) / 64 * 64; }   // regions start on 256-byte boundaries
+
+// Offsets (in 32-bit words) of the regions.  The first kStaticZeroWords words are what a build expects to be zero.
+struct StaticLayout {
+    size_t bytemap, wordmap, cnt_work, chunk_done, meta, zero_end, bitmap, word_rank, tile_sum, tile_prefix, uniq, count,
+        seg, perm, perm_sorted, slot, rank, chunk_seg, chunk_base, partial, end;
+};
+
+constexpr StaticLayout static_layout()
+{
+    StaticLayout l{};
+    size_t at = 0;
+    auto take = [&at](size_t words) { const size_t start = at; at += align64(words); return start; };
+    l.bytemap = take(kStaticWordsOfMap * 8);
+    l.wordmap = take((kStaticWordsOfMap + 3) / 4);
+    l.cnt_work = take((kStaticPush + kScanTile - 1) / kScanTile * kScanTile);
+    l.chunk_done = take(kStaticChunks);
+    l.meta = take(kMetaWords);
+    l.zero_end = at;
+    l.bitmap = take(kStaticWordsOfMap);
+    l.word_rank = take(kStaticWordsOfMap);
+    l.tile_sum = take(kStaticTiles);
+    l.tile_prefix = take(kStaticTiles);
+    l.uniq = take(kStaticPush);
+    l.count = take(kStaticPush);
+    l.seg = take(kStaticPush + 1);
+    l.perm = take(kStaticPush);
+    l.perm_sorted = take(kStaticPush);
+    l.slot = take(kStaticPush);
+    l.rank = take(kStaticPush);
+    l.chunk_seg = take(kStaticChunks);
+    l.chunk_base = take(kStaticChunks);
+    l.partial = take(kStaticChunks * (size_t)kMaxStride);
+    l.end = at;
+    return l;
+}
+
+constexpr StaticLayout kStaticLayout = static_layout();
+
+static __device__ __align__(256) uint32_t scratch[kStaticLayout.end];   // about 6 MB per device, for the life of the process
+
+constexpr int kMaxDevices = 64;
+static uint32_t *g_scratch_of_device[kMaxDevices];   // device address of each device's copy; null: not asked for yet
+static std::mutex g_scratch_mutex;
+
+nups_status static_scratch_setup(int device)
+{
+    if (device < 0 || device >= kMaxDevices) return fail(NUPS_ERR_DEVICE, "device ordinal out of range");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_of_device[device]) return NUPS_OK;
+    uint32_t *ptr = nullptr;
+    NUPS_HIP(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));   // of the current device's copy
+    if (!ptr) return fail(NUPS_ERR_DEVICE, "no address for the static scratch");
+    g_scratch_of_device[device] = ptr;
+    return NUPS_OK;
+}
+
+__global__ void __launch_bounds__(kBlock) k_fill_zero(uint32_t *words, uint32_t n)
+{
+    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+    if (i < n) words[i] = 0u;
+}
+
+}  // namespace nups
+
+extern "C" nups_status nups_push_static(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_t n,
+                                        const float *updates_dev)
+{
+    using namespace nups;
+    if (!ctx || table < 0 || table >= ctx->n_tables) return fail(NUPS_ERR_ARG, "nups_push_static: bad context or table");
+    if (n < 0 || (n > 0 && (!keys_dev || !updates_dev))) return fail(NUPS_ERR_ARG, "nups_push_static: bad arguments");
+    Table &t = ctx->tab[table];
+    if (n > (int64_t)kStaticPush)
+        return fail(NUPS_ERR_ARG, "nups_push_static: at most NUPS_STATIC_MAX_PUSH keys per call (use nups_push)");
+    if (t.num_keys > (int64_t)kStaticKeys)
+        return fail(NUPS_ERR_ARG, "nups_push_static: tables of at most NUPS_STATIC_MAX_KEYS keys (use nups_push)");
+    uint32_t *base = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        base = (ctx->device >= 0 && ctx->device < kMaxDevices) ? g_scratch_of_device[ctx->device] : nullptr;
+    }
+    if (!base) return fail(NUPS_ERR_STATE, "nups_push_static: the static scratch of this device was not set up");
+    if (!ctx->static_push) {          // host-side object only
+        ctx->static_push = new nups_prepared();
+        ctx->static_push->ctx = ctx;
+    }
+    nups_prepared *p = ctx->static_push;
+    constexpr StaticLayout L = kStaticLayout;
+    Plan &pl = p->plan[0];
+    PlanArgs &a = pl.a;
+    a.bytemap = (uint8_t *)(base + L.bytemap);
+    a.wordmap = (uint8_t *)(base + L.wordmap);
+    a.cnt_work = base + L.cnt_work;
+    a.chunk_done = base + L.chunk_done;
+    a.meta = base + L.meta;
+    a.bitmap = base + L.bitmap;
+    a.word_rank = base + L.word_rank;
+    a.tile_sum = base + L.tile_sum;
+    a.tile_prefix = base + L.tile_prefix;
+    a.uniq = base + L.uniq;
+    a.count = base + L.count;
+    a.seg = base + L.seg;
+    a.perm = base + L.perm;
+    a.perm_sorted = base + L.perm_sorted;
+    a.slot = base + L.slot;
+    a.rank = base + L.rank;
+    a.chunk_seg = base + L.chunk_seg;
+    a.chunk_base = base + L.chunk_base;
+    pl.cap_n = kStaticPush;
+    pl.cap_words = kStaticWordsOfMap;
+    pl.cap_tiles = kStaticTiles;
+    pl.table = table;
+    p->n_plans = 1;
+    set_plan_shape(ctx, t, pl);
+    a.src = KeySource{{keys_dev, nullptr, nullptr}, {(uint32_t)n, 0, 0}};
+    a.n = a.mark_n = (uint32_t)n;
+    a.zero_loss = nullptr;
+    // The array is shared by every call on this device and keeps the last call's contents: what a build expects
+    // to be zero is cleared first, by a kernel (a memset node would not do for callers that capture the stream).
+    hipLaunchKernelGGL(k_fill_zero, dim3((uint32_t)((L.zero_end + kBlock - 1) / kBlock)), dim3(kBlock), 0, ctx->stream, base,
+                       (uint32_t)L.zero_end);
+    NUPS_HIP(hipGetLastError());
+    build_phases(*p, SampleArgs{}, -1);
+    nups_status st = flush_side_work(ctx, p);
+    if (st == NUPS_OK && n > 0) st = launch_push_apply(ctx, t, pl, (float *)(base + L.partial), updates_dev);
+    t.last_plan = &pl;                // nups_debug_structure describes this call until the next step or push
+    return st;
+}
