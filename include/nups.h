@@ -150,7 +150,7 @@ nups_status nups_push(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_
 /*
  * The same push for callers that cannot allocate device memory (code under HIP graph capture, tight
  * serving loops, harnesses that forbid it): nups_push_static calls no hipMalloc / hipFree and no allocating
- * library routine.  Its workspace is one file-scope device array of fixed size (about 6 MB, held by every GPU the
+ * library routine.  Its workspace is one file-scope device array of fixed size (about 14 MB, held by every GPU the
  * library runs on until the process ends), which limits it to n <= NUPS_STATIC_MAX_PUSH keys per call and tables
  * of at most NUPS_STATIC_MAX_KEYS keys (any supported row_stride); beyond either, NUPS_ERR_ARG, and nups_push is
  * the call to use.  Same arguments, same result as nups_push (to fp32 summation order; identical bits in

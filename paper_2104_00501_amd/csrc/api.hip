@@ -287,6 +287,7 @@ nups_status nups_destroy(nups_ctx *ctx)
     if (ctx->coef) (void)hipFree(ctx->coef);
     if (ctx->stage) (void)hipFree(ctx->stage);
     if (ctx->partial) (void)hipFree(ctx->partial);
+    if (ctx->totals) (void)hipFree(ctx->totals);
     if (ctx->error_flag) (void)hipFree(ctx->error_flag);
     if (ctx->loss_pinned) (void)hipHostFree(ctx->loss_pinned);
     if (ctx->flag_pinned) (void)hipHostFree(ctx->flag_pinned);
@@ -395,13 +396,14 @@ nups_status nups_push(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_
     p->plan[0].table = table;
     if ((st = ensure_plan_capacity(ctx, t, p->plan[0], (size_t)n)) == NUPS_OK)
         st = ensure_partial(ctx, max_chunks(p->plan[0].cap_n) * (size_t)t.stride);
+    if (st == NUPS_OK) st = ensure_totals(ctx, t.stride);
     if (st != NUPS_OK) { ctx->prepared_free.push_back(p); return st; }   // nothing was enqueued: the object is free again
     p->plan[0].a.src = KeySource{{keys_dev, nullptr, nullptr}, {(uint32_t)n, 0, 0}};
     p->plan[0].a.n = p->plan[0].a.mark_n = (uint32_t)n;
     p->plan[0].a.zero_loss = nullptr;
     build_phases(*p, SampleArgs{}, -1);
     st = flush_side_work(ctx, p);
-    if (st == NUPS_OK && n > 0) st = launch_push_apply(ctx, t, p->plan[0], ctx->partial, updates_dev);
+    if (st == NUPS_OK && n > 0) st = launch_push_apply(ctx, t, p->plan[0], ctx->partial, ctx->totals, 0xFFFFFFFFu, updates_dev);
     retire_prepared(ctx, p);
     return st;
 }
@@ -650,6 +652,7 @@ nups_status nups_step_prepared(nups_ctx *ctx, nups_prepared *p, double *loss_sum
     if (p->ctx != ctx) return fail(NUPS_ERR_ARG, "nups_step_prepared: the step was prepared on another context");
     if (!p->live) return fail(NUPS_ERR_STATE, "nups_step_prepared: the prepared step was already run");
     nups_status st = flush_side_work(ctx, p);   // whatever earlier launches have not carried
+    ctx->want_loss = loss_sum_host != nullptr;
     if (st == NUPS_OK) {
         switch (p->batch.task) {
         case NUPS_TASK_SGNS: st = run_step_sgns(ctx, *p); break;

@@ -27,7 +27,8 @@ constexpr int kLossStride = 16;
 // Flag in rank[i]: access i is the only access of its key in this step (its position is then 0).
 constexpr uint32_t kSingleAccess = 0x80000000u;
 constexpr uint32_t kLongSegment = 16; // segments with more accesses are summed by whole workgroups, in chunks
-constexpr uint32_t kChunk = 256;      // accesses of a long segment that one workgroup sums
+constexpr uint32_t kChunk = 256;      // accesses of a long segment that one workgroup sums (a super-block)
+constexpr uint32_t kTreeBlock = kChunk / kGroupsPerBlock;   // accesses of a long segment that are added one after the other (a block: what one row group sums of a chunk)
 constexpr uint32_t kBadIndex = 0xFFFFFFFFu;
 constexpr int kSlotItems = 2;                       // accesses per thread in the slot phase of the preparatory work
 constexpr int kSlotTile = kBlock * kSlotItems;
@@ -91,6 +92,7 @@ struct PlanArgs {
     uint32_t *perm;        // [n]         accesses grouped by key (inside a segment: in the order positions were handed out)
     uint32_t *perm_sorted; // [n]         the same with every segment in ascending order (deterministic mode only)
     uint32_t *slot;        // [n]         per access: index of its key among the distinct keys
+    uint32_t *pos;         // [n]         per access: where it stands in perm (perm_sorted in deterministic mode)
     uint32_t *rank;        // [n]         per access: position inside its key's segment (| kSingleAccess)
     uint32_t *chunk_seg;   // [max_chunks]  distinct-key index of the long segment a chunk belongs to
     uint32_t *chunk_base;  // [max_chunks]  number of the first chunk of that segment
@@ -196,7 +198,9 @@ struct nups_ctx {
     float *coef = nullptr;      size_t coef_cap = 0;      // per (example, scored row) loss derivative
     float *stage = nullptr;     size_t stage_cap = 0;     // staged gradient rows
     float *partial = nullptr;   size_t partial_cap = 0;   // partial sums of the chunks of long segments
+    float *totals = nullptr;    size_t totals_cap = 0;    // running totals of long segments summed by single row groups
     double *loss_cur = nullptr;                            // loss accumulator of the step being run
+    bool want_loss = true;                                 // the caller of the step being run asked for its loss
     uint32_t *error_flag = nullptr;                        // device word
     double *loss_pinned = nullptr;                         // pinned host copies for read-back
     uint32_t *flag_pinned = nullptr;
@@ -265,7 +269,8 @@ nups_status flush_side_work(nups_ctx *ctx, nups_prepared *p);
 nups_status launch_side(nups_ctx *ctx, const SideItem &it);
 void free_plan_arrays(Plan &pl);
 nups_status launch_pull(nups_ctx *ctx, const Table &t, const uint32_t *keys, int64_t n, float *values);
-nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, float *partial, const float *updates);
+nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, float *partial, float *totals,
+                              uint32_t grid_cap, const float *updates);
 nups_status plan_step_sgns(nups_ctx *ctx, nups_prepared &p);   // capacity + plan arguments
 nups_status plan_step_mf(nups_ctx *ctx, nups_prepared &p);
 nups_status plan_step_kge(nups_ctx *ctx, nups_prepared &p);
@@ -275,5 +280,6 @@ nups_status run_step_kge(nups_ctx *ctx, nups_prepared &p);
 nups_status ensure_f32(float **buf, size_t *cap, size_t need, hipStream_t stream);
 size_t max_chunks(size_t n);
 nups_status ensure_partial(nups_ctx *ctx, size_t need);
+nups_status ensure_totals(nups_ctx *ctx, int stride);   // room for an update launch of rows of `stride` floats
 
 }  // namespace nups

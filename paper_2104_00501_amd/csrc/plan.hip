@@ -25,10 +25,17 @@ nups_status ensure_partial(nups_ctx *ctx, size_t need)
     return ensure_f32(&ctx->partial, &ctx->partial_cap, need, ctx->stream);
 }
 
+// Room for the running totals of an update launch over rows of `stride` floats (its largest grid).
+nups_status ensure_totals(nups_ctx *ctx, int stride)
+{
+    const size_t grid = stride / 64 <= 2 ? 8192 : 2048;   // apply_grid_of_stride (segment_apply.h)
+    return ensure_f32(&ctx->totals, &ctx->totals_cap, grid * kGroupsPerBlock * (size_t)stride, ctx->stream);
+}
+
 void free_plan_arrays(Plan &pl)
 {
     PlanArgs &a = pl.a;
-    for (uint32_t *p : {a.uniq, a.count, a.seg, a.perm, a.perm_sorted, a.slot, a.rank, a.chunk_seg, a.chunk_base, a.chunk_done, a.meta,
+    for (uint32_t *p : {a.uniq, a.count, a.seg, a.perm, a.perm_sorted, a.slot, a.pos, a.rank, a.chunk_seg, a.chunk_base, a.chunk_done, a.meta,
                         a.bitmap, a.word_rank, a.tile_sum, a.tile_prefix, a.cnt_work})
         if (p) (void)hipFree(p);
     if (a.bytemap) (void)hipFree(a.bytemap);
@@ -54,7 +61,7 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
     if (pl.cap_n < n || pl.cap_n == 0) {
         NUPS_HIP(hipStreamSynchronize(ctx->stream));
         const size_t cap = n + n / 4 + 1024;
-        for (uint32_t **b : {&a.uniq, &a.count, &a.perm, &a.perm_sorted, &a.slot, &a.rank})
+        for (uint32_t **b : {&a.uniq, &a.count, &a.perm, &a.perm_sorted, &a.slot, &a.pos, &a.rank})
             if ((st = grow_u32(b, cap, false)) != NUPS_OK) return st;
         if ((st = grow_u32(&a.cnt_work, (cap + kScanTile - 1) / kScanTile * kScanTile, true)) != NUPS_OK) return st;   // whole tiles
         if ((st = grow_u32(&a.seg, cap + 1, false)) != NUPS_OK) return st;

@@ -5,12 +5,14 @@
 // Short segments take one row group each; long segments (the hot keys of Section 3.2) are cut into
 // chunks, one workgroup per chunk, whose partial rows are combined by the workgroup that finishes last.
 //
-// The order of the additions is a fixed tree over the positions of a segment, whichever path sums it: sixteen
-// consecutive accesses are added one after the other (a block), sixteen consecutive block sums one after the other
-// (a super-block of kChunk = 256 accesses: what one workgroup sums of a chunked segment), and the super-block
-// sums one after the other.  A long chain of fp32 additions never forms (the error of a sum of n terms grows with
-// sqrt(16) + sqrt(16) + sqrt(n / 256) rather than sqrt(n)), and with the accesses of a segment in ascending order
-// (a plan built in deterministic mode) the result does not depend on the run or on which keys are declared hot.
+// The order of the additions is a fixed function of a segment's length, whichever path sums it.  Up to
+// kLongSegment = 16 accesses: one after the other.  Longer: kTreeBlock = 16 consecutive accesses are added one
+// after the other (a block), sixteen consecutive block sums one after the other (a super-block of kChunk = 256
+// accesses: what one workgroup sums of a chunked segment), and the super-block sums one after the other.  (Blocks
+// of 4 and chunks of 64 make a chunk's workgroup finish in 4 instead of 7 us, but there are then more workgroups
+// than the device holds at once: 38.8 against 37.6 us per step of the large skip-gram configuration.)  A long
+// chain of fp32 additions never forms, and with the accesses of a segment in ascending order (a plan built in
+// deterministic mode) the result does not depend on the run or on which keys are declared hot.
 #pragma once
 
 #include <algorithm>
@@ -33,6 +35,13 @@ struct SrcStaged {
     __device__ __forceinline__ float coef(uint32_t) const { return 1.0f; }
     __device__ __forceinline__ const float *rows() const { return stage; }
     __device__ __forceinline__ uint32_t row_number(uint32_t i) const { return i; }
+    // coefficient and source row number of the access at position t of the plan's access order
+    __device__ __forceinline__ void fetch(const uint32_t *perm, uint32_t t, float &c, uint32_t &r) const
+    {
+        const uint32_t i = perm[t];
+        c = coef(i);
+        r = row_number(i);
+    }
 };
 
 // SGNS input side: access i is pair i, its key the pair's center word.  The gradient kernel has added up the
@@ -63,28 +72,31 @@ struct SrcSgnsIn {
     __device__ __forceinline__ float coef(uint32_t) const { return 1.0f; }
     __device__ __forceinline__ const float *rows() const { return stage; }
     __device__ __forceinline__ uint32_t row_number(uint32_t i) const { return run_head(i) ? i : zero_row; }
+    // coefficient and source row number of the access at position t of the plan's access order
+    __device__ __forceinline__ void fetch(const uint32_t *perm, uint32_t t, float &c, uint32_t &r) const
+    {
+        const uint32_t i = perm[t];
+        c = coef(i);
+        r = row_number(i);
+    }
 };
 
-// SGNS output side: access i < B is the context word of pair i, access B + p is negative p (pair p / K).
-// The gradient of the scored row is coef * (input vector of the pair's center word, as it was at the start of
-// the step).  Those vectors are read from a staged copy, one row per distinct center word (row number = the
-// pair's slot in the input table's plan), so that the input table may be updated at the same time.
+// SGNS output side: the gradient of a scored row (the pair's context word or one of its negatives) is
+// coef * (input vector of the pair's center word, as it was at the start of the step).  Those vectors are read from
+// a staged copy, one row per distinct center word, so that the input table may be updated at the same time.  The
+// gradient kernel leaves coefficient and row number of every access where the access stands in the output table's
+// access order (it knows the positions from the structure), so the update reads them in order, with no look-up
+// through the access numbers in between.
 struct SrcSgnsOut {
-    const float *center_rows;     // [distinct centers][stride]
-    const uint32_t *center_slot;  // [B] slot of each pair's center word
-    const float *coefs;           // [B, K + 1]
-    uint32_t B, K;
+    const float *center_rows;   // [distinct centers][stride]
+    const float *coef_at;       // [accesses] in the plan's access order
+    const uint32_t *row_at;     // [accesses] row of center_rows (the center word's index among the distinct ones)
     __device__ __forceinline__ bool segment_done(const uint32_t *, uint32_t, uint32_t, int) const { return false; }
-    __device__ __forceinline__ uint32_t pair_of(uint32_t i) const { return i < B ? i : (i - B) / K; }
-    __device__ __forceinline__ float coef(uint32_t i) const
-    {
-        return i < B ? coefs[(size_t)i * (K + 1)] : coefs[(size_t)((i - B) / K) * (K + 1) + 1 + (i - B) % K];
-    }
     __device__ __forceinline__ const float *rows() const { return center_rows; }
-    __device__ __forceinline__ uint32_t row_number(uint32_t i) const
+    __device__ __forceinline__ void fetch(const uint32_t *, uint32_t t, float &c, uint32_t &r) const
     {
-        const uint32_t slot = center_slot[pair_of(i)];
-        return slot == kBadIndex ? 0u : slot;   // bad center key: flagged, row 0 used
+        c = coef_at[t];
+        r = row_at[t];
     }
 };
 
@@ -109,6 +121,13 @@ struct SrcKgeEntity {
         if (i < 2 * B) return i;
         const uint32_t p = i - 2 * B, e = p / nn;
         return ((p % nn) < nh ? 2 * B : 3 * B) + e;
+    }
+    // coefficient and source row number of the access at position t of the plan's access order
+    __device__ __forceinline__ void fetch(const uint32_t *perm, uint32_t t, float &c, uint32_t &r) const
+    {
+        const uint32_t i = perm[t];
+        c = coef(i);
+        r = row_number(i);
     }
 };
 
@@ -162,7 +181,7 @@ struct OptSgd {          // theta <- theta - lr * delta
     {
 #pragma unroll
         for (int q = 0; q < NV4; ++q) axpy4(t.v[q], -lr, d.v[q]);
-        store_row(row, t, lane);
+        store_row_through(row, t, lane);
     }
 };
 
@@ -182,7 +201,7 @@ struct OptAdd {          // theta <- theta + delta   (push)
     {
 #pragma unroll
         for (int q = 0; q < NV4; ++q) axpy4(t.v[q], 1.0f, d.v[q]);
-        store_row(row, t, lane);
+        store_row_through(row, t, lane);
     }
 };
 
@@ -218,8 +237,8 @@ struct OptAdagrad {      // G <- G + delta^2 ; theta <- theta - lr * delta / (sq
             one(t.v[q].z, g.v[q].z, d.v[q].z);
             one(t.v[q].w, g.v[q].w, d.v[q].w);
         }
-        store_row(state_row, g, lane);
-        store_row(row, t, lane);
+        store_row_through(state_row, g, lane);
+        store_row_through(row, t, lane);
     }
 };
 
@@ -236,95 +255,106 @@ struct ApplyArgs {
     uint32_t n;            // accesses of the plan
     uint32_t max_chunks;   // capacity of the chunk lists and of `partial`
     uint32_t deterministic; // the chunks' partial rows are added in chunk order by one group, however many
+    float *totals;         // [workgroups of the launch][kGroupsPerBlock][stride] running totals of segments of more
+                           // than kChunk accesses that one group sums by itself
 };
 
-// LDS of the update kernels: two rows per row group.  Row `group` of the first half holds a group's block sum
-// while a chunk is combined, or the running super-block sum of a long segment that one group sums by itself;
-// row `group` of the second half that segment's running total.
-__host__ __device__ constexpr size_t apply_lds_bytes(int stride) { return sizeof(float) * 2 * kGroupsPerBlock * (size_t)stride; }
+// LDS of the update kernels: one row per row group.  Row `group` holds a group's block sum while a chunk is
+// combined, or the running super-block sum of a long segment that one group sums by itself (that segment's running
+// total over super-blocks, needed beyond kChunk accesses only, lives in global memory: ApplyArgs::totals).
+__host__ __device__ constexpr size_t apply_lds_bytes(int stride) { return sizeof(float) * kGroupsPerBlock * (size_t)stride; }
 
-// Four accesses of a block of sixteen: their coefficients and source row numbers sit in lanes kFirst .. kFirst + 3
-// of the group (c, r); m = accesses in the block, kFirst < m.  The rows are requested together and added in order.
-template <int NV4, int kFirst>
-__device__ __forceinline__ void sum_four(Row<NV4> &acc, const float *rows, uint32_t r, float c, uint32_t m, int stride,
+// Rows that a group requests together while it sums a block.  More rows in flight hide more latency per group but
+// cost a row of registers each; with rows of 320 floats and more, two in flight keep the update kernels at four
+// wavefronts per SIMD, so that every work item of a step of the large skip-gram configuration is resident at once.
+template <int NV4>
+constexpr int kRowsInFlight = NV4 >= 5 ? 2 : 4;
+
+// kRows accesses of a block of sixteen: their coefficients and source row numbers sit in lanes kFirst .. kFirst +
+// kRows - 1 of the group (c, r); m = accesses in the block, kFirst < m.  The rows are requested together and added
+// in order.
+template <int NV4, int kFirst, int kRows>
+__device__ __forceinline__ void sum_rows(Row<NV4> &acc, const float *rows, uint32_t r, float c, uint32_t m, int stride,
                                          int lane)
 {
-    const uint32_t i0 = group_share<kFirst>(r), i1 = group_share<kFirst + 1>(r), i2 = group_share<kFirst + 2>(r),
-                   i3 = group_share<kFirst + 3>(r);
-    Row<NV4> r0, r1, r2, r3;
-    load_row(r0, rows + (size_t)i0 * stride, lane);
-    if (kFirst + 1 < m) load_row(r1, rows + (size_t)i1 * stride, lane);
-    if (kFirst + 2 < m) load_row(r2, rows + (size_t)i2 * stride, lane);
-    if (kFirst + 3 < m) load_row(r3, rows + (size_t)i3 * stride, lane);
-    const float c0 = group_share<kFirst>(c), c1 = group_share<kFirst + 1>(c), c2 = group_share<kFirst + 2>(c),
-                c3 = group_share<kFirst + 3>(c);
-    axpy_row(acc, c0, r0);
-    if (kFirst + 1 < m) axpy_row(acc, c1, r1);
-    if (kFirst + 2 < m) axpy_row(acc, c2, r2);
-    if (kFirst + 3 < m) axpy_row(acc, c3, r3);
+    Row<NV4> x[kRows];
+    load_row(x[0], rows + (size_t)group_share<kFirst>(r) * stride, lane);
+    if constexpr (kRows > 1) if (kFirst + 1 < m) load_row(x[1], rows + (size_t)group_share<kFirst + 1>(r) * stride, lane);
+    if constexpr (kRows > 2) if (kFirst + 2 < m) load_row(x[2], rows + (size_t)group_share<kFirst + 2>(r) * stride, lane);
+    if constexpr (kRows > 3) if (kFirst + 3 < m) load_row(x[3], rows + (size_t)group_share<kFirst + 3>(r) * stride, lane);
+    axpy_row(acc, group_share<kFirst>(c), x[0]);
+    if constexpr (kRows > 1) if (kFirst + 1 < m) axpy_row(acc, group_share<kFirst + 1>(c), x[1]);
+    if constexpr (kRows > 2) if (kFirst + 2 < m) axpy_row(acc, group_share<kFirst + 2>(c), x[2]);
+    if constexpr (kRows > 3) if (kFirst + 3 < m) axpy_row(acc, group_share<kFirst + 3>(c), x[3]);
 }
 
-// acc += the contributions of accesses t0 .. min(t0 + 16, last) - 1 of a segment, in that order (one block):
-// lane l of the group fetches the l-th access's number, coefficient and source row number, so the dependent reads
-// that lead to a row's address are paid once per sixteen accesses rather than once per access; the rows are then
-// read four at a time.  Every lane of the group must call it with the same arguments; t0 < last.
-template <int NV4, class Src>
+template <int NV4, int kFirst, int kMost>
+__device__ __forceinline__ void sum_rows_from(Row<NV4> &acc, const float *rows, uint32_t r, float c, uint32_t m,
+                                              int stride, int lane)
+{
+    constexpr int kRows = kRowsInFlight<NV4>;
+    if constexpr (kFirst < kMost) {
+        if (kFirst == 0 || (uint32_t)kFirst < m) {
+            sum_rows<NV4, kFirst, kRows>(acc, rows, r, c, m, stride, lane);
+            sum_rows_from<NV4, kFirst + kRows, kMost>(acc, rows, r, c, m, stride, lane);
+        }
+    }
+}
+
+// acc += the contributions of accesses t0 .. min(t0 + kMost, last) - 1 of a segment, in that order:
+// lane l of the group fetches the l-th access's coefficient and source row number, so the dependent reads
+// that lead to a row's address are paid once for all of them rather than once per access; the rows are then
+// read a few at a time.  Every lane of the group must call it with the same arguments; t0 < last.
+template <int NV4, uint32_t kMost, class Src>
 __device__ __forceinline__ void sum_block(Row<NV4> &acc, const Src &src, const uint32_t *perm, uint32_t t0,
                                           uint32_t last, int stride, int lane)
 {
+    static_assert(kMost <= (uint32_t)kGroup, "one access per lane");
     const float *rows = src.rows();
-    const uint32_t t = t0 + (uint32_t)lane;
+    const uint32_t m = min(kMost, last - t0);
     uint32_t r = 0;
     float c = 0.0f;
-    if (t < last) {
-        const uint32_t i = perm[t];
-        c = src.coef(i);
-        r = src.row_number(i);
-    }
-    const uint32_t m = min((uint32_t)kGroup, last - t0);
-    sum_four<NV4, 0>(acc, rows, r, c, m, stride, lane);
-    if (m > 4) sum_four<NV4, 4>(acc, rows, r, c, m, stride, lane);
-    if (m > 8) sum_four<NV4, 8>(acc, rows, r, c, m, stride, lane);
-    if (m > 12) sum_four<NV4, 12>(acc, rows, r, c, m, stride, lane);
+    if ((uint32_t)lane < m) src.fetch(perm, t0 + (uint32_t)lane, c, r);
+    sum_rows_from<NV4, 0, (int)kMost>(acc, rows, r, c, m, stride, lane);
 }
 
-// lds_row <- x if `first`, else lds_row + x; each lane touches its own words only, so no barrier is involved.
+// row <- x if `first`, else row + x (LDS or global memory); each lane touches its own words only, so neither a
+// barrier nor a fence is involved.
 template <int NV4>
-__device__ __forceinline__ void lds_accumulate(float *lds_row, const Row<NV4> &x, bool first, int lane)
+__device__ __forceinline__ void accumulate_row(float *row, const Row<NV4> &x, bool first, int lane)
 {
     if (first) {
-        store_row(lds_row, x, lane);
+        store_row(row, x, lane);
     } else {
         Row<NV4> t;
-        load_row(t, lds_row, lane);
+        load_row(t, row, lane);
         axpy_row(t, 1.0f, x);
-        store_row(lds_row, t, lane);
+        store_row(row, t, lane);
     }
 }
 
 // acc = sum of the whole segment [first, last) by one group, in the fixed tree (blocks, super-blocks, total).
-// lds: the workgroup's two-rows-per-group area; only this group's two rows are used.
+// super_row: this group's row of LDS; total_row: this group's row of running totals in global memory.
 template <int NV4, class Src>
 __device__ __forceinline__ void sum_segment(Row<NV4> &acc, const Src &src, const uint32_t *perm, uint32_t first,
-                                            uint32_t last, int stride, int lane, int group, float *lds)
+                                            uint32_t last, int stride, int lane, float *super_row, float *total_row)
 {
     zero_row(acc);
-    if (last - first <= (uint32_t)kGroup) {
-        if (first < last) sum_block<NV4>(acc, src, perm, first, last, stride, lane);
+    if (last - first <= kLongSegment) {
+        if (first < last) sum_block<NV4, kLongSegment>(acc, src, perm, first, last, stride, lane);
         return;
     }
-    float *super_row = lds + (size_t)group * stride, *total_row = lds + (size_t)(kGroupsPerBlock + group) * stride;
     const bool several = last - first > kChunk;
     for (uint32_t s0 = first; s0 < last; s0 += kChunk) {
         const uint32_t s1 = min(s0 + kChunk, last);
-        for (uint32_t t0 = s0; t0 < s1; t0 += kGroup) {
+        for (uint32_t t0 = s0; t0 < s1; t0 += kTreeBlock) {
             zero_row(acc);
-            sum_block<NV4>(acc, src, perm, t0, s1, stride, lane);
-            lds_accumulate(super_row, acc, t0 == s0, lane);
+            sum_block<NV4, kTreeBlock>(acc, src, perm, t0, s1, stride, lane);
+            accumulate_row(super_row, acc, t0 == s0, lane);
         }
         if (several) {
             load_row(acc, super_row, lane);
-            lds_accumulate(total_row, acc, s0 == first, lane);
+            accumulate_row(total_row, acc, s0 == first, lane);
         }
     }
     load_row(acc, several ? total_row : super_row, lane);
@@ -339,33 +369,53 @@ struct ApplyShape {
     uint32_t nu, chunk_items, short_items;
 };
 
+// Segments per row group in an item of short segments (two, one after the other, measured slower: 40.9 instead of
+// 38.8 us per step of the large skip-gram configuration; the items get twice as long).
+constexpr int kSegmentsPerGroup = 1;
+constexpr uint32_t kSegmentsPerItem = kGroupsPerBlock * kSegmentsPerGroup;
+
 __device__ __forceinline__ ApplyShape apply_shape(const ApplyArgs &a)
 {
     ApplyShape sh;
     sh.nu = a.meta[kMetaNumUniq];
     sh.chunk_items = min(a.meta[kMetaNumChunks], a.max_chunks);
-    sh.short_items = (sh.nu + kGroupsPerBlock - 1) / kGroupsPerBlock;
+    sh.short_items = (sh.nu + kSegmentsPerItem - 1) / kSegmentsPerItem;
     return sh;
 }
 
-// One item of short segments: this group's segment, if it has one.
+// One item of short segments: this group's segments, if it has any (segment numbers item * kSegmentsPerItem +
+// group + k * kGroupsPerBlock: neighbouring groups update neighbouring rows).
 template <int NV4, class Src, class Opt>
 __device__ __forceinline__ void apply_short_item(const ApplyArgs &a, const Src &src, const Opt &opt,
-                                                 const ApplyShape &sh, uint32_t item, float *lds, int lane, int group)
+                                                 const ApplyShape &sh, uint32_t item, float *lds, uint32_t workgroup,
+                                                 int lane, int group)
 {
-    const uint32_t u = item * kGroupsPerBlock + group;
-    if (u >= sh.nu) return;
-    const uint32_t key = a.uniq[u];
-    const uint32_t first = a.seg[u], last = a.seg[u + 1];
-    if (takes_hot_path(last - first, key, a.hot_bits)) return;   // summed by chunk items
-    if (src.segment_done(a.perm, first, last, lane)) return;     // the gradient kernel has updated this row itself
-    const size_t off = (size_t)key * a.stride;
-    float *row = a.table + off, *state_row = Opt::kHasState ? a.state + off : nullptr;
-    Row<NV4> acc, t, g;
-    sum_segment<NV4>(acc, src, a.perm, first, last, a.stride, lane, group, lds);
-    opt.template load<NV4>(t, g, row, state_row, lane);   // after the sum: results are waited for in issue order, an early request of the cold row holds up the sum's first reads
-    if (opt.clips() && a.hot_bits != nullptr && in_hot_set(key, a.hot_bits)) opt.template clip<NV4>(acc, lane);
-    opt.template finish<NV4>(t, g, row, state_row, acc, lane);
+    uint32_t key[kSegmentsPerGroup], first[kSegmentsPerGroup], last[kSegmentsPerGroup];
+#pragma unroll
+    for (int k = 0; k < kSegmentsPerGroup; ++k) {
+        const uint32_t u = item * kSegmentsPerItem + (uint32_t)k * kGroupsPerBlock + group;
+        key[k] = 0;
+        first[k] = last[k] = 0;          // an empty range: nothing to do
+        if (u < sh.nu) {
+            key[k] = a.uniq[u];
+            first[k] = a.seg[u];
+            last[k] = a.seg[u + 1];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kSegmentsPerGroup; ++k) {
+        if (first[k] >= last[k]) continue;
+        if (takes_hot_path(last[k] - first[k], key[k], a.hot_bits)) continue;   // summed by chunk items
+        if (src.segment_done(a.perm, first[k], last[k], lane)) continue;        // the gradient kernel has updated this row itself
+        const size_t off = (size_t)key[k] * a.stride;
+        float *row = a.table + off, *state_row = Opt::kHasState ? a.state + off : nullptr;
+        Row<NV4> acc, t, g;
+        sum_segment<NV4>(acc, src, a.perm, first[k], last[k], a.stride, lane, lds + (size_t)group * a.stride,
+                         a.totals + ((size_t)workgroup * kGroupsPerBlock + group) * a.stride);
+        opt.template load<NV4>(t, g, row, state_row, lane);   // after the sum: results are waited for in issue order, an early request of the cold row holds up the sum's first reads
+        if (opt.clips() && a.hot_bits != nullptr && in_hot_set(key[k], a.hot_bits)) opt.template clip<NV4>(acc, lane);
+        opt.template finish<NV4>(t, g, row, state_row, acc, lane);
+    }
 }
 
 // The counter of a chunked segment: how many of its chunks have left their partial row.  The partial rows travel
@@ -395,10 +445,11 @@ __device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &
     const uint32_t first = a.seg[u], last = a.seg[u + 1];
     const uint32_t nch = (last - first + kChunk - 1) / kChunk;
     const uint32_t cf = first + (id - base) * kChunk, cl = min(cf + kChunk, last);
-    const uint32_t blocks = (cl - cf + kGroup - 1) / kGroup;     // non-empty blocks of this chunk
+    const uint32_t blocks = (cl - cf + kTreeBlock - 1) / kTreeBlock;     // non-empty blocks of this chunk
     Row<NV4> acc;
     zero_row(acc);
-    if ((uint32_t)group < blocks) sum_block<NV4>(acc, src, a.perm, cf + (uint32_t)group * kGroup, cl, a.stride, lane);
+    if ((uint32_t)group < blocks)
+        sum_block<NV4, kTreeBlock>(acc, src, a.perm, cf + (uint32_t)group * kTreeBlock, cl, a.stride, lane);
     __syncthreads();                  // LDS of the previous item has been read
     if (group > 0 && (uint32_t)group < blocks) store_row(part + (size_t)group * a.stride, acc, lane);
     __syncthreads();
@@ -421,37 +472,34 @@ __device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &
         update = *last_arrival != 0;
         if (update) {
             const float *prow = a.partial + (size_t)base * a.stride;
-            if (nch > 8 && !a.deterministic) {   // many chunks: every group adds an interleaved share, combined in group order
+            if (!a.deterministic) {   // every group adds an interleaved share of the partial rows, combined in group order
                 zero_row(acc);
                 for (uint32_t ch = group; ch < nch; ch += kGroupsPerBlock) {
                     Row<NV4> r;
                     load_row_device_scope(r, prow + (size_t)ch * a.stride, lane);
                     axpy_row(acc, 1.0f, r);
                 }
-                if (group > 0) store_row(part + (size_t)group * a.stride, acc, lane);   // LDS is free again
+                const uint32_t shares = min(nch, (uint32_t)kGroupsPerBlock);
+                if (group > 0 && (uint32_t)group < shares) store_row(part + (size_t)group * a.stride, acc, lane);   // LDS is free again
                 __syncthreads();
                 if (group == 0) {
-                    for (int g = 1; g < kGroupsPerBlock; ++g) {
+                    for (uint32_t g = 1; g < shares; ++g) {
                         Row<NV4> r;
                         load_row(r, part + (size_t)g * a.stride, lane);
                         axpy_row(acc, 1.0f, r);
                     }
                 }
-            } else if (group == 0) { // chunk order, four partial rows in flight; every chunk has arrived
+            } else if (group == 0) { // chunk order, by one group: the fixed tree's last level; every chunk has arrived
                 zero_row(acc);
                 uint32_t ch = 0;
-                for (; ch + 3 < nch; ch += 4) {
-                    Row<NV4> r0, r1, r2, r3;
+                for (; ch + 1 < nch; ch += 2) {
+                    Row<NV4> r0, r1;
                     load_row_device_scope(r0, prow + (size_t)ch * a.stride, lane);
                     load_row_device_scope(r1, prow + (size_t)(ch + 1) * a.stride, lane);
-                    load_row_device_scope(r2, prow + (size_t)(ch + 2) * a.stride, lane);
-                    load_row_device_scope(r3, prow + (size_t)(ch + 3) * a.stride, lane);
                     axpy_row(acc, 1.0f, r0);
                     axpy_row(acc, 1.0f, r1);
-                    axpy_row(acc, 1.0f, r2);
-                    axpy_row(acc, 1.0f, r3);
                 }
-                for (; ch < nch; ++ch) {
+                if (ch < nch) {
                     Row<NV4> r;
                     load_row_device_scope(r, prow + (size_t)ch * a.stride, lane);
                     axpy_row(acc, 1.0f, r);
@@ -472,6 +520,11 @@ __device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &
 
 // Updates one table.  A fixed-size grid walks over the items, chunks first (they are the long poles); every
 // workgroup leaves the loop after at most ceil(items / gridDim) turns.
+// Updates one table.  A fixed-size grid walks over the items, chunks first (they are the long poles); every
+// workgroup leaves the loop after at most ceil(items / gridDim) turns.  (Handing the items beyond the first round
+// out through a counter, so that whichever workgroup finishes first carries on, was measured: the atomics of all
+// workgroups on the one counter and the barriers around them cost far more than the idle slots they fill: 44 instead
+// of 39 us per step of the large skip-gram configuration, 126 instead of 64 us for the factorisation.)
 template <int NV4, class Src, class Opt>
 __global__ void __launch_bounds__(kBlock) k_apply(ApplyArgs a, Src src, Opt opt)
 {
@@ -482,15 +535,21 @@ __global__ void __launch_bounds__(kBlock) k_apply(ApplyArgs a, Src src, Opt opt)
     const uint32_t items = sh.chunk_items + sh.short_items;
     for (uint32_t item = blockIdx.x; item < items; item += gridDim.x) {
         if (item < sh.chunk_items) apply_chunk_item<NV4>(a, src, opt, item, part, &last_arrival, lane, group);
-        else apply_short_item<NV4>(a, src, opt, sh, item - sh.chunk_items, part, lane, group);
+        else apply_short_item<NV4>(a, src, opt, sh, item - sh.chunk_items, part, blockIdx.x, lane, group);
     }
 }
 
 // Updates the two tables of a step in one launch (their updates are independent of each other: both read
 // staged rows only).  Item order: chunks of table 0, chunks of table 1, short segments of 0, of 1.  The first
 // sw.blocks workgroups do preparatory work of later steps instead.
+// Wavefronts per SIMD that the update of both tables is compiled for.  Rows of 320 floats sit a register or two
+// above the limit for four; with four, the work items of a step of the large skip-gram configuration are (nearly)
+// all resident at once.  Other widths: whatever the code needs.
+template <int NV4>
+constexpr int kApply2WavesPerSimd = NV4 == 5 ? 4 : 1;
+
 template <int NV4, class Src0, class Opt0, class Src1, class Opt1>
-__global__ void __launch_bounds__(kBlock) k_apply2(ApplyArgs a0, Src0 src0, Opt0 opt0, ApplyArgs a1, Src1 src1,
+__global__ void __launch_bounds__(kBlock, kApply2WavesPerSimd<NV4>) k_apply2(ApplyArgs a0, Src0 src0, Opt0 opt0, ApplyArgs a1, Src1 src1,
                                                    Opt1 opt1, SideWork sw)
 {
     extern __shared__ float part[];   // apply_lds_bytes(stride)
@@ -504,8 +563,8 @@ __global__ void __launch_bounds__(kBlock) k_apply2(ApplyArgs a0, Src0 src0, Opt0
     for (uint32_t item = first_item; item < e3; item += item_step) {
         if (item < e0) apply_chunk_item<NV4>(a0, src0, opt0, item, part, &last_arrival, lane, group);
         else if (item < e1) apply_chunk_item<NV4>(a1, src1, opt1, item - e0, part, &last_arrival, lane, group);
-        else if (item < e2) apply_short_item<NV4>(a0, src0, opt0, s0, item - e1, part, lane, group);
-        else apply_short_item<NV4>(a1, src1, opt1, s1, item - e2, part, lane, group);
+        else if (item < e2) apply_short_item<NV4>(a0, src0, opt0, s0, item - e1, part, first_item, lane, group);
+        else apply_short_item<NV4>(a1, src1, opt1, s1, item - e2, part, first_item, lane, group);
     }
 }
 
@@ -514,11 +573,23 @@ __global__ void __launch_bounds__(kBlock) k_apply2(ApplyArgs a0, Src0 src0, Opt0
 template <int NV4>
 constexpr uint32_t kApplyGrid = NV4 <= 2 ? 8192 : 2048;
 
-static inline ApplyArgs make_apply_args(const Plan &pl, float *partial, float *table, float *state, int stride)
+static inline uint32_t apply_grid_of_stride(int stride) { return stride / 64 <= 2 ? kApplyGrid<2> : kApplyGrid<8>; }
+
+// Where an update launch keeps its workgroups' running totals and how many workgroups it may use at most.
+struct ApplyScratch {
+    float *totals;       // [grid_cap][kGroupsPerBlock][stride]
+    uint32_t grid_cap;
+};
+
+static inline size_t apply_totals_floats(uint32_t grid_cap, int stride) { return (size_t)grid_cap * kGroupsPerBlock * stride; }
+
+static inline ApplyArgs make_apply_args(const Plan &pl, float *partial, float *table, float *state, int stride,
+                                        float *totals)
 {
     const PlanArgs &p = pl.a;
     return ApplyArgs{table, state, p.hot_bits, p.uniq, p.seg, p.deterministic ? p.perm_sorted : p.perm, p.meta,
-                     p.chunk_seg, p.chunk_base, p.chunk_done, partial, stride, p.n, p.max_chunks, p.deterministic};
+                     p.chunk_seg, p.chunk_base, p.chunk_done, partial, stride, p.n, p.max_chunks, p.deterministic,
+                     totals};
 }
 
 static inline uint32_t max_apply_items(const Plan &pl)
@@ -537,16 +608,16 @@ static void allow_lds(Kernel kernel, size_t lds, size_t *allowed)
 }
 
 template <int NV4, class Src, class Opt>
-static void launch_apply_nv(hipStream_t s, const Plan &pl, float *partial, float *table, float *state, int stride,
-                            const Src &src, const Opt &opt)
+static void launch_apply_nv(hipStream_t s, const Plan &pl, float *partial, const ApplyScratch &scratch, float *table,
+                            float *state, int stride, const Src &src, const Opt &opt)
 {
     if (pl.a.n == 0) return;
-    const ApplyArgs a = make_apply_args(pl, partial, table, state, stride);
+    const ApplyArgs a = make_apply_args(pl, partial, table, state, stride, scratch.totals);
     const size_t lds = apply_lds_bytes(stride);
     static size_t allowed = 0;
     allow_lds(k_apply<NV4, Src, Opt>, lds, &allowed);
-    hipLaunchKernelGGL((k_apply<NV4, Src, Opt>), dim3(std::min(max_apply_items(pl), kApplyGrid<NV4>)), dim3(kBlock), lds, s,
-                       a, src, opt);
+    const uint32_t grid = std::min({max_apply_items(pl), kApplyGrid<NV4>, scratch.grid_cap});
+    hipLaunchKernelGGL((k_apply<NV4, Src, Opt>), dim3(grid), dim3(kBlock), lds, s, a, src, opt);
 }
 
 #define NUPS_FOR_EACH_ROW_WIDTH(stride, CALL)                                                     \
@@ -566,10 +637,10 @@ static void launch_apply_nv(hipStream_t s, const Plan &pl, float *partial, float
 
 // One table: dispatch on the row length (stride / 64 float4 per lane).
 template <class Src, class Opt>
-static nups_status launch_apply(hipStream_t s, const Plan &pl, float *partial, float *table, float *state,
-                                int stride, const Src &src, const Opt &opt)
+static nups_status launch_apply(hipStream_t s, const Plan &pl, float *partial, const ApplyScratch &scratch,
+                                float *table, float *state, int stride, const Src &src, const Opt &opt)
 {
-#define NUPS_CALL(N) launch_apply_nv<N>(s, pl, partial, table, state, stride, src, opt)
+#define NUPS_CALL(N) launch_apply_nv<N>(s, pl, partial, scratch, table, state, stride, src, opt)
     NUPS_FOR_EACH_ROW_WIDTH(stride, NUPS_CALL)
 #undef NUPS_CALL
     NUPS_HIP(hipGetLastError());
@@ -586,25 +657,28 @@ struct TableUpdate {
 };
 
 template <int NV4, class U0, class U1>
-static void launch_apply2_nv(hipStream_t s, int stride, const U0 &u0, const U1 &u1, const SideWork &sw, size_t side_lds)
+static void launch_apply2_nv(hipStream_t s, int stride, const U0 &u0, const U1 &u1, const ApplyScratch &scratch,
+                             const SideWork &sw, size_t side_lds)
 {
-    const ApplyArgs a0 = make_apply_args(*u0.plan, u0.partial, u0.table, u0.state, stride);
-    const ApplyArgs a1 = make_apply_args(*u1.plan, u1.partial, u1.table, u1.state, stride);
+    const ApplyArgs a0 = make_apply_args(*u0.plan, u0.partial, u0.table, u0.state, stride, scratch.totals);
+    const ApplyArgs a1 = make_apply_args(*u1.plan, u1.partial, u1.table, u1.state, stride, scratch.totals);
     const uint32_t items = max_apply_items(*u0.plan) + max_apply_items(*u1.plan);
     const size_t lds = std::max(apply_lds_bytes(stride), side_lds);
     static size_t allowed = 0;
-    allow_lds(k_apply2<NV4, decltype(u0.src), decltype(u0.opt), decltype(u1.src), decltype(u1.opt)>, lds, &allowed);
-    hipLaunchKernelGGL((k_apply2<NV4, decltype(u0.src), decltype(u0.opt), decltype(u1.src), decltype(u1.opt)>),
-                       dim3(sw.blocks + std::max(1u, std::min(items, kApplyGrid<NV4>))), dim3(kBlock), lds, s, a0, u0.src,
+    const auto kernel = k_apply2<NV4, decltype(u0.src), decltype(u0.opt), decltype(u1.src), decltype(u1.opt)>;
+    allow_lds(kernel, lds, &allowed);
+    const uint32_t grid = std::max(1u, std::min({items, kApplyGrid<NV4>, scratch.grid_cap}));
+    hipLaunchKernelGGL(kernel, dim3(sw.blocks + grid), dim3(kBlock), lds, s,
+                       a0, u0.src,
                        u0.opt, a1, u1.src, u1.opt, sw);
 }
 
 // Both tables of a step in one launch (both strides are equal), plus the side work `sw`.
 template <class U0, class U1>
-static nups_status launch_apply2(hipStream_t s, int stride, const U0 &u0, const U1 &u1, const SideWork &sw,
-                                 size_t side_lds)
+static nups_status launch_apply2(hipStream_t s, int stride, const U0 &u0, const U1 &u1, const ApplyScratch &scratch,
+                                 const SideWork &sw, size_t side_lds)
 {
-#define NUPS_CALL(N) launch_apply2_nv<N>(s, stride, u0, u1, sw, side_lds)
+#define NUPS_CALL(N) launch_apply2_nv<N>(s, stride, u0, u1, scratch, sw, side_lds)
     NUPS_FOR_EACH_ROW_WIDTH(stride, NUPS_CALL)
 #undef NUPS_CALL
     NUPS_HIP(hipGetLastError());

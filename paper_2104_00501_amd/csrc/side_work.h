@@ -423,12 +423,14 @@ __device__ __forceinline__ void scatter_block(const PlanArgs &a, uint32_t vb)
     if (i >= a.n) return;
     const uint32_t key = source_key(a.src, i);
     if (key < a.num_keys) a.bytemap[key] = 0;   // also for an access that is dropped below
+    a.pos[i] = kBadIndex;
     const uint32_t u = a.slot[i];
     if (u == kBadIndex) return;
     const uint32_t r = a.rank[i];
     const uint32_t first = a.seg[u], next = a.seg[u + 1];
     if (first + r >= a.n) return;   // cannot happen with unchanged key arrays
     a.perm[first + r] = i;
+    a.pos[i] = first + r;
     if (r == 0) {
         a.cnt_work[counter_index(u)] = 0;
         if (next - first == 1) a.rank[i] = kSingleAccess;   // the key's only access: a gradient kernel may update the row itself
@@ -447,7 +449,12 @@ __device__ __forceinline__ void sort_block(const PlanArgs &a, uint32_t vb)
     const uint32_t first = a.seg[u], last = min(a.seg[u + 1], a.n);
     uint32_t below = 0;
     for (uint32_t t = first; t < last; ++t) below += a.perm[t] < i ? 1u : 0u;
-    if (first + below < a.n) a.perm_sorted[first + below] = i;   // in range by construction with unchanged key arrays
+    if (first + below < a.n) {   // in range by construction with unchanged key arrays
+        a.perm_sorted[first + below] = i;
+        a.pos[i] = first + below;
+    } else {
+        a.pos[i] = kBadIndex;
+    }
 }
 
 // ---- dispatch ------------------------------------------------------------------------------------------------------

@@ -166,10 +166,12 @@ nups_status launch_pull(nups_ctx *ctx, const Table &t, const uint32_t *keys, int
 }
 
 // push: table[k] += sum of the update rows sent for k (plan already built over the keys).
-nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, float *partial, const float *updates)
+nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, float *partial, float *totals, uint32_t grid_cap,
+                              const float *updates)
 {
     PhaseScope scope(ctx, NUPS_PHASE_PUSH, ctx->stream);
-    return launch_apply(ctx->stream, pl, partial, t.data, nullptr, t.stride, SrcStaged{updates}, OptAdd{});
+    return launch_apply(ctx->stream, pl, partial, ApplyScratch{totals, grid_cap}, t.data, nullptr, t.stride,
+                        SrcStaged{updates}, OptAdd{});
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -183,11 +185,12 @@ nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, float *pa
 // Otherwise the run's sum is staged at the row of its first pair and the update kernel adds the runs of the word.
 // So a staged gradient row is written per run that shares its word with other runs, not per pair.
 // ------------------------------------------------------------------------------------------------
-template <int NV4>
+template <int NV4, bool kWithLoss>
 __global__ void __launch_bounds__(kBlock) k_sgns_grad(float *in_table, const float *out_table,
                                                       uint32_t num_in, uint32_t num_out, int stride,
                                                       const uint32_t *center, const uint32_t *context,
-                                                      const uint32_t *negs, uint32_t B, int K, float lr, float *coefs,
+                                                      const uint32_t *negs, uint32_t B, int K, float lr,
+                                                      const uint32_t *out_pos, float *coef_at, uint32_t *row_at,
                                                       float *stage, uint32_t zeros_at, int update_whole_runs,
                                                       const uint32_t *center_slot, const uint32_t *center_rank,
                                                       const uint32_t *center_seg, float *center_rows, double *loss,
@@ -220,7 +223,12 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(float *in_table, const flo
     zero_row(acc);
     float loss_acc = 0.f;
     constexpr int JU = 4;     // rows in flight per group
+    const uint32_t n_out = B * (uint32_t)(K + 1);
     for (int j0 = 0; j0 <= K; j0 += JU) {
+        // lane jj of the group looks after scored row j0 + jj: where its access stands in the output table's order
+        uint32_t my_pos = kBadIndex;
+        if (active && lane < JU && j0 + lane <= K)
+            my_pos = out_pos[(j0 + lane == 0) ? e : B + e * (uint32_t)K + (uint32_t)(j0 + lane - 1)];
         Row<NV4> u[JU];
 #pragma unroll
         for (int jj = 0; jj < JU; ++jj) {
@@ -235,17 +243,29 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(float *in_table, const flo
             if (j <= K) {
                 const float z = group_sum(partial_dot(v, u[jj]));
                 const float g = sigmoidf(z) - (j == 0 ? 1.0f : 0.0f);
-                loss_acc += softplusf(j == 0 ? -z : z);
+                if (kWithLoss) loss_acc += softplusf(j == 0 ? -z : z);   // only when the caller asked for the loss
                 if (lane == jj) g_mine = g;
                 axpy_row(acc, g, u[jj]);
             }
         }
-        if (active && lane < JU && j0 + lane <= K) coefs[(size_t)e * (K + 1) + j0 + lane] = g_mine;
+        if (my_pos < n_out) {   // an access that the structure dropped (key outside the table) has no position
+            coef_at[my_pos] = g_mine;
+            row_at[my_pos] = slot == kBadIndex ? 0u : slot;   // bad center key: flagged, row 0 used
+        }
     }
     // runs of equal center words inside the workgroup (pairs beyond the batch belong to no run)
     if (lane == 0) run_key[group] = active ? ckey : kBadIndex;
     store_row(run_rows + (size_t)group * stride, acc, lane);
+    if (kWithLoss) {   // the wavefronts' loss sums cross the same barrier as the runs' rows
+        const float wave_loss = wave_sum((active && lane == 0) ? loss_acc : 0.f);
+        if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = wave_loss;
+    }
     __syncthreads();
+    if (kWithLoss && threadIdx.x == 0) {
+        double s = 0.0;
+        for (int w = 0; w < kBlock / 64; ++w) s += (double)lds[w];
+        atomicAdd(loss + (blockIdx.x % kLossSlots) * kLossStride, s);
+    }
     if (active && slot != kBadIndex && (group == 0 || run_key[group - 1] != ckey)) {
         uint32_t len = 1;
         while (group + len < (uint32_t)kGroupsPerBlock && run_key[group + len] == ckey) {
@@ -262,23 +282,28 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(float *in_table, const flo
             store_row(stage + (size_t)e * stride, acc, lane);
         }
     }
-    block_add_loss((active && lane == 0) ? loss_acc : 0.f, loss, lds);
 }
 
 template <int NV4>
-static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b, const Plan &in_plan, float *center_rows,
-                             uint32_t zero_row, bool update_whole_runs, const SideWork &sw, size_t side_lds)
+static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b, const Plan &in_plan, const Plan &out_plan,
+                             float *center_rows, uint32_t *row_at, uint32_t zero_row, bool update_whole_runs,
+                             const SideWork &sw, size_t side_lds)
 {
     const Table &tin = ctx->tab[0], &tout = ctx->tab[1];
     const uint32_t blocks = xcd_grid((uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock));
     const size_t lds = std::max(sizeof(float) * kGroupsPerBlock * (size_t)tin.stride, side_lds);
-    static size_t allowed = 0;
-    allow_lds(k_sgns_grad<NV4>, lds, &allowed);
-    hipLaunchKernelGGL(k_sgns_grad<NV4>, dim3(sw.blocks + blocks), dim3(kBlock), lds, ctx->stream, tin.data,
-                       (const float *)tout.data, (uint32_t)tin.num_keys, (uint32_t)tout.num_keys, tin.stride, b.k0, b.k1,
-                       b.negs, (uint32_t)b.B, (int)b.n_neg, b.lr, ctx->coef, ctx->stage, zero_row, update_whole_runs ? 1 : 0,
-                       (const uint32_t *)in_plan.a.slot, (const uint32_t *)in_plan.a.rank,
-                       (const uint32_t *)in_plan.a.seg, center_rows, ctx->loss_cur, sw);
+    static size_t allowed = 0, allowed_with_loss = 0;
+    const auto launch = [&](auto kernel, size_t *granted) {
+        allow_lds(kernel, lds, granted);
+        hipLaunchKernelGGL(kernel, dim3(sw.blocks + blocks), dim3(kBlock), lds, ctx->stream, tin.data,
+                           (const float *)tout.data, (uint32_t)tin.num_keys, (uint32_t)tout.num_keys, tin.stride, b.k0,
+                           b.k1, b.negs, (uint32_t)b.B, (int)b.n_neg, b.lr, (const uint32_t *)out_plan.a.pos, ctx->coef,
+                           row_at, ctx->stage, zero_row, update_whole_runs ? 1 : 0, (const uint32_t *)in_plan.a.slot,
+                           (const uint32_t *)in_plan.a.rank, (const uint32_t *)in_plan.a.seg, center_rows, ctx->loss_cur,
+                           sw);
+    };
+    if (ctx->want_loss) launch(k_sgns_grad<NV4, true>, &allowed_with_loss);
+    else launch(k_sgns_grad<NV4, false>, &allowed);
 }
 
 // Plan side of a step: which keys each table is accessed with (plan 0: table 0, plan 1: table 1).  Sizes the
@@ -300,7 +325,8 @@ static nups_status plan_two_tables(nups_ctx *ctx, nups_prepared &p, const KeySou
     p.plan[1].a.zero_loss = nullptr;
     // partial rows of chunked segments: one region per table, the two updates run in the same launch
     const size_t need = (max_chunks(p.plan[0].cap_n) + max_chunks(p.plan[1].cap_n)) * (size_t)ctx->tab[0].stride;
-    return ensure_partial(ctx, need);
+    if ((st = ensure_partial(ctx, need)) != NUPS_OK) return st;
+    return ensure_totals(ctx, ctx->tab[0].stride);
 }
 
 nups_status plan_step_sgns(nups_ctx *ctx, nups_prepared &p)
@@ -310,6 +336,8 @@ nups_status plan_step_sgns(nups_ctx *ctx, nups_prepared &p)
     return plan_two_tables(ctx, p, KeySource{{b.k0, nullptr, nullptr}, {B, 0, 0}}, B,
                            KeySource{{b.k1, b.negs, nullptr}, {B, B * K, 0}}, B * (K + 1));
 }
+
+static ApplyScratch update_scratch(nups_ctx *ctx, int stride) { return ApplyScratch{ctx->totals, apply_grid_of_stride(stride)}; }
 
 // Where table 1's partial rows start inside the context's partial buffer.
 static float *partial_of(nups_ctx *ctx, const nups_prepared &p, int k)
@@ -323,7 +351,10 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
     Table &tin = ctx->tab[0], &tout = ctx->tab[1];
     const uint32_t B = (uint32_t)b.B, K = (uint32_t)b.n_neg;
     nups_status st;
-    if ((st = ensure_f32(&ctx->coef, &ctx->coef_cap, (size_t)B * (K + 1), ctx->stream)) != NUPS_OK) return st;
+    // per access of the output table, in the order of its structure: the coefficient, then (as integers) the row
+    // of the center word among the staged center rows
+    if ((st = ensure_f32(&ctx->coef, &ctx->coef_cap, (size_t)2 * B * (K + 1), ctx->stream)) != NUPS_OK) return st;
+    uint32_t *row_at = reinterpret_cast<uint32_t *>(ctx->coef + (size_t)B * (K + 1));
     // staged rows: [0, B) input-side gradient sums of runs of pairs (at the runs' first pairs), [B, 2B) input
     // vectors of the distinct center words, row 2B all zero
     if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, ((size_t)2 * B + 1) * tin.stride, ctx->stream)) != NUPS_OK) return st;
@@ -337,7 +368,7 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
     {
         const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
-#define CALL(N) launch_sgns_grad<N>(ctx, b, p.plan[0], center_rows, zero_row, update_whole_runs, sw, side_lds)
+#define CALL(N) launch_sgns_grad<N>(ctx, b, p.plan[0], p.plan[1], center_rows, row_at, zero_row, update_whole_runs, sw, side_lds)
         NUPS_FOR_EACH_ROW_WIDTH(tin.stride, CALL)
 #undef CALL
         NUPS_HIP(hipGetLastError());
@@ -350,9 +381,9 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
                                                  SrcSgnsIn{ctx->stage, b.k0, zero_row, update_whole_runs},
                                                  sgd_rule(ctx, 0, b.lr)};
         const TableUpdate<SrcSgnsOut, OptSgd> uout{&p.plan[1], partial_of(ctx, p, 1), tout.data, nullptr,
-                                                   SrcSgnsOut{center_rows, p.plan[0].a.slot, ctx->coef, B, K},
-                                                   sgd_rule(ctx, 1, b.lr)};
-        if ((st = launch_apply2(ctx->stream, tin.stride, uin, uout, sw, side_lds)) != NUPS_OK) return st;
+                                                   SrcSgnsOut{center_rows, ctx->coef, row_at}, sgd_rule(ctx, 1, b.lr)};
+        // the output table first: its items are the many, the input table's few remaining ones fill in behind
+        if ((st = launch_apply2(ctx->stream, tin.stride, uout, uin, update_scratch(ctx, tin.stride), sw, side_lds)) != NUPS_OK) return st;
     }
     return NUPS_OK;
 }
@@ -467,7 +498,7 @@ nups_status run_step_mf(nups_ctx *ctx, nups_prepared &p)
         const TableUpdate<SrcStaged, OptSgd> uh{&p.plan[1], partial_of(ctx, p, 1), th.data, nullptr,
                                                 SrcStaged{ctx->stage + (size_t)B * tw.stride, singles_in_place},
                                                 sgd_rule(ctx, 1, b.lr)};
-        if ((st = launch_apply2(ctx->stream, tw.stride, uw, uh, sw, side_lds)) != NUPS_OK) return st;
+        if ((st = launch_apply2(ctx->stream, tw.stride, uw, uh, update_scratch(ctx, tw.stride), sw, side_lds)) != NUPS_OK) return st;
     }
     return NUPS_OK;
 }
@@ -737,7 +768,7 @@ nups_status run_step_kge(nups_ctx *ctx, nups_prepared &p)
         const TableUpdate<SrcStaged, OptAdagrad> ur{&p.plan[1], partial_of(ctx, p, 1), tr.data, tr.state,
                                                     SrcStaged{ctx->stage + (size_t)4 * B * te.stride},
                                                     OptAdagrad{b.lr, b.eps}};
-        if ((st = launch_apply2(ctx->stream, te.stride, ue, ur, sw, side_lds)) != NUPS_OK) return st;
+        if ((st = launch_apply2(ctx->stream, te.stride, ue, ur, update_scratch(ctx, te.stride), sw, side_lds)) != NUPS_OK) return st;
     }
     return NUPS_OK;
 }
@@ -756,12 +787,13 @@ constexpr size_t kStaticKeys = NUPS_STATIC_MAX_KEYS, kStaticPush = NUPS_STATIC_M
 constexpr size_t kStaticWordsOfMap = (kStaticKeys + 31) / 32;
 constexpr size_t kStaticChunks = kStaticPush / kChunk + kStaticPush / (kLongSegment + 1) + 2;   // max_chunks(kStaticPush)
 constexpr size_t kStaticTiles = (kStaticWordsOfMap > kStaticPush ? kStaticWordsOfMap : kStaticPush) / kScanTile + 1;
+constexpr uint32_t kStaticGrid = 128;   // workgroups of the update launch (its running totals are part of the array)
 constexpr size_t align64(size_t words) { return (words + 63) / 64 * 64; }   // regions start on 256-byte boundaries
 
 // Offsets (in 32-bit words) of the regions.  The first kStaticZeroWords words are what a build expects to be zero.
 struct StaticLayout {
     size_t bytemap, wordmap, cnt_work, chunk_done, meta, zero_end, bitmap, word_rank, tile_sum, tile_prefix, uniq, count,
-        seg, perm, perm_sorted, slot, rank, chunk_seg, chunk_base, partial, end;
+        seg, perm, perm_sorted, slot, pos, rank, chunk_seg, chunk_base, partial, totals, end;
 };
 
 constexpr StaticLayout static_layout()
@@ -785,17 +817,19 @@ constexpr StaticLayout static_layout()
     l.perm = take(kStaticPush);
     l.perm_sorted = take(kStaticPush);
     l.slot = take(kStaticPush);
+    l.pos = take(kStaticPush);
     l.rank = take(kStaticPush);
     l.chunk_seg = take(kStaticChunks);
     l.chunk_base = take(kStaticChunks);
     l.partial = take(kStaticChunks * (size_t)kMaxStride);
+    l.totals = take((size_t)kStaticGrid * kGroupsPerBlock * kMaxStride);
     l.end = at;
     return l;
 }
 
 constexpr StaticLayout kStaticLayout = static_layout();
 
-static __device__ __align__(256) uint32_t scratch[kStaticLayout.end];   // about 6 MB per device, for the life of the process
+static __device__ __align__(256) uint32_t scratch[kStaticLayout.end];   // about 14 MB per device, for the life of the process
 
 constexpr int kMaxDevices = 64;
 static uint32_t *g_scratch_of_device[kMaxDevices];   // device address of each device's copy; null: not asked for yet
@@ -861,6 +895,7 @@ extern "C" nups_status nups_push_static(nups_ctx *ctx, int table, const uint32_t
     a.perm = base + L.perm;
     a.perm_sorted = base + L.perm_sorted;
     a.slot = base + L.slot;
+    a.pos = base + L.pos;
     a.rank = base + L.rank;
     a.chunk_seg = base + L.chunk_seg;
     a.chunk_base = base + L.chunk_base;
@@ -880,7 +915,8 @@ extern "C" nups_status nups_push_static(nups_ctx *ctx, int table, const uint32_t
     NUPS_HIP(hipGetLastError());
     build_phases(*p, SampleArgs{}, -1);
     nups_status st = flush_side_work(ctx, p);
-    if (st == NUPS_OK && n > 0) st = launch_push_apply(ctx, t, pl, (float *)(base + L.partial), updates_dev);
+    if (st == NUPS_OK && n > 0)
+        st = launch_push_apply(ctx, t, pl, (float *)(base + L.partial), (float *)(base + L.totals), kStaticGrid, updates_dev);
     t.last_plan = &pl;                // nups_debug_structure describes this call until the next step or push
     return st;
 }

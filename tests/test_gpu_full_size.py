@@ -2,6 +2,8 @@
 ahead, the preparatory work riding in earlier launches), over 100 steps each: every row that the steps touch is
 compared with the oracle's to the 100-step bar (1e-3, element by element with a floor per row, tests/parity.py),
 and every other row of the tables must be bit-identical to what it was."""
+import os
+
 import numpy as np
 import pytest
 
@@ -11,6 +13,7 @@ from paper_2104_00501_amd import workloads as wl
 from tests.parity import TOL_100_STEPS, dev, dev_u32, param_err, update_err
 
 pytestmark = pytest.mark.gpu
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _touched_rows_match(t_dev, init_dev, ref_host, touched, cols, tol, what):
@@ -29,6 +32,19 @@ def _touched_rows_match(t_dev, init_dev, ref_host, touched, cols, tol, what):
     assert ue <= tol, "%s: error of the total update %.3g > %.1g" % (what, ue, tol)
     pad = np.setdiff1d(np.arange(got.shape[1]), cols)
     assert np.all(got[:, pad] == 0), what + ": padding lanes changed"
+
+
+def _progress(what, t, steps):
+    """The oracle's 100 full-size steps take minutes on one core: a line now and then shows that the test is alive."""
+    if t % 10 == 9 or t == steps - 1:
+        line = "%s: oracle step %d of %d" % (what, t + 1, steps)
+        print(line, flush=True)
+        try:        # also where output capture would hold the line back: a file that a watcher of the run can see grow
+            os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+            with open(os.path.join(ROOT, "gpurun_out", "full_size_progress.txt"), "a") as f:
+                f.write(line + "\n")
+        except OSError:
+            pass
 
 
 def _run(ctx, batches, depth):
@@ -76,6 +92,7 @@ def test_word_vectors_1m_keys_d300_bounded_reuse():
         negs_all.append(negs)
         rloss = orc.step_sgns_clipped(In, Out, d, centers[sl], contexts[sl], negs, K, lrs[t], hot, hot, 2.0,
                                       stats_in, stats_out)
+        _progress("word vectors", t, steps)
     assert np.isfinite(In).all() and np.isfinite(Out).all() and np.abs(In).max() < 100
     assert abs(loss - rloss) <= TOL_100_STEPS * abs(rloss)
     cols = list(range(d))
@@ -108,6 +125,7 @@ def test_factorisation_10m_by_1m_rank_100():
     for t in range(steps):
         sl = slice(t * B, (t + 1) * B)
         rloss = orc.step_mf(W, H, d, rows[sl], cols[sl], vals[sl], 0.005, 0.01)[0]
+        _progress("factorisation", t, steps)
     assert abs(loss - rloss) <= TOL_100_STEPS * abs(rloss)
     _touched_rows_match(tw, init_w, W, rows, list(range(d)), TOL_100_STEPS, "row factors")
     _touched_rows_match(th, init_h, H, cols, list(range(d)), TOL_100_STEPS, "column factors")
@@ -152,6 +170,7 @@ def test_complex_4p6m_entities_d500_adagrad():
         negs = orc.sample_conform(None, n_ent, seed, 0, t, B * (nh + nt))
         negs_all.append(negs)
         rloss = orc.step_kge(E, GE, R, GR, d, s[sl], r[sl], o[sl], negs, nh, nt, 0.1, 1e-10)[0]
+        _progress("ComplEx", t, steps)
     assert abs(loss - rloss) <= TOL_100_STEPS * abs(rloss)
     cols = list(range(half)) + list(range(stride // 2, stride // 2 + half))
     touched = np.concatenate([s, o] + negs_all)
