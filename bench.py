@@ -52,6 +52,7 @@ class Sgns:
         self.scheme = scheme or ("BOUNDED" if U > 1 else "CONFORM")
         self.hot, self.decay = hot, decay       # hot: None = decided per step, else the top-`hot` keys are declared
         self.clip = 0.0                         # factor of the norm clipping of hot-key updates, 0 = off
+        self.replicas, self.sync_every = 0, 1   # stale replicas of the hot keys (paper Section 3.2), 0 = off
         self.unit = "pairs"
 
     def setup(self, nb, wl, total_steps):
@@ -83,6 +84,8 @@ class Sgns:
                 nb.nups_set_hot_keys(self.ctx, table, np.arange(self.hot, dtype=np.uint32))
         if self.clip > 0.0:
             nb.nups_set_update_clipping(self.ctx, self.clip)
+        if self.replicas > 0:
+            nb.nups_set_replicas(self.ctx, self.replicas)
         epoch_steps = max(1, wl.num_window_pairs(self.stream_tokens, window) // B)
         self.lrs = [float(wl.linear_lr(self.lr0, t, epoch_steps)) if self.decay else self.lr0
                     for t in range(total_steps)]
@@ -132,6 +135,16 @@ class Sgns:
             hot = np.arange(self.hot, dtype=np.uint32)
             orc.step_sgns_clipped(self.In, self.Out, self.d, c, o, ng, K, self.lrs[t], hot, hot, self.clip,
                                   *self.clip_stats)
+        elif self.replicas > 0:
+            from oracle import replicas as rep
+            hot = np.arange(self.hot, dtype=np.uint32)
+            if not hasattr(self, "ext"):
+                self.ext = [rep.extend_table(self.In, hot, self.replicas), rep.extend_table(self.Out, hot, self.replicas)]
+            rep.step_sgns_replicated(self.ext[0], self.ext[1], self.d, c, o, ng, K, self.lrs[t], self.V, self.V, hot, hot,
+                                     self.replicas)
+            if (t + 1) % self.sync_every == 0:
+                for e in self.ext:
+                    rep.sync_replicas(e, self.V, hot, self.replicas, self.d)
         else:
             orc.step_sgns(self.In, self.Out, self.d, c, o, ng, K, self.lrs[t])
 
@@ -141,7 +154,8 @@ class Sgns:
                 "scheme": {"BOUNDED": "BOUNDED U=%d G=%d" % (self.U, self.G), "LONGTERM": "LONG-TERM P=1e6 R=16"}.get(
                     self.scheme, self.scheme),
                 "batch": self.B, "window": self.window, "zipf_s": self.s, "lr0": self.lr0, "pairs": "stream order",
-                "update_clipping": self.clip or "off"}
+                "update_clipping": self.clip or "off",
+                "replicas": "%d, synchronised every %d steps" % (self.replicas, self.sync_every) if self.replicas else "off"}
 
 
 class Mf:
@@ -395,6 +409,10 @@ def main() -> int:
     ap.add_argument("--clip", type=float, default=0.0,
                     help="SGD workloads: clip hot-key updates at this factor times their mean norm (0: off); "
                          "declares the 1,000 most frequent keys of each table as hot if the workload declares none")
+    ap.add_argument("--replicas", type=int, default=0,
+                    help="skip-gram workloads: this many stale replicas of each hot key (paper Section 3.2), one per "
+                         "contiguous part of the batch; declares the 1,000 most frequent keys hot if none are declared")
+    ap.add_argument("--sync-every", type=int, default=8, help="steps between two synchronisations of the replicas")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -420,6 +438,13 @@ def main() -> int:
             w.hot = 1000
     n_windows = 5                                    # further timed windows after the headline region
     window = max(20, min(args.steps, 100))
+    if args.replicas > 0:
+        if not isinstance(w, Sgns) or args.clip > 0.0:
+            print("--replicas applies to the skip-gram workloads, without --clip", file=sys.stderr)
+            return 2
+        w.replicas, w.sync_every = args.replicas, max(1, args.sync_every)
+        if not w.hot:
+            w.hot = 1000
     total_steps = w.setup(nb, wl, args.warmup + args.steps + n_windows * window)
     steps = args.steps
     assert total_steps >= args.warmup + steps, "not enough examples for the requested steps"
@@ -448,6 +473,8 @@ def main() -> int:
             for _ in range(count):
                 nb.nups_step_prepared(ctx, self.queue.pop(0))
                 self.next_run += 1
+                if getattr(w, "replicas", 0) and self.next_run % w.sync_every == 0:
+                    nb.nups_sync_replicas(ctx)              # inside the timed region: part of the method's cost
                 self.fill()
 
     def run(first, count):                           # a pipeline of its own (the per-kernel pass)

@@ -103,6 +103,36 @@ nups_status nups_set_state(nups_ctx *ctx, int table, float *state_dev);
 nups_status nups_set_hot_keys(nups_ctx *ctx, int table, const uint32_t *keys_host, int64_t k);
 
 /*
+ * Stale replicas of the hot keys (Section 3.2: hot-spot keys are replicated on every node; a node's workers read
+ * and update the node's replica through shared memory; replicas are synchronised periodically by exchanging the
+ * updates accumulated since the last synchronisation; Section 5.7 varies how often).  On one device the nodes
+ * become `replicas` contiguous parts of the minibatch (example e of B belongs to part e * replicas / B; with 8,
+ * a part is what one of the eight dies works on).  With replicas > 0 every key of the declared hot sets of tables
+ * 0 and 1 (nups_set_hot_keys, before this call) gets that many replica rows in a buffer of the library's, all
+ * starting from the key's row; from then on NUPS_TASK_SGNS and NUPS_TASK_MF steps read a hot key from the
+ * replica of the accessing example's part and add that part's summed gradient to that replica only, while the
+ * key's row in the table keeps the value of the last synchronisation; keys that are not hot behave as always.
+ * nups_sync_replicas (enqueued on the stream; call it every so many steps: the paper's staleness bound is a
+ * time, 40 ms by default, here it is the caller's step count) adds every replica's difference from the row to
+ * the row, in replica order, and sets row and replicas to the result.  With one replica, or when synchronising
+ * after every step, the result is the plain step's (bit for bit with one replica, to rounding otherwise); in
+ * between, a part does not see what the other parts did to a hot key.  replicas = 0 synchronises, frees the
+ * replicas and returns to the plain step.  Waits for the stream.
+ * While replicas are on: NUPS_TASK_KGE steps return NUPS_ERR_UNIMPLEMENTED (its AdaGrad state is not
+ * replicated); nups_push / nups_push_static on a table with replicas, nups_set_hot_keys and
+ * nups_set_update_clipping return NUPS_ERR_STATE; nups_pull returns the rows of the table (the last
+ * synchronised values); nups_debug_structure lists the replica row r * H + s of hot key number s (of H) as
+ * key num_keys + r * H + s.  NUPS_ERR_STATE while prepared steps are outstanding or clipping is on;
+ * NUPS_ERR_ARG for replicas outside 0..64.
+ */
+nups_status nups_set_replicas(nups_ctx *ctx, int32_t replicas);
+nups_status nups_sync_replicas(nups_ctx *ctx);
+
+/* Device address and number of rows of a table's replica buffer ([replicas * hot keys][row_stride]; null and 0
+ * without replicas), valid until the next nups_set_replicas or nups_destroy: for inspection. */
+nups_status nups_replica_rows(nups_ctx *ctx, int table, float **rows_dev, int64_t *n_rows);
+
+/*
  * Reproducible aggregation (the push of Section 3.1 sums the updates sent for a key; in which order is left
  * open).  By default the accesses of a key are listed in the order in which positions were handed out by
  * atomic operations, so the fp32 sum of a key's contributions can differ in its last bits from run to run and

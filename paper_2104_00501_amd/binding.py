@@ -23,6 +23,7 @@ NUPS_STATIC_MAX_PUSH, NUPS_STATIC_MAX_KEYS = 16384, 1048576
 
 EXPORTS = [
     "nups_init", "nups_destroy", "nups_set_state", "nups_set_hot_keys", "nups_set_deterministic",
+    "nups_set_replicas", "nups_sync_replicas", "nups_replica_rows",
     "nups_set_update_clipping",
     "nups_get_update_clipping", "nups_pull", "nups_push", "nups_push_static",
     "nups_build_alias_table", "nups_register_distribution", "nups_register_distribution_at_level",
@@ -122,6 +123,21 @@ def nups_set_hot_keys(ctx, table, keys_host):
     import numpy as np
     k = np.ascontiguousarray(keys_host, dtype=np.uint32)
     _check(lib().nups_set_hot_keys(ctx, C.c_int(table), _ptr(k) if len(k) else C.c_void_p(None), C.c_int64(len(k))))
+
+
+def nups_set_replicas(ctx, replicas):
+    _check(lib().nups_set_replicas(ctx, C.c_int32(replicas)))
+
+
+def nups_sync_replicas(ctx):
+    _check(lib().nups_sync_replicas(ctx))
+
+
+def nups_replica_rows(ctx, table):
+    """Returns (device address, number of rows) of the table's replica buffer."""
+    rows, n = C.c_void_p(None), C.c_int64(0)
+    _check(lib().nups_replica_rows(ctx, C.c_int(table), C.byref(rows), C.byref(n)))
+    return rows.value, n.value
 
 
 def nups_set_deterministic(ctx, enable):

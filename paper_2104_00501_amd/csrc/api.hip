@@ -123,6 +123,15 @@ static nups_status sync_and_check(nups_ctx *ctx)
     return NUPS_OK;
 }
 
+static void free_replicas(Table &t)
+{
+    if (t.hot_slot_dev) (void)hipFree(t.hot_slot_dev);
+    if (t.hot_list_dev) (void)hipFree(t.hot_list_dev);
+    if (t.replica_rows) (void)hipFree(t.replica_rows);
+    t.hot_slot_dev = t.hot_list_dev = nullptr;
+    t.replica_rows = nullptr;
+}
+
 static bool valid_table(const nups_ctx *ctx, int t) { return ctx && t >= 0 && t < ctx->n_tables; }
 
 static nups_status get_prepared(nups_ctx *ctx, nups_prepared **out)
@@ -280,8 +289,10 @@ nups_status nups_destroy(nups_ctx *ctx)
     for (nups_dist *d : ctx->dists) free_dist(d);
     for (nups_prepared *p : ctx->prepared_all) free_prepared(p);
     delete ctx->static_push;   // its arrays are not its own
-    for (int t = 0; t < kMaxTables; ++t)
+    for (int t = 0; t < kMaxTables; ++t) {
         if (ctx->tab[t].hot_bits_dev) (void)hipFree(ctx->tab[t].hot_bits_dev);
+        free_replicas(ctx->tab[t]);
+    }
     if (ctx->clip_stats) (void)hipFree(ctx->clip_stats);
     if (ctx->clip_bound) (void)hipFree(ctx->clip_bound);
     if (ctx->coef) (void)hipFree(ctx->coef);
@@ -312,6 +323,7 @@ nups_status nups_set_hot_keys(nups_ctx *ctx, int table, const uint32_t *keys_hos
     if (!valid_table(ctx, table)) return fail(NUPS_ERR_ARG, "nups_set_hot_keys: bad context or table");
     if (k < 0 || (k > 0 && !keys_host)) return fail(NUPS_ERR_ARG, "nups_set_hot_keys: bad key list");
     Table &t = ctx->tab[table];
+    if (ctx->replicas > 0) return fail(NUPS_ERR_STATE, "nups_set_hot_keys: switch the replicas off first (nups_set_replicas)");
     std::vector<uint32_t> keys(keys_host, keys_host + k);
     std::vector<uint32_t> sorted(keys);
     std::sort(sorted.begin(), sorted.end());
@@ -331,6 +343,72 @@ nups_status nups_set_hot_keys(nups_ctx *ctx, int table, const uint32_t *keys_hos
     return NUPS_OK;
 }
 
+nups_status nups_set_replicas(nups_ctx *ctx, int32_t replicas)
+{
+    if (!ctx) return fail(NUPS_ERR_ARG, "nups_set_replicas: null context");
+    if (replicas < 0 || replicas > 64) return fail(NUPS_ERR_ARG, "nups_set_replicas: 0 (off) to 64 replicas");
+    if (ctx->n_tables < 2) return fail(NUPS_ERR_STATE, "nups_set_replicas: the context needs two tables");
+    for (nups_prepared *q : ctx->prepared_all)
+        if (q->live) return fail(NUPS_ERR_STATE, "nups_set_replicas: prepared steps are outstanding");
+    if (replicas > 0 && ctx->clip_factor > 0.0f)
+        return fail(NUPS_ERR_STATE, "nups_set_replicas: not together with update clipping");
+    NUPS_HIP(hipStreamSynchronize(ctx->stream));
+    if (ctx->replicas > 0) {             // what the replicas have accumulated goes into the tables first
+        for (int k = 0; k < 2; ++k) {
+            nups_status st = launch_replicas(ctx, ctx->tab[k], true);
+            if (st != NUPS_OK) return st;
+        }
+        NUPS_HIP(hipStreamSynchronize(ctx->stream));
+    }
+    for (int k = 0; k < 2; ++k) free_replicas(ctx->tab[k]);
+    ctx->replicas = 0;
+    if (replicas == 0) return NUPS_OK;
+    for (int k = 0; k < 2; ++k) {
+        Table &t = ctx->tab[k];
+        const size_t H = t.hot_keys.size();
+        if (H == 0) continue;            // no declared hot keys: no replicas for this table
+        if ((uint64_t)t.num_keys + (uint64_t)replicas * H > 0xFFFFFFF0ull)
+            return fail(NUPS_ERR_ARG, "nups_set_replicas: too many replica rows for 32-bit keys");
+        std::vector<uint32_t> slot((size_t)t.num_keys, kBadIndex);
+        for (size_t i = 0; i < H; ++i) slot[t.hot_keys[i]] = (uint32_t)i;
+        hipError_t e = hipMalloc((void **)&t.hot_slot_dev, sizeof(uint32_t) * slot.size());
+        if (e == hipSuccess) e = hipMalloc((void **)&t.hot_list_dev, sizeof(uint32_t) * H);
+        if (e == hipSuccess) e = hipMalloc((void **)&t.replica_rows, sizeof(float) * (size_t)replicas * H * t.stride);
+        if (e == hipSuccess) e = hipMemcpy(t.hot_slot_dev, slot.data(), sizeof(uint32_t) * slot.size(), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(t.hot_list_dev, t.hot_keys.data(), sizeof(uint32_t) * H, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            hip_ok(e, "nups_set_replicas: replica buffers");
+            for (int j = 0; j < 2; ++j) free_replicas(ctx->tab[j]);
+            return NUPS_ERR_DEVICE;
+        }
+    }
+    ctx->replicas = replicas;
+    for (int k = 0; k < 2; ++k) {
+        nups_status st = launch_replicas(ctx, ctx->tab[k], false);
+        if (st != NUPS_OK) return st;
+    }
+    return NUPS_OK;
+}
+
+nups_status nups_sync_replicas(nups_ctx *ctx)
+{
+    if (!ctx) return fail(NUPS_ERR_ARG, "nups_sync_replicas: null context");
+    for (int k = 0; k < 2 && k < ctx->n_tables; ++k) {
+        nups_status st = launch_replicas(ctx, ctx->tab[k], true);
+        if (st != NUPS_OK) return st;
+    }
+    return NUPS_OK;
+}
+
+nups_status nups_replica_rows(nups_ctx *ctx, int table, float **rows_dev, int64_t *n_rows)
+{
+    if (!valid_table(ctx, table) || !rows_dev || !n_rows) return fail(NUPS_ERR_ARG, "nups_replica_rows: bad arguments");
+    const Table &t = ctx->tab[table];
+    *rows_dev = t.replica_rows;
+    *n_rows = t.replica_rows ? (int64_t)ctx->replicas * (int64_t)t.hot_keys.size() : 0;
+    return NUPS_OK;
+}
+
 nups_status nups_set_deterministic(nups_ctx *ctx, int enable)
 {
     if (!ctx) return fail(NUPS_ERR_ARG, "nups_set_deterministic: null context");
@@ -345,6 +423,8 @@ nups_status nups_set_update_clipping(nups_ctx *ctx, float factor)
     if (!ctx) return fail(NUPS_ERR_ARG, "nups_set_update_clipping: null context");
     if (!(factor >= 0.0f) || !std::isfinite(factor))
         return fail(NUPS_ERR_ARG, "nups_set_update_clipping: factor must be finite and not negative");
+    if (factor > 0.0f && ctx->replicas > 0)
+        return fail(NUPS_ERR_STATE, "nups_set_update_clipping: not together with replicas");
     const size_t stats_bytes = sizeof(double) * kMaxTables * kLossSlots * kLossStride;
     if (factor > 0.0f && !(ctx->clip_factor > 0.0f)) {   // switched on: statistics start from nothing
         if (!ctx->clip_stats) {
@@ -389,6 +469,7 @@ nups_status nups_push(nups_ctx *ctx, int table, const uint32_t *keys_dev, int64_
     if (n < 0 || n > 0x7FFFFFFFll || (n > 0 && (!keys_dev || !updates_dev)))
         return fail(NUPS_ERR_ARG, "nups_push: bad arguments");
     Table &t = ctx->tab[table];
+    if (t.replica_rows) return fail(NUPS_ERR_STATE, "nups_push: the table has replicas of its hot keys (nups_set_replicas)");
     nups_prepared *p = nullptr;
     nups_status st = get_prepared(ctx, &p);
     if (st != NUPS_OK) return st;

@@ -293,23 +293,50 @@ static inline uint32_t xcd_grid(uint32_t blocks) { return (blocks + kNumXcd - 1)
 // Which technique a key gets (Section 3.2: hot spots and the long tail are managed differently).  A segment of
 // `count` accesses is cut into chunks for several workgroups if it is long and, when the caller declared a
 // hot-key set, the key is in it; every other segment is summed by a single row group.
-__device__ __forceinline__ bool in_hot_set(uint32_t key, const uint32_t *hot_bits)
+__device__ __forceinline__ bool in_hot_set(uint32_t key, const uint32_t *hot_bits, uint32_t base_keys)
 {
+    if (key >= base_keys) return true;   // a replica row of a hot key
     return ((hot_bits[key >> 5] >> (key & 31)) & 1u) != 0;
 }
 
-__device__ __forceinline__ bool takes_hot_path(uint32_t count, uint32_t key, const uint32_t *hot_bits)
+__device__ __forceinline__ bool takes_hot_path(uint32_t count, uint32_t key, const uint32_t *hot_bits, uint32_t base_keys)
 {
     if (count <= kLongSegment) return false;
-    return hot_bits == nullptr || in_hot_set(key, hot_bits);
+    return hot_bits == nullptr || in_hot_set(key, hot_bits, base_keys);
 }
 
-__device__ __forceinline__ uint32_t source_key(const KeySource &s, uint32_t i)
+// The row that example `example`'s access to `key` (a valid key of the table) goes to: the key's replica for the
+// example's part of the minibatch if the table has replicas and the key is hot, the key itself otherwise.
+__device__ __forceinline__ uint32_t replica_key(const ReplicaMap &m, uint32_t key, uint32_t example)
 {
-    if (i < s.len[0]) return s.ptr[0][i];
-    i -= s.len[0];
-    if (i < s.len[1]) return s.ptr[1][i];
-    return s.ptr[2][i - s.len[1]];
+    if (m.hot_slot == nullptr) return key;
+    const uint32_t s = m.hot_slot[key];
+    if (s == kBadIndex) return key;
+    const uint32_t part = (uint32_t)(((uint64_t)example * m.replicas) / m.batch);
+    return m.base_keys + part * m.hot_count + s;
+}
+
+// Address of row `key` of an extended key space: a row of the table or a replica row.
+__device__ __forceinline__ float *extended_row(float *table, float *replica_rows, uint32_t base_keys, uint32_t key,
+                                               int stride)
+{
+    return key < base_keys ? table + (size_t)key * stride : replica_rows + (size_t)(key - base_keys) * stride;
+}
+
+// Access i of a step's accesses to one table: its key in the table's extended key space, kBadIndex if the batch's
+// key is outside the table.
+__device__ __forceinline__ uint32_t plan_key(const KeySource &s, const ReplicaMap &m, uint32_t i)
+{
+    int which = 0;
+    if (i >= s.len[0]) {
+        i -= s.len[0];
+        which = 1;
+        if (i >= s.len[1]) { i -= s.len[1]; which = 2; }
+    }
+    const uint32_t key = s.ptr[which][i];
+    if (key >= m.base_keys) return kBadIndex;
+    const uint32_t per = s.per[which] ? s.per[which] : 1u;
+    return replica_key(m, key, i / per);
 }
 
 }  // namespace nups

@@ -60,6 +60,18 @@ bool hip_ok(hipError_t e, const char *what);
 struct KeySource {
     const uint32_t *ptr[3];
     uint32_t len[3];
+    uint32_t per[3];       // entries of each array per example (0 is read as 1): entry j belongs to example j / per
+};
+
+// Stale replicas of a table's hot keys (Section 3.2: hot-spot keys are replicated on every node, and a node's workers
+// read and update the node's replica).  The nodes are `replicas` contiguous parts of the minibatch: example e of
+// `batch` belongs to part e * replicas / batch.  Replica r of hot key number s is row r * hot_count + s of a buffer
+// of the library's, addressed as key base_keys + r * hot_count + s of an extended key space; keys below base_keys
+// are the table's own rows.  hot_slot == null: the table has no replicas.
+struct ReplicaMap {
+    const uint32_t *hot_slot;   // [base_keys] number of the key in the hot list, kBadIndex if it is not hot
+    uint32_t base_keys;         // keys of the table itself
+    uint32_t hot_count, replicas, batch;
 };
 
 // Device-side description of the per-key aggregation structure of one table for one step:
@@ -69,7 +81,8 @@ struct PlanArgs {
     uint32_t n;            // accesses (sum of src.len)
     uint32_t mark_n;       // the first mark_n accesses are marked by the structure's own first phase; the rest
                            // (samples that the step draws itself) are marked as they are drawn
-    uint32_t num_keys;     // V
+    uint32_t num_keys;     // V, plus the replica rows of the hot keys if the table has replicas (rep)
+    ReplicaMap rep;        // rep.base_keys = V also without replicas: a key of the batch is valid below it
     uint32_t words;        // bitmap words = ceil(V / 32)
     uint32_t bitmap_tiles; // ceil(words / kScanTile)
     uint32_t count_tiles;  // ceil(n / kScanTile)
@@ -119,6 +132,10 @@ struct Table {
     int32_t stride = 0;
     std::vector<uint32_t> hot_keys;   // hottest first (as declared by the caller)
     uint32_t *hot_bits_dev = nullptr; // [ceil(V/32)] membership bitmap of the declared set; null = none declared
+    // stale replicas of the hot keys (nups_set_replicas); all null / 0 while they are off
+    uint32_t *hot_slot_dev = nullptr; // [V] number of the key in hot_keys, kBadIndex if it is not hot
+    uint32_t *hot_list_dev = nullptr; // [hot keys] the hot keys
+    float *replica_rows = nullptr;    // [replicas x hot keys][stride]
     Plan *last_plan = nullptr;        // structure of the last step / push on this table (owned by a prepared step)
 };
 
@@ -132,10 +149,12 @@ struct SampleArgs {
     int32_t half;                     // LONG-TERM: bits per half of the Feistel domain
     const uint32_t *local_a, *local_b;
     uint32_t local_n, per_example, split, tile;
+    uint32_t per_sample;              // samples per example of the step that draws them (marking only; 0 is read as 1)
     uint32_t *out;                    // [n] sample keys
     uint32_t blocks;                  // workgroups that the drawing needs
     uint8_t *bytemap, *wordmap;       // maps of the step's structure to mark the keys in, or null
-    uint32_t mark_keys;               // size of that structure's table
+    uint32_t mark_keys;               // size of that structure's (extended) key space
+    ReplicaMap rep;                   // the replicas of that structure's table, to mark a drawn hot key's replica
     uint32_t *error_flag;
 };
 
@@ -208,6 +227,7 @@ struct nups_ctx {
     float clip_factor = 0.0f;
     double *clip_stats = nullptr;   // [kMaxTables][kLossSlots * kLossStride]: per slot {sum of norms, number of norms}
     float *clip_bound = nullptr;    // [kMaxTables] factor x mean norm, refreshed before each update launch
+    int replicas = 0;               // parts of the minibatch with replicas of their own of the hot keys; 0: off
     bool deterministic = false;     // structures built from now on list every segment's accesses in ascending order
     bool profiling = false;
     nups::Phase phase[NUPS_PHASE_COUNT];
@@ -261,6 +281,7 @@ struct PhaseScope {
 SampleArgs sample_args(const nups_dist *d, uint32_t *keys_out, int64_t n_samples, uint64_t step);
 nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n);
 void set_plan_shape(const nups_ctx *ctx, const Table &t, Plan &pl);
+int64_t extended_keys(const nups_ctx *ctx, const Table &t);
 nups_status static_scratch_setup(int device);   // once per device, with that device current
 void build_phases(nups_prepared &p, const SampleArgs &draw, int mark_plan);
 size_t side_lds_bytes(const SideItem &it);
@@ -268,6 +289,7 @@ SideWork take_side_work(nups_ctx *ctx, size_t *lds_bytes, uint32_t max_wgs_per_p
 nups_status flush_side_work(nups_ctx *ctx, nups_prepared *p);
 nups_status launch_side(nups_ctx *ctx, const SideItem &it);
 void free_plan_arrays(Plan &pl);
+nups_status launch_replicas(nups_ctx *ctx, Table &t, bool sync);   // false: replicas <- rows; true: synchronise
 nups_status launch_pull(nups_ctx *ctx, const Table &t, const uint32_t *keys, int64_t n, float *values);
 nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, float *partial, float *totals,
                               uint32_t grid_cap, const float *updates);

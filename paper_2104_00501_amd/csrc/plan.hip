@@ -17,6 +17,12 @@ static nups_status grow_u32(uint32_t **buf, size_t n, bool zero)
     return NUPS_OK;
 }
 
+// Keys of a table's extended key space: its rows, then the replica rows of its hot keys.
+int64_t extended_keys(const nups_ctx *ctx, const Table &t)
+{
+    return t.num_keys + (ctx->replicas > 0 && t.hot_slot_dev ? (int64_t)ctx->replicas * (int64_t)t.hot_keys.size() : 0);
+}
+
 size_t max_chunks(size_t n) { return n / kChunk + n / (kLongSegment + 1) + 2; }
 
 // Room for `need` floats of partial rows of chunked segments; growing waits for the stream.
@@ -49,7 +55,7 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
 {
     PlanArgs &a = pl.a;
     nups_status st;
-    const size_t words = (size_t)((t.num_keys + 31) / 32);
+    const size_t words = (size_t)((extended_keys(ctx, t) + 31) / 32);
     if (pl.cap_words < words) {
         NUPS_HIP(hipStreamSynchronize(ctx->stream));
         if ((st = grow_u32(&a.bitmap, words, true)) != NUPS_OK) return st;
@@ -86,8 +92,11 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
 void set_plan_shape(const nups_ctx *ctx, const Table &t, Plan &pl)
 {
     PlanArgs &a = pl.a;
-    const size_t words = (size_t)((t.num_keys + 31) / 32);
-    a.num_keys = (uint32_t)t.num_keys;
+    const size_t words = (size_t)((extended_keys(ctx, t) + 31) / 32);
+    a.num_keys = (uint32_t)extended_keys(ctx, t);
+    a.rep = ReplicaMap{nullptr, (uint32_t)t.num_keys, 0u, 0u, 1u};
+    if (ctx->replicas > 0 && t.hot_slot_dev)   // rep.batch: set with the step's batch size
+        a.rep = ReplicaMap{t.hot_slot_dev, (uint32_t)t.num_keys, (uint32_t)t.hot_keys.size(), (uint32_t)ctx->replicas, 1u};
     a.max_chunks = (uint32_t)max_chunks(pl.cap_n);
     a.rank_items = 4u;   // accesses per thread of the rank phase (2 measured slower, also in narrow-row carriers)
     a.words = (uint32_t)words;
@@ -139,6 +148,8 @@ void build_phases(nups_prepared &p, const SampleArgs &draw, int mark_plan)
         it.draw.bytemap = p.plan[mark_plan].a.bytemap;
         it.draw.wordmap = p.plan[mark_plan].a.wordmap;
         it.draw.mark_keys = p.plan[mark_plan].a.num_keys;
+        it.draw.rep = p.plan[mark_plan].a.rep;
+        it.draw.per_sample = (uint32_t)(p.batch.n_neg + p.batch.n_neg2);
     }
     const uint32_t draw_blocks = draw.scheme != 0 ? draw.blocks : 0u;
     it.draw.blocks = draw_blocks;

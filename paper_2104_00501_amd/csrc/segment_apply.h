@@ -49,14 +49,23 @@ struct SrcStaged {
 // consecutive pairs) and staged the sum at the row of the run's first pair; the other pairs of a run contribute
 // nothing more and point at a row of zeros.  A center word whose pairs are all in one run was updated by the
 // gradient kernel itself (runs_done), which had the sum and the row in registers.
+// The row that pair i's center word lives in (its replica for the pair's part of the minibatch if the word is
+// hot and the input table has replicas); kBadIndex for a key outside the table.  Runs are runs of equal rows.
+__device__ __forceinline__ uint32_t sgns_center_row(const uint32_t *center, const ReplicaMap &rep, uint32_t i)
+{
+    const uint32_t key = center[i];
+    return key < rep.base_keys ? replica_key(rep, key, i) : kBadIndex;
+}
+
 struct SrcSgnsIn {
     const float *stage;       // [B] run sums at the rows of the runs' first pairs, [zero_row] all zero
     const uint32_t *center;   // [B]
     uint32_t zero_row;
     bool runs_done;
+    ReplicaMap rep;           // of the input table
     __device__ __forceinline__ bool run_head(uint32_t i) const
     {
-        return i % kGroupsPerBlock == 0 || center[i - 1] != center[i];
+        return i % kGroupsPerBlock == 0 || sgns_center_row(center, rep, i - 1) != sgns_center_row(center, rep, i);
     }
     // Every lane of the group calls it.  The segment is one run iff its access numbers are consecutive and within
     // one workgroup of the gradient kernel.
@@ -255,6 +264,8 @@ struct ApplyArgs {
     uint32_t n;            // accesses of the plan
     uint32_t max_chunks;   // capacity of the chunk lists and of `partial`
     uint32_t deterministic; // the chunks' partial rows are added in chunk order by one group, however many
+    float *replica_rows;   // rows of the keys from base_keys on (replicas of hot keys), or null
+    uint32_t base_keys;    // keys below are rows of `table`
     float *totals;         // [workgroups of the launch][kGroupsPerBlock][stride] running totals of segments of more
                            // than kChunk accesses that one group sums by itself
 };
@@ -405,15 +416,15 @@ __device__ __forceinline__ void apply_short_item(const ApplyArgs &a, const Src &
 #pragma unroll
     for (int k = 0; k < kSegmentsPerGroup; ++k) {
         if (first[k] >= last[k]) continue;
-        if (takes_hot_path(last[k] - first[k], key[k], a.hot_bits)) continue;   // summed by chunk items
+        if (takes_hot_path(last[k] - first[k], key[k], a.hot_bits, a.base_keys)) continue;   // summed by chunk items
         if (src.segment_done(a.perm, first[k], last[k], lane)) continue;        // the gradient kernel has updated this row itself
-        const size_t off = (size_t)key[k] * a.stride;
-        float *row = a.table + off, *state_row = Opt::kHasState ? a.state + off : nullptr;
+        float *row = extended_row(a.table, a.replica_rows, a.base_keys, key[k], a.stride);
+        float *state_row = Opt::kHasState ? a.state + (size_t)key[k] * a.stride : nullptr;   // tables with state have no replicas
         Row<NV4> acc, t, g;
         sum_segment<NV4>(acc, src, a.perm, first[k], last[k], a.stride, lane, lds + (size_t)group * a.stride,
                          a.totals + ((size_t)workgroup * kGroupsPerBlock + group) * a.stride);
         opt.template load<NV4>(t, g, row, state_row, lane);   // after the sum: results are waited for in issue order, an early request of the cold row holds up the sum's first reads
-        if (opt.clips() && a.hot_bits != nullptr && in_hot_set(key[k], a.hot_bits)) opt.template clip<NV4>(acc, lane);
+        if (opt.clips() && a.hot_bits != nullptr && in_hot_set(key[k], a.hot_bits, a.base_keys)) opt.template clip<NV4>(acc, lane);
         opt.template finish<NV4>(t, g, row, state_row, acc, lane);
     }
 }
@@ -509,11 +520,13 @@ __device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &
         }
     }
     if (update && group == 0) {
-        const size_t off = (size_t)a.uniq[u] * a.stride;
+        const uint32_t key = a.uniq[u];
+        float *row = extended_row(a.table, a.replica_rows, a.base_keys, key, a.stride);
+        float *state_row = Opt::kHasState ? a.state + (size_t)key * a.stride : nullptr;
         Row<NV4> t, g;
-        opt.template load<NV4>(t, g, a.table + off, Opt::kHasState ? a.state + off : nullptr, lane);
+        opt.template load<NV4>(t, g, row, state_row, lane);
         if (opt.clips() && a.hot_bits != nullptr) opt.template clip<NV4>(acc, lane);   // chunked and declared: a hot key
-        opt.template finish<NV4>(t, g, a.table + off, Opt::kHasState ? a.state + off : nullptr, acc, lane);
+        opt.template finish<NV4>(t, g, row, state_row, acc, lane);
     }
     __syncthreads();                  // the block sums in LDS have been read: the groups' rows are theirs again
 }
@@ -584,12 +597,12 @@ struct ApplyScratch {
 static inline size_t apply_totals_floats(uint32_t grid_cap, int stride) { return (size_t)grid_cap * kGroupsPerBlock * stride; }
 
 static inline ApplyArgs make_apply_args(const Plan &pl, float *partial, float *table, float *state, int stride,
-                                        float *totals)
+                                        float *totals, float *replica_rows = nullptr)
 {
     const PlanArgs &p = pl.a;
     return ApplyArgs{table, state, p.hot_bits, p.uniq, p.seg, p.deterministic ? p.perm_sorted : p.perm, p.meta,
                      p.chunk_seg, p.chunk_base, p.chunk_done, partial, stride, p.n, p.max_chunks, p.deterministic,
-                     totals};
+                     replica_rows, p.rep.base_keys, totals};
 }
 
 static inline uint32_t max_apply_items(const Plan &pl)
@@ -654,14 +667,15 @@ struct TableUpdate {
     float *partial, *table, *state;
     Src src;
     Opt opt;
+    float *replica_rows = nullptr;   // of the table's hot keys, if it has replicas
 };
 
 template <int NV4, class U0, class U1>
 static void launch_apply2_nv(hipStream_t s, int stride, const U0 &u0, const U1 &u1, const ApplyScratch &scratch,
                              const SideWork &sw, size_t side_lds)
 {
-    const ApplyArgs a0 = make_apply_args(*u0.plan, u0.partial, u0.table, u0.state, stride, scratch.totals);
-    const ApplyArgs a1 = make_apply_args(*u1.plan, u1.partial, u1.table, u1.state, stride, scratch.totals);
+    const ApplyArgs a0 = make_apply_args(*u0.plan, u0.partial, u0.table, u0.state, stride, scratch.totals, u0.replica_rows);
+    const ApplyArgs a1 = make_apply_args(*u1.plan, u1.partial, u1.table, u1.state, stride, scratch.totals, u1.replica_rows);
     const uint32_t items = max_apply_items(*u0.plan) + max_apply_items(*u1.plan);
     const size_t lds = std::max(apply_lds_bytes(stride), side_lds);
     static size_t allowed = 0;

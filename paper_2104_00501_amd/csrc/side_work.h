@@ -52,9 +52,11 @@ __device__ __forceinline__ void emit_sample(const SampleArgs &d, uint64_t pos, u
 {
     d.out[pos] = key;
     if (d.bytemap == nullptr) return;
-    if (key >= d.mark_keys) { atomicOr(d.error_flag, 1u); return; }   // batch-local keys can be anything
-    d.bytemap[key] = 1;
-    d.wordmap[key >> 5] = 1;
+    if (key >= d.rep.base_keys) { atomicOr(d.error_flag, 1u); return; }   // batch-local keys can be anything
+    const uint32_t k = replica_key(d.rep, key, (uint32_t)pos / (d.per_sample ? d.per_sample : 1u));
+    if (k >= d.mark_keys) return;
+    d.bytemap[k] = 1;
+    d.wordmap[k >> 5] = 1;
 }
 
 // Workgroup `vb` of a drawing of d.n samples; `word` is LDS for kMaxPool + 8 words, 16-byte aligned.
@@ -150,7 +152,7 @@ __device__ __forceinline__ void mark_block(const PlanArgs &a, uint32_t vb)
     if (i == 0) a.meta[kMetaNumChunks] = 0;
     if (i < kLossSlots && a.zero_loss) a.zero_loss[i * kLossStride] = 0.0;   // the step's loss starts from zero
     if (i >= a.mark_n) return;
-    const uint32_t key = source_key(a.src, i);
+    const uint32_t key = plan_key(a.src, a.rep, i);
     if (key >= a.num_keys) { atomicOr(a.error_flag, 1u); return; }
     a.bytemap[key] = 1;
     a.wordmap[key >> 5] = 1;
@@ -245,7 +247,7 @@ __device__ __forceinline__ void slot_block(const PlanArgs &a, uint32_t vb, uint3
 #pragma unroll
     for (int j = 0; j < kSlotItems; ++j) {
         const uint32_t i = vb * kSlotTile + j * kBlock + threadIdx.x;
-        key[j] = i < a.n ? source_key(a.src, i) : kBadIndex;
+        key[j] = i < a.n ? plan_key(a.src, a.rep, i) : kBadIndex;
         if (key[j] >= a.num_keys) key[j] = kBadIndex;     // outside the table: flagged when it was marked
     }
 #pragma unroll
@@ -305,7 +307,7 @@ __device__ __forceinline__ void rank_block(const PlanArgs &a, uint32_t vb, uint3
     for (int j = 0; j < kRankItems; ++j) {
         const uint32_t i = vb * kRankTile + j * kBlock + threadIdx.x;
         uidx[j] = i < a.n ? a.slot[i] : kBadIndex;
-        key[j] = i < a.n ? source_key(a.src, i) : kBadIndex;
+        key[j] = i < a.n ? plan_key(a.src, a.rep, i) : kBadIndex;
     }
     for (uint32_t s = threadIdx.x; s < kHashSlots; s += kBlock) { hkey[s] = kBadIndex; hcnt[s] = 0; }
     __syncthreads();
@@ -388,7 +390,7 @@ __device__ __forceinline__ void counts_block(const PlanArgs &a, uint32_t vb, uin
     uint32_t nch[kScanItems], my_chunks = 0;
 #pragma unroll
     for (int j = 0; j < kScanItems; ++j) {
-        nch[j] = (u0 + j < nu && takes_hot_path(cnt[j], a.uniq[u0 + j], a.hot_bits)) ? (cnt[j] + kChunk - 1) / kChunk : 0u;
+        nch[j] = (u0 + j < nu && takes_hot_path(cnt[j], a.uniq[u0 + j], a.hot_bits, a.rep.base_keys)) ? (cnt[j] + kChunk - 1) / kChunk : 0u;
         my_chunks += nch[j];
     }
     uint32_t block_chunks;
@@ -421,7 +423,7 @@ __device__ __forceinline__ void scatter_block(const PlanArgs &a, uint32_t vb)
 {
     const uint32_t i = vb * kBlock + threadIdx.x;
     if (i >= a.n) return;
-    const uint32_t key = source_key(a.src, i);
+    const uint32_t key = plan_key(a.src, a.rep, i);
     if (key < a.num_keys) a.bytemap[key] = 0;   // also for an access that is dropped below
     a.pos[i] = kBadIndex;
     const uint32_t u = a.slot[i];

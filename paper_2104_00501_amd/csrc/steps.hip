@@ -174,6 +174,22 @@ nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, float *pa
                         SrcStaged{updates}, OptAdd{});
 }
 
+// Where the rows of a table live for the gradient kernels: the table, and the replicas of its hot keys if it has
+// any (Section 3.2).  row(key, example): the row that the example's access to `key` reads (and updates).
+struct RowSpace {
+    float *table;
+    float *replica_rows;
+    ReplicaMap rep;          // rep.base_keys: keys of the table
+    __device__ __forceinline__ uint32_t keys() const { return rep.base_keys; }
+    __device__ __forceinline__ float *row(uint32_t key, uint32_t example, int stride) const
+    {
+        const uint32_t valid = min(key, rep.base_keys - 1);   // keys outside the table are flagged by the structure
+        return extended_row(table, replica_rows, rep.base_keys, replica_key(rep, valid, example), stride);
+    }
+};
+
+static RowSpace row_space(const Table &t, const Plan &pl) { return RowSpace{t.data, t.replica_rows, pl.a.rep}; }
+
 // ------------------------------------------------------------------------------------------------
 // Skip-gram with negative sampling.  One 16-lane group per (center, context) pair:
 //   z_j = <v, u_j>, g_j = sigma(z_j) - label_j, input-side gradient of the pair = sum_j g_j u_j.
@@ -186,8 +202,7 @@ nups_status launch_push_apply(nups_ctx *ctx, Table &t, const Plan &pl, float *pa
 // So a staged gradient row is written per run that shares its word with other runs, not per pair.
 // ------------------------------------------------------------------------------------------------
 template <int NV4, bool kWithLoss>
-__global__ void __launch_bounds__(kBlock) k_sgns_grad(float *in_table, const float *out_table,
-                                                      uint32_t num_in, uint32_t num_out, int stride,
+__global__ void __launch_bounds__(kBlock) k_sgns_grad(RowSpace in_rows, RowSpace out_rows, int stride,
                                                       const uint32_t *center, const uint32_t *context,
                                                       const uint32_t *negs, uint32_t B, int K, float lr,
                                                       const uint32_t *out_pos, float *coef_at, uint32_t *row_at,
@@ -210,12 +225,12 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(float *in_table, const flo
         zero_row(z);
         store_row(stage + (size_t)zeros_at * stride, z, lane);
     }
-    const uint32_t ckey = center[e];
+    const uint32_t crow = sgns_center_row(center, in_rows.rep, e);   // the row (or replica row) of the center word
     const uint32_t slot = center_slot[e];          // kBadIndex: the center key is outside the table
     uint32_t seg_len = 0;
     if (slot != kBadIndex) seg_len = center_seg[slot + 1] - center_seg[slot];
     Row<NV4> v, acc;
-    float *v_row = in_table + (size_t)min(ckey, num_in - 1) * stride;
+    float *v_row = in_rows.row(center[e], e, stride);
     load_row(v, v_row, lane);
     // the first pair of every distinct center word keeps a copy of the input vector for the output-side update
     if (active && slot != kBadIndex && (center_rank[e] & ~kSingleAccess) == 0)
@@ -234,7 +249,7 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(float *in_table, const flo
         for (int jj = 0; jj < JU; ++jj) {
             const int j = min(j0 + jj, K);
             const uint32_t key = (j == 0) ? context[e] : negs[(size_t)e * K + (j - 1)];
-            load_row(u[jj], out_table + (size_t)min(key, num_out - 1) * stride, lane);
+            load_row(u[jj], out_rows.row(key, e, stride), lane);
         }
         float g_mine = 0.f;   // lane jj of the group keeps coefficient j0 + jj: one store for the JU of them
 #pragma unroll
@@ -254,7 +269,7 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(float *in_table, const flo
         }
     }
     // runs of equal center words inside the workgroup (pairs beyond the batch belong to no run)
-    if (lane == 0) run_key[group] = active ? ckey : kBadIndex;
+    if (lane == 0) run_key[group] = active ? crow : kBadIndex;
     store_row(run_rows + (size_t)group * stride, acc, lane);
     if (kWithLoss) {   // the wavefronts' loss sums cross the same barrier as the runs' rows
         const float wave_loss = wave_sum((active && lane == 0) ? loss_acc : 0.f);
@@ -266,9 +281,9 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(float *in_table, const flo
         for (int w = 0; w < kBlock / 64; ++w) s += (double)lds[w];
         atomicAdd(loss + (blockIdx.x % kLossSlots) * kLossStride, s);
     }
-    if (active && slot != kBadIndex && (group == 0 || run_key[group - 1] != ckey)) {
+    if (active && slot != kBadIndex && (group == 0 || run_key[group - 1] != crow)) {
         uint32_t len = 1;
-        while (group + len < (uint32_t)kGroupsPerBlock && run_key[group + len] == ckey) {
+        while (group + len < (uint32_t)kGroupsPerBlock && run_key[group + len] == crow) {
             Row<NV4> r;
             load_row(r, run_rows + (size_t)(group + len) * stride, lane);
             axpy_row(acc, 1.0f, r);
@@ -295,9 +310,8 @@ static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b, const Plan &in_
     static size_t allowed = 0, allowed_with_loss = 0;
     const auto launch = [&](auto kernel, size_t *granted) {
         allow_lds(kernel, lds, granted);
-        hipLaunchKernelGGL(kernel, dim3(sw.blocks + blocks), dim3(kBlock), lds, ctx->stream, tin.data,
-                           (const float *)tout.data, (uint32_t)tin.num_keys, (uint32_t)tout.num_keys, tin.stride, b.k0,
-                           b.k1, b.negs, (uint32_t)b.B, (int)b.n_neg, b.lr, (const uint32_t *)out_plan.a.pos, ctx->coef,
+        hipLaunchKernelGGL(kernel, dim3(sw.blocks + blocks), dim3(kBlock), lds, ctx->stream, row_space(tin, in_plan),
+                           row_space(tout, out_plan), tin.stride, b.k0, b.k1, b.negs, (uint32_t)b.B, (int)b.n_neg, b.lr, (const uint32_t *)out_plan.a.pos, ctx->coef,
                            row_at, ctx->stage, zero_row, update_whole_runs ? 1 : 0, (const uint32_t *)in_plan.a.slot,
                            (const uint32_t *)in_plan.a.rank, (const uint32_t *)in_plan.a.seg, center_rows, ctx->loss_cur,
                            sw);
@@ -323,6 +337,7 @@ static nups_status plan_two_tables(nups_ctx *ctx, nups_prepared &p, const KeySou
     p.plan[1].a.n = p.plan[1].a.mark_n = n1;
     p.plan[0].a.zero_loss = p.loss_dev;
     p.plan[1].a.zero_loss = nullptr;
+    p.plan[0].a.rep.batch = p.plan[1].a.rep.batch = (uint32_t)std::max<int64_t>(p.batch.B, 1);
     // partial rows of chunked segments: one region per table, the two updates run in the same launch
     const size_t need = (max_chunks(p.plan[0].cap_n) + max_chunks(p.plan[1].cap_n)) * (size_t)ctx->tab[0].stride;
     if ((st = ensure_partial(ctx, need)) != NUPS_OK) return st;
@@ -333,8 +348,8 @@ nups_status plan_step_sgns(nups_ctx *ctx, nups_prepared &p)
 {
     const nups_batch &b = p.batch;
     const uint32_t B = (uint32_t)b.B, K = (uint32_t)b.n_neg;
-    return plan_two_tables(ctx, p, KeySource{{b.k0, nullptr, nullptr}, {B, 0, 0}}, B,
-                           KeySource{{b.k1, b.negs, nullptr}, {B, B * K, 0}}, B * (K + 1));
+    return plan_two_tables(ctx, p, KeySource{{b.k0, nullptr, nullptr}, {B, 0, 0}, {1, 0, 0}}, B,
+                           KeySource{{b.k1, b.negs, nullptr}, {B, B * K, 0}, {1, K, 0}}, B * (K + 1));
 }
 
 static ApplyScratch update_scratch(nups_ctx *ctx, int stride) { return ApplyScratch{ctx->totals, apply_grid_of_stride(stride)}; }
@@ -378,13 +393,66 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
         PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
         if ((st = refresh_clip_bounds(ctx)) != NUPS_OK) return st;
         const TableUpdate<SrcSgnsIn, OptSgd> uin{&p.plan[0], partial_of(ctx, p, 0), tin.data, nullptr,
-                                                 SrcSgnsIn{ctx->stage, b.k0, zero_row, update_whole_runs},
-                                                 sgd_rule(ctx, 0, b.lr)};
+                                                 SrcSgnsIn{ctx->stage, b.k0, zero_row, update_whole_runs, p.plan[0].a.rep},
+                                                 sgd_rule(ctx, 0, b.lr), tin.replica_rows};
         const TableUpdate<SrcSgnsOut, OptSgd> uout{&p.plan[1], partial_of(ctx, p, 1), tout.data, nullptr,
-                                                   SrcSgnsOut{center_rows, ctx->coef, row_at}, sgd_rule(ctx, 1, b.lr)};
+                                                   SrcSgnsOut{center_rows, ctx->coef, row_at}, sgd_rule(ctx, 1, b.lr),
+                                                   tout.replica_rows};
         // the output table first: its items are the many, the input table's few remaining ones fill in behind
         if ((st = launch_apply2(ctx->stream, tin.stride, uout, uin, update_scratch(ctx, tin.stride), sw, side_lds)) != NUPS_OK) return st;
     }
+    return NUPS_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Replicas of hot keys (Section 3.2).  init: every replica starts as a copy of its key's row.  sync: the periodic
+// synchronisation, an exchange of the updates accumulated since the last one: the key's row (the value at the
+// last synchronisation) gains every replica's difference from it, in replica order, and row and replicas are set
+// to the result.  One 16-lane group per hot key.
+// ------------------------------------------------------------------------------------------------
+template <int NV4, bool kSync>
+__global__ void __launch_bounds__(kBlock) k_replicas(float *table, float *replica_rows, const uint32_t *hot_list,
+                                                     uint32_t hot_count, uint32_t replicas, int stride)
+{
+    const int lane = threadIdx.x & (kGroup - 1);
+    const uint32_t s = (blockIdx.x * kBlock + threadIdx.x) / kGroup;
+    if (s >= hot_count) return;
+    float *base_row = table + (size_t)hot_list[s] * stride;
+    Row<NV4> base, total;
+    load_row(base, base_row, lane);
+    total = base;
+    if (kSync) {
+        for (uint32_t r = 0; r < replicas; ++r) {
+            Row<NV4> v;
+            load_row(v, replica_rows + ((size_t)r * hot_count + s) * stride, lane);
+#pragma unroll
+            for (int q = 0; q < NV4; ++q) {
+                total.v[q].x += v.v[q].x - base.v[q].x;
+                total.v[q].y += v.v[q].y - base.v[q].y;
+                total.v[q].z += v.v[q].z - base.v[q].z;
+                total.v[q].w += v.v[q].w - base.v[q].w;
+            }
+        }
+        store_row(base_row, total, lane);
+    }
+    for (uint32_t r = 0; r < replicas; ++r) store_row(replica_rows + ((size_t)r * hot_count + s) * stride, total, lane);
+}
+
+nups_status launch_replicas(nups_ctx *ctx, Table &t, bool sync)
+{
+    const uint32_t H = (uint32_t)t.hot_keys.size();
+    if (!t.replica_rows || H == 0) return NUPS_OK;
+    const uint32_t blocks = (H + kGroupsPerBlock - 1) / kGroupsPerBlock;
+#define CALL(N)                                                                                                      \
+    if (sync)                                                                                                        \
+        hipLaunchKernelGGL((k_replicas<N, true>), dim3(blocks), dim3(kBlock), 0, ctx->stream, t.data, t.replica_rows,  \
+                           (const uint32_t *)t.hot_list_dev, H, (uint32_t)ctx->replicas, t.stride);                  \
+    else                                                                                                             \
+        hipLaunchKernelGGL((k_replicas<N, false>), dim3(blocks), dim3(kBlock), 0, ctx->stream, t.data, t.replica_rows, \
+                           (const uint32_t *)t.hot_list_dev, H, (uint32_t)ctx->replicas, t.stride)
+    NUPS_FOR_EACH_ROW_WIDTH(t.stride, CALL)
+#undef CALL
+    NUPS_HIP(hipGetLastError());
     return NUPS_OK;
 }
 
@@ -397,8 +465,7 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
 // tail are of this kind).  rank_w / rank_h: the plans' per-access flags (kSingleAccess); null: stage everything.
 // ------------------------------------------------------------------------------------------------
 template <int NV4>
-__global__ void __launch_bounds__(kBlock) k_mf_grad(float *W, float *H, uint32_t n_rows, uint32_t n_cols,
-                                                    int stride, const uint32_t *row, const uint32_t *col,
+__global__ void __launch_bounds__(kBlock) k_mf_grad(RowSpace W, RowSpace H, int stride, const uint32_t *row, const uint32_t *col,
                                                     const float *val, uint32_t B, float l2, float lr,
                                                     const uint32_t *rank_w, const uint32_t *rank_h, float *stage,
                                                     double *loss, SideWork sw)
@@ -411,9 +478,9 @@ __global__ void __launch_bounds__(kBlock) k_mf_grad(float *W, float *H, uint32_t
     const uint32_t c = active ? c_raw : B - 1;
     Row<NV4> w, h;
     const uint32_t rk = row[c], ck = col[c];
-    const bool alone_w = rank_w != nullptr && rk < n_rows && (rank_w[c] & kSingleAccess) != 0;
-    const bool alone_h = rank_h != nullptr && ck < n_cols && (rank_h[c] & kSingleAccess) != 0;
-    float *w_row = W + (size_t)min(rk, n_rows - 1) * stride, *h_row = H + (size_t)min(ck, n_cols - 1) * stride;
+    const bool alone_w = rank_w != nullptr && rk < W.keys() && (rank_w[c] & kSingleAccess) != 0;
+    const bool alone_h = rank_h != nullptr && ck < H.keys() && (rank_h[c] & kSingleAccess) != 0;
+    float *w_row = W.row(rk, c, stride), *h_row = H.row(ck, c, stride);
     load_row(w, w_row, lane);
     load_row(h, h_row, lane);
     const float dot = group_sum(partial_dot(w, h));
@@ -448,13 +515,13 @@ __global__ void __launch_bounds__(kBlock) k_mf_grad(float *W, float *H, uint32_t
 }
 
 template <int NV4>
-static void launch_mf_grad(nups_ctx *ctx, const nups_batch &b, const uint32_t *rank_w, const uint32_t *rank_h,
-                           const SideWork &sw, size_t side_lds)
+static void launch_mf_grad(nups_ctx *ctx, const nups_batch &b, const nups_prepared &p, const uint32_t *rank_w,
+                           const uint32_t *rank_h, const SideWork &sw, size_t side_lds)
 {
     const Table &tw = ctx->tab[0], &th = ctx->tab[1];
     const uint32_t blocks = xcd_grid((uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock));
-    hipLaunchKernelGGL(k_mf_grad<NV4>, dim3(sw.blocks + blocks), dim3(kBlock), side_lds, ctx->stream, tw.data, th.data,
-                       (uint32_t)tw.num_keys, (uint32_t)th.num_keys, tw.stride, b.k0, b.k1, b.val, (uint32_t)b.B, b.l2,
+    hipLaunchKernelGGL(k_mf_grad<NV4>, dim3(sw.blocks + blocks), dim3(kBlock), side_lds, ctx->stream,
+                       row_space(tw, p.plan[0]), row_space(th, p.plan[1]), tw.stride, b.k0, b.k1, b.val, (uint32_t)b.B, b.l2,
                        b.lr, rank_w, rank_h, ctx->stage, ctx->loss_cur, sw);
 }
 
@@ -484,7 +551,7 @@ nups_status run_step_mf(nups_ctx *ctx, nups_prepared &p)
     {
         const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
-#define CALL(N) launch_mf_grad<N>(ctx, b, rank_w, rank_h, sw, side_lds)
+#define CALL(N) launch_mf_grad<N>(ctx, b, p, rank_w, rank_h, sw, side_lds)
         NUPS_FOR_EACH_ROW_WIDTH(tw.stride, CALL)
 #undef CALL
         NUPS_HIP(hipGetLastError());
@@ -494,10 +561,11 @@ nups_status run_step_mf(nups_ctx *ctx, nups_prepared &p)
         PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
         if ((st = refresh_clip_bounds(ctx)) != NUPS_OK) return st;
         const TableUpdate<SrcStaged, OptSgd> uw{&p.plan[0], partial_of(ctx, p, 0), tw.data, nullptr,
-                                                SrcStaged{ctx->stage, singles_in_place}, sgd_rule(ctx, 0, b.lr)};
+                                                SrcStaged{ctx->stage, singles_in_place}, sgd_rule(ctx, 0, b.lr),
+                                                tw.replica_rows};
         const TableUpdate<SrcStaged, OptSgd> uh{&p.plan[1], partial_of(ctx, p, 1), th.data, nullptr,
                                                 SrcStaged{ctx->stage + (size_t)B * tw.stride, singles_in_place},
-                                                sgd_rule(ctx, 1, b.lr)};
+                                                sgd_rule(ctx, 1, b.lr), th.replica_rows};
         if ((st = launch_apply2(ctx->stream, tw.stride, uw, uh, update_scratch(ctx, tw.stride), sw, side_lds)) != NUPS_OK) return st;
     }
     return NUPS_OK;
@@ -730,6 +798,8 @@ nups_status plan_step_kge(nups_ctx *ctx, nups_prepared &p)
 {
     const nups_batch &b = p.batch;
     const uint32_t B = (uint32_t)b.B, nn = (uint32_t)(b.n_neg + b.n_neg2);
+    if (ctx->replicas > 0)
+        return fail(NUPS_ERR_UNIMPLEMENTED, "NUPS_TASK_KGE has no replicas (AdaGrad state): switch nups_set_replicas off");
     if (ctx->tab[0].stride % 128 != 0 || ctx->tab[0].stride > 512)
         return fail(NUPS_ERR_UNIMPLEMENTED, "KGE tables need a row_stride of 128, 256, 384 or 512 floats");
     return plan_two_tables(ctx, p, KeySource{{b.k0, b.k2, b.negs}, {B, B, B * nn}}, B * (2 + nn),
@@ -862,6 +932,7 @@ extern "C" nups_status nups_push_static(nups_ctx *ctx, int table, const uint32_t
     if (!ctx || table < 0 || table >= ctx->n_tables) return fail(NUPS_ERR_ARG, "nups_push_static: bad context or table");
     if (n < 0 || (n > 0 && (!keys_dev || !updates_dev))) return fail(NUPS_ERR_ARG, "nups_push_static: bad arguments");
     Table &t = ctx->tab[table];
+    if (t.replica_rows) return fail(NUPS_ERR_STATE, "nups_push_static: the table has replicas of its hot keys");
     if (n > (int64_t)kStaticPush)
         return fail(NUPS_ERR_ARG, "nups_push_static: at most NUPS_STATIC_MAX_PUSH keys per call (use nups_push)");
     if (t.num_keys > (int64_t)kStaticKeys)

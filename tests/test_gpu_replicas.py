@@ -1,0 +1,150 @@
+"""GPU parity of the steps with stale replicas of the hot keys (paper Section 3.2; oracle/replicas.py): tables and
+replica rows against the oracle's extended tables, between and after synchronisations."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from oracle import replicas as rep
+from paper_2104_00501_amd import binding as nb
+from paper_2104_00501_amd import workloads as wl
+from tests.parity import assert_table, dev, dev_u32
+
+pytestmark = pytest.mark.gpu
+
+
+def _replica_rows(ctx, table, stride):
+    """The library's replica buffer of a table, copied to the host."""
+    import torch
+    addr, n = nb.nups_replica_rows(ctx, table)
+    out = torch.empty((n, stride), dtype=torch.float32, device="cuda")
+    if n:
+        torch.cuda.synchronize()
+        hip = C.CDLL("libamdhip64.so")
+        assert hip.hipMemcpy(C.c_void_p(out.data_ptr()), C.c_void_p(addr), C.c_size_t(n * stride * 4), C.c_int(3)) == 0
+    return out.cpu().numpy()
+
+
+def _extended(ctx, table, tensor):
+    return np.concatenate([tensor.cpu().numpy(), _replica_rows(ctx, table, tensor.shape[1])], axis=0)
+
+
+@pytest.mark.parametrize("R,B,depth", [(8, 4096, 0), (3, 4100, 3), (1, 2048, 1)])
+def test_sgns_steps_with_replicas(R, B, depth):
+    V, d, K, window, lr, steps, sync_every = 20_000, 200, 5, 5, 0.01, 6, 3
+    toks = wl.zipf_stream(V, 1.1, steps * B // (2 * window) + 2 * window + 8, 11)
+    w = wl.unigram_weights(toks, V)
+    In, Out = wl.sgns_tables(V, d, 12)
+    Out[:] = wl.uniform_table(V, d, -0.5 / d, 0.5 / d, 13)
+    hot_in, hot_out = np.arange(64, dtype=np.uint32), np.arange(40, dtype=np.uint32)      # keys are frequency ranks
+    tin, tout = dev(In), dev(Out)
+    ctx = nb.nups_init([tin, tout], [d, d])
+    nb.nups_set_hot_keys(ctx, 0, hot_in)
+    nb.nups_set_hot_keys(ctx, 1, hot_out)
+    nb.nups_set_replicas(ctx, R)
+    assert nb.nups_replica_rows(ctx, 0)[1] == R * 64 and nb.nups_replica_rows(ctx, 1)[1] == R * 40
+    dist = nb.nups_register_distribution(ctx, 1, w, nb.NUPS_CONFORM, seed=11)
+    alias = orc.alias_build(w)
+    Ie, Oe = rep.extend_table(In, hot_in, R), rep.extend_table(Out, hot_out, R)
+    I0, O0 = Ie.copy(), Oe.copy()
+    synced_in, synced_out = In[hot_in].copy(), Out[hot_out].copy()      # the hot rows as the last synchronisation left them
+    cols = list(range(d))
+    for first in range(0, steps, sync_every):                  # rounds of steps, a synchronisation after each
+        pairs = [wl.window_pairs(toks, window, t * B, B) for t in range(first, first + sync_every)]
+        keys = [(dev_u32(c), dev_u32(o)) for c, o in pairs]
+        batches = [nb.make_batch(nb.NUPS_TASK_SGNS, B, keys[i][0], keys[i][1], n_neg=K, lr=lr, dist=dist,
+                                 sample_step=first + i) for i in range(sync_every)]
+        if depth == 0:
+            for b in batches:
+                nb.nups_step(ctx, b)
+        else:
+            queue = [nb.nups_prepare_step(ctx, b) for b in batches[:depth]]
+            for i in range(sync_every):
+                if i + depth < sync_every:
+                    queue.append(nb.nups_prepare_step(ctx, batches[i + depth]))
+                nb.nups_step_prepared(ctx, queue.pop(0))
+        nb.nups_check(ctx)
+        for i, (c, o) in enumerate(pairs):
+            negs = orc.sample_conform(alias, V, 11, 0, first + i, B * K)
+            rep.step_sgns_replicated(Ie, Oe, d, c, o, negs, K, lr, V, V, hot_in, hot_out, R)
+        # between synchronisations: the hot keys' rows have not moved, the replicas have drifted apart
+        gin, gout = _extended(ctx, 0, tin), _extended(ctx, 1, tout)
+        assert np.array_equal(gin[hot_in], synced_in) and np.array_equal(gout[hot_out], synced_out)
+        assert R == 1 or not np.array_equal(gin[V:V + 64], gin[V + 64:V + 128])
+        assert_table(gin, Ie, I0, cols, 1e-4, "input table and replicas, steps %d.." % first, tol_update=1e-4)
+        assert_table(gout, Oe, O0, cols, 1e-4, "output table and replicas, steps %d.." % first, tol_update=1e-4)
+        nb.nups_sync_replicas(ctx)
+        rep.sync_replicas(Ie, V, hot_in, R, d)
+        rep.sync_replicas(Oe, V, hot_out, R, d)
+        gin, gout = _extended(ctx, 0, tin), _extended(ctx, 1, tout)
+        assert_table(gin, Ie, I0, cols, 1e-4, "input table after synchronisation", tol_update=1e-4)
+        assert_table(gout, Oe, O0, cols, 1e-4, "output table after synchronisation", tol_update=1e-4)
+        for r in range(R):
+            assert np.array_equal(gin[V + 64 * r:V + 64 * (r + 1)], gin[hot_in])
+        synced_in, synced_out = gin[hot_in].copy(), gout[hot_out].copy()
+    nb.nups_destroy(ctx)
+
+
+def test_mf_steps_with_replicas_and_the_calls_they_exclude():
+    nr, nc, d, B, steps, R = 50_000, 5_000, 100, 8192, 4, 8
+    rows, cols, vals = wl.mf_cells(nr, nc, 1.1, steps * B, 21)
+    W, H = wl.uniform_table(nr, d, -0.1, 0.1, 1), wl.uniform_table(nc, d, -0.1, 0.1, 2)
+    hot_w, hot_h = np.arange(100, dtype=np.uint32), np.arange(50, dtype=np.uint32)
+    tw, th = dev(W), dev(H)
+    ctx = nb.nups_init([tw, th], [d, d])
+    nb.nups_set_hot_keys(ctx, 0, hot_w)
+    nb.nups_set_hot_keys(ctx, 1, hot_h)
+    nb.nups_set_replicas(ctx, R)
+    with pytest.raises(nb.NupsError) as e:
+        nb.nups_set_hot_keys(ctx, 0, hot_w)
+    assert e.value.status == nb.NUPS_ERR_STATE
+    with pytest.raises(nb.NupsError) as e:
+        nb.nups_set_update_clipping(ctx, 2.0)
+    assert e.value.status == nb.NUPS_ERR_STATE
+    with pytest.raises(nb.NupsError) as e:
+        nb.nups_push(ctx, 0, dev_u32([1]), 1, dev(np.zeros((1, W.shape[1]), dtype=np.float32)))
+    assert e.value.status == nb.NUPS_ERR_STATE
+    with pytest.raises(nb.NupsError) as e:
+        nb.nups_set_replicas(ctx, 65)
+    assert e.value.status == nb.NUPS_ERR_ARG
+    kr, kc, kv = dev_u32(rows), dev_u32(cols), dev(vals)
+    We, He = rep.extend_table(W, hot_w, R), rep.extend_table(H, hot_h, R)
+    W0, H0 = We.copy(), He.copy()
+    for t in range(steps):
+        nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_MF, B, kr.data_ptr() + 4 * t * B, kc.data_ptr() + 4 * t * B,
+                                        val=kv.data_ptr() + 4 * t * B, lr=0.005, l2=0.01))
+        sl = slice(t * B, (t + 1) * B)
+        rep.step_mf_replicated(We, He, d, rows[sl], cols[sl], vals[sl], 0.005, 0.01, nr, nc, hot_w, hot_h, R)
+    nb.nups_check(ctx)
+    cols_ = list(range(d))
+    assert_table(_extended(ctx, 0, tw), We, W0, cols_, 1e-4, "row factors and replicas", tol_update=1e-4)
+    assert_table(_extended(ctx, 1, th), He, H0, cols_, 1e-4, "column factors and replicas", tol_update=1e-4)
+    nb.nups_set_replicas(ctx, 0)                                # synchronises, then back to the plain step
+    rep.sync_replicas(We, nr, hot_w, R, d)
+    rep.sync_replicas(He, nc, hot_h, R, d)
+    assert nb.nups_replica_rows(ctx, 0) == (None, 0)
+    Wp, Hp = We[:nr].copy(), He[:nc].copy()
+    assert_table(tw.cpu().numpy(), Wp, W, cols_, 1e-4, "row factors after the replicas were switched off", tol_update=1e-4)
+    t = steps - 1
+    nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_MF, B, kr.data_ptr() + 4 * t * B, kc.data_ptr() + 4 * t * B,
+                                    val=kv.data_ptr() + 4 * t * B, lr=0.005, l2=0.01), want_loss=True)
+    sl = slice(t * B, (t + 1) * B)
+    orc.step_mf(Wp, Hp, d, rows[sl], cols[sl], vals[sl], 0.005, 0.01)
+    assert_table(tw.cpu().numpy(), Wp, W, cols_, 1e-4, "row factors after a plain step", tol_update=1e-4)
+    assert_table(th.cpu().numpy(), Hp, H, cols_, 1e-4, "column factors after a plain step", tol_update=1e-4)
+    nb.nups_destroy(ctx)
+
+
+def test_complex_steps_refuse_replicas():
+    E = dev(wl.complex_table(100, 64, -1, 1, 1)); R = dev(wl.complex_table(5, 64, -1, 1, 2))
+    ctx = nb.nups_init([E, R], [64, 64])
+    nb.nups_set_state(ctx, 0, dev(np.zeros((100, E.shape[1]), dtype=np.float32)))
+    nb.nups_set_state(ctx, 1, dev(np.zeros((5, E.shape[1]), dtype=np.float32)))
+    nb.nups_set_hot_keys(ctx, 0, np.arange(4, dtype=np.uint32))
+    nb.nups_set_replicas(ctx, 2)
+    k = dev_u32([1])
+    with pytest.raises(nb.NupsError) as e:
+        nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_KGE, 1, k, k, k2=k, lr=0.1, eps=1e-10))
+    assert e.value.status == nb.NUPS_ERR_UNIMPLEMENTED
+    nb.nups_destroy(ctx)
