@@ -119,6 +119,33 @@ def sample_longterm(table, num_keys, seed, dist_id, P, R, cursor, n):
     return out
 
 
+def postpone_within_handle(samples, resident_keys):
+    """Sample reuse with postponing (Section 4.4), within the N samples of one handle: walking through the
+    samples, one whose key is not local is moved to the end of the handle's samples and its key re-localised (it is
+    local from then on); every sample is postponed at most once: those met a second time, towards the end, are used
+    wherever their key is.  `resident_keys`: the keys that are local from the start (on one device: the declared hot
+    keys, which a replication technique keeps local everywhere).  Pure Python, sample by sample, as the paper words it."""
+    seq = [int(k) for k in samples]
+    local = set(int(k) for k in resident_keys)
+    postponed = [False] * len(seq)
+    i = 0
+    while i < len(seq):
+        if seq[i] in local or postponed[i]:
+            i += 1                                  # used here
+            continue
+        k = seq.pop(i)                              # not local: to the end of this handle's samples, once
+        postponed.pop(i)
+        seq.append(k)
+        postponed.append(True)
+        local.add(k)                                # its relocation has been requested
+    return np.array(seq, dtype=np.uint32)
+
+
+def sample_longterm_postponed(table, num_keys, seed, dist_id, P, R, cursor, n, resident_keys):
+    """The n samples of a handle under sample reuse with postponing: the pool's sequence, postponed within the handle."""
+    return postpone_within_handle(sample_longterm(table, num_keys, seed, dist_id, P, R, cursor, n), resident_keys)
+
+
 def sample_nonconform(keys_a, keys_b, per_example, split, T, seed, dist_id, step, n):
     a, b = _u32(keys_a), _u32(keys_b)
     assert len(a) == len(b)

@@ -169,3 +169,48 @@ def test_nonconform_tiles_and_roles():
     assert set(s[96:, 0]) <= {96, 97, 98, 99}
     with pytest.raises(ValueError):
         orc.sample_nonconform(a, b, K, 1, T, 1, 0, 0, B * K + 1)
+
+
+# ---- sample reuse with postponing (Section 4.4) ------------------------------------------------------------------
+def test_postponing_worked_examples():
+    # nothing local at first: a is postponed (and re-localised), b is postponed, the second a is used, c is
+    # postponed, the second b is used; then the postponed ones in the order in which they were postponed
+    a, b, c = 5, 9, 2
+    assert list(orc.postpone_within_handle([a, b, a, c, b], [])) == [a, b, a, b, c]
+    # a local from the start
+    assert list(orc.postpone_within_handle([a, b, a, c, b], [a])) == [a, a, b, b, c]
+    # a sample that has been postponed is used when it is reached again, even though c never became local before
+    assert list(orc.postpone_within_handle([c], [])) == [c]
+    assert list(orc.postpone_within_handle([], [1])) == []
+
+
+def test_postponing_is_a_rearrangement_with_closed_form():
+    # every sample is kept (the multiset of the handle is unchanged: what the long-term level needs), samples of
+    # local keys keep their order at the front, and exactly the first occurrences of keys that are not local from
+    # the start go to the back, in their order
+    rng = np.random.default_rng(7)
+    for trial in range(30):
+        V, n = int(rng.integers(2, 40)), int(rng.integers(0, 200))
+        samples = rng.integers(0, V, n)
+        resident = rng.choice(V, int(rng.integers(0, V)), replace=False)
+        got = orc.postpone_within_handle(samples, resident)
+        assert sorted(got) == sorted(samples)
+        first = np.zeros(n, dtype=bool)
+        seen = set(int(k) for k in resident)
+        for i, k in enumerate(samples):
+            if int(k) not in seen:
+                first[i] = True
+                seen.add(int(k))
+        assert list(got) == list(samples[~first]) + list(samples[first])
+    # everything local: nothing moves; nothing local and all keys distinct: everything is postponed once, in order
+    assert list(orc.postpone_within_handle([3, 1, 3, 2], [1, 2, 3])) == [3, 1, 3, 2]
+    assert list(orc.postpone_within_handle([4, 2, 7], [])) == [4, 2, 7]
+
+
+def test_longterm_with_postponing_keeps_the_pool_samples():
+    V, P, R = 50, 200, 3
+    table = orc.alias_build(np.arange(1, V + 1, dtype=np.float64))
+    plain = orc.sample_longterm(table, V, 3, 0, P, R, 40, 300)
+    post = orc.sample_longterm_postponed(table, V, 3, 0, P, R, 40, 300, resident_keys=[49, 48, 47])
+    assert sorted(post) == sorted(plain) and not np.array_equal(post, plain)
+    assert np.array_equal(orc.sample_longterm_postponed(table, V, 3, 0, P, R, 40, 300, range(V)), plain)
