@@ -412,6 +412,8 @@ def main() -> int:
     ap.add_argument("--replicas", type=int, default=0,
                     help="skip-gram workloads: this many stale replicas of each hot key (paper Section 3.2), one per "
                          "contiguous part of the batch; declares the 1,000 most frequent keys hot if none are declared")
+    ap.add_argument("--deterministic", action="store_true",
+                    help="sum every key's contributions in a fixed order (results bit-identical from run to run)")
     ap.add_argument("--sync-every", type=int, default=8, help="steps between two synchronisations of the replicas")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -450,6 +452,8 @@ def main() -> int:
     assert total_steps >= args.warmup + steps, "not enough examples for the requested steps"
     n_windows = min(n_windows, (total_steps - args.warmup - steps) // window)
     ctx, B = w.ctx, w.B
+    if args.deterministic:
+        nb.nups_set_deterministic(ctx, 1)
     if args.cpu_steps != 0 and getattr(w, "In", None) is None:   # the oracle starts from the same initial tables
         w.tables_initial = [t.clone() for t in w.tables]
         if hasattr(w, "states"):
@@ -536,6 +540,20 @@ def main() -> int:
     cal_out = torch.empty((n_cal, w.stride), dtype=torch.float32, device="cuda")
     nb.nups_pull(ctx, 0, cal_keys, n_cal, cal_out)
     torch.cuda.synchronize()
+    # the same number of rows at uniformly random keys (the second launch of the gather kernel, for the same
+    # scaling on a random gather), then both again several times for the gather's own rate
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    rnd_keys = torch.randint(0, int(w.tables[0].shape[0]), (n_cal,), dtype=torch.int32, device="cuda", generator=gen)
+    nb.nups_pull(ctx, 0, rnd_keys, n_cal, cal_out)
+    torch.cuda.synchronize()
+    pull = {"rows": n_cal, "bytes_per_call": 2 * n_cal * w.stride * 4}
+    for name, keys in (("in_order", cal_keys), ("random", rnd_keys)):
+        t1 = time.perf_counter()
+        for _ in range(10):
+            nb.nups_pull(ctx, 0, keys, n_cal, cal_out)
+        torch.cuda.synchronize()
+        pull[name + "_GBps"] = 10 * pull["bytes_per_call"] / (time.perf_counter() - t1) / 1e9
     del cal_out
 
     # Algorithmic bytes under snapshot semantics: every distinct touched row is read once and written
@@ -546,12 +564,15 @@ def main() -> int:
     dominant = max((p for p in ("grad", "apply0", "apply1") if p in phases and p in alg), key=lambda p: phases[p])
     dom_ms = phases[dominant]
     achieved = alg[dominant] / (dom_ms * 1e-3) / 1e9
+    step_traffic = recorded_traffic(args.workload, "step")     # all kernels of a step, by the same counters
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBPS, "traffic": recorded_traffic(args.workload, dominant),
                 "algorithmic_bytes_per_launch": alg[dominant], "kernel_ms": dom_ms,
                 "per_kernel_GBps": {p: alg[p] / (phases[p] * 1e-3) / 1e9 for p in ("grad", "apply0", "apply1")
                                     if p in phases and p in alg},
                 "whole_step_algorithmic_GBps": alg["step"] / (ms_per_step * 1e-3) / 1e9,
+                "whole_step_traffic": step_traffic,
+                "whole_step_traffic_GBps": None if step_traffic is None else step_traffic / (ms_per_step * 1e-3) / 1e9,
                 "whole_step_logical_GBps": w.logical_bytes() / (ms_per_step * 1e-3) / 1e9,
                 "distinct_rows_per_step": {"table0": nu0, "table1": nu1}}
 
@@ -578,7 +599,7 @@ def main() -> int:
         "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": w.config(), "roofline": roofline, "phases_ms_per_step": phases, "cpu_baseline": cpu,
-        "finite": finite,
+        "finite": finite, "gather_kernel": pull, "deterministic": bool(args.deterministic),
         "windows_ms_per_step": {"steps_per_window": window, "median": float(np.median(window_ms)) if window_ms else None,
                                 "min": min(window_ms) if window_ms else None, "max": max(window_ms) if window_ms else None},
     }

@@ -255,6 +255,21 @@ nups_status nups_set_local_keys(nups_dist *dist, const uint32_t *keys_a_dev, con
                                 int64_t n_examples, int32_t per_example, int32_t split, int32_t tile);
 
 /*
+ * NUPS_LONGTERM only: sample reuse WITH POSTPONING (Section 4.4, "Sample reuse with postponing").  The paper's
+ * server walks through the prepared samples and moves one whose key is not local at that moment to the end, once,
+ * while the key is relocated.  On one device "local" is read as "in the table's declared hot set" (the keys a
+ * replication technique keeps resident everywhere; none declared: no key is resident at the start), and the
+ * walk covers the N samples of one handle: handles prepared while postponing is on hold the pool's sequence with
+ * the first occurrence (within the handle) of every non-resident key moved behind all other samples, the moved
+ * samples in the order in which they were met, every other sample in its original order.  The hot set is read
+ * when the handle is prepared.  enable = 0 switches back to the plain pool sequence.  Costs 4 bytes of device
+ * memory per key of the table while on.  Steps take such samples through batch.sample (the handle); naming the
+ * distribution in batch.dist instead returns NUPS_ERR_UNIMPLEMENTED.
+ * Errors: NUPS_ERR_ARG for a null distribution, NUPS_ERR_STATE for another scheme, NUPS_ERR_DEVICE.
+ */
+nups_status nups_set_postponing(nups_dist *dist, int enable);
+
+/*
  * PrepareSample(dist, N): enqueues the drawing of N sample keys for step `step` (one
  * launch on the stream) and returns at once.  For NUPS_LONGTERM the distribution's cursor advances by N (step
  * is ignored).  The handle must be released with nups_release_sample.

@@ -27,7 +27,7 @@ EXPORTS = [
     "nups_set_update_clipping",
     "nups_get_update_clipping", "nups_pull", "nups_push", "nups_push_static",
     "nups_build_alias_table", "nups_register_distribution", "nups_register_distribution_at_level",
-    "nups_select_hot_keys", "nups_set_local_keys", "nups_prepare_sample",
+    "nups_select_hot_keys", "nups_set_local_keys", "nups_set_postponing", "nups_prepare_sample",
     "nups_pull_sample", "nups_sample_keys", "nups_release_sample", "nups_step", "nups_prepare_step",
     "nups_step_prepared", "nups_debug_structure",
     "nups_check", "nups_profile", "nups_profile_read", "nups_phase_name", "nups_last_error",
@@ -212,6 +212,10 @@ def nups_select_hot_keys(frequency_host, factor=100.0):
 def nups_set_local_keys(dist, keys_a, keys_b, n_examples, per_example, split, tile):
     _check(lib().nups_set_local_keys(dist, _ptr(keys_a), _ptr(keys_b), C.c_int64(n_examples),
                                      C.c_int32(per_example), C.c_int32(split), C.c_int32(tile)))
+
+
+def nups_set_postponing(dist, enable):
+    _check(lib().nups_set_postponing(dist, C.c_int(1 if enable else 0)))
 
 
 def nups_prepare_sample(dist, n, step):

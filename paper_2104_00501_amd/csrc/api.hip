@@ -65,6 +65,7 @@ PhaseScope::~PhaseScope()
 static void free_sample(nups_sample *h)
 {
     if (h->keys_dev) (void)hipFree(h->keys_dev);
+    if (h->raw_dev) (void)hipFree(h->raw_dev);
     delete h;
 }
 
@@ -74,6 +75,8 @@ static void free_dist(nups_dist *d)
     for (nups_sample *h : d->recycled) free_sample(h);
     if (d->thresh_dev) (void)hipFree(d->thresh_dev);
     if (d->alias_dev) (void)hipFree(d->alias_dev);
+    if (d->first_pos_dev) (void)hipFree(d->first_pos_dev);
+    if (d->tile_counts_dev) (void)hipFree(d->tile_counts_dev);
     delete d;
 }
 
@@ -191,6 +194,9 @@ static nups_status check_batch(nups_ctx *ctx, const nups_batch *b)
             return fail(NUPS_ERR_ARG, "nups_step: SGNS negatives index table 1: register the distribution there");
         if (b->task == NUPS_TASK_KGE && b->dist->table != 0)
             return fail(NUPS_ERR_ARG, "nups_step: KGE negatives index table 0: register the distribution there");
+        if (b->dist->postpone)
+            return fail(NUPS_ERR_UNIMPLEMENTED, "nups_step: a distribution with postponing is drawn from through "
+                                                "nups_prepare_sample; pass the handle as batch.sample");
         if (b->dist->scheme == NUPS_NONCONFORM && !b->dist->local_a)
             return fail(NUPS_ERR_STATE, "nups_step: call nups_set_local_keys first");
         if (b->dist->scheme == NUPS_NONCONFORM && b->B * nn > b->dist->local_n * (int64_t)b->dist->per_example)
@@ -581,6 +587,25 @@ nups_status nups_set_local_keys(nups_dist *dist, const uint32_t *keys_a_dev, con
     return NUPS_OK;
 }
 
+nups_status nups_set_postponing(nups_dist *dist, int enable)
+{
+    if (!dist) return fail(NUPS_ERR_ARG, "nups_set_postponing: null distribution");
+    if (dist->scheme != NUPS_LONGTERM) return fail(NUPS_ERR_STATE, "nups_set_postponing: scheme is not LONG-TERM");
+    if (enable && !dist->first_pos_dev) {
+        const size_t bytes = sizeof(uint32_t) * (size_t)dist->ctx->tab[dist->table].num_keys;
+        hipError_t e = hipMalloc((void **)&dist->first_pos_dev, bytes);
+        if (e == hipSuccess) e = hipMemset(dist->first_pos_dev, 0xFF, bytes);    // "not seen" everywhere
+        if (e != hipSuccess) {
+            hip_ok(e, "nups_set_postponing: first-occurrence array");
+            if (dist->first_pos_dev) (void)hipFree(dist->first_pos_dev);
+            dist->first_pos_dev = nullptr;
+            return NUPS_ERR_DEVICE;
+        }
+    }
+    dist->postpone = enable != 0;
+    return NUPS_OK;
+}
+
 nups_status nups_prepare_sample(nups_dist *dist, int64_t n, uint64_t step, nups_sample **out)
 {
     if (!out) return fail(NUPS_ERR_ARG, "nups_prepare_sample: out is null");
@@ -606,6 +631,14 @@ nups_status nups_prepare_sample(nups_dist *dist, int64_t n, uint64_t step, nups_
         if (e == hipSuccess) e = hipMalloc((void **)&h->keys_dev, sizeof(uint32_t) * h->cap);
         if (e != hipSuccess) { hip_ok(e, "nups_prepare_sample: key buffer"); h->cap = 0; st = NUPS_ERR_DEVICE; }
     }
+    if (st == NUPS_OK && dist->postpone && h->raw_cap < (size_t)n) {
+        hipError_t e = hipStreamSynchronize(ctx->stream);
+        if (e == hipSuccess && h->raw_dev) e = hipFree(h->raw_dev);
+        h->raw_dev = nullptr;
+        h->raw_cap = h->cap;
+        if (e == hipSuccess) e = hipMalloc((void **)&h->raw_dev, sizeof(uint32_t) * h->raw_cap);
+        if (e != hipSuccess) { hip_ok(e, "nups_prepare_sample: key buffer"); h->raw_cap = 0; st = NUPS_ERR_DEVICE; }
+    }
     if (st != NUPS_OK) { dist->recycled.push_back(h); return st; }
     h->n = n;
     h->pulled = 0;
@@ -615,10 +648,11 @@ nups_status nups_prepare_sample(nups_dist *dist, int64_t n, uint64_t step, nups_
         it.phase = kSideDraw;
         it.n_plans = 0;
         it.blocks_per_plan = 1;
-        it.draw = sample_args(dist, h->keys_dev, n, step);
+        it.draw = sample_args(dist, dist->postpone ? h->raw_dev : h->keys_dev, n, step);
         it.blocks = it.draw.blocks;
         PhaseScope scope(ctx, NUPS_PHASE_SAMPLE, ctx->stream);
         st = launch_side(ctx, it);
+        if (st == NUPS_OK && dist->postpone) st = launch_postpone(dist, h->raw_dev, h->keys_dev, n);
     }
     if (dist->scheme == NUPS_LONGTERM) dist->cursor += (uint64_t)n;
     if (st != NUPS_OK) { h->live = false; dist->recycled.push_back(h); return st; }

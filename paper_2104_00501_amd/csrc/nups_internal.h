@@ -249,6 +249,10 @@ struct nups_dist {
     int64_t P = 1;
     uint64_t seed = 0;
     uint64_t cursor = 0;           // LONG-TERM: samples handed to earlier handles
+    // LONG-TERM with postponing (Section 4.4): samples of keys that are not resident move to the end of their handle
+    bool postpone = false;
+    uint32_t *first_pos_dev = nullptr;      // [num_keys] first position of a key in the handle being built, else ~0
+    uint32_t *tile_counts_dev = nullptr;   size_t tile_cap = 0;
     // NON-CONFORM
     const uint32_t *local_a = nullptr, *local_b = nullptr;
     int64_t local_n = 0;
@@ -260,6 +264,7 @@ struct nups_dist {
 struct nups_sample {
     nups_dist *dist = nullptr;
     uint32_t *keys_dev = nullptr;   size_t cap = 0;
+    uint32_t *raw_dev = nullptr;    size_t raw_cap = 0;   // the pool's sequence before postponing
     int64_t n = 0;
     int64_t pulled = 0;
     bool live = false;
@@ -279,6 +284,7 @@ struct PhaseScope {
 
 // host-side helpers and launchers (defined in the .hip files)
 SampleArgs sample_args(const nups_dist *d, uint32_t *keys_out, int64_t n_samples, uint64_t step);
+nups_status launch_postpone(nups_dist *d, const uint32_t *raw, uint32_t *out, int64_t n_samples);
 nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n);
 void set_plan_shape(const nups_ctx *ctx, const Table &t, Plan &pl);
 int64_t extended_keys(const nups_ctx *ctx, const Table &t);

@@ -159,3 +159,149 @@ def test_a_conformity_level_selects_the_scheme_of_the_untuned_configuration():
         nb.nups_register_distribution_at_level(ctx, 0, w, 7, seed=31)
     assert e.value.status == nb.NUPS_ERR_ARG
     nb.nups_destroy(ctx)
+
+
+@pytest.mark.parametrize("V,n_hot,P,R,sizes", [(500_000, 1000, 1_000_000, 16, (40_960, 1, 100_000, 12_345)),
+                                               (500_000, 0, 1000, 2, (5000, 3000)),
+                                               (37, 5, 77, 3, (1000, 256, 257)),
+                                               (5, 0, 1, 1, (3,))])
+def test_longterm_with_postponing_is_bit_exact(V, n_hot, P, R, sizes):
+    """Sample reuse with postponing (Section 4.4) within each handle; the resident keys are the declared hot set."""
+    ctx, _ = _ctx(V, d=20)
+    w = wl.expected_unigram_weights(V, 1.0, 2e8)
+    hot = np.arange(n_hot, dtype=np.uint32)                 # keys are frequency ranks
+    if n_hot:
+        nb.nups_set_hot_keys(ctx, 0, hot)
+    dist = nb.nups_register_distribution(ctx, 0, w, nb.NUPS_LONGTERM, P=P, R=R, seed=5)
+    nb.nups_set_postponing(dist, True)
+    table = orc.alias_build(w)
+    cursor = 0
+    for n in sizes:
+        h = nb.nups_prepare_sample(dist, n, 0)
+        got = _keys_of(h, n)
+        nb.nups_release_sample(h)
+        ref = orc.sample_longterm_postponed(table, V, 5, 0, P, R, cursor, n, hot)
+        assert np.array_equal(got, ref)
+        plain = orc.sample_longterm(table, V, 5, 0, P, R, cursor, n)
+        assert n < 100 or not np.array_equal(got, plain)                    # something did move
+        cursor += n
+    nb.nups_set_postponing(dist, False)                     # back to the pool's own sequence, the cursor goes on
+    h = nb.nups_prepare_sample(dist, 1000, 0)
+    assert np.array_equal(_keys_of(h, 1000), orc.sample_longterm(table, V, 5, 0, P, R, cursor, 1000))
+    nb.nups_release_sample(h)
+    other = nb.nups_register_distribution(ctx, 0, w, nb.NUPS_CONFORM, seed=5)
+    with pytest.raises(nb.NupsError) as e:
+        nb.nups_set_postponing(other, True)
+    assert e.value.status == nb.NUPS_ERR_STATE
+    nb.nups_destroy(ctx)
+
+
+def test_steps_take_postponed_samples_through_the_handle_only():
+    from tests.parity import assert_table
+    V, d, B, K, lr = 20_000, 100, 4096, 3, 0.01
+    toks = wl.zipf_stream(V, 1.1, B // 4 + 20, 11)
+    c, o = wl.window_pairs(toks, 2, 0, B)
+    w = wl.unigram_weights(toks, V)
+    In, Out = wl.sgns_tables(V, d, 12)
+    Out[:] = wl.uniform_table(V, d, -0.5 / d, 0.5 / d, 13)
+    tin, tout = dev(In), dev(Out)
+    ctx = nb.nups_init([tin, tout], [d, d])
+    hot = np.arange(200, dtype=np.uint32)
+    nb.nups_set_hot_keys(ctx, 1, hot)
+    dist = nb.nups_register_distribution(ctx, 1, w, nb.NUPS_LONGTERM, P=100_000, R=4, seed=9)
+    nb.nups_set_postponing(dist, True)
+    kc, ko = dev_u32(c), dev_u32(o)
+    with pytest.raises(nb.NupsError) as e:
+        nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_SGNS, B, kc, ko, n_neg=K, lr=lr, dist=dist))
+    assert e.value.status == nb.NUPS_ERR_UNIMPLEMENTED
+    h = nb.nups_prepare_sample(dist, B * K, 0)
+    nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_SGNS, B, kc, ko, n_neg=K, lr=lr, sample=h))
+    nb.nups_check(ctx)
+    nb.nups_release_sample(h)
+    negs = orc.sample_longterm_postponed(orc.alias_build(w), V, 9, 0, 100_000, 4, 0, B * K, hot)
+    Ir, Or = In.copy(), Out.copy()
+    orc.step_sgns(Ir, Or, d, c, o, negs, K, lr)
+    cols = list(range(d))
+    assert_table(tin.cpu().numpy(), Ir, In, cols, 1e-5, "input table")
+    assert_table(tout.cpu().numpy(), Or, Out, cols, 1e-5, "output table")
+    nb.nups_destroy(ctx)
+
+
+def test_partial_pulls_of_handles_between_prepared_steps_that_draw_in_running_launches():
+    """PullSample in its n_j form (Section 4.3): two handles are consumed piece by piece while steps run whose own
+    drawing and structure, prepared three ahead, ride in the launches of the steps before them.  Every pulled key
+    is the oracle's, every pulled row is the oracle's table as the steps enqueued before the pull left it."""
+    import torch
+    from tests.parity import assert_table, param_err
+    V, d, B, K, lr, steps, depth = 30_000, 100, 2048, 3, 0.01, 8, 3
+    toks = wl.zipf_stream(V, 1.1, steps * B // 4 + 20, 21)
+    pairs = [wl.window_pairs(toks, 2, t * B, B) for t in range(steps)]
+    w = wl.unigram_weights(toks, V)
+    In, Out = wl.sgns_tables(V, d, 22)
+    Out[:] = wl.uniform_table(V, d, -0.5 / d, 0.5 / d, 23)
+    tin, tout = dev(In), dev(Out)
+    ctx = nb.nups_init([tin, tout], [d, d])
+    step_dist = nb.nups_register_distribution(ctx, 1, w, nb.NUPS_BOUNDED, U=4, G=250, seed=31)
+    pull_dist = nb.nups_register_distribution(ctx, 1, w, nb.NUPS_CONFORM, seed=32)
+    alias = orc.alias_build(w)
+    keys = [(dev_u32(c), dev_u32(o)) for c, o in pairs]
+    batches = [nb.make_batch(nb.NUPS_TASK_SGNS, B, keys[t][0], keys[t][1], n_neg=K, lr=lr, dist=step_dist,
+                             sample_step=t) for t in range(steps)]
+    n1, n2 = 5000, 3001
+    ref1 = orc.sample_conform(alias, V, 32, 1, 100, n1)
+    ref2 = orc.sample_conform(alias, V, 32, 1, 101, n2)
+    h1 = nb.nups_prepare_sample(pull_dist, n1, 100)
+    h2 = None
+    stride = tout.shape[1]
+    got_keys = {1: torch.zeros(n1, dtype=torch.int32, device="cuda"), 2: torch.zeros(n2, dtype=torch.int32, device="cuda")}
+    got_vals = {1: torch.zeros((n1, stride), dtype=torch.float32, device="cuda"),
+                2: torch.zeros((n2, stride), dtype=torch.float32, device="cuda")}
+    pieces = []                                            # (handle number, first, count, steps run before the pull)
+    done = {1: 0, 2: 0}
+
+    def pull_piece(which, handle, count, after_steps):
+        first = done[which]
+        nb.nups_pull_sample(handle, count, got_keys[which][first:first + count], got_vals[which][first:first + count])
+        pieces.append((which, first, count, after_steps))
+        done[which] += count
+
+    queue = [nb.nups_prepare_step(ctx, b) for b in batches[:depth]]
+    for t in range(steps):
+        if t + depth < steps:
+            queue.append(nb.nups_prepare_step(ctx, batches[t + depth]))
+        pull_piece(1, h1, 617 if t < steps - 1 else n1 - done[1], t)        # before step t: sees steps 0..t-1
+        nb.nups_step_prepared(ctx, queue.pop(0))
+        if t == 2:
+            h2 = nb.nups_prepare_sample(pull_dist, n2, 101)
+        if h2 is not None and done[2] < n2:
+            pull_piece(2, h2, min(1000, n2 - done[2]), t + 1)               # after step t
+    nb.nups_check(ctx)
+    torch.cuda.synchronize()
+    assert done == {1: n1, 2: n2}
+    assert np.array_equal(host_u32(got_keys[1]), ref1) and np.array_equal(host_u32(got_keys[2]), ref2)
+    # the oracle's tables after 0, 1, ..., steps steps
+    Ir, Or = In.copy(), Out.copy()
+    snapshots = [Or.copy()]
+    for t, (c, o) in enumerate(pairs):
+        negs = orc.sample_bounded(alias, V, 31, 0, t, B * K, 4, 250)
+        orc.step_sgns(Ir, Or, d, c, o, negs, K, lr)
+        snapshots.append(Or.copy())
+    vals = {1: got_vals[1].cpu().numpy(), 2: got_vals[2].cpu().numpy()}
+    refs = {1: ref1, 2: ref2}
+    worst = 0.0
+    for which, first, count, after in pieces:
+        k = refs[which][first:first + count]
+        rel, _ = param_err(vals[which][first:first + count], snapshots[after][k], Out[k], list(range(d)))
+        worst = max(worst, rel)
+        if after == 0:
+            assert np.array_equal(vals[which][first:first + count], Out[k])
+    print("pulled rows against the oracle's tables at the time of the pull: parameter err %.3g" % worst)
+    assert worst <= 1e-4
+    changed = [not np.array_equal(snapshots[a][refs[wh][f:f + n]], Out[refs[wh][f:f + n]]) for wh, f, n, a in pieces if a > 0]
+    assert all(changed)                                     # the later pieces did see rows that steps had moved
+    cols = list(range(d))
+    assert_table(tin.cpu().numpy(), Ir, In, cols, 1e-4, "input table after the steps", tol_update=1e-4)
+    assert_table(tout.cpu().numpy(), Or, Out, cols, 1e-4, "output table after the steps", tol_update=1e-4)
+    nb.nups_release_sample(h1)
+    nb.nups_release_sample(h2)
+    nb.nups_destroy(ctx)

@@ -59,6 +59,8 @@ def test_init_rejects_bad_shapes_before_touching_the_device():
     assert call(10, 100, 64) == nb.NUPS_ERR_ARG          # dim > row_stride
     assert call(10, 100, 100) == nb.NUPS_ERR_ARG         # stride not a multiple of 64
     assert call(10, 100, 2048) == nb.NUPS_ERR_ARG        # stride too large
+    assert call(10, 100, 448) == nb.NUPS_ERR_ARG         # a multiple of 64 outside the supported set
+    assert call(10, 100, 960) == nb.NUPS_ERR_ARG
     assert call(0, 100, 128) == nb.NUPS_ERR_ARG          # no keys
     assert call(10, 0, 128) == nb.NUPS_ERR_ARG
     assert call(10, 100, 128, n=0) == nb.NUPS_ERR_ARG
@@ -77,6 +79,7 @@ def test_null_objects_are_rejected():
     assert lib.nups_pull_sample(None, C.c_int64(1), None, None) == nb.NUPS_ERR_ARG
     assert lib.nups_prepare_sample(None, C.c_int64(1), C.c_uint64(0), C.byref(C.c_void_p())) == nb.NUPS_ERR_ARG
     assert lib.nups_check(None) == nb.NUPS_ERR_ARG
+    assert lib.nups_set_postponing(None, C.c_int(1)) == nb.NUPS_ERR_ARG
     assert nb.nups_phase_name(nb.NUPS_PHASE_GRAD) == "grad" and nb.nups_phase_name(99) == ""
 
 
