@@ -404,7 +404,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="sgns_1m_d300_bounded_u4", choices=sorted(WORKLOADS))
     ap.add_argument("--depth", type=int, default=None,
-                    help="steps prepared ahead of the one that runs (default 3; 4 for matrix factorisation)")
+                    help="steps prepared ahead of the one that runs (default 3; 4 for matrix factorisation and "
+                         "with --deterministic)")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: about 15 s worth, 0: skip)")
     ap.add_argument("--clip", type=float, default=0.0,
                     help="SGD workloads: clip hot-key updates at this factor times their mean norm (0: off); "
@@ -430,7 +431,7 @@ def main() -> int:
     torch.cuda.set_device(0)
     w = WORKLOADS[args.workload]()
     if args.depth is None:
-        args.depth = 4 if isinstance(w, Mf) else 3
+        args.depth = 4 if isinstance(w, Mf) or args.deterministic else 3   # deterministic mode: two more phases per step
     if args.clip > 0.0:
         if isinstance(w, Kge):
             print("--clip applies to the SGD workloads; the AdaGrad steps are never clipped", file=sys.stderr)

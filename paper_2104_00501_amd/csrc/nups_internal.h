@@ -16,7 +16,7 @@ constexpr int kGroup = 16;            // lanes that cooperate on one row (one DP
 constexpr int kBlock = 256;           // threads per workgroup (4 wavefronts, 16 row groups)
 constexpr int kGroupsPerBlock = kBlock / kGroup;
 constexpr int kMaxTables = 4;
-constexpr int kMaxSide = 3;            // later steps whose preparatory work one launch can carry (one phase each)
+constexpr int kMaxSide = 4;            // later steps whose preparatory work one launch can carry (one phase each)
 constexpr int kMaxStride = 1024;
 constexpr int kScanItems = 2;         // items per thread in the tile scans
 constexpr int kScanTile = kBlock * kScanItems;
@@ -104,6 +104,8 @@ struct PlanArgs {
     uint32_t *seg;         // [n + 1]     exclusive prefix sums of count
     uint32_t *perm;        // [n]         accesses grouped by key (inside a segment: in the order positions were handed out)
     uint32_t *perm_sorted; // [n]         the same with every segment in ascending order (deterministic mode only)
+    uint32_t *perm_pieces; // [n]         on the way there: ascending inside every piece of a segment (a piece: the part of
+                           //             the segment inside one block of kBlock consecutive positions)
     uint32_t *slot;        // [n]         per access: index of its key among the distinct keys
     uint32_t *pos;         // [n]         per access: where it stands in perm (perm_sorted in deterministic mode)
     uint32_t *rank;        // [n]         per access: position inside its key's segment (| kSingleAccess)
@@ -160,7 +162,7 @@ struct SampleArgs {
 
 // Phases of a step's preparatory work, in order (side_work.h).
 enum SidePhase : int32_t {
-    kSideDraw = 0, kSideTiles, kSidePrefix, kSideSlot, kSideRank, kSideCountTiles, kSideCounts, kSideScatter, kSideSort
+    kSideDraw = 0, kSideTiles, kSidePrefix, kSideSlot, kSideRank, kSideCountTiles, kSideCounts, kSideScatter, kSideSort, kSideMerge
 };
 
 // One phase of one step: units block0 .. block0 + blocks - 1 of it.

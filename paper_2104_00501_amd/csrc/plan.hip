@@ -41,7 +41,7 @@ nups_status ensure_totals(nups_ctx *ctx, int stride)
 void free_plan_arrays(Plan &pl)
 {
     PlanArgs &a = pl.a;
-    for (uint32_t *p : {a.uniq, a.count, a.seg, a.perm, a.perm_sorted, a.slot, a.pos, a.rank, a.chunk_seg, a.chunk_base, a.chunk_done, a.meta,
+    for (uint32_t *p : {a.uniq, a.count, a.seg, a.perm, a.perm_sorted, a.perm_pieces, a.slot, a.pos, a.rank, a.chunk_seg, a.chunk_base, a.chunk_done, a.meta,
                         a.bitmap, a.word_rank, a.tile_sum, a.tile_prefix, a.cnt_work})
         if (p) (void)hipFree(p);
     if (a.bytemap) (void)hipFree(a.bytemap);
@@ -67,8 +67,12 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
     if (pl.cap_n < n || pl.cap_n == 0) {
         NUPS_HIP(hipStreamSynchronize(ctx->stream));
         const size_t cap = n + n / 4 + 1024;
-        for (uint32_t **b : {&a.uniq, &a.count, &a.perm, &a.perm_sorted, &a.slot, &a.pos, &a.rank})
+        for (uint32_t **b : {&a.uniq, &a.count, &a.slot, &a.rank})
             if ((st = grow_u32(b, cap, false)) != NUPS_OK) return st;
+        // zeroed: a position that a build leaves out (a key array changed behind a prepared step) then holds an
+        // access number of an earlier build or zero, never an arbitrary word
+        for (uint32_t **b : {&a.perm, &a.perm_sorted, &a.perm_pieces, &a.pos})
+            if ((st = grow_u32(b, cap, true)) != NUPS_OK) return st;
         if ((st = grow_u32(&a.cnt_work, (cap + kScanTile - 1) / kScanTile * kScanTile, true)) != NUPS_OK) return st;   // whole tiles
         if ((st = grow_u32(&a.seg, cap + 1, false)) != NUPS_OK) return st;
         if ((st = grow_u32(&a.chunk_seg, max_chunks(cap), false)) != NUPS_OK) return st;
@@ -111,6 +115,7 @@ size_t side_lds_bytes(const SideItem &it)
 {
     if (it.phase == kSideRank) return rank_lds_bytes((int)it.plan[0].rank_items);
     if (it.phase == kSideSlot) return kSlotLdsBytes;
+    if (it.phase == kSideSort) return sizeof(uint32_t) * kBlock;
     if (it.phase == kSideDraw && it.draw.scheme == NUPS_BOUNDED) return kDrawLdsBytes;
     return 0;
 }
@@ -164,7 +169,10 @@ void build_phases(nups_prepared &p, const SampleArgs &draw, int mark_plan)
     if (need_count_tiles) add(kSideCountTiles, max_ctiles, 0);
     add(kSideCounts, max_ctiles, 0);
     add(kSideScatter, std::max(1u, (max_n + kBlock - 1) / kBlock), 0);
-    if (p.plan[0].a.deterministic) add(kSideSort, std::max(1u, (max_n + kBlock - 1) / kBlock), 0);
+    if (p.plan[0].a.deterministic) {
+        add(kSideSort, std::max(1u, (max_n + kBlock - 1) / kBlock), 0);
+        add(kSideMerge, std::max(1u, (max_n + kBlock - 1) / kBlock), 0);
+    }
 }
 
 }  // namespace nups

@@ -439,24 +439,66 @@ __device__ __forceinline__ void scatter_block(const PlanArgs &a, uint32_t vb)
     }
 }
 
-// Deterministic mode: every segment's accesses once more, in ascending order.  The position of an access is the
-// number of smaller access numbers in its segment, counted by its own thread (quadratic in the segment length, and
-// free of any dependence on the order in which the rank phase's atomics were served).
-__device__ __forceinline__ void sort_block(const PlanArgs &a, uint32_t vb)
+// Deterministic mode: every segment's accesses once more, in ascending order, free of any dependence on the order
+// in which the rank phase's atomics were served.  Two phases over blocks of kBlock consecutive positions of perm.
+// First: the piece of each segment that lies inside the block, sorted by counting, for every access, the smaller
+// access numbers of its piece (from LDS).  A position that is not consistent with the structure (possible only if
+// a key array was changed behind a prepared step) keeps what it holds.
+__device__ __forceinline__ void sort_pieces_block(const PlanArgs &a, uint32_t vb, uint32_t *held)
 {
-    const uint32_t i = vb * kBlock + threadIdx.x;
-    if (i >= a.n) return;
-    const uint32_t u = a.slot[i];
-    if (u == kBadIndex) return;
-    const uint32_t first = a.seg[u], last = min(a.seg[u + 1], a.n);
-    uint32_t below = 0;
-    for (uint32_t t = first; t < last; ++t) below += a.perm[t] < i ? 1u : 0u;
-    if (first + below < a.n) {   // in range by construction with unchanged key arrays
-        a.perm_sorted[first + below] = i;
-        a.pos[i] = first + below;
-    } else {
-        a.pos[i] = kBadIndex;
+    const uint32_t total = min(a.meta[kMetaTotal], a.n);
+    const uint32_t block0 = vb * kBlock, t = block0 + threadIdx.x;
+    uint32_t v = kBadIndex, first = 0, last = 0;
+    bool placed = false;
+    if (t < total) {
+        v = a.perm[t];
+        const uint32_t u = v < a.n ? a.slot[v] : kBadIndex;
+        if (u != kBadIndex && u < a.meta[kMetaNumUniq]) {
+            first = a.seg[u];
+            last = min(a.seg[u + 1], total);
+            placed = first <= t && t < last;
+        }
     }
+    held[threadIdx.x] = v;
+    __syncthreads();
+    if (t >= total) return;
+    if (!placed) { a.perm_pieces[t] = v < a.n ? v : 0u; return; }
+    const uint32_t lo = max(first, block0) - block0, hi = min(last, block0 + kBlock) - block0;
+    uint32_t below = 0;
+    for (uint32_t j = lo; j < hi; ++j) below += held[j] < v ? 1u : 0u;
+    a.perm_pieces[block0 + lo + below] = v;
+}
+
+// Second: the position of an access in its segment is its position in its own piece plus, for every other piece
+// of the segment, the number of smaller access numbers there (a binary search: the pieces are sorted).  Most
+// segments have one piece and end here with their first phase's result.
+__device__ __forceinline__ void merge_pieces_block(const PlanArgs &a, uint32_t vb)
+{
+    const uint32_t total = min(a.meta[kMetaTotal], a.n);
+    const uint32_t block0 = vb * kBlock, t = block0 + threadIdx.x;
+    if (t >= total) return;
+    const uint32_t v = a.perm_pieces[t];       // below a.n by the first phase
+    const uint32_t u = a.slot[v];
+    uint32_t first = 0, last = 0;
+    if (u != kBadIndex && u < a.meta[kMetaNumUniq]) {
+        first = a.seg[u];
+        last = min(a.seg[u + 1], total);
+    }
+    if (!(first <= t && t < last)) { a.perm_sorted[t] = v; return; }
+    uint32_t below = t - max(first, block0);
+    for (uint32_t q = first / kBlock; q <= (last - 1) / kBlock; ++q) {
+        if (q == vb) continue;
+        const uint32_t lo = max(first, q * kBlock);
+        uint32_t l = lo, h = min(last, q * kBlock + kBlock);
+        while (l < h) {
+            const uint32_t m = (l + h) >> 1;
+            if (a.perm_pieces[m] < v) l = m + 1;
+            else h = m;
+        }
+        below += l - lo;
+    }
+    a.perm_sorted[first + below] = v;
+    a.pos[v] = first + below;
 }
 
 // ---- dispatch ------------------------------------------------------------------------------------------------------
@@ -487,7 +529,8 @@ __device__ __forceinline__ void side_item_unit(const SideItem &it, uint32_t vb)
     case kSideCountTiles: count_tiles_block(a, vb, side_lds); break;
     case kSideCounts: counts_block(a, vb, side_lds); break;
     case kSideScatter: scatter_block(a, vb); break;
-    case kSideSort: sort_block(a, vb); break;
+    case kSideSort: sort_pieces_block(a, vb, side_dyn); break;
+    case kSideMerge: merge_pieces_block(a, vb); break;
     default: break;
     }
 }

@@ -181,9 +181,13 @@ struct RowSpace {
     float *replica_rows;
     ReplicaMap rep;          // rep.base_keys: keys of the table
     __device__ __forceinline__ uint32_t keys() const { return rep.base_keys; }
+    // kReplicas false: the caller knows that neither table of the step has replicas (a kernel compiled for that
+    // case carries none of the look-ups)
+    template <bool kReplicas = true>
     __device__ __forceinline__ float *row(uint32_t key, uint32_t example, int stride) const
     {
         const uint32_t valid = min(key, rep.base_keys - 1);   // keys outside the table are flagged by the structure
+        if (!kReplicas) return table + (size_t)valid * stride;
         return extended_row(table, replica_rows, rep.base_keys, replica_key(rep, valid, example), stride);
     }
 };
@@ -201,7 +205,7 @@ static RowSpace row_space(const Table &t, const Plan &pl) { return RowSpace{t.da
 // Otherwise the run's sum is staged at the row of its first pair and the update kernel adds the runs of the word.
 // So a staged gradient row is written per run that shares its word with other runs, not per pair.
 // ------------------------------------------------------------------------------------------------
-template <int NV4, bool kWithLoss>
+template <int NV4, bool kWithLoss, bool kReplicas>
 __global__ void __launch_bounds__(kBlock) k_sgns_grad(RowSpace in_rows, RowSpace out_rows, int stride,
                                                       const uint32_t *center, const uint32_t *context,
                                                       const uint32_t *negs, uint32_t B, int K, float lr,
@@ -225,12 +229,14 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(RowSpace in_rows, RowSpace
         zero_row(z);
         store_row(stage + (size_t)zeros_at * stride, z, lane);
     }
-    const uint32_t crow = sgns_center_row(center, in_rows.rep, e);   // the row (or replica row) of the center word
+    // the row (or replica row) of the center word
+    const uint32_t crow = kReplicas ? sgns_center_row(center, in_rows.rep, e)
+                                    : (center[e] < in_rows.keys() ? center[e] : kBadIndex);
     const uint32_t slot = center_slot[e];          // kBadIndex: the center key is outside the table
     uint32_t seg_len = 0;
     if (slot != kBadIndex) seg_len = center_seg[slot + 1] - center_seg[slot];
     Row<NV4> v, acc;
-    float *v_row = in_rows.row(center[e], e, stride);
+    float *v_row = in_rows.template row<kReplicas>(center[e], e, stride);
     load_row(v, v_row, lane);
     // the first pair of every distinct center word keeps a copy of the input vector for the output-side update
     if (active && slot != kBadIndex && (center_rank[e] & ~kSingleAccess) == 0)
@@ -249,7 +255,7 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(RowSpace in_rows, RowSpace
         for (int jj = 0; jj < JU; ++jj) {
             const int j = min(j0 + jj, K);
             const uint32_t key = (j == 0) ? context[e] : negs[(size_t)e * K + (j - 1)];
-            load_row(u[jj], out_rows.row(key, e, stride), lane);
+            load_row(u[jj], out_rows.template row<kReplicas>(key, e, stride), lane);
         }
         float g_mine = 0.f;   // lane jj of the group keeps coefficient j0 + jj: one store for the JU of them
 #pragma unroll
@@ -307,7 +313,7 @@ static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b, const Plan &in_
     const Table &tin = ctx->tab[0], &tout = ctx->tab[1];
     const uint32_t blocks = xcd_grid((uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock));
     const size_t lds = std::max(sizeof(float) * kGroupsPerBlock * (size_t)tin.stride, side_lds);
-    static size_t allowed = 0, allowed_with_loss = 0;
+    static size_t allowed[4] = {0, 0, 0, 0};
     const auto launch = [&](auto kernel, size_t *granted) {
         allow_lds(kernel, lds, granted);
         hipLaunchKernelGGL(kernel, dim3(sw.blocks + blocks), dim3(kBlock), lds, ctx->stream, row_space(tin, in_plan),
@@ -316,8 +322,11 @@ static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b, const Plan &in_
                            (const uint32_t *)in_plan.a.rank, (const uint32_t *)in_plan.a.seg, center_rows, ctx->loss_cur,
                            sw);
     };
-    if (ctx->want_loss) launch(k_sgns_grad<NV4, true>, &allowed_with_loss);
-    else launch(k_sgns_grad<NV4, false>, &allowed);
+    const bool replicas = in_plan.a.rep.hot_slot != nullptr || out_plan.a.rep.hot_slot != nullptr;
+    if (ctx->want_loss && replicas) launch(k_sgns_grad<NV4, true, true>, &allowed[3]);
+    else if (ctx->want_loss) launch(k_sgns_grad<NV4, true, false>, &allowed[2]);
+    else if (replicas) launch(k_sgns_grad<NV4, false, true>, &allowed[1]);
+    else launch(k_sgns_grad<NV4, false, false>, &allowed[0]);
 }
 
 // Plan side of a step: which keys each table is accessed with (plan 0: table 0, plan 1: table 1).  Sizes the
@@ -863,7 +872,7 @@ constexpr size_t align64(size_t words) { return (words + 63) / 64 * 64; }   // r
 // Offsets (in 32-bit words) of the regions.  The first kStaticZeroWords words are what a build expects to be zero.
 struct StaticLayout {
     size_t bytemap, wordmap, cnt_work, chunk_done, meta, zero_end, bitmap, word_rank, tile_sum, tile_prefix, uniq, count,
-        seg, perm, perm_sorted, slot, pos, rank, chunk_seg, chunk_base, partial, totals, end;
+        seg, perm, perm_sorted, perm_pieces, slot, pos, rank, chunk_seg, chunk_base, partial, totals, end;
 };
 
 constexpr StaticLayout static_layout()
@@ -886,6 +895,7 @@ constexpr StaticLayout static_layout()
     l.seg = take(kStaticPush + 1);
     l.perm = take(kStaticPush);
     l.perm_sorted = take(kStaticPush);
+    l.perm_pieces = take(kStaticPush);
     l.slot = take(kStaticPush);
     l.pos = take(kStaticPush);
     l.rank = take(kStaticPush);
@@ -965,6 +975,7 @@ extern "C" nups_status nups_push_static(nups_ctx *ctx, int table, const uint32_t
     a.seg = base + L.seg;
     a.perm = base + L.perm;
     a.perm_sorted = base + L.perm_sorted;
+    a.perm_pieces = base + L.perm_pieces;
     a.slot = base + L.slot;
     a.pos = base + L.pos;
     a.rank = base + L.rank;
