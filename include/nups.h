@@ -137,7 +137,8 @@ nups_status nups_replica_rows(nups_ctx *ctx, int table, float **rows_dev, int64_
  * open).  By default the accesses of a key are listed in the order in which positions were handed out by
  * atomic operations, so the fp32 sum of a key's contributions can differ in its last bits from run to run and
  * with the declared hot set.  enable != 0: structures built from now on also list every key's accesses in
- * ascending order (one more phase of preparatory work, quadratic in the longest segment), and the update
+ * ascending order (two more phases of preparatory work: the pieces of a segment are sorted in blocks of 256
+ * positions, then merged by binary search; prepare steps four ahead to hide them), and the update
  * kernels add them in a fixed tree over that order (blocks of 16, super-blocks of 256, then in order), whichever
  * technique a key gets: tables are then bit-identical between runs and between hot sets.  The reported loss and
  * the clipping statistics are still accumulated with atomic additions (their last bits may vary).
@@ -333,8 +334,9 @@ nups_status nups_step(nups_ctx *ctx, const nups_batch *batch, double *loss_sum_h
  * nups_prepare_step hands the batch to the library and returns at once, without enqueuing
  * anything: the work that depends only on the batch's keys (drawing the step's own negatives,
  * the per-key aggregation structure) is a chain of six short phases (seven for more than
- * 131,072 accesses to a table), and every gradient or update launch of a step that runs
- * afterwards carries one phase of each of the three oldest prepared steps in spare workgroups.
+ * 131,072 accesses to a table, two more in deterministic mode), and every gradient or update launch
+ * of a step that runs afterwards carries one phase of each of the four oldest prepared steps in spare
+ * workgroups.
  * nups_step_prepared first enqueues, as launches of their own, whatever phases of this step
  * have not been carried yet, then the step's two launches.  So with steps prepared three
  * ahead (prepare t+3, run t) a step costs two launches and its preparatory work hides inside

@@ -148,3 +148,37 @@ def test_complex_steps_refuse_replicas():
         nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_KGE, 1, k, k, k2=k, lr=0.1, eps=1e-10))
     assert e.value.status == nb.NUPS_ERR_UNIMPLEMENTED
     nb.nups_destroy(ctx)
+
+
+def test_fewer_examples_than_replicas_and_deterministic_mode():
+    """Parts that are empty (B < R), and replicas together with the fixed summation order: same bits on a rerun."""
+    V, d, K, lr, R = 300, 64, 2, 0.05, 8
+    In, Out = wl.uniform_table(V, d, -0.5, 0.5, 1), wl.uniform_table(V, d, -0.5, 0.5, 2)
+    hot = np.array([3, 0, 7], dtype=np.uint32)
+    cols = list(range(d))
+    for B in (5, 1, 700):
+        rng = np.random.default_rng(B)
+        c = rng.integers(0, 10, B).astype(np.uint32)
+        o = rng.integers(0, 10, B).astype(np.uint32)
+        negs = rng.integers(0, 12, B * K).astype(np.uint32)
+        got = []
+        for _ in range(2):
+            tin, tout = dev(In), dev(Out)
+            ctx = nb.nups_init([tin, tout], [d, d])
+            nb.nups_set_hot_keys(ctx, 0, hot)
+            nb.nups_set_hot_keys(ctx, 1, hot)
+            nb.nups_set_deterministic(ctx, True)
+            nb.nups_set_replicas(ctx, R)
+            kc, ko, kn = dev_u32(c), dev_u32(o), dev_u32(negs)
+            for _ in range(2):
+                nb.nups_step(ctx, nb.make_batch(nb.NUPS_TASK_SGNS, B, kc, ko, n_neg=K, lr=lr, negs=kn))
+            nb.nups_check(ctx)
+            got.append((_extended(ctx, 0, tin), _extended(ctx, 1, tout)))
+            nb.nups_destroy(ctx)
+        assert np.array_equal(got[0][0], got[1][0]) and np.array_equal(got[0][1], got[1][1])
+        Ie, Oe = rep.extend_table(In, hot, R), rep.extend_table(Out, hot, R)
+        I0, O0 = Ie.copy(), Oe.copy()
+        for _ in range(2):
+            rep.step_sgns_replicated(Ie, Oe, d, c, o, negs, K, lr, V, V, hot, hot, R)
+        assert_table(got[0][0], Ie, I0, cols, 1e-4, "input table and replicas, B = %d" % B, tol_update=1e-4)
+        assert_table(got[0][1], Oe, O0, cols, 1e-4, "output table and replicas, B = %d" % B, tol_update=1e-4)

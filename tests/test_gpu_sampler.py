@@ -305,3 +305,25 @@ def test_partial_pulls_of_handles_between_prepared_steps_that_draw_in_running_la
     nb.nups_release_sample(h1)
     nb.nups_release_sample(h2)
     nb.nups_destroy(ctx)
+
+
+def test_postponing_follows_the_hot_set_of_the_moment_and_takes_an_empty_handle():
+    V = 2000
+    ctx, _ = _ctx(V, d=20)
+    w = wl.expected_unigram_weights(V, 1.0, 1e6)
+    dist = nb.nups_register_distribution(ctx, 0, w, nb.NUPS_LONGTERM, P=5000, R=3, seed=8)
+    nb.nups_set_postponing(dist, True)
+    table = orc.alias_build(w)
+    cursor = 0
+    for hot, n in ((np.arange(0, dtype=np.uint32), 700), (np.arange(50, dtype=np.uint32), 0),
+                   (np.arange(50, dtype=np.uint32), 3000), (np.array([5, 1999, 17], dtype=np.uint32), 3000),
+                   (np.arange(V, dtype=np.uint32), 900)):
+        nb.nups_set_hot_keys(ctx, 0, hot)
+        h = nb.nups_prepare_sample(dist, n, 0)
+        got = _keys_of(h, n)
+        nb.nups_release_sample(h)
+        assert np.array_equal(got, orc.sample_longterm_postponed(table, V, 8, 0, 5000, 3, cursor, n, hot))
+        if len(hot) == V:                                   # every key resident: the pool's own sequence
+            assert np.array_equal(got, orc.sample_longterm(table, V, 8, 0, 5000, 3, cursor, n))
+        cursor += n
+    nb.nups_destroy(ctx)
