@@ -397,6 +397,11 @@ def recorded_traffic(workload, kernel):
     return None
 
 
+def progress(text):
+    """One line on stderr per finished part of the run (the JSON line on stdout stays the only output there)."""
+    print("bench: " + text, file=sys.stderr, flush=True)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -451,6 +456,7 @@ def main() -> int:
     total_steps = w.setup(nb, wl, args.warmup + args.steps + n_windows * window)
     steps = args.steps
     assert total_steps >= args.warmup + steps, "not enough examples for the requested steps"
+    progress("workload %s set up (%d steps of input resident)" % (args.workload, total_steps))
     n_windows = min(n_windows, (total_steps - args.warmup - steps) // window)
     ctx, B = w.ctx, w.B
     if args.deterministic:
@@ -508,6 +514,7 @@ def main() -> int:
     nb.nups_check(ctx)
     finite = all(bool(torch.isfinite(t).all().item()) for t in w.tables)
     total_steps = args.warmup + steps + n_windows * window
+    progress("timed region done: %.4f ms per step over %d steps, %d further windows" % (ms_per_step, steps, n_windows))
 
     # ---- per-kernel pass: the last steps again, unpipelined, HIP events around every phase on its stream ---
     n_prof = min(steps, 64)
@@ -533,6 +540,7 @@ def main() -> int:
         if n:
             phases[nb.nups_phase_name(p)] = ms / n_prof
     nb.nups_profile(ctx, False)
+    progress("per-kernel pass done (%d unpipelined steps)" % n_prof)
 
     # a plain copy of known size through the library's own gather kernel (rows 0..n-1 in order): the
     # reference that hardware byte counters are scaled with
@@ -582,11 +590,17 @@ def main() -> int:
     if args.cpu_steps != 0:
         from oracle import oracle as orc
         n_cpu = args.cpu_steps if args.cpu_steps > 0 else 10 ** 9
+        progress("oracle: copying the initial tables to the host")
         w.oracle_step(orc, 0)                                # first call also builds tables / alias table
+        progress("oracle: first step done, timing further steps")
         done, t_cpu = 1, time.perf_counter()
+        t_said = t_cpu
         while done < min(n_cpu + 1, total_steps):
             w.oracle_step(orc, done)
             done += 1
+            if time.perf_counter() - t_said > 30.0:
+                t_said = time.perf_counter()
+                progress("oracle: %d steps timed" % (done - 1))
             if args.cpu_steps < 0 and time.perf_counter() - t_cpu > 15.0:
                 break
         dt = time.perf_counter() - t_cpu

@@ -23,8 +23,14 @@ namespace nups {
 
 // ---- contribution sources: access i -> (coefficient, source row) ---------------------------
 
+// An access that contributes nothing to its key's sum has this source row number (sources whose kSkips is true may
+// return it from fetch): its row is neither read nor added.  Leaving a term of zero out of a sum that starts at +0
+// changes no bit of the result.
+constexpr uint32_t kNoRow = 0xFFFFFFFFu;
+
 // Row i of a staging array, coefficient one (SGNS input side, MF, KGE subject/object/relation, push).
 struct SrcStaged {
+    static constexpr bool kSkips = false;   // every access contributes a row
     const float *stage;
     bool singles_done = false;   // the gradient kernel has updated the keys with a single access itself
     __device__ __forceinline__ bool done_already(uint32_t) const { return singles_done; }
@@ -47,8 +53,9 @@ struct SrcStaged {
 // SGNS input side: access i is pair i, its key the pair's center word.  The gradient kernel has added up the
 // input-side gradients of each run of pairs with the same center word inside one of its workgroups (kGroupsPerBlock
 // consecutive pairs) and staged the sum at the row of the run's first pair; the other pairs of a run contribute
-// nothing more and point at a row of zeros.  A center word whose pairs are all in one run was updated by the
-// gradient kernel itself (runs_done), which had the sum and the row in registers.
+// nothing more (kNoRow).  A center word whose pairs are all in one run was updated by the
+// gradient kernel itself (runs_done), which had the sum and the row in registers.  Nine of ten accesses of this
+// source are pairs inside a run: the update kernel's L1 traffic, which bounds it, is spared their rows.
 // The row that pair i's center word lives in (its replica for the pair's part of the minibatch if the word is
 // hot and the input table has replicas); kBadIndex for a key outside the table.  Runs are runs of equal rows.
 __device__ __forceinline__ uint32_t sgns_center_row(const uint32_t *center, const ReplicaMap &rep, uint32_t i)
@@ -58,9 +65,9 @@ __device__ __forceinline__ uint32_t sgns_center_row(const uint32_t *center, cons
 }
 
 struct SrcSgnsIn {
-    const float *stage;       // [B] run sums at the rows of the runs' first pairs, [zero_row] all zero
+    static constexpr bool kSkips = true;
+    const float *stage;       // [B] run sums at the rows of the runs' first pairs
     const uint32_t *center;   // [B]
-    uint32_t zero_row;
     bool runs_done;
     ReplicaMap rep;           // of the input table
     __device__ __forceinline__ bool run_head(uint32_t i) const
@@ -80,7 +87,7 @@ struct SrcSgnsIn {
     }
     __device__ __forceinline__ float coef(uint32_t) const { return 1.0f; }
     __device__ __forceinline__ const float *rows() const { return stage; }
-    __device__ __forceinline__ uint32_t row_number(uint32_t i) const { return run_head(i) ? i : zero_row; }
+    __device__ __forceinline__ uint32_t row_number(uint32_t i) const { return run_head(i) ? i : kNoRow; }
     // coefficient and source row number of the access at position t of the plan's access order
     __device__ __forceinline__ void fetch(const uint32_t *perm, uint32_t t, float &c, uint32_t &r) const
     {
@@ -97,6 +104,7 @@ struct SrcSgnsIn {
 // access order (it knows the positions from the structure), so the update reads them in order, with no look-up
 // through the access numbers in between.
 struct SrcSgnsOut {
+    static constexpr bool kSkips = false;
     const float *center_rows;   // [distinct centers][stride]
     const float *coef_at;       // [accesses] in the plan's access order
     const uint32_t *row_at;     // [accesses] row of center_rows (the center word's index among the distinct ones)
@@ -114,6 +122,7 @@ struct SrcSgnsOut {
 // triple: rows 2B.. for replaced subjects, rows 3B.. for replaced objects).  A negative that is its entity's only
 // access of the step was updated by the gradient kernel.
 struct SrcKgeEntity {
+    static constexpr bool kSkips = false;
     const float *stage;
     const float *coefs;   // [B, nn]
     uint32_t B, nn, nh;
@@ -281,33 +290,60 @@ __host__ __device__ constexpr size_t apply_lds_bytes(int stride) { return sizeof
 template <int NV4>
 constexpr int kRowsInFlight = NV4 >= 5 ? 2 : 4;
 
+// Does the access in lane kLane of the group (source row number r there) take part in a block of m accesses?
+template <int kLane, bool kSkips>
+__device__ __forceinline__ bool takes_part(uint32_t r, uint32_t m)
+{
+    if constexpr (kLane >= kGroup) {
+        return false;
+    } else {
+        if ((uint32_t)kLane >= m) return false;
+        return !kSkips || group_share<kLane>(r) != kNoRow;
+    }
+}
+
+template <int NV4, int kLane>
+__device__ __forceinline__ void load_shared_row(Row<NV4> &x, const float *rows, uint32_t r, int stride, int lane)
+{
+    if constexpr (kLane < kGroup) load_row(x, rows + (size_t)group_share<kLane>(r) * stride, lane);
+}
+
+template <int NV4, int kLane>
+__device__ __forceinline__ void add_shared_row(Row<NV4> &acc, float c, const Row<NV4> &x)
+{
+    if constexpr (kLane < kGroup) axpy_row(acc, group_share<kLane>(c), x);
+}
+
 // kRows accesses of a block of sixteen: their coefficients and source row numbers sit in lanes kFirst .. kFirst +
 // kRows - 1 of the group (c, r); m = accesses in the block, kFirst < m.  The rows are requested together and added
 // in order.
-template <int NV4, int kFirst, int kRows>
+template <int NV4, int kFirst, int kRows, bool kSkips>
 __device__ __forceinline__ void sum_rows(Row<NV4> &acc, const float *rows, uint32_t r, float c, uint32_t m, int stride,
                                          int lane)
 {
+    static_assert(kRows >= 1 && kRows <= 4, "one to four rows in flight");
     Row<NV4> x[kRows];
-    load_row(x[0], rows + (size_t)group_share<kFirst>(r) * stride, lane);
-    if constexpr (kRows > 1) if (kFirst + 1 < m) load_row(x[1], rows + (size_t)group_share<kFirst + 1>(r) * stride, lane);
-    if constexpr (kRows > 2) if (kFirst + 2 < m) load_row(x[2], rows + (size_t)group_share<kFirst + 2>(r) * stride, lane);
-    if constexpr (kRows > 3) if (kFirst + 3 < m) load_row(x[3], rows + (size_t)group_share<kFirst + 3>(r) * stride, lane);
-    axpy_row(acc, group_share<kFirst>(c), x[0]);
-    if constexpr (kRows > 1) if (kFirst + 1 < m) axpy_row(acc, group_share<kFirst + 1>(c), x[1]);
-    if constexpr (kRows > 2) if (kFirst + 2 < m) axpy_row(acc, group_share<kFirst + 2>(c), x[2]);
-    if constexpr (kRows > 3) if (kFirst + 3 < m) axpy_row(acc, group_share<kFirst + 3>(c), x[3]);
+    const bool on0 = takes_part<kFirst, kSkips>(r, m), on1 = kRows > 1 && takes_part<kFirst + 1, kSkips>(r, m),
+               on2 = kRows > 2 && takes_part<kFirst + 2, kSkips>(r, m), on3 = kRows > 3 && takes_part<kFirst + 3, kSkips>(r, m);
+    if (on0) load_shared_row<NV4, kFirst>(x[0], rows, r, stride, lane);
+    if constexpr (kRows > 1) if (on1) load_shared_row<NV4, kFirst + 1>(x[1], rows, r, stride, lane);
+    if constexpr (kRows > 2) if (on2) load_shared_row<NV4, kFirst + 2>(x[2], rows, r, stride, lane);
+    if constexpr (kRows > 3) if (on3) load_shared_row<NV4, kFirst + 3>(x[3], rows, r, stride, lane);
+    if (on0) add_shared_row<NV4, kFirst>(acc, c, x[0]);
+    if constexpr (kRows > 1) if (on1) add_shared_row<NV4, kFirst + 1>(acc, c, x[1]);
+    if constexpr (kRows > 2) if (on2) add_shared_row<NV4, kFirst + 2>(acc, c, x[2]);
+    if constexpr (kRows > 3) if (on3) add_shared_row<NV4, kFirst + 3>(acc, c, x[3]);
 }
 
-template <int NV4, int kFirst, int kMost>
+template <int NV4, int kFirst, int kMost, bool kSkips>
 __device__ __forceinline__ void sum_rows_from(Row<NV4> &acc, const float *rows, uint32_t r, float c, uint32_t m,
                                               int stride, int lane)
 {
     constexpr int kRows = kRowsInFlight<NV4>;
     if constexpr (kFirst < kMost) {
         if (kFirst == 0 || (uint32_t)kFirst < m) {
-            sum_rows<NV4, kFirst, kRows>(acc, rows, r, c, m, stride, lane);
-            sum_rows_from<NV4, kFirst + kRows, kMost>(acc, rows, r, c, m, stride, lane);
+            sum_rows<NV4, kFirst, kRows, kSkips>(acc, rows, r, c, m, stride, lane);
+            sum_rows_from<NV4, kFirst + kRows, kMost, kSkips>(acc, rows, r, c, m, stride, lane);
         }
     }
 }
@@ -326,7 +362,7 @@ __device__ __forceinline__ void sum_block(Row<NV4> &acc, const Src &src, const u
     uint32_t r = 0;
     float c = 0.0f;
     if ((uint32_t)lane < m) src.fetch(perm, t0 + (uint32_t)lane, c, r);
-    sum_rows_from<NV4, 0, (int)kMost>(acc, rows, r, c, m, stride, lane);
+    sum_rows_from<NV4, 0, (int)kMost, Src::kSkips>(acc, rows, r, c, m, stride, lane);
 }
 
 // row <- x if `first`, else row + x (LDS or global memory); each lane touches its own words only, so neither a

@@ -210,7 +210,7 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(RowSpace in_rows, RowSpace
                                                       const uint32_t *center, const uint32_t *context,
                                                       const uint32_t *negs, uint32_t B, int K, float lr,
                                                       const uint32_t *out_pos, float *coef_at, uint32_t *row_at,
-                                                      float *stage, uint32_t zeros_at, int update_whole_runs,
+                                                      float *stage, int update_whole_runs,
                                                       const uint32_t *center_slot, const uint32_t *center_rank,
                                                       const uint32_t *center_seg, float *center_rows, double *loss,
                                                       SideWork sw)
@@ -224,11 +224,6 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(RowSpace in_rows, RowSpace
     const uint32_t e_raw = (xcd_block(own_block, gridDim.x - sw.blocks) * kBlock + threadIdx.x) / kGroup;
     const bool active = e_raw < B;
     const uint32_t e = active ? e_raw : B - 1;
-    if (own_block == 0 && group == kGroupsPerBlock - 1) {   // the row of zeros that pairs inside a run point at
-        Row<NV4> z;
-        zero_row(z);
-        store_row(stage + (size_t)zeros_at * stride, z, lane);
-    }
     // the row (or replica row) of the center word
     const uint32_t crow = kReplicas ? sgns_center_row(center, in_rows.rep, e)
                                     : (center[e] < in_rows.keys() ? center[e] : kBadIndex);
@@ -307,7 +302,7 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(RowSpace in_rows, RowSpace
 
 template <int NV4>
 static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b, const Plan &in_plan, const Plan &out_plan,
-                             float *center_rows, uint32_t *row_at, uint32_t zero_row, bool update_whole_runs,
+                             float *center_rows, uint32_t *row_at, bool update_whole_runs,
                              const SideWork &sw, size_t side_lds)
 {
     const Table &tin = ctx->tab[0], &tout = ctx->tab[1];
@@ -318,7 +313,7 @@ static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b, const Plan &in_
         allow_lds(kernel, lds, granted);
         hipLaunchKernelGGL(kernel, dim3(sw.blocks + blocks), dim3(kBlock), lds, ctx->stream, row_space(tin, in_plan),
                            row_space(tout, out_plan), tin.stride, b.k0, b.k1, b.negs, (uint32_t)b.B, (int)b.n_neg, b.lr, (const uint32_t *)out_plan.a.pos, ctx->coef,
-                           row_at, ctx->stage, zero_row, update_whole_runs ? 1 : 0, (const uint32_t *)in_plan.a.slot,
+                           row_at, ctx->stage, update_whole_runs ? 1 : 0, (const uint32_t *)in_plan.a.slot,
                            (const uint32_t *)in_plan.a.rank, (const uint32_t *)in_plan.a.seg, center_rows, ctx->loss_cur,
                            sw);
     };
@@ -380,19 +375,18 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
     if ((st = ensure_f32(&ctx->coef, &ctx->coef_cap, (size_t)2 * B * (K + 1), ctx->stream)) != NUPS_OK) return st;
     uint32_t *row_at = reinterpret_cast<uint32_t *>(ctx->coef + (size_t)B * (K + 1));
     // staged rows: [0, B) input-side gradient sums of runs of pairs (at the runs' first pairs), [B, 2B) input
-    // vectors of the distinct center words, row 2B all zero
-    if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, ((size_t)2 * B + 1) * tin.stride, ctx->stream)) != NUPS_OK) return st;
+    // vectors of the distinct center words
+    if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)2 * B * tin.stride, ctx->stream)) != NUPS_OK) return st;
     ctx->loss_cur = p.loss_dev;   // zeroed by the step's plan construction
     if (B == 0) return NUPS_OK;
     float *center_rows = ctx->stage + (size_t)B * tin.stride;
-    const uint32_t zero_row = 2 * B;
     // With norm clipping on, every update goes through the update kernel, which measures and clips the hot keys'.
     const bool update_whole_runs = !(ctx->clip_factor > 0.0f);
     size_t side_lds = 0;
     {
         const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
-#define CALL(N) launch_sgns_grad<N>(ctx, b, p.plan[0], p.plan[1], center_rows, row_at, zero_row, update_whole_runs, sw, side_lds)
+#define CALL(N) launch_sgns_grad<N>(ctx, b, p.plan[0], p.plan[1], center_rows, row_at, update_whole_runs, sw, side_lds)
         NUPS_FOR_EACH_ROW_WIDTH(tin.stride, CALL)
 #undef CALL
         NUPS_HIP(hipGetLastError());
@@ -402,7 +396,7 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
         PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
         if ((st = refresh_clip_bounds(ctx)) != NUPS_OK) return st;
         const TableUpdate<SrcSgnsIn, OptSgd> uin{&p.plan[0], partial_of(ctx, p, 0), tin.data, nullptr,
-                                                 SrcSgnsIn{ctx->stage, b.k0, zero_row, update_whole_runs, p.plan[0].a.rep},
+                                                 SrcSgnsIn{ctx->stage, b.k0, update_whole_runs, p.plan[0].a.rep},
                                                  sgd_rule(ctx, 0, b.lr), tin.replica_rows};
         const TableUpdate<SrcSgnsOut, OptSgd> uout{&p.plan[1], partial_of(ctx, p, 1), tout.data, nullptr,
                                                    SrcSgnsOut{center_rows, ctx->coef, row_at}, sgd_rule(ctx, 1, b.lr),
