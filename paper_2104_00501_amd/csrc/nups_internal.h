@@ -109,8 +109,8 @@ struct PlanArgs {
     uint32_t *slot;        // [n]         per access: index of its key among the distinct keys
     uint32_t *pos;         // [n]         per access: where it stands in perm (perm_sorted in deterministic mode)
     uint32_t *rank;        // [n]         per access: position inside its key's segment (| kSingleAccess)
-    uint32_t *chunk_seg;   // [max_chunks]  distinct-key index of the long segment a chunk belongs to
-    uint32_t *chunk_base;  // [max_chunks]  number of the first chunk of that segment
+    uint4 *chunk_of;       // [max_chunks]  per chunk of a long segment: {distinct-key index of the segment, number of the
+                           //               segment's first chunk, first position of the segment, position after its last}
     uint32_t *chunk_done;  // [max_chunks]  arrival counter per long segment (at its first chunk), zero between steps
     uint32_t *meta;        // [kMetaWords]
     uint32_t *error_flag;  // shared by the context: bit 0 = key out of range

@@ -41,7 +41,7 @@ nups_status ensure_totals(nups_ctx *ctx, int stride)
 void free_plan_arrays(Plan &pl)
 {
     PlanArgs &a = pl.a;
-    for (uint32_t *p : {a.uniq, a.count, a.seg, a.perm, a.perm_sorted, a.perm_pieces, a.slot, a.pos, a.rank, a.chunk_seg, a.chunk_base, a.chunk_done, a.meta,
+    for (uint32_t *p : {a.uniq, a.count, a.seg, a.perm, a.perm_sorted, a.perm_pieces, a.slot, a.pos, a.rank, (uint32_t *)a.chunk_of, a.chunk_done, a.meta,
                         a.bitmap, a.word_rank, a.tile_sum, a.tile_prefix, a.cnt_work})
         if (p) (void)hipFree(p);
     if (a.bytemap) (void)hipFree(a.bytemap);
@@ -75,8 +75,7 @@ nups_status ensure_plan_capacity(nups_ctx *ctx, Table &t, Plan &pl, size_t n)
             if ((st = grow_u32(b, cap, true)) != NUPS_OK) return st;
         if ((st = grow_u32(&a.cnt_work, (cap + kScanTile - 1) / kScanTile * kScanTile, true)) != NUPS_OK) return st;   // whole tiles
         if ((st = grow_u32(&a.seg, cap + 1, false)) != NUPS_OK) return st;
-        if ((st = grow_u32(&a.chunk_seg, max_chunks(cap), false)) != NUPS_OK) return st;
-        if ((st = grow_u32(&a.chunk_base, max_chunks(cap), false)) != NUPS_OK) return st;
+        if ((st = grow_u32((uint32_t **)&a.chunk_of, 4 * max_chunks(cap), false)) != NUPS_OK) return st;
         if ((st = grow_u32(&a.chunk_done, max_chunks(cap), true)) != NUPS_OK) return st;
         if ((st = grow_u32(&a.meta, kMetaWords, true)) != NUPS_OK) return st;
         pl.cap_n = cap;

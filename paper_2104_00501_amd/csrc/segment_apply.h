@@ -266,7 +266,8 @@ struct ApplyArgs {
     float *table;
     float *state;
     const uint32_t *hot_bits; // the table's declared hot-key set or null (see takes_hot_path)
-    const uint32_t *uniq, *seg, *perm, *meta, *chunk_seg, *chunk_base;
+    const uint32_t *uniq, *seg, *perm, *meta;
+    const uint4 *chunk_of; // per chunk: {segment, the segment's first chunk, the segment's first position, its end}
     uint32_t *chunk_done;
     float *partial;        // [max_chunks][stride] partial sums of chunked segments
     int stride;
@@ -486,10 +487,10 @@ __device__ __forceinline__ uint32_t count_chunk_in(uint32_t *counter)
 // workgroup must call it with the same `id`.
 template <int NV4, class Src, class Opt>
 __device__ __forceinline__ void apply_chunk_item(const ApplyArgs &a, const Src &src, const Opt &opt, uint32_t id,
-                                                 float *part, uint32_t *last_arrival, int lane, int group)
+                                                 const uint4 chunk, float *part, uint32_t *last_arrival, int lane,
+                                                 int group)
 {
-    const uint32_t u = a.chunk_seg[id], base = a.chunk_base[id];
-    const uint32_t first = a.seg[u], last = a.seg[u + 1];
+    const uint32_t u = chunk.x, base = chunk.y, first = chunk.z, last = chunk.w;   // chunk = a.chunk_of[id]
     const uint32_t nch = (last - first + kChunk - 1) / kChunk;
     const uint32_t cf = first + (id - base) * kChunk, cl = min(cf + kChunk, last);
     const uint32_t blocks = (cl - cf + kTreeBlock - 1) / kTreeBlock;     // non-empty blocks of this chunk
@@ -583,7 +584,7 @@ __global__ void __launch_bounds__(kBlock) k_apply(ApplyArgs a, Src src, Opt opt)
     const ApplyShape sh = apply_shape(a);
     const uint32_t items = sh.chunk_items + sh.short_items;
     for (uint32_t item = blockIdx.x; item < items; item += gridDim.x) {
-        if (item < sh.chunk_items) apply_chunk_item<NV4>(a, src, opt, item, part, &last_arrival, lane, group);
+        if (item < sh.chunk_items) apply_chunk_item<NV4>(a, src, opt, item, a.chunk_of[item], part, &last_arrival, lane, group);
         else apply_short_item<NV4>(a, src, opt, sh, item - sh.chunk_items, part, blockIdx.x, lane, group);
     }
 }
@@ -606,12 +607,17 @@ __global__ void __launch_bounds__(kBlock, kApply2WavesPerSimd<NV4>) k_apply2(App
     if (side_work_block(sw)) return;
     const uint32_t first_item = blockIdx.x - sw.blocks, item_step = gridDim.x - sw.blocks;
     const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
+    // The first items are the chunks of the first table, the longest of the launch: a workgroup asks for the chunk
+    // that its number stands for together with the item counts (one dependent read fewer in front of the rows; the
+    // entry is inside the array whatever it holds, and is used only if the counts confirm it).
+    uint4 own_chunk = make_uint4(0u, 0u, 0u, 0u);
+    if (first_item < a0.max_chunks) own_chunk = a0.chunk_of[first_item];
     const ApplyShape s0 = apply_shape(a0), s1 = apply_shape(a1);
     const uint32_t e0 = s0.chunk_items, e1 = e0 + s1.chunk_items, e2 = e1 + s0.short_items,
                    e3 = e2 + s1.short_items;
     for (uint32_t item = first_item; item < e3; item += item_step) {
-        if (item < e0) apply_chunk_item<NV4>(a0, src0, opt0, item, part, &last_arrival, lane, group);
-        else if (item < e1) apply_chunk_item<NV4>(a1, src1, opt1, item - e0, part, &last_arrival, lane, group);
+        if (item < e0) apply_chunk_item<NV4>(a0, src0, opt0, item, item == first_item ? own_chunk : a0.chunk_of[item], part, &last_arrival, lane, group);
+        else if (item < e1) apply_chunk_item<NV4>(a1, src1, opt1, item - e0, a1.chunk_of[item - e0], part, &last_arrival, lane, group);
         else if (item < e2) apply_short_item<NV4>(a0, src0, opt0, s0, item - e1, part, first_item, lane, group);
         else apply_short_item<NV4>(a1, src1, opt1, s1, item - e2, part, first_item, lane, group);
     }
@@ -637,7 +643,7 @@ static inline ApplyArgs make_apply_args(const Plan &pl, float *partial, float *t
 {
     const PlanArgs &p = pl.a;
     return ApplyArgs{table, state, p.hot_bits, p.uniq, p.seg, p.deterministic ? p.perm_sorted : p.perm, p.meta,
-                     p.chunk_seg, p.chunk_base, p.chunk_done, partial, stride, p.n, p.max_chunks, p.deterministic,
+                     p.chunk_of, p.chunk_done, partial, stride, p.n, p.max_chunks, p.deterministic,
                      replica_rows, p.rep.base_keys, totals};
 }
 

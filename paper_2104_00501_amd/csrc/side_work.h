@@ -405,8 +405,7 @@ __device__ __forceinline__ void counts_block(const PlanArgs &a, uint32_t vb, uin
             a.seg[u0 + j] = run;
             a.count[u0 + j] = cnt[j];
             for (uint32_t ch = 0; ch < nch[j] && chunk + ch < a.max_chunks; ++ch) {   // in range by construction
-                a.chunk_seg[chunk + ch] = u0 + j;
-                a.chunk_base[chunk + ch] = chunk;
+                a.chunk_of[chunk + ch] = make_uint4(u0 + j, chunk, run, run + cnt[j]);
             }
             chunk += nch[j];
         }

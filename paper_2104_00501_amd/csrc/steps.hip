@@ -68,8 +68,10 @@ nups_status flush_side_work(nups_ctx *ctx, nups_prepared *p)
     if (p->next_phase >= p->phases.size()) return NUPS_OK;
     nups_status st = NUPS_OK;
     const SideItem &first = p->phases[p->next_phase];
-    const bool draws = first.phase == kSideDraw && first.draw.blocks > 0;
-    if (draws) {   // the drawing is timed as a phase of its own, apart from the marking that shares its launch
+    // when phases are timed, the drawing is a launch (and a timed phase) of its own, apart from the marking that
+    // otherwise shares its launch
+    const bool draws = ctx->profiling && first.phase == kSideDraw && first.draw.blocks > 0;
+    if (draws) {
         SideItem draw = first;
         draw.blocks = first.draw.blocks;
         PhaseScope scope(ctx, NUPS_PHASE_SAMPLE, ctx->stream);
@@ -866,7 +868,7 @@ constexpr size_t align64(size_t words) { return (words + 63) / 64 * 64; }   // r
 // Offsets (in 32-bit words) of the regions.  The first kStaticZeroWords words are what a build expects to be zero.
 struct StaticLayout {
     size_t bytemap, wordmap, cnt_work, chunk_done, meta, zero_end, bitmap, word_rank, tile_sum, tile_prefix, uniq, count,
-        seg, perm, perm_sorted, perm_pieces, slot, pos, rank, chunk_seg, chunk_base, partial, totals, end;
+        seg, perm, perm_sorted, perm_pieces, slot, pos, rank, chunk_of, partial, totals, end;
 };
 
 constexpr StaticLayout static_layout()
@@ -893,8 +895,7 @@ constexpr StaticLayout static_layout()
     l.slot = take(kStaticPush);
     l.pos = take(kStaticPush);
     l.rank = take(kStaticPush);
-    l.chunk_seg = take(kStaticChunks);
-    l.chunk_base = take(kStaticChunks);
+    l.chunk_of = take(4 * kStaticChunks);
     l.partial = take(kStaticChunks * (size_t)kMaxStride);
     l.totals = take((size_t)kStaticGrid * kGroupsPerBlock * kMaxStride);
     l.end = at;
@@ -973,8 +974,7 @@ extern "C" nups_status nups_push_static(nups_ctx *ctx, int table, const uint32_t
     a.slot = base + L.slot;
     a.pos = base + L.pos;
     a.rank = base + L.rank;
-    a.chunk_seg = base + L.chunk_seg;
-    a.chunk_base = base + L.chunk_base;
+    a.chunk_of = reinterpret_cast<uint4 *>(base + L.chunk_of);   // regions start on 256-byte boundaries
     pl.cap_n = kStaticPush;
     pl.cap_words = kStaticWordsOfMap;
     pl.cap_tiles = kStaticTiles;

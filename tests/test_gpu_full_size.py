@@ -16,35 +16,47 @@ pytestmark = pytest.mark.gpu
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
+def _say(line):
+    """A line for whoever watches the run: on stdout and, where output capture would hold it back, in a file."""
+    print(line, flush=True)
+    try:
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "full_size_progress.txt"), "a") as f:
+            f.write(line + "\n")
+    except OSError:
+        pass
+
+
 def _touched_rows_match(t_dev, init_dev, ref_host, touched, cols, tol, what):
+    """Both metrics are maxima over rows with a floor per row, so the touched rows are compared in blocks (millions
+    of rows of 2 KB would otherwise be held several times over in fp64, silently, for minutes)."""
     import torch
     touched = np.unique(np.asarray(touched, dtype=np.int64))
     changed = (t_dev != init_dev).any(dim=1).nonzero().ravel().cpu().numpy()
     assert np.isin(changed, touched).all(), what + ": a row outside the steps' keys changed"
-    index = torch.from_numpy(touched).cuda()
-    got, before = t_dev[index].cpu().numpy(), init_dev[index].cpu().numpy()
-    ref = ref_host[touched]
-    rel, ab = param_err(got, ref, before, cols)
-    ue = update_err(got, ref, before, cols)
-    print("%s: %d touched rows of %d, %d changed; parameter err %.3g (abs %.3g), update err %.3g"
-          % (what, len(touched), t_dev.shape[0], len(changed), rel, ab, ue))
+    pad = np.setdiff1d(np.arange(t_dev.shape[1]), cols)
+    rel = ab = ue = 0.0
+    block = 131_072
+    for n, lo in enumerate(range(0, len(touched), block)):
+        rows = touched[lo:lo + block]
+        index = torch.from_numpy(rows).cuda()
+        got, before = t_dev[index].cpu().numpy(), init_dev[index].cpu().numpy()
+        ref = ref_host[rows]
+        r, a = param_err(got, ref, before, cols)
+        rel, ab, ue = max(rel, r), max(ab, a), max(ue, update_err(got, ref, before, cols))
+        assert np.all(got[:, pad] == 0), what + ": padding lanes changed"
+        if n % 4 == 3:
+            _say("%s: %d of %d touched rows compared" % (what, lo + len(rows), len(touched)))
+    _say("%s: %d touched rows of %d, %d changed; parameter err %.3g (abs %.3g), update err %.3g"
+         % (what, len(touched), t_dev.shape[0], len(changed), rel, ab, ue))
     assert rel <= tol, "%s: parameter error %.3g (abs %.3g) > %.1g" % (what, rel, ab, tol)
     assert ue <= tol, "%s: error of the total update %.3g > %.1g" % (what, ue, tol)
-    pad = np.setdiff1d(np.arange(got.shape[1]), cols)
-    assert np.all(got[:, pad] == 0), what + ": padding lanes changed"
 
 
 def _progress(what, t, steps):
     """The oracle's 100 full-size steps take minutes on one core: a line now and then shows that the test is alive."""
     if t % 10 == 9 or t == steps - 1:
-        line = "%s: oracle step %d of %d" % (what, t + 1, steps)
-        print(line, flush=True)
-        try:        # also where output capture would hold the line back: a file that a watcher of the run can see grow
-            os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-            with open(os.path.join(ROOT, "gpurun_out", "full_size_progress.txt"), "a") as f:
-                f.write(line + "\n")
-        except OSError:
-            pass
+        _say("%s: oracle step %d of %d" % (what, t + 1, steps))
 
 
 def _run(ctx, batches, depth):
