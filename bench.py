@@ -37,6 +37,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 
 
+def progress(text):
+    """One line on stderr per finished part of the run (the JSON line on stdout stays the only output there)."""
+    print("bench: " + text, file=sys.stderr, flush=True)
+
+
 def dev_keys(x):
     import torch
     return torch.from_numpy(np.ascontiguousarray(x, dtype=np.uint32).view(np.int32)).cuda()
@@ -173,7 +178,9 @@ class Mf:
         B = self.B
         if self.by_column:      # 64 workers, each column by column; the least loaded worker ends the run
             cells = wl.mf_cells(self.n_rows, self.n_cols, self.s, int(2.5 * total_steps * B), self.seed)
+            progress("%d cells generated" % len(cells[0]))
             self.rows, self.cols, self.vals = wl.mf_visit_by_column(*cells, B, self.seed + 3)
+            progress("cells put in the workers' by-column visiting order")
             assert len(self.rows) >= total_steps * B, "not enough cells for the requested steps"
         else:
             self.rows, self.cols, self.vals = wl.mf_cells(self.n_rows, self.n_cols, self.s, total_steps * B, self.seed)
@@ -186,6 +193,7 @@ class Mf:
             return t
 
         self.tables = [table(self.n_rows), table(self.n_cols)]
+        progress("factor tables initialised on the device")
         self.kr, self.kcol = dev_keys(self.rows), dev_keys(self.cols)
         self.kv = torch.from_numpy(self.vals).cuda()
         self.ctx = nb.nups_init(self.tables, [self.d, self.d])
@@ -395,11 +403,6 @@ def recorded_traffic(workload, kernel):
                     and parts[4] == digest:
                 return float(parts[2]) + float(parts[3])
     return None
-
-
-def progress(text):
-    """One line on stderr per finished part of the run (the JSON line on stdout stays the only output there)."""
-    print("bench: " + text, file=sys.stderr, flush=True)
 
 
 def main() -> int:
