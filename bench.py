@@ -215,17 +215,27 @@ class Mf:
         return self.B, self.B
 
     def note_structure(self, t, table, keys, counts):
-        """Rows / columns that the gradient kernel updates itself: those with one access in step t."""
+        """Rows / columns that the gradient kernel updates itself: rows with one access in step t, columns whose
+        cells of step t all stand in one run (consecutive cells inside one block of 16 cells)."""
         if self.clip > 0.0:         # with clipping on every update goes through the update kernel
             return
         self.alone = getattr(self, "alone", [[], []])
-        self.alone[table].append(int((counts == 1).sum()))
+        if table == 0 or self.stride < 256:      # narrow rows: columns are treated like rows (kMfRunsFromNV4)
+            self.alone[table].append(int((counts == 1).sum()))
+            return
+        c = self.cols[t * self.B:(t + 1) * self.B]
+        head = np.ones(len(c), dtype=bool)
+        head[1:] = c[1:] != c[:-1]
+        head[::16] = True
+        run_len = np.diff(np.append(np.flatnonzero(head), len(c)))
+        whole = run_len == counts[np.searchsorted(keys, c[head])]
+        self.alone[1].append(int(whole.sum()))
 
     def algorithmic_bytes(self, nu0, nu1):
         row, B = 4 * self.d, self.B
         a0, a1 = [float(np.mean(x)) if x else 0.0 for x in getattr(self, "alone", [[], []])]
-        # every distinct row read once and written once: written by the gradient kernel if the row has a single
-        # access, by the update kernel (which reads it again) otherwise
+        # every distinct row read once and written once: written by the gradient kernel if it updates the row itself
+        # (note_structure), by the update kernel (which reads it again) otherwise
         return {"grad": (nu0 + nu1) * row + (a0 + a1) * row + 12 * B,
                 "apply0": (nu0 - a0) * row * 2 + 4 * B, "apply1": (nu1 - a1) * row * 2 + 4 * B,
                 "step": (nu0 + nu1) * row * 2 + 12 * B}

@@ -28,9 +28,10 @@ namespace nups {
 // changes no bit of the result.
 constexpr uint32_t kNoRow = 0xFFFFFFFFu;
 
-// Row i of a staging array, coefficient one (SGNS input side, MF, KGE subject/object/relation, push).
+// Row i of a staging array, coefficient one (KGE relations, push).
 struct SrcStaged {
     static constexpr bool kSkips = false;   // every access contributes a row
+    static constexpr bool kDoneInRows = false;
     const float *stage;
     bool singles_done = false;   // the gradient kernel has updated the keys with a single access itself
     __device__ __forceinline__ bool done_already(uint32_t) const { return singles_done; }
@@ -50,50 +51,53 @@ struct SrcStaged {
     }
 };
 
-// SGNS input side: access i is pair i, its key the pair's center word.  The gradient kernel has added up the
-// input-side gradients of each run of pairs with the same center word inside one of its workgroups (kGroupsPerBlock
-// consecutive pairs) and staged the sum at the row of the run's first pair; the other pairs of a run contribute
-// nothing more (kNoRow).  A center word whose pairs are all in one run was updated by the
-// gradient kernel itself (runs_done), which had the sum and the row in registers.  Nine of ten accesses of this
-// source are pairs inside a run: the update kernel's L1 traffic, which bounds it, is spared their rows.
-// The row that pair i's center word lives in (its replica for the pair's part of the minibatch if the word is
-// hot and the input table has replicas); kBadIndex for a key outside the table.  Runs are runs of equal rows.
-__device__ __forceinline__ uint32_t sgns_center_row(const uint32_t *center, const ReplicaMap &rep, uint32_t i)
+// The row that example i's key lives in (its replica for the example's part of the minibatch if the key is hot and
+// the table has replicas); kBadIndex for a key outside the table.  Runs of examples are runs of equal rows.
+__device__ __forceinline__ uint32_t run_row(const uint32_t *keys, const ReplicaMap &rep, uint32_t i)
 {
-    const uint32_t key = center[i];
+    const uint32_t key = keys[i];
     return key < rep.base_keys ? replica_key(rep, key, i) : kBadIndex;
 }
 
-struct SrcSgnsIn {
+// Staged rows whose numbers the gradient kernel has left where the accesses stand in the plan's access order (it
+// knows the positions from the structure), so the update reads them in order, with no look-up through access
+// numbers or keys in between.  An entry is a row of `stage`; kNoRow for an access that contributes nothing more
+// (an example inside a run whose gradients the gradient kernel has added up and staged at the run's first example:
+// SGNS input side, where 2 x window consecutive pairs of a stream share their center word, and the column side of a
+// factorisation whose workers walk their cells column by column); or kRowDone for an access whose key the gradient
+// kernel has updated itself (a key with a single access, or with all its accesses in one run: it had the sum and
+// the row in registers).  Nine of ten SGNS accesses of this source are pairs inside a run: the update kernel's L1
+// traffic, which bounds it, is spared their rows.
+constexpr uint32_t kRowDone = 0xFFFFFFFEu;
+
+struct SrcStagedAt {
     static constexpr bool kSkips = true;
-    const float *stage;       // [B] run sums at the rows of the runs' first pairs
-    const uint32_t *center;   // [B]
-    bool runs_done;
-    ReplicaMap rep;           // of the input table
-    __device__ __forceinline__ bool run_head(uint32_t i) const
+    // Whether a short segment is done shows in the row numbers that its sum fetches anyway: the update of a short
+    // segment fetches them once and asks done_in_rows, instead of segment_done and a second read.
+    static constexpr bool kDoneInRows = true;
+    const float *stage;
+    const uint32_t *row_at;   // [accesses] in the plan's access order
+    bool singles_done;        // the gradient kernel updates keys by itself where it can: a key with one access is then
+                              // done, which its segment's length says without a read
+    // Every lane of the group calls it; r: the row number of the segment's access number `lane` (any value in lanes
+    // beyond the segment's n <= kGroup accesses).  Only a segment of at most kGroupsPerBlock accesses can be done (a
+    // run lies inside one workgroup of the gradient kernel); it is done iff one of its accesses says so.
+    __device__ __forceinline__ bool done_in_rows(uint32_t r, uint32_t n, int lane) const
     {
-        return i % kGroupsPerBlock == 0 || sgns_center_row(center, rep, i - 1) != sgns_center_row(center, rep, i);
+        return group_max(((uint32_t)lane < n && r == kRowDone) ? 1u : 0u) != 0u;
     }
-    // Every lane of the group calls it.  The segment is one run iff its access numbers are consecutive and within
-    // one workgroup of the gradient kernel.
-    __device__ __forceinline__ bool segment_done(const uint32_t *perm, uint32_t first, uint32_t last, int lane) const
+    __device__ __forceinline__ bool segment_done(const uint32_t *, uint32_t first, uint32_t last, int lane) const
     {
         const uint32_t n = last - first;
-        if (!runs_done || n > (uint32_t)kGroupsPerBlock) return false;
-        const bool mine = (uint32_t)lane < n;
-        const uint32_t i = mine ? perm[first + lane] : 0u;
-        const uint32_t lo = group_min(mine ? i : 0xFFFFFFFFu), hi = group_max(i);
-        return hi - lo + 1 == n && lo / kGroupsPerBlock == hi / kGroupsPerBlock;
+        if (n > (uint32_t)kGroupsPerBlock) return false;
+        if (n == 1 && singles_done) return true;
+        return done_in_rows((uint32_t)lane < n ? row_at[first + lane] : 0u, n, lane);
     }
-    __device__ __forceinline__ float coef(uint32_t) const { return 1.0f; }
     __device__ __forceinline__ const float *rows() const { return stage; }
-    __device__ __forceinline__ uint32_t row_number(uint32_t i) const { return run_head(i) ? i : kNoRow; }
-    // coefficient and source row number of the access at position t of the plan's access order
-    __device__ __forceinline__ void fetch(const uint32_t *perm, uint32_t t, float &c, uint32_t &r) const
+    __device__ __forceinline__ void fetch(const uint32_t *, uint32_t t, float &c, uint32_t &r) const
     {
-        const uint32_t i = perm[t];
-        c = coef(i);
-        r = row_number(i);
+        c = 1.0f;
+        r = row_at[t];
     }
 };
 
@@ -105,6 +109,7 @@ struct SrcSgnsIn {
 // through the access numbers in between.
 struct SrcSgnsOut {
     static constexpr bool kSkips = false;
+    static constexpr bool kDoneInRows = false;
     const float *center_rows;   // [distinct centers][stride]
     const float *coef_at;       // [accesses] in the plan's access order
     const uint32_t *row_at;     // [accesses] row of center_rows (the center word's index among the distinct ones)
@@ -123,6 +128,7 @@ struct SrcSgnsOut {
 // access of the step was updated by the gradient kernel.
 struct SrcKgeEntity {
     static constexpr bool kSkips = false;
+    static constexpr bool kDoneInRows = false;
     const float *stage;
     const float *coefs;   // [B, nn]
     uint32_t B, nn, nh;
@@ -287,9 +293,11 @@ __host__ __device__ constexpr size_t apply_lds_bytes(int stride) { return sizeof
 
 // Rows that a group requests together while it sums a block.  More rows in flight hide more latency per group but
 // cost a row of registers each; with rows of 320 floats and more, two in flight keep the update kernels at four
-// wavefronts per SIMD, so that every work item of a step of the large skip-gram configuration is resident at once.
+// wavefronts per SIMD, so that every work item of a step of the large skip-gram configuration is resident at once;
+// rows of 1,024 floats (64 registers each) one at a time: two wavefronts per SIMD instead of one (update kernel of
+// the 1.9M-word, d = 1000 workload: 39.7 -> 35.3 us).
 template <int NV4>
-constexpr int kRowsInFlight = NV4 >= 5 ? 2 : 4;
+constexpr int kRowsInFlight = NV4 >= 16 ? 1 : NV4 >= 5 ? 2 : 4;
 
 // Does the access in lane kLane of the group (source row number r there) take part in a block of m accesses?
 template <int kLane, bool kSkips>
@@ -299,7 +307,7 @@ __device__ __forceinline__ bool takes_part(uint32_t r, uint32_t m)
         return false;
     } else {
         if ((uint32_t)kLane >= m) return false;
-        return !kSkips || group_share<kLane>(r) != kNoRow;
+        return !kSkips || group_share<kLane>(r) < kRowDone;   // neither kNoRow nor kRowDone: a row of the source
     }
 }
 
@@ -431,6 +439,21 @@ __device__ __forceinline__ ApplyShape apply_shape(const ApplyArgs &a)
     return sh;
 }
 
+// src.done_in_rows for the sources that have it (kDoneInRows); never called for the others.
+template <class Src>
+__device__ __forceinline__ bool done_in_rows_of(const Src &src, uint32_t r, uint32_t n, int lane)
+{
+    if constexpr (Src::kDoneInRows) return src.done_in_rows(r, n, lane);
+    else return false;
+}
+
+template <class Src>
+__device__ __forceinline__ bool single_is_done(const Src &src)
+{
+    if constexpr (Src::kDoneInRows) return src.singles_done;
+    else return false;
+}
+
 // One item of short segments: this group's segments, if it has any (segment numbers item * kSegmentsPerItem +
 // group + k * kGroupsPerBlock: neighbouring groups update neighbouring rows).
 template <int NV4, class Src, class Opt>
@@ -454,12 +477,24 @@ __device__ __forceinline__ void apply_short_item(const ApplyArgs &a, const Src &
     for (int k = 0; k < kSegmentsPerGroup; ++k) {
         if (first[k] >= last[k]) continue;
         if (takes_hot_path(last[k] - first[k], key[k], a.hot_bits, a.base_keys)) continue;   // summed by chunk items
-        if (src.segment_done(a.perm, first[k], last[k], lane)) continue;        // the gradient kernel has updated this row itself
+        Row<NV4> acc, t, g;
+        const uint32_t n = last[k] - first[k];
+        if (Src::kDoneInRows && n <= kLongSegment) {   // one fetch serves the question and the sum
+            static_assert(kLongSegment <= (uint32_t)kGroup, "one access per lane");
+            if (n == 1 && single_is_done(src)) continue;
+            uint32_t r = 0;
+            float c = 0.0f;
+            if ((uint32_t)lane < n) src.fetch(a.perm, first[k] + (uint32_t)lane, c, r);
+            if (done_in_rows_of(src, r, n, lane)) continue;      // the gradient kernel has updated this row itself
+            zero_row(acc);
+            sum_rows_from<NV4, 0, (int)kLongSegment, Src::kSkips>(acc, src.rows(), r, c, n, a.stride, lane);
+        } else {
+            if (src.segment_done(a.perm, first[k], last[k], lane)) continue;    // the gradient kernel has updated this row itself
+            sum_segment<NV4>(acc, src, a.perm, first[k], last[k], a.stride, lane, lds + (size_t)group * a.stride,
+                             a.totals + ((size_t)workgroup * kGroupsPerBlock + group) * a.stride);
+        }
         float *row = extended_row(a.table, a.replica_rows, a.base_keys, key[k], a.stride);
         float *state_row = Opt::kHasState ? a.state + (size_t)key[k] * a.stride : nullptr;   // tables with state have no replicas
-        Row<NV4> acc, t, g;
-        sum_segment<NV4>(acc, src, a.perm, first[k], last[k], a.stride, lane, lds + (size_t)group * a.stride,
-                         a.totals + ((size_t)workgroup * kGroupsPerBlock + group) * a.stride);
         opt.template load<NV4>(t, g, row, state_row, lane);   // after the sum: results are waited for in issue order, an early request of the cold row holds up the sum's first reads
         if (opt.clips() && a.hot_bits != nullptr && in_hot_set(key[k], a.hot_bits, a.base_keys)) opt.template clip<NV4>(acc, lane);
         opt.template finish<NV4>(t, g, row, state_row, acc, lane);

@@ -214,7 +214,8 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(RowSpace in_rows, RowSpace
                                                       const uint32_t *out_pos, float *coef_at, uint32_t *row_at,
                                                       float *stage, int update_whole_runs,
                                                       const uint32_t *center_slot, const uint32_t *center_rank,
-                                                      const uint32_t *center_seg, float *center_rows, double *loss,
+                                                      const uint32_t *center_seg, const uint32_t *center_pos,
+                                                      uint32_t *in_row_at, float *center_rows, double *loss,
                                                       SideWork sw)
 {
     extern __shared__ float run_rows[];   // [kGroupsPerBlock][stride]: the pairs' input-side gradients
@@ -227,9 +228,10 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(RowSpace in_rows, RowSpace
     const bool active = e_raw < B;
     const uint32_t e = active ? e_raw : B - 1;
     // the row (or replica row) of the center word
-    const uint32_t crow = kReplicas ? sgns_center_row(center, in_rows.rep, e)
+    const uint32_t crow = kReplicas ? run_row(center, in_rows.rep, e)
                                     : (center[e] < in_rows.keys() ? center[e] : kBadIndex);
     const uint32_t slot = center_slot[e];          // kBadIndex: the center key is outside the table
+    const uint32_t in_pos = center_pos[e];         // where the pair's access stands in the input table's order
     uint32_t seg_len = 0;
     if (slot != kBadIndex) seg_len = center_seg[slot + 1] - center_seg[slot];
     Row<NV4> v, acc;
@@ -240,7 +242,10 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(RowSpace in_rows, RowSpace
         store_row(center_rows + (size_t)slot * stride, v, lane);
     zero_row(acc);
     float loss_acc = 0.f;
-    constexpr int JU = 4;     // rows in flight per group
+    // rows in flight per group: all of a pair's scored rows at three negatives; rows of 1,024 floats take 64
+    // registers each, and two of them in flight leave room for two wavefronts per SIMD instead of one (gradient kernel
+    // of the 1.9M-word, d = 1000 workload: 60 -> 33 us)
+    constexpr int JU = NV4 >= 16 ? 2 : 4;
     const uint32_t n_out = B * (uint32_t)(K + 1);
     for (int j0 = 0; j0 <= K; j0 += JU) {
         // lane jj of the group looks after scored row j0 + jj: where its access stands in the output table's order
@@ -284,27 +289,33 @@ __global__ void __launch_bounds__(kBlock) k_sgns_grad(RowSpace in_rows, RowSpace
         for (int w = 0; w < kBlock / 64; ++w) s += (double)lds[w];
         atomicAdd(loss + (blockIdx.x % kLossSlots) * kLossStride, s);
     }
-    if (active && slot != kBadIndex && (group == 0 || run_key[group - 1] != crow)) {
-        uint32_t len = 1;
-        while (group + len < (uint32_t)kGroupsPerBlock && run_key[group + len] == crow) {
-            Row<NV4> r;
-            load_row(r, run_rows + (size_t)(group + len) * stride, lane);
-            axpy_row(acc, 1.0f, r);
-            ++len;
-        }
-        if (update_whole_runs && len == seg_len) {
+    if (active && slot != kBadIndex) {
+        uint32_t source = kNoRow;   // what the update kernel finds at this access: nothing more, inside a run
+        if (group == 0 || run_key[group - 1] != crow) {
+            uint32_t len = 1;
+            while (group + len < (uint32_t)kGroupsPerBlock && run_key[group + len] == crow) {
+                Row<NV4> r;
+                load_row(r, run_rows + (size_t)(group + len) * stride, lane);
+                axpy_row(acc, 1.0f, r);
+                ++len;
+            }
+            if (update_whole_runs && len == seg_len) {
 #pragma unroll
-            for (int q = 0; q < NV4; ++q) axpy4(v.v[q], -lr, acc.v[q]);
-            store_row(v_row, v, lane);
-        } else {
-            store_row(stage + (size_t)e * stride, acc, lane);
+                for (int q = 0; q < NV4; ++q) axpy4(v.v[q], -lr, acc.v[q]);
+                store_row(v_row, v, lane);
+                source = kRowDone;
+            } else {
+                store_row(stage + (size_t)e * stride, acc, lane);
+                source = e;
+            }
         }
+        if (lane == 0 && in_pos < B) in_row_at[in_pos] = source;
     }
 }
 
 template <int NV4>
 static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b, const Plan &in_plan, const Plan &out_plan,
-                             float *center_rows, uint32_t *row_at, bool update_whole_runs,
+                             float *center_rows, uint32_t *row_at, uint32_t *in_row_at, bool update_whole_runs,
                              const SideWork &sw, size_t side_lds)
 {
     const Table &tin = ctx->tab[0], &tout = ctx->tab[1];
@@ -316,8 +327,8 @@ static void launch_sgns_grad(nups_ctx *ctx, const nups_batch &b, const Plan &in_
         hipLaunchKernelGGL(kernel, dim3(sw.blocks + blocks), dim3(kBlock), lds, ctx->stream, row_space(tin, in_plan),
                            row_space(tout, out_plan), tin.stride, b.k0, b.k1, b.negs, (uint32_t)b.B, (int)b.n_neg, b.lr, (const uint32_t *)out_plan.a.pos, ctx->coef,
                            row_at, ctx->stage, update_whole_runs ? 1 : 0, (const uint32_t *)in_plan.a.slot,
-                           (const uint32_t *)in_plan.a.rank, (const uint32_t *)in_plan.a.seg, center_rows, ctx->loss_cur,
-                           sw);
+                           (const uint32_t *)in_plan.a.rank, (const uint32_t *)in_plan.a.seg,
+                           (const uint32_t *)in_plan.a.pos, in_row_at, center_rows, ctx->loss_cur, sw);
     };
     const bool replicas = in_plan.a.rep.hot_slot != nullptr || out_plan.a.rep.hot_slot != nullptr;
     if (ctx->want_loss && replicas) launch(k_sgns_grad<NV4, true, true>, &allowed[3]);
@@ -373,9 +384,11 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
     const uint32_t B = (uint32_t)b.B, K = (uint32_t)b.n_neg;
     nups_status st;
     // per access of the output table, in the order of its structure: the coefficient, then (as integers) the row
-    // of the center word among the staged center rows
-    if ((st = ensure_f32(&ctx->coef, &ctx->coef_cap, (size_t)2 * B * (K + 1), ctx->stream)) != NUPS_OK) return st;
+    // of the center word among the staged center rows; then per access of the input table, in the order of its
+    // structure: the staged row of its run's sum (SrcStagedAt)
+    if ((st = ensure_f32(&ctx->coef, &ctx->coef_cap, (size_t)2 * B * (K + 1) + B, ctx->stream)) != NUPS_OK) return st;
     uint32_t *row_at = reinterpret_cast<uint32_t *>(ctx->coef + (size_t)B * (K + 1));
+    uint32_t *in_row_at = row_at + (size_t)B * (K + 1);
     // staged rows: [0, B) input-side gradient sums of runs of pairs (at the runs' first pairs), [B, 2B) input
     // vectors of the distinct center words
     if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)2 * B * tin.stride, ctx->stream)) != NUPS_OK) return st;
@@ -388,7 +401,7 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
     {
         const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
-#define CALL(N) launch_sgns_grad<N>(ctx, b, p.plan[0], p.plan[1], center_rows, row_at, update_whole_runs, sw, side_lds)
+#define CALL(N) launch_sgns_grad<N>(ctx, b, p.plan[0], p.plan[1], center_rows, row_at, in_row_at, update_whole_runs, sw, side_lds)
         NUPS_FOR_EACH_ROW_WIDTH(tin.stride, CALL)
 #undef CALL
         NUPS_HIP(hipGetLastError());
@@ -397,9 +410,9 @@ nups_status run_step_sgns(nups_ctx *ctx, nups_prepared &p)
         const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
         if ((st = refresh_clip_bounds(ctx)) != NUPS_OK) return st;
-        const TableUpdate<SrcSgnsIn, OptSgd> uin{&p.plan[0], partial_of(ctx, p, 0), tin.data, nullptr,
-                                                 SrcSgnsIn{ctx->stage, b.k0, update_whole_runs, p.plan[0].a.rep},
-                                                 sgd_rule(ctx, 0, b.lr), tin.replica_rows};
+        const TableUpdate<SrcStagedAt, OptSgd> uin{&p.plan[0], partial_of(ctx, p, 0), tin.data, nullptr,
+                                                   SrcStagedAt{ctx->stage, in_row_at, update_whole_runs}, sgd_rule(ctx, 0, b.lr),
+                                                   tin.replica_rows};
         const TableUpdate<SrcSgnsOut, OptSgd> uout{&p.plan[1], partial_of(ctx, p, 1), tout.data, nullptr,
                                                    SrcSgnsOut{center_rows, ctx->coef, row_at}, sgd_rule(ctx, 1, b.lr),
                                                    tout.replica_rows};
@@ -464,27 +477,53 @@ nups_status launch_replicas(nups_ctx *ctx, Table &t, bool sync)
 // ------------------------------------------------------------------------------------------------
 // Matrix factorisation.  One group per cell: err = x - <w, h>; staged rows
 //   dW = -2 err h + 2 l2 w   (rows [0, B))      dH = -2 err w + 2 l2 h   (rows [B, 2B)).
-// A row (or column) whose only access of the step is this cell is updated here instead, theta <- theta - lr d,
-// while it is in registers: nobody else reads it in this step, so every gradient is still taken at the values of
-// the step's start, and the row is read once and written once in all, with no staged copy (most rows of a long
-// tail are of this kind).  rank_w / rank_h: the plans' per-access flags (kSingleAccess); null: stage everything.
+// A row whose only access of the step is this cell is updated here instead, theta <- theta - lr d, while it is in
+// registers: nobody else reads it in this step, so every gradient is still taken at the values of the step's start,
+// and the row is read once and written once in all, with no staged copy (most rows of a long tail are of this
+// kind).  rank_w: the row plan's per-access flags (kSingleAccess); null: stage everything.
+// Columns: the task's workers walk their cells column by column (Section 5.1), so consecutive cells share their
+// column.  As for the center words of skip-gram pairs, the column gradients of a run of consecutive cells with one
+// column are added up inside the workgroup, through LDS, by the group of the run's first cell, in cell order; a
+// column whose cells of this step all sit in the run (a single cell included) is updated right away, otherwise the
+// run's sum is staged at the row of its first cell: one staged row per run instead of one per cell.
+// slot_h, seg_h: the column plan's per-access key numbers and segment bounds.  kRuns false (narrow rows, see
+// kMfRunsFromNV4): columns are treated like rows (rank_h: the column plan's flags), nothing goes through LDS, and the
+// update kernel finds the staged rows through the plans' access numbers (SrcStaged).
 // ------------------------------------------------------------------------------------------------
-template <int NV4>
+// Row width (in units of 64 floats) from which the column gradients of runs are added up in the gradient kernel.
+// Measured on 10M x 1M factors, 65,536 cells per step: rows of 128 floats: the look-ups and the round trip through
+// LDS cost more than the staged rows they save (cells in generation order 68.8 against 64.5 us per step, visited by
+// column 59.6 against 55.9); rows of 1,024 floats visited by column: 210 against 301 us.
+constexpr int kMfRunsFromNV4 = 4;
+
+template <int NV4, bool kRuns>
 __global__ void __launch_bounds__(kBlock) k_mf_grad(RowSpace W, RowSpace H, int stride, const uint32_t *row, const uint32_t *col,
                                                     const float *val, uint32_t B, float l2, float lr,
-                                                    const uint32_t *rank_w, const uint32_t *rank_h, float *stage,
-                                                    double *loss, SideWork sw)
+                                                    const uint32_t *rank_w, const uint32_t *rank_h,
+                                                    const uint32_t *slot_h, const uint32_t *seg_h, const uint32_t *pos_w, const uint32_t *pos_h, uint32_t *row_at_w,
+                                                    uint32_t *row_at_h, int update_whole_runs, float *stage, double *loss,
+                                                    SideWork sw)
 {
+    extern __shared__ float run_rows[];   // [kGroupsPerBlock][stride]: the cells' column gradients
     __shared__ float lds[kBlock / 64];
+    __shared__ uint32_t run_key[kGroupsPerBlock];
     if (side_work_block(sw)) return;   // the first sw.blocks workgroups prepare later steps
-    const int lane = threadIdx.x & (kGroup - 1);
+    const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
     const uint32_t c_raw = (xcd_block(blockIdx.x - sw.blocks, gridDim.x - sw.blocks) * kBlock + threadIdx.x) / kGroup;
     const bool active = c_raw < B;
     const uint32_t c = active ? c_raw : B - 1;
     Row<NV4> w, h;
     const uint32_t rk = row[c], ck = col[c];
     const bool alone_w = rank_w != nullptr && rk < W.keys() && (rank_w[c] & kSingleAccess) != 0;
-    const bool alone_h = rank_h != nullptr && ck < H.keys() && (rank_h[c] & kSingleAccess) != 0;
+    const bool alone_h = !kRuns && rank_h != nullptr && ck < H.keys() && (rank_h[c] & kSingleAccess) != 0;
+    uint32_t h_id = kBadIndex, h_slot = kBadIndex, h_seg_len = 0, at_w = kBadIndex, at_h = kBadIndex;
+    if (kRuns) {
+        h_id = run_row(col, H.rep, c);   // the column's row (or replica row); kBadIndex: outside the table
+        h_slot = slot_h[c];              // kBadIndex: dropped by the structure
+        if (h_slot != kBadIndex) h_seg_len = seg_h[h_slot + 1] - seg_h[h_slot];
+        at_w = pos_w[c];                 // where the cell's accesses stand in the plans' orders
+        at_h = pos_h[c];
+    }
     float *w_row = W.row(rk, c, stride), *h_row = H.row(ck, c, stride);
     load_row(w, w_row, lane);
     load_row(h, h_row, lane);
@@ -508,26 +547,65 @@ __global__ void __launch_bounds__(kBlock) k_mf_grad(RowSpace W, RowSpace H, int 
         } else {
             store_row(stage + (size_t)c * stride, dw, lane);
         }
-        if (alone_h) {
+        if (kRuns && lane == 0 && at_w < B) row_at_w[at_w] = alone_w ? kRowDone : c;   // what the update kernel finds (SrcStagedAt)
+        if (!kRuns) {
+            if (alone_h) {
 #pragma unroll
-            for (int q = 0; q < NV4; ++q) axpy4(h.v[q], -lr, dh.v[q]);
-            store_row(h_row, h, lane);
-        } else {
-            store_row(stage + ((size_t)B + c) * stride, dh, lane);
+                for (int q = 0; q < NV4; ++q) axpy4(h.v[q], -lr, dh.v[q]);
+                store_row(h_row, h, lane);
+            } else {
+                store_row(stage + ((size_t)B + c) * stride, dh, lane);
+            }
         }
     }
-    block_add_loss((active && lane == 0) ? err * err + l2 * (nw + nh) : 0.f, loss, lds);
+    if (!kRuns) {
+        block_add_loss((active && lane == 0) ? err * err + l2 * (nw + nh) : 0.f, loss, lds);
+        return;
+    }
+    // runs of equal columns inside the workgroup (cells beyond the batch and keys outside the table belong to none)
+    if (lane == 0) run_key[group] = active ? h_id : kBadIndex;
+    store_row(run_rows + (size_t)group * stride, dh, lane);
+    block_add_loss((active && lane == 0) ? err * err + l2 * (nw + nh) : 0.f, loss, lds);   // its barrier serves the runs too
+    if (active && h_slot != kBadIndex) {
+        uint32_t source = kNoRow;   // inside a run: nothing more to add
+        if (group == 0 || run_key[group - 1] != h_id) {
+            uint32_t len = 1;
+            while (group + len < (uint32_t)kGroupsPerBlock && run_key[group + len] == h_id) {
+                Row<NV4> r;
+                load_row(r, run_rows + (size_t)(group + len) * stride, lane);
+                axpy_row(dh, 1.0f, r);
+                ++len;
+            }
+            if (update_whole_runs && len == h_seg_len) {
+#pragma unroll
+                for (int q = 0; q < NV4; ++q) axpy4(h.v[q], -lr, dh.v[q]);
+                store_row(h_row, h, lane);
+                source = kRowDone;
+            } else {
+                store_row(stage + ((size_t)B + c) * stride, dh, lane);
+                source = c;
+            }
+        }
+        if (lane == 0 && at_h < B) row_at_h[at_h] = source;
+    }
 }
 
 template <int NV4>
 static void launch_mf_grad(nups_ctx *ctx, const nups_batch &b, const nups_prepared &p, const uint32_t *rank_w,
-                           const uint32_t *rank_h, const SideWork &sw, size_t side_lds)
+                           uint32_t *row_at, bool update_whole_runs, const SideWork &sw, size_t side_lds)
 {
     const Table &tw = ctx->tab[0], &th = ctx->tab[1];
     const uint32_t blocks = xcd_grid((uint32_t)((b.B + kGroupsPerBlock - 1) / kGroupsPerBlock));
-    hipLaunchKernelGGL(k_mf_grad<NV4>, dim3(sw.blocks + blocks), dim3(kBlock), side_lds, ctx->stream,
+    constexpr bool kRuns = NV4 >= kMfRunsFromNV4;
+    const size_t lds = kRuns ? std::max(sizeof(float) * kGroupsPerBlock * (size_t)tw.stride, side_lds) : side_lds;
+    static size_t allowed = 0;
+    allow_lds(k_mf_grad<NV4, kRuns>, lds, &allowed);
+    const uint32_t *rank_h = rank_w ? (const uint32_t *)p.plan[1].a.rank : nullptr;
+    hipLaunchKernelGGL((k_mf_grad<NV4, kRuns>), dim3(sw.blocks + blocks), dim3(kBlock), lds, ctx->stream,
                        row_space(tw, p.plan[0]), row_space(th, p.plan[1]), tw.stride, b.k0, b.k1, b.val, (uint32_t)b.B, b.l2,
-                       b.lr, rank_w, rank_h, ctx->stage, ctx->loss_cur, sw);
+                       b.lr, rank_w, rank_h, (const uint32_t *)p.plan[1].a.slot, (const uint32_t *)p.plan[1].a.seg,
+                       (const uint32_t *)p.plan[0].a.pos, (const uint32_t *)p.plan[1].a.pos, row_at,
+                       row_at + (size_t)b.B, update_whole_runs ? 1 : 0, ctx->stage, ctx->loss_cur, sw);
 }
 
 nups_status plan_step_mf(nups_ctx *ctx, nups_prepared &p)
@@ -545,18 +623,20 @@ nups_status run_step_mf(nups_ctx *ctx, nups_prepared &p)
     const uint32_t B = (uint32_t)b.B;
     nups_status st;
     if ((st = ensure_f32(&ctx->stage, &ctx->stage_cap, (size_t)2 * B * tw.stride, ctx->stream)) != NUPS_OK) return st;
+    // per access of either table, in the order of its structure: the staged row to add (SrcStagedAt)
+    if ((st = ensure_f32(&ctx->coef, &ctx->coef_cap, (size_t)2 * B, ctx->stream)) != NUPS_OK) return st;
+    uint32_t *row_at = reinterpret_cast<uint32_t *>(ctx->coef);
     ctx->loss_cur = p.loss_dev;   // zeroed by the step's plan construction
     if (B == 0) return NUPS_OK;
     size_t side_lds = 0;
-    // Rows and columns with a single access are updated by the gradient kernel; with norm clipping on, every
-    // update goes through the update kernel, which measures and clips the hot keys' updates.
+    // Rows with a single access and columns whose cells are all in one run are updated by the gradient kernel; with
+    // norm clipping on, every update goes through the update kernel, which measures and clips the hot keys' updates.
     const bool singles_in_place = !(ctx->clip_factor > 0.0f);
     const uint32_t *rank_w = singles_in_place ? p.plan[0].a.rank : nullptr;
-    const uint32_t *rank_h = singles_in_place ? p.plan[1].a.rank : nullptr;
     {
         const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_GRAD, ctx->stream);
-#define CALL(N) launch_mf_grad<N>(ctx, b, p, rank_w, rank_h, sw, side_lds)
+#define CALL(N) launch_mf_grad<N>(ctx, b, p, rank_w, row_at, singles_in_place, sw, side_lds)
         NUPS_FOR_EACH_ROW_WIDTH(tw.stride, CALL)
 #undef CALL
         NUPS_HIP(hipGetLastError());
@@ -565,13 +645,24 @@ nups_status run_step_mf(nups_ctx *ctx, nups_prepared &p)
         const SideWork sw = take_side_work(ctx, &side_lds, kSideWgsNarrow);
         PhaseScope scope(ctx, NUPS_PHASE_APPLY0, ctx->stream);
         if ((st = refresh_clip_bounds(ctx)) != NUPS_OK) return st;
-        const TableUpdate<SrcStaged, OptSgd> uw{&p.plan[0], partial_of(ctx, p, 0), tw.data, nullptr,
-                                                SrcStaged{ctx->stage, singles_in_place}, sgd_rule(ctx, 0, b.lr),
-                                                tw.replica_rows};
-        const TableUpdate<SrcStaged, OptSgd> uh{&p.plan[1], partial_of(ctx, p, 1), th.data, nullptr,
-                                                SrcStaged{ctx->stage + (size_t)B * tw.stride, singles_in_place},
-                                                sgd_rule(ctx, 1, b.lr), th.replica_rows};
-        if ((st = launch_apply2(ctx->stream, tw.stride, uw, uh, update_scratch(ctx, tw.stride), sw, side_lds)) != NUPS_OK) return st;
+        if (tw.stride / 64 >= kMfRunsFromNV4) {
+            const TableUpdate<SrcStagedAt, OptSgd> uw{&p.plan[0], partial_of(ctx, p, 0), tw.data, nullptr,
+                                                      SrcStagedAt{ctx->stage, row_at, singles_in_place}, sgd_rule(ctx, 0, b.lr),
+                                                      tw.replica_rows};
+            const TableUpdate<SrcStagedAt, OptSgd> uh{&p.plan[1], partial_of(ctx, p, 1), th.data, nullptr,
+                                                      SrcStagedAt{ctx->stage + (size_t)B * tw.stride, row_at + (size_t)B, singles_in_place},
+                                                      sgd_rule(ctx, 1, b.lr), th.replica_rows};
+            st = launch_apply2(ctx->stream, tw.stride, uw, uh, update_scratch(ctx, tw.stride), sw, side_lds);
+        } else {
+            const TableUpdate<SrcStaged, OptSgd> uw{&p.plan[0], partial_of(ctx, p, 0), tw.data, nullptr,
+                                                    SrcStaged{ctx->stage, singles_in_place}, sgd_rule(ctx, 0, b.lr),
+                                                    tw.replica_rows};
+            const TableUpdate<SrcStaged, OptSgd> uh{&p.plan[1], partial_of(ctx, p, 1), th.data, nullptr,
+                                                    SrcStaged{ctx->stage + (size_t)B * tw.stride, singles_in_place},
+                                                    sgd_rule(ctx, 1, b.lr), th.replica_rows};
+            st = launch_apply2(ctx->stream, tw.stride, uw, uh, update_scratch(ctx, tw.stride), sw, side_lds);
+        }
+        if (st != NUPS_OK) return st;
     }
     return NUPS_OK;
 }
