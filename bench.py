@@ -553,6 +553,16 @@ def main() -> int:
         if n:
             phases[nb.nups_phase_name(p)] = ms / n_prof
     nb.nups_profile(ctx, False)
+    # what a pair of HIP events reads with nothing between them, on the stream the kernels run on: a bracket around
+    # one launch includes this much besides the kernel (rocprofv3's per-dispatch durations do not)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    empty_ms = []
+    for _ in range(51):
+        ev0.record()
+        ev1.record()
+        torch.cuda.synchronize()
+        empty_ms.append(ev0.elapsed_time(ev1))
+    empty_bracket_ms = float(np.median(empty_ms))
     progress("per-kernel pass done (%d unpipelined steps)" % n_prof)
 
     # a plain copy of known size through the library's own gather kernel (rows 0..n-1 in order): the
@@ -590,6 +600,7 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBPS, "traffic": recorded_traffic(args.workload, dominant),
                 "algorithmic_bytes_per_launch": alg[dominant], "kernel_ms": dom_ms,
+                "empty_event_bracket_ms": empty_bracket_ms,
                 "per_kernel_GBps": {p: alg[p] / (phases[p] * 1e-3) / 1e9 for p in ("grad", "apply0", "apply1")
                                     if p in phases and p in alg},
                 "whole_step_algorithmic_GBps": alg["step"] / (ms_per_step * 1e-3) / 1e9,

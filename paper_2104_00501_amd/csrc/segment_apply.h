@@ -644,14 +644,17 @@ __global__ void __launch_bounds__(kBlock, kApply2WavesPerSimd<NV4>) k_apply2(App
     const int lane = threadIdx.x & (kGroup - 1), group = threadIdx.x / kGroup;
     // The first items are the chunks of the first table, the longest of the launch: a workgroup asks for the chunk
     // that its number stands for together with the item counts (one dependent read fewer in front of the rows; the
-    // entry is inside the array whatever it holds, and is used only if the counts confirm it).
+    // entry is inside the array whatever it holds, and is used only if the counts confirm it).  Not for rows of up
+    // to 128 floats, whose launches have four times as many workgroups with little to do each: there the extra
+    // read costs more than it saves (factorisation at rank 100: 64.9 against 63.2 us per step).
+    constexpr bool kAskAhead = NV4 >= 3;
     uint4 own_chunk = make_uint4(0u, 0u, 0u, 0u);
-    if (first_item < a0.max_chunks) own_chunk = a0.chunk_of[first_item];
+    if (kAskAhead && first_item < a0.max_chunks) own_chunk = a0.chunk_of[first_item];
     const ApplyShape s0 = apply_shape(a0), s1 = apply_shape(a1);
     const uint32_t e0 = s0.chunk_items, e1 = e0 + s1.chunk_items, e2 = e1 + s0.short_items,
                    e3 = e2 + s1.short_items;
     for (uint32_t item = first_item; item < e3; item += item_step) {
-        if (item < e0) apply_chunk_item<NV4>(a0, src0, opt0, item, item == first_item ? own_chunk : a0.chunk_of[item], part, &last_arrival, lane, group);
+        if (item < e0) apply_chunk_item<NV4>(a0, src0, opt0, item, (kAskAhead && item == first_item) ? own_chunk : a0.chunk_of[item], part, &last_arrival, lane, group);
         else if (item < e1) apply_chunk_item<NV4>(a1, src1, opt1, item - e0, a1.chunk_of[item - e0], part, &last_arrival, lane, group);
         else if (item < e2) apply_short_item<NV4>(a0, src0, opt0, s0, item - e1, part, first_item, lane, group);
         else apply_short_item<NV4>(a1, src1, opt1, s1, item - e2, part, first_item, lane, group);
