@@ -206,6 +206,9 @@ static RowSpace row_space(const Table &t, const Plan &pl) { return RowSpace{t.da
 // registers, nobody else reads it in this step, and the output side works from the staged copy of the row.
 // Otherwise the run's sum is staged at the row of its first pair and the update kernel adds the runs of the word.
 // So a staged gradient row is written per run that shares its word with other runs, not per pair.
+// What the update kernel needs it finds where the accesses stand in the tables' segment orders (out_pos, center_pos:
+// the structure's positions): per scored row its coefficient and the number of the pair's staged center row; per
+// pair the staged row of its run's sum, "none" inside a run, "done" for a word updated here (SrcStagedAt).
 // ------------------------------------------------------------------------------------------------
 template <int NV4, bool kWithLoss, bool kReplicas>
 __global__ void __launch_bounds__(kBlock) k_sgns_grad(RowSpace in_rows, RowSpace out_rows, int stride,
